@@ -1,0 +1,185 @@
+/*
+ * anszp.h -- C ABI of libanszp: inference-time tabled-ANS (tANS) decoding of
+ * entropy-coded, zero-point-quantized, mixed-precision network weights on
+ * AMD MI355X (gfx950), fused with dequantisation to compute-ready weights.
+ *
+ * Method (citations are to the paper "Efficient Neural Compression with
+ * Inference-time Decoding"):
+ *   Sec. II-A    the decoder is a look-up table with one entry per state holding
+ *                (symbol, nb_bits, newX); a step emits the symbol, reads nb_bits
+ *                bits from the compressed stream and moves to state newX + bits;
+ *                transitions that read no bits allow rates below 1 bit/weight.
+ *   Sec. III-A   one table per layer.
+ *   Sec. III-B   several streams are decoded at once with one shared table and a
+ *                vector of states (here: one GPU lane per stream).
+ *   Sec. II-B    weights come from a uniform quantizer with a zero-point, so
+ *                w = scale * (q - zero_point).
+ *
+ * General conventions
+ *   - Pointers marked [device] are device addresses of the current HIP device;
+ *     pointers marked [host] are ordinary host addresses.  The caller owns every
+ *     buffer.  The library keeps no global state and allocates no device memory.
+ *   - `hip_stream` is a hipStream_t (NULL = default stream).  Device work is
+ *     enqueued on it and the call returns without waiting, unless stated.
+ *   - Return value: 0 on success, a negative ANSZP_E_* code when the host can
+ *     see the problem (nothing has been enqueued then).  Problems only the GPU
+ *     can see (corrupt stream, descriptor out of range) are OR-ed into the
+ *     caller's status words; no device access ever leaves the caller's buffers
+ *     because every index is checked or clamped first.
+ *   - No exceptions, aborts or prints cross this boundary.
+ *
+ * Compressed container (all little-endian)
+ *   A layer is a flat row-major array of n symbols q_i in [0, 256).  It is cut
+ *   into consecutive chunks of `chunk_size` symbols (the last may be short).
+ *   Inside a chunk, element j belongs to stream (j mod N) and is that stream's
+ *   symbol number (j div N); N = n_streams <= 64.  Each stream is a private run
+ *   of 32-bit words: the bits the decoder reads, in the order it reads them,
+ *   least significant bit first, zero-padded to a whole word.  A chunk's
+ *   payload is its N streams' words back to back in stream order and starts at
+ *   a word offset that is a multiple of 4.  Each stream has one 32-bit header:
+ *   bits 0..15 the decoder's initial state X (0 <= X < 2^table_log), bits
+ *   16..31 the stream's length in words.  The encoder starts every stream in
+ *   state X = 0 and runs over its symbols last to first, so a correct decode
+ *   ends in state 0 having read exactly the stream's words.
+ */
+#ifndef ANSZP_H
+#define ANSZP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANSZP_ALPHABET        256   /* symbols are bytes; frequency rows have 256 entries     */
+#define ANSZP_MAX_TABLE_LOG   12    /* tables have L = 2^table_log states, 1 <= table_log <= 12 */
+#define ANSZP_MAX_STREAMS     64    /* streams per chunk = lanes of one wavefront              */
+
+/* error codes returned by the functions */
+#define ANSZP_OK              0
+#define ANSZP_E_NULL         (-1)   /* a required pointer is NULL                              */
+#define ANSZP_E_RANGE        (-2)   /* an argument is outside its documented range             */
+#define ANSZP_E_FREQ         (-3)   /* a frequency row does not sum to 2^table_log             */
+#define ANSZP_E_SYMBOL       (-4)   /* data contains a symbol whose frequency is zero          */
+#define ANSZP_E_SPACE        (-5)   /* an output buffer is too small / a stream exceeds 65535 words */
+#define ANSZP_E_HIP          (-6)   /* the HIP runtime reported an error                       */
+#define ANSZP_E_NOMEM        (-7)   /* host allocation failed                                  */
+
+/* bits OR-ed into status[0] by the decode kernels */
+#define ANSZP_ST_BAD_DESC     1u    /* chunk descriptor points outside a buffer; chunk skipped */
+#define ANSZP_ST_BAD_STATE    2u    /* a stream did not end in state 0                          */
+#define ANSZP_ST_BAD_LENGTH   4u    /* a stream read more or fewer words than its header says   */
+
+/* output element types */
+#define ANSZP_OUT_U8          0     /* decoded symbols, no dequantisation                       */
+#define ANSZP_OUT_F32         1     /* IEEE binary32                                            */
+#define ANSZP_OUT_BF16        2     /* bfloat16, round-to-nearest-even of the binary32 value    */
+
+/* One chunk (32 bytes).  Arrays of these live in device memory for anszp_decode. */
+typedef struct {
+    uint32_t layer_id;        /* selects the table and the anszp_layer_t                       */
+    uint32_t n_symbols;       /* symbols in this chunk; stream k holds ceil((n_symbols-k)/N)   */
+    uint64_t out_offset;      /* element index of the chunk's first symbol in `out`            */
+    uint64_t payload_offset;  /* first word of the chunk in `payload`; multiple of 4           */
+    uint32_t payload_words;   /* sum of the chunk's stream lengths                             */
+    uint32_t stream_offset;   /* index of stream 0's header in `stream_hdr`                    */
+} anszp_chunk_t;
+
+/* One layer's quantizer (32 bytes), Sec. II-B. */
+typedef struct {
+    float    scale;           /* used when channel_len == 0                                    */
+    uint32_t zero_point;      /* z: symbol that decodes to +0.0                                */
+    uint32_t bitwidth;        /* informational: symbols are < 2^bitwidth, 1..8                 */
+    uint32_t channel_len;     /* 0: one scale per layer; else elements per output channel and
+                                 the scale of layer element e is scales[scales_offset + e / channel_len] */
+    uint64_t scales_offset;   /* index of the layer's first channel scale in `scales`          */
+    uint64_t out_base;        /* element index of the layer's first element in `out`           */
+} anszp_layer_t;
+
+/* Arguments of anszp_decode (the struct itself is read on the host). */
+typedef struct {
+    const uint64_t*      tables;        /* [device] n_tables * 2^table_log entries from anszp_build_tables */
+    uint32_t             n_tables;
+    uint32_t             table_log;     /* R, 1..12                                             */
+    uint32_t             n_streams;     /* N, 1..64                                             */
+    uint32_t             out_dtype;     /* ANSZP_OUT_*                                          */
+    const anszp_chunk_t* chunks;        /* [device]                                             */
+    uint64_t             n_chunks;      /* may be 0 (nothing is enqueued)                       */
+    const uint32_t*      stream_hdr;    /* [device] one header per stream                       */
+    uint64_t             n_stream_hdr;
+    const uint32_t*      payload;       /* [device] 16-byte aligned                             */
+    uint64_t             payload_words;
+    const anszp_layer_t* layers;        /* [device] n_tables entries                            */
+    const float*         scales;        /* [device] per-channel scales, may be NULL if unused   */
+    uint64_t             n_scales;
+    void*                out;           /* [device] out_elems elements of out_dtype, 16-byte aligned */
+    uint64_t             out_elems;
+    uint32_t*            status;        /* [device] 2 words: [0] OR of ANSZP_ST_*, [1] number of
+                                           failing chunks.  Never cleared by the library: zero it
+                                           once, read it after synchronising the stream.        */
+} anszp_decode_args_t;
+
+/* Library version (major * 100 + minor). */
+int anszp_version(void);
+
+/* Text for an ANSZP_E_* code; never NULL; static storage. */
+const char* anszp_strerror(int code);
+
+/* [host only] Turn symbol counts into table frequencies (the paper does not say how):
+ * freqs[s] >= 1 exactly when counts[s] > 0 and sum(freqs) == 2^table_log.
+ * counts, freqs: [host] 256 entries.  Errors: E_NULL, E_RANGE, E_FREQ (no symbols, or more
+ * distinct symbols than states). */
+int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs);
+
+/* [host only] Sec. II-A / III-A: build n_tables decode tables from normalised frequencies.
+ * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 2^table_log entries.
+ * Entry layout (uint64):
+ *   bits  0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol        -- the paper's triple
+ *   bits 32..34 c-1       bits 35..46 newX'     bit 47 end-flag
+ *   bits 48..55 symbol'   bits 56..63 nb_bits'                            -- the same automaton
+ *   with up to 8 steps merged: from this state the next c-1 symbols are zero-bit transitions of
+ *   the dominant symbol (f > L/2), then symbol' is emitted, nb_bits' bits are read and the state
+ *   becomes newX' + bits.  end-flag: the state before the c-th symbol is state 0.
+ * Errors: E_NULL, E_RANGE, E_FREQ. */
+int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint64_t* tables);
+
+/* Same, writing the tables to device memory.  tables_dev: [device].  The host-to-device copy
+ * is enqueued on hip_stream and waited for before returning.  Errors: as above, E_HIP, E_NOMEM. */
+int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
+                       uint64_t* tables_dev, void* hip_stream);
+
+/* [host only] Worst-case sizes for anszp_pack_layer: number of chunks and payload words. */
+int anszp_pack_bound(uint64_t n_symbols, int table_log, int n_streams, uint32_t chunk_size,
+                     uint64_t* n_chunks, uint64_t* payload_words);
+
+/* [host only] Offline compressor (Sec. II-A encoder; container described at the top).
+ * Encodes one layer's symbols with the table given by freqs and appends to caller arrays:
+ * chunks_out[0..n_chunks), stream_hdr_out[0..n_chunks*N), payload_out[0..*payload_words_used).
+ * layer_id / out_offset / payload_word_offset / stream_offset are the positions the layer's
+ * first chunk will have in the full container (payload_word_offset must be a multiple of 4).
+ * Errors: E_NULL, E_RANGE, E_FREQ, E_SYMBOL, E_SPACE, E_NOMEM. */
+int anszp_pack_layer(const uint8_t* symbols, uint64_t n_symbols, const uint32_t* freqs,
+                     int table_log, int n_streams, uint32_t chunk_size,
+                     uint32_t layer_id, uint64_t out_offset, uint64_t payload_word_offset,
+                     uint32_t stream_offset,
+                     anszp_chunk_t* chunks_out, uint32_t* stream_hdr_out,
+                     uint32_t* payload_out, uint64_t payload_cap_words, uint64_t* payload_words_used);
+
+/* Sec. II-A decoder + Sec. III-B parallel streams + Sec. II-B dequantisation, fused: decode
+ * every chunk (one wavefront per chunk, one lane per stream) and write out[out_offset + j] for
+ * each of its symbols j, as raw symbols, fp32 or bf16 weights.  One kernel launch on hip_stream.
+ * Errors: E_NULL, E_RANGE (table_log, n_streams, out_dtype, n_tables == 0, n_chunks >= 2^31,
+ * payload or out not 16-byte aligned). */
+int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
+
+/* Sec. II-B alone: out[i] = scale * (symbols[i] - zero_point) for i < n, the scale chosen as in
+ * anszp_layer_t with the layer starting at element 0.  symbols_dev, scales_dev, out_dev: [device];
+ * layer: [host].  out_dtype is ANSZP_OUT_F32 or ANSZP_OUT_BF16.  Errors: E_NULL, E_RANGE. */
+int anszp_dequant_zp(const uint8_t* symbols_dev, uint64_t n, const anszp_layer_t* layer,
+                     const float* scales_dev, uint64_t n_scales, void* out_dev, int out_dtype,
+                     void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANSZP_H */

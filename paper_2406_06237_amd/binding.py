@@ -1,0 +1,316 @@
+"""Thin ctypes binding of libanszp.so (declared in include/anszp.h).
+
+Argument marshalling only: every step of the decode path (table staging, tANS decode,
+dequantisation, stores) runs in the library's HIP kernels, and the container is built by the
+library's host packer.  PyTorch is used for device memory and streams.  There is no CPU
+fallback: if the library is missing or the call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libanszp.so")
+
+OUT_U8, OUT_F32, OUT_BF16 = 0, 1, 2
+OUT_CODES = {"u8": OUT_U8, "f32": OUT_F32, "bf16": OUT_BF16}
+ST_BAD_DESC, ST_BAD_STATE, ST_BAD_LENGTH = 1, 2, 4
+MAX_TABLE_LOG, MAX_STREAMS, ALPHABET = 12, 64, 256
+
+CHUNK_DTYPE = np.dtype([("layer_id", "<u4"), ("n_symbols", "<u4"), ("out_offset", "<u8"),
+                        ("payload_offset", "<u8"), ("payload_words", "<u4"), ("stream_offset", "<u4")])
+LAYER_DTYPE = np.dtype([("scale", "<f4"), ("zero_point", "<u4"), ("bitwidth", "<u4"), ("channel_len", "<u4"),
+                        ("scales_offset", "<u8"), ("out_base", "<u8")])
+assert CHUNK_DTYPE.itemsize == 32 and LAYER_DTYPE.itemsize == 32
+
+
+class DecodeArgs(C.Structure):
+    _fields_ = [("tables", C.c_void_p), ("n_tables", C.c_uint32), ("table_log", C.c_uint32),
+                ("n_streams", C.c_uint32), ("out_dtype", C.c_uint32),
+                ("chunks", C.c_void_p), ("n_chunks", C.c_uint64),
+                ("stream_hdr", C.c_void_p), ("n_stream_hdr", C.c_uint64),
+                ("payload", C.c_void_p), ("payload_words", C.c_uint64),
+                ("layers", C.c_void_p), ("scales", C.c_void_p), ("n_scales", C.c_uint64),
+                ("out", C.c_void_p), ("out_elems", C.c_uint64), ("status", C.c_void_p)]
+
+
+class AnszpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
+           "anszp_build_tables", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_dequant_zp"]
+
+
+def lib():
+    """Load libanszp.so (build it first with `python -m paper_2406_06237_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build()")
+        L = C.CDLL(LIB_PATH)
+        L.anszp_strerror.restype = C.c_char_p
+        L.anszp_strerror.argtypes = [C.c_int]
+        L.anszp_normalize_freqs.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        L.anszp_build_tables_host.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.anszp_build_tables.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.anszp_pack_bound.argtypes = [C.c_uint64, C.c_int, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.anszp_pack_layer.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int, C.c_int, C.c_uint32,
+                                       C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.anszp_decode.argtypes = [C.POINTER(DecodeArgs), C.c_void_p]
+        L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
+                                       C.c_void_p, C.c_int, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().anszp_strerror(code).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise AnszpError(rc, where)
+
+
+def version() -> int:
+    return lib().anszp_version()
+
+
+# ----------------------------------------------------------------------------- host entry points
+def normalize_freqs(counts: np.ndarray, table_log: int) -> np.ndarray:
+    c = np.zeros(ALPHABET, dtype=np.uint64)
+    c[:len(counts)] = counts
+    f = np.zeros(ALPHABET, dtype=np.uint32)
+    _check(lib().anszp_normalize_freqs(c.ctypes.data, table_log, f.ctypes.data), "anszp_normalize_freqs")
+    return f
+
+
+def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
+    freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
+    size = len(freqs) << max(0, min(table_log, 20))
+    tables = np.zeros(size, dtype=np.uint64)
+    _check(lib().anszp_build_tables_host(freqs.ctypes.data, len(freqs), table_log, tables.ctypes.data),
+           "anszp_build_tables_host")
+    return tables.reshape(len(freqs), -1)
+
+
+def split_table(tables: np.ndarray):
+    """Fields of the table entries: the paper's triple and the merged-step fields."""
+    t = np.asarray(tables, dtype=np.uint64)
+    lo = (t & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+    hi = (t >> np.uint64(32)).astype(np.uint32)
+    return {"newX": (lo & 0xFFFF).astype(np.uint16), "nb": ((lo >> 16) & 0xFF).astype(np.uint8),
+            "sym": (lo >> 24).astype(np.uint8),
+            "count": ((hi & 7) + 1).astype(np.uint8), "m_newX": ((hi >> 3) & 0xFFF).astype(np.uint16),
+            "m_end": ((hi >> 15) & 1).astype(np.uint8), "m_sym": ((hi >> 16) & 0xFF).astype(np.uint8),
+            "m_nb": (hi >> 24).astype(np.uint8)}
+
+
+@dataclass
+class HostContainer:
+    table_log: int
+    n_streams: int
+    chunk_size: int
+    out_dtype: str
+    freqs: np.ndarray        # [n_layers, 256] u32
+    layers: np.ndarray       # LAYER_DTYPE [n_layers]
+    chunks: np.ndarray       # CHUNK_DTYPE [n_chunks]
+    stream_hdr: np.ndarray   # u32
+    payload: np.ndarray      # u32
+    scales: np.ndarray       # f32 (per-channel scales of all layers, possibly empty)
+    numel: int
+
+    def compressed_bytes(self) -> int:
+        """Bytes a decode has to read: stream words, stream headers."""
+        return int(self.chunks["payload_words"].astype(np.uint64).sum()) * 4 + 4 * len(self.stream_hdr)
+
+
+def pack_layer(symbols: np.ndarray, freqs: np.ndarray, table_log: int, n_streams: int, chunk_size: int,
+               layer_id: int = 0, out_offset: int = 0, payload_word_offset: int = 0, stream_offset: int = 0):
+    sym = np.ascontiguousarray(symbols, dtype=np.uint8)
+    f = np.zeros(ALPHABET, dtype=np.uint32)
+    f[:len(freqs)] = freqs
+    nc, cap = C.c_uint64(0), C.c_uint64(0)
+    _check(lib().anszp_pack_bound(len(sym), table_log, n_streams, chunk_size, C.addressof(nc), C.addressof(cap)),
+           "anszp_pack_bound")
+    chunks = np.zeros(nc.value, dtype=CHUNK_DTYPE)
+    hdr = np.zeros(nc.value * n_streams, dtype=np.uint32)
+    payload = np.zeros(cap.value + 4, dtype=np.uint32)
+    used = C.c_uint64(0)
+    _check(lib().anszp_pack_layer(sym.ctypes.data, len(sym), f.ctypes.data, table_log, n_streams, chunk_size,
+                                  layer_id, out_offset, payload_word_offset, stream_offset,
+                                  chunks.ctypes.data, hdr.ctypes.data, payload.ctypes.data, len(payload),
+                                  C.addressof(used)), "anszp_pack_layer")
+    return chunks, hdr, payload[:used.value].copy()
+
+
+def pack_layers(layer_symbols: Sequence[np.ndarray], table_log: int, n_streams: int, chunk_size: int,
+                zero_points: Sequence[int], scales: Sequence[float], bitwidths: Optional[Sequence[int]] = None,
+                channel_len: Optional[Sequence[int]] = None,
+                channel_scales: Optional[Sequence[Optional[np.ndarray]]] = None,
+                out_dtype: str = "bf16", freqs: Optional[Sequence[np.ndarray]] = None) -> HostContainer:
+    """Compress a list of layers into one container with the library's host packer."""
+    nl = len(layer_symbols)
+    layers = np.zeros(nl, dtype=LAYER_DTYPE)
+    fr, ch, hd, pl, sc = [], [], [], [], []
+    elem = words = streams = n_sc = 0
+    for li, sym in enumerate(layer_symbols):
+        sym = np.ascontiguousarray(sym, dtype=np.uint8)
+        f = (normalize_freqs(np.bincount(sym, minlength=ALPHABET), table_log) if freqs is None
+             else np.ascontiguousarray(freqs[li], dtype=np.uint32))
+        chunks, hdr, payload = pack_layer(sym, f, table_log, n_streams, chunk_size, li, elem, words, streams)
+        layers[li] = (scales[li], zero_points[li], bitwidths[li] if bitwidths is not None else 8,
+                      channel_len[li] if channel_len is not None else 0, n_sc, elem)
+        if channel_len is not None and channel_len[li]:
+            cs = np.ascontiguousarray(channel_scales[li], dtype=np.float32)
+            sc.append(cs)
+            n_sc += len(cs)
+        fr.append(f); ch.append(chunks); hd.append(hdr); pl.append(payload)
+        elem += len(sym); words += len(payload); streams += len(hdr)
+    cat = np.concatenate
+    return HostContainer(table_log, n_streams, chunk_size, out_dtype, np.stack(fr), layers, cat(ch), cat(hd),
+                         cat(pl) if words else np.zeros(0, np.uint32),
+                         cat(sc) if sc else np.zeros(0, np.float32), elem)
+
+
+def pack_workload(w) -> HostContainer:
+    """Compress a workloads.Workload."""
+    L = w.layers
+    return pack_layers(w.symbols(), w.table_log, w.n_streams, w.chunk_size,
+                       [l.zero_point for l in L], [l.scale for l in L], [l.bitwidth for l in L],
+                       [l.channel_len for l in L], [l.channel_scales for l in L], w.out_dtype)
+
+
+# --------------------------------------------------------------------------- device entry points
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("libanszp device entry points need a GPU (torch.cuda.is_available() is False)")
+    return torch
+
+
+def _dev(arr: np.ndarray, device):
+    """Copy a numpy array to the device as raw bytes (at least 16 bytes so the pointer is valid)."""
+    torch = _torch()
+    raw = np.ascontiguousarray(arr).view(np.uint8).reshape(-1)
+    if raw.size < 16:
+        raw = np.concatenate([raw, np.zeros(16 - raw.size, np.uint8)])
+    return torch.from_numpy(raw.copy()).to(device)
+
+
+def _stream_ptr(torch, device):
+    return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
+    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 2^table_log uint64)."""
+    torch = _torch()
+    freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
+    with torch.cuda.device(device):
+        tables = torch.empty((len(freqs) << table_log) * 8, dtype=torch.uint8, device=device)
+        _check(lib().anszp_build_tables(freqs.ctypes.data, len(freqs), table_log, tables.data_ptr(),
+                                        _stream_ptr(torch, device)), "anszp_build_tables")
+    return tables
+
+
+_TORCH_OUT = {"u8": "uint8", "f32": "float32", "bf16": "bfloat16"}
+
+
+@dataclass
+class DeviceContainer:
+    host: HostContainer
+    device: str
+    tables: object
+    layers: object
+    chunks: object
+    stream_hdr: object
+    payload: object
+    scales: object
+    status: object
+
+    def read_status(self):
+        torch = _torch()
+        torch.cuda.synchronize(self.device)
+        st = self.status.cpu().numpy().view(np.uint32)
+        return int(st[0]), int(st[1])
+
+
+def to_device(h: HostContainer, device="cuda:0") -> DeviceContainer:
+    """Upload a container and build its decode tables on the device."""
+    torch = _torch()
+    tables = build_tables(h.freqs, h.table_log, device)
+    return DeviceContainer(h, device, tables, _dev(h.layers, device), _dev(h.chunks, device),
+                           _dev(h.stream_hdr, device), _dev(h.payload, device), _dev(h.scales, device),
+                           torch.zeros(2, dtype=torch.int32, device=device))
+
+
+def alloc_out(d: DeviceContainer, out_dtype: Optional[str] = None):
+    torch = _torch()
+    dt = getattr(torch, _TORCH_OUT[out_dtype or d.host.out_dtype])
+    return torch.empty(max(d.host.numel, 8), dtype=dt, device=d.device)
+
+
+def decode_args(d: DeviceContainer, out, out_dtype: Optional[str] = None) -> DecodeArgs:
+    h = d.host
+    a = DecodeArgs()
+    a.tables = d.tables.data_ptr(); a.n_tables = len(h.freqs); a.table_log = h.table_log
+    a.n_streams = h.n_streams; a.out_dtype = OUT_CODES[out_dtype or h.out_dtype]
+    a.chunks = d.chunks.data_ptr(); a.n_chunks = len(h.chunks)
+    a.stream_hdr = d.stream_hdr.data_ptr(); a.n_stream_hdr = len(h.stream_hdr)
+    a.payload = d.payload.data_ptr(); a.payload_words = len(h.payload)
+    a.layers = d.layers.data_ptr(); a.scales = d.scales.data_ptr(); a.n_scales = len(h.scales)
+    a.out = out.data_ptr(); a.out_elems = h.numel; a.status = d.status.data_ptr()
+    return a
+
+
+def decode_raw(args: DecodeArgs, device="cuda:0"):
+    """anszp_decode on torch's current stream of `device`."""
+    torch = _torch()
+    with torch.cuda.device(device):
+        _check(lib().anszp_decode(C.byref(args), _stream_ptr(torch, device)), "anszp_decode")
+
+
+def decode(d: DeviceContainer, out=None, out_dtype: Optional[str] = None):
+    """Decode + dequantise the whole container; returns the output tensor (first numel elements valid)."""
+    if out is None:
+        out = alloc_out(d, out_dtype)
+    decode_raw(decode_args(d, out, out_dtype), d.device)
+    return out
+
+
+def dequant_zp(symbols, zero_point: int, scale: float, out_dtype: str = "bf16", channel_len: int = 0,
+               channel_scales=None):
+    """anszp_dequant_zp on a uint8 device tensor of symbols."""
+    torch = _torch()
+    n = symbols.numel()
+    dev = symbols.device
+    out = torch.empty(max(n, 8), dtype=getattr(torch, _TORCH_OUT[out_dtype]), device=dev)
+    lay = np.zeros(1, dtype=LAYER_DTYPE)
+    lay[0] = (scale, zero_point, 8, channel_len, 0, 0)
+    n_sc = 0 if channel_scales is None else channel_scales.numel()
+    with torch.cuda.device(dev):
+        _check(lib().anszp_dequant_zp(symbols.data_ptr(), n, lay.ctypes.data,
+                                      channel_scales.data_ptr() if channel_scales is not None else None, n_sc,
+                                      out.data_ptr(), OUT_CODES[out_dtype], _stream_ptr(torch, dev)),
+               "anszp_dequant_zp")
+    return out[:n]
+
+
+def bits_of(t) -> np.ndarray:
+    """Raw bit patterns of an output tensor as numpy (u8 / u32 / u16)."""
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    if t.dtype == torch.float32:
+        return t.view(torch.int32).cpu().numpy().view(np.uint32)
+    return t.cpu().numpy()

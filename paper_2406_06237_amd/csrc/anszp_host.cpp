@@ -1,0 +1,289 @@
+// Host side of libanszp: frequency normalisation, decode-table construction and the
+// offline compressor.  No HIP calls here, so these entry points work on a machine
+// without a GPU.
+//
+// Paper sections followed: Sec. II-A (automaton, look-up table entry = symbol, nb_bits,
+// newX; rate depends on how symbols are spread over states), Sec. III-A (one table per
+// layer), Sec. III-B (parallel streams sharing one table).
+#include "anszp.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <queue>
+#include <vector>
+
+namespace {
+
+constexpr int kMaxMerged = 8;   // symbols one merged entry may emit
+
+bool freqs_ok(const uint32_t* f, int table_log) {
+    uint64_t total = 0;
+    for (int s = 0; s < ANSZP_ALPHABET; ++s) total += f[s];
+    return total == (1ull << table_log);
+}
+
+// Position of occurrence i of a symbol with frequency f is (2i+1)/(2f).  Ordered by that
+// fraction, ties by symbol.  Kept as numerator/denominator and compared by cross product.
+struct Slot {
+    uint64_t num;   // 2i+1
+    uint64_t den;   // f (the common factor 2 cancels)
+    uint32_t sym;
+};
+struct SlotLater {
+    bool operator()(const Slot& a, const Slot& b) const {
+        const uint64_t l = a.num * b.den, r = b.num * a.den;
+        if (l != r) return l > r;
+        return a.sym > b.sym;
+    }
+};
+
+// Sec. II-A "initialization of the states": merge the per-symbol position sequences.
+void spread_states(const uint32_t* f, int table_log, std::vector<uint8_t>& state_sym) {
+    const uint32_t L = 1u << table_log;
+    state_sym.resize(L);
+    std::priority_queue<Slot, std::vector<Slot>, SlotLater> heap;
+    for (uint32_t s = 0; s < ANSZP_ALPHABET; ++s)
+        if (f[s]) heap.push(Slot{1, f[s], s});
+    for (uint32_t X = 0; X < L; ++X) {
+        Slot top = heap.top();
+        heap.pop();
+        state_sym[X] = static_cast<uint8_t>(top.sym);
+        top.num += 2;
+        if (top.num < 2ull * top.den) heap.push(top);
+    }
+}
+
+struct StepTable {
+    std::vector<uint8_t> sym, nb;
+    std::vector<uint16_t> newX;
+};
+
+// Sec. II-A table: the j-th state (in increasing X) of symbol s has sub-state f_s + j; it is
+// shifted left until it lies in [L, 2L).
+void build_step_table(const uint32_t* f, int table_log, StepTable& t) {
+    const uint32_t L = 1u << table_log;
+    spread_states(f, table_log, t.sym);
+    t.nb.assign(L, 0);
+    t.newX.assign(L, 0);
+    uint32_t sub[ANSZP_ALPHABET];
+    for (int s = 0; s < ANSZP_ALPHABET; ++s) sub[s] = f[s];
+    for (uint32_t X = 0; X < L; ++X) {
+        uint32_t v = sub[t.sym[X]]++;
+        uint32_t shift = 0;
+        while (v < L) { v <<= 1; ++shift; }
+        t.nb[X] = static_cast<uint8_t>(shift);
+        t.newX[X] = static_cast<uint16_t>(v - L);
+    }
+}
+
+void build_one_table(const uint32_t* f, int table_log, uint64_t* out) {
+    const uint32_t L = 1u << table_log;
+    StepTable t;
+    build_step_table(f, table_log, t);
+    bool dominant = false;
+    for (int s = 0; s < ANSZP_ALPHABET; ++s)
+        if (f[s] > L / 2 && f[s] < L) dominant = true;
+    for (uint32_t X = 0; X < L; ++X) {
+        const uint64_t step = uint64_t(t.newX[X]) | (uint64_t(t.nb[X]) << 16) | (uint64_t(t.sym[X]) << 24);
+        // merged entry: follow empty-label transitions (they all carry the dominant symbol)
+        uint32_t Y = X, hops = 0;
+        if (dominant)
+            while (hops < kMaxMerged && t.nb[Y] == 0) { Y = t.newX[Y]; ++hops; }
+        uint32_t count, last_sym, last_nb, last_newX, end_flag;
+        if (hops == kMaxMerged) {            // eight empty transitions, continue from Y
+            count = kMaxMerged; last_sym = t.sym[X]; last_nb = 0; last_newX = Y; end_flag = 0;
+        } else {                             // hops empty transitions, then the one at Y
+            count = hops + 1; last_sym = t.sym[Y]; last_nb = t.nb[Y]; last_newX = t.newX[Y];
+            end_flag = (Y == 0) ? 1u : 0u;
+        }
+        const uint64_t merged = uint64_t(count - 1) | (uint64_t(last_newX) << 3) | (uint64_t(end_flag) << 15) |
+                                (uint64_t(last_sym) << 16) | (uint64_t(last_nb) << 24);
+        out[X] = step | (merged << 32);
+    }
+}
+
+// Writes bit groups from the end of a scratch bit array towards its start (encoding runs over
+// the symbols backwards, the decoder reads forwards).
+class BackwardBits {
+public:
+    explicit BackwardBits(uint64_t max_bits) : words_((max_bits + 63) / 64 + 1, 0), pos_(words_.size() * 64) {}
+    void put(uint32_t value, uint32_t nbits) {
+        if (!nbits) return;
+        pos_ -= nbits;
+        const uint64_t w = pos_ >> 6, sh = pos_ & 63;
+        words_[w] |= uint64_t(value) << sh;
+        if (sh + nbits > 64) words_[w + 1] |= uint64_t(value) >> (64 - sh);
+    }
+    uint64_t bit_count() const { return words_.size() * 64 - pos_; }
+    // copy the written bits, first written-last, to 32-bit words starting at bit 0
+    void extract(uint32_t* dst, uint64_t n_words32) const {
+        const uint64_t total = bit_count();
+        for (uint64_t i = 0; i < n_words32; ++i) {
+            const uint64_t b = pos_ + 32 * i;
+            const uint64_t w = b >> 6, sh = b & 63;
+            uint64_t v = words_[w] >> sh;
+            if (sh > 32 && w + 1 < words_.size()) v |= words_[w + 1] << (64 - sh);
+            uint32_t out = static_cast<uint32_t>(v);
+            const uint64_t left = total - 32 * i;
+            if (left < 32) out &= (1u << left) - 1u;
+            dst[i] = out;
+        }
+    }
+private:
+    std::vector<uint64_t> words_;
+    uint64_t pos_;
+};
+
+struct Encoder {
+    uint32_t L;
+    uint32_t f[ANSZP_ALPHABET];
+    uint32_t first[ANSZP_ALPHABET];        // index of symbol s's first state in `states`
+    std::vector<uint16_t> states;          // states of each symbol in increasing X
+    void init(const uint32_t* freqs, int table_log) {
+        L = 1u << table_log;
+        std::vector<uint8_t> state_sym;
+        spread_states(freqs, table_log, state_sym);
+        uint32_t acc = 0;
+        for (int s = 0; s < ANSZP_ALPHABET; ++s) { f[s] = freqs[s]; first[s] = acc; acc += freqs[s]; }
+        states.resize(L);
+        uint32_t fill[ANSZP_ALPHABET];
+        std::memcpy(fill, first, sizeof(fill));
+        for (uint32_t X = 0; X < L; ++X) states[fill[state_sym[X]]++] = static_cast<uint16_t>(X);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+int anszp_version(void) { return 100; }
+
+const char* anszp_strerror(int code) {
+    switch (code) {
+        case ANSZP_OK: return "ok";
+        case ANSZP_E_NULL: return "required pointer is NULL";
+        case ANSZP_E_RANGE: return "argument out of range";
+        case ANSZP_E_FREQ: return "frequencies do not sum to 2^table_log (or cannot be normalised)";
+        case ANSZP_E_SYMBOL: return "symbol with zero frequency in the data";
+        case ANSZP_E_SPACE: return "output buffer too small or stream longer than 65535 words";
+        case ANSZP_E_HIP: return "HIP runtime error";
+        case ANSZP_E_NOMEM: return "host allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs) {
+    if (!counts || !freqs) return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG) return ANSZP_E_RANGE;
+    const uint64_t L = 1ull << table_log;
+    unsigned __int128 total = 0;
+    uint32_t distinct = 0;
+    for (int s = 0; s < ANSZP_ALPHABET; ++s) { total += counts[s]; distinct += counts[s] != 0; }
+    if (total == 0 || distinct > L) return ANSZP_E_FREQ;
+    int64_t assigned = 0;
+    for (int s = 0; s < ANSZP_ALPHABET; ++s) {
+        uint64_t share = static_cast<uint64_t>((static_cast<unsigned __int128>(counts[s]) * L) / total);
+        if (counts[s] && share == 0) share = 1;
+        freqs[s] = static_cast<uint32_t>(share);
+        assigned += static_cast<int64_t>(share);
+    }
+    // the remainder goes, unit by unit, to (or comes from) whichever symbol is largest then
+    for (int64_t rest = static_cast<int64_t>(L) - assigned; rest != 0;) {
+        uint32_t* top = std::max_element(freqs, freqs + ANSZP_ALPHABET);   // first maximum
+        if (rest > 0) { ++*top; --rest; }
+        else { if (*top <= 1) return ANSZP_E_FREQ; --*top; ++rest; }
+    }
+    return ANSZP_OK;
+}
+
+int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint64_t* tables) {
+    if (!freqs || !tables) return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
+    for (int t = 0; t < n_tables; ++t)
+        if (!freqs_ok(freqs + size_t(t) * ANSZP_ALPHABET, table_log)) return ANSZP_E_FREQ;
+    try {
+        for (int t = 0; t < n_tables; ++t)
+            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << table_log));
+    } catch (const std::bad_alloc&) {
+        return ANSZP_E_NOMEM;
+    }
+    return ANSZP_OK;
+}
+
+int anszp_pack_bound(uint64_t n_symbols, int table_log, int n_streams, uint32_t chunk_size,
+                     uint64_t* n_chunks, uint64_t* payload_words) {
+    if (!n_chunks || !payload_words) return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_streams < 1 || n_streams > ANSZP_MAX_STREAMS ||
+        chunk_size < 1)
+        return ANSZP_E_RANGE;
+    const uint64_t nc = (n_symbols + chunk_size - 1) / chunk_size;
+    *n_chunks = nc;
+    // at most table_log bits per symbol, one partial word per stream, three pad words per chunk
+    *payload_words = (n_symbols * uint64_t(table_log) + 31) / 32 + nc * (uint64_t(n_streams) + 3);
+    return ANSZP_OK;
+}
+
+int anszp_pack_layer(const uint8_t* symbols, uint64_t n_symbols, const uint32_t* freqs,
+                     int table_log, int n_streams, uint32_t chunk_size,
+                     uint32_t layer_id, uint64_t out_offset, uint64_t payload_word_offset,
+                     uint32_t stream_offset,
+                     anszp_chunk_t* chunks_out, uint32_t* stream_hdr_out,
+                     uint32_t* payload_out, uint64_t payload_cap_words, uint64_t* payload_words_used) {
+    if (!freqs || !payload_words_used || (n_symbols && (!symbols || !chunks_out || !stream_hdr_out)))
+        return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_streams < 1 || n_streams > ANSZP_MAX_STREAMS ||
+        chunk_size < 1 || (payload_word_offset & 3))
+        return ANSZP_E_RANGE;
+    if (!freqs_ok(freqs, table_log)) return ANSZP_E_FREQ;
+    if (!payload_out && payload_cap_words) return ANSZP_E_NULL;
+    try {
+        Encoder enc;
+        enc.init(freqs, table_log);
+        const uint32_t N = static_cast<uint32_t>(n_streams);
+        const uint64_t n_chunks = (n_symbols + chunk_size - 1) / chunk_size;
+        uint64_t cursor = 0;                                   // words written so far
+        for (uint64_t c = 0; c < n_chunks; ++c) {
+            const uint64_t begin = c * uint64_t(chunk_size);
+            const uint32_t cn = static_cast<uint32_t>(std::min<uint64_t>(chunk_size, n_symbols - begin));
+            anszp_chunk_t& d = chunks_out[c];
+            d.layer_id = layer_id;
+            d.n_symbols = cn;
+            d.out_offset = out_offset + begin;
+            d.payload_offset = payload_word_offset + cursor;
+            d.stream_offset = stream_offset + static_cast<uint32_t>(c) * N;
+            uint32_t chunk_words = 0;
+            for (uint32_t k = 0; k < N; ++k) {
+                const uint32_t len = cn > k ? (cn - k + N - 1) / N : 0;
+                BackwardBits bits(uint64_t(len) * table_log);
+                uint32_t x = enc.L;                            // every stream starts in X = 0
+                for (uint32_t i = len; i-- > 0;) {
+                    const uint32_t s = symbols[begin + k + uint64_t(i) * N];
+                    const uint32_t fs = enc.f[s];
+                    if (!fs) return ANSZP_E_SYMBOL;
+                    uint32_t drop = 0;
+                    while ((x >> drop) >= 2 * fs) ++drop;      // bring x into [f_s, 2 f_s)
+                    bits.put(x & ((1u << drop) - 1u), drop);
+                    x = enc.L + enc.states[enc.first[s] + (x >> drop) - fs];
+                }
+                const uint64_t nw = (bits.bit_count() + 31) / 32;
+                if (nw > 0xFFFF || cursor + nw > payload_cap_words) return ANSZP_E_SPACE;
+                bits.extract(payload_out + cursor, nw);
+                stream_hdr_out[c * N + k] = (x - enc.L) | (static_cast<uint32_t>(nw) << 16);
+                cursor += nw;
+                chunk_words += static_cast<uint32_t>(nw);
+            }
+            d.payload_words = chunk_words;
+            while (cursor & 3) {
+                if (cursor >= payload_cap_words) return ANSZP_E_SPACE;
+                payload_out[cursor++] = 0;
+            }
+        }
+        *payload_words_used = cursor;
+    } catch (const std::bad_alloc&) {
+        return ANSZP_E_NOMEM;
+    }
+    return ANSZP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,138 @@
+"""GPU parity: libanszp's decode + dequant through the C ABI against the CPU oracle, element by
+element and bit for bit, on containers the ORACLE's encoder produced."""
+import numpy as np
+import pytest
+
+from paper_2406_06237_amd import binding as B
+from paper_2406_06237_amd import workloads as W
+
+from helpers import host_from_oracle, oracle_encode, oracle_expected
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(orc, w, out_dtype=None):
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w, out_dtype)
+    d = B.to_device(host_from_oracle(c, w))
+    out = B.decode(d, out_dtype=out_dtype)
+    status = d.read_status()
+    got = B.bits_of(out)[:w.numel]
+    assert status == (0, 0), f"status {status}"
+    bad = np.nonzero(got != expect)[0]
+    assert len(bad) == 0, f"{len(bad)} mismatches, first at {bad[:5]}: got {got[bad[:5]]} want {expect[bad[:5]]}"
+    return d, out
+
+
+def test_config1_single_conv_fp32(orc):
+    _run(orc, W.config1())
+
+
+@pytest.mark.parametrize("dtype", ["u8", "f32", "bf16"])
+@pytest.mark.parametrize("N,chunk,n,R,b,p0", [
+    (64, 2048, 5000, 10, 4, 0.8), (64, 65536, 65536 + 1000, 12, 8, 0.7), (32, 16384, 40000, 11, 3, 0.6),
+    (1, 3000, 7001, 10, 4, 0.5), (7, 100, 999, 9, 2, 0.9), (64, 4096, 40, 8, 5, 0.75),
+    (64, 1024, 3 * 1024, 12, 1, 0.95), (33, 555, 5555, 6, 6, 0.3), (64, 128, 1, 5, 4, 0.8),
+])
+def test_ragged_geometries(orc, dtype, N, chunk, n, R, b, p0):
+    w = W.tiny(seed=n, n=n, bitwidth=b, n_streams=N, chunk_size=chunk, table_log=R, p0=p0, out_dtype=dtype)
+    _run(orc, w)
+
+
+def test_single_symbol_layer_and_flat_distribution(orc):
+    z = 4
+    lay = W.Layer("const", (10000,), 3, z, 0.5, np.eye(1, 8, z)[0], 5)
+    flat = W.Layer("flat", (20000,), 8, 128, 0.01, np.ones(256) / 256, 6)
+    w = W.Workload("mix", [lay, flat, lay], 12, 64, 4096, "bf16")
+    _run(orc, w)
+    _run(orc, w, "f32")
+
+
+def test_per_channel_scales(orc):
+    w = W.config4(n_blocks=1, d_model=256, d_ff=704)
+    w.chunk_size = 32768
+    _run(orc, w)
+    _run(orc, w, "f32")
+    # channel length that is not a multiple of the stream count
+    rng = np.random.default_rng(1)
+    lay = W.Layer("odd", (37, 101), 4, 8, 0.0, W.laplace_pmf(16, 8, 1.0), 9, channel_len=101,
+                  channel_scales=rng.uniform(0.005, 0.05, 37).astype(np.float32))
+    _run(orc, W.Workload("odd", [lay, lay], 10, 64, 1000, "bf16"))
+
+
+def test_config2_resnet18(orc):
+    _run(orc, W.config2())
+
+
+def test_config3_resnet50(orc):
+    _run(orc, W.config3())
+
+
+def test_library_packer_output_decodes_too(orc):
+    """The same weights compressed by the library's own host packer."""
+    w = W.tiny(n=70000, chunk_size=8192, table_log=11, p0=0.85)
+    h = B.pack_workload(w)
+    d = B.to_device(h)
+    out = B.decode(d)
+    assert d.read_status() == (0, 0)
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    assert np.array_equal(B.bits_of(out)[:w.numel], expect)
+
+
+def test_dequant_zp_alone(orc):
+    import torch
+    rng = np.random.default_rng(2)
+    q = rng.integers(0, 256, size=100003, dtype=np.uint8)
+    qd = torch.from_numpy(q).cuda()
+    for dt in ("f32", "bf16"):
+        got = B.bits_of(B.dequant_zp(qd, 128, 0.0173, dt))
+        want = orc.dequant(q, 128, 0.0173, dt)
+        assert np.array_equal(got, want.view(np.uint32) if dt == "f32" else want)
+    scales = rng.uniform(0.001, 0.1, size=1001).astype(np.float32)
+    got = B.bits_of(B.dequant_zp(qd, 7, 0.0, "bf16", 100, torch.from_numpy(scales).cuda()))
+    assert np.array_equal(got, orc.dequant(q, 7, 0.0, "bf16", 100, scales))
+    # tie and denormal cases of the bf16 rounding
+    for pattern in (0x3F808000, 0x3F818000, 0x00000007, 0x7F000000 // 255):
+        s = float(np.array([pattern], np.uint32).view(np.float32)[0])
+        small = torch.arange(0, 256, dtype=torch.uint8).cuda()
+        for dt in ("f32", "bf16"):
+            got = B.bits_of(B.dequant_zp(small, 3, s, dt))
+            want = orc.dequant(np.arange(256, dtype=np.uint8), 3, s, dt)
+            assert np.array_equal(got, want.view(np.uint32) if dt == "f32" else want)
+
+
+def test_corruption_is_flagged_not_fatal(orc):
+    """Damaged inputs set status bits; nothing is read or written outside the buffers."""
+    import torch
+    w = W.tiny(n=50000, chunk_size=4096, table_log=10, p0=0.7)
+    c = oracle_encode(orc, w)
+    good = host_from_oracle(c, w)
+
+    def status_of(h):
+        d = B.to_device(h)
+        guard = torch.full((w.numel + 4096,), 0x5A5A, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        B.decode_raw(B.decode_args(d, guard), d.device)
+        st = d.read_status()
+        assert bool((guard[w.numel:].view(torch.int16) == 0x5A5A).all()), "wrote past the output"
+        return st
+
+    assert status_of(good) == (0, 0)
+    import copy
+    h = copy.deepcopy(good); h.payload[len(h.payload) // 2] ^= np.uint32(0x10)
+    assert status_of(h)[0] & (B.ST_BAD_STATE | B.ST_BAD_LENGTH)
+    h = copy.deepcopy(good); h.stream_hdr[5] ^= np.uint32(1)
+    assert status_of(h)[0] & (B.ST_BAD_STATE | B.ST_BAD_LENGTH)
+    h = copy.deepcopy(good); h.stream_hdr[7] += np.uint32(1 << 16)
+    assert status_of(h)[0] != 0
+    h = copy.deepcopy(good); h.payload = h.payload[: len(h.payload) // 2].copy()
+    assert status_of(h)[0] & B.ST_BAD_DESC
+    h = copy.deepcopy(good); h.chunks["out_offset"][3] = w.numel
+    assert status_of(h)[0] & B.ST_BAD_DESC
+    h = copy.deepcopy(good); h.chunks["layer_id"][0] = 9
+    assert status_of(h)[0] & B.ST_BAD_DESC
+    h = copy.deepcopy(good); h.chunks["stream_offset"][-1] = len(h.stream_hdr)
+    assert status_of(h)[0] & B.ST_BAD_DESC
+    h = copy.deepcopy(good); h.chunks["n_symbols"][2] += 1
+    st = status_of(h)
+    assert st[0] != 0 and st[1] >= 1

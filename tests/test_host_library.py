@@ -1,0 +1,181 @@
+"""CPU-side checks of libanszp: the ABI surface and the host entry points (no GPU calls).
+
+The library's table builder and packer are written independently of the oracle; both follow
+the same container definition, so their outputs must agree bit for bit.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2406_06237_amd import binding as B
+from paper_2406_06237_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "anszp.h")).read()
+    declared = sorted(set(re.findall(r"\b(anszp_[a-z_0-9]+)\s*\(", header)))
+    assert declared == sorted(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.version() == 100
+    assert B.strerror(0) == "ok" and "range" in B.strerror(-2)
+
+
+def test_struct_layouts_match_header():
+    # sizes and offsets as the C compiler lays the header's structs out
+    src = ('#include <stdio.h>\n#include <stddef.h>\n#include "anszp.h"\nint main(void){printf("%zu %zu %zu %zu %zu %zu\\n",'
+           'sizeof(anszp_decode_args_t), offsetof(anszp_decode_args_t, status), offsetof(anszp_decode_args_t, out),'
+           'sizeof(anszp_chunk_t), sizeof(anszp_layer_t), offsetof(anszp_decode_args_t, chunks));return 0;}')
+    import subprocess, tempfile
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.c"), "w").write(src)
+        subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", os.path.join(d, "t"), os.path.join(d, "t.c")])
+        got = [int(v) for v in subprocess.check_output([os.path.join(d, "t")]).split()]
+    assert got == [C.sizeof(B.DecodeArgs), B.DecodeArgs.status.offset, B.DecodeArgs.out.offset,
+                   B.CHUNK_DTYPE.itemsize, B.LAYER_DTYPE.itemsize, B.DecodeArgs.chunks.offset]
+    assert B.CHUNK_DTYPE.fields["out_offset"][1] == 8 and B.CHUNK_DTYPE.fields["payload_words"][1] == 24
+    assert B.LAYER_DTYPE.fields["scales_offset"][1] == 16 and B.LAYER_DTYPE.fields["out_base"][1] == 24
+
+
+def _random_freqs(rng, R, max_syms=40):
+    L = 1 << R
+    A = int(rng.integers(1, min(L, max_syms) + 1))
+    cuts = np.sort(rng.choice(np.arange(1, L), size=A - 1, replace=False)) if A > 1 else np.array([], int)
+    f = np.zeros(256, dtype=np.uint32)
+    f[np.sort(rng.choice(256, size=A, replace=False))] = np.diff(np.concatenate(([0], cuts, [L])))
+    return f
+
+
+@pytest.mark.parametrize("R", [1, 2, 5, 8, 10, 11, 12])
+def test_tables_equal_oracle_tables(orc, R):
+    rng = np.random.default_rng(100 + R)
+    rows = [_random_freqs(rng, R) for _ in range(6)]
+    L = 1 << R
+    peaked = np.zeros(256, dtype=np.uint32)
+    peaked[9] = L - min(3, L - 1)
+    rest = L - int(peaked[9])
+    for i in range(rest):
+        peaked[10 + i] = 1
+    rows.append(peaked)
+    single = np.zeros(256, dtype=np.uint32)
+    single[200] = L
+    rows.append(single)
+    tables = B.build_tables_host(np.stack(rows), R)
+    for row, t in zip(rows, tables):
+        f = B.split_table(t)
+        sym, nb, newX = orc.decode_table(row, R)
+        assert np.array_equal(f["sym"], sym) and np.array_equal(f["nb"], nb) and np.array_equal(f["newX"], newX)
+
+
+@pytest.mark.parametrize("R", [3, 8, 12])
+def test_merged_entries_follow_the_step_automaton(orc, R):
+    """The second half of an entry is the same automaton with up to 8 steps merged: replaying
+    single steps from the oracle's table must give the same symbols, bit count and next state."""
+    L = 1 << R
+    rng = np.random.default_rng(R)
+    for p0 in (0.55, 0.75, 0.9, 0.97, 0.999):
+        f = np.zeros(256, dtype=np.uint32)
+        f[7] = max(L // 2 + 1, min(L - 2, int(p0 * L)))
+        rest = L - int(f[7])
+        others = rng.multinomial(rest, np.ones(5) / 5) if rest >= 5 else np.array([rest, 0, 0, 0, 0])
+        f[20:25] = others
+        if f[7] <= L // 2:
+            continue
+        sym, nb, newX = orc.decode_table(f, R)
+        m = B.split_table(B.build_tables_host(f[None, :], R)[0])
+        assert int(m["count"].max()) <= 8
+        for X in range(L):
+            Y, emitted = X, []
+            c = int(m["count"][X])
+            for _ in range(c - 1):
+                assert nb[Y] == 0 and sym[Y] == 7
+                emitted.append(int(sym[Y]))
+                Y = int(newX[Y])
+            if c == 8 and nb[Y] == 0:                      # capped run: last symbol is an empty step too
+                assert m["m_nb"][X] == 0 and m["m_sym"][X] == 7 and m["m_newX"][X] == newX[Y]
+                assert m["m_end"][X] == 0
+            else:
+                assert c == 8 or nb[Y] > 0                 # runs are followed to their end
+                assert m["m_sym"][X] == sym[Y] and m["m_nb"][X] == nb[Y] and m["m_newX"][X] == newX[Y]
+                assert m["m_end"][X] == (1 if Y == 0 else 0)
+    # no dominant symbol: merged entry is the plain step
+    f = _random_freqs(np.random.default_rng(1), R, 6)
+    if f.max() <= L // 2:
+        m = B.split_table(B.build_tables_host(f[None, :], R)[0])
+        assert np.all(m["count"] == 1) and np.array_equal(m["m_newX"], m["newX"])
+        assert np.array_equal(m["m_nb"], m["nb"]) and np.array_equal(m["m_sym"], m["sym"])
+
+
+def test_normalize_equals_oracle(orc):
+    rng = np.random.default_rng(5)
+    for R in (4, 8, 10, 12):
+        for _ in range(25):
+            A = int(rng.integers(1, min(1 << R, 256) + 1))
+            counts = np.zeros(256, dtype=np.uint64)
+            counts[rng.choice(256, size=A, replace=False)] = rng.integers(1, 10 ** int(rng.integers(1, 9)), size=A)
+            assert np.array_equal(B.normalize_freqs(counts, R), orc.normalize(counts, R))
+    with pytest.raises(B.AnszpError):
+        B.normalize_freqs(np.zeros(256, dtype=np.uint64), 8)
+    with pytest.raises(B.AnszpError):
+        B.normalize_freqs(np.ones(256, dtype=np.uint64), 13)
+
+
+@pytest.mark.parametrize("N,chunk,n,R", [(1, 36864, 36864, 10), (32, 16384, 50000, 11), (64, 65536, 140001, 12),
+                                          (64, 1024, 37, 6), (5, 333, 4000, 9), (64, 4096, 0, 8)])
+def test_packer_equals_oracle_encoder(orc, N, chunk, n, R):
+    w = W.tiny(seed=n + N, n=max(n, 1), bitwidth=5, p0=0.83)
+    sym = w.layers[0].symbols()[:n]
+    if n == 0:
+        h = B.pack_layers([sym], R, N, chunk, [16], [0.1], freqs=[np.eye(1, 256, 3, dtype=np.uint32)[0] << R])
+        assert len(h.chunks) == 0 and len(h.payload) == 0
+        return
+    h = B.pack_layers([sym, sym[::-1].copy()], R, N, chunk, [16, 16], [0.1, 0.2])
+    c = orc.encode_layers([sym, sym[::-1].copy()], R, N, chunk)
+    assert np.array_equal(h.freqs, c.freqs)
+    assert np.array_equal(h.stream_hdr, c.stream_hdr)
+    assert np.array_equal(h.payload, c.payload)
+    assert np.array_equal(h.chunks["layer_id"], c.chunk_layer)
+    assert np.array_equal(h.chunks["n_symbols"], c.chunk_nsym)
+    assert np.array_equal(h.chunks["out_offset"], c.chunk_out_off)
+    assert np.array_equal(h.chunks["payload_offset"], c.chunk_payload_off)
+    assert np.array_equal(h.chunks["payload_words"], c.chunk_payload_words)
+    assert np.array_equal(h.chunks["stream_offset"], c.chunk_stream_off)
+    assert np.array_equal(h.layers["out_base"], c.layer_out_base)
+
+
+def test_host_error_codes():
+    lib = B.lib()
+    f = np.zeros(256, dtype=np.uint32)
+    f[0] = 255
+    t = np.zeros(256, dtype=np.uint64)
+    assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == -3          # sum != 2^R
+    f[0] = 256
+    assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == 0
+    assert lib.anszp_build_tables_host(f.ctypes.data, 1, 13, t.ctypes.data) == -2
+    assert lib.anszp_build_tables_host(None, 1, 8, t.ctypes.data) == -1
+    assert lib.anszp_build_tables_host(f.ctypes.data, 0, 8, t.ctypes.data) == -2
+    with pytest.raises(B.AnszpError) as e:
+        B.pack_layer(np.array([0, 1], dtype=np.uint8), f, 8, 64, 1024)                    # symbol 1 has f = 0
+    assert e.value.code == -4
+    with pytest.raises(B.AnszpError) as e:
+        B.pack_layer(np.array([0], dtype=np.uint8), f, 8, 65, 1024)
+    assert e.value.code == -2
+    with pytest.raises(B.AnszpError) as e:
+        B.pack_layer(np.array([0], dtype=np.uint8), f, 8, 64, 1024, payload_word_offset=2)
+    assert e.value.code == -2
+    # decode argument validation happens before any GPU call
+    a = B.DecodeArgs()
+    assert lib.anszp_decode(None, None) == -1
+    assert lib.anszp_decode(C.byref(a), None) == 0            # zero chunks: nothing to do
+    a.n_chunks = 1
+    assert lib.anszp_decode(C.byref(a), None) == -1           # NULL pointers
+    lay = np.zeros(1, dtype=B.LAYER_DTYPE)
+    assert lib.anszp_dequant_zp(None, 0, lay.ctypes.data, None, 0, None, 3, None) == -2
+    assert lib.anszp_dequant_zp(None, 0, lay.ctypes.data, None, 0, None, 1, None) == 0
+    assert lib.anszp_dequant_zp(None, 5, lay.ctypes.data, None, 0, None, 1, None) == -1
