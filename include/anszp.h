@@ -172,6 +172,16 @@ int anszp_pack_layer(const uint8_t* symbols, uint64_t n_symbols, const uint32_t*
  * payload or out not 16-byte aligned). */
 int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
 
+/* The same call with the kernel chosen by hand; results are identical for every variant.
+ *   0  automatic (what anszp_decode does)
+ *   1  step-wise kernel: one look-up per symbol, exactly the loop of Sec. II-A / III-B; also the
+ *      path any chunk takes whose compressed words exceed the on-chip window or whose first
+ *      output element is not 16-byte aligned
+ *   2  merged-run kernel: a run of empty-label transitions and the step that ends it are one
+ *      look-up, compressed words and decoded symbols are staged in LDS
+ * Errors: as anszp_decode, E_RANGE for an unknown variant. */
+int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
+
 /* Sec. II-B alone: out[i] = scale * (symbols[i] - zero_point) for i < n, the scale chosen as in
  * anszp_layer_t with the layer starting at element 0.  symbols_dev, scales_dev, out_dev: [device];
  * layer: [host].  out_dtype is ANSZP_OUT_F32 or ANSZP_OUT_BF16.  Errors: E_NULL, E_RANGE. */

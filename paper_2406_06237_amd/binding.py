@@ -47,7 +47,8 @@ class AnszpError(RuntimeError):
 
 _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
-           "anszp_build_tables", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_dequant_zp"]
+           "anszp_build_tables", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
+           "anszp_dequant_zp"]
 
 
 def lib():
@@ -67,6 +68,7 @@ def lib():
                                        C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         L.anszp_decode.argtypes = [C.POINTER(DecodeArgs), C.c_void_p]
+        L.anszp_decode_variant.argtypes = [C.POINTER(DecodeArgs), C.c_int, C.c_void_p]
         L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
                                        C.c_void_p, C.c_int, C.c_void_p]
         _lib = L
@@ -273,18 +275,25 @@ def decode_args(d: DeviceContainer, out, out_dtype: Optional[str] = None) -> Dec
     return a
 
 
-def decode_raw(args: DecodeArgs, device="cuda:0"):
-    """anszp_decode on torch's current stream of `device`."""
+VARIANT_AUTO, VARIANT_STEPWISE, VARIANT_MERGED = 0, 1, 2
+
+
+def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None):
+    """anszp_decode (or anszp_decode_variant) on torch's current stream of `device`."""
     torch = _torch()
     with torch.cuda.device(device):
-        _check(lib().anszp_decode(C.byref(args), _stream_ptr(torch, device)), "anszp_decode")
+        if variant is None:
+            _check(lib().anszp_decode(C.byref(args), _stream_ptr(torch, device)), "anszp_decode")
+        else:
+            _check(lib().anszp_decode_variant(C.byref(args), variant, _stream_ptr(torch, device)),
+                   "anszp_decode_variant")
 
 
-def decode(d: DeviceContainer, out=None, out_dtype: Optional[str] = None):
+def decode(d: DeviceContainer, out=None, out_dtype: Optional[str] = None, variant: Optional[int] = None):
     """Decode + dequantise the whole container; returns the output tensor (first numel elements valid)."""
     if out is None:
         out = alloc_out(d, out_dtype)
-    decode_raw(decode_args(d, out, out_dtype), d.device)
+    decode_raw(decode_args(d, out, out_dtype), d.device, variant)
     return out
 
 

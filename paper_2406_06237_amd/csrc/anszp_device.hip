@@ -2,8 +2,19 @@
 // dequantisation, and the stand-alone dequantiser.
 //
 // Paper sections followed: Sec. II-A (one decode step = table look-up, read nb_bits, state =
-// newX + bits), Sec. III-B (a vector of states, one per stream, all sharing one table: here a
-// 64-lane wavefront is the vector and a lane is a stream), Sec. II-B (w = scale * (q - z)).
+// newX + bits; empty-label transitions read no bits), Sec. III-B (a vector of states, one per
+// stream, all sharing one table: here a 64-lane wavefront is the vector and a lane is a stream),
+// Sec. III-A (one table per layer), Sec. II-B (w = scale * (q - z)).
+//
+// Two code paths produce identical results:
+//   decode_chunk_stepwise  one look-up per symbol, words read from global memory; handles every
+//                          geometry the ABI allows.
+//   decode_chunk_merged    look-ups use the merged half of the table entries (a run of empty-label
+//                          transitions of the dominant symbol plus the step that ends it is ONE
+//                          look-up), the chunk's compressed words are staged in LDS, symbols are
+//                          gathered in an LDS ring and leave as 16-byte-per-lane coalesced stores.
+// The merged path needs the chunk's words to fit its LDS window and the chunk's first output
+// element to be 16-byte aligned; other chunks take the step-wise path inside the same launch.
 #include "anszp.h"
 
 #include <hip/hip_runtime.h>
@@ -11,6 +22,13 @@
 namespace {
 
 constexpr int kWave = 64;
+constexpr int kBlock = 256;                    // 4 wavefronts stage; wavefront 0 decodes
+constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB of LDS entries
+constexpr uint32_t kRingBytes = 16u * 1024u;   // LDS ring of decoded codes (2 bytes each)
+constexpr uint32_t kRingElems = kRingBytes / 2u;
+constexpr uint32_t kSlab = 512u;               // elements flushed per wave store (8 per lane)
+constexpr uint32_t kPayloadWords = 7680u;      // LDS window for one chunk's compressed words
+constexpr uint32_t kMaxMerged = 8u;
 
 struct DecodeParams {
     const uint64_t* tables;
@@ -30,21 +48,21 @@ struct DecodeParams {
     uint32_t n_streams;
 };
 
-__device__ __forceinline__ uint16_t bf16_rne(float w) {
+__device__ __forceinline__ uint32_t bf16_rne(float w) {
     uint32_t u = __float_as_uint(w);
     u += 0x7FFFu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float dequant(uint32_t sym, uint32_t z, float scale) {
+    return scale * static_cast<float>(static_cast<int>(sym) - static_cast<int>(z));
 }
 
 template <int OUT>
 __device__ __forceinline__ void store_weight(void* out, uint64_t idx, uint32_t sym, uint32_t z, float scale) {
-    if constexpr (OUT == ANSZP_OUT_U8) {
-        static_cast<uint8_t*>(out)[idx] = static_cast<uint8_t>(sym);
-    } else {
-        const float w = scale * static_cast<float>(static_cast<int>(sym) - static_cast<int>(z));
-        if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(out)[idx] = w;
-        else static_cast<uint16_t*>(out)[idx] = bf16_rne(w);
-    }
+    if constexpr (OUT == ANSZP_OUT_U8) static_cast<uint8_t*>(out)[idx] = static_cast<uint8_t>(sym);
+    else if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(out)[idx] = dequant(sym, z, scale);
+    else static_cast<uint16_t*>(out)[idx] = static_cast<uint16_t>(bf16_rne(dequant(sym, z, scale)));
 }
 
 __device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
@@ -64,34 +82,34 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
     return inc - v;
 }
 
-// Returns true (for the whole wavefront) when the chunk descriptor stays inside the caller's buffers.
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) v |= __shfl_xor(v, d, kWave);
+    return v;
+}
+
+// True (for the whole workgroup) when the chunk descriptor stays inside the caller's buffers.
 __device__ __forceinline__ bool chunk_in_bounds(const DecodeParams& p, const anszp_chunk_t& c) {
-    return c.layer_id < p.n_tables &&
+    return c.layer_id < p.n_tables && c.n_symbols <= (1u << 31) &&
            c.out_offset <= p.out_elems && c.n_symbols <= p.out_elems - c.out_offset &&
            c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
            uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
 }
 
+__device__ __forceinline__ float channel_scale(const DecodeParams& p, const anszp_layer_t& lay, uint64_t layer_elem) {
+    const uint64_t ch = lay.scales_offset + layer_elem / lay.channel_len;
+    return ch < p.n_scales ? p.scales[ch] : 0.0f;
+}
+
 // ---------------------------------------------------------------------------------------------
-// Reference-shaped kernel: one wavefront per chunk, one lane per stream, one table look-up per
-// symbol (Sec. III-B: n look-ups and n small additions for a stream of n weights).  Handles
-// every geometry the ABI allows; compressed words are read straight from global memory.
+// One look-up per symbol (Sec. III-B: n look-ups and n small additions for a stream of n
+// weights).  Executed by one wavefront; `table` is 2^table_log dwords of LDS holding the
+// (newX, nb_bits, symbol) half of the entries.  Returns the chunk's error bits (wave-uniform).
 template <int OUT>
-__global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
-    __shared__ uint32_t table[1u << ANSZP_MAX_TABLE_LOG];
-    const uint32_t lane = threadIdx.x;
+__device__ uint32_t decode_chunk_stepwise(const DecodeParams& p, const anszp_chunk_t& c, const anszp_layer_t& lay,
+                                          const uint32_t* table, uint32_t lane) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
-    const anszp_chunk_t c = p.chunks[blockIdx.x];
-    if (!chunk_in_bounds(p, c)) {
-        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
-        return;
-    }
-    const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
-    for (uint32_t i = lane; i < L; i += kWave) table[i] = static_cast<uint32_t>(src[i]);
-    const anszp_layer_t lay = p.layers[c.layer_id];
-    __syncthreads();
-
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
     uint32_t X = hdr & (L - 1u);
     const uint32_t n_words = hdr >> 16;
@@ -123,11 +141,7 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
             have -= nb;
             X = ((e & 0xFFFFu) + bits) & (L - 1u);
             const uint64_t j = uint64_t(t) * N + lane;
-            float scale = lay.scale;
-            if (per_channel) {
-                const uint64_t ch = lay.scales_offset + (layer_elem0 + j) / lay.channel_len;
-                scale = ch < p.n_scales ? p.scales[ch] : 0.0f;
-            }
+            const float scale = per_channel ? channel_scale(p, lay, layer_elem0 + j) : lay.scale;
             store_weight<OUT>(p.out, c.out_offset + j, e >> 24, lay.zero_point, scale);
         }
     }
@@ -135,11 +149,258 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
         if (X != 0) err |= ANSZP_ST_BAD_STATE;
         if (next_word - first_word != n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
-    // one report per chunk
-    uint32_t any = err;
+    return wave_or(err);
+}
+
+template <int OUT>
+__global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
+    __shared__ uint32_t table[1u << ANSZP_MAX_TABLE_LOG];
+    const uint32_t lane = threadIdx.x;
+    const anszp_chunk_t c = p.chunks[blockIdx.x];
+    if (!chunk_in_bounds(p, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
+    for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = static_cast<uint32_t>(src[i]);
+    const anszp_layer_t lay = p.layers[c.layer_id];
+    __syncthreads();
+    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
+    if (err && lane == 0) report(p.status, err);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Merged-run path.
+//
+// LDS entry (8 bytes) derived from the merged half of a table entry while staging:
+//   lo: bits 0..2 c-1 | bits 3..14 newX' (so lo & 0x7FF8 is the byte offset of the next entry
+//       before the stream bits are OR-ed in) | bit 15 end-flag | bits 16..31 code of symbol'
+//   hi: (1 << nb_bits') - 1
+// One look-up emits c symbols: c-1 copies of the dominant symbol, which the ring already holds
+// as background, then symbol'.  code = bf16 weight when the output is bf16 with a per-layer
+// scale (dequantisation folded into the table), else the symbol itself and dequantisation
+// happens when a slab leaves the ring.
+template <int OUT, bool PER_CHANNEL>
+struct Flusher {
+    // Convert the 8 codes of one lane (elements g .. g+7 of the output) and store them.
+    static __device__ __forceinline__ void store8(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
+                                                  uint64_t layer_elem, uint4 codes) {
+        if constexpr (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL) {
+            *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) = codes;
+        } else {
+            const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+            uint32_t sym[8];
 #pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) any |= __shfl_xor(any, d, kWave);
-    if (any && lane == 0) report(p.status, any);
+            for (int i = 0; i < 4; ++i) { sym[2 * i] = w[i] & 0xFFFFu; sym[2 * i + 1] = w[i] >> 16; }
+            if constexpr (OUT == ANSZP_OUT_U8) {
+                uint2 o;
+                o.x = sym[0] | (sym[1] << 8) | (sym[2] << 16) | (sym[3] << 24);
+                o.y = sym[4] | (sym[5] << 8) | (sym[6] << 16) | (sym[7] << 24);
+                *reinterpret_cast<uint2*>(static_cast<uint8_t*>(p.out) + g) = o;
+            } else {
+                float v[8];
+                if constexpr (PER_CHANNEL) {
+                    const uint32_t e0 = static_cast<uint32_t>(layer_elem);
+                    const uint32_t left = lay.channel_len - e0 % lay.channel_len;   // elements left in this channel
+                    if (left >= 8u) {
+                        const float s = channel_scale(p, lay, layer_elem);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = dequant(sym[i], lay.zero_point, s);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            v[i] = dequant(sym[i], lay.zero_point, channel_scale(p, lay, layer_elem + i));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = dequant(sym[i], lay.zero_point, lay.scale);
+                }
+                if constexpr (OUT == ANSZP_OUT_F32) {
+                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(p.out) + g);
+                    dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+                    dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+                } else {
+                    uint4 o;
+                    o.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
+                    o.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
+                    o.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
+                    o.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
+                    *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) = o;
+                }
+            }
+        }
+    }
+    // One element (tail of a chunk).
+    static __device__ __forceinline__ void store1(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
+                                                  uint64_t layer_elem, uint32_t code) {
+        if constexpr (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL) {
+            static_cast<uint16_t*>(p.out)[g] = static_cast<uint16_t>(code);
+        } else {
+            const float s = PER_CHANNEL ? channel_scale(p, lay, layer_elem) : lay.scale;
+            store_weight<OUT>(p.out, g, code, lay.zero_point, s);
+        }
+    }
+};
+
+template <int OUT, bool PER_CHANNEL>
+__global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_table[kTableBytes];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_ring[kRingElems];
+    __shared__ __attribute__((aligned(16))) uint32_t lds_words[kPayloadWords + 8];
+    constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
+    constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & (kWave - 1);
+    const uint32_t N = p.n_streams;
+    const uint32_t L = 1u << p.table_log;
+    const anszp_chunk_t c = p.chunks[blockIdx.x];
+    if (!chunk_in_bounds(p, c)) {
+        if (tid == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const anszp_layer_t lay = p.layers[c.layer_id];
+    const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
+    const uint64_t layer_elem0 = c.out_offset - lay.out_base;
+    const bool merged_ok = c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
+                           PER_CHANNEL == (lay.channel_len != 0) &&
+                           (!PER_CHANNEL || layer_elem0 + c.n_symbols < (1ull << 32));
+
+    if (!merged_ok) {                                     // whole workgroup agrees
+        uint32_t* table = reinterpret_cast<uint32_t*>(lds_table);
+        for (uint32_t i = tid; i < L; i += kBlock) table[i] = static_cast<uint32_t>(src[i]);
+        __syncthreads();
+        if (tid >= kWave) return;
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
+        if (err && lane == 0) report(p.status, err);
+        return;
+    }
+
+    // ---- stage: table (with dequantisation folded in), compressed words, ring background
+    const uint32_t top = static_cast<uint32_t>(src[L - 1]);            // state L-1: dominant symbol if nb == 0
+    const uint32_t bg_sym = top >> 24;
+    const uint32_t bg_code = kFolded ? bf16_rne(dequant(bg_sym, lay.zero_point, lay.scale)) : bg_sym;
+    const uint32_t bg2 = bg_code | (bg_code << 16);
+    {
+        uint2* dst = reinterpret_cast<uint2*>(lds_table);
+        for (uint32_t i = tid; i < L; i += kBlock) {
+            const uint32_t m = static_cast<uint32_t>(src[i] >> 32);
+            const uint32_t sym = (m >> 16) & 0xFFu;
+            const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
+            const uint32_t code = kFolded ? bf16_rne(dequant(sym, lay.zero_point, lay.scale)) : sym;
+            dst[i] = make_uint2((m & 0xFFFFu) | (code << 16), (1u << nb) - 1u);
+        }
+        const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
+        uint4* wdst = reinterpret_cast<uint4*>(lds_words);
+        const uint32_t quads = c.payload_words >> 2;
+        for (uint32_t i = tid; i < quads; i += kBlock) wdst[i] = wsrc[i];
+        if (tid < 8) {                                   // tail words, then zeros for clamped reads
+            const uint32_t w = (quads << 2) + tid;
+            lds_words[w] = w < c.payload_words ? p.payload[c.payload_offset + w] : 0u;
+        }
+        uint4* rdst = reinterpret_cast<uint4*>(lds_ring);
+        for (uint32_t i = tid; i < kRingBytes / 16u; i += kBlock) rdst[i] = make_uint4(bg2, bg2, bg2, bg2);
+    }
+    __syncthreads();
+    if (tid >= kWave) return;                            // helper wavefronts are done
+
+    // ---- per-lane stream state
+    const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
+    const uint32_t n_words = hdr >> 16;
+    uint32_t total_words;
+    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
+    uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+    const uint32_t word_cap = c.payload_words;           // lds_words[word_cap ..] are zeros
+    auto word_at = [&](uint32_t i) { return lds_words[min(i, word_cap)]; };
+
+    uint32_t X8 = (hdr & (L - 1u)) << 3;
+    uint64_t buf = uint64_t(word_at(first_word)) | (uint64_t(word_at(first_word + 1)) << 32);
+    uint32_t have = 64;                                  // valid bits in buf
+    uint32_t used = 2;                                   // words moved into buf
+    uint32_t ahead = word_at(first_word + 2);            // next word, read one refill early
+    uint32_t pos = 0;                                    // symbols emitted by this lane
+    if (len == 0 && X8 != 0) err |= ANSZP_ST_BAD_STATE;
+
+    uint32_t flushed = 0;                                // elements of the chunk already stored
+    const uint32_t n = c.n_symbols;
+    bool pending = false;                                // a slab read from the ring waits to be stored
+    uint4 slab_codes = make_uint4(0, 0, 0, 0);
+    uint32_t slab_first = 0;
+
+    uint2 e = *reinterpret_cast<const uint2*>(lds_table + X8);
+    for (;;) {
+        const bool live = pos < len;
+        if (__ballot(live) == 0) break;
+        const uint32_t next_elem = pos * N + lane;       // chunk index of this lane's next symbol
+        const bool go = live && (next_elem + kMaxMerged * N <= flushed + kRingElems);
+
+        // Sec. II-A step on a merged entry: state' = newX' | (stream bits & mask)
+        const uint32_t bits = static_cast<uint32_t>(buf) & e.y;
+        const uint32_t X8_next = (e.x & 0x7FF8u) | (bits << 3);
+        X8 = go ? X8_next : X8;
+        const uint2 e_next = *reinterpret_cast<const uint2*>(lds_table + X8);
+
+        if (pending) {                                   // slab read during the previous look-up
+            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + slab_first + lane * 8u,
+                                              layer_elem0 + slab_first + lane * 8u, slab_codes);
+            pending = false;
+        }
+
+        if (go) {
+            const uint32_t count_m1 = e.x & 7u;
+            const uint32_t left = len - pos;
+            if (count_m1 < left) {                       // all c symbols belong to the stream
+                const uint32_t nb = __popc(e.y);
+                buf >>= nb;
+                have -= nb;
+                lds_ring[(next_elem + count_m1 * N) & (kRingElems - 1u)] = static_cast<uint16_t>(e.x >> 16);
+                pos += count_m1 + 1u;
+                if (have <= 32u) {
+                    buf |= uint64_t(ahead) << have;
+                    have += 32u;
+                    ++used;
+                    ahead = word_at(first_word + used);
+                }
+                if (pos == len && X8_next != 0) err |= ANSZP_ST_BAD_STATE;
+            } else {                                     // stream ends inside the run of empty steps
+                if (!(left == count_m1 && (e.x & 0x8000u))) err |= ANSZP_ST_BAD_STATE;
+                pos = len;
+            }
+        }
+        e = e_next;
+
+        // a slab is final once every unfinished lane's next symbol lies beyond it
+        if (flushed + kSlab <= n) {
+            const uint32_t np = pos * N + lane;
+            if (__ballot(pos < len && np < flushed + kSlab) == 0) {
+                uint4* slot = reinterpret_cast<uint4*>(lds_ring + ((flushed & (kRingElems - 1u)) + lane * 8u));
+                slab_codes = *slot;
+                *slot = make_uint4(bg2, bg2, bg2, bg2);
+                slab_first = flushed;
+                flushed += kSlab;
+                pending = true;
+            }
+        }
+    }
+    if (pending)
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + slab_first + lane * 8u,
+                                          layer_elem0 + slab_first + lane * 8u, slab_codes);
+    // every stream is finished: the rest of the ring is final
+    while (flushed + kSlab <= n) {
+        const uint4 codes = *reinterpret_cast<const uint4*>(lds_ring + ((flushed & (kRingElems - 1u)) + lane * 8u));
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + flushed + lane * 8u, layer_elem0 + flushed + lane * 8u, codes);
+        flushed += kSlab;
+    }
+    for (uint32_t j = flushed + lane; j < n; j += kWave)
+        Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, lds_ring[j & (kRingElems - 1u)]);
+
+    if (lane < N) {
+        const uint32_t bits_read = 32u * used - have;
+        if (((bits_read + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
+    }
+    err = wave_or(err);
+    if (err && lane == 0) report(p.status, err);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -156,6 +417,41 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* sym, uint64
         }
         store_weight<OUT>(out, i, sym[i], lay.zero_point, scale);
     }
+}
+
+template <int OUT>
+void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, hipStream_t s) {
+    if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
+    else if (per_channel) hipLaunchKernelGGL((decode_merged<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL((decode_merged<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
+}
+
+int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
+    if (!a) return ANSZP_E_NULL;
+    if (a->n_chunks == 0) return ANSZP_OK;
+    if (!a->tables || !a->chunks || !a->stream_hdr || !a->layers || !a->out || !a->status) return ANSZP_E_NULL;
+    if (!a->payload && a->payload_words) return ANSZP_E_NULL;
+    if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 ||
+        a->n_streams > ANSZP_MAX_STREAMS || a->out_dtype > ANSZP_OUT_BF16 || a->n_tables == 0 ||
+        a->n_chunks >= (1ull << 31) || (reinterpret_cast<uintptr_t>(a->payload) & 15) ||
+        (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 2)
+        return ANSZP_E_RANGE;
+    DecodeParams p;
+    p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
+    p.layers = a->layers; p.scales = a->scales; p.out = a->out; p.status = a->status;
+    p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words;
+    p.n_scales = a->scales ? a->n_scales : 0; p.out_elems = a->out_elems;
+    p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
+    const bool stepwise = mode == 1;
+    const bool per_channel = a->scales != nullptr && a->n_scales != 0;
+    switch (a->out_dtype) {
+        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, s); break;
+        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, s); break;
+        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, s); break;
+    }
+    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }
 
 }  // namespace
@@ -181,30 +477,10 @@ int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
     return rc;
 }
 
-int anszp_decode(const anszp_decode_args_t* a, void* hip_stream) {
-    if (!a) return ANSZP_E_NULL;
-    if (a->n_chunks == 0) return ANSZP_OK;
-    if (!a->tables || !a->chunks || !a->stream_hdr || !a->layers || !a->out || !a->status) return ANSZP_E_NULL;
-    if (!a->payload && a->payload_words) return ANSZP_E_NULL;
-    if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 ||
-        a->n_streams > ANSZP_MAX_STREAMS || a->out_dtype > ANSZP_OUT_BF16 || a->n_tables == 0 ||
-        a->n_chunks >= (1ull << 31) || (reinterpret_cast<uintptr_t>(a->payload) & 15) ||
-        (reinterpret_cast<uintptr_t>(a->out) & 15))
-        return ANSZP_E_RANGE;
-    DecodeParams p;
-    p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
-    p.layers = a->layers; p.scales = a->scales; p.out = a->out; p.status = a->status;
-    p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words;
-    p.n_scales = a->scales ? a->n_scales : 0; p.out_elems = a->out_elems;
-    p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid(static_cast<uint32_t>(a->n_chunks)), block(kWave);
-    switch (a->out_dtype) {
-        case ANSZP_OUT_U8: hipLaunchKernelGGL(decode_stepwise<ANSZP_OUT_U8>, grid, block, 0, s, p); break;
-        case ANSZP_OUT_F32: hipLaunchKernelGGL(decode_stepwise<ANSZP_OUT_F32>, grid, block, 0, s, p); break;
-        default: hipLaunchKernelGGL(decode_stepwise<ANSZP_OUT_BF16>, grid, block, 0, s, p); break;
-    }
-    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+int anszp_decode(const anszp_decode_args_t* args, void* hip_stream) { return decode_impl(args, 0, hip_stream); }
+
+int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream) {
+    return decode_impl(args, variant, hip_stream);
 }
 
 int anszp_dequant_zp(const uint8_t* symbols_dev, uint64_t n, const anszp_layer_t* layer,

@@ -2,6 +2,7 @@
 element and bit for bit, on containers the ORACLE's encoder produced."""
 import numpy as np
 import pytest
+import torch
 
 from paper_2406_06237_amd import binding as B
 from paper_2406_06237_amd import workloads as W
@@ -15,12 +16,16 @@ def _run(orc, w, out_dtype=None):
     c = oracle_encode(orc, w)
     _, expect = oracle_expected(orc, c, w, out_dtype)
     d = B.to_device(host_from_oracle(c, w))
-    out = B.decode(d, out_dtype=out_dtype)
-    status = d.read_status()
-    got = B.bits_of(out)[:w.numel]
-    assert status == (0, 0), f"status {status}"
-    bad = np.nonzero(got != expect)[0]
-    assert len(bad) == 0, f"{len(bad)} mismatches, first at {bad[:5]}: got {got[bad[:5]]} want {expect[bad[:5]]}"
+    for variant in (None, B.VARIANT_STEPWISE, B.VARIANT_MERGED):
+        out = B.alloc_out(d, out_dtype)
+        out.view(torch.uint8).fill_(0xA5)
+        B.decode(d, out=out, out_dtype=out_dtype, variant=variant)
+        status = d.read_status()
+        got = B.bits_of(out)[:w.numel]
+        assert status == (0, 0), f"variant {variant}: status {status}"
+        bad = np.nonzero(got != expect)[0]
+        assert len(bad) == 0, (f"variant {variant}: {len(bad)} mismatches, first at {bad[:5]}: "
+                               f"got {got[bad[:5]]} want {expect[bad[:5]]}")
     return d, out
 
 
@@ -110,12 +115,18 @@ def test_corruption_is_flagged_not_fatal(orc):
     good = host_from_oracle(c, w)
 
     def status_of(h):
-        d = B.to_device(h)
-        guard = torch.full((w.numel + 4096,), 0x5A5A, dtype=torch.int16, device="cuda").view(torch.bfloat16)
-        B.decode_raw(B.decode_args(d, guard), d.device)
-        st = d.read_status()
-        assert bool((guard[w.numel:].view(torch.int16) == 0x5A5A).all()), "wrote past the output"
-        return st
+        worst = (0, 0)
+        for variant in (B.VARIANT_STEPWISE, B.VARIANT_MERGED):
+            d = B.to_device(h)
+            guard = torch.full((w.numel + 4096,), 0x5A5A, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+            B.decode_raw(B.decode_args(d, guard), d.device, variant)
+            st = d.read_status()
+            assert bool((guard[w.numel:].view(torch.int16) == 0x5A5A).all()), "wrote past the output"
+            if variant == B.VARIANT_STEPWISE:
+                worst = st
+            else:
+                assert (st[0] != 0) == (worst[0] != 0), f"variants disagree: {worst} vs {st}"
+        return worst
 
     assert status_of(good) == (0, 0)
     import copy
