@@ -245,10 +245,12 @@ struct Flusher {
 template <int OUT, bool PER_CHANNEL>
 __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_table[kTableBytes];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_ring[kRingElems];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_ring[kRingElems + 8];     // + a slot for discarded writes
     __shared__ __attribute__((aligned(16))) uint32_t lds_words[kPayloadWords + 8];
     constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
+    constexpr uint32_t kTableLoads = (1u << ANSZP_MAX_TABLE_LOG) / 2u / kBlock;     // 16-byte loads per thread
+    constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1);
@@ -259,12 +261,15 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         if (tid == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
-    const anszp_layer_t lay = p.layers[c.layer_id];
+    // issue every global read that depends only on the descriptor before waiting for any of them
+    const uint32_t hdr = (tid < N) ? p.stream_hdr[c.stream_offset + tid] : 0u;
     const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
+    const anszp_layer_t lay = p.layers[c.layer_id];
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
+    const uint32_t n = c.n_symbols;
     const bool merged_ok = c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
-                           PER_CHANNEL == (lay.channel_len != 0) &&
-                           (!PER_CHANNEL || layer_elem0 + c.n_symbols < (1ull << 32));
+                           n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
+                           (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
 
     if (!merged_ok) {                                     // whole workgroup agrees
         uint32_t* table = reinterpret_cast<uint32_t*>(lds_table);
@@ -276,117 +281,135 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         return;
     }
 
-    // ---- stage: table (with dequantisation folded in), compressed words, ring background
-    const uint32_t top = static_cast<uint32_t>(src[L - 1]);            // state L-1: dominant symbol if nb == 0
+    // ---- stage: table (dequantisation folded in), compressed words, ring background
+    const uint32_t top = static_cast<uint32_t>(src[L - 1]);     // state L-1 carries the dominant symbol if there is one
+    {
+        const uint4* tsrc = reinterpret_cast<const uint4*>(src);
+        const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
+        const uint32_t quads = c.payload_words >> 2;
+        // unconditional loads from clamped (always valid) indices, so that all of them are in flight together
+        uint4 tv[kTableLoads], wv[kWordLoads];
+        const uint32_t t_last = (L >> 1) - 1u;
+        const uint32_t w_last = quads ? quads - 1u : 0u;
+        const uint4* wsafe = quads ? wsrc : tsrc;
+#pragma unroll
+        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsrc[min(tid + k * kBlock, t_last)];
+#pragma unroll
+        for (uint32_t k = 0; k < kWordLoads; ++k) wv[k] = wsafe[min(tid + k * kBlock, w_last)];
+        uint32_t tail = 0;
+        if (tid < 8 && (quads << 2) + tid < c.payload_words) tail = p.payload[c.payload_offset + (quads << 2) + tid];
+
+        auto entry = [&](uint32_t m) {
+            const uint32_t sym = (m >> 16) & 0xFFu;
+            const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
+            const uint32_t code = kFolded ? bf16_rne(dequant(sym, lay.zero_point, lay.scale)) : sym;
+            return make_uint2((m & 0xFFFFu) | (code << 16), (1u << nb) - 1u);
+        };
+        uint4* tdst = reinterpret_cast<uint4*>(lds_table);
+#pragma unroll
+        for (uint32_t k = 0; k < kTableLoads; ++k) {
+            const uint32_t i = tid + k * kBlock;
+            if (2u * i < L) {
+                const uint2 a = entry(tv[k].y), b = entry(tv[k].w);
+                tdst[i] = make_uint4(a.x, a.y, b.x, b.y);
+            }
+        }
+        uint4* wdst = reinterpret_cast<uint4*>(lds_words);
+#pragma unroll
+        for (uint32_t k = 0; k < kWordLoads; ++k) {
+            const uint32_t i = tid + k * kBlock;
+            if (i < quads) wdst[i] = wv[k];
+        }
+        if (tid < 8) lds_words[(quads << 2) + tid] = tail;      // tail words, then zeros for clamped reads
+    }
     const uint32_t bg_sym = top >> 24;
     const uint32_t bg_code = kFolded ? bf16_rne(dequant(bg_sym, lay.zero_point, lay.scale)) : bg_sym;
     const uint32_t bg2 = bg_code | (bg_code << 16);
     {
-        uint2* dst = reinterpret_cast<uint2*>(lds_table);
-        for (uint32_t i = tid; i < L; i += kBlock) {
-            const uint32_t m = static_cast<uint32_t>(src[i] >> 32);
-            const uint32_t sym = (m >> 16) & 0xFFu;
-            const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
-            const uint32_t code = kFolded ? bf16_rne(dequant(sym, lay.zero_point, lay.scale)) : sym;
-            dst[i] = make_uint2((m & 0xFFFFu) | (code << 16), (1u << nb) - 1u);
-        }
-        const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
-        uint4* wdst = reinterpret_cast<uint4*>(lds_words);
-        const uint32_t quads = c.payload_words >> 2;
-        for (uint32_t i = tid; i < quads; i += kBlock) wdst[i] = wsrc[i];
-        if (tid < 8) {                                   // tail words, then zeros for clamped reads
-            const uint32_t w = (quads << 2) + tid;
-            lds_words[w] = w < c.payload_words ? p.payload[c.payload_offset + w] : 0u;
-        }
         uint4* rdst = reinterpret_cast<uint4*>(lds_ring);
-        for (uint32_t i = tid; i < kRingBytes / 16u; i += kBlock) rdst[i] = make_uint4(bg2, bg2, bg2, bg2);
+#pragma unroll
+        for (uint32_t k = 0; k < kRingBytes / 16u / kBlock; ++k) rdst[tid + k * kBlock] = make_uint4(bg2, bg2, bg2, bg2);
     }
     __syncthreads();
     if (tid >= kWave) return;                            // helper wavefronts are done
 
-    // ---- per-lane stream state
-    const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
+    // ---- per-lane stream state (lane == tid in wavefront 0)
     const uint32_t n_words = hdr >> 16;
     uint32_t total_words;
     const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
-    const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
     uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
-    const uint32_t word_cap = c.payload_words;           // lds_words[word_cap ..] are zeros
-    auto word_at = [&](uint32_t i) { return lds_words[min(i, word_cap)]; };
+    const uint32_t last_word4 = c.payload_words << 2;    // byte offset of the zero words behind the payload
 
-    uint32_t X8 = (hdr & (L - 1u)) << 3;
-    uint64_t buf = uint64_t(word_at(first_word)) | (uint64_t(word_at(first_word + 1)) << 32);
-    uint32_t have = 64;                                  // valid bits in buf
-    uint32_t used = 2;                                   // words moved into buf
-    uint32_t ahead = word_at(first_word + 2);            // next word, read one refill early
-    uint32_t pos = 0;                                    // symbols emitted by this lane
-    if (len == 0 && X8 != 0) err |= ANSZP_ST_BAD_STATE;
+    const uint32_t n2 = 2u * n, N2 = 2u * N;             // element indices are kept doubled (ring byte offsets)
+    constexpr uint32_t kRing2 = 2u * kRingElems, kSlab2 = 2u * kSlab;
+    uint32_t X8 = (hdr & (L - 1u)) << 3;                 // byte offset of the current entry
+    uint32_t abit = first_word << 5;                     // bit position in the chunk's payload
+    uint32_t ne2 = (lane < N) ? 2u * lane : n2;          // 2 * chunk index of this lane's next symbol
+    if (ne2 >= n2 && X8 != 0) err |= ANSZP_ST_BAD_STATE; // empty stream must carry state 0
 
-    uint32_t flushed = 0;                                // elements of the chunk already stored
-    const uint32_t n = c.n_symbols;
-    bool pending = false;                                // a slab read from the ring waits to be stored
-    uint4 slab_codes = make_uint4(0, 0, 0, 0);
-    uint32_t slab_first = 0;
+    uint32_t flushed2 = 0;                               // 2 * elements already stored (wave-uniform)
+    constexpr uint32_t kBatch = 4;                       // slabs stored per flush
+    constexpr uint32_t kBatch2 = kBatch * kSlab2;
 
+    // two consecutive payload words starting at a 4-byte aligned LDS byte offset
+    auto word_pair = [&](uint32_t byte_off) {
+        const uint32_t* q = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(lds_words) + byte_off);
+        return make_uint2(q[0], q[1]);
+    };
+    uint8_t* ring8 = reinterpret_cast<uint8_t*>(lds_ring);
     uint2 e = *reinterpret_cast<const uint2*>(lds_table + X8);
-    for (;;) {
-        const bool live = pos < len;
-        if (__ballot(live) == 0) break;
-        const uint32_t next_elem = pos * N + lane;       // chunk index of this lane's next symbol
-        const bool go = live && (next_elem + kMaxMerged * N <= flushed + kRingElems);
+    uint2 w = word_pair(min(first_word << 2, last_word4));
 
-        // Sec. II-A step on a merged entry: state' = newX' | (stream bits & mask)
-        const uint32_t bits = static_cast<uint32_t>(buf) & e.y;
-        const uint32_t X8_next = (e.x & 0x7FF8u) | (bits << 3);
-        X8 = go ? X8_next : X8;
-        const uint2 e_next = *reinterpret_cast<const uint2*>(lds_table + X8);
-
-        if (pending) {                                   // slab read during the previous look-up
-            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + slab_first + lane * 8u,
-                                              layer_elem0 + slab_first + lane * 8u, slab_codes);
-            pending = false;
-        }
-
-        if (go) {
-            const uint32_t count_m1 = e.x & 7u;
-            const uint32_t left = len - pos;
-            if (count_m1 < left) {                       // all c symbols belong to the stream
-                const uint32_t nb = __popc(e.y);
-                buf >>= nb;
-                have -= nb;
-                lds_ring[(next_elem + count_m1 * N) & (kRingElems - 1u)] = static_cast<uint16_t>(e.x >> 16);
-                pos += count_m1 + 1u;
-                if (have <= 32u) {
-                    buf |= uint64_t(ahead) << have;
-                    have += 32u;
-                    ++used;
-                    ahead = word_at(first_word + used);
+    // One look-up for every lane that is neither finished nor too far ahead of the slowest lane
+    // for the ring.  Sec. II-A step on a merged entry: state' = newX' | (next stream bits & mask).
+    auto step = [&](uint32_t bound) {
+        if (ne2 < bound) {
+            const uint32_t window = __builtin_amdgcn_alignbit(w.y, w.x, abit);
+            const uint32_t ex = e.x, nb = __popc(e.y);
+            X8 = (ex & 0x7FF8u) | ((window & e.y) << 3);
+            e = *reinterpret_cast<const uint2*>(lds_table + X8);
+            const uint32_t last2 = __umul24(ex & 7u, N2) + ne2;      // doubled index of the entry's last symbol
+            abit += nb;
+            w = word_pair(min((abit >> 3) & ~3u, last_word4));
+            // beyond the chunk's end (stream finished inside a run) this hits a ring slot nobody reads
+            *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(ex >> 16);
+            ne2 = last2 + N2;
+            if (ne2 >= n2) {                             // stream finished: it must have arrived in state 0
+                bool ok = X8 == 0;
+                if (last2 >= n2) {                       // ended inside the run of empty steps: no bits were read
+                    ok = (last2 - N2 < n2) && (ex & 0x8000u);
+                    abit -= nb;
                 }
-                if (pos == len && X8_next != 0) err |= ANSZP_ST_BAD_STATE;
-            } else {                                     // stream ends inside the run of empty steps
-                if (!(left == count_m1 && (e.x & 0x8000u))) err |= ANSZP_ST_BAD_STATE;
-                pos = len;
+                if (!ok) err |= ANSZP_ST_BAD_STATE;
             }
         }
-        e = e_next;
+    };
 
-        // a slab is final once every unfinished lane's next symbol lies beyond it
-        if (flushed + kSlab <= n) {
-            const uint32_t np = pos * N + lane;
-            if (__ballot(pos < len && np < flushed + kSlab) == 0) {
-                uint4* slot = reinterpret_cast<uint4*>(lds_ring + ((flushed & (kRingElems - 1u)) + lane * 8u));
-                slab_codes = *slot;
-                *slot = make_uint4(bg2, bg2, bg2, bg2);
-                slab_first = flushed;
-                flushed += kSlab;
-                pending = true;
-            }
+    for (;;) {
+        if (__ballot(ne2 < n2) == 0) break;
+        const uint32_t bound = min(n2, flushed2 + kRing2 - kMaxMerged * N2 + 1u);
+        step(bound);
+        step(bound);
+        step(bound);
+        step(bound);
+        // slabs are final once every unfinished lane's next symbol lies beyond them
+        if (flushed2 + kBatch2 <= n2 && __ballot(ne2 < flushed2 + kBatch2) == 0) {
+            uint4 codes[kBatch];
+            uint4* slot = reinterpret_cast<uint4*>(ring8 + ((flushed2 & (kRing2 - 1u)) + lane * 16u));
+#pragma unroll
+            for (uint32_t k = 0; k < kBatch; ++k) codes[k] = slot[k * (kSlab2 / 16u)];
+#pragma unroll
+            for (uint32_t k = 0; k < kBatch; ++k) slot[k * (kSlab2 / 16u)] = make_uint4(bg2, bg2, bg2, bg2);
+            const uint32_t first = (flushed2 >> 1) + lane * 8u;
+#pragma unroll
+            for (uint32_t k = 0; k < kBatch; ++k)
+                Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + k * kSlab,
+                                                  layer_elem0 + first + k * kSlab, codes[k]);
+            flushed2 += kBatch2;
         }
     }
-    if (pending)
-        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + slab_first + lane * 8u,
-                                          layer_elem0 + slab_first + lane * 8u, slab_codes);
     // every stream is finished: the rest of the ring is final
+    uint32_t flushed = flushed2 >> 1;
     while (flushed + kSlab <= n) {
         const uint4 codes = *reinterpret_cast<const uint4*>(lds_ring + ((flushed & (kRingElems - 1u)) + lane * 8u));
         Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + flushed + lane * 8u, layer_elem0 + flushed + lane * 8u, codes);
@@ -396,7 +419,7 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, lds_ring[j & (kRingElems - 1u)]);
 
     if (lane < N) {
-        const uint32_t bits_read = 32u * used - have;
+        const uint32_t bits_read = abit - (first_word << 5);
         if (((bits_read + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
     err = wave_or(err);
