@@ -244,9 +244,13 @@ struct Flusher {
 
 template <int OUT, bool PER_CHANNEL>
 __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_table[kTableBytes];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_ring[kRingElems + 8];     // + a slot for discarded writes
-    __shared__ __attribute__((aligned(16))) uint32_t lds_words[kPayloadWords + 8];
+    // one LDS block, carved by hand so that the compressed words sit at offset 0 (their two-dword
+    // reads have no room for a large immediate offset), then the table, then the ring
+    constexpr uint32_t kWordsBytes = (kPayloadWords + 8u) * 4u;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kWordsBytes + kTableBytes + kRingBytes];
+    uint32_t* const lds_words = reinterpret_cast<uint32_t*>(lds);
+    uint8_t* const lds_table = lds + kWordsBytes;
+    uint16_t* const lds_ring = reinterpret_cast<uint16_t*>(lds + kWordsBytes + kTableBytes);
     constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
     constexpr uint32_t kTableLoads = (1u << ANSZP_MAX_TABLE_LOG) / 2u / kBlock;     // 16-byte loads per thread
@@ -385,14 +389,8 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         }
     };
 
-    for (;;) {
-        if (__ballot(ne2 < n2) == 0) break;
-        const uint32_t bound = min(n2, flushed2 + kRing2 - kMaxMerged * N2 + 1u);
-        step(bound);
-        step(bound);
-        step(bound);
-        step(bound);
-        // slabs are final once every unfinished lane's next symbol lies beyond them
+    // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.
+    auto flush_ready = [&]() {
         if (flushed2 + kBatch2 <= n2 && __ballot(ne2 < flushed2 + kBatch2) == 0) {
             uint4 codes[kBatch];
             uint4* slot = reinterpret_cast<uint4*>(ring8 + ((flushed2 & (kRing2 - 1u)) + lane * 16u));
@@ -407,6 +405,45 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
                                                   layer_elem0 + first + k * kSlab, codes[k]);
             flushed2 += kBatch2;
         }
+    };
+
+    // Bulk phase: blocks of kBlockSteps look-ups with no per-step checks.  A lane joins a block only
+    // if even kBlockSteps full-length entries keep it inside its stream and inside the ring, so
+    // nothing can finish or overrun in the middle of a block.
+    constexpr uint32_t kBlockSteps = 4;
+    const uint32_t reach2 = kBlockSteps * kMaxMerged * N2;
+    auto bulk_step = [&]() {
+        const uint32_t window = __builtin_amdgcn_alignbit(w.y, w.x, abit);
+        const uint32_t ex = e.x, ey = e.y;
+        X8 = (ex & 0x7FF8u) | ((window & ey) << 3);
+        e = *reinterpret_cast<const uint2*>(lds_table + X8);
+        abit += __popc(ey);
+        w = word_pair(min((abit >> 3) & ~3u, last_word4));
+        const uint32_t last2 = __umul24(ex & 7u, N2) + ne2;
+        *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(ex >> 16);
+        ne2 = last2 + N2;
+    };
+    while (n2 > reach2) {
+        const uint32_t limit = min(n2, flushed2 + kRing2) - reach2;
+        if (__ballot(ne2 < limit) == 0) break;
+        if (ne2 < limit) {
+            bulk_step();
+            bulk_step();
+            bulk_step();
+            bulk_step();
+        }
+        flush_ready();
+    }
+
+    // Careful phase: every look-up checks the end of the stream and the room in the ring.
+    for (;;) {
+        if (__ballot(ne2 < n2) == 0) break;
+        const uint32_t bound = min(n2, flushed2 + kRing2 - kMaxMerged * N2 + 1u);
+        step(bound);
+        step(bound);
+        step(bound);
+        step(bound);
+        flush_ready();
     }
     // every stream is finished: the rest of the ring is final
     uint32_t flushed = flushed2 >> 1;
