@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
     ap.add_argument("--blocks", type=int, default=32, help="config 4 only: number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
+                    help="also run a plain device copy of this many MiB five times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build decodes on ONE GPU (chunks are independent; sharding them over GPUs needs "
@@ -106,6 +108,12 @@ def main():
         print(f"bench.py: device status {status}", file=sys.stderr)
         sys.exit(1)
     kernel_ms = ev0.elapsed_time(ev1) / args.steps
+    if args.calib_copy:
+        src = torch.full((args.calib_copy << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize(dev)
     ms_per_step = wall * 1e3 / args.steps
 
     elem_bytes = {"u8": 1, "f32": 4, "bf16": 2}[w.out_dtype]
