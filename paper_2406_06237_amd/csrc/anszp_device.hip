@@ -24,10 +24,10 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kBlock = 256;                    // 4 wavefronts stage; wavefront 0 decodes
 constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB of LDS entries
-constexpr uint32_t kRingBytes = 16u * 1024u;   // LDS ring of decoded codes (2 bytes each)
+constexpr uint32_t kRingBytes = 32u * 1024u;   // LDS ring of decoded codes (2 bytes each)
 constexpr uint32_t kRingElems = kRingBytes / 2u;
 constexpr uint32_t kSlab = 512u;               // elements flushed per wave store (8 per lane)
-constexpr uint32_t kPayloadWords = 7680u;      // LDS window for one chunk's compressed words
+constexpr uint32_t kPayloadWords = 3584u;      // LDS window for one chunk's compressed words
 constexpr uint32_t kMaxMerged = 8u;
 
 struct DecodeParams {
@@ -173,9 +173,8 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
 // Merged-run path.
 //
 // LDS entry (8 bytes) derived from the merged half of a table entry while staging:
-//   lo: bits 0..2 c-1 | bits 3..14 newX' (so lo & 0x7FF8 is the byte offset of the next entry
-//       before the stream bits are OR-ed in) | bit 15 end-flag | bits 16..31 code of symbol'
-//   hi: (1 << nb_bits') - 1
+//   lo: newX' * 8, the byte offset of the next entry before the stream bits are OR-ed in
+//   hi: bits 0..4 nb_bits' | bits 8..10 c-1 | bit 15 end-flag | bits 16..31 code of symbol'
 // One look-up emits c symbols: c-1 copies of the dominant symbol, which the ring already holds
 // as background, then symbol'.  code = bf16 weight when the output is bf16 with a per-layer
 // scale (dequantisation folded into the table), else the symbol itself and dequantisation
@@ -307,7 +306,7 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
             const uint32_t sym = (m >> 16) & 0xFFu;
             const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
             const uint32_t code = kFolded ? bf16_rne(dequant(sym, lay.zero_point, lay.scale)) : sym;
-            return make_uint2((m & 0xFFFFu) | (code << 16), (1u << nb) - 1u);
+            return make_uint2(m & 0x7FF8u, nb | ((m & 7u) << 8) | (m & 0x8000u) | (code << 16));
         };
         uint4* tdst = reinterpret_cast<uint4*>(lds_table);
 #pragma unroll
@@ -369,19 +368,19 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     auto step = [&](uint32_t bound) {
         if (ne2 < bound) {
             const uint32_t window = __builtin_amdgcn_alignbit(w.y, w.x, abit);
-            const uint32_t ex = e.x, nb = __popc(e.y);
-            X8 = (ex & 0x7FF8u) | ((window & e.y) << 3);
+            const uint32_t eh = e.y, nb = eh & 31u;
+            X8 = e.x | (__builtin_amdgcn_ubfe(window, 0u, nb) << 3);
             e = *reinterpret_cast<const uint2*>(lds_table + X8);
-            const uint32_t last2 = __umul24(ex & 7u, N2) + ne2;      // doubled index of the entry's last symbol
+            const uint32_t last2 = __umul24((eh >> 8) & 7u, N2) + ne2;   // doubled index of the entry's last symbol
             abit += nb;
             w = word_pair(min((abit >> 3) & ~3u, last_word4));
             // beyond the chunk's end (stream finished inside a run) this hits a ring slot nobody reads
-            *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(ex >> 16);
+            *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(eh >> 16);
             ne2 = last2 + N2;
             if (ne2 >= n2) {                             // stream finished: it must have arrived in state 0
                 bool ok = X8 == 0;
                 if (last2 >= n2) {                       // ended inside the run of empty steps: no bits were read
-                    ok = (last2 - N2 < n2) && (ex & 0x8000u);
+                    ok = (last2 - N2 < n2) && (eh & 0x8000u);
                     abit -= nb;
                 }
                 if (!ok) err |= ANSZP_ST_BAD_STATE;
@@ -407,32 +406,80 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         }
     };
 
-    // Bulk phase: blocks of kBlockSteps look-ups with no per-step checks.  A lane joins a block only
-    // if even kBlockSteps full-length entries keep it inside its stream and inside the ring, so
-    // nothing can finish or overrun in the middle of a block.
-    constexpr uint32_t kBlockSteps = 4;
+    // Bulk phase: blocks of 8 look-ups with no per-step checks.  A lane joins a block only if even
+    // 8 full-length entries keep it inside its stream and inside the ring, so nothing can finish
+    // or overrun in the middle of a block.  The block is hand-scheduled because a lone wavefront
+    // issues one instruction every 5-8 cycles: what a look-up costs is its instruction count plus
+    // the part of the LDS round trip it cannot cover.  At the start of a block a lane loads four
+    // payload words (128 bits, at least 97 of them ahead of its bit position: 8 look-ups read at
+    // most 96) and shifts them down so that the stream continues at bit 0 of w0.  Per look-up:
+    //   X8   = e.lo | (bfe(w0, 0, nb) << 3);  e' = table[X8]        Sec. II-A: newX' + bits, issued first
+    //   w0..w3 >>= nb (funnel shift);  sum += e.hi                   low byte of sum = bits read so far
+    //   last = ((e.hi >> 8) & 7) * 2N + ne2;  ring[last & mask] = e.hi >> 16;  ne2 = last + 2N
+    constexpr uint32_t kBlockSteps = 8;
     const uint32_t reach2 = kBlockSteps * kMaxMerged * N2;
-    auto bulk_step = [&]() {
-        const uint32_t window = __builtin_amdgcn_alignbit(w.y, w.x, abit);
-        const uint32_t ex = e.x, ey = e.y;
-        X8 = (ex & 0x7FF8u) | ((window & ey) << 3);
-        e = *reinterpret_cast<const uint2*>(lds_table + X8);
-        abit += __popc(ey);
-        w = word_pair(min((abit >> 3) & ~3u, last_word4));
-        const uint32_t last2 = __umul24(ex & 7u, N2) + ne2;
-        *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(ex >> 16);
-        ne2 = last2 + N2;
-    };
-    while (n2 > reach2) {
-        const uint32_t limit = min(n2, flushed2 + kRing2) - reach2;
-        if (__ballot(ne2 < limit) == 0) break;
-        if (ne2 < limit) {
-            bulk_step();
-            bulk_step();
-            bulk_step();
-            bulk_step();
+    {
+        uint32_t e_lo = e.x, e_hi = e.y;
+#define ANSZP_STEP(EA0, EA1, EB)                                                       \
+        "s_waitcnt lgkmcnt(1)\n"                                                       \
+        "v_bfe_u32 v52, v44, 0, " EA1 "\n"                                             \
+        "v_lshl_or_b32 v52, v52, 3, " EA0 "\n"                                         \
+        "ds_read_b64 " EB ", v52 offset:%[table]\n"                                    \
+        "v_alignbit_b32 v44, v45, v44, " EA1 "\n"                                      \
+        "v_alignbit_b32 v45, v46, v45, " EA1 "\n"                                      \
+        "v_alignbit_b32 v46, v47, v46, " EA1 "\n"                                      \
+        "v_lshrrev_b32 v47, " EA1 ", v47\n"                                            \
+        "v_bfe_u32 v55, " EA1 ", 8, 3\n"                                               \
+        "v_add_u32 v57, v57, " EA1 "\n"                                                \
+        "v_mad_u32_u24 v55, v55, %[n2s], v50\n"                                        \
+        "v_and_b32 v56, %[rmask], v55\n"                                               \
+        "v_add_u32 v50, %[n2s], v55\n"                                                 \
+        "ds_write_b16_d16_hi v56, " EA1 " offset:%[ring]\n"
+#define ANSZP_STEP_AB ANSZP_STEP("v40", "v41", "v[42:43]")
+#define ANSZP_STEP_BA ANSZP_STEP("v42", "v43", "v[40:41]")
+        while (n2 > reach2) {
+            const uint32_t limit = min(n2, flushed2 + kRing2) - reach2;
+            if (__ballot(ne2 < limit) == 0) break;
+            const uint32_t flush_at = (flushed2 + kBatch2 <= n2) ? flushed2 + kBatch2 : 0xFFFFFFFFu;
+            asm volatile(
+                "v_mov_b32 v40, %[elo]\n v_mov_b32 v41, %[ehi]\n v_mov_b32 v48, %[ab]\n v_mov_b32 v50, %[ne]\n"
+                "1:\n"
+                "v_cmp_gt_u32 vcc, %[lim], v50\n"
+                "s_cbranch_vccz 2f\n"                    // no lane can run a whole block
+                "s_and_saveexec_b64 s[40:41], vcc\n"
+                "v_lshrrev_b32 v54, 3, v48\n"
+                "v_and_b32 v54, 0x1ffffffc, v54\n"
+                "v_min_u32 v54, %[lastw], v54\n"
+                "ds_read2_b32 v[44:45], v54 offset1:1\n"
+                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"
+                "v_mov_b32 v57, 0\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                "v_alignbit_b32 v44, v45, v44, v48\n"
+                "v_alignbit_b32 v45, v46, v45, v48\n"
+                "v_alignbit_b32 v46, v47, v46, v48\n"
+                "v_lshrrev_b32 v47, v48, v47\n"
+                ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA
+                ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA
+                "v_and_b32 v57, 0xff, v57\n"
+                "v_add_u32 v48, v48, v57\n"
+                "s_mov_b64 exec, s[40:41]\n"
+                "v_cmp_gt_u32 vcc, %[fat], v50\n"
+                "s_cbranch_vccnz 1b\n"                   // some lane is still inside the next slabs: no flush yet
+                "2:\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                "v_mov_b32 %[elo], v40\n v_mov_b32 %[ehi], v41\n v_mov_b32 %[ab], v48\n v_mov_b32 %[ne], v50\n"
+                : [elo] "+v"(e_lo), [ehi] "+v"(e_hi), [ab] "+v"(abit), [ne] "+v"(ne2)
+                : [lim] "s"(limit), [fat] "s"(flush_at), [n2s] "s"(N2), [lastw] "s"(last_word4),
+                  [table] "n"(kWordsBytes), [ring] "n"(kWordsBytes + kTableBytes), [rmask] "n"(kRing2 - 1u)
+                : "memory", "vcc", "scc", "s40", "s41", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48",
+                  "v50", "v52", "v54", "v55", "v56", "v57");
+            flush_ready();
         }
-        flush_ready();
+#undef ANSZP_STEP_AB
+#undef ANSZP_STEP_BA
+#undef ANSZP_STEP
+        e = make_uint2(e_lo, e_hi);
+        w = word_pair(min((abit >> 3) & ~3u, last_word4));
     }
 
     // Careful phase: every look-up checks the end of the stream and the room in the ring.
