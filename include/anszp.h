@@ -98,7 +98,7 @@ typedef struct {
 
 /* Arguments of anszp_decode (the struct itself is read on the host). */
 typedef struct {
-    const uint64_t*      tables;        /* [device] n_tables * 2^table_log entries from anszp_build_tables */
+    const uint32_t*      tables;        /* [device] n_tables * 2 * 2^table_log words from anszp_build_tables, 16-byte aligned */
     uint32_t             n_tables;
     uint32_t             table_log;     /* R, 1..12                                             */
     uint32_t             n_streams;     /* N, 1..64                                             */
@@ -132,21 +132,22 @@ const char* anszp_strerror(int code);
 int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs);
 
 /* [host only] Sec. II-A / III-A: build n_tables decode tables from normalised frequencies.
- * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 2^table_log entries.
- * Entry layout (uint64):
- *   bits  0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol        -- the paper's triple
- *   bits 32..34 c-1       bits 35..46 newX'     bit 47 end-flag
- *   bits 48..55 symbol'   bits 56..63 nb_bits'                            -- the same automaton
- *   with up to 8 steps merged: from this state the next c-1 symbols are zero-bit transitions of
- *   the dominant symbol (f > L/2), then symbol' is emitted, nb_bits' bits are read and the state
+ * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 2 * 2^table_log 32-bit words.
+ * Table t occupies words [t*2L, (t+1)*2L), L = 2^table_log, in two halves indexed by state X:
+ *   word [X]      bits  0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol    -- the paper's triple
+ *   word [L + X]  bits  0..2  c-1       bits  3..14 newX'     bit 15 end-flag
+ *                 bits 16..23 symbol'   bits 24..31 nb_bits'                        -- the same automaton
+ *   with up to 8 steps merged: from state X the next c-1 symbols are zero-bit transitions of the
+ *   dominant symbol (f > L/2), then symbol' is emitted, nb_bits' bits are read and the state
  *   becomes newX' + bits.  end-flag: the state before the c-th symbol is state 0.
  * Errors: E_NULL, E_RANGE, E_FREQ. */
-int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint64_t* tables);
+int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint32_t* tables);
 
-/* Same, writing the tables to device memory.  tables_dev: [device].  The host-to-device copy
- * is enqueued on hip_stream and waited for before returning.  Errors: as above, E_HIP, E_NOMEM. */
+/* Same, writing the tables to device memory.  tables_dev: [device], 16-byte aligned.  The
+ * host-to-device copy is enqueued on hip_stream and waited for before returning.
+ * Errors: as above, E_HIP, E_NOMEM. */
 int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
-                       uint64_t* tables_dev, void* hip_stream);
+                       uint32_t* tables_dev, void* hip_stream);
 
 /* [host only] Worst-case sizes for anszp_pack_layer: number of chunks and payload words. */
 int anszp_pack_bound(uint64_t n_symbols, int table_log, int n_streams, uint32_t chunk_size,

@@ -99,8 +99,8 @@ def normalize_freqs(counts: np.ndarray, table_log: int) -> np.ndarray:
 
 def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
-    size = len(freqs) << max(0, min(table_log, 20))
-    tables = np.zeros(size, dtype=np.uint64)
+    size = len(freqs) << (max(0, min(table_log, 20)) + 1)
+    tables = np.zeros(size, dtype=np.uint32)
     _check(lib().anszp_build_tables_host(freqs.ctypes.data, len(freqs), table_log, tables.ctypes.data),
            "anszp_build_tables_host")
     return tables.reshape(len(freqs), -1)
@@ -108,9 +108,9 @@ def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
 
 def split_table(tables: np.ndarray):
     """Fields of the table entries: the paper's triple and the merged-step fields."""
-    t = np.asarray(tables, dtype=np.uint64)
-    lo = (t & np.uint64(0xFFFFFFFF)).astype(np.uint32)
-    hi = (t >> np.uint64(32)).astype(np.uint32)
+    t = np.asarray(tables, dtype=np.uint32)
+    L = t.shape[-1] // 2
+    lo, hi = t[..., :L], t[..., L:]
     return {"newX": (lo & 0xFFFF).astype(np.uint16), "nb": ((lo >> 16) & 0xFF).astype(np.uint8),
             "sym": (lo >> 24).astype(np.uint8),
             "count": ((hi & 7) + 1).astype(np.uint8), "m_newX": ((hi >> 3) & 0xFFF).astype(np.uint16),
@@ -215,7 +215,7 @@ def _stream_ptr(torch, device):
 
 
 def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
-    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 2^table_log uint64)."""
+    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 2 * 2^table_log uint32)."""
     torch = _torch()
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
     with torch.cuda.device(device):

@@ -22,7 +22,7 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 256;                    // 4 wavefronts stage; wavefront 0 decodes
+constexpr int kBlock = 1024;                   // 16 wavefronts stage; wavefront 0 decodes
 constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB of LDS entries
 constexpr uint32_t kRingBytes = 32u * 1024u;   // LDS ring of decoded codes (2 bytes each)
 constexpr uint32_t kRingElems = kRingBytes / 2u;
@@ -31,7 +31,7 @@ constexpr uint32_t kPayloadWords = 3584u;      // LDS window for one chunk's com
 constexpr uint32_t kMaxMerged = 8u;
 
 struct DecodeParams {
-    const uint64_t* tables;
+    const uint32_t* tables;
     const anszp_chunk_t* chunks;
     const uint32_t* stream_hdr;
     const uint32_t* payload;
@@ -161,8 +161,8 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
-    const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
-    for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = static_cast<uint32_t>(src[i]);
+    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 1));    // first half: the paper's triple
+    for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = src[i];
     const anszp_layer_t lay = p.layers[c.layer_id];
     __syncthreads();
     const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     uint16_t* const lds_ring = reinterpret_cast<uint16_t*>(lds + kWordsBytes + kTableBytes);
     constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
-    constexpr uint32_t kTableLoads = (1u << ANSZP_MAX_TABLE_LOG) / 2u / kBlock;     // 16-byte loads per thread
+    constexpr uint32_t kTableLoads = ((1u << ANSZP_MAX_TABLE_LOG) / 4u + kBlock - 1u) / kBlock;   // 16-byte loads per thread
     constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;
 
     const uint32_t tid = threadIdx.x;
@@ -264,19 +264,40 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         if (tid == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
-    // issue every global read that depends only on the descriptor before waiting for any of them
+    // Issue every global read that depends only on the descriptor before waiting for any of them:
+    // stream headers, the merged half of the layer's table, the chunk's compressed words (from
+    // clamped, always valid indices) and the layer's quantizer.
     const uint32_t hdr = (tid < N) ? p.stream_hdr[c.stream_offset + tid] : 0u;
-    const uint64_t* src = p.tables + (uint64_t(c.layer_id) << p.table_log);
+    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 1));
+    const uint4* tsrc = reinterpret_cast<const uint4*>(src + L);              // merged half, 4 entries per load
+    const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
+    const uint32_t quads = min(c.payload_words, kPayloadWords) >> 2;
+    const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte rows
+    uint4 tv[kTableLoads], wv[kWordLoads];
+    {
+        const uint32_t t_last = wide ? (L >> 2) - 1u : 0u;
+        const uint32_t w_last = quads ? quads - 1u : 0u;
+        const uint4* tsafe = wide ? tsrc : reinterpret_cast<const uint4*>(p.tables);
+        const uint4* wsafe = quads ? wsrc : tsafe;
+#pragma unroll
+        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsafe[min(tid + k * kBlock, t_last)];
+#pragma unroll
+        for (uint32_t k = 0; k < kWordLoads; ++k) wv[k] = wsafe[min(tid + k * kBlock, w_last)];
+    }
+    uint32_t tail = 0;
+    if (tid < 8 && (quads << 2) + tid < c.payload_words && c.payload_words <= kPayloadWords)
+        tail = p.payload[c.payload_offset + (quads << 2) + tid];
+    const uint32_t top = src[L - 1];                     // state L-1 carries the dominant symbol if there is one
     const anszp_layer_t lay = p.layers[c.layer_id];
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
     const uint32_t n = c.n_symbols;
-    const bool merged_ok = c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
+    const bool merged_ok = wide && c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
                            n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
 
     if (!merged_ok) {                                     // whole workgroup agrees
         uint32_t* table = reinterpret_cast<uint32_t*>(lds_table);
-        for (uint32_t i = tid; i < L; i += kBlock) table[i] = static_cast<uint32_t>(src[i]);
+        for (uint32_t i = tid; i < L; i += kBlock) table[i] = src[i];
         __syncthreads();
         if (tid >= kWave) return;
         const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
@@ -285,23 +306,7 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     }
 
     // ---- stage: table (dequantisation folded in), compressed words, ring background
-    const uint32_t top = static_cast<uint32_t>(src[L - 1]);     // state L-1 carries the dominant symbol if there is one
     {
-        const uint4* tsrc = reinterpret_cast<const uint4*>(src);
-        const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
-        const uint32_t quads = c.payload_words >> 2;
-        // unconditional loads from clamped (always valid) indices, so that all of them are in flight together
-        uint4 tv[kTableLoads], wv[kWordLoads];
-        const uint32_t t_last = (L >> 1) - 1u;
-        const uint32_t w_last = quads ? quads - 1u : 0u;
-        const uint4* wsafe = quads ? wsrc : tsrc;
-#pragma unroll
-        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsrc[min(tid + k * kBlock, t_last)];
-#pragma unroll
-        for (uint32_t k = 0; k < kWordLoads; ++k) wv[k] = wsafe[min(tid + k * kBlock, w_last)];
-        uint32_t tail = 0;
-        if (tid < 8 && (quads << 2) + tid < c.payload_words) tail = p.payload[c.payload_offset + (quads << 2) + tid];
-
         auto entry = [&](uint32_t m) {
             const uint32_t sym = (m >> 16) & 0xFFu;
             const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
@@ -312,9 +317,10 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
 #pragma unroll
         for (uint32_t k = 0; k < kTableLoads; ++k) {
             const uint32_t i = tid + k * kBlock;
-            if (2u * i < L) {
-                const uint2 a = entry(tv[k].y), b = entry(tv[k].w);
-                tdst[i] = make_uint4(a.x, a.y, b.x, b.y);
+            if (4u * i < L) {
+                const uint2 a = entry(tv[k].x), b = entry(tv[k].y), cc = entry(tv[k].z), d = entry(tv[k].w);
+                tdst[2u * i] = make_uint4(a.x, a.y, b.x, b.y);
+                tdst[2u * i + 1u] = make_uint4(cc.x, cc.y, d.x, d.y);
             }
         }
         uint4* wdst = reinterpret_cast<uint4*>(lds_words);
@@ -331,7 +337,8 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     {
         uint4* rdst = reinterpret_cast<uint4*>(lds_ring);
 #pragma unroll
-        for (uint32_t k = 0; k < kRingBytes / 16u / kBlock; ++k) rdst[tid + k * kBlock] = make_uint4(bg2, bg2, bg2, bg2);
+        for (uint32_t k = 0; k < (kRingBytes / 16u + kBlock - 1u) / kBlock; ++k)
+            if (tid + k * kBlock < kRingBytes / 16u) rdst[tid + k * kBlock] = make_uint4(bg2, bg2, bg2, bg2);
     }
     __syncthreads();
     if (tid >= kWave) return;                            // helper wavefronts are done
@@ -560,6 +567,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 ||
         a->n_streams > ANSZP_MAX_STREAMS || a->out_dtype > ANSZP_OUT_BF16 || a->n_tables == 0 ||
         a->n_chunks >= (1ull << 31) || (reinterpret_cast<uintptr_t>(a->payload) & 15) ||
+        (reinterpret_cast<uintptr_t>(a->tables) & 15) ||
         (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 2)
         return ANSZP_E_RANGE;
     DecodeParams p;
@@ -585,17 +593,18 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
 extern "C" {
 
 int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
-                       uint64_t* tables_dev, void* hip_stream) {
+                       uint32_t* tables_dev, void* hip_stream) {
     if (!freqs_host || !tables_dev) return ANSZP_E_NULL;
     if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
-    const size_t entries = size_t(n_tables) << table_log;
-    uint64_t* staging = nullptr;
-    if (hipHostMalloc(reinterpret_cast<void**>(&staging), entries * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess)
+    if (reinterpret_cast<uintptr_t>(tables_dev) & 15) return ANSZP_E_RANGE;
+    const size_t entries = size_t(n_tables) << (table_log + 1);
+    uint32_t* staging = nullptr;
+    if (hipHostMalloc(reinterpret_cast<void**>(&staging), entries * sizeof(uint32_t), hipHostMallocDefault) != hipSuccess)
         return ANSZP_E_NOMEM;
     int rc = anszp_build_tables_host(freqs_host, n_tables, table_log, staging);
     if (rc == ANSZP_OK) {
         hipStream_t s = static_cast<hipStream_t>(hip_stream);
-        if (hipMemcpyAsync(tables_dev, staging, entries * sizeof(uint64_t), hipMemcpyHostToDevice, s) != hipSuccess ||
+        if (hipMemcpyAsync(tables_dev, staging, entries * sizeof(uint32_t), hipMemcpyHostToDevice, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess)
             rc = ANSZP_E_HIP;
     }

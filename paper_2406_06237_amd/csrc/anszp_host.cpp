@@ -77,7 +77,7 @@ void build_step_table(const uint32_t* f, int table_log, StepTable& t) {
     }
 }
 
-void build_one_table(const uint32_t* f, int table_log, uint64_t* out) {
+void build_one_table(const uint32_t* f, int table_log, uint32_t* out) {
     const uint32_t L = 1u << table_log;
     StepTable t;
     build_step_table(f, table_log, t);
@@ -85,7 +85,7 @@ void build_one_table(const uint32_t* f, int table_log, uint64_t* out) {
     for (int s = 0; s < ANSZP_ALPHABET; ++s)
         if (f[s] > L / 2 && f[s] < L) dominant = true;
     for (uint32_t X = 0; X < L; ++X) {
-        const uint64_t step = uint64_t(t.newX[X]) | (uint64_t(t.nb[X]) << 16) | (uint64_t(t.sym[X]) << 24);
+        const uint32_t step = uint32_t(t.newX[X]) | (uint32_t(t.nb[X]) << 16) | (uint32_t(t.sym[X]) << 24);
         // merged entry: follow empty-label transitions (they all carry the dominant symbol)
         uint32_t Y = X, hops = 0;
         if (dominant)
@@ -97,9 +97,9 @@ void build_one_table(const uint32_t* f, int table_log, uint64_t* out) {
             count = hops + 1; last_sym = t.sym[Y]; last_nb = t.nb[Y]; last_newX = t.newX[Y];
             end_flag = (Y == 0) ? 1u : 0u;
         }
-        const uint64_t merged = uint64_t(count - 1) | (uint64_t(last_newX) << 3) | (uint64_t(end_flag) << 15) |
-                                (uint64_t(last_sym) << 16) | (uint64_t(last_nb) << 24);
-        out[X] = step | (merged << 32);
+        const uint32_t merged = (count - 1) | (last_newX << 3) | (end_flag << 15) | (last_sym << 16) | (last_nb << 24);
+        out[X] = step;            // first half of the table: the paper's triple
+        out[L + X] = merged;      // second half: merged steps
     }
 }
 
@@ -197,14 +197,14 @@ int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs
     return ANSZP_OK;
 }
 
-int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint64_t* tables) {
+int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint32_t* tables) {
     if (!freqs || !tables) return ANSZP_E_NULL;
     if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
     for (int t = 0; t < n_tables; ++t)
         if (!freqs_ok(freqs + size_t(t) * ANSZP_ALPHABET, table_log)) return ANSZP_E_FREQ;
     try {
         for (int t = 0; t < n_tables; ++t)
-            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << table_log));
+            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << (table_log + 1)));
     } catch (const std::bad_alloc&) {
         return ANSZP_E_NOMEM;
     }
