@@ -423,8 +423,9 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     //   X8   = e.lo | (bfe(w0, 0, nb) << 3);  e' = table[X8]        Sec. II-A: newX' + bits, issued first
     //   w0..w3 >>= nb (funnel shift);  sum += e.hi                   low byte of sum = bits read so far
     //   last = ((e.hi >> 8) & 7) * 2N + ne2;  ring[last & mask] = e.hi >> 16;  ne2 = last + 2N
-    constexpr uint32_t kBlockSteps = 8;
-    const uint32_t reach2 = kBlockSteps * kMaxMerged * N2;
+    // Blocks of 8 look-ups run first; when no lane can take one any more (streams within 64
+    // symbols of their end), blocks of 4 and then of 2 take over, and only the last few symbols
+    // of each stream go through the checked step below.
     {
         uint32_t e_lo = e.x, e_hi = e.y;
 #define ANSZP_STEP(EA0, EA1, EB)                                                       \
@@ -444,63 +445,69 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         "ds_write_b16_d16_hi v56, " EA1 " offset:%[ring]\n"
 #define ANSZP_STEP_AB ANSZP_STEP("v40", "v41", "v[42:43]")
 #define ANSZP_STEP_BA ANSZP_STEP("v42", "v43", "v[40:41]")
-        while (n2 > reach2) {
-            const uint32_t limit = min(n2, flushed2 + kRing2) - reach2;
-            if (__ballot(ne2 < limit) == 0) break;
-            const uint32_t flush_at = (flushed2 + kBatch2 <= n2) ? flushed2 + kBatch2 : 0xFFFFFFFFu;
-            asm volatile(
-                "v_mov_b32 v40, %[elo]\n v_mov_b32 v41, %[ehi]\n v_mov_b32 v48, %[ab]\n v_mov_b32 v50, %[ne]\n"
-                "v_cmp_gt_u32 vcc, %[lim], v50\n"
-                "s_and_saveexec_b64 s[40:41], vcc\n"     // lanes that can run a whole block
-                "v_lshrrev_b32 v54, 3, v48\n"
-                "v_and_b32 v54, 0x1ffffffc, v54\n"
-                "v_min_u32 v54, %[lastw], v54\n"
-                "ds_read2_b32 v[44:45], v54 offset1:1\n"
-                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"
-                "1:\n"
-                "v_mov_b32 v57, 0\n"
-                "s_waitcnt lgkmcnt(0)\n"
-                "v_alignbit_b32 v44, v45, v44, v48\n"
-                "v_alignbit_b32 v45, v46, v45, v48\n"
-                "v_alignbit_b32 v46, v47, v46, v48\n"
-                "v_lshrrev_b32 v47, v48, v47\n"
-                ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA
-                ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB
-                // eighth look-up: no window shift; the next block's four words are requested instead
-                "s_waitcnt lgkmcnt(1)\n"
-                "v_bfe_u32 v52, v44, 0, v43\n"
-                "v_lshl_or_b32 v52, v52, 3, v42\n"
-                "ds_read_b64 v[40:41], v52 offset:%[table]\n"
-                "v_add_u32 v57, v57, v43\n"
-                "v_bfe_u32 v55, v43, 8, 3\n"
-                "v_and_b32 v57, 0xff, v57\n"
-                "v_mad_u32_u24 v55, v55, %[n2s], v50\n"
-                "v_add_u32 v48, v48, v57\n"              // bit position after the block
-                "v_and_b32 v56, %[rmask], v55\n"
-                "v_lshrrev_b32 v54, 3, v48\n"
-                "v_add_u32 v50, %[n2s], v55\n"
-                "v_and_b32 v54, 0x1ffffffc, v54\n"
-                "ds_write_b16_d16_hi v56, v43 offset:%[ring]\n"
-                "v_min_u32 v54, %[lastw], v54\n"
-                "v_cmp_gt_u32 s[42:43], %[fat], v50\n"  // lanes of this block still inside the next slabs
-                "v_cmp_gt_u32 vcc, %[lim], v50\n"        // lanes that can run another block
-                "ds_read2_b32 v[44:45], v54 offset1:1\n"
-                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"
-                "s_cmp_eq_u64 s[42:43], 0\n"
-                "s_cbranch_scc1 2f\n"                    // none: slabs may be ready to leave the ring
-                "s_and_b64 exec, exec, vcc\n"
-                "s_cbranch_scc1 1b\n"
-                "2:\n"
-                "s_mov_b64 exec, s[40:41]\n"
-                "s_waitcnt lgkmcnt(0)\n"
-                "v_mov_b32 %[elo], v40\n v_mov_b32 %[ehi], v41\n v_mov_b32 %[ab], v48\n v_mov_b32 %[ne], v50\n"
-                : [elo] "+v"(e_lo), [ehi] "+v"(e_hi), [ab] "+v"(abit), [ne] "+v"(ne2)
-                : [lim] "s"(limit), [fat] "s"(flush_at), [n2s] "s"(N2), [lastw] "s"(last_word4),
-                  [table] "n"(kWordsBytes), [ring] "n"(kWordsBytes + kTableBytes), [rmask] "n"(kRing2 - 1u)
-                : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "v40", "v41", "v42", "v43", "v44", "v45", "v46",
-                  "v47", "v48", "v50", "v52", "v54", "v55", "v56", "v57");
-            flush_ready();
+// BODY = all look-ups of a block but the last, which is written out below: it skips the window
+// shift and requests the next block's four words instead.  Blocks have an even number of
+// look-ups, so the entry ends up in v[40:41] again.
+#define ANSZP_RUN_BLOCKS(STEPS, BODY)                                                                                 \
+        while (n2 > (STEPS) * kMaxMerged * N2) {                                                                      \
+            const uint32_t limit = min(n2, flushed2 + kRing2) - (STEPS) * kMaxMerged * N2;                            \
+            if (__ballot(ne2 < limit) == 0) break;                                                                    \
+            const uint32_t flush_at = (flushed2 + kBatch2 <= n2) ? flushed2 + kBatch2 : 0xFFFFFFFFu;                  \
+            asm volatile(                                                                                             \
+                "v_mov_b32 v40, %[elo]\n v_mov_b32 v41, %[ehi]\n v_mov_b32 v48, %[ab]\n v_mov_b32 v50, %[ne]\n"       \
+                "v_cmp_gt_u32 vcc, %[lim], v50\n"                                                                     \
+                "s_and_saveexec_b64 s[40:41], vcc\n" /* lanes that can run a whole block */                           \
+                "v_lshrrev_b32 v54, 3, v48\n"                                                                         \
+                "v_and_b32 v54, 0x1ffffffc, v54\n"                                                                    \
+                "v_min_u32 v54, %[lastw], v54\n"                                                                      \
+                "ds_read2_b32 v[44:45], v54 offset1:1\n"                                                              \
+                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"                                                    \
+                "1:\n"                                                                                                \
+                "v_mov_b32 v57, 0\n"                                                                                  \
+                "s_waitcnt lgkmcnt(0)\n"                                                                              \
+                "v_alignbit_b32 v44, v45, v44, v48\n"                                                                 \
+                "v_alignbit_b32 v45, v46, v45, v48\n"                                                                 \
+                "v_alignbit_b32 v46, v47, v46, v48\n"                                                                 \
+                "v_lshrrev_b32 v47, v48, v47\n"                                                                       \
+                BODY                                                                                                  \
+                "s_waitcnt lgkmcnt(1)\n"                                                                              \
+                "v_bfe_u32 v52, v44, 0, v43\n"                                                                        \
+                "v_lshl_or_b32 v52, v52, 3, v42\n"                                                                    \
+                "ds_read_b64 v[40:41], v52 offset:%[table]\n"                                                         \
+                "v_add_u32 v57, v57, v43\n"                                                                           \
+                "v_bfe_u32 v55, v43, 8, 3\n"                                                                          \
+                "v_and_b32 v57, 0xff, v57\n"                                                                          \
+                "v_mad_u32_u24 v55, v55, %[n2s], v50\n"                                                               \
+                "v_add_u32 v48, v48, v57\n" /* bit position after the block */                                        \
+                "v_and_b32 v56, %[rmask], v55\n"                                                                      \
+                "v_lshrrev_b32 v54, 3, v48\n"                                                                         \
+                "v_add_u32 v50, %[n2s], v55\n"                                                                        \
+                "v_and_b32 v54, 0x1ffffffc, v54\n"                                                                    \
+                "ds_write_b16_d16_hi v56, v43 offset:%[ring]\n"                                                       \
+                "v_min_u32 v54, %[lastw], v54\n"                                                                      \
+                "v_cmp_gt_u32 s[42:43], %[fat], v50\n" /* lanes of this block still inside the next slabs */          \
+                "v_cmp_gt_u32 vcc, %[lim], v50\n"      /* lanes that can run another block */                         \
+                "ds_read2_b32 v[44:45], v54 offset1:1\n"                                                              \
+                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"                                                    \
+                "s_cmp_eq_u64 s[42:43], 0\n"                                                                          \
+                "s_cbranch_scc1 2f\n"                  /* none: slabs may be ready to leave the ring */               \
+                "s_and_b64 exec, exec, vcc\n"                                                                         \
+                "s_cbranch_scc1 1b\n"                                                                                 \
+                "2:\n"                                                                                                \
+                "s_mov_b64 exec, s[40:41]\n"                                                                          \
+                "s_waitcnt lgkmcnt(0)\n"                                                                              \
+                "v_mov_b32 %[elo], v40\n v_mov_b32 %[ehi], v41\n v_mov_b32 %[ab], v48\n v_mov_b32 %[ne], v50\n"       \
+                : [elo] "+v"(e_lo), [ehi] "+v"(e_hi), [ab] "+v"(abit), [ne] "+v"(ne2)                                 \
+                : [lim] "s"(limit), [fat] "s"(flush_at), [n2s] "s"(N2), [lastw] "s"(last_word4),                      \
+                  [table] "n"(kWordsBytes), [ring] "n"(kWordsBytes + kTableBytes), [rmask] "n"(kRing2 - 1u)           \
+                : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "v40", "v41", "v42", "v43", "v44", "v45",       \
+                  "v46", "v47", "v48", "v50", "v52", "v54", "v55", "v56", "v57");                                     \
+            flush_ready();                                                                                            \
         }
+        ANSZP_RUN_BLOCKS(8u, ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB)
+        ANSZP_RUN_BLOCKS(4u, ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB)
+        ANSZP_RUN_BLOCKS(2u, ANSZP_STEP_AB)
+#undef ANSZP_RUN_BLOCKS
 #undef ANSZP_STEP_AB
 #undef ANSZP_STEP_BA
 #undef ANSZP_STEP
