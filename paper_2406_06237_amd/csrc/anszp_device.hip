@@ -120,29 +120,41 @@ __device__ uint32_t decode_chunk_stepwise(const DecodeParams& p, const anszp_chu
 
     const uint32_t* words = p.payload + c.payload_offset;
     const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
-    uint32_t next_word = first_word;
+    auto word_at = [&](uint32_t i) { return i < word_limit ? words[i] : 0u; };
+    uint32_t next_word = first_word;                  // words moved into buf so far (plus first_word)
     uint64_t buf = 0;
     uint32_t have = 0;
+    uint32_t ahead = word_at(first_word);             // the word after those in buf, requested one refill early
     const uint32_t steps = (c.n_symbols + N - 1u) / N;
     const bool per_channel = lay.channel_len != 0;
-    const uint64_t layer_elem0 = c.out_offset - lay.out_base;
+    // per-channel scales: channel index and position inside the channel advance by N per step
+    const uint64_t elem0 = c.out_offset - lay.out_base + lane;
+    uint64_t channel = per_channel ? lay.scales_offset + elem0 / lay.channel_len : 0;
+    uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
+    float scale = lay.scale;
+    if (per_channel) scale = channel < p.n_scales ? p.scales[channel] : 0.0f;
     for (uint32_t t = 0; t < steps; ++t) {
         if (t < len) {
             const uint32_t e = table[X];
             const uint32_t nb = (e >> 16) & 0xFFu;
             if (have < nb) {
-                const uint32_t w = next_word < word_limit ? words[next_word] : 0u;
-                ++next_word;
-                buf |= uint64_t(w) << have;
+                buf |= uint64_t(ahead) << have;
                 have += 32;
+                ++next_word;
+                ahead = word_at(next_word);
             }
             const uint32_t bits = static_cast<uint32_t>(buf) & ((1u << nb) - 1u);
             buf >>= nb;
             have -= nb;
             X = ((e & 0xFFFFu) + bits) & (L - 1u);
-            const uint64_t j = uint64_t(t) * N + lane;
-            const float scale = per_channel ? channel_scale(p, lay, layer_elem0 + j) : lay.scale;
-            store_weight<OUT>(p.out, c.out_offset + j, e >> 24, lay.zero_point, scale);
+            store_weight<OUT>(p.out, c.out_offset + uint64_t(t) * N + lane, e >> 24, lay.zero_point, scale);
+            if (per_channel) {
+                in_channel += N;
+                if (in_channel >= lay.channel_len) {
+                    do { in_channel -= lay.channel_len; ++channel; } while (in_channel >= lay.channel_len);
+                    scale = channel < p.n_scales ? p.scales[channel] : 0.0f;
+                }
+            }
         }
     }
     if (lane < N) {
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
     if (ne2 >= n2 && X8 != 0) err |= ANSZP_ST_BAD_STATE; // empty stream must carry state 0
 
     uint32_t flushed2 = 0;                               // 2 * elements already stored (wave-uniform)
-    constexpr uint32_t kBatch = 8;                       // slabs stored per flush
+    constexpr uint32_t kBatch = 16;                      // slabs stored per flush
     constexpr uint32_t kBatch2 = kBatch * kSlab2;
 
     // two consecutive payload words starting at a 4-byte aligned LDS byte offset
@@ -585,7 +597,9 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
-    const bool stepwise = mode == 1;
+    // chunks whose compressed words cannot fit the merged kernel's LDS window would all take its
+    // fallback; launch the light step-wise kernel (many more wavefronts per CU) for them instead
+    const bool stepwise = mode == 1 || (mode == 0 && a->payload_words / a->n_chunks > kPayloadWords);
     const bool per_channel = a->scales != nullptr && a->n_scales != 0;
     switch (a->out_dtype) {
         case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, s); break;

@@ -73,6 +73,24 @@ def test_config3_resnet50(orc):
     _run(orc, W.config3())
 
 
+def test_config4_one_block_at_real_shapes(orc):
+    """One of config 4's 32 identical blocks (4 of 4096x4096 and 3 of 4096x11008, 262,144-symbol chunks,
+    per-output-channel scales): every chunk has the full-size geometry of the whole set."""
+    w = W.config4(n_blocks=1)
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    d = B.to_device(host_from_oracle(c, w))
+    out = B.decode(d)
+    assert d.read_status() == (0, 0)
+    got = B.bits_of(out)[:w.numel]
+    assert np.array_equal(got, expect)
+    # the merged kernel forced onto the same chunks (they exceed its window and fall back inside it)
+    idx = np.random.default_rng(0).integers(0, w.numel, size=200000)
+    out2 = B.decode(d, variant=B.VARIANT_MERGED)
+    assert d.read_status() == (0, 0)
+    assert np.array_equal(B.bits_of(out2)[:w.numel][idx], expect[idx])
+
+
 def test_library_packer_output_decodes_too(orc):
     """The same weights compressed by the library's own host packer."""
     w = W.tiny(n=70000, chunk_size=8192, table_log=11, p0=0.85)
