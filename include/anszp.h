@@ -34,7 +34,8 @@
  *   Inside a chunk, element j belongs to stream (j mod N) and is that stream's
  *   symbol number (j div N); N = n_streams <= 64.  Each stream is a private run
  *   of 32-bit words: the bits the decoder reads, in the order it reads them,
- *   least significant bit first, zero-padded to a whole word.  A chunk's
+ *   filling each word from bit 0 upwards, zero-padded to a whole word.  The
+ *   nb_bits of one step are read most significant first (bits = 2*bits + next).  A chunk's
  *   payload is its N streams' words back to back in stream order and starts at
  *   a word offset that is a multiple of 4.  Each stream has one 32-bit header:
  *   bits 0..15 the decoder's initial state X (0 <= X < 2^table_log), bits
@@ -69,6 +70,7 @@ extern "C" {
 #define ANSZP_ST_BAD_DESC     1u    /* chunk descriptor points outside a buffer; chunk skipped */
 #define ANSZP_ST_BAD_STATE    2u    /* a stream did not end in state 0                          */
 #define ANSZP_ST_BAD_LENGTH   4u    /* a stream read more or fewer words than its header says   */
+#define ANSZP_ST_INTERNAL     8u    /* a hand-over between wavefronts did not complete; chunk abandoned */
 
 /* output element types */
 #define ANSZP_OUT_U8          0     /* decoded symbols, no dequantisation                       */
@@ -98,7 +100,7 @@ typedef struct {
 
 /* Arguments of anszp_decode (the struct itself is read on the host). */
 typedef struct {
-    const uint32_t*      tables;        /* [device] n_tables * 2 * 2^table_log words from anszp_build_tables, 16-byte aligned */
+    const uint32_t*      tables;        /* [device] n_tables * 4 * 2^table_log words from anszp_build_tables, 16-byte aligned */
     uint32_t             n_tables;
     uint32_t             table_log;     /* R, 1..12                                             */
     uint32_t             n_streams;     /* N, 1..64                                             */
@@ -132,14 +134,19 @@ const char* anszp_strerror(int code);
 int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs);
 
 /* [host only] Sec. II-A / III-A: build n_tables decode tables from normalised frequencies.
- * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 2 * 2^table_log 32-bit words.
- * Table t occupies words [t*2L, (t+1)*2L), L = 2^table_log, in two halves indexed by state X:
- *   word [X]      bits  0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol    -- the paper's triple
- *   word [L + X]  bits  0..2  c-1       bits  3..14 newX'     bit 15 end-flag
- *                 bits 16..23 symbol'   bits 24..31 nb_bits'                        -- the same automaton
- *   with up to 8 steps merged: from state X the next c-1 symbols are zero-bit transitions of the
- *   dominant symbol (f > L/2), then symbol' is emitted, nb_bits' bits are read and the state
- *   becomes newX' + bits.  end-flag: the state before the c-th symbol is state 0.
+ * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 4 * 2^table_log 32-bit words.
+ * Table t occupies words [t*4L, (t+1)*4L), L = 2^table_log:
+ *   word [2L + X]   the paper's triple for state X:
+ *                   bits 0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol
+ *   word [2X + b]   the same automaton with up to 4 steps merged and one bit of look-ahead: in state
+ *                   X with next stream bit b (peeked, not consumed) the next c-1 symbols are the
+ *                   dominant symbol (f > L/2: its zero-bit transitions and at most one of its 1-bit
+ *                   transitions, which consumes b), then `symbol` is emitted; T stream bits are
+ *                   consumed in all, and with v = the next T+1 stream bits, first bit on top, the
+ *                   next index is base + v.
+ *                   bits 0..4 31-T (T <= 12)   bits 5..7 zero   bits 8..15 symbol
+ *                   bits 16..17 c-1            bits 18..31 base (two's complement)
+ *   words [3L, 4L)  zero
  * Errors: E_NULL, E_RANGE, E_FREQ. */
 int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint32_t* tables);
 

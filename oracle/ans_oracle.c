@@ -226,9 +226,9 @@ int orc_build_encode_map(const uint32_t *f, int R, uint16_t *enc, uint32_t *base
  * after the first symbol has been encoded is the decoder's initial state.
  *
  * Bit order (paper: silent).  Reading: the stream's bit sequence is the groups
- * in DECODE order (symbol 0 first); within a group the least significant bit
- * comes first; the sequence is packed LSB-first into 32-bit words and
- * zero-padded to a whole word.
+ * in DECODE order (symbol 0 first); within a group the most significant bit
+ * of its value comes first; the sequence is packed into 32-bit words starting
+ * at bit 0 of each word and zero-padded to a whole word.
  *
  * Returns the number of 32-bit words written, or a negative error.          */
 int64_t orc_encode_stream(const uint8_t *sym, uint64_t first, uint64_t stride, uint64_t count,
@@ -260,7 +260,7 @@ int64_t orc_encode_stream(const uint8_t *sym, uint64_t first, uint64_t stride, u
     bitpos = 0;
     for (uint64_t i = 0; i < count; i++) {
         for (int b = 0; b < gnb[i]; b++) {
-            if ((gval[i] >> b) & 1u) words[bitpos >> 5] |= 1u << (bitpos & 31);
+            if ((gval[i] >> (gnb[i] - 1 - b)) & 1u) words[bitpos >> 5] |= 1u << (bitpos & 31);
             bitpos++;
         }
     }
@@ -287,7 +287,7 @@ int orc_decode_stream(const uint32_t *words, uint64_t nwords, uint16_t init_stat
         if (bitpos + n > nwords * 32) return ORC_E_CORRUPT;
         for (uint32_t b = 0; b < n; b++) {
             uint64_t p = bitpos + b;
-            v |= ((words[p >> 5] >> (p & 31)) & 1u) << b;
+            v = (v << 1) | ((words[p >> 5] >> (p & 31)) & 1u);
         }
         bitpos += n;
         out[first + i * stride] = tsym[X];

@@ -99,7 +99,7 @@ def normalize_freqs(counts: np.ndarray, table_log: int) -> np.ndarray:
 
 def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
-    size = len(freqs) << (max(0, min(table_log, 20)) + 1)
+    size = len(freqs) << (max(0, min(table_log, 20)) + 2)
     tables = np.zeros(size, dtype=np.uint32)
     _check(lib().anszp_build_tables_host(freqs.ctypes.data, len(freqs), table_log, tables.ctypes.data),
            "anszp_build_tables_host")
@@ -107,15 +107,17 @@ def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
 
 
 def split_table(tables: np.ndarray):
-    """Fields of the table entries: the paper's triple and the merged-step fields."""
+    """Fields of a table (or stack of tables): the paper's triple per state and the look-ahead entries."""
     t = np.asarray(tables, dtype=np.uint32)
-    L = t.shape[-1] // 2
-    lo, hi = t[..., :L], t[..., L:]
+    L = t.shape[-1] // 4
+    la, lo = t[..., :2 * L], t[..., 2 * L:3 * L]
+    base = (la >> 18).astype(np.int32)
+    base = np.where(base >= 1 << 13, base - (1 << 14), base)
     return {"newX": (lo & 0xFFFF).astype(np.uint16), "nb": ((lo >> 16) & 0xFF).astype(np.uint8),
             "sym": (lo >> 24).astype(np.uint8),
-            "count": ((hi & 7) + 1).astype(np.uint8), "m_newX": ((hi >> 3) & 0xFFF).astype(np.uint16),
-            "m_end": ((hi >> 15) & 1).astype(np.uint8), "m_sym": ((hi >> 16) & 0xFF).astype(np.uint8),
-            "m_nb": (hi >> 24).astype(np.uint8)}
+            "la_bits": (31 - (la & 31)).astype(np.uint8), "la_pad": ((la >> 5) & 7).astype(np.uint8),
+            "la_sym": ((la >> 8) & 0xFF).astype(np.uint8), "la_count": (((la >> 16) & 3) + 1).astype(np.uint8),
+            "la_base": base, "tail": t[..., 3 * L:]}
 
 
 @dataclass
@@ -215,11 +217,11 @@ def _stream_ptr(torch, device):
 
 
 def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
-    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 2 * 2^table_log uint32)."""
+    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 4 * 2^table_log uint32)."""
     torch = _torch()
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
     with torch.cuda.device(device):
-        tables = torch.empty((len(freqs) << table_log) * 8, dtype=torch.uint8, device=device)
+        tables = torch.empty((len(freqs) << table_log) * 16, dtype=torch.uint8, device=device)
         _check(lib().anszp_build_tables(freqs.ctypes.data, len(freqs), table_log, tables.data_ptr(),
                                         _stream_ptr(torch, device)), "anszp_build_tables")
     return tables

@@ -19,16 +19,21 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 1024;                   // 16 wavefronts stage; wavefront 0 decodes
-constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB of LDS entries
-constexpr uint32_t kRingBytes = 32u * 1024u;   // LDS ring of decoded codes (2 bytes each)
-constexpr uint32_t kRingElems = kRingBytes / 2u;
-constexpr uint32_t kSlab = 512u;               // elements flushed per wave store (8 per lane)
+constexpr int kBlock = 512;                    // 8 wavefronts stage, five of them stay for the decode; two such
+                                               // workgroups fit a CU with 128 VGPRs per wavefront
+constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB: two look-ahead entries of 4 bytes per state
+constexpr uint32_t kRingElems = 16u * 1024u;   // LDS ring of decoded symbols (one byte each)
+constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
 constexpr uint32_t kPayloadWords = 3584u;      // LDS window for one chunk's compressed words
-constexpr uint32_t kMaxMerged = 8u;
+constexpr uint32_t kMaxMerged = 4u;             // symbols one look-ahead entry can stand for
+constexpr uint32_t kLogSlots = 4u;              // blocks of look-ups in flight between two wavefronts
+constexpr uint32_t kLogSlotBytes = 8u * kWave * 4u;
+constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
 struct DecodeParams {
     const uint32_t* tables;
@@ -46,6 +51,7 @@ struct DecodeParams {
     uint32_t n_tables;
     uint32_t table_log;
     uint32_t n_streams;
+    uint32_t n_cus;             // compute units of the device: workgroups n_cus apart tend to share one
 };
 
 __device__ __forceinline__ uint32_t bf16_rne(float w) {
@@ -81,6 +87,13 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
     *total = __shfl(inc, kWave - 1, kWave);
     return inc - v;
 }
+
+// A word in LDS that another wavefront of the workgroup writes or reads: every access is performed,
+// in order, as an LDS instruction.
+typedef volatile __attribute__((address_space(3))) uint32_t lds_flag_t;
+
+// A value every lane holds alike, moved to a scalar register.
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
 __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
 #pragma unroll
@@ -143,7 +156,8 @@ __device__ uint32_t decode_chunk_stepwise(const DecodeParams& p, const anszp_chu
                 ++next_word;
                 ahead = word_at(next_word);
             }
-            const uint32_t bits = static_cast<uint32_t>(buf) & ((1u << nb) - 1u);
+            const uint32_t low = static_cast<uint32_t>(buf) & ((1u << nb) - 1u);
+            const uint32_t bits = nb ? __brev(low) >> (32u - nb) : 0u;      // first bit read is the top bit
             buf >>= nb;
             have -= nb;
             X = ((e & 0xFFFFu) + bits) & (L - 1u);
@@ -173,7 +187,7 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
-    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 1));    // first half: the paper's triple
+    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + (2u << p.table_log);   // the paper's triples
     for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = src[i];
     const anszp_layer_t lay = p.layers[c.layer_id];
     __syncthreads();
@@ -182,41 +196,36 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Merged-run path.
-//
-// LDS entry (8 bytes) derived from the merged half of a table entry while staging:
-//   lo: newX' * 8, the byte offset of the next entry before the stream bits are OR-ed in
-//   hi: bits 0..4 nb_bits' | bits 8..10 c-1 | bit 15 end-flag | bits 16..31 code of symbol'
-// One look-up emits c symbols: c-1 copies of the dominant symbol, which the ring already holds
-// as background, then symbol'.  code = bf16 weight when the output is bf16 with a per-layer
-// scale (dequantisation folded into the table), else the symbol itself and dequantisation
-// happens when a slab leaves the ring.
+// Look-ahead path: conversion of decoded symbols on their way from the LDS ring to global memory.
+// `lut` maps a symbol to its bf16 weight when dequantisation is per layer and the output bf16
+// (Sec. II-B computed once per symbol value instead of once per weight).
 template <int OUT, bool PER_CHANNEL>
 struct Flusher {
-    // Convert the 8 codes of one lane (elements g .. g+7 of the output) and store them.
+    static constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
+    // Convert the 8 symbols of one lane (bytes of `s`, elements g .. g+7 of the output) and store them.
     static __device__ __forceinline__ void store8(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
-                                                  uint64_t layer_elem, uint4 codes) {
-        if constexpr (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL) {
-            *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) = codes;
+                                                  uint64_t layer_elem, uint2 s, const uint16_t* lut) {
+        if constexpr (OUT == ANSZP_OUT_U8) {
+            *reinterpret_cast<uint2*>(static_cast<uint8_t*>(p.out) + g) = s;
         } else {
-            const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
             uint32_t sym[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { sym[2 * i] = w[i] & 0xFFFFu; sym[2 * i + 1] = w[i] >> 16; }
-            if constexpr (OUT == ANSZP_OUT_U8) {
-                uint2 o;
-                o.x = sym[0] | (sym[1] << 8) | (sym[2] << 16) | (sym[3] << 24);
-                o.y = sym[4] | (sym[5] << 8) | (sym[6] << 16) | (sym[7] << 24);
-                *reinterpret_cast<uint2*>(static_cast<uint8_t*>(p.out) + g) = o;
+            for (int i = 0; i < 4; ++i) { sym[i] = (s.x >> (8 * i)) & 0xFFu; sym[4 + i] = (s.y >> (8 * i)) & 0xFFu; }
+            if constexpr (kFolded) {
+                uint32_t w[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) w[i] = lut[sym[i]];
+                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) =
+                    make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
             } else {
                 float v[8];
                 if constexpr (PER_CHANNEL) {
                     const uint32_t e0 = static_cast<uint32_t>(layer_elem);
                     const uint32_t left = lay.channel_len - e0 % lay.channel_len;   // elements left in this channel
                     if (left >= 8u) {
-                        const float s = channel_scale(p, lay, layer_elem);
+                        const float sc = channel_scale(p, lay, layer_elem);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] = dequant(sym[i], lay.zero_point, s);
+                        for (int i = 0; i < 8; ++i) v[i] = dequant(sym[i], lay.zero_point, sc);
                     } else {
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
@@ -243,32 +252,54 @@ struct Flusher {
     }
     // One element (tail of a chunk).
     static __device__ __forceinline__ void store1(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
-                                                  uint64_t layer_elem, uint32_t code) {
-        if constexpr (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL) {
-            static_cast<uint16_t*>(p.out)[g] = static_cast<uint16_t>(code);
+                                                  uint64_t layer_elem, uint32_t sym, const uint16_t* lut) {
+        if constexpr (kFolded) {
+            static_cast<uint16_t*>(p.out)[g] = lut[sym];
         } else {
-            const float s = PER_CHANNEL ? channel_scale(p, lay, layer_elem) : lay.scale;
-            store_weight<OUT>(p.out, g, code, lay.zero_point, s);
+            const float sc = PER_CHANNEL ? channel_scale(p, lay, layer_elem) : lay.scale;
+            store_weight<OUT>(p.out, g, sym, lay.zero_point, sc);
         }
     }
 };
 
 template <int OUT, bool PER_CHANNEL>
-__global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
-    // one LDS block, carved by hand so that the compressed words sit at offset 0 (their two-dword
-    // reads have no room for a large immediate offset), then the table, then the ring
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))   // 2 workgroups per CU; more buys nothing
+void decode_merged(DecodeParams p) {
+    // One LDS block carved by hand.  The compressed words sit at offset 0 (their two-dword reads have no
+    // room for a large immediate offset); everything the hand-scheduled look-up addresses with an
+    // immediate offset lies below 64 KiB.
     constexpr uint32_t kWordsBytes = (kPayloadWords + 8u) * 4u;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kWordsBytes + kTableBytes + kRingBytes];
+    constexpr uint32_t kCtlOff = kWordsBytes;                       // hand-over words, then block headers
+    constexpr uint32_t kHdrOff = kCtlOff + 32u;
+    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 16u;        // per lane: doubled index of the next symbol to expand
+    constexpr uint32_t kSimdOff = kProgOff + kWave * 4u;            // SIMD each of the first 8 wavefronts runs on
+    constexpr uint32_t kTableOff = kSimdOff + 32u;                  // 2L look-ahead entries, later the L triples
+    constexpr uint32_t kLutOff = kTableOff + kTableBytes;           // symbol -> bf16 weight
+    constexpr uint32_t kRingOff = kLutOff + 512u;
+    constexpr uint32_t kLogOff = kRingOff + kRingElems;             // logged entries: [slot][look-up][lane]
+    constexpr uint32_t kLdsBytes = kLogOff + kLogSlots * kLogSlotBytes;
+    static_assert(kTableOff % 16u == 0 && kRingOff % 16u == 0 && kCtlOff % 8u == 0 && kRingOff < 65536u, "LDS layout");
+    static_assert(2u * kLdsBytes <= 160u * 1024u, "two workgroups per CU");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     uint32_t* const lds_words = reinterpret_cast<uint32_t*>(lds);
-    uint8_t* const lds_table = lds + kWordsBytes;
-    uint16_t* const lds_ring = reinterpret_cast<uint16_t*>(lds + kWordsBytes + kTableBytes);
-    constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
+    uint32_t* const lds_table = reinterpret_cast<uint32_t*>(lds + kTableOff);
+    uint16_t* const lds_lut = reinterpret_cast<uint16_t*>(lds + kLutOff);
+    uint8_t* const ring8 = lds + kRingOff;
+    // hand-over words: 0 blocks logged by the decoding wavefront | 1 its block phase is over | 2 blocks
+    // expanded | 3 elements stored | 4, 7 lower, upper half of the triples are in LDS | 5 a wait gave up |
+    // 6 the storing wavefront has stored all it can
+    lds_flag_t* const ctl = (lds_flag_t*)(lds + kCtlOff);
+    lds_flag_t* const blk_hdr = (lds_flag_t*)(lds + kHdrOff);   // lanes lo, hi, look-ups, -
+    enum { kLogged = 0, kOver = 1, kExpanded = 2, kStored = 3, kTriplesLo = 4, kGaveUp = 5, kStoreDone = 6, kTriplesHi = 7 };
+    constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
-    constexpr uint32_t kTableLoads = ((1u << ANSZP_MAX_TABLE_LOG) / 4u + kBlock - 1u) / kBlock;   // 16-byte loads per thread
+    constexpr uint32_t kTableLoads = ((2u << ANSZP_MAX_TABLE_LOG) / 4u + kBlock - 1u) / kBlock;   // 16-byte loads per thread
     constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;
+    constexpr uint32_t kTripleLoads = (1u << ANSZP_MAX_TABLE_LOG) / 4u / kWave;                   // per lane of one wavefront
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
     const anszp_chunk_t c = p.chunks[blockIdx.x];
@@ -277,29 +308,28 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
         return;
     }
     // Issue every global read that depends only on the descriptor before waiting for any of them:
-    // stream headers, the merged half of the layer's table, the chunk's compressed words (from
+    // stream headers, the look-ahead half of the layer's table, the chunk's compressed words (from
     // clamped, always valid indices) and the layer's quantizer.
-    const uint32_t hdr = (tid < N) ? p.stream_hdr[c.stream_offset + tid] : 0u;
-    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 1));
-    const uint4* tsrc = reinterpret_cast<const uint4*>(src + L);              // merged half, 4 entries per load
+    const uint32_t hdr = (wave < 8u && lane < N) ? p.stream_hdr[c.stream_offset + lane] : 0u;   // any of them may decode
+    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2));
+    const uint4* tsrc = reinterpret_cast<const uint4*>(src);                  // look-ahead entries, 4 per load
     const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
     const uint32_t quads = min(c.payload_words, kPayloadWords) >> 2;
-    const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte rows
+    const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte row of triples
     uint4 tv[kTableLoads], wv[kWordLoads];
     {
-        const uint32_t t_last = wide ? (L >> 2) - 1u : 0u;
+        const uint32_t t_last = (L >> 1) - 1u;
         const uint32_t w_last = quads ? quads - 1u : 0u;
-        const uint4* tsafe = wide ? tsrc : reinterpret_cast<const uint4*>(p.tables);
-        const uint4* wsafe = quads ? wsrc : tsafe;
+        const uint4* wsafe = quads ? wsrc : tsrc;
 #pragma unroll
-        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsafe[min(tid + k * kBlock, t_last)];
+        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsrc[min(tid + k * kBlock, t_last)];
 #pragma unroll
         for (uint32_t k = 0; k < kWordLoads; ++k) wv[k] = wsafe[min(tid + k * kBlock, w_last)];
     }
     uint32_t tail = 0;
     if (tid < 8 && (quads << 2) + tid < c.payload_words && c.payload_words <= kPayloadWords)
         tail = p.payload[c.payload_offset + (quads << 2) + tid];
-    const uint32_t top = src[L - 1];                     // state L-1 carries the dominant symbol if there is one
+    const uint32_t top = src[3u * L - 1u];               // state L-1 carries the dominant symbol if there is one
     const anszp_layer_t lay = p.layers[c.layer_id];
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
     const uint32_t n = c.n_symbols;
@@ -308,244 +338,463 @@ __global__ __launch_bounds__(kBlock) void decode_merged(DecodeParams p) {
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
 
     if (!merged_ok) {                                     // whole workgroup agrees
-        uint32_t* table = reinterpret_cast<uint32_t*>(lds_table);
-        for (uint32_t i = tid; i < L; i += kBlock) table[i] = src[i];
+        for (uint32_t i = tid; i < L; i += kBlock) lds_table[i] = src[2u * L + i];
         __syncthreads();
-        if (tid >= kWave) return;
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
+        if (wave != 0) return;
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, lds_table, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
 
-    // ---- stage: table (dequantisation folded in), compressed words, ring background
+    // ---- stage: look-ahead entries, compressed words, symbol -> code, ring background, hand-over words
     {
-        auto entry = [&](uint32_t m) {
-            const uint32_t sym = (m >> 16) & 0xFFu;
-            const uint32_t nb = min(m >> 24, uint32_t(ANSZP_MAX_TABLE_LOG));
-            const uint32_t code = kFolded ? bf16_rne(dequant(sym, lay.zero_point, lay.scale)) : sym;
-            return make_uint2(m & 0x7FF8u, nb | ((m & 7u) << 8) | (m & 0x8000u) | (code << 16));
-        };
+        // every thread stores what it loaded, to the clamped index it loaded from (threads past the
+        // end repeat the last row): stores under a per-thread condition would let the compiler move
+        // each load down to its store and wait for them one at a time
         uint4* tdst = reinterpret_cast<uint4*>(lds_table);
 #pragma unroll
-        for (uint32_t k = 0; k < kTableLoads; ++k) {
-            const uint32_t i = tid + k * kBlock;
-            if (4u * i < L) {
-                const uint2 a = entry(tv[k].x), b = entry(tv[k].y), cc = entry(tv[k].z), d = entry(tv[k].w);
-                tdst[2u * i] = make_uint4(a.x, a.y, b.x, b.y);
-                tdst[2u * i + 1u] = make_uint4(cc.x, cc.y, d.x, d.y);
-            }
-        }
-        uint4* wdst = reinterpret_cast<uint4*>(lds_words);
+        for (uint32_t k = 0; k < kTableLoads; ++k) tdst[min(tid + k * kBlock, (L >> 1) - 1u)] = tv[k];
+        uint4* wdst = reinterpret_cast<uint4*>(quads ? lds : lds + kLogOff);     // no whole row of words: anywhere unused
 #pragma unroll
-        for (uint32_t k = 0; k < kWordLoads; ++k) {
-            const uint32_t i = tid + k * kBlock;
-            if (i < quads) wdst[i] = wv[k];
-        }
+        for (uint32_t k = 0; k < kWordLoads; ++k) wdst[min(tid + k * kBlock, quads ? quads - 1u : 0u)] = wv[k];
         if (tid < 8) lds_words[(quads << 2) + tid] = tail;      // tail words, then zeros for clamped reads
+        if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
+        if (tid < 8 + kLogSlots * 4u) reinterpret_cast<uint32_t*>(lds + kCtlOff)[tid] = 0u;
+        if (tid < kWave) reinterpret_cast<uint32_t*>(lds + kProgOff)[tid] = (tid < N) ? tid : n;
+        if (lane == 0 && wave < 8u)                      // HW_ID bits 4..5: the SIMD this wavefront runs on
+            reinterpret_cast<uint32_t*>(lds + kSimdOff)[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
     }
-    const uint32_t bg_sym = top >> 24;
-    const uint32_t bg_code = kFolded ? bf16_rne(dequant(bg_sym, lay.zero_point, lay.scale)) : bg_sym;
-    const uint32_t bg2 = bg_code | (bg_code << 16);
+    const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the ring's background: the dominant symbol
     {
-        uint4* rdst = reinterpret_cast<uint4*>(lds_ring);
+        uint4* rdst = reinterpret_cast<uint4*>(ring8);
 #pragma unroll
-        for (uint32_t k = 0; k < (kRingBytes / 16u + kBlock - 1u) / kBlock; ++k)
-            if (tid + k * kBlock < kRingBytes / 16u) rdst[tid + k * kBlock] = make_uint4(bg2, bg2, bg2, bg2);
+        for (uint32_t k = 0; k < (kRingElems / 16u + kBlock - 1u) / kBlock; ++k)
+            if (tid + k * kBlock < kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(bg4, bg4, bg4, bg4);
     }
     __syncthreads();
-    if (tid >= kWave) return;                            // helper wavefronts are done
+    // Five wavefronts stay, each with one task; the others were staging helpers.  A lone wavefront's
+    // speed is set by how often its SIMD lets it issue, so the busy tasks are spread over the CU's
+    // four SIMDs, and two workgroups that share a CU (workgroups n_cus apart, as a rule) pick
+    // different SIMDs for their decoding wavefronts:  SIMD 0/1 decode | 2/3 expand | 3/2 store;
+    // the two placing wavefronts sleep until the end and go where the other workgroup decodes.
+    enum { kDecode = 0, kExpand = 1, kStore = 2, kPlaceLo = 3, kPlaceHi = 4, kNoTask = 5 };
+    uint32_t task = kNoTask;
+    {
+        const uint32_t second = (blockIdx.x / max(p.n_cus, 1u)) & 1u;
+        const uint32_t want[5] = {second, 2u + second, 3u - second, 1u - second, 1u - second};
+        const uint32_t mine = reinterpret_cast<const uint32_t*>(lds + kSimdOff)[lane & 7u];   // one read, eight answers
+        uint32_t simd[8];
+#pragma unroll
+        for (uint32_t w = 0; w < 8u; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
+        uint32_t taken = 0;
+#pragma unroll
+        for (uint32_t t = 0; t < 5u; ++t) {
+            uint32_t pick = 8u;
+#pragma unroll
+            for (uint32_t w = 0; w < 8u; ++w)
+                if (pick == 8u && !((taken >> w) & 1u) && simd[w] == want[t]) pick = w;
+#pragma unroll
+            for (uint32_t w = 0; w < 8u; ++w)          // no wavefront on that SIMD: any free one
+                if (pick == 8u && !((taken >> w) & 1u)) pick = w;
+            taken |= 1u << pick;
+            if (pick == wave) task = t;
+        }
+    }
+    if (task == kNoTask) return;
 
-    // ---- per-lane stream state (lane == tid in wavefront 0)
+    constexpr uint32_t kRingMask = kRingElems - 1u;
+
+    if (task == kPlaceLo || task == kPlaceHi) {
+        // ---- placing wavefronts: when the block phase is over the look-ahead entries are dead; put
+        // the triples (Sec. II-A), kept in registers until then, in their place for the last symbols
+        // of every stream.  Each of the two holds half of the rows (eight named values rather than
+        // an array: an array that lives across the wait is kept in scratch memory by the compiler).
+        const uint4* psrc = reinterpret_cast<const uint4*>(src + 2u * L);
+        const uint32_t rows = L >> 2;
+        const uint32_t first_row = lane + (task == kPlaceHi ? kTripleLoads / 2u : 0u) * kWave;
+#define ANSZP_8(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
+#define ANSZP_LOAD_ROW(k) const uint4 row##k = psrc[min(first_row + k * kWave, rows - 1u)];
+#define ANSZP_STORE_ROW(k) if (first_row + k * kWave < rows) dst[first_row + k * kWave] = row##k;
+        static_assert(kTripleLoads == 16u, "eight 16-byte rows per lane and wavefront");
+        ANSZP_8(ANSZP_LOAD_ROW)
+        for (uint32_t spins = 0; !uniform(ctl[kOver]); ++spins) {
+            if (uniform(ctl[kGaveUp]) || spins > kSpinLimit) return;
+            __builtin_amdgcn_s_sleep(4);
+        }
+        uint4* dst = reinterpret_cast<uint4*>(lds_table);
+        ANSZP_8(ANSZP_STORE_ROW)
+#undef ANSZP_STORE_ROW
+#undef ANSZP_LOAD_ROW
+#undef ANSZP_8
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) ctl[task == kPlaceHi ? kTriplesHi : kTriplesLo] = 1u;
+        return;
+    }
+
+    // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.  Up to
+    // four leave per call, their LDS reads issued together.  A lane takes elements 8*lane .. 8*lane+7
+    // of each half of a slab, so that every store instruction writes one contiguous run.
+    auto store_slabs = [&](uint32_t stored, auto count) {
+        constexpr uint32_t K = decltype(count)::value;
+        uint2 lo[K], hi[K];
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) {              // the ring is a whole number of slabs: wrap per slab
+            const uint8_t* q = ring8 + (((stored + k * kSlab) & kRingMask) + lane * 8u);
+            lo[k] = *reinterpret_cast<const uint2*>(q);
+            hi[k] = *reinterpret_cast<const uint2*>(q + kSlab / 2u);
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) {
+            uint8_t* q = ring8 + (((stored + k * kSlab) & kRingMask) + lane * 8u);
+            *reinterpret_cast<uint2*>(q) = make_uint2(bg4, bg4);
+            *reinterpret_cast<uint2*>(q + kSlab / 2u) = make_uint2(bg4, bg4);
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) {
+            const uint32_t first = stored + k * kSlab + lane * 8u;
+            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first, layer_elem0 + first, lo[k], lds_lut);
+            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u,
+                                              hi[k], lds_lut);
+        }
+    };
+    constexpr uint32_t kStoreBatch = PER_CHANNEL ? 1u : 2u;   // conversion needs the registers
+    auto store_ready = [&](uint32_t ne, uint32_t& stored) {
+        for (;;) {
+            uint32_t ready = 0;
+            while (ready < kStoreBatch && stored + (ready + 1u) * kSlab <= n &&
+                   __ballot(ne < stored + (ready + 1u) * kSlab) == 0)
+                ++ready;
+            if (ready == 0) return;
+            if constexpr (kStoreBatch == 2u) {
+                if (ready == 2u) store_slabs(stored, std::integral_constant<uint32_t, 2u>{});
+                else store_slabs(stored, std::integral_constant<uint32_t, 1u>{});
+            } else {
+                store_slabs(stored, std::integral_constant<uint32_t, 1u>{});
+            }
+            stored += ready * kSlab;
+            if (ready < kStoreBatch) return;
+        }
+    };
+
+    if (task == kExpand) {
+        // ---- expanding wavefront: turn logged entries into symbols in the ring.  An entry stands for c symbols: c-1
+        // copies of the dominant symbol, which the ring already holds as background, then its own
+        // symbol.  Every pass reads the count of logged
+        // blocks and, in the same batch of LDS reads, the header and the entries of the block it
+        // waits for: if the count (read first) says the block is there, what was read after it is
+        // the block.
+        uint32_t ne = (lane < N) ? lane : n;             // chunk index of this lane's next symbol
+        uint32_t expanded = 0, spins = 0;
+        for (;;) {
+            const uint32_t slot = expanded & (kLogSlots - 1u);
+            uint32_t logged_v, lookups_v, ent[8];
+            uint64_t lanes_v;
+            // one batch of LDS reads (no wait between them; LDS serves a wavefront's reads in order)
+            asm volatile(
+                "ds_read_b32 %[lg], %[zero] offset:%[ctlw0]\n"
+                "ds_read_b64 %[lanes], %[hdra] offset:%[hdr]\n"
+                "ds_read_b32 %[lk], %[hdra] offset:%[hdr]+8\n"
+                "ds_read_b32 %[e0], %[loga]\n"
+                "ds_read_b32 %[e1], %[loga] offset:256\n"
+                "ds_read_b32 %[e2], %[loga] offset:512\n"
+                "ds_read_b32 %[e3], %[loga] offset:768\n"
+                "ds_read_b32 %[e4], %[loga] offset:1024\n"
+                "ds_read_b32 %[e5], %[loga] offset:1280\n"
+                "ds_read_b32 %[e6], %[loga] offset:1536\n"
+                "ds_read_b32 %[e7], %[loga] offset:1792\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                : [lg] "=&v"(logged_v), [lanes] "=&v"(lanes_v), [lk] "=&v"(lookups_v),
+                  [e0] "=&v"(ent[0]), [e1] "=&v"(ent[1]), [e2] "=&v"(ent[2]), [e3] "=&v"(ent[3]),
+                  [e4] "=&v"(ent[4]), [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7])
+                : [zero] "v"(0u), [hdra] "v"(slot * 16u), [loga] "v"(kLogOff + slot * kLogSlotBytes + lane * 4u),
+                  [ctlw0] "n"(kCtlOff), [hdr] "n"(kHdrOff)
+                : "memory");
+            if (uniform(logged_v) == expanded) {         // nothing new
+                if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
+                    if (uniform(ctl[kLogged]) == expanded) break;
+                    continue;
+                }
+                if (uniform(ctl[kGaveUp])) break;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                continue;
+            }
+            spins = 0;
+            const uint32_t lookups = uniform(lookups_v);
+            if ((lanes_v >> lane) & 1u) {                // the same word in every lane: did this lane take part?
+                auto expand = [&](auto count) {
+                    constexpr uint32_t S = decltype(count)::value;
+#pragma unroll
+                    for (uint32_t k = 0; k < S; ++k) {
+                        const uint32_t last = __umul24((ent[k] >> 16) & 3u, N) + ne;
+                        ring8[last & kRingMask] = static_cast<uint8_t>(ent[k] >> 8);
+                        ne = last + N;
+                    }
+                };
+                if (lookups == 8u) expand(std::integral_constant<uint32_t, 8u>{});
+                else if (lookups == 4u) expand(std::integral_constant<uint32_t, 4u>{});
+                else expand(std::integral_constant<uint32_t, 2u>{});
+            }
+            ++expanded;
+            // publish the lanes' positions, then the count, issued after the ring writes above (LDS keeps
+            // a wavefront's accesses in order, so nothing has to be waited for)
+            asm volatile("ds_write_b32 %[pa], %[ne]\n"
+                         "ds_write_b32 %[zero], %[ex] offset:%[ctlw2]\n"
+                         :: [pa] "v"(kProgOff + lane * 4u), [ne] "v"(ne), [zero] "v"(0u), [ex] "v"(expanded),
+                            [ctlw2] "n"(kCtlOff + 8u)
+                         : "memory");
+        }
+        return;
+    }
+
+    if (task == kStore) {
+        // ---- storing wavefront: move finished slabs of the ring to global memory
+        uint32_t stored = 0, spins = 0;
+        for (;;) {
+            uint32_t over_v, logged_v, expanded_v, next;
+            asm volatile(                                // the flag first, the positions last
+                "ds_read_b32 %[ov], %[zero] offset:%[ctlw1]\n"
+                "ds_read_b32 %[lg], %[zero] offset:%[ctlw0]\n"
+                "ds_read_b32 %[ex], %[zero] offset:%[ctlw2]\n"
+                "ds_read_b32 %[nx], %[pa]\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                : [ov] "=&v"(over_v), [lg] "=&v"(logged_v), [ex] "=&v"(expanded_v), [nx] "=&v"(next)
+                : [zero] "v"(0u), [pa] "v"(kProgOff + lane * 4u), [ctlw0] "n"(kCtlOff), [ctlw1] "n"(kCtlOff + 4u),
+                  [ctlw2] "n"(kCtlOff + 8u)
+                : "memory");
+            // everything logged was expanded before the positions were read: no more will come
+            const bool last_pass = uniform(over_v) && uniform(logged_v) == uniform(expanded_v);
+            const uint32_t before = stored;
+            store_ready(next, stored);
+            if (stored != before) {
+                asm volatile("ds_write_b32 %[zero], %[st] offset:%[ctlw3]\n"
+                             :: [zero] "v"(0u), [st] "v"(stored), [ctlw3] "n"(kCtlOff + 12u) : "memory");
+                spins = 0;
+            }
+            if (last_pass) {
+                if (lane == 0) ctl[kStoreDone] = 1u;
+                break;
+            }
+            if (stored == before) {
+                if (uniform(ctl[kGaveUp])) break;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        return;
+    }
+
+    // ---- decoding wavefront: per-lane stream state
     const uint32_t n_words = hdr >> 16;
     uint32_t total_words;
     const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
     uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
     const uint32_t last_word4 = c.payload_words << 2;    // byte offset of the zero words behind the payload
 
-    const uint32_t n2 = 2u * n, N2 = 2u * N;             // element indices are kept doubled (ring byte offsets)
-    constexpr uint32_t kRing2 = 2u * kRingElems, kSlab2 = 2u * kSlab;
-    uint32_t X8 = (hdr & (L - 1u)) << 3;                 // byte offset of the current entry
+    // Look-ahead entries are indexed by 2 * state + the next stream bit (peeked, not yet read).
+    uint32_t X4 = (2u * (hdr & (L - 1u)) + (lds_words[min(first_word, c.payload_words)] & 1u)) << 2;
     uint32_t abit = first_word << 5;                     // bit position in the chunk's payload
-    uint32_t ne2 = (lane < N) ? 2u * lane : n2;          // 2 * chunk index of this lane's next symbol
-    if (ne2 >= n2 && X8 != 0) err |= ANSZP_ST_BAD_STATE; // empty stream must carry state 0
+    uint32_t ne = (lane < N) ? lane : n;                 // chunk index of this lane's next symbol
+    if (ne >= n && (hdr & (L - 1u)) != 0) err |= ANSZP_ST_BAD_STATE;   // empty stream must carry state 0
+    uint32_t logged = 0;
+    bool gave_up = false;
 
-    uint32_t flushed2 = 0;                               // 2 * elements already stored (wave-uniform)
-    constexpr uint32_t kBatch = 16;                      // slabs stored per flush
-    constexpr uint32_t kBatch2 = kBatch * kSlab2;
-
-    // two consecutive payload words starting at a 4-byte aligned LDS byte offset
-    auto word_pair = [&](uint32_t byte_off) {
-        const uint32_t* q = reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(lds_words) + byte_off);
-        return make_uint2(q[0], q[1]);
-    };
-    uint8_t* ring8 = reinterpret_cast<uint8_t*>(lds_ring);
-    uint2 e = *reinterpret_cast<const uint2*>(lds_table + X8);
-    uint2 w = word_pair(min(first_word << 2, last_word4));
-
-    // One look-up for every lane that is neither finished nor too far ahead of the slowest lane
-    // for the ring.  Sec. II-A step on a merged entry: state' = newX' | (next stream bits & mask).
-    auto step = [&](uint32_t bound) {
-        if (ne2 < bound) {
-            const uint32_t window = __builtin_amdgcn_alignbit(w.y, w.x, abit);
-            const uint32_t eh = e.y, nb = eh & 31u;
-            X8 = e.x | (__builtin_amdgcn_ubfe(window, 0u, nb) << 3);
-            e = *reinterpret_cast<const uint2*>(lds_table + X8);
-            const uint32_t last2 = __umul24((eh >> 8) & 7u, N2) + ne2;   // doubled index of the entry's last symbol
-            abit += nb;
-            w = word_pair(min((abit >> 3) & ~3u, last_word4));
-            // beyond the chunk's end (stream finished inside a run) this hits a ring slot nobody reads
-            *reinterpret_cast<uint16_t*>(ring8 + (last2 & (kRing2 - 1u))) = static_cast<uint16_t>(eh >> 16);
-            ne2 = last2 + N2;
-            if (ne2 >= n2) {                             // stream finished: it must have arrived in state 0
-                bool ok = X8 == 0;
-                if (last2 >= n2) {                       // ended inside the run of empty steps: no bits were read
-                    ok = (last2 - N2 < n2) && (eh & 0x8000u);
-                    abit -= nb;
-                }
-                if (!ok) err |= ANSZP_ST_BAD_STATE;
-            }
-        }
-    };
-
-    // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.
-    auto flush_ready = [&]() {
-        if (flushed2 + kBatch2 <= n2 && __ballot(ne2 < flushed2 + kBatch2) == 0) {
-            uint4 codes[kBatch];
-            uint4* slot = reinterpret_cast<uint4*>(ring8 + ((flushed2 & (kRing2 - 1u)) + lane * 16u));
-#pragma unroll
-            for (uint32_t k = 0; k < kBatch; ++k) codes[k] = slot[k * (kSlab2 / 16u)];
-#pragma unroll
-            for (uint32_t k = 0; k < kBatch; ++k) slot[k * (kSlab2 / 16u)] = make_uint4(bg2, bg2, bg2, bg2);
-            const uint32_t first = (flushed2 >> 1) + lane * 8u;
-#pragma unroll
-            for (uint32_t k = 0; k < kBatch; ++k)
-                Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + k * kSlab,
-                                                  layer_elem0 + first + k * kSlab, codes[k]);
-            flushed2 += kBatch2;
-        }
-    };
-
-    // Bulk phase: blocks of 8 look-ups with no per-step checks.  A lane joins a block only if even
-    // 8 full-length entries keep it inside its stream and inside the ring, so nothing can finish
-    // or overrun in the middle of a block.  The block is hand-scheduled because a lone wavefront
-    // issues one instruction every 5-8 cycles: what a look-up costs is its instruction count plus
-    // the part of the LDS round trip it cannot cover.  At the start of a block a lane loads four
-    // payload words (128 bits, at least 97 of them ahead of its bit position: 8 look-ups read at
-    // most 96) and shifts them down so that the stream continues at bit 0 of w0.  Per look-up:
-    //   X8   = e.lo | (bfe(w0, 0, nb) << 3);  e' = table[X8]        Sec. II-A: newX' + bits, issued first
-    //   w0..w3 >>= nb (funnel shift);  sum += e.hi                   low byte of sum = bits read so far
-    //   last = ((e.hi >> 8) & 7) * 2N + ne2;  ring[last & mask] = e.hi >> 16;  ne2 = last + 2N
-    // Blocks of 8 look-ups run first; when no lane can take one any more (streams within 64
+    // Block phase: blocks of 8 look-ups with no per-step checks.  A lane joins a block only if even
+    // 8 full-length entries keep it inside its stream and inside the ring (whose room follows from
+    // what the storing wavefront has stored), so nothing can finish or overrun in the middle of a block.
+    // The block is hand-scheduled: a lone wavefront issues one instruction every 5-8 cycles, and
+    // what a look-up costs is the LDS round trip plus the instructions between its arrival and the
+    // next read.  This wavefront therefore only walks the automaton and logs the entries it passes;
+    // the expanding wavefront turns them into symbols.  At the start of a block every lane loads four payload
+    // words (128 bits, at least 97 of them ahead of its bit position: 8 look-ups use at most 8 * 12
+    // and peek one more) and shifts them down so that the stream continues at bit 0 of w0; r is w0
+    // bit-reversed, so the first bit read is on top.  Per look-up, for an entry e with T bits:
+    //   index' = base(e) + (r >> (31 - T));  e' = table[index']       Sec. II-A: newX' + bits, plus the peeked bit
+    //   log[k] = e;  w0..w3 >>= T (funnel shift);  r = bitrev(w0)
+    //   sum += e (low byte: 31 - T per look-up);  ne += (c(e) - 1) * N
+    // A block ends by publishing the lanes that took part and the new count of logged blocks,
+    // reloading every lane's four words and recomputing who may join the next block from the words
+    // the other wavefronts publish (read at the start of the block, so their latency is hidden).
+    // Blocks of 8 look-ups run first; when no lane can take one any more (streams within 32
     // symbols of their end), blocks of 4 and then of 2 take over, and only the last few symbols
     // of each stream go through the checked step below.
     {
-        uint32_t e_lo = e.x, e_hi = e.y;
-#define ANSZP_STEP(EA0, EA1, EB)                                                       \
+        uint32_t e = lds_table[X4 >> 2];
+        const uint32_t lane_log = kLogOff + lane * 4u;
+#define ANSZP_LOOKUP(EA, EB, K)                                                         \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
-        "v_bfe_u32 v52, v44, 0, " EA1 "\n"                                             \
-        "v_lshl_or_b32 v52, v52, 3, " EA0 "\n"                                         \
-        "ds_read_b64 " EB ", v52 offset:%[table]\n"                                    \
-        "v_alignbit_b32 v44, v45, v44, " EA1 "\n"                                      \
-        "v_alignbit_b32 v45, v46, v45, " EA1 "\n"                                      \
-        "v_alignbit_b32 v46, v47, v46, " EA1 "\n"                                      \
-        "v_lshrrev_b32 v47, " EA1 ", v47\n"                                            \
-        "v_bfe_u32 v55, " EA1 ", 8, 3\n"                                               \
-        "v_add_u32 v57, v57, " EA1 "\n"                                                \
-        "v_mad_u32_u24 v55, v55, %[n2s], v50\n"                                        \
-        "v_and_b32 v56, %[rmask], v55\n"                                               \
-        "v_add_u32 v50, %[n2s], v55\n"                                                 \
-        "ds_write_b16_d16_hi v56, " EA1 " offset:%[ring]\n"
-#define ANSZP_STEP_AB ANSZP_STEP("v40", "v41", "v[42:43]")
-#define ANSZP_STEP_BA ANSZP_STEP("v42", "v43", "v[40:41]")
+        "v_lshrrev_b32 v36, " EA ", v33\n"                                             \
+        "v_bfe_i32 v37, " EA ", 18, 14\n"                                              \
+        "v_add_lshl_u32 v36, v36, v37, 2\n"                                            \
+        "ds_read_b32 " EB ", v36 offset:%[table]\n"                                    \
+        "ds_write_b32 v42, " EA " offset:" K "*256\n"                                  \
+        "v_not_b32 v35, " EA "\n"                                                      \
+        "v_bfe_u32 v39, " EA ", 16, 2\n"                                               \
+        "v_alignbit_b32 v28, v29, v28, v35\n"                                          \
+        "v_alignbit_b32 v29, v30, v29, v35\n"                                          \
+        "v_alignbit_b32 v30, v31, v30, v35\n"                                          \
+        "v_bfrev_b32 v33, v28\n"                                                       \
+        "v_lshrrev_b32 v31, v35, v31\n"                                                \
+        "v_add_u32 v41, v41, " EA "\n"                                                 \
+        "v_mad_u32_u24 v34, v39, %[nstr], v34\n"
+#define ANSZP_AB(K) ANSZP_LOOKUP("v24", "v25", K)
+#define ANSZP_BA(K) ANSZP_LOOKUP("v25", "v24", K)
 // BODY = all look-ups of a block but the last, which is written out below: it skips the window
-// shift and requests the next block's four words instead.  Blocks have an even number of
-// look-ups, so the entry ends up in v[40:41] again.
+// shift.  Blocks have an even number of look-ups, so the entry ends up in v24 again.
 #define ANSZP_RUN_BLOCKS(STEPS, BODY)                                                                                 \
-        while (n2 > (STEPS) * kMaxMerged * N2) {                                                                      \
-            const uint32_t limit = min(n2, flushed2 + kRing2) - (STEPS) * kMaxMerged * N2;                            \
-            if (__ballot(ne2 < limit) == 0) break;                                                                    \
-            const uint32_t flush_at = (flushed2 + kBatch2 <= n2) ? flushed2 + kBatch2 : 0xFFFFFFFFu;                  \
+        while (!gave_up && n > (STEPS) * kMaxMerged * N) {                                                            \
+            const uint32_t reach = (STEPS) * kMaxMerged * N;                                                          \
+            const uint32_t near_end = n - reach;                                                                      \
+            if (__ballot(ne < near_end) == 0) break;                                                                  \
+            const uint32_t stored = uniform(ctl[kStored]), expanded = uniform(ctl[kExpanded]);                        \
+            const uint32_t limit = min(near_end, stored + (kRingElems - reach));                                      \
+            if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) { /* ring or log full: wait */           \
+                if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;                                    \
+                __builtin_amdgcn_s_sleep(1);                                                                          \
+                continue;                                                                                             \
+            }                                                                                                         \
+            spins = 0;                                                                                                \
+            uint32_t logged_v = logged;                                                                               \
             asm volatile(                                                                                             \
-                "v_mov_b32 v40, %[elo]\n v_mov_b32 v41, %[ehi]\n v_mov_b32 v48, %[ab]\n v_mov_b32 v50, %[ne]\n"       \
-                "v_cmp_gt_u32 vcc, %[lim], v50\n"                                                                     \
-                "s_and_saveexec_b64 s[40:41], vcc\n" /* lanes that can run a whole block */                           \
-                "v_lshrrev_b32 v54, 3, v48\n"                                                                         \
-                "v_and_b32 v54, 0x1ffffffc, v54\n"                                                                    \
-                "v_min_u32 v54, %[lastw], v54\n"                                                                      \
-                "ds_read2_b32 v[44:45], v54 offset1:1\n"                                                              \
-                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"                                                    \
+                "v_mov_b32 v24, %[e]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v34, %[ne]\n v_mov_b32 v47, %[x4]\n"          \
+                "v_mov_b32 v43, 0\n v_mov_b32 v46, " #STEPS "\n"                                                      \
+                "v_readfirstlane_b32 s44, %[logged]\n"                                                                        \
+                "s_mov_b64 s[40:41], exec\n"                                                                          \
+                "v_cmp_gt_u32 vcc, %[lim], v34\n"                                                                     \
+                "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
+                "v_and_b32 v38, 0x1ffffffc, v38\n"                                                                    \
+                "v_min_u32 v38, %[lastw], v38\n"                                                                      \
+                "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
+                "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
+                "s_and_b64 exec, s[40:41], vcc\n"      /* lanes that can run a whole block (some can) */              \
                 "1:\n"                                                                                                \
-                "v_mov_b32 v57, 0\n"                                                                                  \
+                "s_and_b32 s46, s44, %[slotmask]\n"                                                                   \
+                "s_lshl_b32 s47, s46, %[slotshift]\n"                                                                 \
+                "v_add_u32 v42, s47, %[lanelog]\n"     /* this lane's column in the block's log slot */               \
+                "s_lshl_b32 s46, s46, 4\n"                                                                            \
+                "v_mov_b32 v40, s46\n"                 /* offset of the block's header */                             \
+                "v_mov_b32 v41, 0\n"                                                                                  \
                 "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "v_alignbit_b32 v44, v45, v44, v48\n"                                                                 \
-                "v_alignbit_b32 v45, v46, v45, v48\n"                                                                 \
-                "v_alignbit_b32 v46, v47, v46, v48\n"                                                                 \
-                "v_lshrrev_b32 v47, v48, v47\n"                                                                       \
+                "ds_read_b64 v[48:49], v43 offset:%[ctlw1]\n" /* blocks expanded, elements stored */                  \
+                "v_alignbit_b32 v28, v29, v28, v32\n"                                                                 \
+                "v_alignbit_b32 v29, v30, v29, v32\n"                                                                 \
+                "v_alignbit_b32 v30, v31, v30, v32\n"                                                                 \
+                "v_lshrrev_b32 v31, v32, v31\n"                                                                       \
+                "v_bfrev_b32 v33, v28\n"                                                                              \
                 BODY                                                                                                  \
                 "s_waitcnt lgkmcnt(1)\n"                                                                              \
-                "v_bfe_u32 v52, v44, 0, v43\n"                                                                        \
-                "v_lshl_or_b32 v52, v52, 3, v42\n"                                                                    \
-                "ds_read_b64 v[40:41], v52 offset:%[table]\n"                                                         \
-                "v_add_u32 v57, v57, v43\n"                                                                           \
-                "v_bfe_u32 v55, v43, 8, 3\n"                                                                          \
-                "v_and_b32 v57, 0xff, v57\n"                                                                          \
-                "v_mad_u32_u24 v55, v55, %[n2s], v50\n"                                                               \
-                "v_add_u32 v48, v48, v57\n" /* bit position after the block */                                        \
-                "v_and_b32 v56, %[rmask], v55\n"                                                                      \
-                "v_lshrrev_b32 v54, 3, v48\n"                                                                         \
-                "v_add_u32 v50, %[n2s], v55\n"                                                                        \
-                "v_and_b32 v54, 0x1ffffffc, v54\n"                                                                    \
-                "ds_write_b16_d16_hi v56, v43 offset:%[ring]\n"                                                       \
-                "v_min_u32 v54, %[lastw], v54\n"                                                                      \
-                "v_cmp_gt_u32 s[42:43], %[fat], v50\n" /* lanes of this block still inside the next slabs */          \
-                "v_cmp_gt_u32 vcc, %[lim], v50\n"      /* lanes that can run another block */                         \
-                "ds_read2_b32 v[44:45], v54 offset1:1\n"                                                              \
-                "ds_read2_b32 v[46:47], v54 offset0:2 offset1:3\n"                                                    \
-                "s_cmp_eq_u64 s[42:43], 0\n"                                                                          \
-                "s_cbranch_scc1 2f\n"                  /* none: slabs may be ready to leave the ring */               \
-                "s_and_b64 exec, exec, vcc\n"                                                                         \
+                "v_lshrrev_b32 v36, v25, v33\n"                                                                       \
+                "v_bfe_i32 v37, v25, 18, 14\n"                                                                        \
+                "v_add_lshl_u32 v36, v36, v37, 2\n"                                                                   \
+                "ds_read_b32 v24, v36 offset:%[table]\n"                                                              \
+                "ds_write_b32 v42, v25 offset:(" #STEPS "-1)*256\n"                                                   \
+                "v_bfe_u32 v39, v25, 16, 2\n"                                                                         \
+                "v_add_u32 v41, v41, v25\n"                                                                           \
+                "v_mad_u32_u24 v34, v39, %[nstr], v34\n"                                                               \
+                "v_mov_b32 v47, v36\n"                                                                                \
+                "v_and_b32 v41, 0xff, v41\n"                                                                          \
+                "v_add_u32 v34, %[snstr], v34\n"         /* one symbol per look-up on top of the runs */                \
+                "v_sub_u32 v41, 31*" #STEPS ", v41\n"                                                                 \
+                "v_mov_b32 v44, exec_lo\n"                                                                            \
+                "v_mov_b32 v45, exec_hi\n"                                                                            \
+                "v_add_u32 v32, v32, v41\n"            /* bit position after the block */                             \
+                "ds_write_b64 v40, v[44:45] offset:%[hdr]\n"                                                          \
+                "ds_write_b32 v40, v46 offset:%[hdr]+8\n"                                                             \
+                "s_add_u32 s44, s44, 1\n"                                                                             \
+                "v_mov_b32 v44, s44\n"                                                                                \
+                "v_readfirstlane_b32 s46, v48\n"       /* blocks expanded when this block began */                    \
+                "v_readfirstlane_b32 s47, v49\n"       /* 2 * elements stored when this block began */                \
+                "ds_write_b32 v43, v44 offset:%[ctlw0]\n" /* publish the block */                                     \
+                "s_mov_b64 exec, s[40:41]\n"           /* every lane reloads its words */                             \
+                "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
+                "v_and_b32 v38, 0x1ffffffc, v38\n"                                                                    \
+                "v_min_u32 v38, %[lastw], v38\n"                                                                      \
+                "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
+                "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
+                "s_add_u32 s47, s47, %[room]\n"                                                                       \
+                "s_min_u32 s47, s47, %[nearend]\n"                                                                    \
+                "v_cmp_gt_u32 vcc, s47, v34\n"         /* lanes that can run another block */                         \
+                "s_sub_u32 s46, s44, s46\n"                                                                           \
+                "s_cmp_ge_u32 s46, %[slots]\n"         /* the next log slot may still be in use */                    \
+                "s_cbranch_scc1 2f\n"                                                                                 \
+                "s_and_b64 exec, s[40:41], vcc\n"                                                                     \
                 "s_cbranch_scc1 1b\n"                                                                                 \
                 "2:\n"                                                                                                \
                 "s_mov_b64 exec, s[40:41]\n"                                                                          \
                 "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "v_mov_b32 %[elo], v40\n v_mov_b32 %[ehi], v41\n v_mov_b32 %[ab], v48\n v_mov_b32 %[ne], v50\n"       \
-                : [elo] "+v"(e_lo), [ehi] "+v"(e_hi), [ab] "+v"(abit), [ne] "+v"(ne2)                                 \
-                : [lim] "s"(limit), [fat] "s"(flush_at), [n2s] "s"(N2), [lastw] "s"(last_word4),                      \
-                  [table] "n"(kWordsBytes), [ring] "n"(kWordsBytes + kTableBytes), [rmask] "n"(kRing2 - 1u)           \
-                : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "v40", "v41", "v42", "v43", "v44", "v45",       \
-                  "v46", "v47", "v48", "v50", "v52", "v54", "v55", "v56", "v57");                                     \
-            flush_ready();                                                                                            \
+                "v_mov_b32 %[e], v24\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v34\n v_mov_b32 %[x4], v47\n"          \
+                "v_mov_b32 %[logged], s44\n"                                                                          \
+                : [e] "+v"(e), [ab] "+v"(abit), [ne] "+v"(ne), [x4] "+v"(X4), [logged] "+v"(logged_v)                 \
+                : [lim] "s"(uniform(limit)), [nearend] "s"(uniform(near_end)), [room] "s"(uniform(kRingElems - reach)),\
+                  [nstr] "s"(uniform(N)), [snstr] "s"(uniform((STEPS) * N)), [lastw] "s"(uniform(last_word4)),        \
+                  [lanelog] "v"(lane_log),                                                                            \
+                  [table] "n"(kTableOff), [hdr] "n"(kHdrOff), [ctlw0] "n"(kCtlOff), [ctlw1] "n"(kCtlOff + 8u),        \
+                  [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [slotshift] "n"(11)                         \
+                : "memory", "vcc", "scc", "s40", "s41", "s44", "s46", "s47", "v24", "v25", "v28", "v29", "v30",       \
+                  "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44",   \
+                  "v45", "v46", "v47", "v48", "v49");                                                                 \
+            logged = uniform(logged_v);                                                                               \
         }
-        ANSZP_RUN_BLOCKS(8u, ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB)
-        ANSZP_RUN_BLOCKS(4u, ANSZP_STEP_AB ANSZP_STEP_BA ANSZP_STEP_AB)
-        ANSZP_RUN_BLOCKS(2u, ANSZP_STEP_AB)
+        uint32_t spins = 0;
+        ANSZP_RUN_BLOCKS(8, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2") ANSZP_BA("3") ANSZP_AB("4") ANSZP_BA("5") ANSZP_AB("6"))
+        ANSZP_RUN_BLOCKS(4, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2"))
+        ANSZP_RUN_BLOCKS(2, ANSZP_AB("0"))
 #undef ANSZP_RUN_BLOCKS
-#undef ANSZP_STEP_AB
-#undef ANSZP_STEP_BA
-#undef ANSZP_STEP
-        e = make_uint2(e_lo, e_hi);
-        w = word_pair(min((abit >> 3) & ~3u, last_word4));
+#undef ANSZP_AB
+#undef ANSZP_BA
+#undef ANSZP_LOOKUP
+        // the block phase is over: the look-ahead entries may be replaced, the expanding and storing
+        // wavefronts finish what is logged; then this wavefront owns the ring
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) ctl[kOver] = 1u;
+        for (spins = 0; !gave_up && (!uniform(ctl[kStoreDone]) || !uniform(ctl[kTriplesLo]) || !uniform(ctl[kTriplesHi])); ++spins) {
+            if (uniform(ctl[kGaveUp]) || spins > kSpinLimit) gave_up = true;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (gave_up) {
+            if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+            return;
+        }
     }
 
-    // Careful phase: every look-up checks the end of the stream and the room in the ring.
+    // Careful phase (Sec. II-A, one step per symbol): every step checks the end of the stream and
+    // the room in the ring.
+    uint32_t X = X4 >> 3;                                // the peeked bit is dropped: it has not been read
+    uint32_t stored = uniform(ctl[kStored]);
+    auto step = [&](uint32_t bound) {
+        if (ne < bound) {
+            const uint32_t t = lds_table[X];
+            const uint32_t nb = (t >> 16) & 0xFFu;
+            const uint32_t* q = reinterpret_cast<const uint32_t*>(lds + min((abit >> 3) & ~3u, last_word4));
+            const uint32_t window = __builtin_amdgcn_alignbit(q[1], q[0], abit);
+            const uint32_t bits = nb ? __brev(window) >> (32u - nb) : 0u;    // first bit read is the top bit
+            X = ((t & 0xFFFFu) + bits) & (L - 1u);
+            ring8[ne & kRingMask] = static_cast<uint8_t>(t >> 24);
+            abit += nb;
+            ne += N;
+            if (ne >= n && X != 0) err |= ANSZP_ST_BAD_STATE;     // stream finished: it must have arrived in state 0
+        }
+    };
     for (;;) {
-        if (__ballot(ne2 < n2) == 0) break;
-        const uint32_t bound = min(n2, flushed2 + kRing2 - kMaxMerged * N2 + 1u);
+        if (__ballot(ne < n) == 0) break;
+        const uint32_t bound = min(n, stored + kRingElems);
         step(bound);
         step(bound);
         step(bound);
         step(bound);
-        flush_ready();
+        store_ready(ne, stored);
     }
     // every stream is finished: the rest of the ring is final
-    uint32_t flushed = flushed2 >> 1;
-    while (flushed + kSlab <= n) {
-        const uint4 codes = *reinterpret_cast<const uint4*>(lds_ring + ((flushed & (kRingElems - 1u)) + lane * 8u));
-        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + flushed + lane * 8u, layer_elem0 + flushed + lane * 8u, codes);
-        flushed += kSlab;
-    }
-    for (uint32_t j = flushed + lane; j < n; j += kWave)
-        Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, lds_ring[j & (kRingElems - 1u)]);
+    while (stored + kSlab <= n) { store_slabs(stored, std::integral_constant<uint32_t, 1u>{}); stored += kSlab; }
+    for (uint32_t j = stored + lane; j < n; j += kWave)
+        Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & kRingMask], lds_lut);
 
     if (lane < N) {
         const uint32_t bits_read = abit - (first_word << 5);
@@ -569,6 +818,19 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* sym, uint64
         }
         store_weight<OUT>(out, i, sym[i], lay.zero_point, scale);
     }
+}
+
+// Compute units of the current device (queried once per device).
+uint32_t device_cus() {
+    static uint32_t cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256u;
+    if (!cached[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = static_cast<uint32_t>(n);
+    }
+    return cached[dev];
 }
 
 template <int OUT>
@@ -595,6 +857,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words;
     p.n_scales = a->scales ? a->n_scales : 0; p.out_elems = a->out_elems;
     p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
+    p.n_cus = device_cus();
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
     // chunks whose compressed words cannot fit the merged kernel's LDS window would all take its
@@ -618,7 +881,7 @@ int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
     if (!freqs_host || !tables_dev) return ANSZP_E_NULL;
     if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
     if (reinterpret_cast<uintptr_t>(tables_dev) & 15) return ANSZP_E_RANGE;
-    const size_t entries = size_t(n_tables) << (table_log + 1);
+    const size_t entries = size_t(n_tables) << (table_log + 2);
     uint32_t* staging = nullptr;
     if (hipHostMalloc(reinterpret_cast<void**>(&staging), entries * sizeof(uint32_t), hipHostMallocDefault) != hipSuccess)
         return ANSZP_E_NOMEM;

@@ -15,7 +15,7 @@
 
 namespace {
 
-constexpr int kMaxMerged = 8;   // symbols one merged entry may emit
+constexpr uint32_t kMaxMerged = 4;   // symbols one look-ahead entry may emit
 
 bool freqs_ok(const uint32_t* f, int table_log) {
     uint64_t total = 0;
@@ -77,30 +77,60 @@ void build_step_table(const uint32_t* f, int table_log, StepTable& t) {
     }
 }
 
+// One table = 4L words: [0, 2L) look-ahead entries indexed by 2X + b (b = the next stream bit,
+// peeked, not yet consumed), [2L, 3L) the paper's triple per state, [3L, 4L) zero.
+//
+// A look-ahead entry is the same automaton with up to kMaxMerged steps merged into one look-up:
+// starting in state X with next bit b it emits c-1 copies of the dominant symbol (the symbol with
+// f > L/2: empty-label transitions, and at most one of its 1-bit transitions, which consumes b)
+// and then one more symbol, having consumed T <= 12 stream bits in all.  With v = the next T+1
+// stream bits read most significant first (so v ends in the new peeked bit), the next index is
+// base + v.
 void build_one_table(const uint32_t* f, int table_log, uint32_t* out) {
     const uint32_t L = 1u << table_log;
     StepTable t;
     build_step_table(f, table_log, t);
-    bool dominant = false;
+    int dominant = -1;
     for (int s = 0; s < ANSZP_ALPHABET; ++s)
-        if (f[s] > L / 2 && f[s] < L) dominant = true;
+        if (f[s] > L / 2) dominant = s;
     for (uint32_t X = 0; X < L; ++X) {
-        const uint32_t step = uint32_t(t.newX[X]) | (uint32_t(t.nb[X]) << 16) | (uint32_t(t.sym[X]) << 24);
-        // merged entry: follow empty-label transitions (they all carry the dominant symbol)
-        uint32_t Y = X, hops = 0;
-        if (dominant)
-            while (hops < kMaxMerged && t.nb[Y] == 0) { Y = t.newX[Y]; ++hops; }
-        uint32_t count, last_sym, last_nb, last_newX, end_flag;
-        if (hops == kMaxMerged) {            // eight empty transitions, continue from Y
-            count = kMaxMerged; last_sym = t.sym[X]; last_nb = 0; last_newX = Y; end_flag = 0;
-        } else {                             // hops empty transitions, then the one at Y
-            count = hops + 1; last_sym = t.sym[Y]; last_nb = t.nb[Y]; last_newX = t.newX[Y];
-            end_flag = (Y == 0) ? 1u : 0u;
+        out[2 * L + X] = uint32_t(t.newX[X]) | (uint32_t(t.nb[X]) << 16) | (uint32_t(t.sym[X]) << 24);
+        out[3 * L + X] = 0;
+        for (uint32_t b = 0; b < 2; ++b) {
+            uint32_t Y = X, count = 0, bits = 0;
+            bool took_b = false;
+            uint32_t saved_Y = 0, saved_count = 0;
+            int32_t base = 0;
+            uint32_t last_sym = 0;
+            for (;;) {
+                const uint32_t n = t.nb[Y];
+                const bool room = count + 1 < kMaxMerged;          // another symbol may follow this one
+                if (n == 0 && room) { ++count; Y = t.newX[Y]; continue; }
+                if (n == 1 && room && !took_b && int(t.sym[Y]) == dominant) {
+                    saved_Y = Y; saved_count = count;
+                    took_b = true; ++count; Y = t.newX[Y] | b;
+                    continue;
+                }
+                if (took_b && 1 + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {   // too many bits for one look-up: stop at the 1-bit step
+                    Y = saved_Y; count = saved_count; took_b = false;
+                    bits = 1; base = int32_t(2 * t.newX[Y]); last_sym = t.sym[Y];
+                    break;
+                }
+                bits = (took_b ? 1 : 0) + n;
+                base = int32_t(2 * t.newX[Y]) - (took_b ? int32_t(b << (n + 1)) : 0);
+                last_sym = t.sym[Y];
+                break;
+            }
+            out[2 * X + b] = (31u - bits) | (last_sym << 8) | (count << 16) | (uint32_t(base) << 18);
         }
-        const uint32_t merged = (count - 1) | (last_newX << 3) | (end_flag << 15) | (last_sym << 16) | (last_nb << 24);
-        out[X] = step;            // first half of the table: the paper's triple
-        out[L + X] = merged;      // second half: merged steps
     }
+}
+
+// The low `n` bits of v in reverse order (n <= 16).
+uint32_t reversed_bits(uint32_t v, uint32_t n) {
+    uint32_t r = 0;
+    for (uint32_t i = 0; i < n; ++i) r |= ((v >> i) & 1u) << (n - 1 - i);
+    return r;
 }
 
 // Writes bit groups from the end of a scratch bit array towards its start (encoding runs over
@@ -204,7 +234,7 @@ int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, 
         if (!freqs_ok(freqs + size_t(t) * ANSZP_ALPHABET, table_log)) return ANSZP_E_FREQ;
     try {
         for (int t = 0; t < n_tables; ++t)
-            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << (table_log + 1)));
+            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << (table_log + 2)));
     } catch (const std::bad_alloc&) {
         return ANSZP_E_NOMEM;
     }
@@ -263,7 +293,7 @@ int anszp_pack_layer(const uint8_t* symbols, uint64_t n_symbols, const uint32_t*
                     if (!fs) return ANSZP_E_SYMBOL;
                     uint32_t drop = 0;
                     while ((x >> drop) >= 2 * fs) ++drop;      // bring x into [f_s, 2 f_s)
-                    bits.put(x & ((1u << drop) - 1u), drop);
+                    bits.put(reversed_bits(x & ((1u << drop) - 1u), drop), drop);   // first bit read = top bit
                     x = enc.L + enc.states[enc.first[s] + (x >> drop) - fs];
                 }
                 const uint64_t nw = (bits.bit_count() + 31) / 32;

@@ -73,43 +73,64 @@ def test_tables_equal_oracle_tables(orc, R):
         assert np.array_equal(f["sym"], sym) and np.array_equal(f["nb"], nb) and np.array_equal(f["newX"], newX)
 
 
-@pytest.mark.parametrize("R", [3, 8, 12])
-def test_merged_entries_follow_the_step_automaton(orc, R):
-    """The second half of an entry is the same automaton with up to 8 steps merged: replaying
-    single steps from the oracle's table must give the same symbols, bit count and next state."""
+def _lookahead_decode(t, words, x0, n, dominant):
+    """Decode n symbols with the look-ahead entries only (pure Python), returning symbols and bits consumed
+    at the last entry boundary not after the stream's end."""
+    bits = int.from_bytes(np.asarray(words, dtype=np.uint32).tobytes(), "little")
+
+    def peek(pos, k):                                   # next k stream bits, first bit on top
+        v = 0
+        for i in range(k):
+            v = (v << 1) | ((bits >> (pos + i)) & 1)
+        return v
+
+    pos, out = 0, []
+    idx = 2 * x0 + peek(0, 1)
+    while len(out) < n:
+        T, c = int(t["la_bits"][idx]), int(t["la_count"][idx])
+        out.extend([dominant] * (c - 1))
+        out.append(int(t["la_sym"][idx]))
+        idx = int(t["la_base"][idx]) + peek(pos, T + 1)
+        pos += T
+        assert 0 <= idx < len(t["la_bits"])
+    return np.array(out[:n], dtype=np.uint8), len(out), pos, idx
+
+
+@pytest.mark.parametrize("R", [2, 3, 6, 8, 11, 12])
+def test_lookahead_entries_decode_what_the_oracle_encodes(orc, R):
+    """The look-ahead half of a table is the paper's automaton with steps merged: decoding oracle-encoded
+    streams with it alone must give back the symbols, read exactly the stream's bits and end in state 0."""
     L = 1 << R
-    rng = np.random.default_rng(R)
-    for p0 in (0.55, 0.75, 0.9, 0.97, 0.999):
-        f = np.zeros(256, dtype=np.uint32)
-        f[7] = max(L // 2 + 1, min(L - 2, int(p0 * L)))
-        rest = L - int(f[7])
-        others = rng.multinomial(rest, np.ones(5) / 5) if rest >= 5 else np.array([rest, 0, 0, 0, 0])
-        f[20:25] = others
-        if f[7] <= L // 2:
-            continue
-        sym, nb, newX = orc.decode_table(f, R)
-        m = B.split_table(B.build_tables_host(f[None, :], R)[0])
-        assert int(m["count"].max()) <= 8
-        for X in range(L):
-            Y, emitted = X, []
-            c = int(m["count"][X])
-            for _ in range(c - 1):
-                assert nb[Y] == 0 and sym[Y] == 7
-                emitted.append(int(sym[Y]))
-                Y = int(newX[Y])
-            if c == 8 and nb[Y] == 0:                      # capped run: last symbol is an empty step too
-                assert m["m_nb"][X] == 0 and m["m_sym"][X] == 7 and m["m_newX"][X] == newX[Y]
-                assert m["m_end"][X] == 0
-            else:
-                assert c == 8 or nb[Y] > 0                 # runs are followed to their end
-                assert m["m_sym"][X] == sym[Y] and m["m_nb"][X] == nb[Y] and m["m_newX"][X] == newX[Y]
-                assert m["m_end"][X] == (1 if Y == 0 else 0)
-    # no dominant symbol: merged entry is the plain step
-    f = _random_freqs(np.random.default_rng(1), R, 6)
-    if f.max() <= L // 2:
-        m = B.split_table(B.build_tables_host(f[None, :], R)[0])
-        assert np.all(m["count"] == 1) and np.array_equal(m["m_newX"], m["newX"])
-        assert np.array_equal(m["m_nb"], m["nb"]) and np.array_equal(m["m_sym"], m["sym"])
+    rng = np.random.default_rng(40 + R)
+    cases = []
+    for p0 in (0.3, 0.55, 0.7, 0.76, 0.9, 0.97):
+        A = int(rng.integers(2, min(L, 40) + 1))
+        pmf = W.peaked_geometric_pmf(A, A // 2, p0)
+        cases.append(pmf)
+    cases.append(np.eye(1, 5, 2)[0])                    # single symbol
+    for pmf in cases:
+        n = 3000
+        sym = W.sample_symbols(pmf, n, int(rng.integers(1 << 30)))
+        f = orc.normalize(np.bincount(sym, minlength=256), R)
+        t = B.split_table(B.build_tables_host(f[None, :], R)[0])
+        assert np.all(t["la_pad"] == 0) and np.all(t["tail"] == 0)
+        assert int(t["la_bits"].max()) <= 12 and int(t["la_count"].max()) <= 4
+        dominant = int(np.argmax(f)) if f.max() > L // 2 else 255
+        for length in (n, 1, 2, 7, 100):
+            words, x0 = orc.encode_stream(sym[:length], f, R)
+            out, emitted, pos, idx = _lookahead_decode(t, words, x0, length, dominant)
+            assert np.array_equal(out, sym[:length])
+            if emitted == length:                       # stream ended on an entry boundary
+                _, _, total = orc.decode_stream(words, x0, length, f, R)
+                assert pos == total and idx >> 1 == 0
+        # entries with and without look-ahead agree when there is no dominant symbol
+        if f.max() <= L // 2:
+            assert np.all(t["la_count"] == 1)
+            la = B.build_tables_host(f[None, :], R)[0][:2 * L].reshape(L, 2)
+            assert np.array_equal(la[:, 0], la[:, 1])
+            assert np.array_equal(t["la_bits"].reshape(L, 2)[:, 0], t["nb"])
+            assert np.array_equal(t["la_sym"].reshape(L, 2)[:, 0], t["sym"])
+            assert np.array_equal(t["la_base"].reshape(L, 2)[:, 0], 2 * t["newX"].astype(np.int32))
 
 
 def test_normalize_equals_oracle(orc):
@@ -153,7 +174,7 @@ def test_host_error_codes():
     lib = B.lib()
     f = np.zeros(256, dtype=np.uint32)
     f[0] = 255
-    t = np.zeros(256, dtype=np.uint64)
+    t = np.zeros(4 * 256, dtype=np.uint32)
     assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == -3          # sum != 2^R
     f[0] = 256
     assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == 0
