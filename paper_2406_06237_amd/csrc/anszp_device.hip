@@ -31,7 +31,7 @@ constexpr uint32_t kRingElems = 16u * 1024u;   // LDS ring of decoded symbols (o
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
 constexpr uint32_t kPayloadWords = 3584u;      // LDS window for one chunk's compressed words
 constexpr uint32_t kMaxMerged = 4u;             // symbols one look-ahead entry can stand for
-constexpr uint32_t kLogSlots = 4u;              // blocks of look-ups in flight between two wavefronts
+constexpr uint32_t kLogSlots = 8u;              // blocks of look-ups in flight between two wavefronts
 constexpr uint32_t kLogSlotBytes = 8u * kWave * 4u;
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
@@ -270,8 +270,8 @@ void decode_merged(DecodeParams p) {
     // immediate offset lies below 64 KiB.
     constexpr uint32_t kWordsBytes = (kPayloadWords + 8u) * 4u;
     constexpr uint32_t kCtlOff = kWordsBytes;                       // hand-over words, then block headers
-    constexpr uint32_t kHdrOff = kCtlOff + 32u;
-    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 16u;        // per lane: doubled index of the next symbol to expand
+    constexpr uint32_t kHdrOff = kCtlOff + 64u;
+    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 16u;        // per lane: chunk index of the next symbol to expand
     constexpr uint32_t kSimdOff = kProgOff + kWave * 4u;            // SIMD each of the first 8 wavefronts runs on
     constexpr uint32_t kTableOff = kSimdOff + 32u;                  // 2L look-ahead entries, later the L triples
     constexpr uint32_t kLutOff = kTableOff + kTableBytes;           // symbol -> bf16 weight
@@ -285,12 +285,13 @@ void decode_merged(DecodeParams p) {
     uint32_t* const lds_table = reinterpret_cast<uint32_t*>(lds + kTableOff);
     uint16_t* const lds_lut = reinterpret_cast<uint16_t*>(lds + kLutOff);
     uint8_t* const ring8 = lds + kRingOff;
-    // hand-over words: 0 blocks logged by the decoding wavefront | 1 its block phase is over | 2 blocks
-    // expanded | 3 elements stored | 4, 7 lower, upper half of the triples are in LDS | 5 a wait gave up |
-    // 6 the storing wavefront has stored all it can
+    // hand-over words: 0 blocks logged by the decoding wavefront | 1 blocks expanded | 2, 3 first element of
+    // the next slab each storing wavefront will take | 4 the block phase is over | 5 a wait gave up |
+    // 6, 7 a storing wavefront has stored all it can | 8, 9 lower, upper half of the triples are in LDS
     lds_flag_t* const ctl = (lds_flag_t*)(lds + kCtlOff);
     lds_flag_t* const blk_hdr = (lds_flag_t*)(lds + kHdrOff);   // lanes lo, hi, look-ups, -
-    enum { kLogged = 0, kOver = 1, kExpanded = 2, kStored = 3, kTriplesLo = 4, kGaveUp = 5, kStoreDone = 6, kTriplesHi = 7 };
+    enum { kLogged = 0, kExpanded = 1, kStored0 = 2, kStored1 = 3, kOver = 4, kGaveUp = 5, kStoreDone0 = 6, kStoreDone1 = 7,
+           kTriplesLo = 8, kTriplesHi = 9 };
     constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
     constexpr uint32_t kTableLoads = ((2u << ANSZP_MAX_TABLE_LOG) / 4u + kBlock - 1u) / kBlock;   // 16-byte loads per thread
@@ -316,21 +317,56 @@ void decode_merged(DecodeParams p) {
     const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
     const uint32_t quads = min(c.payload_words, kPayloadWords) >> 2;
     const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte row of triples
-    uint4 tv[kTableLoads], wv[kWordLoads];
-    {
-        const uint32_t t_last = (L >> 1) - 1u;
-        const uint32_t w_last = quads ? quads - 1u : 0u;
-        const uint4* wsafe = quads ? wsrc : tsrc;
-#pragma unroll
-        for (uint32_t k = 0; k < kTableLoads; ++k) tv[k] = tsrc[min(tid + k * kBlock, t_last)];
-#pragma unroll
-        for (uint32_t k = 0; k < kWordLoads; ++k) wv[k] = wsafe[min(tid + k * kBlock, w_last)];
-    }
+    // (named values rather than arrays: an array that lives across a barrier is kept in scratch
+    // memory by the compiler)
+    static_assert(kTableLoads == 4u && kWordLoads == 2u, "loads per thread are written out below");
+    const uint32_t t_last = (L >> 1) - 1u;
+    const uint32_t w_last = quads ? quads - 1u : 0u;
+    const uint4* wsafe = quads ? wsrc : tsrc;
+    const uint4 tv0 = tsrc[min(tid, t_last)], tv1 = tsrc[min(tid + kBlock, t_last)];
+    const uint4 tv2 = tsrc[min(tid + 2u * kBlock, t_last)], tv3 = tsrc[min(tid + 3u * kBlock, t_last)];
+    const uint4 wv0 = wsafe[min(tid, w_last)], wv1 = wsafe[min(tid + kBlock, w_last)];
     uint32_t tail = 0;
     if (tid < 8 && (quads << 2) + tid < c.payload_words && c.payload_words <= kPayloadWords)
         tail = p.payload[c.payload_offset + (quads << 2) + tid];
     const uint32_t top = src[3u * L - 1u];               // state L-1 carries the dominant symbol if there is one
     const anszp_layer_t lay = p.layers[c.layer_id];
+    // While those loads are in flight: which wavefront does what, and where each stream's words begin.
+    if (lane == 0 && wave < 8u)                          // HW_ID bits 4..5: the SIMD this wavefront runs on
+        reinterpret_cast<uint32_t*>(lds + kSimdOff)[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
+    __syncthreads();
+    // Six wavefronts stay, each with one task; the others were staging helpers.  A lone wavefront's
+    // speed is set by how often its SIMD lets it issue, so the tasks are spread over the CU's four
+    // SIMDs, and two workgroups that share a CU (workgroups n_cus apart, as a rule) pick different
+    // SIMDs for their decoding wavefronts, which then have a SIMD each to themselves but for a
+    // sleeper:  SIMD 0/1 decode | 2/3 expand | 2 first storer | 3 second storer; the two placing
+    // wavefronts sleep until the end.
+    enum { kDecode = 0, kExpand = 1, kStore0 = 2, kStore1 = 3, kPlaceLo = 4, kPlaceHi = 5, kNoTask = 6 };
+    uint32_t task = kNoTask;
+    {
+        const uint32_t second = (blockIdx.x / max(p.n_cus, 1u)) & 1u;
+        const uint32_t want[6] = {second, 2u + second, 2u, 3u, 1u - second, 3u - second};
+        const uint32_t mine = reinterpret_cast<const uint32_t*>(lds + kSimdOff)[lane & 7u];   // one read, eight answers
+        uint32_t simd[8];
+#pragma unroll
+        for (uint32_t w = 0; w < 8u; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
+        uint32_t taken = 0;
+#pragma unroll
+        for (uint32_t t = 0; t < 6u; ++t) {
+            uint32_t pick = 8u;
+#pragma unroll
+            for (uint32_t w = 0; w < 8u; ++w)
+                if (pick == 8u && !((taken >> w) & 1u) && simd[w] == want[t]) pick = w;
+#pragma unroll
+            for (uint32_t w = 0; w < 8u; ++w)          // no wavefront on that SIMD: any free one
+                if (pick == 8u && !((taken >> w) & 1u)) pick = w;
+            taken |= 1u << pick;
+            if (pick == wave) task = t;
+        }
+    }
+    const uint32_t n_words = hdr >> 16;
+    uint32_t total_words = 0, first_word = 0;
+    if (task == kDecode) first_word = wave_exclusive_sum(n_words, &total_words);
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
     const uint32_t n = c.n_symbols;
     const bool merged_ok = wide && c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
@@ -352,17 +388,18 @@ void decode_merged(DecodeParams p) {
         // end repeat the last row): stores under a per-thread condition would let the compiler move
         // each load down to its store and wait for them one at a time
         uint4* tdst = reinterpret_cast<uint4*>(lds_table);
-#pragma unroll
-        for (uint32_t k = 0; k < kTableLoads; ++k) tdst[min(tid + k * kBlock, (L >> 1) - 1u)] = tv[k];
+        tdst[min(tid, t_last)] = tv0;
+        tdst[min(tid + kBlock, t_last)] = tv1;
+        tdst[min(tid + 2u * kBlock, t_last)] = tv2;
+        tdst[min(tid + 3u * kBlock, t_last)] = tv3;
         uint4* wdst = reinterpret_cast<uint4*>(quads ? lds : lds + kLogOff);     // no whole row of words: anywhere unused
-#pragma unroll
-        for (uint32_t k = 0; k < kWordLoads; ++k) wdst[min(tid + k * kBlock, quads ? quads - 1u : 0u)] = wv[k];
+        wdst[min(tid, w_last)] = wv0;
+        wdst[min(tid + kBlock, w_last)] = wv1;
         if (tid < 8) lds_words[(quads << 2) + tid] = tail;      // tail words, then zeros for clamped reads
         if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
-        if (tid < 8 + kLogSlots * 4u) reinterpret_cast<uint32_t*>(lds + kCtlOff)[tid] = 0u;
+        if (tid < 16 + kLogSlots * 4u) reinterpret_cast<uint32_t*>(lds + kCtlOff)[tid] = 0u;
+        if (tid == 0) reinterpret_cast<uint32_t*>(lds + kCtlOff)[kStored1] = kSlab;   // the second storer's first slab
         if (tid < kWave) reinterpret_cast<uint32_t*>(lds + kProgOff)[tid] = (tid < N) ? tid : n;
-        if (lane == 0 && wave < 8u)                      // HW_ID bits 4..5: the SIMD this wavefront runs on
-            reinterpret_cast<uint32_t*>(lds + kSimdOff)[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
     }
     const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the ring's background: the dominant symbol
     {
@@ -372,34 +409,6 @@ void decode_merged(DecodeParams p) {
             if (tid + k * kBlock < kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(bg4, bg4, bg4, bg4);
     }
     __syncthreads();
-    // Five wavefronts stay, each with one task; the others were staging helpers.  A lone wavefront's
-    // speed is set by how often its SIMD lets it issue, so the busy tasks are spread over the CU's
-    // four SIMDs, and two workgroups that share a CU (workgroups n_cus apart, as a rule) pick
-    // different SIMDs for their decoding wavefronts:  SIMD 0/1 decode | 2/3 expand | 3/2 store;
-    // the two placing wavefronts sleep until the end and go where the other workgroup decodes.
-    enum { kDecode = 0, kExpand = 1, kStore = 2, kPlaceLo = 3, kPlaceHi = 4, kNoTask = 5 };
-    uint32_t task = kNoTask;
-    {
-        const uint32_t second = (blockIdx.x / max(p.n_cus, 1u)) & 1u;
-        const uint32_t want[5] = {second, 2u + second, 3u - second, 1u - second, 1u - second};
-        const uint32_t mine = reinterpret_cast<const uint32_t*>(lds + kSimdOff)[lane & 7u];   // one read, eight answers
-        uint32_t simd[8];
-#pragma unroll
-        for (uint32_t w = 0; w < 8u; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
-        uint32_t taken = 0;
-#pragma unroll
-        for (uint32_t t = 0; t < 5u; ++t) {
-            uint32_t pick = 8u;
-#pragma unroll
-            for (uint32_t w = 0; w < 8u; ++w)
-                if (pick == 8u && !((taken >> w) & 1u) && simd[w] == want[t]) pick = w;
-#pragma unroll
-            for (uint32_t w = 0; w < 8u; ++w)          // no wavefront on that SIMD: any free one
-                if (pick == 8u && !((taken >> w) & 1u)) pick = w;
-            taken |= 1u << pick;
-            if (pick == wave) task = t;
-        }
-    }
     if (task == kNoTask) return;
 
     constexpr uint32_t kRingMask = kRingElems - 1u;
@@ -483,6 +492,7 @@ void decode_merged(DecodeParams p) {
         // blocks and, in the same batch of LDS reads, the header and the entries of the block it
         // waits for: if the count (read first) says the block is there, what was read after it is
         // the block.
+        __builtin_amdgcn_s_setprio(2);                   // ahead of the storing wavefronts it shares a SIMD with
         uint32_t ne = (lane < N) ? lane : n;             // chunk index of this lane's next symbol
         uint32_t expanded = 0, spins = 0;
         for (;;) {
@@ -542,43 +552,48 @@ void decode_merged(DecodeParams p) {
             // publish the lanes' positions, then the count, issued after the ring writes above (LDS keeps
             // a wavefront's accesses in order, so nothing has to be waited for)
             asm volatile("ds_write_b32 %[pa], %[ne]\n"
-                         "ds_write_b32 %[zero], %[ex] offset:%[ctlw2]\n"
+                         "ds_write_b32 %[zero], %[ex] offset:%[ctlw1]\n"
                          :: [pa] "v"(kProgOff + lane * 4u), [ne] "v"(ne), [zero] "v"(0u), [ex] "v"(expanded),
-                            [ctlw2] "n"(kCtlOff + 8u)
+                            [ctlw1] "n"(kCtlOff + 4u)
                          : "memory");
         }
         return;
     }
 
-    if (task == kStore) {
-        // ---- storing wavefront: move finished slabs of the ring to global memory
-        uint32_t stored = 0, spins = 0;
+    if (task == kStore0 || task == kStore1) {
+        // ---- storing wavefronts: move finished slabs of the ring to global memory; one takes the
+        // even slabs, the other the odd ones
+        const uint32_t which = task - kStore0;
+        uint32_t mine = which * kSlab, spins = 0;        // first element of the next slab this one takes
         for (;;) {
             uint32_t over_v, logged_v, expanded_v, next;
             asm volatile(                                // the flag first, the positions last
-                "ds_read_b32 %[ov], %[zero] offset:%[ctlw1]\n"
+                "ds_read_b32 %[ov], %[zero] offset:%[ctlw4]\n"
                 "ds_read_b32 %[lg], %[zero] offset:%[ctlw0]\n"
-                "ds_read_b32 %[ex], %[zero] offset:%[ctlw2]\n"
+                "ds_read_b32 %[ex], %[zero] offset:%[ctlw1]\n"
                 "ds_read_b32 %[nx], %[pa]\n"
                 "s_waitcnt lgkmcnt(0)\n"
                 : [ov] "=&v"(over_v), [lg] "=&v"(logged_v), [ex] "=&v"(expanded_v), [nx] "=&v"(next)
                 : [zero] "v"(0u), [pa] "v"(kProgOff + lane * 4u), [ctlw0] "n"(kCtlOff), [ctlw1] "n"(kCtlOff + 4u),
-                  [ctlw2] "n"(kCtlOff + 8u)
+                  [ctlw4] "n"(kCtlOff + 16u)
                 : "memory");
             // everything logged was expanded before the positions were read: no more will come
             const bool last_pass = uniform(over_v) && uniform(logged_v) == uniform(expanded_v);
-            const uint32_t before = stored;
-            store_ready(next, stored);
-            if (stored != before) {
-                asm volatile("ds_write_b32 %[zero], %[st] offset:%[ctlw3]\n"
-                             :: [zero] "v"(0u), [st] "v"(stored), [ctlw3] "n"(kCtlOff + 12u) : "memory");
+            const uint32_t before = mine;
+            while (mine + kSlab <= n && __ballot(next < mine + kSlab) == 0) {
+                store_slabs(mine, std::integral_constant<uint32_t, 1u>{});
+                mine += 2u * kSlab;
+            }
+            if (mine != before) {
+                asm volatile("ds_write_b32 %[wa], %[st]\n"
+                             :: [wa] "v"(kCtlOff + 4u * (kStored0 + which)), [st] "v"(mine) : "memory");
                 spins = 0;
             }
             if (last_pass) {
-                if (lane == 0) ctl[kStoreDone] = 1u;
+                if (lane == 0) ctl[kStoreDone0 + which] = 1u;
                 break;
             }
-            if (stored == before) {
+            if (mine == before) {
                 if (uniform(ctl[kGaveUp])) break;
                 if (++spins > kSpinLimit) {
                     if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
@@ -591,9 +606,7 @@ void decode_merged(DecodeParams p) {
     }
 
     // ---- decoding wavefront: per-lane stream state
-    const uint32_t n_words = hdr >> 16;
-    uint32_t total_words;
-    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    __builtin_amdgcn_s_setprio(3);
     uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
     const uint32_t last_word4 = c.payload_words << 2;    // byte offset of the zero words behind the payload
 
@@ -652,7 +665,8 @@ void decode_merged(DecodeParams p) {
             const uint32_t reach = (STEPS) * kMaxMerged * N;                                                          \
             const uint32_t near_end = n - reach;                                                                      \
             if (__ballot(ne < near_end) == 0) break;                                                                  \
-            const uint32_t stored = uniform(ctl[kStored]), expanded = uniform(ctl[kExpanded]);                        \
+            const uint4 seen = hand_over_words();                                                                     \
+            const uint32_t stored = min(uniform(seen.z), uniform(seen.w)), expanded = uniform(seen.y);               \
             const uint32_t limit = min(near_end, stored + (kRingElems - reach));                                      \
             if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) { /* ring or log full: wait */           \
                 if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;                                    \
@@ -681,7 +695,7 @@ void decode_merged(DecodeParams p) {
                 "v_mov_b32 v40, s46\n"                 /* offset of the block's header */                             \
                 "v_mov_b32 v41, 0\n"                                                                                  \
                 "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "ds_read_b64 v[48:49], v43 offset:%[ctlw1]\n" /* blocks expanded, elements stored */                  \
+                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* -, blocks expanded, elements stored (two) */        \
                 "v_alignbit_b32 v28, v29, v28, v32\n"                                                                 \
                 "v_alignbit_b32 v29, v30, v29, v32\n"                                                                 \
                 "v_alignbit_b32 v30, v31, v30, v32\n"                                                                 \
@@ -708,8 +722,9 @@ void decode_merged(DecodeParams p) {
                 "ds_write_b32 v40, v46 offset:%[hdr]+8\n"                                                             \
                 "s_add_u32 s44, s44, 1\n"                                                                             \
                 "v_mov_b32 v44, s44\n"                                                                                \
-                "v_readfirstlane_b32 s46, v48\n"       /* blocks expanded when this block began */                    \
-                "v_readfirstlane_b32 s47, v49\n"       /* 2 * elements stored when this block began */                \
+                "v_readfirstlane_b32 s46, v49\n"       /* blocks expanded when this block began */                    \
+                "v_readfirstlane_b32 s47, v50\n"       /* elements stored when this block began: every slab */        \
+                "v_readfirstlane_b32 s45, v51\n"       /* below the next one of either storing wavefront */           \
                 "ds_write_b32 v43, v44 offset:%[ctlw0]\n" /* publish the block */                                     \
                 "s_mov_b64 exec, s[40:41]\n"           /* every lane reloads its words */                             \
                 "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
@@ -717,6 +732,7 @@ void decode_merged(DecodeParams p) {
                 "v_min_u32 v38, %[lastw], v38\n"                                                                      \
                 "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
                 "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
+                "s_min_u32 s47, s47, s45\n"                                                                           \
                 "s_add_u32 s47, s47, %[room]\n"                                                                       \
                 "s_min_u32 s47, s47, %[nearend]\n"                                                                    \
                 "v_cmp_gt_u32 vcc, s47, v34\n"         /* lanes that can run another block */                         \
@@ -734,14 +750,21 @@ void decode_merged(DecodeParams p) {
                 : [lim] "s"(uniform(limit)), [nearend] "s"(uniform(near_end)), [room] "s"(uniform(kRingElems - reach)),\
                   [nstr] "s"(uniform(N)), [snstr] "s"(uniform((STEPS) * N)), [lastw] "s"(uniform(last_word4)),        \
                   [lanelog] "v"(lane_log),                                                                            \
-                  [table] "n"(kTableOff), [hdr] "n"(kHdrOff), [ctlw0] "n"(kCtlOff), [ctlw1] "n"(kCtlOff + 8u),        \
+                  [table] "n"(kTableOff), [hdr] "n"(kHdrOff), [ctlw0] "n"(kCtlOff),                                \
                   [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [slotshift] "n"(11)                         \
-                : "memory", "vcc", "scc", "s40", "s41", "s44", "s46", "s47", "v24", "v25", "v28", "v29", "v30",       \
+                : "memory", "vcc", "scc", "s40", "s41", "s44", "s45", "s46", "s47", "v24", "v25", "v28", "v29", "v30",\
                   "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44",   \
-                  "v45", "v46", "v47", "v48", "v49");                                                                 \
+                  "v45", "v46", "v47", "v48", "v49", "v50", "v51");                                                   \
             logged = uniform(logged_v);                                                                               \
         }
         uint32_t spins = 0;
+        // the first four hand-over words in one LDS read
+        auto hand_over_words = [&]() {
+            uint4 v;
+            asm volatile("ds_read_b128 %[v], %[zero] offset:%[ctlw0]\n s_waitcnt lgkmcnt(0)\n"
+                         : [v] "=v"(v) : [zero] "v"(0u), [ctlw0] "n"(kCtlOff) : "memory");
+            return v;
+        };
         ANSZP_RUN_BLOCKS(8, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2") ANSZP_BA("3") ANSZP_AB("4") ANSZP_BA("5") ANSZP_AB("6"))
         ANSZP_RUN_BLOCKS(4, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2"))
         ANSZP_RUN_BLOCKS(2, ANSZP_AB("0"))
@@ -753,7 +776,8 @@ void decode_merged(DecodeParams p) {
         // wavefronts finish what is logged; then this wavefront owns the ring
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         if (lane == 0) ctl[kOver] = 1u;
-        for (spins = 0; !gave_up && (!uniform(ctl[kStoreDone]) || !uniform(ctl[kTriplesLo]) || !uniform(ctl[kTriplesHi])); ++spins) {
+        for (spins = 0; !gave_up && (!uniform(ctl[kStoreDone0]) || !uniform(ctl[kStoreDone1]) || !uniform(ctl[kTriplesLo]) ||
+                                       !uniform(ctl[kTriplesHi])); ++spins) {
             if (uniform(ctl[kGaveUp]) || spins > kSpinLimit) gave_up = true;
             __builtin_amdgcn_s_sleep(1);
         }
@@ -767,7 +791,7 @@ void decode_merged(DecodeParams p) {
     // Careful phase (Sec. II-A, one step per symbol): every step checks the end of the stream and
     // the room in the ring.
     uint32_t X = X4 >> 3;                                // the peeked bit is dropped: it has not been read
-    uint32_t stored = uniform(ctl[kStored]);
+    uint32_t stored = min(uniform(ctl[kStored0]), uniform(ctl[kStored1]));
     auto step = [&](uint32_t bound) {
         if (ne < bound) {
             const uint32_t t = lds_table[X];
