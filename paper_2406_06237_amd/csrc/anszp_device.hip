@@ -26,14 +26,21 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kBlock = 512;                    // 8 wavefronts stage, five of them stay for the decode; two such
                                                // workgroups fit a CU with 128 VGPRs per wavefront
-constexpr uint32_t kTableBytes = 8u << ANSZP_MAX_TABLE_LOG;   // 32 KiB: two look-ahead entries of 4 bytes per state
-constexpr uint32_t kRingElems = 16u * 1024u;   // LDS ring of decoded symbols (one byte each)
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
-constexpr uint32_t kPayloadWords = 3584u;      // LDS window for one chunk's compressed words
 constexpr uint32_t kMaxMerged = 4u;             // symbols one look-ahead entry can stand for
-constexpr uint32_t kLogSlots = 8u;              // blocks of look-ups in flight between two wavefronts
 constexpr uint32_t kLogSlotBytes = 8u * kWave * 4u;
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
+
+// LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states and leaves
+// room for two workgroups per CU; the small one (tables of up to 2^11 states, shorter windows) for three.
+struct LargeLds {
+    static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 3584u, kRingElems = 16u * 1024u;
+    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 2u;
+};
+struct SmallLds {
+    static constexpr uint32_t kTableLog = 11u, kPayloadWords = 2048u, kRingElems = 8u * 1024u;
+    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 3u;
+};
 
 struct DecodeParams {
     const uint32_t* tables;
@@ -262,9 +269,12 @@ struct Flusher {
     }
 };
 
-template <int OUT, bool PER_CHANNEL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))   // 2 workgroups per CU; more buys nothing
-void decode_merged(DecodeParams p) {
+template <int OUT, bool PER_CHANNEL, class G>
+__device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
+    constexpr uint32_t kTableBytes = 8u << G::kTableLog;           // two look-ahead entries of 4 bytes per state
+    constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each)
+    constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
+    constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks of look-ups in flight between two wavefronts
     // One LDS block carved by hand.  The compressed words sit at offset 0 (their two-dword reads have no
     // room for a large immediate offset); everything the hand-scheduled look-up addresses with an
     // immediate offset lies below 64 KiB.
@@ -279,7 +289,7 @@ void decode_merged(DecodeParams p) {
     constexpr uint32_t kLogOff = kRingOff + kRingElems;             // logged entries: [slot][look-up][lane]
     constexpr uint32_t kLdsBytes = kLogOff + kLogSlots * kLogSlotBytes;
     static_assert(kTableOff % 16u == 0 && kRingOff % 16u == 0 && kCtlOff % 8u == 0 && kRingOff < 65536u, "LDS layout");
-    static_assert(2u * kLdsBytes <= 160u * 1024u, "two workgroups per CU");
+    static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     uint32_t* const lds_words = reinterpret_cast<uint32_t*>(lds);
     uint32_t* const lds_table = reinterpret_cast<uint32_t*>(lds + kTableOff);
@@ -294,7 +304,7 @@ void decode_merged(DecodeParams p) {
            kTriplesLo = 8, kTriplesHi = 9 };
     constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
-    constexpr uint32_t kTableLoads = ((2u << ANSZP_MAX_TABLE_LOG) / 4u + kBlock - 1u) / kBlock;   // 16-byte loads per thread
+    constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 4u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
     constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;
     constexpr uint32_t kTripleLoads = (1u << ANSZP_MAX_TABLE_LOG) / 4u / kWave;                   // per lane of one wavefront
 
@@ -319,7 +329,7 @@ void decode_merged(DecodeParams p) {
     const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte row of triples
     // (named values rather than arrays: an array that lives across a barrier is kept in scratch
     // memory by the compiler)
-    static_assert(kTableLoads == 4u && kWordLoads == 2u, "loads per thread are written out below");
+    static_assert(kTableLoads <= 4u && kWordLoads <= 2u, "loads per thread are written out below (clamped when fewer)");
     const uint32_t t_last = (L >> 1) - 1u;
     const uint32_t w_last = quads ? quads - 1u : 0u;
     const uint4* wsafe = quads ? wsrc : tsrc;
@@ -344,8 +354,9 @@ void decode_merged(DecodeParams p) {
     enum { kDecode = 0, kExpand = 1, kStore0 = 2, kStore1 = 3, kPlaceLo = 4, kPlaceHi = 5, kNoTask = 6 };
     uint32_t task = kNoTask;
     {
-        const uint32_t second = (blockIdx.x / max(p.n_cus, 1u)) & 1u;
-        const uint32_t want[6] = {second, 2u + second, 2u, 3u, 1u - second, 3u - second};
+        const uint32_t turn = (blockIdx.x / max(p.n_cus, 1u)) % G::kWorkgroupsPerCu;
+        const uint32_t want[6] = {turn, turn < 2u ? 2u + turn : 3u, turn < 2u ? 2u : 0u, turn < 2u ? 3u : 1u,
+                                  turn < 2u ? 1u - turn : 3u, turn < 2u ? 3u - turn : 3u};
         const uint32_t mine = reinterpret_cast<const uint32_t*>(lds + kSimdOff)[lane & 7u];   // one read, eight answers
         uint32_t simd[8];
 #pragma unroll
@@ -369,7 +380,7 @@ void decode_merged(DecodeParams p) {
     if (task == kDecode) first_word = wave_exclusive_sum(n_words, &total_words);
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
     const uint32_t n = c.n_symbols;
-    const bool merged_ok = wide && c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
+    const bool merged_ok = wide && p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
                            n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
 
@@ -828,6 +839,14 @@ void decode_merged(DecodeParams p) {
     if (err && lane == 0) report(p.status, err);
 }
 
+template <int OUT, bool PER_CHANNEL>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))   // 2 workgroups per CU; more buys nothing
+void decode_merged(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, LargeLds>(p); }
+
+template <int OUT, bool PER_CHANNEL>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 6)))   // 3 workgroups per CU
+void decode_merged_small(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, SmallLds>(p); }
+
 // ---------------------------------------------------------------------------------------------
 // Sec. II-B alone.
 template <int OUT>
@@ -858,8 +877,10 @@ uint32_t device_cus() {
 }
 
 template <int OUT>
-void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, hipStream_t s) {
+void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, bool small, hipStream_t s) {
     if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
+    else if (small && per_channel) hipLaunchKernelGGL((decode_merged_small<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
+    else if (small) hipLaunchKernelGGL((decode_merged_small<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
     else if (per_channel) hipLaunchKernelGGL((decode_merged<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
     else hipLaunchKernelGGL((decode_merged<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
 }
@@ -886,12 +907,15 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
     // chunks whose compressed words cannot fit the merged kernel's LDS window would all take its
     // fallback; launch the light step-wise kernel (many more wavefronts per CU) for them instead
-    const bool stepwise = mode == 1 || (mode == 0 && a->payload_words / a->n_chunks > kPayloadWords);
+    const uint64_t mean_words = a->payload_words / a->n_chunks;
+    const bool stepwise = mode == 1 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    // small tables and short chunks: the variant that fits three workgroups on a CU
+    const bool small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords;
     const bool per_channel = a->scales != nullptr && a->n_scales != 0;
     switch (a->out_dtype) {
-        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, s); break;
-        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, s); break;
-        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, s); break;
+        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, small, s); break;
+        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, small, s); break;
+        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, small, s); break;
     }
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }
