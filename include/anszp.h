@@ -185,8 +185,9 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  *   1  step-wise kernel: one look-up per symbol, exactly the loop of Sec. II-A / III-B; also the
  *      path any chunk takes whose compressed words exceed the on-chip window or whose first
  *      output element is not 16-byte aligned
- *   2  merged-run kernel: a run of empty-label transitions and the step that ends it are one
- *      look-up, compressed words and decoded symbols are staged in LDS
+ *   2  look-ahead kernel: look-ups use the merged entries of the table (word [2X + b] above),
+ *      compressed words and decoded symbols are staged in LDS, and the work of a chunk is split
+ *      over several wavefronts of its workgroup
  * Errors: as anszp_decode, E_RANGE for an unknown variant. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 

@@ -7,13 +7,16 @@
 // Sec. III-A (one table per layer), Sec. II-B (w = scale * (q - z)).
 //
 // Two code paths produce identical results:
-//   decode_chunk_stepwise  one look-up per symbol, words read from global memory; handles every
-//                          geometry the ABI allows.
-//   decode_chunk_merged    look-ups use the merged half of the table entries (a run of empty-label
-//                          transitions of the dominant symbol plus the step that ends it is ONE
-//                          look-up), the chunk's compressed words are staged in LDS, symbols are
-//                          gathered in an LDS ring and leave as 16-byte-per-lane coalesced stores.
-// The merged path needs the chunk's words to fit its LDS window and the chunk's first output
+//   decode_chunk_stepwise  one look-up per symbol from the paper's triple, words read from global
+//                          memory; handles every geometry the ABI allows.
+//   decode_lookahead       look-ups use the look-ahead entries of the table (a run of empty-label
+//                          transitions of the dominant symbol, at most one of its 1-bit transitions
+//                          and the step that ends them are ONE look-up, indexed by the state and the
+//                          next stream bit).  The chunk's compressed words are staged in LDS.  One
+//                          wavefront only walks the automaton and logs the entries it passes; a
+//                          second turns logged entries into symbols in an LDS ring; two more convert
+//                          finished slabs of the ring and store them, 16 bytes per lane.
+// The look-ahead path needs the chunk's words to fit its LDS window and the chunk's first output
 // element to be 16-byte aligned; other chunks take the step-wise path inside the same launch.
 #include "anszp.h"
 
@@ -24,8 +27,7 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 512;                    // 8 wavefronts stage, five of them stay for the decode; two such
-                                               // workgroups fit a CU with 128 VGPRs per wavefront
+constexpr int kBlock = 512;                    // 8 wavefronts stage, six of them stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
 constexpr uint32_t kMaxMerged = 4u;             // symbols one look-ahead entry can stand for
 constexpr uint32_t kLogSlotBytes = 8u * kWave * 4u;
@@ -380,8 +382,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     if (task == kDecode) first_word = wave_exclusive_sum(n_words, &total_words);
     const uint64_t layer_elem0 = c.out_offset - lay.out_base;
     const uint32_t n = c.n_symbols;
-    const bool merged_ok = wide && p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords && ((c.out_offset * kElemBytes) & 15u) == 0 &&
-                           n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
+    const bool merged_ok = wide && p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords &&
+                           ((c.out_offset * kElemBytes) & 15u) == 0 && n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
 
     if (!merged_ok) {                                     // whole workgroup agrees
