@@ -188,6 +188,9 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  *   2  look-ahead kernel: look-ups use the merged entries of the table (word [2X + b] above),
  *      compressed words and decoded symbols are staged in LDS, and the work of a chunk is split
  *      over several wavefronts of its workgroup
+ *   3  step-wise kernel with sixteen chunks per workgroup sharing the tables in LDS
+ *   4  the same with each stream's words fetched 32 bytes at a time through a ring in LDS (what
+ *      the automatic choice takes for thousands of chunks too large for the on-chip window)
  * Errors: as anszp_decode, E_RANGE for an unknown variant. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 

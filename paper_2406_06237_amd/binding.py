@@ -277,7 +277,7 @@ def decode_args(d: DeviceContainer, out, out_dtype: Optional[str] = None) -> Dec
     return a
 
 
-VARIANT_AUTO, VARIANT_STEPWISE, VARIANT_MERGED = 0, 1, 2
+VARIANT_AUTO, VARIANT_STEPWISE, VARIANT_MERGED, VARIANT_STEPWISE_SHARED, VARIANT_STREAMING = 0, 1, 2, 3, 4
 
 
 def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None):

@@ -204,6 +204,199 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
     if (err && lane == 0) report(p.status, err);
 }
 
+// The same loop for launches with many large chunks: sixteen wavefronts, each with a chunk of its own,
+// share a workgroup and its LDS tables, so that a SIMD has eight wavefronts to hide each other's memory
+// waits behind.  Consecutive chunks belong to at most two layers unless layers are tiny: the tables of the
+// first and the last chunk's layers are staged; a chunk of any other layer reads its table from global memory.
+constexpr int kSharedWaves = 16;
+template <int OUT>
+__global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(DecodeParams p, uint32_t n_chunks) {
+    __shared__ uint32_t table[2][1u << ANSZP_MAX_TABLE_LOG];
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t first = blockIdx.x * kSharedWaves, last = min(first + kSharedWaves, n_chunks) - 1u;
+    const uint32_t L = 1u << p.table_log;
+    const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
+    if (layer_a < p.n_tables) {
+        const uint32_t* src = p.tables + (uint64_t(layer_a) << (p.table_log + 2)) + 2u * L;    // the paper's triples
+        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[0][i] = src[i];
+    }
+    if (layer_b != layer_a && layer_b < p.n_tables) {
+        const uint32_t* src = p.tables + (uint64_t(layer_b) << (p.table_log + 2)) + 2u * L;
+        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[1][i] = src[i];
+    }
+    __syncthreads();
+    if (first + wave > last) return;
+    const anszp_chunk_t c = p.chunks[first + wave];
+    if (!chunk_in_bounds(p, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const anszp_layer_t lay = p.layers[c.layer_id];
+    const uint32_t* mine = c.layer_id == layer_a ? table[0] : c.layer_id == layer_b ? table[1]
+                           : p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L;
+    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, mine, lane);
+    if (err && lane == 0) report(p.status, err);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One look-up per symbol for launches with thousands of chunks too large for an LDS window (Sec.
+// III-B at scale).  The plain loop above reads a stream's words four bytes at a time; with two
+// thousand streams per CU each of those reads brings a whole cache line from HBM again, and the
+// launch is bound by re-reading its own input.  Here a stream's words come through a ring in LDS,
+// 32 bytes per fetch and one fetch ahead, and a lane keeps a 128-bit window in registers that it
+// reloads from the ring every 8 steps (no per-step refill test: lanes need their refills at
+// different steps, so such a test would run its body at nearly every step).
+constexpr uint32_t kStreamRingWords = 16u;      // per stream, in LDS
+constexpr uint32_t kStreamFetchWords = 8u;      // per fetch from global memory
+constexpr uint32_t kStreamScales = 128u;        // per-channel scales of one chunk kept in LDS
+typedef uint4 __attribute__((aligned(4))) uint4_word_aligned;
+
+template <int OUT>
+__global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeParams p, uint32_t n_chunks) {
+    __shared__ uint32_t table[2][1u << ANSZP_MAX_TABLE_LOG];
+    __shared__ uint32_t rings[kSharedWaves][kStreamRingWords][kWave];   // word s of lane l at [wave][s mod 16][l]
+    __shared__ float chunk_scales[kSharedWaves][kStreamScales];          // per-channel scales of each wavefront's chunk
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t first = blockIdx.x * kSharedWaves, last = min(first + kSharedWaves, n_chunks) - 1u;
+    const uint32_t L = 1u << p.table_log, N = p.n_streams;
+    const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
+    if (layer_a < p.n_tables) {
+        const uint32_t* src = p.tables + (uint64_t(layer_a) << (p.table_log + 2)) + 2u * L;    // the paper's triples
+        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[0][i] = src[i];
+    }
+    if (layer_b != layer_a && layer_b < p.n_tables) {
+        const uint32_t* src = p.tables + (uint64_t(layer_b) << (p.table_log + 2)) + 2u * L;
+        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[1][i] = src[i];
+    }
+    __syncthreads();
+    if (first + wave > last) return;
+    const anszp_chunk_t c = p.chunks[first + wave];
+    if (!chunk_in_bounds(p, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const anszp_layer_t lay = p.layers[c.layer_id];
+    // per-channel scales come from LDS: a load from global memory inside the loop would make every
+    // step wait for the stores before it (loads and stores share one in-order counter)
+    const bool per_channel = lay.channel_len != 0;
+    const uint64_t chunk_elem0 = c.out_offset - lay.out_base;
+    const uint64_t channel0 = per_channel ? chunk_elem0 / lay.channel_len : 0;           // within the layer
+    const uint64_t channels = per_channel && c.n_symbols ? (chunk_elem0 + c.n_symbols - 1u) / lay.channel_len - channel0 + 1u : 0;
+    const uint32_t* tab = c.layer_id == layer_a ? table[0] : table[1];
+    if ((c.layer_id != layer_a && c.layer_id != layer_b) || channels > kStreamScales) {
+        // a third layer in one workgroup, or more channels than the LDS holds: the plain loop
+        if (c.layer_id != layer_a && c.layer_id != layer_b) tab = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L;
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, tab, lane);
+        if (err && lane == 0) report(p.status, err);
+        return;
+    }
+    for (uint32_t i = lane; i < channels; i += kWave) {
+        const uint64_t ch = lay.scales_offset + channel0 + i;
+        chunk_scales[wave][i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
+    }
+    uint32_t (*ring)[kWave] = rings[wave];
+
+    const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
+    uint32_t X = hdr & (L - 1u);
+    const uint32_t n_words = hdr >> 16;
+    uint32_t total_words;
+    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
+    uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+    const uint32_t full_steps = c.n_symbols / N;          // steps every stream of the chunk takes
+
+    // words of this stream: index relative to the stream's first word; reads beyond the caller's
+    // payload buffer see zeros (beyond the stream they see its neighbours' words, never used)
+    const uint64_t base = c.payload_offset + uint64_t(min(first_word, c.payload_words));
+    auto fetch = [&](uint32_t at, uint4& lo, uint4& hi) {
+        const uint64_t g = base + at;
+        if (g + kStreamFetchWords <= p.payload_words) {
+            const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(p.payload + g);
+            lo = q[0];
+            hi = q[1];
+        } else {
+            auto one = [&](uint32_t i) { return g + i < p.payload_words ? p.payload[g + i] : 0u; };
+            lo = make_uint4(one(0), one(1), one(2), one(3));
+            hi = make_uint4(one(4), one(5), one(6), one(7));
+        }
+    };
+    auto land = [&](uint32_t at, const uint4& lo, const uint4& hi) {      // at is a multiple of 8: no wrap inside
+        const uint32_t s0 = at & (kStreamRingWords - 1u);
+        ring[s0][lane] = lo.x; ring[s0 + 1][lane] = lo.y; ring[s0 + 2][lane] = lo.z; ring[s0 + 3][lane] = lo.w;
+        ring[s0 + 4][lane] = hi.x; ring[s0 + 5][lane] = hi.y; ring[s0 + 6][lane] = hi.z; ring[s0 + 7][lane] = hi.w;
+    };
+    uint4 glo, ghi;
+    fetch(0, glo, ghi);
+    land(0, glo, ghi);
+    fetch(kStreamFetchWords, glo, ghi);
+    land(kStreamFetchWords, glo, ghi);
+    uint32_t fetched = 2u * kStreamFetchWords;            // words of the stream that are in the ring or before it
+    bool pending = false;                                 // glo, ghi hold words [fetched, fetched + 8) on their way
+
+    const uint64_t elem0 = chunk_elem0 + lane;
+    uint32_t channel = per_channel ? static_cast<uint32_t>(elem0 / lay.channel_len - channel0) : 0;   // within the chunk
+    uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
+    float scale = lay.scale;
+    if (per_channel) scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];
+
+    uint32_t abit = 0;                                    // bits of the stream read so far
+    uint64_t out_at = c.out_offset + lane;
+    // K steps from a window loaded once: K * table_log + 31 bits must fit 128
+    auto run = [&](auto count) {
+        constexpr uint32_t K = decltype(count)::value;
+        const uint32_t cw = abit >> 5;
+        uint32_t w0 = ring[cw & 15u][lane], w1 = ring[(cw + 1u) & 15u][lane];
+        uint32_t w2 = ring[(cw + 2u) & 15u][lane], w3 = ring[(cw + 3u) & 15u][lane];
+        w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
+        w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
+        w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
+        w3 >>= (abit & 31u);
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) {
+            const uint32_t e = tab[X];
+            const uint32_t nb = (e >> 16) & 31u;
+            const uint32_t bits = (__brev(w0) >> (31u - nb)) >> 1;          // first bit read is the top bit; none: 0
+            X = ((e & 0xFFFFu) + bits) & (L - 1u);                         // Sec. II-A: newX + bits
+            w0 = __builtin_amdgcn_alignbit(w1, w0, nb);
+            w1 = __builtin_amdgcn_alignbit(w2, w1, nb);
+            w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
+            w3 >>= nb;
+            abit += nb;
+            store_weight<OUT>(p.out, out_at, e >> 24, lay.zero_point, scale);
+            out_at += N;
+            if (per_channel) {
+                in_channel += N;
+                if (in_channel >= lay.channel_len) {
+                    do { in_channel -= lay.channel_len; ++channel; } while (in_channel >= lay.channel_len);
+                    scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];   // beyond the chunk: never stored
+                }
+            }
+        }
+        // the fetch issued after the previous call has had K steps to arrive
+        if (pending) {
+            land(fetched, glo, ghi);
+            fetched += kStreamFetchWords;
+            pending = false;
+        }
+        if (fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords) {
+            fetch(fetched, glo, ghi);
+            pending = true;
+        }
+    };
+    if (lane < N) {
+        uint32_t t = 0;
+        for (; t + 8u <= full_steps; t += 8u) run(std::integral_constant<uint32_t, 8u>{});
+        for (; t < full_steps; ++t) run(std::integral_constant<uint32_t, 1u>{});
+        if (len > full_steps) run(std::integral_constant<uint32_t, 1u>{});     // ragged tail: streams 0 .. n mod N - 1
+        if (X != 0) err |= ANSZP_ST_BAD_STATE;
+        if (((abit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
+    }
+    err = wave_or(err);
+    if (err && lane == 0) report(p.status, err);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Look-ahead path: conversion of decoded symbols on their way from the LDS ring to global memory.
 // `lut` maps a symbol to its bf16 weight when dequantisation is per layer and the output bf16
@@ -879,8 +1072,15 @@ uint32_t device_cus() {
 }
 
 template <int OUT>
-void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, bool small, hipStream_t s) {
-    if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
+void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, bool shared, bool streaming,
+                   bool small, hipStream_t s) {
+    if (stepwise && streaming)
+        hipLaunchKernelGGL(decode_streaming<OUT>, dim3((n_chunks + kSharedWaves - 1) / kSharedWaves),
+                           dim3(kSharedWaves * kWave), 0, s, p, n_chunks);
+    else if (stepwise && shared)
+        hipLaunchKernelGGL(decode_stepwise_shared<OUT>, dim3((n_chunks + kSharedWaves - 1) / kSharedWaves),
+                           dim3(kSharedWaves * kWave), 0, s, p, n_chunks);
+    else if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
     else if (small && per_channel) hipLaunchKernelGGL((decode_merged_small<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
     else if (small) hipLaunchKernelGGL((decode_merged_small<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
     else if (per_channel) hipLaunchKernelGGL((decode_merged<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
@@ -896,7 +1096,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
         a->n_streams > ANSZP_MAX_STREAMS || a->out_dtype > ANSZP_OUT_BF16 || a->n_tables == 0 ||
         a->n_chunks >= (1ull << 31) || (reinterpret_cast<uintptr_t>(a->payload) & 15) ||
         (reinterpret_cast<uintptr_t>(a->tables) & 15) ||
-        (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 2)
+        (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 4)
         return ANSZP_E_RANGE;
     DecodeParams p;
     p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
@@ -910,14 +1110,17 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     // chunks whose compressed words cannot fit the merged kernel's LDS window would all take its
     // fallback; launch the light step-wise kernel (many more wavefronts per CU) for them instead
     const uint64_t mean_words = a->payload_words / a->n_chunks;
-    const bool stepwise = mode == 1 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    const bool stepwise = mode == 1 || mode >= 3 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    // sixteen chunks per workgroup when there are enough chunks to fill every SIMD several deep
+    const bool shared = mode == 3;
+    const bool streaming = mode == 4 || (mode == 0 && stepwise && nc >= 4096u);
     // small tables and short chunks: the variant that fits three workgroups on a CU
     const bool small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords;
     const bool per_channel = a->scales != nullptr && a->n_scales != 0;
     switch (a->out_dtype) {
-        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, small, s); break;
-        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, small, s); break;
-        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, small, s); break;
+        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
+        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
+        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
     }
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }

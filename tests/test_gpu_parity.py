@@ -16,7 +16,7 @@ def _run(orc, w, out_dtype=None):
     c = oracle_encode(orc, w)
     _, expect = oracle_expected(orc, c, w, out_dtype)
     d = B.to_device(host_from_oracle(c, w))
-    for variant in (None, B.VARIANT_STEPWISE, B.VARIANT_MERGED):
+    for variant in (None, B.VARIANT_STEPWISE, B.VARIANT_MERGED, B.VARIANT_STEPWISE_SHARED, B.VARIANT_STREAMING):
         out = B.alloc_out(d, out_dtype)
         out.view(torch.uint8).fill_(0xA5)
         B.decode(d, out=out, out_dtype=out_dtype, variant=variant)
@@ -134,7 +134,7 @@ def test_corruption_is_flagged_not_fatal(orc):
 
     def status_of(h):
         worst = (0, 0)
-        for variant in (B.VARIANT_STEPWISE, B.VARIANT_MERGED):
+        for variant in (B.VARIANT_STEPWISE, B.VARIANT_MERGED, B.VARIANT_STEPWISE_SHARED, B.VARIANT_STREAMING):
             d = B.to_device(h)
             guard = torch.full((w.numel + 4096,), 0x5A5A, dtype=torch.int16, device="cuda").view(torch.bfloat16)
             B.decode_raw(B.decode_args(d, guard), d.device, variant)
