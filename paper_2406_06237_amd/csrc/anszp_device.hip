@@ -101,6 +101,13 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
 // in order, as an LDS instruction.
 typedef volatile __attribute__((address_space(3))) uint32_t lds_flag_t;
 
+typedef __attribute__((address_space(3))) uint64_t lds_uint64_t;
+
+// Byte address inside the workgroup's LDS of an object in __shared__ memory.
+__device__ __forceinline__ uint32_t lds_address(const void* shared) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) void*)shared));
+}
+
 // A value every lane holds alike, moved to a scalar register.
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -254,7 +261,11 @@ typedef uint4 __attribute__((aligned(4))) uint4_word_aligned;
 
 template <int OUT>
 __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeParams p, uint32_t n_chunks) {
-    __shared__ uint32_t table[2][1u << ANSZP_MAX_TABLE_LOG];
+    // LDS entry derived from the paper's triple of state X while staging (Sec. II-A fields, arranged so
+    // that a step needs no field extraction):
+    //   lo: bits 0..4 31 - nb_bits | bits 8..15 symbol | bits 16..31 float(symbol - zero_point) as bf16 (exact)
+    //   hi: LDS byte address of the entry of state newX
+    __shared__ uint2 table[2][1u << ANSZP_MAX_TABLE_LOG];
     __shared__ uint32_t rings[kSharedWaves][kStreamRingWords][kWave];   // word s of lane l at [wave][s mod 16][l]
     __shared__ float chunk_scales[kSharedWaves][kStreamScales];          // per-channel scales of each wavefront's chunk
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -262,14 +273,20 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     const uint32_t first = blockIdx.x * kSharedWaves, last = min(first + kSharedWaves, n_chunks) - 1u;
     const uint32_t L = 1u << p.table_log, N = p.n_streams;
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
-    if (layer_a < p.n_tables) {
-        const uint32_t* src = p.tables + (uint64_t(layer_a) << (p.table_log + 2)) + 2u * L;    // the paper's triples
-        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[0][i] = src[i];
-    }
-    if (layer_b != layer_a && layer_b < p.n_tables) {
-        const uint32_t* src = p.tables + (uint64_t(layer_b) << (p.table_log + 2)) + 2u * L;
-        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[1][i] = src[i];
-    }
+    auto stage = [&](uint32_t layer, uint2* dst) {
+        const uint32_t* src = p.tables + (uint64_t(layer) << (p.table_log + 2)) + 2u * L;      // the paper's triples
+        const uint32_t z = p.layers[layer].zero_point;
+        const uint32_t dst0 = lds_address(dst);
+        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) {
+            const uint32_t e = src[i];
+            const uint32_t sym = e >> 24, nb = min((e >> 16) & 0xFFu, 31u);
+            const float centred = static_cast<float>(static_cast<int>(sym) - static_cast<int>(z));   // |.| <= 255: exact in bf16
+            dst[i] = make_uint2((31u - nb) | (sym << 8) | (__float_as_uint(centred) & 0xFFFF0000u),
+                                dst0 + ((e & (L - 1u)) << 3));
+        }
+    };
+    if (layer_a < p.n_tables) stage(layer_a, table[0]);
+    if (layer_b != layer_a && layer_b < p.n_tables) stage(layer_b, table[1]);
     __syncthreads();
     if (first + wave > last) return;
     const anszp_chunk_t c = p.chunks[first + wave];
@@ -284,11 +301,10 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     const uint64_t chunk_elem0 = c.out_offset - lay.out_base;
     const uint64_t channel0 = per_channel ? chunk_elem0 / lay.channel_len : 0;           // within the layer
     const uint64_t channels = per_channel && c.n_symbols ? (chunk_elem0 + c.n_symbols - 1u) / lay.channel_len - channel0 + 1u : 0;
-    const uint32_t* tab = c.layer_id == layer_a ? table[0] : table[1];
     if ((c.layer_id != layer_a && c.layer_id != layer_b) || channels > kStreamScales) {
-        // a third layer in one workgroup, or more channels than the LDS holds: the plain loop
-        if (c.layer_id != layer_a && c.layer_id != layer_b) tab = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L;
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, tab, lane);
+        // a third layer in one workgroup, or more channels than the LDS holds: the plain loop, table
+        // from global memory
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
@@ -299,7 +315,8 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     uint32_t (*ring)[kWave] = rings[wave];
 
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
-    uint32_t X = hdr & (L - 1u);
+    const uint32_t table0 = lds_address(c.layer_id == layer_a ? table[0] : table[1]);
+    uint32_t X = table0 + ((hdr & (L - 1u)) << 3);       // LDS byte address of the current state's entry
     const uint32_t n_words = hdr >> 16;
     uint32_t total_words;
     const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
@@ -353,18 +370,26 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
         w3 >>= (abit & 31u);
+        uint32_t sum = 0;                                 // low byte: 31 - nb_bits over the K steps
 #pragma unroll
         for (uint32_t k = 0; k < K; ++k) {
-            const uint32_t e = tab[X];
-            const uint32_t nb = (e >> 16) & 31u;
-            const uint32_t bits = (__brev(w0) >> (31u - nb)) >> 1;          // first bit read is the top bit; none: 0
-            X = ((e & 0xFFFFu) + bits) & (L - 1u);                         // Sec. II-A: newX + bits
+            const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
+            const uint2 e = make_uint2(static_cast<uint32_t>(both), static_cast<uint32_t>(both >> 32));
+            const uint32_t bits = (__brev(w0) >> (e.x & 31u)) >> 1;        // first bit read is the top bit; none: 0
+            X = e.y + (bits << 3);                                         // Sec. II-A: newX + bits
+            const uint32_t nb = ~e.x;                                      // low five bits
             w0 = __builtin_amdgcn_alignbit(w1, w0, nb);
             w1 = __builtin_amdgcn_alignbit(w2, w1, nb);
             w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
-            w3 >>= nb;
-            abit += nb;
-            store_weight<OUT>(p.out, out_at, e >> 24, lay.zero_point, scale);
+            w3 >>= (nb & 31u);
+            sum += e.x;
+            if constexpr (OUT == ANSZP_OUT_U8) {
+                static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(e.x >> 8);
+            } else {
+                const float w = scale * __uint_as_float(e.x & 0xFFFF0000u);   // Sec. II-B: scale * (q - z)
+                if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = w;
+                else static_cast<uint16_t*>(p.out)[out_at] = static_cast<uint16_t>(bf16_rne(w));
+            }
             out_at += N;
             if (per_channel) {
                 in_channel += N;
@@ -374,6 +399,7 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
                 }
             }
         }
+        abit += 31u * K - (sum & 0xFFu);
         // the fetch issued after the previous call has had K steps to arrive
         if (pending) {
             land(fetched, glo, ghi);
@@ -390,7 +416,7 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
         for (; t + 8u <= full_steps; t += 8u) run(std::integral_constant<uint32_t, 8u>{});
         for (; t < full_steps; ++t) run(std::integral_constant<uint32_t, 1u>{});
         if (len > full_steps) run(std::integral_constant<uint32_t, 1u>{});     // ragged tail: streams 0 .. n mod N - 1
-        if (X != 0) err |= ANSZP_ST_BAD_STATE;
+        if (X != table0) err |= ANSZP_ST_BAD_STATE;          // state 0
         if (((abit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
     err = wave_or(err);
