@@ -57,6 +57,12 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build()")
+        # PyTorch brings its own HIP runtime: load it first, so that the library binds to the same
+        # one (two runtimes in one process do not share devices, streams or allocations)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         L.anszp_strerror.restype = C.c_char_p
         L.anszp_strerror.argtypes = [C.c_int]
