@@ -89,6 +89,25 @@ def test_config4_one_block_at_real_shapes(orc):
     out2 = B.decode(d, variant=B.VARIANT_MERGED)
     assert d.read_status() == (0, 0)
     assert np.array_equal(B.bits_of(out2)[:w.numel][idx], expect[idx])
+    # the kernel the full set gets (24,704 chunks: the automatic choice is the streaming kernel), forced here
+    out3 = B.decode(d, variant=B.VARIANT_STREAMING)
+    assert d.read_status() == (0, 0)
+    assert np.array_equal(B.bits_of(out3)[:w.numel], expect)
+
+
+def test_many_large_chunks_take_the_streaming_kernel(orc):
+    """More than 4096 chunks whose words exceed the on-chip window: the automatic choice must be the
+    streaming kernel (sixteen chunks per workgroup, several layers per workgroup at layer boundaries,
+    per-channel scales, a ragged last chunk per layer) and must decode every element."""
+    w = W.config4(n_blocks=1)
+    w.chunk_size = 49152 - 64 * 3          # 4096 x 4096 and 4096 x 11008 are not multiples: ragged tails
+    c = oracle_encode(orc, w)
+    assert len(c.chunk_nsym) >= 4096 and c.payload.size / len(c.chunk_nsym) > 3584
+    _, expect = oracle_expected(orc, c, w)
+    d = B.to_device(host_from_oracle(c, w))
+    out = B.decode(d)
+    assert d.read_status() == (0, 0)
+    assert np.array_equal(B.bits_of(out)[:w.numel], expect)
 
 
 def test_library_packer_output_decodes_too(orc):
