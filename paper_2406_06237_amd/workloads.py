@@ -217,6 +217,29 @@ def config3() -> Workload:
     return Workload("resnet50_convs", layers, 12, 64, 65536, "bf16")
 
 
+def resnet50_odd_bins() -> Workload:
+    """ResNet-50-shaped conv stack with the alphabets the paper describes (Sec. II-B, III-C): an odd
+    number of bins with the zero-point in the middle, 31 bins for the smaller half of the layers down
+    to 13 bins for the largest ones, mass concentrated on the zero-point so that the set averages
+    below one bit per weight.  Used by the table-size study; any table of 64 states or more can code it."""
+    shapes = resnet50_conv_shapes()
+    n = len(shapes)
+    u = _uniform01(_seed(6, 1 << 16), 2 * n)
+    sizes = np.array([int(np.prod(s)) for _, s in shapes])
+    rank = np.empty(n, dtype=int)
+    rank[np.argsort(sizes, kind="stable")] = np.arange(n)
+    p0_draws = np.sort(0.72 + 0.22 * u[0:n])
+    layers = []
+    for i, (name, shape) in enumerate(shapes):
+        frac = rank[i] / max(n - 1, 1)                       # 0 smallest layer .. 1 largest
+        bins = 31 if frac < 0.5 else int(31 - 18 * (frac - 0.5) / 0.5) | 1   # odd, 31 .. 13
+        z = (bins - 1) // 2
+        scale = float(np.float32(0.005 + u[n + i] * 0.045))
+        layers.append(Layer(name, shape, 5, z, scale,
+                            peaked_geometric_pmf(bins, z, float(p0_draws[rank[i]])), _seed(6, i)))
+    return Workload("resnet50_odd_bins", layers, 8, 64, 65536, "bf16")
+
+
 def config4(n_blocks: int = 32, d_model: int = 4096, d_ff: int = 11008) -> Workload:
     """Transformer-sized linear stack: per block 4 of d x d and 3 of d x d_ff, 4-bit,
     Laplace at ~2.5 bit, per-output-channel fp32 scales, 64 streams / 262144."""

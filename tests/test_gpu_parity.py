@@ -110,6 +110,16 @@ def test_many_large_chunks_take_the_streaming_kernel(orc):
     assert np.array_equal(B.bits_of(out)[:w.numel], expect)
 
 
+@pytest.mark.parametrize("R", [6, 8])
+def test_odd_bin_alphabets_with_small_tables(orc, R):
+    """The alphabets the paper describes (odd bin counts 13..31, zero-point in the middle) coded with the
+    table sizes of its Sec. III-B study (64 and 256 states)."""
+    w = W.resnet50_odd_bins()
+    w.layers = w.layers[:24]
+    w.table_log = R
+    _run(orc, w)
+
+
 def test_library_packer_output_decodes_too(orc):
     """The same weights compressed by the library's own host packer."""
     w = W.tiny(n=70000, chunk_size=8192, table_log=11, p0=0.85)

@@ -200,3 +200,18 @@ def test_host_error_codes():
     assert lib.anszp_dequant_zp(None, 0, lay.ctypes.data, None, 0, None, 3, None) == -2
     assert lib.anszp_dequant_zp(None, 0, lay.ctypes.data, None, 0, None, 1, None) == 0
     assert lib.anszp_dequant_zp(None, 5, lay.ctypes.data, None, 0, None, 1, None) == -1
+
+
+def test_table_size_study_trend():
+    """Sec. III-B on the synthetic odd-bin ResNet-50 (first layers only, for speed): the gap to the entropy
+    bound grows as the table shrinks, and parallel streams cost little once only the paper's per-stream
+    cost (the final state) is counted."""
+    from paper_2406_06237_amd import table_size_study as T
+    rows, bound, numel = T.study(states=(64, 128, 256, 4096), max_layers=14)
+    single = {st: total for st, g, total, _, _ in rows if g.startswith("single")}
+    assert single[64] > single[128] > single[256] > single[4096] >= bound * 0.999
+    assert single[4096] < bound * 1.01 and single[256] < bound * 1.12
+    for st, g, total, paper_like, streams in rows:
+        if not g.startswith("single"):
+            assert total > single[st]                                  # framing is not free
+            assert paper_like < single[st] * 1.03, (st, g, paper_like / single[st])
