@@ -1026,11 +1026,13 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     uint32_t stored = min(uniform(ctl[kStored0]), uniform(ctl[kStored1]));
     auto step = [&](uint32_t bound) {
         if (ne < bound) {
-            const uint32_t t = lds_table[X];
-            const uint32_t nb = (t >> 16) & 0xFFu;
+            // both reads are issued before either is waited for, and there is no branch on nb_bits
             const uint32_t* q = reinterpret_cast<const uint32_t*>(lds + min((abit >> 3) & ~3u, last_word4));
-            const uint32_t window = __builtin_amdgcn_alignbit(q[1], q[0], abit);
-            const uint32_t bits = nb ? __brev(window) >> (32u - nb) : 0u;    // first bit read is the top bit
+            const uint32_t q0 = q[0], q1 = q[1];
+            const uint32_t t = lds_table[X];
+            const uint32_t nb = min((t >> 16) & 0xFFu, 31u);
+            const uint32_t window = __builtin_amdgcn_alignbit(q1, q0, abit);
+            const uint32_t bits = (__brev(window) >> (31u - nb)) >> 1;       // first bit read is the top bit; none: 0
             X = ((t & 0xFFFFu) + bits) & (L - 1u);
             ring8[ne & kRingMask] = static_cast<uint8_t>(t >> 24);
             abit += nb;
