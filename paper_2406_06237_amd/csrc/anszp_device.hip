@@ -255,42 +255,90 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
 // III-B at scale).  The plain loop above reads a stream's words four bytes at a time; with two
 // thousand streams per CU each of those reads brings a whole cache line from HBM again, and the
 // launch is bound by re-reading its own input.  Here a stream's words come through a ring in LDS,
-// 32 bytes per fetch and one fetch ahead, and a lane keeps a 128-bit window in registers that it
-// reloads from the ring every 8 steps (no per-step refill test: lanes need their refills at
+// 32 bytes per fetch and one fetch ahead, and a lane keeps a window of the stream in registers that
+// it reloads from the ring every K steps (no per-step refill test: lanes need their refills at
 // different steps, so such a test would run its body at nearly every step).
+//
+// The launch is bound by the instructions a step issues, so the LDS entries are derived from the
+// paper's triples (Sec. II-A) while staging, in one of two forms:
+//   fast form (64 streams per chunk, no state of either table reads zero bits):
+//     lo: bits 0..4 32 - nb_bits | bits 8..15 symbol | bits 16..31 (symbol - zero_point) as fp16 (exact)
+//     the window holds the stream most significant bit first: bits = window >> (32 - nb_bits), and
+//     one funnel shift per window register consumes them
+//   plain form: lo: bits 0..4 31 - nb_bits | bits 8..15 symbol | bits 16..31 the same as bf16;
+//     least significant bit first, every shift written so that nb_bits = 0 works
+//   hi, both forms: LDS byte address of the entry of state newX
+// With the fast form, when every wavefront-step lies inside one output channel, the scale is a
+// wavefront-uniform value per block of steps and the store address is one base plus immediates.
 constexpr uint32_t kStreamRingWords = 16u;      // per stream, in LDS
 constexpr uint32_t kStreamFetchWords = 8u;      // per fetch from global memory
 constexpr uint32_t kStreamScales = 128u;        // per-channel scales of one chunk kept in LDS
 typedef uint4 __attribute__((aligned(4))) uint4_word_aligned;
 
+// scale * (q - z) (Sec. II-B) with q - z read as fp16 from the high half of `entry_lo`: the product
+// is rounded once, like the plain multiplication; the addend -0 keeps the sign of a zero product.
+__device__ __forceinline__ float scaled_high_half(uint32_t entry_lo, float scale) {
+    float w;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(w) : "v"(entry_lo), "v"(scale), "v"(-0.0f));
+    return w;
+}
+
 template <int OUT>
 __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeParams p, uint32_t n_chunks) {
-    // LDS entry derived from the paper's triple of state X while staging (Sec. II-A fields, arranged so
-    // that a step needs no field extraction):
-    //   lo: bits 0..4 31 - nb_bits | bits 8..15 symbol | bits 16..31 float(symbol - zero_point) as bf16 (exact)
-    //   hi: LDS byte address of the entry of state newX
     __shared__ uint2 table[2][1u << ANSZP_MAX_TABLE_LOG];
     __shared__ uint32_t rings[kSharedWaves][kStreamRingWords][kWave];   // word s of lane l at [wave][s mod 16][l]
     __shared__ float chunk_scales[kSharedWaves][kStreamScales];          // per-channel scales of each wavefront's chunk
+    constexpr uint32_t kThreads = kSharedWaves * kWave;
+    constexpr uint32_t kPerThread = (1u << ANSZP_MAX_TABLE_LOG) / kThreads;
+    constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : OUT == ANSZP_OUT_F32 ? 4u : 2u;
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t first = blockIdx.x * kSharedWaves, last = min(first + kSharedWaves, n_chunks) - 1u;
     const uint32_t L = 1u << p.table_log, N = p.n_streams;
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
-    auto stage = [&](uint32_t layer, uint2* dst) {
-        const uint32_t* src = p.tables + (uint64_t(layer) << (p.table_log + 2)) + 2u * L;      // the paper's triples
-        const uint32_t z = p.layers[layer].zero_point;
-        const uint32_t dst0 = lds_address(dst);
-        for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) {
-            const uint32_t e = src[i];
-            const uint32_t sym = e >> 24, nb = min((e >> 16) & 0xFFu, 31u);
-            const float centred = static_cast<float>(static_cast<int>(sym) - static_cast<int>(z));   // |.| <= 255: exact in bf16
-            dst[i] = make_uint2((31u - nb) | (sym << 8) | (__float_as_uint(centred) & 0xFFFF0000u),
-                                dst0 + ((e & (L - 1u)) << 3));
-        }
+    const bool have_a = layer_a < p.n_tables, have_b = layer_b != layer_a && layer_b < p.n_tables;
+
+    // the paper's triples of both tables, held in registers until the form of the entries is known
+    const uint32_t* src_a = p.tables + (uint64_t(have_a ? layer_a : 0u) << (p.table_log + 2)) + 2u * L;
+    const uint32_t* src_b = p.tables + (uint64_t(have_b ? layer_b : 0u) << (p.table_log + 2)) + 2u * L;
+    uint32_t ta0 = 0x00010000u, ta1 = ta0, ta2 = ta0, ta3 = ta0, tb0 = ta0, tb1 = ta0, tb2 = ta0, tb3 = ta0;
+    static_assert(kPerThread == 4, "four triples of each table per thread");
+    if (have_a) {
+        if (tid < L) ta0 = src_a[tid];
+        if (tid + kThreads < L) ta1 = src_a[tid + kThreads];
+        if (tid + 2u * kThreads < L) ta2 = src_a[tid + 2u * kThreads];
+        if (tid + 3u * kThreads < L) ta3 = src_a[tid + 3u * kThreads];
+    }
+    if (have_b) {
+        if (tid < L) tb0 = src_b[tid];
+        if (tid + kThreads < L) tb1 = src_b[tid + kThreads];
+        if (tid + 2u * kThreads < L) tb2 = src_b[tid + 2u * kThreads];
+        if (tid + 3u * kThreads < L) tb3 = src_b[tid + 3u * kThreads];
+    }
+    auto reads_no_bits = [](uint32_t e) { return ((e >> 16) & 0xFFu) == 0u; };
+    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) |
+                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3);
+    const bool fast = !__syncthreads_or(some_zero) && N == kWave;
+    auto place = [&](uint32_t e, uint32_t i, uint2* dst, uint32_t z) {
+        if (i >= L) return;
+        const uint32_t sym = e >> 24, nb = min((e >> 16) & 0xFFu, 31u);
+        const int centred = static_cast<int>(sym) - static_cast<int>(z);                       // |.| <= 255: exact in fp16 and bf16
+        uint32_t lo;
+        if (fast) lo = ((32u - nb) & 31u) | (sym << 8) |
+                       (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, static_cast<_Float16>(centred))) << 16);
+        else lo = (31u - nb) | (sym << 8) | (__float_as_uint(static_cast<float>(centred)) & 0xFFFF0000u);
+        dst[i] = make_uint2(lo, lds_address(dst) + ((e & (L - 1u)) << 3));
     };
-    if (layer_a < p.n_tables) stage(layer_a, table[0]);
-    if (layer_b != layer_a && layer_b < p.n_tables) stage(layer_b, table[1]);
+    if (have_a) {
+        const uint32_t z = p.layers[layer_a].zero_point;
+        place(ta0, tid, table[0], z); place(ta1, tid + kThreads, table[0], z);
+        place(ta2, tid + 2u * kThreads, table[0], z); place(ta3, tid + 3u * kThreads, table[0], z);
+    }
+    if (have_b) {
+        const uint32_t z = p.layers[layer_b].zero_point;
+        place(tb0, tid, table[1], z); place(tb1, tid + kThreads, table[1], z);
+        place(tb2, tid + 2u * kThreads, table[1], z); place(tb3, tid + 3u * kThreads, table[1], z);
+    }
     __syncthreads();
     if (first + wave > last) return;
     const anszp_chunk_t c = p.chunks[first + wave];
@@ -304,6 +352,7 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     const bool per_channel = lay.channel_len != 0;
     const uint64_t chunk_elem0 = c.out_offset - lay.out_base;
     const uint64_t channel0 = per_channel ? chunk_elem0 / lay.channel_len : 0;           // within the layer
+    const uint32_t in_channel0 = per_channel ? static_cast<uint32_t>(chunk_elem0 - channel0 * lay.channel_len) : 0;
     const uint64_t channels = per_channel && c.n_symbols ? (chunk_elem0 + c.n_symbols - 1u) / lay.channel_len - channel0 + 1u : 0;
     if ((c.layer_id != layer_a && c.layer_id != layer_b) || channels > kStreamScales) {
         // a third layer in one workgroup, or more channels than the LDS holds: the plain loop, table
@@ -331,14 +380,25 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     // words of this stream: index relative to the stream's first word; reads beyond the caller's
     // payload buffer see zeros (beyond the stream they see its neighbours' words, never used)
     const uint64_t base = c.payload_offset + uint64_t(min(first_word, c.payload_words));
+    const uint32_t* const mine = p.payload + base;
+    const uint64_t after = p.payload_words - base;        // words of the caller's buffer from `mine` on
+    const uint32_t readable = after > 0xFFFFFFF0ull ? 0xFFFFFFF0u : static_cast<uint32_t>(after);
+    // streams whose every fetch stays inside the caller's buffer need no test per fetch: a valid
+    // stream asks for words below n_words + 16; a corrupt one is kept inside by the clamp
+    const bool roomy = __ballot(lane < N && n_words + 2u * kStreamFetchWords > readable) == 0ull;
+    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 16
+    auto fetch_inside = [&](uint32_t at, uint4& lo, uint4& hi) {
+        const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(mine + min(at, last_fetch));
+        lo = q[0];
+        hi = q[1];
+    };
     auto fetch = [&](uint32_t at, uint4& lo, uint4& hi) {
-        const uint64_t g = base + at;
-        if (g + kStreamFetchWords <= p.payload_words) {
-            const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(p.payload + g);
+        if (at + kStreamFetchWords <= readable) {
+            const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(mine + at);
             lo = q[0];
             hi = q[1];
         } else {
-            auto one = [&](uint32_t i) { return g + i < p.payload_words ? p.payload[g + i] : 0u; };
+            auto one = [&](uint32_t i) { return at + i < readable ? mine[at + i] : 0u; };
             lo = make_uint4(one(0), one(1), one(2), one(3));
             hi = make_uint4(one(4), one(5), one(6), one(7));
         }
@@ -348,78 +408,173 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
         ring[s0][lane] = lo.x; ring[s0 + 1][lane] = lo.y; ring[s0 + 2][lane] = lo.z; ring[s0 + 3][lane] = lo.w;
         ring[s0 + 4][lane] = hi.x; ring[s0 + 5][lane] = hi.y; ring[s0 + 6][lane] = hi.z; ring[s0 + 7][lane] = hi.w;
     };
-    uint4 glo, ghi;
-    fetch(0, glo, ghi);
-    land(0, glo, ghi);
-    fetch(kStreamFetchWords, glo, ghi);
-    land(kStreamFetchWords, glo, ghi);
+    {
+        uint4 glo, ghi;
+        fetch(0, glo, ghi);
+        land(0, glo, ghi);
+        fetch(kStreamFetchWords, glo, ghi);
+        land(kStreamFetchWords, glo, ghi);
+    }
     uint32_t fetched = 2u * kStreamFetchWords;            // words of the stream that are in the ring or before it
-    bool pending = false;                                 // glo, ghi hold words [fetched, fetched + 8) on their way
-
-    const uint64_t elem0 = chunk_elem0 + lane;
-    uint32_t channel = per_channel ? static_cast<uint32_t>(elem0 / lay.channel_len - channel0) : 0;   // within the chunk
-    uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
-    float scale = lay.scale;
-    if (per_channel) scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];
 
     uint32_t abit = 0;                                    // bits of the stream read so far
-    uint64_t out_at = c.out_offset + lane;
-    // K steps from a window loaded once: K * table_log + 31 bits must fit 128
-    auto run = [&](auto count) {
-        constexpr uint32_t K = decltype(count)::value;
+    // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
+    auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
         const uint32_t cw = abit >> 5;
-        uint32_t w0 = ring[cw & 15u][lane], w1 = ring[(cw + 1u) & 15u][lane];
-        uint32_t w2 = ring[(cw + 2u) & 15u][lane], w3 = ring[(cw + 3u) & 15u][lane];
+        w0 = ring[cw & 15u][lane];
+        w1 = ring[(cw + 1u) & 15u][lane];
+        w2 = ring[(cw + 2u) & 15u][lane];
+        w3 = ring[(cw + 3u) & 15u][lane];
         w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
         w3 >>= (abit & 31u);
-        uint32_t sum = 0;                                 // low byte: 31 - nb_bits over the K steps
-#pragma unroll
-        for (uint32_t k = 0; k < K; ++k) {
-            const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
-            const uint2 e = make_uint2(static_cast<uint32_t>(both), static_cast<uint32_t>(both >> 32));
-            const uint32_t bits = (__brev(w0) >> (e.x & 31u)) >> 1;        // first bit read is the top bit; none: 0
-            X = e.y + (bits << 3);                                         // Sec. II-A: newX + bits
-            const uint32_t nb = ~e.x;                                      // low five bits
-            w0 = __builtin_amdgcn_alignbit(w1, w0, nb);
-            w1 = __builtin_amdgcn_alignbit(w2, w1, nb);
-            w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
-            w3 >>= (nb & 31u);
-            sum += e.x;
-            if constexpr (OUT == ANSZP_OUT_U8) {
-                static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(e.x >> 8);
-            } else {
-                const float w = scale * __uint_as_float(e.x & 0xFFFF0000u);   // Sec. II-B: scale * (q - z)
-                if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = w;
-                else static_cast<uint16_t*>(p.out)[out_at] = static_cast<uint16_t>(bf16_rne(w));
-            }
-            out_at += N;
-            if (per_channel) {
-                in_channel += N;
-                if (in_channel >= lay.channel_len) {
-                    do { in_channel -= lay.channel_len; ++channel; } while (in_channel >= lay.channel_len);
-                    scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];   // beyond the chunk: never stored
-                }
-            }
+    };
+    // A block of K steps reads at most three words beyond its first.  Before the steps, a lane with
+    // room for eight more words in its ring asks for them; they have the K steps to arrive and are
+    // put into the ring after the steps (over words the lane has passed).
+    auto wants_words = [&]() { return fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords; };
+    // K steps of the fast form.  Step k may read table_log <= 12 bits, so of the 96 bits in w0..w2
+    // only those a later step of the block can still reach are kept in place.
+    auto steps_fast = [&](auto count, auto inside, auto&& emit) {
+        constexpr int K = static_cast<int>(decltype(count)::value);
+        static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of a block");
+        const bool fetching = wants_words();
+        uint4 glo, ghi;
+        if (fetching) {
+            if constexpr (decltype(inside)::value) fetch_inside(fetched, glo, ghi);
+            else fetch(fetched, glo, ghi);
         }
-        abit += 31u * K - (sum & 0xFFu);
-        // the fetch issued after the previous call has had K steps to arrive
-        if (pending) {
+        uint32_t w0, w1, w2, w3;
+        window(w0, w1, w2, w3);
+        w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
+        uint32_t sum = 0;                                 // low byte: 32 - nb_bits over the K steps
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
+            const uint32_t lo = static_cast<uint32_t>(both), hi = static_cast<uint32_t>(both >> 32);
+            const uint32_t bits = w0 >> (lo & 31u);                        // first bit read is the top bit
+            X = hi + (bits << 3);                                          // Sec. II-A: newX + bits
+            if (k <= K - 2) w0 = __builtin_amdgcn_alignbit(w0, w1, lo);
+            if (k <= K - 4) w1 = __builtin_amdgcn_alignbit(w1, w2, lo);
+            if (k <= K - 7) w2 = __builtin_amdgcn_alignbit(w2, 0u, lo);
+            sum += lo;
+            emit(k, lo);
+        }
+        abit += 32u * K - (sum & 0xFFu);
+        if (fetching) {
             land(fetched, glo, ghi);
             fetched += kStreamFetchWords;
-            pending = false;
-        }
-        if (fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords) {
-            fetch(fetched, glo, ghi);
-            pending = true;
         }
     };
+
     if (lane < N) {
-        uint32_t t = 0;
-        for (; t + 8u <= full_steps; t += 8u) run(std::integral_constant<uint32_t, 8u>{});
-        for (; t < full_steps; ++t) run(std::integral_constant<uint32_t, 1u>{});
-        if (len > full_steps) run(std::integral_constant<uint32_t, 1u>{});     // ragged tail: streams 0 .. n mod N - 1
+        const bool aligned = !per_channel || (lay.channel_len % kWave == 0u && in_channel0 % kWave == 0u);
+        if (fast && aligned && uint64_t(c.n_symbols) * kElemBytes < (1ull << 31)) {
+            // every wavefront-step lies inside one channel: one scale per block, weights of step k at
+            // chunk_out + at + k * 64 * kElemBytes
+            char* const chunk_out = static_cast<char*>(p.out) + c.out_offset * kElemBytes;
+            uint32_t at = lane * kElemBytes;
+            float scale = per_channel ? chunk_scales[wave][0] : lay.scale;
+            uint32_t channel = 0;                                          // within the chunk
+            uint32_t left = uniform(per_channel ? (lay.channel_len - in_channel0) / kWave : 0xFFFFFFFFu);   // steps left under this scale
+            const uint32_t steps = uniform(full_steps);
+            auto emit = [&](int k, uint32_t lo) {
+                char* const q = chunk_out + at + static_cast<uint32_t>(k) * (kWave * kElemBytes);
+                if constexpr (OUT == ANSZP_OUT_U8) *reinterpret_cast<uint8_t*>(q) = static_cast<uint8_t>(lo >> 8);
+                else if constexpr (OUT == ANSZP_OUT_F32) *reinterpret_cast<float*>(q) = scaled_high_half(lo, scale);
+                else *reinterpret_cast<__bf16*>(q) = static_cast<__bf16>(scaled_high_half(lo, scale));
+            };
+            auto all_steps = [&](auto inside) {
+                uint32_t t = 0;
+                while (t < steps) {
+                    uint32_t seg = min(steps - t, left);
+                    t += seg;
+                    left -= seg;
+                    for (; seg >= 8u; seg -= 8u) { steps_fast(std::integral_constant<int, 8>{}, inside, emit); at += 8u * kWave * kElemBytes; }
+                    if (seg >= 4u) { steps_fast(std::integral_constant<int, 4>{}, inside, emit); at += 4u * kWave * kElemBytes; seg -= 4u; }
+                    for (; seg; --seg) { steps_fast(std::integral_constant<int, 1>{}, inside, emit); at += kWave * kElemBytes; }
+                    if (left == 0u) {
+                        ++channel;
+                        left = uniform(lay.channel_len / kWave);
+                        scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];              // beyond the chunk: never used
+                    }
+                }
+                if (len > full_steps) steps_fast(std::integral_constant<int, 1>{}, inside, emit);          // ragged tail: streams 0 .. n mod N - 1
+            };
+            if (roomy) all_steps(std::true_type{});
+            else all_steps(std::false_type{});
+        } else {
+            // a scale per lane, followed from element to element
+            const uint64_t elem0 = chunk_elem0 + lane;
+            uint32_t channel = per_channel ? static_cast<uint32_t>(elem0 / lay.channel_len - channel0) : 0;   // within the chunk
+            uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
+            float scale = lay.scale;
+            if (per_channel) scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];
+            uint64_t out_at = c.out_offset + lane;
+            auto next_element = [&]() {
+                out_at += N;
+                if (per_channel) {
+                    in_channel += N;
+                    if (in_channel >= lay.channel_len) {
+                        do { in_channel -= lay.channel_len; ++channel; } while (in_channel >= lay.channel_len);
+                        scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];   // beyond the chunk: never stored
+                    }
+                }
+            };
+            auto emit_fast = [&](int, uint32_t lo) {
+                if constexpr (OUT == ANSZP_OUT_U8) static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(lo >> 8);
+                else if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = scaled_high_half(lo, scale);
+                else static_cast<__bf16*>(p.out)[out_at] = static_cast<__bf16>(scaled_high_half(lo, scale));
+                next_element();
+            };
+            // K steps of the plain form from a window loaded once: K * table_log + 31 bits must fit 128
+            auto steps_plain = [&](auto count) {
+                constexpr int K = static_cast<int>(decltype(count)::value);
+                const bool fetching = wants_words();
+                uint4 glo, ghi;
+                if (fetching) fetch(fetched, glo, ghi);
+                uint32_t w0, w1, w2, w3;
+                window(w0, w1, w2, w3);
+                uint32_t sum = 0;                                 // low byte: 31 - nb_bits over the K steps
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
+                    const uint32_t lo = static_cast<uint32_t>(both), hi = static_cast<uint32_t>(both >> 32);
+                    const uint32_t bits = (__brev(w0) >> (lo & 31u)) >> 1;         // first bit read is the top bit; none: 0
+                    X = hi + (bits << 3);                                          // Sec. II-A: newX + bits
+                    const uint32_t nb = ~lo;                                       // low five bits
+                    w0 = __builtin_amdgcn_alignbit(w1, w0, nb);
+                    w1 = __builtin_amdgcn_alignbit(w2, w1, nb);
+                    w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
+                    w3 >>= (nb & 31u);
+                    sum += lo;
+                    if constexpr (OUT == ANSZP_OUT_U8) {
+                        static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(lo >> 8);
+                    } else {
+                        const float w = scale * __uint_as_float(lo & 0xFFFF0000u);   // Sec. II-B: scale * (q - z)
+                        if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = w;
+                        else static_cast<uint16_t*>(p.out)[out_at] = static_cast<uint16_t>(bf16_rne(w));
+                    }
+                    next_element();
+                }
+                abit += 31u * K - (sum & 0xFFu);
+                if (fetching) {
+                    land(fetched, glo, ghi);
+                    fetched += kStreamFetchWords;
+                }
+            };
+            uint32_t t = 0;
+            if (fast) {
+                for (; t + 8u <= full_steps; t += 8u) steps_fast(std::integral_constant<int, 8>{}, std::false_type{}, emit_fast);
+                for (; t < full_steps; ++t) steps_fast(std::integral_constant<int, 1>{}, std::false_type{}, emit_fast);
+                if (len > full_steps) steps_fast(std::integral_constant<int, 1>{}, std::false_type{}, emit_fast);
+            } else {
+                for (; t + 8u <= full_steps; t += 8u) steps_plain(std::integral_constant<int, 8>{});
+                for (; t < full_steps; ++t) steps_plain(std::integral_constant<int, 1>{});
+                if (len > full_steps) steps_plain(std::integral_constant<int, 1>{});     // ragged tail: streams 0 .. n mod N - 1
+            }
+        }
         if (X != table0) err |= ANSZP_ST_BAD_STATE;          // state 0
         if (((abit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
