@@ -26,6 +26,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 namespace {
@@ -255,45 +256,76 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
 // III-B at scale).  The plain loop above reads a stream's words four bytes at a time; with two
 // thousand streams per CU each of those reads brings a whole cache line from HBM again, and the
 // launch is bound by re-reading its own input.  Here a stream's words come through a ring in LDS,
-// 32 bytes per fetch and one fetch ahead, and a lane keeps a window of the stream in registers that
-// it reloads from the ring every K steps (no per-step refill test: lanes need their refills at
-// different steps, so such a test would run its body at nearly every step).
+// 32 bytes per fetch, and a lane keeps a window of the stream in registers that it reloads from
+// the ring every K steps (no per-step refill test: lanes need their refills at different steps, so
+// such a test would run its body at nearly every step).
 //
-// The launch is bound by the instructions a step issues, so the LDS entries are derived from the
-// paper's triples (Sec. II-A) while staging, in one of two forms:
-//   fast form (64 streams per chunk, no state of either table reads zero bits):
-//     lo: bits 0..4 32 - nb_bits | bits 8..15 symbol | bits 16..31 (symbol - zero_point) as fp16 (exact)
-//     the window holds the stream most significant bit first: bits = window >> (32 - nb_bits), and
-//     one funnel shift per window register consumes them
-//   plain form: lo: bits 0..4 31 - nb_bits | bits 8..15 symbol | bits 16..31 the same as bf16;
-//     least significant bit first, every shift written so that nb_bits = 0 works
-//   hi, both forms: LDS byte address of the entry of state newX
+// Loads and stores of a wavefront complete in issue order behind one counter, and when the whole
+// chip writes weights a fetch takes longer than a block of 8 steps.  So the ring holds 32 words
+// and, in the main loop, a fetch is asked for before 24 steps and put into the ring after them.
+// That needs LDS: the entries of the two tables a workgroup may need are 4 bytes, derived from the
+// paper's triples (Sec. II-A) while staging:
+//   bits 0..4   fast form (64 streams per chunk, no state of either table reads zero bits):
+//               32 - nb_bits; the window holds the stream most significant bit first,
+//               bits = window >> (32 - nb_bits), one funnel shift per window register consumes them
+//               plain form: 31 - nb_bits; least significant bit first, every shift written so that
+//               nb_bits = 0 works
+//   bits 5..17  index, in the workgroup's two tables, of the entry of state newX
+//   bits 19..31 weights out: the upper 13 bits of (symbol - zero_point) as fp16 (exact: |.| <= 255
+//               leaves the lower 3 bits zero); symbols out: bits 19..26 the symbol
 // With the fast form, when every wavefront-step lies inside one output channel, the scale is a
 // wavefront-uniform value per block of steps and the store address is one base plus immediates.
-constexpr uint32_t kStreamRingWords = 16u;      // per stream, in LDS
+constexpr int kStreamWaves = 15;                // per workgroup, one chunk each
+constexpr uint32_t kStreamRingWords = 32u;      // per stream, in LDS
 constexpr uint32_t kStreamFetchWords = 8u;      // per fetch from global memory
-constexpr uint32_t kStreamScales = 128u;        // per-channel scales of one chunk kept in LDS
-typedef uint4 __attribute__((aligned(4))) uint4_word_aligned;
+typedef uint32_t words4 __attribute__((ext_vector_type(4)));            // four consecutive registers
+typedef words4 __attribute__((aligned(4))) words4_word_aligned;
+typedef __attribute__((address_space(3))) uint32_t lds_uint32_t;
 
-// scale * (q - z) (Sec. II-B) with q - z read as fp16 from the high half of `entry_lo`: the product
-// is rounded once, like the plain multiplication; the addend -0 keeps the sign of a zero product.
-__device__ __forceinline__ float scaled_high_half(uint32_t entry_lo, float scale) {
+// scale * (q - z) (Sec. II-B) with q - z read as fp16 from the high half of `entry` (lower bits
+// cleared): the product is rounded once, like the plain multiplication; the addend -0 keeps the
+// sign of a zero product.
+__device__ __forceinline__ float scaled_high_half(uint32_t entry, float scale) {
     float w;
-    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(w) : "v"(entry_lo), "v"(scale), "v"(-0.0f));
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(w) : "v"(entry & 0xFFF80000u), "v"(scale), "v"(-0.0f));
     return w;
 }
 
+// Byte offset, from the first of the workgroup's entries, of the entry of state newX + bits (Sec.
+// II-A), newX taken from `entry`.  Written out so that the field extraction runs beside the
+// extraction of `bits` and one instruction follows both.
+__device__ __forceinline__ uint32_t next_entry_offset(uint32_t entry, uint32_t bits) {
+    uint32_t index, offset;
+    asm("v_bfe_u32 %0, %1, 5, 13" : "=v"(index) : "v"(entry));
+    asm("v_add_lshl_u32 %0, %1, %2, 2" : "=v"(offset) : "v"(index), "v"(bits));
+    return offset;
+}
+
+// First chunk of workgroup g when n chunks are dealt evenly to `groups` workgroups.
+__host__ __device__ __forceinline__ uint32_t stream_group_begin(uint32_t g, uint32_t n, uint32_t groups) {
+    return static_cast<uint32_t>(uint64_t(g) * n / groups);
+}
+
 template <int OUT>
-__global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeParams p, uint32_t n_chunks) {
-    __shared__ uint2 table[2][1u << ANSZP_MAX_TABLE_LOG];
-    __shared__ uint32_t rings[kSharedWaves][kStreamRingWords][kWave];   // word s of lane l at [wave][s mod 16][l]
-    __shared__ float chunk_scales[kSharedWaves][kStreamScales];          // per-channel scales of each wavefront's chunk
-    constexpr uint32_t kThreads = kSharedWaves * kWave;
-    constexpr uint32_t kPerThread = (1u << ANSZP_MAX_TABLE_LOG) / kThreads;
+__global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeParams p, uint32_t n_chunks, uint32_t n_groups) {
+    constexpr uint32_t kStates = 1u << ANSZP_MAX_TABLE_LOG;
+    // one object, the tables first: their entries are then within reach of an LDS instruction's offset field
+    struct Lds {
+        uint32_t table[2][kStates];
+        uint32_t rings[kStreamWaves][kStreamRingWords][kWave];           // word s of lane l at [wave][s mod 32][l]
+    };
+    __shared__ Lds lds;
+    auto& table = lds.table;
+    auto& rings = lds.rings;
+    constexpr uint32_t kThreads = kStreamWaves * kWave;
+    constexpr uint32_t kPerThread = (kStates + kThreads - 1u) / kThreads;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : OUT == ANSZP_OUT_F32 ? 4u : 2u;
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t first = blockIdx.x * kSharedWaves, last = min(first + kSharedWaves, n_chunks) - 1u;
+    const uint32_t first = stream_group_begin(blockIdx.x, n_chunks, n_groups);
+    const uint32_t count = min(stream_group_begin(blockIdx.x + 1u, n_chunks, n_groups) - first, uint32_t(kStreamWaves));
+    if (count == 0u) return;
+    const uint32_t last = first + count - 1u;
     const uint32_t L = 1u << p.table_log, N = p.n_streams;
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
     const bool have_a = layer_a < p.n_tables, have_b = layer_b != layer_a && layer_b < p.n_tables;
@@ -301,75 +333,78 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     // the paper's triples of both tables, held in registers until the form of the entries is known
     const uint32_t* src_a = p.tables + (uint64_t(have_a ? layer_a : 0u) << (p.table_log + 2)) + 2u * L;
     const uint32_t* src_b = p.tables + (uint64_t(have_b ? layer_b : 0u) << (p.table_log + 2)) + 2u * L;
-    uint32_t ta0 = 0x00010000u, ta1 = ta0, ta2 = ta0, ta3 = ta0, tb0 = ta0, tb1 = ta0, tb2 = ta0, tb3 = ta0;
-    static_assert(kPerThread == 4, "four triples of each table per thread");
+    constexpr uint32_t kNoTriple = 0x00010000u;           // reads one bit
+    uint32_t ta0 = kNoTriple, ta1 = kNoTriple, ta2 = kNoTriple, ta3 = kNoTriple, ta4 = kNoTriple;
+    uint32_t tb0 = kNoTriple, tb1 = kNoTriple, tb2 = kNoTriple, tb3 = kNoTriple, tb4 = kNoTriple;
+    static_assert(kPerThread == 5, "five triples of each table per thread");
     if (have_a) {
         if (tid < L) ta0 = src_a[tid];
         if (tid + kThreads < L) ta1 = src_a[tid + kThreads];
         if (tid + 2u * kThreads < L) ta2 = src_a[tid + 2u * kThreads];
         if (tid + 3u * kThreads < L) ta3 = src_a[tid + 3u * kThreads];
+        if (tid + 4u * kThreads < L) ta4 = src_a[tid + 4u * kThreads];
     }
     if (have_b) {
         if (tid < L) tb0 = src_b[tid];
         if (tid + kThreads < L) tb1 = src_b[tid + kThreads];
         if (tid + 2u * kThreads < L) tb2 = src_b[tid + 2u * kThreads];
         if (tid + 3u * kThreads < L) tb3 = src_b[tid + 3u * kThreads];
+        if (tid + 4u * kThreads < L) tb4 = src_b[tid + 4u * kThreads];
     }
     auto reads_no_bits = [](uint32_t e) { return ((e >> 16) & 0xFFu) == 0u; };
-    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) |
-                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3);
+    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) | reads_no_bits(ta4) |
+                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3) | reads_no_bits(tb4);
     const bool fast = !__syncthreads_or(some_zero) && N == kWave;
-    auto place = [&](uint32_t e, uint32_t i, uint2* dst, uint32_t z) {
+    auto place = [&](uint32_t e, uint32_t i, uint32_t which, uint32_t z) {
         if (i >= L) return;
         const uint32_t sym = e >> 24, nb = min((e >> 16) & 0xFFu, 31u);
-        const int centred = static_cast<int>(sym) - static_cast<int>(z);                       // |.| <= 255: exact in fp16 and bf16
-        uint32_t lo;
-        if (fast) lo = ((32u - nb) & 31u) | (sym << 8) |
-                       (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, static_cast<_Float16>(centred))) << 16);
-        else lo = (31u - nb) | (sym << 8) | (__float_as_uint(static_cast<float>(centred)) & 0xFFFF0000u);
-        dst[i] = make_uint2(lo, lds_address(dst) + ((e & (L - 1u)) << 3));
+        const int centred = static_cast<int>(sym) - static_cast<int>(z);                       // |.| <= 255
+        const uint32_t shift = fast ? (32u - nb) & 31u : 31u - nb;
+        const uint32_t upper = OUT == ANSZP_OUT_U8 ? sym << 19
+            : static_cast<uint32_t>(__builtin_bit_cast(uint16_t, static_cast<_Float16>(centred))) << 16;
+        table[which][i] = shift | ((which * kStates + (e & (L - 1u))) << 5) | upper;
     };
     if (have_a) {
         const uint32_t z = p.layers[layer_a].zero_point;
-        place(ta0, tid, table[0], z); place(ta1, tid + kThreads, table[0], z);
-        place(ta2, tid + 2u * kThreads, table[0], z); place(ta3, tid + 3u * kThreads, table[0], z);
+        place(ta0, tid, 0, z); place(ta1, tid + kThreads, 0, z); place(ta2, tid + 2u * kThreads, 0, z);
+        place(ta3, tid + 3u * kThreads, 0, z); place(ta4, tid + 4u * kThreads, 0, z);
     }
     if (have_b) {
         const uint32_t z = p.layers[layer_b].zero_point;
-        place(tb0, tid, table[1], z); place(tb1, tid + kThreads, table[1], z);
-        place(tb2, tid + 2u * kThreads, table[1], z); place(tb3, tid + 3u * kThreads, table[1], z);
+        place(tb0, tid, 1, z); place(tb1, tid + kThreads, 1, z); place(tb2, tid + 2u * kThreads, 1, z);
+        place(tb3, tid + 3u * kThreads, 1, z); place(tb4, tid + 4u * kThreads, 1, z);
     }
     __syncthreads();
-    if (first + wave > last) return;
+    if (wave >= count) return;
     const anszp_chunk_t c = p.chunks[first + wave];
     if (!chunk_in_bounds(p, c)) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
     const anszp_layer_t lay = p.layers[c.layer_id];
-    // per-channel scales come from LDS: a load from global memory inside the loop would make every
-    // step wait for the stores before it (loads and stores share one in-order counter)
     const bool per_channel = lay.channel_len != 0;
     const uint64_t chunk_elem0 = c.out_offset - lay.out_base;
     const uint64_t channel0 = per_channel ? chunk_elem0 / lay.channel_len : 0;           // within the layer
     const uint32_t in_channel0 = per_channel ? static_cast<uint32_t>(chunk_elem0 - channel0 * lay.channel_len) : 0;
-    const uint64_t channels = per_channel && c.n_symbols ? (chunk_elem0 + c.n_symbols - 1u) / lay.channel_len - channel0 + 1u : 0;
-    if ((c.layer_id != layer_a && c.layer_id != layer_b) || channels > kStreamScales) {
-        // a third layer in one workgroup, or more channels than the LDS holds: the plain loop, table
-        // from global memory
+    auto scale_of = [&](uint64_t channel) {               // channel counted within the chunk
+        const uint64_t ch = lay.scales_offset + channel0 + channel;
+        float v = ch < p.n_scales ? p.scales[ch] : 0.0f;
+        asm volatile("" : "+v"(v));                       // the wait for this load stands here, not at a later write of its register
+        return v;
+    };
+    if (c.layer_id != layer_a && c.layer_id != layer_b) {
+        // a third layer in one workgroup: the plain loop, table from global memory
         const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
-    for (uint32_t i = lane; i < channels; i += kWave) {
-        const uint64_t ch = lay.scales_offset + channel0 + i;
-        chunk_scales[wave][i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
-    }
     uint32_t (*ring)[kWave] = rings[wave];
+    const uint32_t entries = lds_address(&table[0][0]);
+    auto entry_at = [&](uint32_t offset) { return *reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(entries + offset)); };
 
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
-    const uint32_t table0 = lds_address(c.layer_id == layer_a ? table[0] : table[1]);
-    uint32_t X = table0 + ((hdr & (L - 1u)) << 3);       // LDS byte address of the current state's entry
+    const uint32_t state0 = c.layer_id == layer_a ? 0u : 4u * kStates;   // byte offset of the entry of state 0
+    uint32_t X = state0 + ((hdr & (L - 1u)) << 2);       // byte offset of the current state's entry
     const uint32_t n_words = hdr >> 16;
     uint32_t total_words;
     const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
@@ -384,85 +419,93 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     const uint64_t after = p.payload_words - base;        // words of the caller's buffer from `mine` on
     const uint32_t readable = after > 0xFFFFFFF0ull ? 0xFFFFFFF0u : static_cast<uint32_t>(after);
     // streams whose every fetch stays inside the caller's buffer need no test per fetch: a valid
-    // stream asks for words below n_words + 16; a corrupt one is kept inside by the clamp
-    const bool roomy = __ballot(lane < N && n_words + 2u * kStreamFetchWords > readable) == 0ull;
-    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 16
-    auto fetch_inside = [&](uint32_t at, uint4& lo, uint4& hi) {
-        const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(mine + min(at, last_fetch));
-        lo = q[0];
-        hi = q[1];
+    // stream asks for words below n_words + 40; a corrupt one is kept inside by the clamp
+    const bool roomy = __ballot(lane < N && n_words + kStreamRingWords + kStreamFetchWords > readable) == 0ull;
+    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 40
+    // These loads are issued by hand and waited for by hand: left to the compiler, the wait for
+    // them lands right behind their issue in some of the loops below.
+    auto fetch_inside = [&](uint32_t at, words4& lo, words4& hi) {
+        const uint32_t* const q = mine + min(at, last_fetch);
+        asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
+                     : "=&v"(lo), "=&v"(hi) : "v"(q) : "memory");
     };
-    auto fetch = [&](uint32_t at, uint4& lo, uint4& hi) {
+    auto fetch = [&](uint32_t at, words4& lo, words4& hi) {
         if (at + kStreamFetchWords <= readable) {
-            const uint4_word_aligned* q = reinterpret_cast<const uint4_word_aligned*>(mine + at);
+            const words4_word_aligned* q = reinterpret_cast<const words4_word_aligned*>(mine + at);
             lo = q[0];
             hi = q[1];
         } else {
             auto one = [&](uint32_t i) { return at + i < readable ? mine[at + i] : 0u; };
-            lo = make_uint4(one(0), one(1), one(2), one(3));
-            hi = make_uint4(one(4), one(5), one(6), one(7));
+            lo = words4{one(0), one(1), one(2), one(3)};
+            hi = words4{one(4), one(5), one(6), one(7)};
         }
     };
-    auto land = [&](uint32_t at, const uint4& lo, const uint4& hi) {      // at is a multiple of 8: no wrap inside
+    auto land = [&](uint32_t at, const words4& lo, const words4& hi) {      // at is a multiple of 8: no wrap inside
         const uint32_t s0 = at & (kStreamRingWords - 1u);
         ring[s0][lane] = lo.x; ring[s0 + 1][lane] = lo.y; ring[s0 + 2][lane] = lo.z; ring[s0 + 3][lane] = lo.w;
         ring[s0 + 4][lane] = hi.x; ring[s0 + 5][lane] = hi.y; ring[s0 + 6][lane] = hi.z; ring[s0 + 7][lane] = hi.w;
     };
-    {
-        uint4 glo, ghi;
-        fetch(0, glo, ghi);
-        land(0, glo, ghi);
-        fetch(kStreamFetchWords, glo, ghi);
-        land(kStreamFetchWords, glo, ghi);
+    for (uint32_t at = 0; at < kStreamRingWords; at += kStreamFetchWords) {
+        words4 glo, ghi;
+        fetch(at, glo, ghi);
+        land(at, glo, ghi);
     }
-    uint32_t fetched = 2u * kStreamFetchWords;            // words of the stream that are in the ring or before it
+    uint32_t fetched = kStreamRingWords;                  // words of the stream that are in the ring or before it
 
     uint32_t abit = 0;                                    // bits of the stream read so far
     // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
     auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
         const uint32_t cw = abit >> 5;
-        w0 = ring[cw & 15u][lane];
-        w1 = ring[(cw + 1u) & 15u][lane];
-        w2 = ring[(cw + 2u) & 15u][lane];
-        w3 = ring[(cw + 3u) & 15u][lane];
+        w0 = ring[cw & 31u][lane];
+        w1 = ring[(cw + 1u) & 31u][lane];
+        w2 = ring[(cw + 2u) & 31u][lane];
+        w3 = ring[(cw + 3u) & 31u][lane];
         w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
         w3 >>= (abit & 31u);
     };
-    // A block of K steps reads at most three words beyond its first.  Before the steps, a lane with
-    // room for eight more words in its ring asks for them; they have the K steps to arrive and are
-    // put into the ring after the steps (over words the lane has passed).
-    auto wants_words = [&]() { return fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords; };
-    // K steps of the fast form.  Step k may read table_log <= 12 bits, so of the 96 bits in w0..w2
-    // only those a later step of the block can still reach are kept in place.
-    auto steps_fast = [&](auto count, auto inside, auto&& emit) {
-        constexpr int K = static_cast<int>(decltype(count)::value);
-        static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of a block");
+    auto words_ahead = [&]() { return fetched - (abit >> 5); };           // of the lane's position, in the ring
+    // a lane asks for eight more words when the ring has room for them (they replace words it has passed)
+    auto wants_words = [&]() { return words_ahead() <= kStreamRingWords - kStreamFetchWords; };
+    // K steps of the fast form from a window loaded once.  A step may read table_log <= 12 bits,
+    // so of the 96 bits in w0..w2 only those a later step of the K can still reach are kept in place.
+    auto run_fast = [&](auto count_tag, auto&& emit) {
+        constexpr int K = static_cast<int>(decltype(count_tag)::value);
+        static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of K steps");
+        uint32_t w0, w1, w2, w3;
+        window(w0, w1, w2, w3);
+        w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
+        uint32_t sum = 0;                                 // 32 - nb_bits over the K steps
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t e = entry_at(X);
+            const uint32_t bits = w0 >> (e & 31u);                         // first bit read is the top bit
+            X = next_entry_offset(e, bits);
+            if (k <= K - 2) w0 = __builtin_amdgcn_alignbit(w0, w1, e);
+            if (k <= K - 4) w1 = __builtin_amdgcn_alignbit(w1, w2, e);
+            if (k <= K - 7) w2 = __builtin_amdgcn_alignbit(w2, 0u, e);
+            sum += e & 31u;
+            emit(k, e);
+        }
+        abit += 32u * K - sum;
+    };
+    // One block: K steps, with a fetch asked for before them and put into the ring after them.
+    // A block reads at most three words beyond its first one, a lane enters it at least four
+    // words ahead.  `stores_per_step`: global stores emit() issues per step (they are behind the
+    // fetch in the one counter of outstanding accesses).
+    auto block_fast = [&](auto count_tag, auto inside, auto stores_per_step, auto&& emit) {
+        constexpr int K = static_cast<int>(decltype(count_tag)::value);
         const bool fetching = wants_words();
-        uint4 glo, ghi;
+        words4 glo, ghi;
         if (fetching) {
             if constexpr (decltype(inside)::value) fetch_inside(fetched, glo, ghi);
             else fetch(fetched, glo, ghi);
         }
-        uint32_t w0, w1, w2, w3;
-        window(w0, w1, w2, w3);
-        w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
-        uint32_t sum = 0;                                 // low byte: 32 - nb_bits over the K steps
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
-            const uint32_t lo = static_cast<uint32_t>(both), hi = static_cast<uint32_t>(both >> 32);
-            const uint32_t bits = w0 >> (lo & 31u);                        // first bit read is the top bit
-            X = hi + (bits << 3);                                          // Sec. II-A: newX + bits
-            if (k <= K - 2) w0 = __builtin_amdgcn_alignbit(w0, w1, lo);
-            if (k <= K - 4) w1 = __builtin_amdgcn_alignbit(w1, w2, lo);
-            if (k <= K - 7) w2 = __builtin_amdgcn_alignbit(w2, 0u, lo);
-            sum += lo;
-            emit(k, lo);
-        }
-        abit += 32u * K - (sum & 0xFFu);
+        run_fast(count_tag, emit);
         if (fetching) {
+            if constexpr (decltype(inside)::value)
+                asm volatile("s_waitcnt vmcnt(%0)" : : "n"(K * decltype(stores_per_step)::value) : "memory");
             land(fetched, glo, ghi);
             fetched += kStreamFetchWords;
         }
@@ -471,94 +514,103 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
     if (lane < N) {
         const bool aligned = !per_channel || (lay.channel_len % kWave == 0u && in_channel0 % kWave == 0u);
         if (fast && aligned && uint64_t(c.n_symbols) * kElemBytes < (1ull << 31)) {
-            // every wavefront-step lies inside one channel: one scale per block, weights of step k at
-            // chunk_out + at + k * 64 * kElemBytes
+            // every wavefront-step lies inside one channel: one scale per run of steps, weights of
+            // step k at chunk_out + at + k * 64 * kElemBytes
             char* const chunk_out = static_cast<char*>(p.out) + c.out_offset * kElemBytes;
             uint32_t at = lane * kElemBytes;
-            float scale = per_channel ? chunk_scales[wave][0] : lay.scale;
+            // (the scale goes through a scalar register: the wait for its load then stands here, not in the blocks)
+            auto uniform_scale = [&](uint32_t ch) { return __uint_as_float(uniform(__float_as_uint(scale_of(ch)))); };
+            float scale = per_channel ? uniform_scale(0) : lay.scale;
             uint32_t channel = 0;                                          // within the chunk
             uint32_t left = uniform(per_channel ? (lay.channel_len - in_channel0) / kWave : 0xFFFFFFFFu);   // steps left under this scale
             const uint32_t steps = uniform(full_steps);
-            auto emit = [&](int k, uint32_t lo) {
-                char* const q = chunk_out + at + static_cast<uint32_t>(k) * (kWave * kElemBytes);
-                if constexpr (OUT == ANSZP_OUT_U8) *reinterpret_cast<uint8_t*>(q) = static_cast<uint8_t>(lo >> 8);
-                else if constexpr (OUT == ANSZP_OUT_F32) *reinterpret_cast<float*>(q) = scaled_high_half(lo, scale);
-                else *reinterpret_cast<__bf16*>(q) = static_cast<__bf16>(scaled_high_half(lo, scale));
+            auto emit_at = [&](uint32_t step, uint32_t e) {
+                char* const q = chunk_out + at + step * (kWave * kElemBytes);
+                if constexpr (OUT == ANSZP_OUT_U8) *reinterpret_cast<uint8_t*>(q) = static_cast<uint8_t>(e >> 19);
+                else if constexpr (OUT == ANSZP_OUT_F32) *reinterpret_cast<float*>(q) = scaled_high_half(e, scale);
+                else *reinterpret_cast<__bf16*>(q) = static_cast<__bf16>(scaled_high_half(e, scale));
             };
+            auto emit = [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k), e); };
             auto all_steps = [&](auto inside) {
                 uint32_t t = 0;
                 while (t < steps) {
                     uint32_t seg = min(steps - t, left);
                     t += seg;
                     left -= seg;
-                    for (; seg >= 8u; seg -= 8u) { steps_fast(std::integral_constant<int, 8>{}, inside, emit); at += 8u * kWave * kElemBytes; }
-                    if (seg >= 4u) { steps_fast(std::integral_constant<int, 4>{}, inside, emit); at += 4u * kWave * kElemBytes; seg -= 4u; }
-                    for (; seg; --seg) { steps_fast(std::integral_constant<int, 1>{}, inside, emit); at += kWave * kElemBytes; }
+                    if constexpr (decltype(inside)::value) {
+                        // 24 steps around one fetch: they read at most nine words beyond the first
+                        while (seg >= 24u && __ballot(words_ahead() < 10u) == 0ull) {
+                            const bool fetching = wants_words();
+                            words4 glo, ghi;
+                            if (fetching) fetch_inside(fetched, glo, ghi);
+                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k), e); });
+                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 8u, e); });
+                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 16u, e); });
+                            if (fetching) {
+                                asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+                                land(fetched, glo, ghi);
+                                fetched += kStreamFetchWords;
+                            }
+                            at += 24u * kWave * kElemBytes;
+                            seg -= 24u;
+                        }
+                    }
+                    for (; seg >= 8u; seg -= 8u) { block_fast(std::integral_constant<int, 8>{}, inside, std::integral_constant<int, 1>{}, emit); at += 8u * kWave * kElemBytes; }
+                    if (seg >= 4u) { block_fast(std::integral_constant<int, 4>{}, inside, std::integral_constant<int, 1>{}, emit); at += 4u * kWave * kElemBytes; seg -= 4u; }
+                    for (; seg; --seg) { block_fast(std::integral_constant<int, 1>{}, inside, std::integral_constant<int, 1>{}, emit); at += kWave * kElemBytes; }
                     if (left == 0u) {
                         ++channel;
                         left = uniform(lay.channel_len / kWave);
-                        scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];              // beyond the chunk: never used
+                        scale = uniform_scale(channel);
                     }
                 }
-                if (len > full_steps) steps_fast(std::integral_constant<int, 1>{}, inside, emit);          // ragged tail: streams 0 .. n mod N - 1
+                if (len > full_steps) block_fast(std::integral_constant<int, 1>{}, inside, std::integral_constant<int, 1>{}, emit);   // ragged tail: streams 0 .. n mod N - 1
             };
             if (roomy) all_steps(std::true_type{});
             else all_steps(std::false_type{});
         } else {
             // a scale per lane, followed from element to element
             const uint64_t elem0 = chunk_elem0 + lane;
-            uint32_t channel = per_channel ? static_cast<uint32_t>(elem0 / lay.channel_len - channel0) : 0;   // within the chunk
+            uint64_t channel = per_channel ? elem0 / lay.channel_len - channel0 : 0;                   // within the chunk
             uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
-            float scale = lay.scale;
-            if (per_channel) scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];
+            float scale = per_channel ? scale_of(channel) : lay.scale;
             uint64_t out_at = c.out_offset + lane;
-            auto next_element = [&]() {
+            auto emit_one = [&](int, uint32_t e) {
+                if constexpr (OUT == ANSZP_OUT_U8) static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(e >> 19);
+                else if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = scaled_high_half(e, scale);
+                else static_cast<__bf16*>(p.out)[out_at] = static_cast<__bf16>(scaled_high_half(e, scale));
                 out_at += N;
                 if (per_channel) {
                     in_channel += N;
                     if (in_channel >= lay.channel_len) {
                         do { in_channel -= lay.channel_len; ++channel; } while (in_channel >= lay.channel_len);
-                        scale = chunk_scales[wave][min(channel, kStreamScales - 1u)];   // beyond the chunk: never stored
+                        scale = scale_of(channel);                         // beyond the layer's scales: 0, never stored
                     }
                 }
             };
-            auto emit_fast = [&](int, uint32_t lo) {
-                if constexpr (OUT == ANSZP_OUT_U8) static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(lo >> 8);
-                else if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = scaled_high_half(lo, scale);
-                else static_cast<__bf16*>(p.out)[out_at] = static_cast<__bf16>(scaled_high_half(lo, scale));
-                next_element();
-            };
             // K steps of the plain form from a window loaded once: K * table_log + 31 bits must fit 128
-            auto steps_plain = [&](auto count) {
-                constexpr int K = static_cast<int>(decltype(count)::value);
+            auto block_plain = [&](auto count_tag) {
+                constexpr int K = static_cast<int>(decltype(count_tag)::value);
                 const bool fetching = wants_words();
-                uint4 glo, ghi;
+                words4 glo, ghi;
                 if (fetching) fetch(fetched, glo, ghi);
                 uint32_t w0, w1, w2, w3;
                 window(w0, w1, w2, w3);
-                uint32_t sum = 0;                                 // low byte: 31 - nb_bits over the K steps
+                uint32_t sum = 0;                                 // 31 - nb_bits over the K steps
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
-                    const uint64_t both = *reinterpret_cast<const lds_uint64_t*>(static_cast<uintptr_t>(X));
-                    const uint32_t lo = static_cast<uint32_t>(both), hi = static_cast<uint32_t>(both >> 32);
-                    const uint32_t bits = (__brev(w0) >> (lo & 31u)) >> 1;         // first bit read is the top bit; none: 0
-                    X = hi + (bits << 3);                                          // Sec. II-A: newX + bits
-                    const uint32_t nb = ~lo;                                       // low five bits
+                    const uint32_t e = entry_at(X);
+                    const uint32_t bits = (__brev(w0) >> (e & 31u)) >> 1;          // first bit read is the top bit; none: 0
+                    X = next_entry_offset(e, bits);
+                    const uint32_t nb = ~e;                                        // low five bits
                     w0 = __builtin_amdgcn_alignbit(w1, w0, nb);
                     w1 = __builtin_amdgcn_alignbit(w2, w1, nb);
                     w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
                     w3 >>= (nb & 31u);
-                    sum += lo;
-                    if constexpr (OUT == ANSZP_OUT_U8) {
-                        static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(lo >> 8);
-                    } else {
-                        const float w = scale * __uint_as_float(lo & 0xFFFF0000u);   // Sec. II-B: scale * (q - z)
-                        if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = w;
-                        else static_cast<uint16_t*>(p.out)[out_at] = static_cast<uint16_t>(bf16_rne(w));
-                    }
-                    next_element();
+                    sum += e & 31u;
+                    emit_one(k, e);
                 }
-                abit += 31u * K - (sum & 0xFFu);
+                abit += 31u * K - sum;
                 if (fetching) {
                     land(fetched, glo, ghi);
                     fetched += kStreamFetchWords;
@@ -566,16 +618,16 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_streaming(DecodeP
             };
             uint32_t t = 0;
             if (fast) {
-                for (; t + 8u <= full_steps; t += 8u) steps_fast(std::integral_constant<int, 8>{}, std::false_type{}, emit_fast);
-                for (; t < full_steps; ++t) steps_fast(std::integral_constant<int, 1>{}, std::false_type{}, emit_fast);
-                if (len > full_steps) steps_fast(std::integral_constant<int, 1>{}, std::false_type{}, emit_fast);
+                for (; t + 8u <= full_steps; t += 8u) block_fast(std::integral_constant<int, 8>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
+                for (; t < full_steps; ++t) block_fast(std::integral_constant<int, 1>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
+                if (len > full_steps) block_fast(std::integral_constant<int, 1>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
             } else {
-                for (; t + 8u <= full_steps; t += 8u) steps_plain(std::integral_constant<int, 8>{});
-                for (; t < full_steps; ++t) steps_plain(std::integral_constant<int, 1>{});
-                if (len > full_steps) steps_plain(std::integral_constant<int, 1>{});     // ragged tail: streams 0 .. n mod N - 1
+                for (; t + 8u <= full_steps; t += 8u) block_plain(std::integral_constant<int, 8>{});
+                for (; t < full_steps; ++t) block_plain(std::integral_constant<int, 1>{});
+                if (len > full_steps) block_plain(std::integral_constant<int, 1>{});     // ragged tail: streams 0 .. n mod N - 1
             }
         }
-        if (X != table0) err |= ANSZP_ST_BAD_STATE;          // state 0
+        if (X != state0) err |= ANSZP_ST_BAD_STATE;          // state 0
         if (((abit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
     err = wave_or(err);
@@ -1261,10 +1313,13 @@ uint32_t device_cus() {
 template <int OUT>
 void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, bool shared, bool streaming,
                    bool small, hipStream_t s) {
-    if (stepwise && streaming)
-        hipLaunchKernelGGL(decode_streaming<OUT>, dim3((n_chunks + kSharedWaves - 1) / kSharedWaves),
-                           dim3(kSharedWaves * kWave), 0, s, p, n_chunks);
-    else if (stepwise && shared)
+    if (stepwise && streaming) {
+        // chunks dealt evenly to as many workgroups as fill whole rounds of the device's CUs
+        const uint32_t per_round = device_cus() * uint32_t(kStreamWaves);
+        const uint32_t rounds = (n_chunks + per_round - 1u) / per_round;
+        const uint32_t groups = std::min(n_chunks, device_cus() * rounds);
+        hipLaunchKernelGGL(decode_streaming<OUT>, dim3(groups), dim3(kStreamWaves * kWave), 0, s, p, n_chunks, groups);
+    } else if (stepwise && shared)
         hipLaunchKernelGGL(decode_stepwise_shared<OUT>, dim3((n_chunks + kSharedWaves - 1) / kSharedWaves),
                            dim3(kSharedWaves * kWave), 0, s, p, n_chunks);
     else if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
