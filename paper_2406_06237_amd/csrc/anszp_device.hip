@@ -277,7 +277,7 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
 // wavefront-uniform value per block of steps and the store address is one base plus immediates.
 constexpr int kStreamWaves = 15;                // per workgroup, one chunk each
 constexpr uint32_t kStreamRingWords = 32u;      // per stream, in LDS
-constexpr uint32_t kStreamFetchWords = 8u;      // per fetch from global memory
+constexpr uint32_t kStreamFetchWords = 16u;     // per fetch from global memory: half a 128-byte line, on a 64-byte boundary
 typedef uint32_t words4 __attribute__((ext_vector_type(4)));            // four consecutive registers
 typedef words4 __attribute__((aligned(4))) words4_word_aligned;
 typedef __attribute__((address_space(3))) uint32_t lds_uint32_t;
@@ -414,45 +414,58 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
 
     // words of this stream: index relative to the stream's first word; reads beyond the caller's
     // payload buffer see zeros (beyond the stream they see its neighbours' words, never used)
-    const uint64_t base = c.payload_offset + uint64_t(min(first_word, c.payload_words));
+    // Fetches are 64 bytes on 64-byte boundaries (a line is then brought in twice, not once per
+    // touched piece): the words are counted from the boundary at or before the stream's first word.
+    const uint64_t stream_first = c.payload_offset + uint64_t(min(first_word, c.payload_words));
+    const uint32_t ahead_of_boundary = static_cast<uint32_t>((reinterpret_cast<uintptr_t>(p.payload + stream_first) & 63u) >> 2);
+    const uint32_t skew = ahead_of_boundary <= stream_first ? ahead_of_boundary : 0u;      // not before the caller's buffer
+    const uint64_t base = stream_first - skew;
     const uint32_t* const mine = p.payload + base;
     const uint64_t after = p.payload_words - base;        // words of the caller's buffer from `mine` on
     const uint32_t readable = after > 0xFFFFFFF0ull ? 0xFFFFFFF0u : static_cast<uint32_t>(after);
     // streams whose every fetch stays inside the caller's buffer need no test per fetch: a valid
-    // stream asks for words below n_words + 40; a corrupt one is kept inside by the clamp
-    const bool roomy = __ballot(lane < N && n_words + kStreamRingWords + kStreamFetchWords > readable) == 0ull;
-    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 40
+    // stream asks for words below skew + n_words + 32; a corrupt one is kept inside by the clamp
+    const bool roomy = __ballot(lane < N && skew + n_words + kStreamRingWords + kStreamFetchWords > readable) == 0ull;
+    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 48
     // These loads are issued by hand and waited for by hand: left to the compiler, the wait for
     // them lands right behind their issue in some of the loops below.
-    auto fetch_inside = [&](uint32_t at, words4& lo, words4& hi) {
+    struct Fetched { words4 a, b, c, d; };               // sixteen words on their way
+    auto fetch_inside = [&](uint32_t at, Fetched& f) {
         const uint32_t* const q = mine + min(at, last_fetch);
-        asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
-                     : "=&v"(lo), "=&v"(hi) : "v"(q) : "memory");
+        asm volatile("global_load_dwordx4 %0, %4, off\n\tglobal_load_dwordx4 %1, %4, off offset:16\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:32\n\tglobal_load_dwordx4 %3, %4, off offset:48"
+                     : "=&v"(f.a), "=&v"(f.b), "=&v"(f.c), "=&v"(f.d) : "v"(q) : "memory");
     };
-    auto fetch = [&](uint32_t at, words4& lo, words4& hi) {
+    auto fetch = [&](uint32_t at, Fetched& f) {
         if (at + kStreamFetchWords <= readable) {
             const words4_word_aligned* q = reinterpret_cast<const words4_word_aligned*>(mine + at);
-            lo = q[0];
-            hi = q[1];
+            f.a = q[0];
+            f.b = q[1];
+            f.c = q[2];
+            f.d = q[3];
         } else {
             auto one = [&](uint32_t i) { return at + i < readable ? mine[at + i] : 0u; };
-            lo = words4{one(0), one(1), one(2), one(3)};
-            hi = words4{one(4), one(5), one(6), one(7)};
+            f.a = words4{one(0), one(1), one(2), one(3)};
+            f.b = words4{one(4), one(5), one(6), one(7)};
+            f.c = words4{one(8), one(9), one(10), one(11)};
+            f.d = words4{one(12), one(13), one(14), one(15)};
         }
     };
-    auto land = [&](uint32_t at, const words4& lo, const words4& hi) {      // at is a multiple of 8: no wrap inside
+    auto land = [&](uint32_t at, const Fetched& f) {      // at is a multiple of 16: no wrap inside
         const uint32_t s0 = at & (kStreamRingWords - 1u);
-        ring[s0][lane] = lo.x; ring[s0 + 1][lane] = lo.y; ring[s0 + 2][lane] = lo.z; ring[s0 + 3][lane] = lo.w;
-        ring[s0 + 4][lane] = hi.x; ring[s0 + 5][lane] = hi.y; ring[s0 + 6][lane] = hi.z; ring[s0 + 7][lane] = hi.w;
+        ring[s0][lane] = f.a.x; ring[s0 + 1][lane] = f.a.y; ring[s0 + 2][lane] = f.a.z; ring[s0 + 3][lane] = f.a.w;
+        ring[s0 + 4][lane] = f.b.x; ring[s0 + 5][lane] = f.b.y; ring[s0 + 6][lane] = f.b.z; ring[s0 + 7][lane] = f.b.w;
+        ring[s0 + 8][lane] = f.c.x; ring[s0 + 9][lane] = f.c.y; ring[s0 + 10][lane] = f.c.z; ring[s0 + 11][lane] = f.c.w;
+        ring[s0 + 12][lane] = f.d.x; ring[s0 + 13][lane] = f.d.y; ring[s0 + 14][lane] = f.d.z; ring[s0 + 15][lane] = f.d.w;
     };
     for (uint32_t at = 0; at < kStreamRingWords; at += kStreamFetchWords) {
-        words4 glo, ghi;
-        fetch(at, glo, ghi);
-        land(at, glo, ghi);
+        Fetched f;
+        fetch(at, f);
+        land(at, f);
     }
     uint32_t fetched = kStreamRingWords;                  // words of the stream that are in the ring or before it
 
-    uint32_t abit = 0;                                    // bits of the stream read so far
+    uint32_t abit = 32u * skew;                           // bit position, counted from the first word fetched
     // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
     auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
         const uint32_t cw = abit >> 5;
@@ -497,16 +510,16 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     auto block_fast = [&](auto count_tag, auto inside, auto stores_per_step, auto&& emit) {
         constexpr int K = static_cast<int>(decltype(count_tag)::value);
         const bool fetching = wants_words();
-        words4 glo, ghi;
+        Fetched f;
         if (fetching) {
-            if constexpr (decltype(inside)::value) fetch_inside(fetched, glo, ghi);
-            else fetch(fetched, glo, ghi);
+            if constexpr (decltype(inside)::value) fetch_inside(fetched, f);
+            else fetch(fetched, f);
         }
         run_fast(count_tag, emit);
         if (fetching) {
             if constexpr (decltype(inside)::value)
                 asm volatile("s_waitcnt vmcnt(%0)" : : "n"(K * decltype(stores_per_step)::value) : "memory");
-            land(fetched, glo, ghi);
+            land(fetched, f);
             fetched += kStreamFetchWords;
         }
     };
@@ -541,14 +554,14 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                         // 24 steps around one fetch: they read at most nine words beyond the first
                         while (seg >= 24u && __ballot(words_ahead() < 10u) == 0ull) {
                             const bool fetching = wants_words();
-                            words4 glo, ghi;
-                            if (fetching) fetch_inside(fetched, glo, ghi);
+                            Fetched f;
+                            if (fetching) fetch_inside(fetched, f);
                             run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k), e); });
                             run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 8u, e); });
                             run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 16u, e); });
                             if (fetching) {
                                 asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-                                land(fetched, glo, ghi);
+                                land(fetched, f);
                                 fetched += kStreamFetchWords;
                             }
                             at += 24u * kWave * kElemBytes;
@@ -592,8 +605,8 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             auto block_plain = [&](auto count_tag) {
                 constexpr int K = static_cast<int>(decltype(count_tag)::value);
                 const bool fetching = wants_words();
-                words4 glo, ghi;
-                if (fetching) fetch(fetched, glo, ghi);
+                Fetched f;
+                if (fetching) fetch(fetched, f);
                 uint32_t w0, w1, w2, w3;
                 window(w0, w1, w2, w3);
                 uint32_t sum = 0;                                 // 31 - nb_bits over the K steps
@@ -612,7 +625,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                 }
                 abit += 31u * K - sum;
                 if (fetching) {
-                    land(fetched, glo, ghi);
+                    land(fetched, f);
                     fetched += kStreamFetchWords;
                 }
             };
@@ -628,7 +641,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             }
         }
         if (X != state0) err |= ANSZP_ST_BAD_STATE;          // state 0
-        if (((abit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
+        if (((abit + 31u) >> 5) != skew + n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
     err = wave_or(err);
     if (err && lane == 0) report(p.status, err);
