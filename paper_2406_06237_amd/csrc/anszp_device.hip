@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     constexpr uint32_t kNoTriple = 0x00010000u;           // reads one bit
     uint32_t ta0 = kNoTriple, ta1 = kNoTriple, ta2 = kNoTriple, ta3 = kNoTriple, ta4 = kNoTriple;
     uint32_t tb0 = kNoTriple, tb1 = kNoTriple, tb2 = kNoTriple, tb3 = kNoTriple, tb4 = kNoTriple;
-    static_assert(kPerThread == 5, "five triples of each table per thread");
+    static_assert(kPerThread <= 5, "at most five triples of each table per thread");
     if (have_a) {
         if (tid < L) ta0 = src_a[tid];
         if (tid + kThreads < L) ta1 = src_a[tid + kThreads];
@@ -469,10 +469,11 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
     auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
         const uint32_t cw = abit >> 5;
-        w0 = ring[cw & 31u][lane];
-        w1 = ring[(cw + 1u) & 31u][lane];
-        w2 = ring[(cw + 2u) & 31u][lane];
-        w3 = ring[(cw + 3u) & 31u][lane];
+        constexpr uint32_t kMask = kStreamRingWords - 1u;
+        w0 = ring[cw & kMask][lane];
+        w1 = ring[(cw + 1u) & kMask][lane];
+        w2 = ring[(cw + 2u) & kMask][lane];
+        w3 = ring[(cw + 3u) & kMask][lane];
         w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
@@ -531,8 +532,17 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             // step k at chunk_out + at + k * 64 * kElemBytes
             char* const chunk_out = static_cast<char*>(p.out) + c.out_offset * kElemBytes;
             uint32_t at = lane * kElemBytes;
-            // (the scale goes through a scalar register: the wait for its load then stands here, not in the blocks)
-            auto uniform_scale = [&](uint32_t ch) { return __uint_as_float(uniform(__float_as_uint(scale_of(ch)))); };
+            // The scale of a channel comes through the scalar cache: a vector load would have to be waited
+            // for behind every store the wavefront has in flight.
+            auto uniform_scale = [&](uint32_t channel_in_chunk) {
+                const uint64_t ch = lay.scales_offset + channel0 + channel_in_chunk;
+                if (ch >= p.n_scales) return 0.0f;
+                const uintptr_t q = reinterpret_cast<uintptr_t>(p.scales + ch);
+                const uint64_t address = (uint64_t(uniform(static_cast<uint32_t>(q >> 32))) << 32) | uniform(static_cast<uint32_t>(q));
+                uint32_t v;
+                asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(address) : "memory");
+                return __uint_as_float(v);
+            };
             float scale = per_channel ? uniform_scale(0) : lay.scale;
             uint32_t channel = 0;                                          // within the chunk
             uint32_t left = uniform(per_channel ? (lay.channel_len - in_channel0) / kWave : 0xFFFFFFFFu);   // steps left under this scale
