@@ -255,16 +255,23 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
 // One look-up per symbol for launches with thousands of chunks too large for an LDS window (Sec.
 // III-B at scale).  The plain loop above reads a stream's words four bytes at a time; with two
 // thousand streams per CU each of those reads brings a whole cache line from HBM again, and the
-// launch is bound by re-reading its own input.  Here a stream's words come through a ring in LDS,
-// 32 bytes per fetch, and a lane keeps a window of the stream in registers that it reloads from
-// the ring every K steps (no per-step refill test: lanes need their refills at different steps, so
-// such a test would run its body at nearly every step).
+// launch is bound by re-reading its own input.  Here a stream's words come through a ring of 32
+// words in LDS, 64 bytes per fetch, and a lane keeps a window of the stream in registers that it
+// reloads from the ring every 8 steps (no per-step refill test: lanes need their refills at
+// different steps, so such a test would run its body at nearly every step).
 //
-// Loads and stores of a wavefront complete in issue order behind one counter, and when the whole
-// chip writes weights a fetch takes longer than a block of 8 steps.  So the ring holds 32 words
-// and, in the main loop, a fetch is asked for before 24 steps and put into the ring after them.
-// That needs LDS: the entries of the two tables a workgroup may need are 4 bytes, derived from the
-// paper's triples (Sec. II-A) while staging:
+// A wavefront that stores a weight per step and also fetches its stream words is held up by its
+// fetches far beyond their latency (loads and stores of a wavefront complete in issue order behind
+// one counter, and the whole chip is writing).  So the work is split: fourteen wavefronts of a
+// workgroup decode one chunk each and only store; two wavefronts only load: each follows the word
+// positions seven decoding wavefronts publish in LDS, fetches the next 64 bytes of every stream
+// whose ring has room for them, and publishes how far each ring is filled.  LDS accesses of a
+// wavefront are performed in order, so a decoding wavefront that reads "filled up to w" before
+// its window sees every word below w; no fences.  A decoding wavefront whose ring is not filled
+// far enough waits (bounded); that only happens when streams spend several words per 8 steps.
+//
+// The LDS entries of the two tables a workgroup may need are 4 bytes, derived from the paper's
+// triples (Sec. II-A) while staging:
 //   bits 0..4   fast form (64 streams per chunk, no state of either table reads zero bits):
 //               32 - nb_bits; the window holds the stream most significant bit first,
 //               bits = window >> (32 - nb_bits), one funnel shift per window register consumes them
@@ -273,14 +280,22 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
 //   bits 5..17  index, in the workgroup's two tables, of the entry of state newX
 //   bits 19..31 weights out: the upper 13 bits of (symbol - zero_point) as fp16 (exact: |.| <= 255
 //               leaves the lower 3 bits zero); symbols out: bits 19..26 the symbol
-// With the fast form, when every wavefront-step lies inside one output channel, the scale is a
-// wavefront-uniform value per block of steps and the store address is one base plus immediates.
-constexpr int kStreamWaves = 15;                // per workgroup, one chunk each
+// The split needs the fast form and every wavefront-step inside one output channel (the scale is
+// then wavefront-uniform per run of steps and the store address one base plus immediates); other
+// chunks are decoded by their wavefront alone, fetches included.
+constexpr int kStreamWaves = 16;                // per workgroup
+constexpr int kStreamLoaders = 2;               // wavefronts that fetch stream words
+constexpr int kStreamDecoders = kStreamWaves - kStreamLoaders;   // wavefronts that decode, one chunk each
+constexpr int kStreamServed = kStreamDecoders / kStreamLoaders;  // decoding wavefronts per loading wavefront
+constexpr int kStreamBatch = 4;                 // decoders whose fetches a loading wavefront has in flight together
 constexpr uint32_t kStreamRingWords = 32u;      // per stream, in LDS
 constexpr uint32_t kStreamFetchWords = 16u;     // per fetch from global memory: half a 128-byte line, on a 64-byte boundary
+constexpr uint32_t kStreamUrgentWords = 8u;     // a stream this close to the end of its ring makes its wavefront's streams fetch
+constexpr uint32_t kStreamNotStarted = 0xFFFFFFFEu, kStreamFinished = 0xFFFFFFFFu;   // in place of a published word position
 typedef uint32_t words4 __attribute__((ext_vector_type(4)));            // four consecutive registers
 typedef words4 __attribute__((aligned(4))) words4_word_aligned;
 typedef __attribute__((address_space(3))) uint32_t lds_uint32_t;
+static_assert(kStreamDecoders % kStreamLoaders == 0, "every loading wavefront serves the same number of decoders");
 
 // scale * (q - z) (Sec. II-B) with q - z read as fp16 from the high half of `entry` (lower bits
 // cleared): the product is rounded once, like the plain multiplication; the addend -0 keeps the
@@ -312,48 +327,51 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     // one object, the tables first: their entries are then within reach of an LDS instruction's offset field
     struct Lds {
         uint32_t table[2][kStates];
-        uint32_t rings[kStreamWaves][kStreamRingWords][kWave];           // word s of lane l at [wave][s mod 32][l]
+        uint32_t rings[kStreamDecoders][kStreamRingWords][kWave];        // word s of lane l at [wave][s mod 32][l]
+        uint32_t position[kStreamDecoders][kWave];                       // word each stream's window starts at, or not started / finished
+        uint32_t filled[kStreamDecoders][kWave];                         // words of each stream that are in its ring or before it
+        uint32_t gave_up;
     };
     __shared__ Lds lds;
     auto& table = lds.table;
-    auto& rings = lds.rings;
     constexpr uint32_t kThreads = kStreamWaves * kWave;
     constexpr uint32_t kPerThread = (kStates + kThreads - 1u) / kThreads;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : OUT == ANSZP_OUT_F32 ? 4u : 2u;
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t first = stream_group_begin(blockIdx.x, n_chunks, n_groups);
-    const uint32_t count = min(stream_group_begin(blockIdx.x + 1u, n_chunks, n_groups) - first, uint32_t(kStreamWaves));
+    const uint32_t count = min(stream_group_begin(blockIdx.x + 1u, n_chunks, n_groups) - first, uint32_t(kStreamDecoders));
     if (count == 0u) return;
     const uint32_t last = first + count - 1u;
     const uint32_t L = 1u << p.table_log, N = p.n_streams;
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
     const bool have_a = layer_a < p.n_tables, have_b = layer_b != layer_a && layer_b < p.n_tables;
+    lds_flag_t* const gave_up = (lds_flag_t*)&lds.gave_up;
+    if (tid < uint32_t(kStreamDecoders) * kWave) ((lds_flag_t*)&lds.position[0][0])[tid] = kStreamNotStarted;
+    if (tid == 0) *gave_up = 0u;
 
     // the paper's triples of both tables, held in registers until the form of the entries is known
     const uint32_t* src_a = p.tables + (uint64_t(have_a ? layer_a : 0u) << (p.table_log + 2)) + 2u * L;
     const uint32_t* src_b = p.tables + (uint64_t(have_b ? layer_b : 0u) << (p.table_log + 2)) + 2u * L;
     constexpr uint32_t kNoTriple = 0x00010000u;           // reads one bit
-    uint32_t ta0 = kNoTriple, ta1 = kNoTriple, ta2 = kNoTriple, ta3 = kNoTriple, ta4 = kNoTriple;
-    uint32_t tb0 = kNoTriple, tb1 = kNoTriple, tb2 = kNoTriple, tb3 = kNoTriple, tb4 = kNoTriple;
-    static_assert(kPerThread <= 5, "at most five triples of each table per thread");
+    uint32_t ta0 = kNoTriple, ta1 = kNoTriple, ta2 = kNoTriple, ta3 = kNoTriple;
+    uint32_t tb0 = kNoTriple, tb1 = kNoTriple, tb2 = kNoTriple, tb3 = kNoTriple;
+    static_assert(kPerThread == 4, "four triples of each table per thread");
     if (have_a) {
         if (tid < L) ta0 = src_a[tid];
         if (tid + kThreads < L) ta1 = src_a[tid + kThreads];
         if (tid + 2u * kThreads < L) ta2 = src_a[tid + 2u * kThreads];
         if (tid + 3u * kThreads < L) ta3 = src_a[tid + 3u * kThreads];
-        if (tid + 4u * kThreads < L) ta4 = src_a[tid + 4u * kThreads];
     }
     if (have_b) {
         if (tid < L) tb0 = src_b[tid];
         if (tid + kThreads < L) tb1 = src_b[tid + kThreads];
         if (tid + 2u * kThreads < L) tb2 = src_b[tid + 2u * kThreads];
         if (tid + 3u * kThreads < L) tb3 = src_b[tid + 3u * kThreads];
-        if (tid + 4u * kThreads < L) tb4 = src_b[tid + 4u * kThreads];
     }
     auto reads_no_bits = [](uint32_t e) { return ((e >> 16) & 0xFFu) == 0u; };
-    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) | reads_no_bits(ta4) |
-                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3) | reads_no_bits(tb4);
+    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) |
+                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3);
     const bool fast = !__syncthreads_or(some_zero) && N == kWave;
     auto place = [&](uint32_t e, uint32_t i, uint32_t which, uint32_t z) {
         if (i >= L) return;
@@ -366,19 +384,146 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     };
     if (have_a) {
         const uint32_t z = p.layers[layer_a].zero_point;
-        place(ta0, tid, 0, z); place(ta1, tid + kThreads, 0, z); place(ta2, tid + 2u * kThreads, 0, z);
-        place(ta3, tid + 3u * kThreads, 0, z); place(ta4, tid + 4u * kThreads, 0, z);
+        place(ta0, tid, 0, z); place(ta1, tid + kThreads, 0, z); place(ta2, tid + 2u * kThreads, 0, z); place(ta3, tid + 3u * kThreads, 0, z);
     }
     if (have_b) {
         const uint32_t z = p.layers[layer_b].zero_point;
-        place(tb0, tid, 1, z); place(tb1, tid + kThreads, 1, z); place(tb2, tid + 2u * kThreads, 1, z);
-        place(tb3, tid + 3u * kThreads, 1, z); place(tb4, tid + 4u * kThreads, 1, z);
+        place(tb0, tid, 1, z); place(tb1, tid + kThreads, 1, z); place(tb2, tid + 2u * kThreads, 1, z); place(tb3, tid + 3u * kThreads, 1, z);
     }
     __syncthreads();
-    if (wave >= count) return;
+
+    // Where the words of this lane's stream of chunk c are.  Fetches are 64 bytes on 64-byte
+    // boundaries (a line is then brought in twice, not once per touched piece), so words are counted
+    // from the boundary at or before the stream's first word: the stream starts at word `skew` of
+    // the returned pointer, `readable` words from there on are inside the caller's buffer.
+    auto locate = [&](const anszp_chunk_t& c, uint32_t& n_words, uint32_t& skew, uint32_t& readable, bool& sums_up) {
+        const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
+        n_words = hdr >> 16;
+        uint32_t total_words;
+        const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+        sums_up = total_words == c.payload_words;
+        const uint64_t stream_first = c.payload_offset + uint64_t(min(first_word, c.payload_words));
+        const uint32_t ahead_of_boundary = static_cast<uint32_t>((reinterpret_cast<uintptr_t>(p.payload + stream_first) & 63u) >> 2);
+        skew = ahead_of_boundary <= stream_first ? ahead_of_boundary : 0u;      // not before the caller's buffer
+        const uint64_t base = stream_first - skew;
+        const uint64_t after = p.payload_words - base;
+        readable = after > 0xFFFFFFF0ull ? 0xFFFFFFF0u : static_cast<uint32_t>(after);
+        return p.payload + base;
+    };
+    // sixteen words of a stream; beyond the caller's buffer they read as zero (beyond the stream
+    // they are its neighbours' words, never used)
+    struct Fetched { words4 a, b, c, d; };
+    auto fetch = [&](const uint32_t* mine, uint32_t readable, uint32_t at, Fetched& f) {
+        if (at + kStreamFetchWords <= readable) {
+            const words4_word_aligned* q = reinterpret_cast<const words4_word_aligned*>(mine + at);
+            f.a = q[0];
+            f.b = q[1];
+            f.c = q[2];
+            f.d = q[3];
+        } else {
+            auto one = [&](uint32_t i) { return at + i < readable ? mine[at + i] : 0u; };
+            f.a = words4{one(0), one(1), one(2), one(3)};
+            f.b = words4{one(4), one(5), one(6), one(7)};
+            f.c = words4{one(8), one(9), one(10), one(11)};
+            f.d = words4{one(12), one(13), one(14), one(15)};
+        }
+    };
+    auto land = [&](uint32_t (*ring)[kWave], uint32_t at, const Fetched& f) {      // at is a multiple of 16: no wrap inside
+        const uint32_t s0 = at & (kStreamRingWords - 1u);
+        ring[s0][lane] = f.a.x; ring[s0 + 1][lane] = f.a.y; ring[s0 + 2][lane] = f.a.z; ring[s0 + 3][lane] = f.a.w;
+        ring[s0 + 4][lane] = f.b.x; ring[s0 + 5][lane] = f.b.y; ring[s0 + 6][lane] = f.b.z; ring[s0 + 7][lane] = f.b.w;
+        ring[s0 + 8][lane] = f.c.x; ring[s0 + 9][lane] = f.c.y; ring[s0 + 10][lane] = f.c.z; ring[s0 + 11][lane] = f.c.w;
+        ring[s0 + 12][lane] = f.d.x; ring[s0 + 13][lane] = f.d.y; ring[s0 + 14][lane] = f.d.z; ring[s0 + 15][lane] = f.d.w;
+    };
+
+    if (wave >= uint32_t(kStreamDecoders)) {
+        // ---- loading wavefront: decoders wave - 14, + 2, + 4, ...
+        const uint32_t mine_index = wave - uint32_t(kStreamDecoders);
+        const uint32_t* where[kStreamServed];             // all indexed by constants once the loops are unrolled
+        uint32_t readable[kStreamServed], fetched[kStreamServed];
+        bool alive[kStreamServed];
+#pragma unroll
+        for (int j = 0; j < kStreamServed; ++j) {
+            const uint32_t d = mine_index + uint32_t(j * kStreamLoaders);
+            where[j] = p.payload;
+            readable[j] = 0u;
+            fetched[j] = kStreamRingWords;                // the decoding wavefront fills its ring once itself
+            alive[j] = false;
+            if (d < count) {
+                const anszp_chunk_t cj = p.chunks[first + d];
+                if (chunk_in_bounds(p, cj)) {
+                    uint32_t n_words, skew;
+                    bool sums_up;
+                    where[j] = locate(cj, n_words, skew, readable[j], sums_up);
+                    alive[j] = true;
+                }
+            }
+        }
+        for (uint32_t idle = 0;;) {
+            bool any_alive = false, moved = false;
+#pragma unroll
+            for (int b = 0; b < kStreamServed; b += kStreamBatch) {
+                Fetched f[kStreamBatch];
+                bool want[kStreamBatch];
+#pragma unroll
+                for (int i = 0; i < kStreamBatch; ++i) {
+                    const int j = b + i;
+                    want[i] = false;
+                    if (j < kStreamServed && alive[j]) {
+                        const uint32_t d = mine_index + uint32_t(j * kStreamLoaders);
+                        const uint32_t at = ((lds_flag_t*)lds.position[d])[lane];
+                        if (__ballot(at != kStreamFinished) == 0ull) {
+                            alive[j] = false;
+                        } else {
+                            any_alive = true;
+                            // A stream with room for sixteen more words (they replace words it has passed) gets
+                            // them once some stream of its wavefront is down to kStreamUrgentWords: a load
+                            // instruction costs the same for one lane as for sixty-four.
+                            const uint32_t ahead = fetched[j] - at;
+                            const bool started = at < kStreamNotStarted;
+                            if (__ballot(started && ahead <= kStreamUrgentWords) != 0ull) {
+                                want[i] = started && ahead <= kStreamRingWords - kStreamFetchWords;
+                                if (want[i]) fetch(where[j], readable[j], fetched[j], f[i]);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < kStreamBatch; ++i) {
+                    const int j = b + i;
+                    if (j < kStreamServed) {
+                        const uint32_t d = mine_index + uint32_t(j * kStreamLoaders);
+                        if (want[i]) {
+                            land(lds.rings[d], fetched[j], f[i]);
+                            fetched[j] += kStreamFetchWords;
+                            asm volatile("" ::: "memory");
+                            ((lds_flag_t*)lds.filled[d])[lane] = fetched[j];
+                        }
+                        if (__ballot(want[i]) != 0ull) moved = true;
+                    }
+                }
+            }
+            if (!any_alive) break;
+            if (moved) { idle = 0; continue; }
+            if (uniform(*gave_up)) break;
+            if (++idle > kSpinLimit) {
+                if (lane == 0) { *gave_up = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        return;
+    }
+
+    // ---- decoding wavefront
+    lds_flag_t* const position = (lds_flag_t*)lds.position[wave];
+    lds_flag_t* const filled = (lds_flag_t*)lds.filled[wave];
+    auto no_more_positions = [&]() { position[lane] = kStreamFinished; };
+    if (wave >= count) { no_more_positions(); return; }
     const anszp_chunk_t c = p.chunks[first + wave];
     if (!chunk_in_bounds(p, c)) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        no_more_positions();
         return;
     }
     const anszp_layer_t lay = p.layers[c.layer_id];
@@ -394,76 +539,31 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     };
     if (c.layer_id != layer_a && c.layer_id != layer_b) {
         // a third layer in one workgroup: the plain loop, table from global memory
+        no_more_positions();
         const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
-    uint32_t (*ring)[kWave] = rings[wave];
+    uint32_t (*ring)[kWave] = lds.rings[wave];
     const uint32_t entries = lds_address(&table[0][0]);
     auto entry_at = [&](uint32_t offset) { return *reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(entries + offset)); };
 
+    uint32_t n_words, skew, readable;
+    bool sums_up;
+    const uint32_t* const mine = locate(c, n_words, skew, readable, sums_up);
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
     const uint32_t state0 = c.layer_id == layer_a ? 0u : 4u * kStates;   // byte offset of the entry of state 0
     uint32_t X = state0 + ((hdr & (L - 1u)) << 2);       // byte offset of the current state's entry
-    const uint32_t n_words = hdr >> 16;
-    uint32_t total_words;
-    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
     const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
-    uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+    uint32_t err = sums_up ? 0u : ANSZP_ST_BAD_DESC;
     const uint32_t full_steps = c.n_symbols / N;          // steps every stream of the chunk takes
 
-    // words of this stream: index relative to the stream's first word; reads beyond the caller's
-    // payload buffer see zeros (beyond the stream they see its neighbours' words, never used)
-    // Fetches are 64 bytes on 64-byte boundaries (a line is then brought in twice, not once per
-    // touched piece): the words are counted from the boundary at or before the stream's first word.
-    const uint64_t stream_first = c.payload_offset + uint64_t(min(first_word, c.payload_words));
-    const uint32_t ahead_of_boundary = static_cast<uint32_t>((reinterpret_cast<uintptr_t>(p.payload + stream_first) & 63u) >> 2);
-    const uint32_t skew = ahead_of_boundary <= stream_first ? ahead_of_boundary : 0u;      // not before the caller's buffer
-    const uint64_t base = stream_first - skew;
-    const uint32_t* const mine = p.payload + base;
-    const uint64_t after = p.payload_words - base;        // words of the caller's buffer from `mine` on
-    const uint32_t readable = after > 0xFFFFFFF0ull ? 0xFFFFFFF0u : static_cast<uint32_t>(after);
-    // streams whose every fetch stays inside the caller's buffer need no test per fetch: a valid
-    // stream asks for words below skew + n_words + 32; a corrupt one is kept inside by the clamp
-    const bool roomy = __ballot(lane < N && skew + n_words + kStreamRingWords + kStreamFetchWords > readable) == 0ull;
-    const uint32_t last_fetch = readable - kStreamFetchWords;      // roomy: readable >= 48
-    // These loads are issued by hand and waited for by hand: left to the compiler, the wait for
-    // them lands right behind their issue in some of the loops below.
-    struct Fetched { words4 a, b, c, d; };               // sixteen words on their way
-    auto fetch_inside = [&](uint32_t at, Fetched& f) {
-        const uint32_t* const q = mine + min(at, last_fetch);
-        asm volatile("global_load_dwordx4 %0, %4, off\n\tglobal_load_dwordx4 %1, %4, off offset:16\n\t"
-                     "global_load_dwordx4 %2, %4, off offset:32\n\tglobal_load_dwordx4 %3, %4, off offset:48"
-                     : "=&v"(f.a), "=&v"(f.b), "=&v"(f.c), "=&v"(f.d) : "v"(q) : "memory");
-    };
-    auto fetch = [&](uint32_t at, Fetched& f) {
-        if (at + kStreamFetchWords <= readable) {
-            const words4_word_aligned* q = reinterpret_cast<const words4_word_aligned*>(mine + at);
-            f.a = q[0];
-            f.b = q[1];
-            f.c = q[2];
-            f.d = q[3];
-        } else {
-            auto one = [&](uint32_t i) { return at + i < readable ? mine[at + i] : 0u; };
-            f.a = words4{one(0), one(1), one(2), one(3)};
-            f.b = words4{one(4), one(5), one(6), one(7)};
-            f.c = words4{one(8), one(9), one(10), one(11)};
-            f.d = words4{one(12), one(13), one(14), one(15)};
-        }
-    };
-    auto land = [&](uint32_t at, const Fetched& f) {      // at is a multiple of 16: no wrap inside
-        const uint32_t s0 = at & (kStreamRingWords - 1u);
-        ring[s0][lane] = f.a.x; ring[s0 + 1][lane] = f.a.y; ring[s0 + 2][lane] = f.a.z; ring[s0 + 3][lane] = f.a.w;
-        ring[s0 + 4][lane] = f.b.x; ring[s0 + 5][lane] = f.b.y; ring[s0 + 6][lane] = f.b.z; ring[s0 + 7][lane] = f.b.w;
-        ring[s0 + 8][lane] = f.c.x; ring[s0 + 9][lane] = f.c.y; ring[s0 + 10][lane] = f.c.z; ring[s0 + 11][lane] = f.c.w;
-        ring[s0 + 12][lane] = f.d.x; ring[s0 + 13][lane] = f.d.y; ring[s0 + 14][lane] = f.d.z; ring[s0 + 15][lane] = f.d.w;
-    };
     for (uint32_t at = 0; at < kStreamRingWords; at += kStreamFetchWords) {
         Fetched f;
-        fetch(at, f);
-        land(at, f);
+        fetch(mine, readable, at, f);
+        land(ring, at, f);
     }
-    uint32_t fetched = kStreamRingWords;                  // words of the stream that are in the ring or before it
+    uint32_t fetched = kStreamRingWords;                  // words of the stream that are in the ring or before it (when this wavefront fetches itself)
 
     uint32_t abit = 32u * skew;                           // bit position, counted from the first word fetched
     // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
@@ -479,16 +579,12 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
         w3 >>= (abit & 31u);
     };
-    auto words_ahead = [&]() { return fetched - (abit >> 5); };           // of the lane's position, in the ring
-    // a lane asks for eight more words when the ring has room for them (they replace words it has passed)
-    auto wants_words = [&]() { return words_ahead() <= kStreamRingWords - kStreamFetchWords; };
-    // K steps of the fast form from a window loaded once.  A step may read table_log <= 12 bits,
-    // so of the 96 bits in w0..w2 only those a later step of the K can still reach are kept in place.
-    auto run_fast = [&](auto count_tag, auto&& emit) {
+    // K steps of the fast form from the window w0..w2 (bit `abit` of the stream in bit 0 of w0).
+    // A step may read table_log <= 12 bits, so of the 96 bits only those a later step of the K can
+    // still reach are kept in place.
+    auto steps_fast = [&](auto count_tag, uint32_t w0, uint32_t w1, uint32_t w2, auto&& emit) {
         constexpr int K = static_cast<int>(decltype(count_tag)::value);
         static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of K steps");
-        uint32_t w0, w1, w2, w3;
-        window(w0, w1, w2, w3);
         w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
         uint32_t sum = 0;                                 // 32 - nb_bits over the K steps
 #pragma unroll
@@ -504,32 +600,33 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         }
         abit += 32u * K - sum;
     };
-    // One block: K steps, with a fetch asked for before them and put into the ring after them.
-    // A block reads at most three words beyond its first one, a lane enters it at least four
-    // words ahead.  `stores_per_step`: global stores emit() issues per step (they are behind the
-    // fetch in the one counter of outstanding accesses).
-    auto block_fast = [&](auto count_tag, auto inside, auto stores_per_step, auto&& emit) {
-        constexpr int K = static_cast<int>(decltype(count_tag)::value);
+    // a lane asks for sixteen more words when the ring has room for them (they replace words it has passed)
+    auto wants_words = [&]() { return fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords; };
+    // One block of a wavefront that fetches itself: K steps, with a fetch asked for before them
+    // and put into the ring after them.  A block reads at most three words beyond its first one,
+    // a lane enters it at least four words ahead.
+    auto block_fast = [&](auto count_tag, auto&& emit) {
         const bool fetching = wants_words();
         Fetched f;
+        if (fetching) fetch(mine, readable, fetched, f);
+        uint32_t w0, w1, w2, w3;
+        window(w0, w1, w2, w3);
+        steps_fast(count_tag, w0, w1, w2, emit);
         if (fetching) {
-            if constexpr (decltype(inside)::value) fetch_inside(fetched, f);
-            else fetch(fetched, f);
-        }
-        run_fast(count_tag, emit);
-        if (fetching) {
-            if constexpr (decltype(inside)::value)
-                asm volatile("s_waitcnt vmcnt(%0)" : : "n"(K * decltype(stores_per_step)::value) : "memory");
-            land(fetched, f);
+            land(ring, fetched, f);
             fetched += kStreamFetchWords;
         }
     };
 
+    const bool aligned = !per_channel || (lay.channel_len % kWave == 0u && in_channel0 % kWave == 0u);
+    const bool fed = fast && aligned && uint64_t(c.n_symbols) * kElemBytes < (1ull << 31);      // fast: all 64 lanes have a stream
+    if (!fed) no_more_positions();
     if (lane < N) {
-        const bool aligned = !per_channel || (lay.channel_len % kWave == 0u && in_channel0 % kWave == 0u);
-        if (fast && aligned && uint64_t(c.n_symbols) * kElemBytes < (1ull << 31)) {
+        if (fed) {
             // every wavefront-step lies inside one channel: one scale per run of steps, weights of
-            // step k at chunk_out + at + k * 64 * kElemBytes
+            // step k at chunk_out + at + k * 64 * kElemBytes; the stream words come from a loading wavefront
+            filled[lane] = kStreamRingWords;
+            position[lane] = abit >> 5;
             char* const chunk_out = static_cast<char*>(p.out) + c.out_offset * kElemBytes;
             uint32_t at = lane * kElemBytes;
             // The scale of a channel comes through the scalar cache: a vector load would have to be waited
@@ -547,52 +644,49 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             uint32_t channel = 0;                                          // within the chunk
             uint32_t left = uniform(per_channel ? (lay.channel_len - in_channel0) / kWave : 0xFFFFFFFFu);   // steps left under this scale
             const uint32_t steps = uniform(full_steps);
-            auto emit_at = [&](uint32_t step, uint32_t e) {
-                char* const q = chunk_out + at + step * (kWave * kElemBytes);
+            bool stuck = false;
+            auto emit = [&](int k, uint32_t e) {
+                char* const q = chunk_out + at + static_cast<uint32_t>(k) * (kWave * kElemBytes);
                 if constexpr (OUT == ANSZP_OUT_U8) *reinterpret_cast<uint8_t*>(q) = static_cast<uint8_t>(e >> 19);
                 else if constexpr (OUT == ANSZP_OUT_F32) *reinterpret_cast<float*>(q) = scaled_high_half(e, scale);
                 else *reinterpret_cast<__bf16*>(q) = static_cast<__bf16>(scaled_high_half(e, scale));
             };
-            auto emit = [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k), e); };
-            auto all_steps = [&](auto inside) {
-                uint32_t t = 0;
-                while (t < steps) {
-                    uint32_t seg = min(steps - t, left);
-                    t += seg;
-                    left -= seg;
-                    if constexpr (decltype(inside)::value) {
-                        // 24 steps around one fetch: they read at most nine words beyond the first
-                        while (seg >= 24u && __ballot(words_ahead() < 10u) == 0ull) {
-                            const bool fetching = wants_words();
-                            Fetched f;
-                            if (fetching) fetch_inside(fetched, f);
-                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k), e); });
-                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 8u, e); });
-                            run_fast(std::integral_constant<int, 8>{}, [&](int k, uint32_t e) { emit_at(static_cast<uint32_t>(k) + 16u, e); });
-                            if (fetching) {
-                                asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-                                land(fetched, f);
-                                fetched += kStreamFetchWords;
-                            }
-                            at += 24u * kWave * kElemBytes;
-                            seg -= 24u;
-                        }
-                    }
-                    for (; seg >= 8u; seg -= 8u) { block_fast(std::integral_constant<int, 8>{}, inside, std::integral_constant<int, 1>{}, emit); at += 8u * kWave * kElemBytes; }
-                    if (seg >= 4u) { block_fast(std::integral_constant<int, 4>{}, inside, std::integral_constant<int, 1>{}, emit); at += 4u * kWave * kElemBytes; seg -= 4u; }
-                    for (; seg; --seg) { block_fast(std::integral_constant<int, 1>{}, inside, std::integral_constant<int, 1>{}, emit); at += kWave * kElemBytes; }
-                    if (left == 0u) {
-                        ++channel;
-                        left = uniform(lay.channel_len / kWave);
-                        scale = uniform_scale(channel);
-                    }
+            // K steps from the ring as the loading wavefront fills it: the window's four words must be there
+            auto block_fed = [&](auto count_tag) {
+                uint32_t w0, w1, w2, w3;
+                for (uint32_t spins = 0;;) {
+                    const uint32_t have = filled[lane];                    // read before the words themselves
+                    asm volatile("" ::: "memory");
+                    window(w0, w1, w2, w3);
+                    if (__ballot(have - (abit >> 5) < 4u) == 0ull) break;
+                    if (uniform(*gave_up) || ++spins > kSpinLimit) { stuck = true; return; }
+                    __builtin_amdgcn_s_sleep(1);
                 }
-                if (len > full_steps) block_fast(std::integral_constant<int, 1>{}, inside, std::integral_constant<int, 1>{}, emit);   // ragged tail: streams 0 .. n mod N - 1
+                steps_fast(count_tag, w0, w1, w2, emit);
+                position[lane] = abit >> 5;
             };
-            if (roomy) all_steps(std::true_type{});
-            else all_steps(std::false_type{});
+            uint32_t t = 0;
+            while (t < steps && !stuck) {
+                uint32_t seg = min(steps - t, left);
+                t += seg;
+                left -= seg;
+                for (; seg >= 8u && !stuck; seg -= 8u) { block_fed(std::integral_constant<int, 8>{}); at += 8u * kWave * kElemBytes; }
+                if (seg >= 4u && !stuck) { block_fed(std::integral_constant<int, 4>{}); at += 4u * kWave * kElemBytes; seg -= 4u; }
+                for (; seg && !stuck; --seg) { block_fed(std::integral_constant<int, 1>{}); at += kWave * kElemBytes; }
+                if (left == 0u) {
+                    ++channel;
+                    left = uniform(lay.channel_len / kWave);
+                    scale = uniform_scale(channel);
+                }
+            }
+            if (len > full_steps && !stuck) block_fed(std::integral_constant<int, 1>{});   // ragged tail: streams 0 .. n mod N - 1
+            if (stuck) {
+                if (lane == 0) { *gave_up = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                no_more_positions();
+                return;
+            }
         } else {
-            // a scale per lane, followed from element to element
+            // this wavefront alone: a scale per lane, followed from element to element
             const uint64_t elem0 = chunk_elem0 + lane;
             uint64_t channel = per_channel ? elem0 / lay.channel_len - channel0 : 0;                   // within the chunk
             uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
@@ -616,7 +710,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                 constexpr int K = static_cast<int>(decltype(count_tag)::value);
                 const bool fetching = wants_words();
                 Fetched f;
-                if (fetching) fetch(fetched, f);
+                if (fetching) fetch(mine, readable, fetched, f);
                 uint32_t w0, w1, w2, w3;
                 window(w0, w1, w2, w3);
                 uint32_t sum = 0;                                 // 31 - nb_bits over the K steps
@@ -635,15 +729,15 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                 }
                 abit += 31u * K - sum;
                 if (fetching) {
-                    land(fetched, f);
+                    land(ring, fetched, f);
                     fetched += kStreamFetchWords;
                 }
             };
             uint32_t t = 0;
             if (fast) {
-                for (; t + 8u <= full_steps; t += 8u) block_fast(std::integral_constant<int, 8>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
-                for (; t < full_steps; ++t) block_fast(std::integral_constant<int, 1>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
-                if (len > full_steps) block_fast(std::integral_constant<int, 1>{}, std::false_type{}, std::integral_constant<int, 1>{}, emit_one);
+                for (; t + 8u <= full_steps; t += 8u) block_fast(std::integral_constant<int, 8>{}, emit_one);
+                for (; t < full_steps; ++t) block_fast(std::integral_constant<int, 1>{}, emit_one);
+                if (len > full_steps) block_fast(std::integral_constant<int, 1>{}, emit_one);
             } else {
                 for (; t + 8u <= full_steps; t += 8u) block_plain(std::integral_constant<int, 8>{});
                 for (; t < full_steps; ++t) block_plain(std::integral_constant<int, 1>{});
@@ -653,6 +747,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         if (X != state0) err |= ANSZP_ST_BAD_STATE;          // state 0
         if (((abit + 31u) >> 5) != skew + n_words) err |= ANSZP_ST_BAD_LENGTH;
     }
+    no_more_positions();
     err = wave_or(err);
     if (err && lane == 0) report(p.status, err);
 }
@@ -1338,7 +1433,7 @@ void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, b
                    bool small, hipStream_t s) {
     if (stepwise && streaming) {
         // chunks dealt evenly to as many workgroups as fill whole rounds of the device's CUs
-        const uint32_t per_round = device_cus() * uint32_t(kStreamWaves);
+        const uint32_t per_round = device_cus() * uint32_t(kStreamDecoders);
         const uint32_t rounds = (n_chunks + per_round - 1u) / per_round;
         const uint32_t groups = std::min(n_chunks, device_cus() * rounds);
         hipLaunchKernelGGL(decode_streaming<OUT>, dim3(groups), dim3(kStreamWaves * kWave), 0, s, p, n_chunks, groups);
