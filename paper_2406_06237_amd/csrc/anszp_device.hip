@@ -10,9 +10,10 @@
 //   decode_chunk_stepwise  one look-up per symbol from the paper's triple, words read from global
 //                          memory; handles every geometry the ABI allows (kernels decode_stepwise,
 //                          one chunk per workgroup, and decode_stepwise_shared, sixteen).
-//   decode_streaming       the same loop for thousands of large chunks: sixteen chunks per workgroup,
-//                          each stream's words fetched 32 bytes at a time through a ring in LDS, LDS
-//                          entries derived from the triples so that a step extracts no field.
+//   decode_streaming       one look-up per symbol for thousands of large chunks: fourteen wavefronts of
+//                          a workgroup decode a chunk each from 4-byte LDS entries derived from the
+//                          triples and store; two load, 64 bytes at a time, into each stream's ring
+//                          of words in LDS.
 //   decode_lookahead       look-ups use the look-ahead entries of the table (a run of empty-label
 //                          transitions of the dominant symbol, at most one of its 1-bit transitions
 //                          and the step that ends them are ONE look-up, indexed by the state and the
