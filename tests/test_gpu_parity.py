@@ -110,6 +110,36 @@ def test_many_large_chunks_take_the_streaming_kernel(orc):
     assert np.array_equal(B.bits_of(out)[:w.numel], expect)
 
 
+@pytest.mark.parametrize("dtype", ["u8", "f32", "bf16"])
+def test_no_dominant_symbol_ragged(orc, dtype):
+    """64 streams and no state that reads zero bits: the streaming kernel's split into decoding and loading
+    wavefronts, with a ragged last step, in every output type."""
+    w = W.tiny(seed=3, n=5 * 8192 + 37, bitwidth=5, n_streams=64, chunk_size=8192, table_log=10, p0=0.3, out_dtype=dtype)
+    _run(orc, w)
+
+
+def test_streaming_workgroups_spanning_many_layers(orc):
+    """800 layers of one chunk each: a workgroup of the streaming kernel gets chunks of three or four layers, more
+    than the two tables it stages."""
+    rng = np.random.default_rng(5)
+    layers = []
+    for i in range(800):
+        b = int(rng.integers(2, 6))
+        z = 1 << (b - 1)
+        layers.append(W.Layer(f"l{i}", (64 * int(rng.integers(3, 9)) + int(rng.integers(0, 64)),), b, z,
+                              float(rng.uniform(0.005, 0.05)), W.peaked_geometric_pmf(1 << b, z, float(rng.uniform(0.2, 0.9))), 100 + i))
+    w = W.Workload("many_layers", layers, 8, 64, 1024, "bf16")
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    d = B.to_device(host_from_oracle(c, w))
+    for variant in (B.VARIANT_STREAMING, B.VARIANT_STEPWISE_SHARED):
+        out = B.alloc_out(d)
+        out.view(torch.uint8).fill_(0xA5)
+        B.decode(d, out=out, variant=variant)
+        assert d.read_status() == (0, 0), f"variant {variant}"
+        assert np.array_equal(B.bits_of(out)[:w.numel], expect), f"variant {variant}"
+
+
 @pytest.mark.parametrize("R", [6, 8])
 def test_odd_bin_alphabets_with_small_tables(orc, R):
     """The alphabets the paper describes (odd bin counts 13..31, zero-point in the middle) coded with the
