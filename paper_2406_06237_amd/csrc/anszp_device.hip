@@ -646,11 +646,13 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             uint32_t left = uniform(per_channel ? (lay.channel_len - in_channel0) / kWave : 0xFFFFFFFFu);   // steps left under this scale
             const uint32_t steps = uniform(full_steps);
             bool stuck = false;
+            // (stores marked non-temporal: the weights are not read again here, and the lines of stream words,
+            // which are fetched in two halves some microseconds apart, should outlive them in the L2)
             auto emit = [&](int k, uint32_t e) {
                 char* const q = chunk_out + at + static_cast<uint32_t>(k) * (kWave * kElemBytes);
-                if constexpr (OUT == ANSZP_OUT_U8) *reinterpret_cast<uint8_t*>(q) = static_cast<uint8_t>(e >> 19);
-                else if constexpr (OUT == ANSZP_OUT_F32) *reinterpret_cast<float*>(q) = scaled_high_half(e, scale);
-                else *reinterpret_cast<__bf16*>(q) = static_cast<__bf16>(scaled_high_half(e, scale));
+                if constexpr (OUT == ANSZP_OUT_U8) __builtin_nontemporal_store(static_cast<uint8_t>(e >> 19), reinterpret_cast<uint8_t*>(q));
+                else if constexpr (OUT == ANSZP_OUT_F32) __builtin_nontemporal_store(scaled_high_half(e, scale), reinterpret_cast<float*>(q));
+                else __builtin_nontemporal_store(static_cast<__bf16>(scaled_high_half(e, scale)), reinterpret_cast<__bf16*>(q));
             };
             // K steps from the ring as the loading wavefront fills it: the window's four words must be there
             auto block_fed = [&](auto count_tag) {
