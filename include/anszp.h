@@ -71,6 +71,7 @@ extern "C" {
 #define ANSZP_ST_BAD_STATE    2u    /* a stream did not end in state 0                          */
 #define ANSZP_ST_BAD_LENGTH   4u    /* a stream read more or fewer words than its header says   */
 #define ANSZP_ST_INTERNAL     8u    /* a hand-over between wavefronts did not complete; chunk abandoned */
+#define ANSZP_ST_BAD_FREQ     16u   /* anszp_build_tables_device: a frequency row does not sum to 2^table_log */
 
 /* output element types */
 #define ANSZP_OUT_U8          0     /* decoded symbols, no dequantisation                       */
@@ -155,6 +156,16 @@ int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, 
  * Errors: as above, E_HIP, E_NOMEM. */
 int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
                        uint32_t* tables_dev, void* hip_stream);
+
+/* Sec. II-A / III-A on the device: the same tables, word for word, from normalised frequencies that
+ * are already in device memory (one workgroup per table; nothing passes through the host).
+ * freqs_dev: [device] n_tables rows of 256.  tables_dev: [device] n_tables * 4 * 2^table_log words,
+ * 16-byte aligned.  status_dev: [device] 2 words as in anszp_decode_args_t, or NULL: a row that
+ * does not sum to 2^table_log leaves its table all zero and sets ANSZP_ST_BAD_FREQ (the host cannot
+ * see the rows, so this is not a return code).  Asynchronous on hip_stream; both buffers stay owned
+ * by the caller.  Errors: E_NULL, E_RANGE, E_HIP. */
+int anszp_build_tables_device(const uint32_t* freqs_dev, int n_tables, int table_log,
+                              uint32_t* tables_dev, uint32_t* status_dev, void* hip_stream);
 
 /* [host only] Worst-case sizes for anszp_pack_layer: number of chunks and payload words. */
 int anszp_pack_bound(uint64_t n_symbols, int table_log, int n_streams, uint32_t chunk_size,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libanszp.so")
 
 OUT_U8, OUT_F32, OUT_BF16 = 0, 1, 2
 OUT_CODES = {"u8": OUT_U8, "f32": OUT_F32, "bf16": OUT_BF16}
-ST_BAD_DESC, ST_BAD_STATE, ST_BAD_LENGTH = 1, 2, 4
+ST_BAD_DESC, ST_BAD_STATE, ST_BAD_LENGTH, ST_INTERNAL, ST_BAD_FREQ = 1, 2, 4, 8, 16
 MAX_TABLE_LOG, MAX_STREAMS, ALPHABET = 12, 64, 256
 
 CHUNK_DTYPE = np.dtype([("layer_id", "<u4"), ("n_symbols", "<u4"), ("out_offset", "<u8"),
@@ -47,7 +47,7 @@ class AnszpError(RuntimeError):
 
 _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
-           "anszp_build_tables", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
+           "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
            "anszp_dequant_zp"]
 
 
@@ -69,6 +69,7 @@ def lib():
         L.anszp_normalize_freqs.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         L.anszp_build_tables_host.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.anszp_build_tables.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.anszp_build_tables_device.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.anszp_pack_bound.argtypes = [C.c_uint64, C.c_int, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p]
         L.anszp_pack_layer.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int, C.c_int, C.c_uint32,
                                        C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint32,
@@ -230,6 +231,20 @@ def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
         tables = torch.empty((len(freqs) << table_log) * 16, dtype=torch.uint8, device=device)
         _check(lib().anszp_build_tables(freqs.ctypes.data, len(freqs), table_log, tables.data_ptr(),
                                         _stream_ptr(torch, device)), "anszp_build_tables")
+    return tables
+
+
+def build_tables_device(freqs_dev, table_log: int, status=None):
+    """anszp_build_tables_device: freqs_dev is an int32/uint32-valued device tensor of n_tables x 256 entries;
+    returns the tables as a new device tensor (int32 view of n_tables * 4 * 2^table_log words)."""
+    torch = _torch()
+    device = freqs_dev.device
+    n_tables = freqs_dev.numel() // ALPHABET
+    with torch.cuda.device(device):
+        tables = torch.empty((n_tables << table_log) * 4, dtype=torch.int32, device=device)
+        _check(lib().anszp_build_tables_device(freqs_dev.data_ptr(), n_tables, table_log, tables.data_ptr(),
+                                               status.data_ptr() if status is not None else None,
+                                               _stream_ptr(torch, device)), "anszp_build_tables_device")
     return tables
 
 

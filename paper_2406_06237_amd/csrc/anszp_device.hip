@@ -1404,6 +1404,118 @@ void decode_merged_small(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, Sm
 
 // ---------------------------------------------------------------------------------------------
 // Sec. II-B alone.
+// ---------------------------------------------------------------------------------------------
+// Decode tables built on the device (Sec. II-A "initialization of the states", Sec. III-A one
+// table per layer): one workgroup per table, same words as anszp_build_tables_host.
+//
+// The host merges the per-symbol position sequences (occurrence i of a symbol of frequency f sits
+// at (2i+1)/(2f); ties go to the smaller symbol) with a heap.  Here every occurrence computes its
+// own rank instead: the number of occurrences of every other symbol that come before it, in exact
+// integer arithmetic, is a quotient.  The rank is the state X; the occurrence index gives the
+// sub-state f + i, hence nb_bits and newX; the look-ahead entries then follow the step table in LDS.
+constexpr uint32_t kBuildThreads = 1024u;
+
+__global__ __launch_bounds__(kBuildThreads) void build_tables_kernel(const uint32_t* freqs, int table_log, uint32_t* tables,
+                                                                     uint32_t* status) {
+    constexpr uint32_t kStates = 1u << ANSZP_MAX_TABLE_LOG;
+    __shared__ uint32_t freq[ANSZP_ALPHABET];           // of every symbol
+    __shared__ uint32_t used_sym[ANSZP_ALPHABET];       // symbols with f > 0, in increasing order
+    __shared__ uint32_t used_first[ANSZP_ALPHABET + 1]; // occurrences of the symbols before each of them
+    __shared__ uint32_t n_used, total, dominant_sym;
+    __shared__ uint8_t st_sym[kStates], st_nb[kStates];
+    __shared__ uint16_t st_newX[kStates];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t L = 1u << table_log;
+    const uint32_t* f = freqs + size_t(blockIdx.x) * ANSZP_ALPHABET;
+    uint32_t* out = tables + (size_t(blockIdx.x) << (table_log + 2));
+    if (tid < ANSZP_ALPHABET) freq[tid] = f[tid];
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t n = 0, acc = 0, dom = 0xFFFFFFFFu;
+        for (uint32_t sy = 0; sy < ANSZP_ALPHABET; ++sy) {
+            const uint32_t fs = freq[sy];
+            if (fs > L / 2) dom = sy;
+            if (fs) {
+                used_sym[n] = sy;
+                used_first[n] = acc;
+                ++n;
+            }
+            acc = min(acc + min(fs, L + 1u), L + 1u);   // saturating: a row that overshoots is rejected below
+        }
+        used_first[n] = acc;
+        n_used = n;
+        total = acc;
+        dominant_sym = dom;
+    }
+    __syncthreads();
+    if (total != L) {                                   // not a normalised row: an all-zero table and a status bit
+        for (uint32_t i = tid; i < 4u * L; i += kBuildThreads) out[i] = 0u;
+        if (tid == 0 && status) report(status, ANSZP_ST_BAD_FREQ);
+        return;
+    }
+    const uint32_t used = n_used;
+    for (uint32_t g = tid; g < L; g += kBuildThreads) {
+        // occurrence g in symbol order: symbol used_sym[k], its i-th occurrence
+        uint32_t lo = 0, hi = used;                     // used_first[lo] <= g < used_first[hi]
+        while (hi - lo > 1u) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (used_first[mid] <= g) lo = mid; else hi = mid;
+        }
+        const uint32_t sy = used_sym[lo], fs = freq[sy], i = g - used_first[lo];
+        uint32_t rank = i;
+        for (uint32_t k = 0; k < used; ++k) {
+            if (k == lo) continue;
+            const uint32_t fo = freq[used_sym[k]];
+            // occurrences i' of the other symbol with (2i'+1) fs < (2i+1) fo, or <= when it is the smaller symbol
+            // (all quantities are below 2^26: i < fs <= L, fo <= L <= 4096)
+            const int32_t q = static_cast<int32_t>((2u * i + 1u) * fo) - static_cast<int32_t>(fs);
+            uint32_t before;
+            if (k < lo) before = q < 0 ? 0u : static_cast<uint32_t>(q) / (2u * fs) + 1u;
+            else before = q <= 0 ? 0u : (static_cast<uint32_t>(q) + 2u * fs - 1u) / (2u * fs);
+            rank += min(before, fo);
+        }
+        // Sec. II-A: sub-state f + i, shifted left until it lies in [L, 2L)
+        const uint32_t v = fs + i;
+        const uint32_t shift = static_cast<uint32_t>(table_log) - (31u - static_cast<uint32_t>(__clz(v)));
+        st_sym[rank] = static_cast<uint8_t>(sy);
+        st_nb[rank] = static_cast<uint8_t>(shift);
+        st_newX[rank] = static_cast<uint16_t>((v << shift) - L);
+    }
+    __syncthreads();
+    for (uint32_t X = tid; X < L; X += kBuildThreads) {
+        out[2u * L + X] = uint32_t(st_newX[X]) | (uint32_t(st_nb[X]) << 16) | (uint32_t(st_sym[X]) << 24);
+        out[3u * L + X] = 0u;
+    }
+    // look-ahead entries: up to kMaxMerged steps merged into one look-up, indexed by the state and the next bit
+    const uint32_t dominant = dominant_sym;
+    for (uint32_t e = tid; e < 2u * L; e += kBuildThreads) {
+        const uint32_t X = e >> 1, b = e & 1u;
+        uint32_t Y = X, count = 0, bits = 0, last_sym = 0, saved_Y = 0, saved_count = 0;
+        bool took_b = false;
+        int32_t base = 0;
+        for (;;) {
+            const uint32_t n = st_nb[Y];
+            const bool room = count + 1u < kMaxMerged;                 // another symbol may follow this one
+            if (n == 0u && room) { ++count; Y = st_newX[Y]; continue; }
+            if (n == 1u && room && !took_b && uint32_t(st_sym[Y]) == dominant) {
+                saved_Y = Y; saved_count = count;
+                took_b = true; ++count; Y = uint32_t(st_newX[Y]) | b;
+                continue;
+            }
+            if (took_b && 1u + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {    // too many bits for one look-up: stop at the 1-bit step
+                Y = saved_Y; count = saved_count;
+                bits = 1u; base = int32_t(2u * st_newX[Y]); last_sym = st_sym[Y];
+                break;
+            }
+            bits = (took_b ? 1u : 0u) + n;
+            base = int32_t(2u * st_newX[Y]) - (took_b ? int32_t(b << (n + 1u)) : 0);
+            last_sym = st_sym[Y];
+            break;
+        }
+        out[e] = (31u - bits) | (last_sym << 8) | (count << 16) | (uint32_t(base) << 18);
+    }
+}
+
 template <int OUT>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* sym, uint64_t n, anszp_layer_t lay,
                                                       const float* scales, uint64_t n_scales, void* out) {
@@ -1510,6 +1622,16 @@ int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
     }
     (void)hipHostFree(staging);
     return rc;
+}
+
+int anszp_build_tables_device(const uint32_t* freqs_dev, int n_tables, int table_log,
+                              uint32_t* tables_dev, uint32_t* status_dev, void* hip_stream) {
+    if (!freqs_dev || !tables_dev) return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
+    if (reinterpret_cast<uintptr_t>(tables_dev) & 15) return ANSZP_E_RANGE;
+    hipLaunchKernelGGL(build_tables_kernel, dim3(static_cast<uint32_t>(n_tables)), dim3(kBuildThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), freqs_dev, table_log, tables_dev, status_dev);
+    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }
 
 int anszp_decode(const anszp_decode_args_t* args, void* hip_stream) { return decode_impl(args, 0, hip_stream); }

@@ -184,6 +184,53 @@ def test_dequant_zp_alone(orc):
             assert np.array_equal(got, want.view(np.uint32) if dt == "f32" else want)
 
 
+def test_tables_built_on_the_device_equal_the_host_tables(orc):
+    """anszp_build_tables_device against anszp_build_tables_host, word for word, over the frequency rows of the
+    benchmark sets and of edge cases (one symbol, two symbols, all 256, a dominant symbol, ties between symbols of
+    equal frequency), at several table sizes; a row that is not normalised is reported and yields zeros; and a
+    container decodes with device-built tables."""
+    import torch
+    rng = np.random.default_rng(11)
+    for R in (1, 5, 8, 10, 12):
+        L = 1 << R
+        rows = []
+        one = np.zeros(256, np.uint32); one[7] = L; rows.append(one)
+        if L >= 2:
+            two = np.zeros(256, np.uint32); two[3] = L // 2; two[200] = L - L // 2; rows.append(two)
+            dom = np.zeros(256, np.uint32); dom[8] = L - 1; dom[9] = 1; rows.append(dom)
+        if L >= 256:
+            flat = np.full(256, L // 256, np.uint32); rows.append(flat)
+        for _ in range(12):
+            k = int(rng.integers(1, min(L, 256) + 1))
+            counts = np.zeros(256, np.uint64)
+            counts[rng.choice(256, size=k, replace=False)] = rng.integers(1, 1000, size=k).astype(np.uint64) ** int(rng.integers(1, 4))
+            rows.append(B.normalize_freqs(counts, R))
+        freqs = np.stack(rows)
+        want = B.build_tables_host(freqs, R)
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        got = B.build_tables_device(torch.from_numpy(freqs.astype(np.int32)).cuda(), R, status)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32).reshape(want.shape), want), f"table_log {R}"
+        assert status.cpu().tolist() == [0, 0]
+    # not normalised: zeros and a status bit, the other tables of the call are unaffected
+    bad = np.stack([B.normalize_freqs(np.arange(256, dtype=np.uint64) + 1, 10)] * 3)
+    bad[1, 0] += 1
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    got = B.build_tables_device(torch.from_numpy(bad.astype(np.int32)).cuda(), 10, status).cpu().numpy().view(np.uint32).reshape(3, -1)
+    want = B.build_tables_host(bad[[0, 2]], 10)
+    assert np.array_equal(got[[0, 2]], want) and not got[1].any()
+    assert status.cpu().tolist() == [B.ST_BAD_FREQ, 1]
+    # decode with device-built tables
+    w = W.config2()
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    h = host_from_oracle(c, w)
+    d = B.to_device(h)
+    d.tables = B.build_tables_device(torch.from_numpy(np.ascontiguousarray(h.freqs).astype(np.int32)).cuda(), h.table_log)
+    out = B.decode(d)
+    assert d.read_status() == (0, 0)
+    assert np.array_equal(B.bits_of(out)[:w.numel], expect)
+
+
 @pytest.mark.parametrize("p0", [0.7, 0.3])
 def test_corruption_is_flagged_not_fatal(orc, p0):
     """Damaged inputs set status bits; nothing is read or written outside the buffers.  With p0 = 0.3 no state
