@@ -200,8 +200,9 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  *      compressed words and decoded symbols are staged in LDS, and the work of a chunk is split
  *      over several wavefronts of its workgroup
  *   3  step-wise kernel with sixteen chunks per workgroup sharing the tables in LDS
- *   4  the same with each stream's words fetched 32 bytes at a time through a ring in LDS (what
- *      the automatic choice takes for thousands of chunks too large for the on-chip window)
+ *   4  streaming kernel: one look-up per symbol from compact entries in LDS, each stream's words
+ *      fetched 64 bytes at a time through a ring in LDS by wavefronts that only load (what the
+ *      automatic choice takes when the chunks are too large for the on-chip window)
  * Errors: as anszp_decode, E_RANGE for an unknown variant. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 

@@ -96,9 +96,9 @@ def test_config4_one_block_at_real_shapes(orc):
 
 
 def test_many_large_chunks_take_the_streaming_kernel(orc):
-    """More than 4096 chunks whose words exceed the on-chip window: the automatic choice must be the
-    streaming kernel (sixteen chunks per workgroup, several layers per workgroup at layer boundaries,
-    per-channel scales, a ragged last chunk per layer) and must decode every element."""
+    """More than 4096 chunks whose words exceed the on-chip window: the automatic choice is the streaming
+    kernel (fourteen chunks per workgroup, several layers per workgroup at layer boundaries, per-channel
+    scales, a ragged last chunk per layer) and must decode every element."""
     w = W.config4(n_blocks=1)
     w.chunk_size = 49152 - 64 * 3          # 4096 x 4096 and 4096 x 11008 are not multiples: ragged tails
     c = oracle_encode(orc, w)
