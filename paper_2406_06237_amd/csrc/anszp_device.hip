@@ -371,8 +371,8 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         if (tid + 3u * kThreads < L) tb3 = src_b[tid + 3u * kThreads];
     }
     auto reads_no_bits = [](uint32_t e) { return ((e >> 16) & 0xFFu) == 0u; };
-    const bool some_zero = reads_no_bits(ta0) | reads_no_bits(ta1) | reads_no_bits(ta2) | reads_no_bits(ta3) |
-                           reads_no_bits(tb0) | reads_no_bits(tb1) | reads_no_bits(tb2) | reads_no_bits(tb3);
+    const bool some_zero = reads_no_bits(ta0) || reads_no_bits(ta1) || reads_no_bits(ta2) || reads_no_bits(ta3) ||
+                           reads_no_bits(tb0) || reads_no_bits(tb1) || reads_no_bits(tb2) || reads_no_bits(tb3);
     const bool fast = !__syncthreads_or(some_zero) && N == kWave;
     auto place = [&](uint32_t e, uint32_t i, uint32_t which, uint32_t z) {
         if (i >= L) return;
@@ -852,7 +852,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // the next slab each storing wavefront will take | 4 the block phase is over | 5 a wait gave up |
     // 6, 7 a storing wavefront has stored all it can | 8, 9 lower, upper half of the triples are in LDS
     lds_flag_t* const ctl = (lds_flag_t*)(lds + kCtlOff);
-    lds_flag_t* const blk_hdr = (lds_flag_t*)(lds + kHdrOff);   // lanes lo, hi, look-ups, -
+    // (block headers at kHdrOff, written and read by the assembly below: lanes lo, lanes hi, look-ups, -)
     enum { kLogged = 0, kExpanded = 1, kStored0 = 2, kStored1 = 3, kOver = 4, kGaveUp = 5, kStoreDone0 = 6, kStoreDone1 = 7,
            kTriplesLo = 8, kTriplesHi = 9 };
     constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
