@@ -169,8 +169,10 @@ def pack_layers(layer_symbols: Sequence[np.ndarray], table_log: int, n_streams: 
                 zero_points: Sequence[int], scales: Sequence[float], bitwidths: Optional[Sequence[int]] = None,
                 channel_len: Optional[Sequence[int]] = None,
                 channel_scales: Optional[Sequence[Optional[np.ndarray]]] = None,
-                out_dtype: str = "bf16", freqs: Optional[Sequence[np.ndarray]] = None) -> HostContainer:
-    """Compress a list of layers into one container with the library's host packer."""
+                out_dtype: str = "bf16", freqs: Optional[Sequence[np.ndarray]] = None,
+                chunk_sizes: Optional[Sequence[int]] = None) -> HostContainer:
+    """Compress a list of layers into one container with the library's host packer (chunk_sizes: one chunk
+    size per layer instead of chunk_size for all)."""
     nl = len(layer_symbols)
     layers = np.zeros(nl, dtype=LAYER_DTYPE)
     fr, ch, hd, pl, sc = [], [], [], [], []
@@ -179,7 +181,8 @@ def pack_layers(layer_symbols: Sequence[np.ndarray], table_log: int, n_streams: 
         sym = np.ascontiguousarray(sym, dtype=np.uint8)
         f = (normalize_freqs(np.bincount(sym, minlength=ALPHABET), table_log) if freqs is None
              else np.ascontiguousarray(freqs[li], dtype=np.uint32))
-        chunks, hdr, payload = pack_layer(sym, f, table_log, n_streams, chunk_size, li, elem, words, streams)
+        chunks, hdr, payload = pack_layer(sym, f, table_log, n_streams, chunk_sizes[li] if chunk_sizes is not None else chunk_size,
+                                          li, elem, words, streams)
         layers[li] = (scales[li], zero_points[li], bitwidths[li] if bitwidths is not None else 8,
                       channel_len[li] if channel_len is not None else 0, n_sc, elem)
         if channel_len is not None and channel_len[li]:

@@ -1,0 +1,67 @@
+"""Streams grouped as in the paper against the benchmark's geometry (Sec. III-B: the streams of a layer are the
+weights of its input channels, decoded in parallel).
+
+On the ResNet-50-shaped set of config 3, with 64 streams per chunk in both cases:
+  benchmark   chunks of 65,536 symbols, streams of 1,024 symbols
+  by channel  one chunk per 64 input channels: a stream holds the Cout * kh * kw weights of one input channel
+              (weights stored [Cin / 64][Cout][kh][kw][64], so that the 64 streams of a chunk are 64 consecutive
+              input channels and every wavefront-step still writes 64 consecutive elements)
+The synthetic symbols are i.i.d. within a layer, so the layout changes nothing but the geometry: what is
+compared is the framing cost (bytes) and the length of the chain each lane walks (decode time on the GPU).
+
+    python -m paper_2406_06237_amd.stream_grouping_study [--gpu] [--steps K]
+"""
+import argparse
+
+import numpy as np
+
+from . import binding as B
+from . import workloads as W
+
+
+def containers():
+    w = W.config3()
+    L = w.layers
+    by_channel = [64 * max(int(np.prod(l.shape)) // l.shape[1], 1) if len(l.shape) == 4 else int(np.prod(l.shape)) for l in L]
+    out = {}
+    for name, sizes in (("benchmark", None), ("by channel", by_channel)):
+        out[name] = B.pack_layers(w.symbols(), w.table_log, w.n_streams, w.chunk_size, [l.zero_point for l in L],
+                                  [l.scale for l in L], [l.bitwidth for l in L], [l.channel_len for l in L],
+                                  [l.channel_scales for l in L], w.out_dtype, chunk_sizes=sizes)
+    return w, out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpu", action="store_true", help="also time anszp_decode of both containers on cuda:0")
+    ap.add_argument("--steps", type=int, default=20)
+    a = ap.parse_args()
+    w, cs = containers()
+    for name, h in cs.items():
+        used = int(np.count_nonzero(h.stream_hdr >> 16))
+        size = 4 * len(h.payload) + 4 * len(h.stream_hdr)
+        longest = int(h.chunks["n_symbols"].max()) // h.n_streams
+        line = (f"{name:<11} {len(h.chunks):>5} chunks {used:>6} streams, longest stream {longest:>6} symbols, "
+                f"{size / 1e6:.3f} MB ({8 * size / w.numel:.4f} bit/weight)")
+        if a.gpu:
+            import torch
+            d = B.to_device(h, "cuda:0")
+            out = B.alloc_out(d)
+            args = B.decode_args(d, out)
+            stream = torch.cuda.current_stream("cuda:0")
+            for _ in range(3):
+                B.decode_raw(args, "cuda:0")
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(a.steps):
+                B.decode_raw(args, "cuda:0")
+            e1.record(stream)
+            torch.cuda.synchronize()
+            assert d.read_status() == (0, 0)
+            line += f", decode {1e3 * e0.elapsed_time(e1) / a.steps:.1f} us"
+        print(line, flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -215,3 +215,17 @@ def test_table_size_study_trend():
         if not g.startswith("single"):
             assert total > single[st]                                  # framing is not free
             assert paper_like < single[st] * 1.03, (st, g, paper_like / single[st])
+
+
+def test_stream_grouping_geometries():
+    """Sec. III-B grouping (a stream per input channel) against the benchmark's chunks on config 3: about as many
+    streams, hence about the same bytes, but streams up to 4.5 times as long."""
+    from paper_2406_06237_amd import stream_grouping_study as S
+    w, cs = S.containers()
+    size = {k: 4 * len(h.payload) + 4 * len(h.stream_hdr) for k, h in cs.items()}
+    streams = {k: int(np.count_nonzero(h.stream_hdr >> 16)) for k, h in cs.items()}
+    assert sum(int(c) for c in cs["by channel"].chunks["n_symbols"]) == w.numel
+    assert abs(size["by channel"] / size["benchmark"] - 1.0) < 0.01
+    assert abs(streams["by channel"] / streams["benchmark"] - 1.0) < 0.06
+    assert int(cs["by channel"].chunks["n_symbols"].max()) // 64 == 4608
+    assert int(cs["benchmark"].chunks["n_symbols"].max()) // 64 == 1024
