@@ -75,8 +75,8 @@ def main():
                     help="also run a plain device copy of this many MiB five times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build decodes on ONE GPU (chunks are independent; sharding them over GPUs needs "
-              "no collective and is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build decodes on ONE GPU (chunks are independent: each GPU would decode the chunks "
+              "of its own layers, no collective involved). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
