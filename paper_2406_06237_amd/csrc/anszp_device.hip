@@ -438,7 +438,8 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     };
 
     if (wave >= uint32_t(kStreamDecoders)) {
-        // ---- loading wavefront: decoders wave - 14, + 2, + 4, ...
+        // ---- loading wavefront: decoders wave - 14, + 2, + 4, ... (little to issue, and others wait for it: first in line)
+        __builtin_amdgcn_s_setprio(3);
         const uint32_t mine_index = wave - uint32_t(kStreamDecoders);
         const uint32_t* where[kStreamServed];             // all indexed by constants once the loops are unrolled
         uint32_t readable[kStreamServed], fetched[kStreamServed];
@@ -668,12 +669,32 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                 steps_fast(count_tag, w0, w1, w2, emit);
                 position[lane] = abit >> 5;
             };
+            // Wavefronts go to the four SIMDs round robin, and a SIMD serves the oldest of its wavefronts
+            // first: left alone, the decoders of a workgroup finish in the order of their age, 15 % apart,
+            // and the youngest run the end of the launch alone on their SIMDs.  So the decoders of a SIMD
+            // take turns at each priority, every 8 blocks.
+            const uint32_t sharing = (count - (wave & 3u) + 3u) / 4u;      // decoders on this wavefront's SIMD
+            uint32_t turn = 0;
+            auto take_turn = [&]() {
+                if (sharing < 2u) return;
+                switch (((wave >> 2) + (turn >> 3)) % sharing) {
+                    case 0: __builtin_amdgcn_s_setprio(0); break;
+                    case 1: __builtin_amdgcn_s_setprio(1); break;
+                    case 2: __builtin_amdgcn_s_setprio(2); break;
+                    default: __builtin_amdgcn_s_setprio(3); break;
+                }
+            };
+            take_turn();
             uint32_t t = 0;
             while (t < steps && !stuck) {
                 uint32_t seg = min(steps - t, left);
                 t += seg;
                 left -= seg;
-                for (; seg >= 8u && !stuck; seg -= 8u) { block_fed(std::integral_constant<int, 8>{}); at += 8u * kWave * kElemBytes; }
+                for (; seg >= 8u && !stuck; seg -= 8u) {
+                    block_fed(std::integral_constant<int, 8>{});
+                    at += 8u * kWave * kElemBytes;
+                    if ((++turn & 7u) == 0u) take_turn();
+                }
                 if (seg >= 4u && !stuck) { block_fed(std::integral_constant<int, 4>{}); at += 4u * kWave * kElemBytes; seg -= 4u; }
                 for (; seg && !stuck; --seg) { block_fed(std::integral_constant<int, 1>{}); at += kWave * kElemBytes; }
                 if (left == 0u) {
