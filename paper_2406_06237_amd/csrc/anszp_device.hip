@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstddef>
 #include <type_traits>
 
 namespace {
@@ -348,6 +349,10 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
     const bool have_a = layer_a < p.n_tables, have_b = layer_b != layer_a && layer_b < p.n_tables;
     lds_flag_t* const gave_up = (lds_flag_t*)&lds.gave_up;
+    if (lds_address(&lds) % (kStreamRingWords * kWave * 4u) != 0u) {      // the ring addressing below relies on it
+        if (tid == 0) report(p.status, ANSZP_ST_INTERNAL);
+        return;
+    }
     if (tid < uint32_t(kStreamDecoders) * kWave) ((lds_flag_t*)&lds.position[0][0])[tid] = kStreamNotStarted;
     if (tid == 0) *gave_up = 0u;
 
@@ -569,13 +574,19 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
 
     uint32_t abit = 32u * skew;                           // bit position, counted from the first word fetched
     // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
+    // (a ring is as large as it is aligned, so the slot of a word is a bit field of its address: two
+    // instructions per address instead of four)
+    constexpr uint32_t kRingBytes = kStreamRingWords * kWave * 4u;
+    static_assert((kRingBytes & (kRingBytes - 1u)) == 0u && offsetof(Lds, rings) % kRingBytes == 0u, "rings aligned to their size");
+    // (that the object itself starts on such a boundary is checked when the workgroup starts)
+    const uint32_t my_words = lds_address(&ring[0][lane]);               // word 0 of this lane
     auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
-        const uint32_t cw = abit >> 5;
-        constexpr uint32_t kMask = kStreamRingWords - 1u;
-        w0 = ring[cw & kMask][lane];
-        w1 = ring[(cw + 1u) & kMask][lane];
-        w2 = ring[(cw + 2u) & kMask][lane];
-        w3 = ring[(cw + 3u) & kMask][lane];
+        constexpr uint32_t kSlotField = (kStreamRingWords - 1u) * kWave * 4u;          // 0x1F00
+        const uint32_t at = abit << 3;                                     // (abit >> 5) words * 256 bytes per slot, low bits dropped by the mask
+        auto word = [&](uint32_t i) {
+            return *reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(((at + i * kWave * 4u) & kSlotField) | my_words));
+        };
+        w0 = word(0); w1 = word(1); w2 = word(2); w3 = word(3);
         w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
