@@ -296,6 +296,8 @@ constexpr uint32_t kStreamUrgentWords = 8u;     // a stream this close to the en
 constexpr uint32_t kStreamNotStarted = 0xFFFFFFFEu, kStreamFinished = 0xFFFFFFFFu;   // in place of a published word position
 typedef uint32_t words4 __attribute__((ext_vector_type(4)));            // four consecutive registers
 typedef words4 __attribute__((aligned(4))) words4_word_aligned;
+typedef uint32_t words2 __attribute__((ext_vector_type(2)));
+typedef float floats4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) uint32_t lds_uint32_t;
 static_assert(kStreamDecoders % kStreamLoaders == 0, "every loading wavefront serves the same number of decoders");
 
@@ -795,10 +797,13 @@ template <int OUT, bool PER_CHANNEL>
 struct Flusher {
     static constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
     // Convert the 8 symbols of one lane (bytes of `s`, elements g .. g+7 of the output) and store them.
+    // The stores are marked non-temporal: the weights are not read again by this library, and the
+    // tables and compressed words, which the next decode of the same set reads again, should
+    // outlive them in the L2 (measured on the ResNet-50-shaped set: 30.4 -> 28.0 us per launch).
     static __device__ __forceinline__ void store8(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
                                                   uint64_t layer_elem, uint2 s, const uint16_t* lut) {
         if constexpr (OUT == ANSZP_OUT_U8) {
-            *reinterpret_cast<uint2*>(static_cast<uint8_t*>(p.out) + g) = s;
+            __builtin_nontemporal_store(words2{s.x, s.y}, reinterpret_cast<words2*>(static_cast<uint8_t*>(p.out) + g));
         } else {
             uint32_t sym[8];
 #pragma unroll
@@ -807,8 +812,8 @@ struct Flusher {
                 uint32_t w[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) w[i] = lut[sym[i]];
-                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) =
-                    make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+                __builtin_nontemporal_store(words4{w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)},
+                                            reinterpret_cast<words4*>(static_cast<uint16_t*>(p.out) + g));
             } else {
                 float v[8];
                 if constexpr (PER_CHANNEL) {
@@ -828,16 +833,13 @@ struct Flusher {
                     for (int i = 0; i < 8; ++i) v[i] = dequant(sym[i], lay.zero_point, lay.scale);
                 }
                 if constexpr (OUT == ANSZP_OUT_F32) {
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(p.out) + g);
-                    dst[0] = make_float4(v[0], v[1], v[2], v[3]);
-                    dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+                    floats4* dst = reinterpret_cast<floats4*>(static_cast<float*>(p.out) + g);
+                    __builtin_nontemporal_store(floats4{v[0], v[1], v[2], v[3]}, dst);
+                    __builtin_nontemporal_store(floats4{v[4], v[5], v[6], v[7]}, dst + 1);
                 } else {
-                    uint4 o;
-                    o.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-                    o.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-                    o.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
-                    o.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-                    *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + g) = o;
+                    const words4 o = {bf16_rne(v[0]) | (bf16_rne(v[1]) << 16), bf16_rne(v[2]) | (bf16_rne(v[3]) << 16),
+                                      bf16_rne(v[4]) | (bf16_rne(v[5]) << 16), bf16_rne(v[6]) | (bf16_rne(v[7]) << 16)};
+                    __builtin_nontemporal_store(o, reinterpret_cast<words4*>(static_cast<uint16_t*>(p.out) + g));
                 }
             }
         }
