@@ -1238,7 +1238,14 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     {
         uint32_t e = lds_table[X4 >> 2];
         const uint32_t lane_log = kLogOff + lane * 4u;
-#define ANSZP_LOOKUP(EA, EB, K)                                                         \
+// The window is shifted only as far up as a later look-up of the block can still read: a look-up
+// reads at most 12 bits and peeks one, so with j look-ups to follow only the first 12 j + 1 bits
+// matter: w0 is shifted by every look-up but the last, w1 while four or more follow, w2 while
+// seven follow, w3 never (what a stale register feeds into its neighbour lies beyond that reach).
+#define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
+#define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
+#define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
+#define ANSZP_LOOKUP(EA, EB, K, SHIFT)                                                  \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
         "v_lshrrev_b32 v36, " EA ", v33\n"                                             \
         "v_bfe_i32 v37, " EA ", 18, 14\n"                                              \
@@ -1247,15 +1254,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         "ds_write_b32 v42, " EA " offset:" K "*256\n"                                  \
         "v_not_b32 v35, " EA "\n"                                                      \
         "v_bfe_u32 v39, " EA ", 16, 2\n"                                               \
-        "v_alignbit_b32 v28, v29, v28, v35\n"                                          \
-        "v_alignbit_b32 v29, v30, v29, v35\n"                                          \
-        "v_alignbit_b32 v30, v31, v30, v35\n"                                          \
+        SHIFT                                                                          \
         "v_bfrev_b32 v33, v28\n"                                                       \
-        "v_lshrrev_b32 v31, v35, v31\n"                                                \
         "v_add_u32 v41, v41, " EA "\n"                                                 \
         "v_mad_u32_u24 v34, v39, %[nstr], v34\n"
-#define ANSZP_AB(K) ANSZP_LOOKUP("v24", "v25", K)
-#define ANSZP_BA(K) ANSZP_LOOKUP("v25", "v24", K)
+#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT)
+#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v25", "v24", K, SHIFT)
 // BODY = all look-ups of a block but the last, which is written out below: it skips the window
 // shift.  Blocks have an even number of look-ups, so the entry ends up in v24 again.
 #define ANSZP_RUN_BLOCKS(STEPS, BODY)                                                                                 \
@@ -1363,13 +1367,19 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                          : [v] "=v"(v) : [zero] "v"(0u), [ctlw0] "n"(kCtlOff) : "memory");
             return v;
         };
-        ANSZP_RUN_BLOCKS(8, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2") ANSZP_BA("3") ANSZP_AB("4") ANSZP_BA("5") ANSZP_AB("6"))
-        ANSZP_RUN_BLOCKS(4, ANSZP_AB("0") ANSZP_BA("1") ANSZP_AB("2"))
-        ANSZP_RUN_BLOCKS(2, ANSZP_AB("0"))
+        static_assert(ANSZP_MAX_TABLE_LOG <= 12, "the reach of a look-up assumed by the window shifts");
+        ANSZP_RUN_BLOCKS(8, ANSZP_AB("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
+                            ANSZP_BA("3", ANSZP_SHIFT_W1) ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0)
+                            ANSZP_AB("6", ANSZP_SHIFT_W0))
+        ANSZP_RUN_BLOCKS(4, ANSZP_AB("0", ANSZP_SHIFT_W1) ANSZP_BA("1", ANSZP_SHIFT_W0) ANSZP_AB("2", ANSZP_SHIFT_W0))
+        ANSZP_RUN_BLOCKS(2, ANSZP_AB("0", ANSZP_SHIFT_W0))
 #undef ANSZP_RUN_BLOCKS
 #undef ANSZP_AB
 #undef ANSZP_BA
 #undef ANSZP_LOOKUP
+#undef ANSZP_SHIFT_W2
+#undef ANSZP_SHIFT_W1
+#undef ANSZP_SHIFT_W0
         // the block phase is over: the look-ahead entries may be replaced, the expanding and storing
         // wavefronts finish what is logged; then this wavefront owns the ring
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
