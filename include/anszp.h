@@ -78,7 +78,10 @@ extern "C" {
 #define ANSZP_OUT_F32         1     /* IEEE binary32                                            */
 #define ANSZP_OUT_BF16        2     /* bfloat16, round-to-nearest-even of the binary32 value    */
 
-/* One chunk (32 bytes).  Arrays of these live in device memory for anszp_decode. */
+/* One chunk (32 bytes).  Arrays of these live in device memory for anszp_decode.  A descriptor
+   names everything its chunk touches, so the array may be in any order: workgroups are handed
+   out in array order, and a launch whose chunks differ much in size ends sooner when the chunks
+   with the most payload words come first. */
 typedef struct {
     uint32_t layer_id;        /* selects the table and the anszp_layer_t                       */
     uint32_t n_symbols;       /* symbols in this chunk; stream k holds ceil((n_symbols-k)/N)   */
