@@ -875,7 +875,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRingOff = kLutOff + 512u;
     constexpr uint32_t kLogOff = kRingOff + kRingElems;             // logged entries: [slot][look-up][lane]
     constexpr uint32_t kLdsBytes = kLogOff + kLogSlots * kLogSlotBytes;
-    static_assert(kTableOff % 16u == 0 && kRingOff % 16u == 0 && kCtlOff % 8u == 0 && kRingOff < 65536u, "LDS layout");
+    static_assert(kTableOff % 16u == 0 && kRingOff % 16u == 0 && kCtlOff % 16u == 0 && kHdrOff % 16u == 0 &&
+                  kRingOff < 65536u && kLogSlotBytes == 16u << 7, "LDS layout");
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     uint32_t* const lds_words = reinterpret_cast<uint32_t*>(lds);
@@ -1245,7 +1246,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
-#define ANSZP_LOOKUP(EA, EB, K, SHIFT)                                                  \
+#define ANSZP_LOOKUP(EA, EB, K, SHIFT, SUM)                                             \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
         "v_lshrrev_b32 v36, " EA ", v33\n"                                             \
         "v_bfe_i32 v37, " EA ", 18, 14\n"                                              \
@@ -1256,10 +1257,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         "v_bfe_u32 v39, " EA ", 16, 2\n"                                               \
         SHIFT                                                                          \
         "v_bfrev_b32 v33, v28\n"                                                       \
-        "v_add_u32 v41, v41, " EA "\n"                                                 \
+        SUM                                                                            \
         "v_mad_u32_u24 v34, v39, %[nstr], v34\n"
-#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT)
-#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v25", "v24", K, SHIFT)
+// (the first look-up of a block starts the block's sum of 31 - T, the others add to it)
+#define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT, "v_mov_b32 v41, v24\n")
+#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT, "v_add_u32 v41, v41, v24\n")
+#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v25", "v24", K, SHIFT, "v_add_u32 v41, v41, v25\n")
 // BODY = all look-ups of a block but the last, which is written out below: it skips the window
 // shift.  Blocks have an even number of look-ups, so the entry ends up in v24 again.
 #define ANSZP_RUN_BLOCKS(STEPS, BODY)                                                                                 \
@@ -1278,8 +1281,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             spins = 0;                                                                                                \
             uint32_t logged_v = logged;                                                                               \
             asm volatile(                                                                                             \
-                "v_mov_b32 v24, %[e]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v34, %[ne]\n v_mov_b32 v47, %[x4]\n"          \
-                "v_mov_b32 v43, 0\n v_mov_b32 v46, " #STEPS "\n"                                                      \
+                "v_mov_b32 v24, %[e]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v34, %[ne]\n v_mov_b32 v36, %[x4]\n"          \
+                "v_mov_b32 v43, 0\n v_mov_b32 v46, " #STEPS "\n v_mov_b32 v40, %[hdr0]\n"                            \
                 "v_readfirstlane_b32 s44, %[logged]\n"                                                                        \
                 "s_mov_b64 s[40:41], exec\n"                                                                          \
                 "v_cmp_gt_u32 vcc, %[lim], v34\n"                                                                     \
@@ -1288,16 +1291,11 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 "v_min_u32 v38, %[lastw], v38\n"                                                                      \
                 "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
                 "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
+                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* -, blocks expanded, elements stored (two) */        \
                 "s_and_b64 exec, s[40:41], vcc\n"      /* lanes that can run a whole block (some can) */              \
                 "1:\n"                                                                                                \
-                "s_and_b32 s46, s44, %[slotmask]\n"                                                                   \
-                "s_lshl_b32 s47, s46, %[slotshift]\n"                                                                 \
-                "v_add_u32 v42, s47, %[lanelog]\n"     /* this lane's column in the block's log slot */               \
-                "s_lshl_b32 s46, s46, 4\n"                                                                            \
-                "v_mov_b32 v40, s46\n"                 /* offset of the block's header */                             \
-                "v_mov_b32 v41, 0\n"                                                                                  \
-                "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* -, blocks expanded, elements stored (two) */        \
+                "v_lshl_add_u32 v42, v40, 7, %[lanelog]\n" /* this lane's column in the block's log slot */           \
+                "s_waitcnt lgkmcnt(1)\n"              /* the window words; the hand-over words were asked for last */ \
                 "v_alignbit_b32 v28, v29, v28, v32\n"                                                                 \
                 "v_alignbit_b32 v29, v30, v29, v32\n"                                                                 \
                 "v_alignbit_b32 v30, v31, v30, v32\n"                                                                 \
@@ -1313,31 +1311,30 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 "v_bfe_u32 v39, v25, 16, 2\n"                                                                         \
                 "v_add_u32 v41, v41, v25\n"                                                                           \
                 "v_mad_u32_u24 v34, v39, %[nstr], v34\n"                                                               \
-                "v_mov_b32 v47, v36\n"                                                                                \
                 "v_and_b32 v41, 0xff, v41\n"                                                                          \
                 "v_add_u32 v34, %[snstr], v34\n"         /* one symbol per look-up on top of the runs */                \
                 "v_sub_u32 v41, 31*" #STEPS ", v41\n"                                                                 \
                 "v_mov_b32 v44, exec_lo\n"                                                                            \
                 "v_mov_b32 v45, exec_hi\n"                                                                            \
                 "v_add_u32 v32, v32, v41\n"            /* bit position after the block */                             \
-                "ds_write_b64 v40, v[44:45] offset:%[hdr]\n"                                                          \
-                "ds_write_b32 v40, v46 offset:%[hdr]+8\n"                                                             \
+                "ds_write_b96 v40, v[44:46] offset:%[hdr]\n" /* header: lanes taking part, look-ups */              \
                 "s_add_u32 s44, s44, 1\n"                                                                             \
                 "v_mov_b32 v44, s44\n"                                                                                \
-                "v_readfirstlane_b32 s46, v49\n"       /* blocks expanded when this block began */                    \
-                "v_readfirstlane_b32 s47, v50\n"       /* elements stored when this block began: every slab */        \
-                "v_readfirstlane_b32 s45, v51\n"       /* below the next one of either storing wavefront */           \
+                "v_readfirstlane_b32 s46, v49\n"       /* blocks expanded when the previous block ended */            \
                 "ds_write_b32 v43, v44 offset:%[ctlw0]\n" /* publish the block */                                     \
                 "s_mov_b64 exec, s[40:41]\n"           /* every lane reloads its words */                             \
+                "v_add_u32 v40, 16, v40\n"            /* offset of the next block's header */                        \
+                "v_and_b32 v40, %[hdrmask], v40\n"                                                                    \
                 "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
                 "v_and_b32 v38, 0x1ffffffc, v38\n"                                                                    \
                 "v_min_u32 v38, %[lastw], v38\n"                                                                      \
                 "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
                 "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
-                "s_min_u32 s47, s47, s45\n"                                                                           \
-                "s_add_u32 s47, s47, %[room]\n"                                                                       \
-                "s_min_u32 s47, s47, %[nearend]\n"                                                                    \
-                "v_cmp_gt_u32 vcc, s47, v34\n"         /* lanes that can run another block */                         \
+                "v_min_u32 v50, v50, v51\n"           /* elements stored when the previous block ended: every */     \
+                "v_add_u32 v50, %[room], v50\n"       /* slab below the next one of either storing wavefront */      \
+                "v_min_u32 v50, %[nearend], v50\n"                                                                    \
+                "v_cmp_gt_u32 vcc, v50, v34\n"        /* lanes that can run another block */                         \
+                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* the same words, for the end of the next block */    \
                 "s_sub_u32 s46, s44, s46\n"                                                                           \
                 "s_cmp_ge_u32 s46, %[slots]\n"         /* the next log slot may still be in use */                    \
                 "s_cbranch_scc1 2f\n"                                                                                 \
@@ -1346,17 +1343,17 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 "2:\n"                                                                                                \
                 "s_mov_b64 exec, s[40:41]\n"                                                                          \
                 "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "v_mov_b32 %[e], v24\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v34\n v_mov_b32 %[x4], v47\n"          \
+                "v_mov_b32 %[e], v24\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v34\n v_mov_b32 %[x4], v36\n"          \
                 "v_mov_b32 %[logged], s44\n"                                                                          \
                 : [e] "+v"(e), [ab] "+v"(abit), [ne] "+v"(ne), [x4] "+v"(X4), [logged] "+v"(logged_v)                 \
                 : [lim] "s"(uniform(limit)), [nearend] "s"(uniform(near_end)), [room] "s"(uniform(kRingElems - reach)),\
                   [nstr] "s"(uniform(N)), [snstr] "s"(uniform((STEPS) * N)), [lastw] "s"(uniform(last_word4)),        \
-                  [lanelog] "v"(lane_log),                                                                            \
+                  [lanelog] "v"(lane_log), [hdr0] "s"(uniform((logged & (kLogSlots - 1u)) << 4)),                     \
                   [table] "n"(kTableOff), [hdr] "n"(kHdrOff), [ctlw0] "n"(kCtlOff),                                \
-                  [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [slotshift] "n"(11)                         \
-                : "memory", "vcc", "scc", "s40", "s41", "s44", "s45", "s46", "s47", "v24", "v25", "v28", "v29", "v30",\
+                  [slots] "n"(kLogSlots), [hdrmask] "n"(kLogSlots * 16u - 1u)                                         \
+                : "memory", "vcc", "scc", "s40", "s41", "s44", "s46", "v24", "v25", "v28", "v29", "v30",\
                   "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44",   \
-                  "v45", "v46", "v47", "v48", "v49", "v50", "v51");                                                   \
+                  "v45", "v46", "v48", "v49", "v50", "v51");                                                   \
             logged = uniform(logged_v);                                                                               \
         }
         uint32_t spins = 0;
@@ -1368,12 +1365,13 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             return v;
         };
         static_assert(ANSZP_MAX_TABLE_LOG <= 12, "the reach of a look-up assumed by the window shifts");
-        ANSZP_RUN_BLOCKS(8, ANSZP_AB("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
+        ANSZP_RUN_BLOCKS(8, ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
                             ANSZP_BA("3", ANSZP_SHIFT_W1) ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0)
                             ANSZP_AB("6", ANSZP_SHIFT_W0))
-        ANSZP_RUN_BLOCKS(4, ANSZP_AB("0", ANSZP_SHIFT_W1) ANSZP_BA("1", ANSZP_SHIFT_W0) ANSZP_AB("2", ANSZP_SHIFT_W0))
-        ANSZP_RUN_BLOCKS(2, ANSZP_AB("0", ANSZP_SHIFT_W0))
+        ANSZP_RUN_BLOCKS(4, ANSZP_FIRST("0", ANSZP_SHIFT_W1) ANSZP_BA("1", ANSZP_SHIFT_W0) ANSZP_AB("2", ANSZP_SHIFT_W0))
+        ANSZP_RUN_BLOCKS(2, ANSZP_FIRST("0", ANSZP_SHIFT_W0))
 #undef ANSZP_RUN_BLOCKS
+#undef ANSZP_FIRST
 #undef ANSZP_AB
 #undef ANSZP_BA
 #undef ANSZP_LOOKUP
