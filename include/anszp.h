@@ -216,6 +216,47 @@ int anszp_dequant_zp(const uint8_t* symbols_dev, uint64_t n, const anszp_layer_t
                      const float* scales_dev, uint64_t n_scales, void* out_dev, int out_dtype,
                      void* hip_stream);
 
+/* Arguments of anszp_conv_fused (the struct itself is read on the host).  The container fields
+ * mean what they mean in anszp_decode_args_t; `chunks` points at the FIRST chunk of the layer to
+ * convolve with, `n_chunks` counts the chunks from there on. */
+typedef struct {
+    const uint32_t*      tables;         /* [device] as for anszp_decode                          */
+    uint32_t             n_tables;
+    uint32_t             table_log;
+    uint32_t             n_streams;
+    uint32_t             layer_id;       /* the layer's table and anszp_layer_t                   */
+    const anszp_chunk_t* chunks;         /* [device] the layer's chunks, in order of output channel */
+    uint64_t             n_chunks;       /* at least cout / rows_per_chunk                        */
+    const uint32_t*      stream_hdr;     /* [device]                                              */
+    uint64_t             n_stream_hdr;
+    const uint32_t*      payload;        /* [device]                                              */
+    uint64_t             payload_words;
+    const anszp_layer_t* layers;         /* [device] n_tables entries; channel_len is 0 or kh*kw*cin
+                                            (one scale per output channel)                        */
+    const float*         scales;         /* [device] may be NULL if unused                        */
+    uint64_t             n_scales;
+    uint32_t             rows_per_chunk; /* output channels per chunk: 1, 2, 4, 8 or 16; every chunk
+                                            holds rows_per_chunk * kh*kw*cin symbols              */
+    uint32_t             batch, in_h, in_w, cin, cout, kh, kw, stride, pad;
+    const uint16_t*      x;              /* [device] bf16 activations [batch][in_h][in_w][cin], 16-byte aligned */
+    float*               y;              /* [device] [batch][out_h][out_w][cout], out = (in + 2 pad - k) / stride + 1,
+                                            16-byte aligned; every element is written              */
+    uint32_t*            status;         /* [device] 2 words, as for anszp_decode                 */
+} anszp_conv_args_t;
+
+/* Fused decode + convolution (the data are decoded on their way from memory to the compute
+ * units, Sec. II; weights w = scale * (q - z), Sec. II-B): y = conv2d(x, w) with zero padding,
+ * where the layer's symbols q, in the order [cout][kh][kw][cin], are decoded (Sec. II-A, one
+ * stream per lane as in Sec. III-B) into on-chip memory and multiplied there with the activations
+ * by bf16 matrix instructions with fp32 accumulation; the decoded weights are never written to
+ * device memory.  q - z is exact in bf16; the scale multiplies the fp32 sums.
+ * Limits: cout a multiple of 16; kh*kw*cin <= 4608; batch*out_h*out_w < 2^31.  Asynchronous on
+ * hip_stream; the buffers stay the caller's.  Errors: E_NULL, E_RANGE (a limit above, misaligned
+ * x or y, too few chunks), E_HIP; a chunk whose descriptor does not fit the layer, a stream that
+ * ends in the wrong state or length: ANSZP_ST_* bits in status, as for anszp_decode (the outputs
+ * of the affected output channels are then unspecified but finite sums of finite values). */
+int anszp_conv_fused(const anszp_conv_args_t* args, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

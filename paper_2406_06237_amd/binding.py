@@ -39,6 +39,19 @@ class DecodeArgs(C.Structure):
                 ("out", C.c_void_p), ("out_elems", C.c_uint64), ("status", C.c_void_p)]
 
 
+class ConvArgs(C.Structure):
+    _fields_ = [("tables", C.c_void_p), ("n_tables", C.c_uint32), ("table_log", C.c_uint32),
+                ("n_streams", C.c_uint32), ("layer_id", C.c_uint32),
+                ("chunks", C.c_void_p), ("n_chunks", C.c_uint64),
+                ("stream_hdr", C.c_void_p), ("n_stream_hdr", C.c_uint64),
+                ("payload", C.c_void_p), ("payload_words", C.c_uint64),
+                ("layers", C.c_void_p), ("scales", C.c_void_p), ("n_scales", C.c_uint64),
+                ("rows_per_chunk", C.c_uint32), ("batch", C.c_uint32), ("in_h", C.c_uint32), ("in_w", C.c_uint32),
+                ("cin", C.c_uint32), ("cout", C.c_uint32), ("kh", C.c_uint32), ("kw", C.c_uint32),
+                ("stride", C.c_uint32), ("pad", C.c_uint32),
+                ("x", C.c_void_p), ("y", C.c_void_p), ("status", C.c_void_p)]
+
+
 class AnszpError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -48,7 +61,7 @@ class AnszpError(RuntimeError):
 _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
-           "anszp_dequant_zp"]
+           "anszp_dequant_zp", "anszp_conv_fused"]
 
 
 def lib():
@@ -78,6 +91,7 @@ def lib():
         L.anszp_decode_variant.argtypes = [C.POINTER(DecodeArgs), C.c_int, C.c_void_p]
         L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
                                        C.c_void_p, C.c_int, C.c_void_p]
+        L.anszp_conv_fused.argtypes = [C.POINTER(ConvArgs), C.c_void_p]
         _lib = L
     return _lib
 
@@ -349,3 +363,61 @@ def bits_of(t) -> np.ndarray:
     if t.dtype == torch.float32:
         return t.view(torch.int32).cpu().numpy().view(np.uint32)
     return t.cpu().numpy()
+
+
+# --------------------------------------------------------------------------- fused decode + convolution
+CONV_ROWS = 16          # output channels per workgroup of anszp_conv_fused
+CONV_MAX_K = 4608
+
+
+def conv_rows_per_chunk(k: int) -> int:
+    """Output channels per chunk for a layer with reduction length k = kh*kw*cin: the largest power of
+    two (at most 16) that keeps a chunk at 4096 symbols or fewer, so that the four wavefronts of a
+    workgroup have a chunk each to decode where the rows are long."""
+    r = 1
+    while r < CONV_ROWS and 2 * r * k <= 4096:
+        r *= 2
+    return r
+
+
+def pack_conv_layers(layer_symbols: Sequence[np.ndarray], shapes: Sequence[tuple], table_log: int, n_streams: int,
+                     zero_points: Sequence[int], scales: Sequence[float], bitwidths: Optional[Sequence[int]] = None):
+    """Compress conv layers for anszp_conv_fused.  layer_symbols[i] holds the symbols of layer i in the order
+    [cout][kh][kw][cin]; shapes[i] = (cout, cin, kh, kw).  Returns the container, each layer's first chunk
+    and its output channels per chunk."""
+    rows = [conv_rows_per_chunk(cin * kh * kw) for (_, cin, kh, kw) in shapes]
+    sizes = [r * cin * kh * kw for r, (_, cin, kh, kw) in zip(rows, shapes)]
+    for sym, (cout, cin, kh, kw) in zip(layer_symbols, shapes):
+        if len(sym) != cout * cin * kh * kw or cout % CONV_ROWS or cin * kh * kw > CONV_MAX_K:
+            raise ValueError(f"layer shape {(cout, cin, kh, kw)} does not fit anszp_conv_fused")
+    h = pack_layers(layer_symbols, table_log, n_streams, max(sizes), zero_points, scales, bitwidths, chunk_sizes=sizes)
+    first = np.concatenate([[0], np.cumsum([cout // r for r, (cout, _, _, _) in zip(rows, shapes)])])[:-1]
+    return h, [int(f) for f in first], rows
+
+
+def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
+               pad: int, y=None):
+    """anszp_conv_fused on torch's current stream: x is a bf16 NHWC tensor, shape = (cout, cin, kh, kw);
+    returns y, fp32 NHWC."""
+    torch = _torch()
+    h = d.host
+    cout, cin, kh, kw = shape
+    B, H, W, cin_x = x.shape
+    if x.dtype != torch.bfloat16 or not x.is_contiguous() or cin_x != cin:
+        raise ValueError("x must be a contiguous bf16 [batch][h][w][cin] tensor")
+    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    if y is None:
+        y = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=x.device)
+    a = ConvArgs()
+    a.tables = d.tables.data_ptr(); a.n_tables = len(h.freqs); a.table_log = h.table_log
+    a.n_streams = h.n_streams; a.layer_id = layer
+    a.chunks = d.chunks.data_ptr() + first_chunk * CHUNK_DTYPE.itemsize; a.n_chunks = len(h.chunks) - first_chunk
+    a.stream_hdr = d.stream_hdr.data_ptr(); a.n_stream_hdr = len(h.stream_hdr)
+    a.payload = d.payload.data_ptr(); a.payload_words = len(h.payload)
+    a.layers = d.layers.data_ptr(); a.scales = d.scales.data_ptr(); a.n_scales = len(h.scales)
+    a.rows_per_chunk = rows_per_chunk
+    a.batch, a.in_h, a.in_w, a.cin, a.cout, a.kh, a.kw, a.stride, a.pad = B, H, W, cin, cout, kh, kw, stride, pad
+    a.x = x.data_ptr(); a.y = y.data_ptr(); a.status = d.status.data_ptr()
+    with torch.cuda.device(x.device):
+        _check(lib().anszp_conv_fused(C.byref(a), _stream_ptr(torch, x.device)), "anszp_conv_fused")
+    return y

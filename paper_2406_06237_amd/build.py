@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libanszp.so")
-SOURCES = [os.path.join(CSRC, "anszp_host.cpp"), os.path.join(CSRC, "anszp_device.hip")]
+SOURCES = [os.path.join(CSRC, "anszp_host.cpp"), os.path.join(CSRC, "anszp_device.hip"),
+           os.path.join(CSRC, "anszp_conv.hip")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include")]

@@ -1,0 +1,339 @@
+// Fused decode + convolution for gfx950: a conv layer's entropy-coded weights are decoded into LDS
+// and consumed there by bf16 MFMA instructions; the decoded weights never reach global memory
+// (Sec. II: the weights are to be decoded on their way from memory to the compute units).
+//
+// The convolution is an implicit GEMM  Y[n, o] = sum_k A[o, k] * B[k, n]  with
+//   o = output channel, n = (image, output row, output column), k = (kernel row, kernel column,
+//   input channel), input channel innermost,
+//   A[o, k] = q - z, the decoded symbol minus the layer's zero-point (Sec. II-B): an integer of at
+//   most 8 bits and therefore exact in bf16; the scale multiplies the fp32 sums at the end,
+//   B[k, n] = the bf16 activation under kernel tap (r, s) of output pixel n, zero outside the image.
+// Activations and outputs are NHWC, so the 8 consecutive k one lane feeds into an MFMA are 16
+// contiguous bytes of the activation tensor.
+//
+// One workgroup owns 16 output channels (the M of v_mfma_f32_16x16x32_bf16) and a range of output
+// pixels.  Phase 1: its four wavefronts decode the chunks that hold those 16 weight rows, one
+// symbol per look-up with one lane per stream (Sec. II-A, III-B), into a [16][K] byte panel in LDS.
+// Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column tiles): per 32 k it
+// reads 8 panel bytes per lane, converts them once, loads four 16-byte activation vectors and
+// issues four MFMAs.  fp32 accumulators, one 16-byte store per lane and column tile.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "anszp.h"
+
+namespace {
+
+constexpr uint32_t kWave = 64;
+constexpr uint32_t kThreads = 256;
+constexpr uint32_t kWaves = kThreads / kWave;
+constexpr uint32_t kRows = 16;              // output channels per workgroup
+constexpr uint32_t kColsPerWave = 64;       // output pixels a wavefront works on at a time: 4 MFMA column tiles
+constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+typedef __attribute__((ext_vector_type(4))) uint32_t words4;
+typedef __attribute__((ext_vector_type(2))) uint32_t words2;
+
+struct ConvParams {
+    const uint32_t* tables;
+    const anszp_chunk_t* chunks;        // the layer's first chunk
+    const uint32_t* stream_hdr;
+    const uint32_t* payload;
+    const anszp_layer_t* layers;
+    const float* scales;
+    const uint16_t* x;
+    float* y;
+    uint32_t* status;
+    uint64_t n_stream_hdr, payload_words, n_scales;
+    uint32_t layer_id, table_log, n_streams, rows_per_chunk, chunks_per_panel;
+    uint32_t in_h, in_w, cin, cout, kh, kw, stride, pad, out_h, out_w;
+    uint32_t K, row_stride, n_pixels, n_mtiles, blocks_per_split;
+};
+
+__device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
+    atomicOr(&status[0], bits);
+    atomicAdd(&status[1], 1u);
+}
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+#pragma unroll
+    for (int d = 1; d < int(kWave); d <<= 1) v |= __shfl_xor(v, d, kWave);
+    return v;
+}
+
+// Exclusive prefix sum over the wavefront, and the total.
+__device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* total) {
+    uint32_t s = v;
+#pragma unroll
+    for (int d = 1; d < int(kWave); d <<= 1) {
+        const uint32_t t = __shfl_up(s, d, kWave);
+        if ((threadIdx.x & (kWave - 1)) >= uint32_t(d)) s += t;
+    }
+    *total = __shfl(s, kWave - 1, kWave);
+    return s - v;
+}
+
+// One chunk, one look-up per symbol (Sec. II-A; Sec. III-B: one lane per stream), symbols into the
+// LDS panel: symbol i of the chunk belongs to panel row i / K, column i % K.  Returns error bits.
+__device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk_t& c, const uint32_t* table,
+                                          uint8_t* rows, uint32_t lane) {
+    const uint32_t N = p.n_streams;
+    const uint32_t L = 1u << p.table_log;
+    const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
+    uint32_t X = hdr & (L - 1u);
+    const uint32_t n_words = hdr >> 16;
+    uint32_t total_words;
+    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
+    uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+
+    const uint32_t* words = p.payload + c.payload_offset;
+    const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
+    auto word_at = [&](uint32_t i) { return i < word_limit ? words[i] : 0u; };
+    uint32_t next_word = first_word;
+    uint64_t buf = 0;
+    uint32_t have = 0;
+    uint32_t ahead = word_at(first_word);             // the word after those in buf, requested one refill early
+    const uint32_t steps = (c.n_symbols + N - 1u) / N;
+    uint32_t row = lane / p.K, col = lane % p.K;      // of this lane's next symbol
+    const uint32_t row_step = N / p.K, col_step = N % p.K;
+    for (uint32_t t = 0; t < steps; ++t) {
+        if (t < len) {
+            const uint32_t e = table[X];
+            const uint32_t nb = (e >> 16) & 0xFFu;
+            if (have < nb) {
+                buf |= uint64_t(ahead) << have;
+                have += 32;
+                ++next_word;
+                ahead = word_at(next_word);
+            }
+            const uint32_t low = static_cast<uint32_t>(buf) & ((1u << nb) - 1u);
+            const uint32_t bits = nb ? __brev(low) >> (32u - nb) : 0u;      // first bit read is the top bit
+            buf >>= nb;
+            have -= nb;
+            X = ((e & 0xFFFFu) + bits) & (L - 1u);
+            rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
+            row += row_step;
+            col += col_step;
+            if (col >= p.K) { col -= p.K; ++row; }
+        }
+    }
+    if (lane < N) {
+        if (X != 0) err |= ANSZP_ST_BAD_STATE;
+        if (next_word - first_word != n_words) err |= ANSZP_ST_BAD_LENGTH;
+    }
+    return wave_or(err);
+}
+
+// Eight symbols -> eight bf16 values q - z.  |q - z| <= 255 has at most 8 significant bits, so the
+// upper half of its binary32 form is the exact bf16 value.
+__device__ __forceinline__ bf16x8 weights_of(words2 q, float z) {
+    auto byte = [](uint32_t w, uint32_t i) { return static_cast<float>((w >> (8u * i)) & 0xFFu); };   // v_cvt_f32_ubyte<i>
+    const float f0 = byte(q.x, 0) - z, f1 = byte(q.x, 1) - z, f2 = byte(q.x, 2) - z, f3 = byte(q.x, 3) - z;
+    const float f4 = byte(q.y, 0) - z, f5 = byte(q.y, 1) - z, f6 = byte(q.y, 2) - z, f7 = byte(q.y, 3) - z;
+    auto pack = [](float lo, float hi) {              // upper halves of two binary32 values, lo in bits 0..15
+        return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+    };
+    words4 w = {pack(f0, f1), pack(f2, f3), pack(f4, f5), pack(f6, f7)};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// GENERIC: any number of input channels (every activation is addressed on its own); otherwise the
+// input channels are a multiple of 8 and a lane's 8 consecutive k lie under one kernel tap.
+template <bool GENERIC>
+__global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint32_t* table = reinterpret_cast<uint32_t*>(lds);
+    uint8_t* panel = lds + (4u << p.table_log);
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t mtile = blockIdx.x % p.n_mtiles, split = blockIdx.x / p.n_mtiles;
+    const uint32_t L = 1u << p.table_log;
+
+    // ---- phase 1: the layer's triples (Sec. II-A) into LDS, then this workgroup's 16 weight rows
+    const uint32_t* src = p.tables + (uint64_t(p.layer_id) << (p.table_log + 2)) + 2u * L;
+    for (uint32_t i = tid; i < L; i += kThreads) table[i] = src[i];
+    const anszp_layer_t lay = p.layers[p.layer_id];
+    __syncthreads();
+    uint32_t err = (lay.channel_len != 0 && lay.channel_len != p.K) ? ANSZP_ST_BAD_DESC : 0u;   // scales per output channel only
+    for (uint32_t j = wave; j < p.chunks_per_panel; j += kWaves) {
+        const anszp_chunk_t c = p.chunks[uint64_t(mtile) * p.chunks_per_panel + j];
+        const bool ok = c.layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K &&
+                        c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
+                        uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
+        if (!ok) { err |= ANSZP_ST_BAD_DESC; continue; }
+        err |= decode_chunk_to_panel(p, c, table, panel + j * p.rows_per_chunk * p.row_stride, lane);
+    }
+    if (err && lane == 0) report(p.status, err);
+    __syncthreads();
+
+    // ---- phase 2: the panel times the activations
+    const uint32_t col = lane & 15u, kg = lane >> 4;              // MFMA operand layout: row or column, group of 8 k
+    const uint8_t* a_row = panel + col * p.row_stride + 8u * kg;  // A: lane holds row lane % 16, k = 8 * (lane / 16) + 0..7
+    const float zf = static_cast<float>(lay.zero_point);
+    const bool per_channel = lay.channel_len != 0;
+    const uint32_t n_blocks = (p.n_pixels + kColsPerWave - 1u) / kColsPerWave;
+    const uint32_t first_block = split * p.blocks_per_split;
+    const uint32_t end_block = min(first_block + p.blocks_per_split, n_blocks);
+    const uint32_t Kp = (p.K + 31u) & ~31u;
+
+    for (uint32_t blk = first_block + wave; blk < end_block; blk += kWaves) {
+        // B: lane holds column lane % 16 of each of the block's four column tiles
+        uint32_t pix[4];
+        int32_t h0[4], w0[4];
+        uint32_t img[4];
+        bool valid[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            pix[q] = blk * kColsPerWave + q * 16u + col;
+            valid[q] = pix[q] < p.n_pixels;
+            const uint32_t n = valid[q] ? pix[q] : 0u;
+            const uint32_t wo = n % p.out_w, t = n / p.out_w;
+            const uint32_t ho = t % p.out_h, b = t / p.out_h;
+            h0[q] = int32_t(ho * p.stride) - int32_t(p.pad);
+            w0[q] = int32_t(wo * p.stride) - int32_t(p.pad);
+            img[q] = b * p.in_h * p.in_w;
+        }
+        floatx4 acc[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) acc[q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        if constexpr (!GENERIC) {
+            for (uint32_t r = 0; r < p.kh; ++r) {
+                for (uint32_t s = 0; s < p.kw; ++s) {
+                    const uint16_t* src_q[4];
+                    bool inside[4];
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) {
+                        const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(s);
+                        inside[q] = valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                        const uint32_t at = inside[q] ? img[q] + uint32_t(h) * p.in_w + uint32_t(w) : 0u;
+                        src_q[q] = p.x + uint64_t(at) * p.cin + 8u * kg;
+                    }
+                    const uint8_t* a_tap = a_row + (r * p.kw + s) * p.cin;
+                    for (uint32_t c0 = 0; c0 < p.cin; c0 += 32u) {
+                        const bool live = c0 + 8u * kg < p.cin;          // the last 32 k of a tap may be partly beyond it
+                        words4 bq[4];
+#pragma unroll
+                        for (uint32_t q = 0; q < 4; ++q) {
+                            bq[q] = words4{0u, 0u, 0u, 0u};
+                            if (inside[q] && live) bq[q] = *reinterpret_cast<const words4*>(src_q[q] + c0);
+                        }
+                        const words2 aq = *reinterpret_cast<const words2*>(a_tap + c0);
+                        const bf16x8 a = weights_of(aq, zf);
+#pragma unroll
+                        for (uint32_t q = 0; q < 4; ++q)
+                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bq[q]), acc[q], 0, 0, 0);
+                    }
+                }
+            }
+        } else {
+            for (uint32_t k0 = 0; k0 < Kp; k0 += 32u) {
+                const uint32_t kbase = k0 + 8u * kg;
+                uint16_t bv[4][8];
+#pragma unroll
+                for (uint32_t j = 0; j < 8; ++j) {
+                    const uint32_t k = kbase + j;
+                    const uint32_t tap = k / p.cin, c = k % p.cin;
+                    const uint32_t r = tap / p.kw, s = tap % p.kw;
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) {
+                        const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(s);
+                        const bool inside = valid[q] && k < p.K && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                        bv[q][j] = inside ? p.x[uint64_t(img[q] + uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c] : uint16_t(0);
+                    }
+                }
+                const words2 aq = *reinterpret_cast<const words2*>(a_row + k0);
+                const bf16x8 a = weights_of(aq, zf);
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    const words4 b = {uint32_t(bv[q][0]) | uint32_t(bv[q][1]) << 16, uint32_t(bv[q][2]) | uint32_t(bv[q][3]) << 16,
+                                      uint32_t(bv[q][4]) | uint32_t(bv[q][5]) << 16, uint32_t(bv[q][6]) | uint32_t(bv[q][7]) << 16};
+                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b), acc[q], 0, 0, 0);
+                }
+            }
+        }
+
+        // D: lane holds column lane % 16, rows 4 * (lane / 16) + 0..3: four consecutive output channels
+        const uint32_t o = mtile * kRows + 4u * kg;
+        float sc[4];
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) {
+            sc[i] = lay.scale;
+            if (per_channel) {
+                const uint64_t ch = lay.scales_offset + o + i;
+                sc[i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (valid[q]) {
+                const floatx4 out = {acc[q][0] * sc[0], acc[q][1] * sc[1], acc[q][2] * sc[2], acc[q][3] * sc[3]};
+                *reinterpret_cast<floatx4*>(p.y + uint64_t(pix[q]) * p.cout + o) = out;
+            }
+        }
+    }
+}
+
+constexpr uint32_t kMaxK = 4608;           // reduction length whose 16-row panel (72 KiB) fits LDS beside the table
+
+}  // namespace
+
+extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
+    if (!a || !a->tables || !a->chunks || !a->stream_hdr || !a->layers || !a->x || !a->y || !a->status) return ANSZP_E_NULL;
+    if (a->payload_words && !a->payload) return ANSZP_E_NULL;
+    if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 || a->n_streams > 64) return ANSZP_E_RANGE;
+    if (a->layer_id >= a->n_tables) return ANSZP_E_RANGE;
+    if (!a->batch || !a->in_h || !a->in_w || !a->cin || !a->cout || !a->kh || !a->kw || !a->stride) return ANSZP_E_RANGE;
+    if (a->in_h > 32768u || a->in_w > 32768u || a->cin > 65536u || a->kh > 64u || a->kw > 64u || a->pad > 64u) return ANSZP_E_RANGE;
+    if (a->cout % kRows) return ANSZP_E_RANGE;
+    const uint64_t K = uint64_t(a->cin) * a->kh * a->kw;
+    if (K > kMaxK) return ANSZP_E_RANGE;
+    if (a->in_h + 2u * a->pad < a->kh || a->in_w + 2u * a->pad < a->kw) return ANSZP_E_RANGE;
+    const uint32_t R = a->rows_per_chunk;
+    if (R == 0 || R > kRows || (kRows % R)) return ANSZP_E_RANGE;
+    const uint32_t out_h = (a->in_h + 2u * a->pad - a->kh) / a->stride + 1u;
+    const uint32_t out_w = (a->in_w + 2u * a->pad - a->kw) / a->stride + 1u;
+    const uint64_t n_pixels = uint64_t(a->batch) * out_h * out_w;
+    if (n_pixels >= (1ull << 31) || uint64_t(a->batch) * a->in_h * a->in_w >= (1ull << 31)) return ANSZP_E_RANGE;
+    const uint32_t n_mtiles = a->cout / kRows;
+    if (a->n_chunks < uint64_t(n_mtiles) * (kRows / R)) return ANSZP_E_RANGE;
+    if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y)) & 15u) return ANSZP_E_RANGE;
+
+    ConvParams p{};
+    p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
+    p.layers = a->layers; p.scales = a->scales; p.x = a->x; p.y = a->y; p.status = a->status;
+    p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words; p.n_scales = a->scales ? a->n_scales : 0;
+    p.layer_id = a->layer_id; p.table_log = a->table_log; p.n_streams = a->n_streams;
+    p.rows_per_chunk = R; p.chunks_per_panel = kRows / R;
+    p.in_h = a->in_h; p.in_w = a->in_w; p.cin = a->cin; p.cout = a->cout; p.kh = a->kh; p.kw = a->kw;
+    p.stride = a->stride; p.pad = a->pad; p.out_h = out_h; p.out_w = out_w;
+    p.K = uint32_t(K);
+    p.row_stride = ((p.K + 31u) & ~31u) + kRowPad;
+    p.n_pixels = uint32_t(n_pixels);
+    p.n_mtiles = n_mtiles;
+
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
+    // Every workgroup decodes its panel once, so few, long-lived workgroups: about four per CU.
+    const uint32_t n_blocks = uint32_t((n_pixels + kColsPerWave - 1u) / kColsPerWave);
+    uint32_t splits = (4u * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
+    const uint32_t max_splits = (n_blocks + kWaves - 1u) / kWaves;          // at least one block per wavefront
+    if (splits > max_splits) splits = max_splits;
+    if (splits == 0) splits = 1;
+    p.blocks_per_split = (n_blocks + splits - 1u) / splits;
+    splits = (n_blocks + p.blocks_per_split - 1u) / p.blocks_per_split;
+
+    // 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row
+    const uint32_t lds_bytes = (4u << a->table_log) + kRows * p.row_stride + 64u;
+    const bool generic = (a->cin % 8u) != 0;
+    auto kernel = generic ? conv_fused_kernel<true> : conv_fused_kernel<false>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            int(lds_bytes)) != hipSuccess) return ANSZP_E_HIP;
+    hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
+    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+}

@@ -169,6 +169,34 @@ def resnet50_conv_shapes():
     return shapes
 
 
+def resnet50_conv_geometry():
+    """(name, (cout, cin, kh, kw), stride, pad, input height = width) of every conv layer of a ResNet-50 fed
+    with 224 x 224 images (stride on the 3x3 convolution of a stage's first block, as in torchvision)."""
+    out = [("conv1", (64, 3, 7, 7), 2, 3, 224)]
+    size, cin = 56, 64                                   # after the 3x3 stride-2 max pooling
+    for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+        cout = width * 4
+        for block in range(blocks):
+            c_in_block = cin if block == 0 else cout
+            stride = 2 if (block == 0 and stage > 1) else 1
+            out.append((f"layer{stage}.{block}.conv1", (width, c_in_block, 1, 1), 1, 0, size))
+            out.append((f"layer{stage}.{block}.conv2", (width, width, 3, 3), stride, 1, size))
+            out.append((f"layer{stage}.{block}.conv3", (cout, width, 1, 1), 1, 0, size // stride))
+            if block == 0:
+                out.append((f"layer{stage}.{block}.downsample", (cout, c_in_block, 1, 1), stride, 0, size))
+            size //= stride
+        cin = cout
+    return out
+
+
+def bf16_activations(n: int, seed: int):
+    """n standard normal values rounded to bfloat16 (nearest even): their 16-bit codes and their values."""
+    v = np.random.default_rng(seed).standard_normal(n).astype(np.float32)
+    bits = v.view(np.uint32)
+    codes = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16).astype(np.uint16)
+    return codes, (codes.astype(np.uint32) << 16).view(np.float32)
+
+
 def _seed(config: int, layer: int) -> int:
     return (BASE_SEED + (config << 20) + layer) & _MASK64
 

@@ -1,0 +1,128 @@
+"""GPU parity of the fused decode + convolution entry point: anszp_conv_fused through the C ABI on
+containers the ORACLE's encoder produced, against the fp64 convolution oracle applied to the
+generated symbols and activations."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv_oracle as CO
+from paper_2406_06237_amd import binding as B
+from paper_2406_06237_amd import workloads as W
+
+from helpers import host_from_oracle, oracle_encode
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer(shape, bitwidth, p0, seed, scale=0.03125, channel_scales=None):
+    z = 1 << (bitwidth - 1)
+    cout, cin, kh, kw = shape
+    lay = W.Layer("conv", shape, bitwidth, z, scale, W.peaked_geometric_pmf(1 << bitwidth, z, p0), seed)
+    if channel_scales is not None:
+        lay.channel_len = cin * kh * kw
+        lay.channel_scales = channel_scales
+    return lay
+
+
+def _case(orc, shape, B_, H, Wd, stride, pad, bitwidth=4, p0=0.7, n_streams=64, table_log=12, seed=1, per_channel=False):
+    cout, cin, kh, kw = shape
+    K = cin * kh * kw
+    rows = B.conv_rows_per_chunk(K)
+    cs = None
+    if per_channel:
+        cs = (0.01 + 0.002 * np.arange(cout)).astype(np.float32)
+    lay = _layer(shape, bitwidth, p0, seed, channel_scales=cs)
+    w = W.Workload("conv_case", [lay], table_log, n_streams, rows * K, "bf16")
+    c = oracle_encode(orc, w)                                   # the oracle's encoder, the oracle's bytes
+    d = B.to_device(host_from_oracle(c, w))
+    codes, values = W.bf16_activations(B_ * H * Wd * cin, seed + 100)
+    x = torch.from_numpy(codes.view(np.int16).reshape(B_, H, Wd, cin)).to("cuda:0").view(torch.bfloat16)
+    y = B.conv_fused(d, 0, 0, rows, x, shape, stride, pad)
+    status = d.read_status()
+    got = y.cpu().numpy().astype(np.float64)
+
+    sym = lay.symbols().reshape(cout, kh, kw, cin)              # order [cout][kh][kw][cin]
+    q = sym.astype(np.int64) - lay.zero_point
+    x64 = values.astype(np.float64).reshape(B_, H, Wd, cin)
+    if per_channel:
+        wts = q.astype(np.float64) * cs.astype(np.float64)[:, None, None, None]
+    else:
+        wts = CO.dequantized_weights(sym, lay.zero_point, lay.scale, sym.shape)
+    want = CO.conv2d_nhwc(x64, wts, stride, pad)
+    return status, got, want, CO.conv2d_nhwc(np.abs(x64), np.abs(wts), stride, pad)
+
+
+def _check(status, got, want, magnitude):
+    assert status == (0, 0), status
+    assert got.shape == want.shape
+    # every product is exact in fp32 (bf16 x 8-bit integer); what remains is fp32 summation: a few units
+    # in the last place of the sum of magnitudes, and one rounding by the scale
+    bound = 2.0 ** -20 * magnitude + 1e-30
+    worst = np.max(np.abs(got - want) - bound)
+    assert worst <= 0, f"beyond the summation bound by {worst}"
+    # the stated bar of the fused variant: max error relative to the output's scale <= 1e-2
+    assert np.max(np.abs(got - want)) <= 1e-2 * np.max(np.abs(want))
+
+
+@pytest.mark.parametrize("shape,B_,H,Wd,stride,pad", [
+    ((32, 64, 1, 1), 2, 9, 7, 1, 0),          # pointwise
+    ((16, 32, 3, 3), 3, 10, 10, 1, 1),        # 300 output pixels: a ragged last block of 64
+    ((48, 64, 3, 3), 1, 13, 11, 2, 1),        # stride 2
+    ((64, 3, 7, 7), 2, 20, 20, 2, 3),         # first layer: 3 input channels, K = 147
+    ((16, 128, 1, 1), 2, 9, 9, 2, 0),         # strided pointwise (downsample)
+    ((16, 8, 3, 3), 1, 6, 5, 1, 1),           # 8 input channels: a tap is a quarter of an MFMA's k
+    ((32, 40, 3, 3), 1, 7, 7, 1, 1),          # 40 input channels: the last 32 k of a tap are partly beyond it
+    ((16, 512, 3, 3), 1, 7, 7, 1, 1),         # K = 4608: the largest panel
+    ((16, 5, 2, 2), 1, 5, 5, 1, 0),           # odd everything, no padding
+])
+def test_convolution_shapes(orc, shape, B_, H, Wd, stride, pad):
+    _check(*_case(orc, shape, B_, H, Wd, stride, pad))
+
+
+@pytest.mark.parametrize("bitwidth,p0,n_streams,table_log", [(1, 0.9, 64, 12), (8, 0.75, 64, 12), (3, 0.3, 32, 10), (5, 0.8, 7, 9)])
+def test_alphabets_streams_and_table_sizes(orc, bitwidth, p0, n_streams, table_log):
+    _check(*_case(orc, (32, 32, 3, 3), 2, 8, 8, 1, 1, bitwidth=bitwidth, p0=p0, n_streams=n_streams,
+                  table_log=table_log, seed=bitwidth))
+
+
+def test_scale_per_output_channel(orc):
+    _check(*_case(orc, (32, 16, 3, 3), 2, 6, 6, 1, 1, per_channel=True))
+
+
+def test_many_pixels_several_splits(orc):
+    # 2 * 40 * 40 = 3200 output pixels: 50 blocks of 64 spread over workgroups and wavefronts
+    _check(*_case(orc, (64, 32, 3, 3), 2, 40, 40, 1, 1, seed=9))
+
+
+def test_corrupt_stream_is_reported(orc):
+    shape, K = (16, 32, 3, 3), 288
+    rows = B.conv_rows_per_chunk(K)
+    lay = _layer(shape, 4, 0.7, 3)
+    w = W.Workload("conv_case", [lay], 12, 64, rows * K, "bf16")
+    c = oracle_encode(orc, w)
+    h = host_from_oracle(c, w)
+    h.payload[len(h.payload) // 2] ^= 0x00F0F000
+    d = B.to_device(h)
+    codes, _ = W.bf16_activations(1 * 6 * 6 * 32, 4)
+    x = torch.from_numpy(codes.view(np.int16).reshape(1, 6, 6, 32)).to("cuda:0").view(torch.bfloat16)
+    y = B.conv_fused(d, 0, 0, rows, x, shape, 1, 1)
+    bits, count = d.read_status()
+    assert bits & (B.ST_BAD_STATE | B.ST_BAD_LENGTH) and count >= 1
+    assert torch.isfinite(y).all()
+
+
+def test_rejected_arguments(orc):
+    lay = _layer((16, 32, 1, 1), 4, 0.7, 5)
+    w = W.Workload("conv_case", [lay], 12, 64, 16 * 32, "bf16")
+    d = B.to_device(host_from_oracle(oracle_encode(orc, w), w))
+    x = torch.zeros((1, 4, 4, 32), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(B.AnszpError):
+        B.conv_fused(d, 0, 0, 16, x, (24, 32, 1, 1), 1, 0)          # cout not a multiple of 16
+    with pytest.raises(B.AnszpError):
+        B.conv_fused(d, 0, 0, 3, x, (16, 32, 1, 1), 1, 0)           # rows per chunk must divide 16
+    with pytest.raises(B.AnszpError):
+        B.conv_fused(d, 0, 0, 16, x, (16, 32, 5, 5), 1, 0)          # kernel larger than the padded image
+    big = torch.zeros((1, 4, 4, 1024), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(B.AnszpError):
+        B.conv_fused(d, 0, 0, 1, big, (16, 1024, 3, 3), 1, 1)       # K = 9216 > 4608
+    assert d.read_status() == (0, 0)
