@@ -63,12 +63,141 @@ def cpu_baseline(workload, repeats: int = 3):
                       f"{best * 1e3:.1f} ms"}, wts
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
+
+
+def bench_fused_conv(args):
+    """Config 5: every conv layer of the ResNet-50-shaped set, weights decoded inside the convolution kernel
+    (anszp_conv_fused), batch 64 at 224 x 224 geometry, synthetic N(0,1) bf16 activations.  One step = the 53
+    launches, one per layer.  Prints one JSON line: TFLOP/s against the dense bf16 MFMA peak."""
+    import numpy as np
+    import torch
+    from paper_2406_06237_amd import binding as B
+    from paper_2406_06237_amd import workloads as W
+
+    dev = "cuda:0"
+    batch = args.batch
+    w = W.config3()
+    geo = W.resnet50_conv_geometry()
+    shapes = [g[1] for g in geo]
+    syms = w.symbols()                                     # per layer, read as [cout][kh][kw][cin]
+    L = w.layers
+    h, first, rows = B.pack_conv_layers(syms, shapes, w.table_log, w.n_streams, [l.zero_point for l in L],
+                                        [l.scale for l in L], [l.bitwidth for l in L])
+    d = B.to_device(h, dev)
+    n_x = max(batch * g[4] * g[4] * g[1][1] for g in geo)
+    codes, values = W.bf16_activations(n_x, 5)
+    xbuf = torch.from_numpy(codes.view(np.int16)).to(dev).view(torch.bfloat16)
+    out_hw = [(g[4] + 2 * g[3] - g[1][2]) // g[2] + 1 for g in geo]
+    ybuf = torch.empty(max(batch * o * o * g[1][0] for o, g in zip(out_hw, geo)), dtype=torch.float32, device=dev)
+    macs = [g[1][0] * g[1][1] * g[1][2] * g[1][3] * o * o * batch for o, g in zip(out_hw, geo)]
+
+    def views(i):
+        (cout, cin, kh, kw), stride, pad, size = geo[i][1], geo[i][2], geo[i][3], geo[i][4]
+        x = xbuf[:batch * size * size * cin].view(batch, size, size, cin)
+        y = ybuf[:batch * out_hw[i] * out_hw[i] * cout].view(batch, out_hw[i], out_hw[i], cout)
+        return x, y, stride, pad
+
+    def step():
+        for i in range(len(geo)):
+            x, y, stride, pad = views(i)
+            B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+
+    stream = torch.cuda.current_stream(dev)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize(dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize(dev)
+    wall = time.perf_counter() - t0
+    if d.read_status() != (0, 0):
+        print(f"bench.py: device status {d.read_status()}", file=sys.stderr)
+        sys.exit(1)
+    kernel_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+    flops = 2.0 * sum(macs)
+
+    per_layer = []
+    if args.per_layer:
+        for i in range(len(geo)):
+            x, y, stride, pad = views(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(3):
+                B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+            e1.record(stream)
+            torch.cuda.synchronize(dev)
+            ms = e0.elapsed_time(e1) / 3
+            per_layer.append({"layer": geo[i][0], "shape": list(shapes[i]), "in": geo[i][4], "stride": geo[i][2],
+                              "ms": ms, "TFLOPs": 2.0 * macs[i] / (ms * 1e-3) / 1e12})
+
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+    result = {
+        "metric": "fused decode + conv TFLOP/s (ResNet-50 conv layers, weights decoded inside the kernel)",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config5:resnet50_fused_conv", "batch": batch, "layers": len(geo), "image": 224,
+                   "macs_per_step": int(sum(macs)), "symbols": w.numel, "compressed_bytes": h.compressed_bytes(),
+                   "bits_per_symbol": 8.0 * h.compressed_bytes() / w.numel, "chunks": int(len(h.chunks))},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel_ms": kernel_ms},
+    }
+    if per_layer:
+        result["per_layer"] = per_layer
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import conv_oracle as CO
+        # sampled outputs of every layer against the oracle, one dot product each
+        rng = np.random.default_rng(7)
+        worst = 0.0
+        for i in range(len(geo)):
+            x, y, stride, pad = views(i)
+            B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+            torch.cuda.synchronize(dev)
+            cout, cin, kh, kw = shapes[i]
+            where = np.stack([rng.integers(0, n, 24) for n in (batch, out_hw[i], out_hw[i], cout)], axis=1)
+            got = y[tuple(torch.from_numpy(where.T).to(dev))].cpu().numpy().astype(np.float64)
+            size = geo[i][4]
+            xh = values[:batch * size * size * cin].reshape(batch, size, size, cin)
+            wts = CO.dequantized_weights(syms[i], L[i].zero_point, L[i].scale, (cout, kh, kw, cin))
+            want = CO.conv2d_nhwc_samples(xh, wts, stride, pad, where)
+            ref = float(np.sqrt(np.mean(want ** 2))) + 1e-30
+            worst = max(worst, float(np.max(np.abs(got - want))) / ref)
+        result["max_error_over_rms_sampled"] = worst
+        result["matches_oracle"] = bool(worst <= 1e-2)
+        # the oracle itself on the host: decode one layer's weights and convolve in fp64
+        i = [g[0] for g in geo].index("layer3.1.conv2")
+        cout, cin, kh, kw = shapes[i]
+        size = geo[i][4]
+        xh = values[:batch * size * size * cin].reshape(batch, size, size, cin)
+        c = oracle.encode_layers([syms[i]], w.table_log, w.n_streams, rows[i] * cin * kh * kw)
+        cores = min(os.cpu_count() or 1, 16)
+        t0 = time.perf_counter()
+        sym, _, rc = oracle.decode_dequant(c, [L[i].zero_point], [L[i].scale], [0], [None], out_dtype="f32", n_threads=cores)
+        wts = CO.dequantized_weights(sym, L[i].zero_point, L[i].scale, (cout, kh, kw, cin))
+        CO.conv2d_nhwc(xh, wts, geo[i][2], geo[i][3])
+        dt = time.perf_counter() - t0
+        assert rc == 0
+        result["cpu_baseline"] = {"value": 2.0 * macs[i] / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"layer3.1.conv2 ({cout}x{cin}x{kh}x{kw}, {size}x{size}, batch {batch}): oracle "
+                                            f"decode + fp64 convolution, {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--batch", type=int, default=64, help="config 5 only: images per step")
+    ap.add_argument("--per-layer", action="store_true", help="config 5 only: also time every layer on its own")
     ap.add_argument("--blocks", type=int, default=32, help="config 4 only: number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
@@ -78,6 +207,9 @@ def main():
         print("bench.py: this build decodes on ONE GPU (chunks are independent: each GPU would decode the chunks "
               "of its own layers, no collective involved). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    if args.config == 5:
+        return bench_fused_conv(args)
 
     import numpy as np
     import torch
