@@ -366,13 +366,13 @@ def bits_of(t) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- fused decode + convolution
-CONV_ROWS = 16          # output channels per workgroup of anszp_conv_fused
+CONV_ROWS = 16          # anszp_conv_fused works on panels of 16, 32 or 64 output channels
 CONV_MAX_K = 4608
 
 
 def conv_rows_per_chunk(k: int) -> int:
     """Output channels per chunk for a layer with reduction length k = kh*kw*cin: the largest power of
-    two (at most 16) that keeps a chunk at 4096 symbols or fewer, so that the four wavefronts of a
+    two (at most 16) that keeps a chunk at 4096 symbols or fewer, so that the wavefronts of a
     workgroup have a chunk each to decode where the rows are long."""
     r = 1
     while r < CONV_ROWS and 2 * r * k <= 4096:

@@ -12,7 +12,7 @@
 // contiguous bytes of the activation tensor.
 //
 // One workgroup owns 16 output channels (the M of v_mfma_f32_16x16x32_bf16) and a range of output
-// pixels.  Phase 1: its four wavefronts decode the chunks that hold those 16 weight rows, one
+// pixels.  Phase 1: its eight wavefronts decode the chunks that hold those 16 weight rows, one
 // symbol per look-up with one lane per stream (Sec. II-A, III-B), into a [16][K] byte panel in LDS.
 // Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column tiles): per 32 k it
 // reads 8 panel bytes per lane, converts them once, loads four 16-byte activation vectors and
@@ -26,11 +26,13 @@
 namespace {
 
 constexpr uint32_t kWave = 64;
-constexpr uint32_t kThreads = 256;
+constexpr uint32_t kThreads = 512;
 constexpr uint32_t kWaves = kThreads / kWave;
-constexpr uint32_t kRows = 16;              // output channels per workgroup
+constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
 constexpr uint32_t kColsPerWave = 64;       // output pixels a wavefront works on at a time: 4 MFMA column tiles
 constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
+constexpr uint32_t kStageWords = 1280;      // per wavefront: LDS room for one chunk's compressed words (a chunk of
+                                            // 4608 8-bit symbols in 64 streams needs at most 1152 + 64)
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float floatx4;
@@ -50,7 +52,7 @@ struct ConvParams {
     uint64_t n_stream_hdr, payload_words, n_scales;
     uint32_t layer_id, table_log, n_streams, rows_per_chunk, chunks_per_panel;
     uint32_t in_h, in_w, cin, cout, kh, kw, stride, pad, out_h, out_w;
-    uint32_t K, row_stride, n_pixels, n_mtiles, blocks_per_split;
+    uint32_t K, row_stride, n_pixels, n_mtiles, blocks_per_split;   // n_mtiles: panels of 16 * MR rows
 };
 
 __device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
@@ -78,8 +80,10 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
 
 // One chunk, one look-up per symbol (Sec. II-A; Sec. III-B: one lane per stream), symbols into the
 // LDS panel: symbol i of the chunk belongs to panel row i / K, column i % K.  Returns error bits.
+// The chunk's words are first copied to `stage` (LDS, this wavefront's own) with 16-byte loads when they
+// fit, so that the decode loop waits for no global load; a larger chunk is read word by word in place.
 __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk_t& c, const uint32_t* table,
-                                          uint8_t* rows, uint32_t lane) {
+                                          uint32_t* stage, uint8_t* rows, uint32_t lane) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
@@ -92,6 +96,20 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
 
     const uint32_t* words = p.payload + c.payload_offset;
     const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
+    const bool staged = word_limit <= kStageWords;
+    if (staged) {
+        const bool aligned = (c.payload_offset & 3u) == 0;          // the packer's chunks start on 16 bytes
+        for (uint32_t i = 4u * lane; i < word_limit; i += 4u * kWave) {
+            if (aligned && i + 4u <= word_limit) {
+                *reinterpret_cast<words4*>(stage + i) = *reinterpret_cast<const words4*>(words + i);
+            } else {
+                for (uint32_t j = i; j < min(i + 4u, word_limit); ++j) stage[j] = words[j];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // LDS serves a wavefront's accesses in order
+        __builtin_amdgcn_wave_barrier();
+        words = stage;
+    }
     auto word_at = [&](uint32_t i) { return i < word_limit ? words[i] : 0u; };
     uint32_t next_word = first_word;
     uint64_t buf = 0;
@@ -143,11 +161,15 @@ __device__ __forceinline__ bf16x8 weights_of(words2 q, float z) {
 
 // GENERIC: any number of input channels (every activation is addressed on its own); otherwise the
 // input channels are a multiple of 8 and a lane's 8 consecutive k lie under one kernel tap.
-template <bool GENERIC>
+// MR: MFMA row tiles per workgroup.  Every wavefront multiplies all 16 * MR panel rows with its columns, so
+// an activation vector loaded once feeds MR MFMAs.
+template <bool GENERIC, uint32_t MR>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint32_t* table = reinterpret_cast<uint32_t*>(lds);
-    uint8_t* panel = lds + (4u << p.table_log);
+    const uint32_t table_bytes = max(4u << p.table_log, 16u);      // what follows stays 16-byte aligned
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds + table_bytes);
+    uint8_t* panel = lds + table_bytes + kWaves * kStageWords * 4u;
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t mtile = blockIdx.x % p.n_mtiles, split = blockIdx.x / p.n_mtiles;
@@ -165,14 +187,15 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                         c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
                         uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
         if (!ok) { err |= ANSZP_ST_BAD_DESC; continue; }
-        err |= decode_chunk_to_panel(p, c, table, panel + j * p.rows_per_chunk * p.row_stride, lane);
+        err |= decode_chunk_to_panel(p, c, table, stage + wave * kStageWords, panel + j * p.rows_per_chunk * p.row_stride, lane);
     }
     if (err && lane == 0) report(p.status, err);
     __syncthreads();
 
     // ---- phase 2: the panel times the activations
     const uint32_t col = lane & 15u, kg = lane >> 4;              // MFMA operand layout: row or column, group of 8 k
-    const uint8_t* a_row = panel + col * p.row_stride + 8u * kg;  // A: lane holds row lane % 16, k = 8 * (lane / 16) + 0..7
+    const uint8_t* a_row = panel + col * p.row_stride + 8u * kg;  // A: lane holds row lane % 16 of a row tile, k = 8 * (lane / 16) + 0..7
+    const uint32_t tile_stride = kRows * p.row_stride;
     const float zf = static_cast<float>(lay.zero_point);
     const bool per_channel = lay.channel_len != 0;
     const uint32_t n_blocks = (p.n_pixels + kColsPerWave - 1u) / kColsPerWave;
@@ -197,38 +220,65 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             w0[q] = int32_t(wo * p.stride) - int32_t(p.pad);
             img[q] = b * p.in_h * p.in_w;
         }
-        floatx4 acc[4];
+        floatx4 acc[MR][4];
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) acc[q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 
         if constexpr (!GENERIC) {
-            for (uint32_t r = 0; r < p.kh; ++r) {
-                for (uint32_t s = 0; s < p.kw; ++s) {
-                    const uint16_t* src_q[4];
-                    bool inside[4];
-#pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q) {
-                        const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(s);
-                        inside[q] = valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
-                        const uint32_t at = inside[q] ? img[q] + uint32_t(h) * p.in_w + uint32_t(w) : 0u;
-                        src_q[q] = p.x + uint64_t(at) * p.cin + 8u * kg;
-                    }
-                    const uint8_t* a_tap = a_row + (r * p.kw + s) * p.cin;
-                    for (uint32_t c0 = 0; c0 < p.cin; c0 += 32u) {
-                        const bool live = c0 + 8u * kg < p.cin;          // the last 32 k of a tap may be partly beyond it
-                        words4 bq[4];
-#pragma unroll
-                        for (uint32_t q = 0; q < 4; ++q) {
-                            bq[q] = words4{0u, 0u, 0u, 0u};
-                            if (inside[q] && live) bq[q] = *reinterpret_cast<const words4*>(src_q[q] + c0);
-                        }
-                        const words2 aq = *reinterpret_cast<const words2*>(a_tap + c0);
-                        const bf16x8 a = weights_of(aq, zf);
-#pragma unroll
-                        for (uint32_t q = 0; q < 4; ++q)
-                            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bq[q]), acc[q], 0, 0, 0);
-                    }
+            // Steps of 32 k: kernel taps outermost, 32 input channels at a time inside a tap.  The
+            // activation vectors of a group of kGroup steps are requested while the MFMAs of the group
+            // before run, so a wavefront waits for memory once per group at most.
+            const uint32_t steps_per_tap = (p.cin + 31u) / 32u;
+            const uint32_t n_steps = p.kh * p.kw * steps_per_tap;
+            struct Cursor { uint32_t r, s, c0, a_off; };          // a_off: the step's first k (its panel column)
+            auto advance = [&](Cursor& c) {
+                c.c0 += 32u;
+                if (c.c0 >= p.cin) {
+                    c.c0 = 0;
+                    c.a_off += p.cin;
+                    if (++c.s == p.kw) { c.s = 0; ++c.r; }
                 }
+            };
+            auto load_step = [&](const Cursor& c, bool in_range, words4 (&b)[4]) {
+                const bool live = in_range && c.c0 + 8u * kg < p.cin;   // the last 32 k of a tap may be partly beyond it
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    const int32_t h = h0[q] + int32_t(c.r), w = w0[q] + int32_t(c.s);
+                    const bool inside = live && valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                    b[q] = words4{0u, 0u, 0u, 0u};
+                    if (inside)
+                        b[q] = *reinterpret_cast<const words4*>(
+                            p.x + uint64_t(img[q] + uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c.c0 + 8u * kg);
+                }
+            };
+            constexpr uint32_t kGroup = MR >= 4 ? 2 : 4;            // the accumulators need the registers
+            words4 cur[kGroup][4], nxt[kGroup][4];
+            Cursor ld{0u, 0u, 0u, 0u}, use{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (uint32_t j = 0; j < kGroup; ++j) { load_step(ld, j < n_steps, cur[j]); advance(ld); }
+            for (uint32_t g = 0; g < n_steps; g += kGroup) {
+#pragma unroll
+                for (uint32_t j = 0; j < kGroup; ++j) { load_step(ld, g + kGroup + j < n_steps, nxt[j]); advance(ld); }
+#pragma unroll
+                for (uint32_t j = 0; j < kGroup; ++j) {
+                    if (g + j < n_steps) {
+#pragma unroll
+                        for (uint32_t m = 0; m < MR; ++m) {
+                            const words2 aq = *reinterpret_cast<const words2*>(a_row + m * tile_stride + use.a_off + use.c0);
+                            const bf16x8 a = weights_of(aq, zf);
+#pragma unroll
+                            for (uint32_t q = 0; q < 4; ++q)
+                                acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, cur[j][q]), acc[m][q], 0, 0, 0);
+                        }
+                    }
+                    advance(use);
+                }
+#pragma unroll
+                for (uint32_t j = 0; j < kGroup; ++j)
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) cur[j][q] = nxt[j][q];
             }
         } else {
             for (uint32_t k0 = 0; k0 < Kp; k0 += 32u) {
@@ -246,39 +296,48 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                         bv[q][j] = inside ? p.x[uint64_t(img[q] + uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c] : uint16_t(0);
                     }
                 }
-                const words2 aq = *reinterpret_cast<const words2*>(a_row + k0);
-                const bf16x8 a = weights_of(aq, zf);
+                words4 b[4];
 #pragma unroll
-                for (uint32_t q = 0; q < 4; ++q) {
-                    const words4 b = {uint32_t(bv[q][0]) | uint32_t(bv[q][1]) << 16, uint32_t(bv[q][2]) | uint32_t(bv[q][3]) << 16,
-                                      uint32_t(bv[q][4]) | uint32_t(bv[q][5]) << 16, uint32_t(bv[q][6]) | uint32_t(bv[q][7]) << 16};
-                    acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b), acc[q], 0, 0, 0);
+                for (uint32_t q = 0; q < 4; ++q)
+                    b[q] = words4{uint32_t(bv[q][0]) | uint32_t(bv[q][1]) << 16, uint32_t(bv[q][2]) | uint32_t(bv[q][3]) << 16,
+                                  uint32_t(bv[q][4]) | uint32_t(bv[q][5]) << 16, uint32_t(bv[q][6]) | uint32_t(bv[q][7]) << 16};
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m) {
+                    const words2 aq = *reinterpret_cast<const words2*>(a_row + m * tile_stride + k0);
+                    const bf16x8 a = weights_of(aq, zf);
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q)
+                        acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[q]), acc[m][q], 0, 0, 0);
                 }
             }
         }
 
-        // D: lane holds column lane % 16, rows 4 * (lane / 16) + 0..3: four consecutive output channels
-        const uint32_t o = mtile * kRows + 4u * kg;
-        float sc[4];
+        // D: lane holds column lane % 16, rows 4 * (lane / 16) + 0..3 of each row tile: four consecutive output channels
 #pragma unroll
-        for (uint32_t i = 0; i < 4; ++i) {
-            sc[i] = lay.scale;
-            if (per_channel) {
-                const uint64_t ch = lay.scales_offset + o + i;
-                sc[i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
+        for (uint32_t m = 0; m < MR; ++m) {
+            const uint32_t o = (mtile * MR + m) * kRows + 4u * kg;
+            float sc[4];
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) {
+                sc[i] = lay.scale;
+                if (per_channel) {
+                    const uint64_t ch = lay.scales_offset + o + i;
+                    sc[i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
+                }
             }
-        }
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            if (valid[q]) {
-                const floatx4 out = {acc[q][0] * sc[0], acc[q][1] * sc[1], acc[q][2] * sc[2], acc[q][3] * sc[3]};
-                *reinterpret_cast<floatx4*>(p.y + uint64_t(pix[q]) * p.cout + o) = out;
+            for (uint32_t q = 0; q < 4; ++q) {
+                if (valid[q]) {
+                    const floatx4 out = {acc[m][q][0] * sc[0], acc[m][q][1] * sc[1], acc[m][q][2] * sc[2], acc[m][q][3] * sc[3]};
+                    *reinterpret_cast<floatx4*>(p.y + uint64_t(pix[q]) * p.cout + o) = out;
+                }
             }
         }
     }
 }
 
 constexpr uint32_t kMaxK = 4608;           // reduction length whose 16-row panel (72 KiB) fits LDS beside the table
+constexpr uint32_t kLdsLimit = 160u * 1024u;
 
 }  // namespace
 
@@ -299,8 +358,15 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     const uint32_t out_w = (a->in_w + 2u * a->pad - a->kw) / a->stride + 1u;
     const uint64_t n_pixels = uint64_t(a->batch) * out_h * out_w;
     if (n_pixels >= (1ull << 31) || uint64_t(a->batch) * a->in_h * a->in_w >= (1ull << 31)) return ANSZP_E_RANGE;
-    const uint32_t n_mtiles = a->cout / kRows;
-    if (a->n_chunks < uint64_t(n_mtiles) * (kRows / R)) return ANSZP_E_RANGE;
+    if (a->n_chunks < a->cout / R) return ANSZP_E_RANGE;
+    // Row tiles per workgroup: as many of 4, 2, 1 as divide the output channels and leave the panel room in LDS
+    // beside the table and the staging buffers (more rows per activation vector loaded).
+    const uint32_t row_stride = ((uint32_t(K) + 31u) & ~31u) + kRowPad;
+    const uint32_t table_bytes = (4u << a->table_log) < 16u ? 16u : (4u << a->table_log);
+    const uint32_t fixed_bytes = table_bytes + kWaves * kStageWords * 4u + 64u;
+    uint32_t mr = 4;
+    while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride > kLdsLimit)) mr >>= 1;
+    const uint32_t n_mtiles = a->cout / (kRows * mr);
     if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y)) & 15u) return ANSZP_E_RANGE;
 
     ConvParams p{};
@@ -308,30 +374,35 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     p.layers = a->layers; p.scales = a->scales; p.x = a->x; p.y = a->y; p.status = a->status;
     p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words; p.n_scales = a->scales ? a->n_scales : 0;
     p.layer_id = a->layer_id; p.table_log = a->table_log; p.n_streams = a->n_streams;
-    p.rows_per_chunk = R; p.chunks_per_panel = kRows / R;
+    p.rows_per_chunk = R;
     p.in_h = a->in_h; p.in_w = a->in_w; p.cin = a->cin; p.cout = a->cout; p.kh = a->kh; p.kw = a->kw;
     p.stride = a->stride; p.pad = a->pad; p.out_h = out_h; p.out_w = out_w;
     p.K = uint32_t(K);
-    p.row_stride = ((p.K + 31u) & ~31u) + kRowPad;
+    p.row_stride = row_stride;
+    p.chunks_per_panel = kRows * mr / R;
     p.n_pixels = uint32_t(n_pixels);
     p.n_mtiles = n_mtiles;
 
     int device = 0, cus = 0;
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
-    // Every workgroup decodes its panel once, so few, long-lived workgroups: about four per CU.
+    // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once
+    // (one or two per CU, by LDS), each with at least one block of pixels per wavefront.
+    const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride;
+    const uint32_t per_cu = 2u * lds_bytes <= kLdsLimit ? 2u : 1u;
     const uint32_t n_blocks = uint32_t((n_pixels + kColsPerWave - 1u) / kColsPerWave);
-    uint32_t splits = (4u * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
-    const uint32_t max_splits = (n_blocks + kWaves - 1u) / kWaves;          // at least one block per wavefront
+    uint32_t splits = (per_cu * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
+    const uint32_t max_splits = (n_blocks + kWaves - 1u) / kWaves;
     if (splits > max_splits) splits = max_splits;
     if (splits == 0) splits = 1;
     p.blocks_per_split = (n_blocks + splits - 1u) / splits;
     splits = (n_blocks + p.blocks_per_split - 1u) / p.blocks_per_split;
 
-    // 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row
-    const uint32_t lds_bytes = (4u << a->table_log) + kRows * p.row_stride + 64u;
+    // (fixed_bytes counts 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row)
     const bool generic = (a->cin % 8u) != 0;
-    auto kernel = generic ? conv_fused_kernel<true> : conv_fused_kernel<false>;
+    void (*kernel)(ConvParams) = nullptr;
+    if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4> : mr == 2 ? conv_fused_kernel<true, 2> : conv_fused_kernel<true, 1>;
+    else kernel = mr == 4 ? conv_fused_kernel<false, 4> : mr == 2 ? conv_fused_kernel<false, 2> : conv_fused_kernel<false, 1>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             int(lds_bytes)) != hipSuccess) return ANSZP_E_HIP;
     hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);

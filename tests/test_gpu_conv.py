@@ -74,6 +74,8 @@ def _check(status, got, want, magnitude):
     ((32, 40, 3, 3), 1, 7, 7, 1, 1),          # 40 input channels: the last 32 k of a tap are partly beyond it
     ((16, 512, 3, 3), 1, 7, 7, 1, 1),         # K = 4608: the largest panel
     ((16, 5, 2, 2), 1, 5, 5, 1, 0),           # odd everything, no padding
+    ((64, 256, 3, 3), 2, 7, 7, 1, 1),         # K = 2304: two row tiles per workgroup is what fits on chip
+    ((128, 64, 3, 3), 2, 9, 9, 1, 1),         # four row tiles per workgroup, two such panels
 ])
 def test_convolution_shapes(orc, shape, B_, H, Wd, stride, pad):
     _check(*_case(orc, shape, B_, H, Wd, stride, pad))
