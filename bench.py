@@ -89,7 +89,8 @@ def bench_fused_conv(args):
     codes, values = W.bf16_activations(n_x, 5)
     xbuf = torch.from_numpy(codes.view(np.int16)).to(dev).view(torch.bfloat16)
     out_hw = [(g[4] + 2 * g[3] - g[1][2]) // g[2] + 1 for g in geo]
-    ybuf = torch.empty(max(batch * o * o * g[1][0] for o, g in zip(out_hw, geo)), dtype=torch.float32, device=dev)
+    ybuf = torch.empty(max(batch * o * o * g[1][0] for o, g in zip(out_hw, geo)),
+                       dtype=torch.float32 if args.y_dtype == "f32" else torch.bfloat16, device=dev)
     macs = [g[1][0] * g[1][1] * g[1][2] * g[1][3] * o * o * batch for o, g in zip(out_hw, geo)]
 
     def views(i):
@@ -98,10 +99,14 @@ def bench_fused_conv(args):
         y = ybuf[:batch * out_hw[i] * out_hw[i] * cout].view(batch, out_hw[i], out_hw[i], cout)
         return x, y, stride, pad
 
+    calls = []
+    for i in range(len(geo)):
+        x, y, stride, pad = views(i)
+        calls.append(B.conv_args(d, i, first[i], rows[i], x, shapes[i], stride, pad, y))
+
     def step():
-        for i in range(len(geo)):
-            x, y, stride, pad = views(i)
-            B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+        for a in calls:
+            B.conv_fused_raw(a, dev)
 
     stream = torch.cuda.current_stream(dev)
     for _ in range(args.warmup):
@@ -129,7 +134,7 @@ def bench_fused_conv(args):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(3):
-                B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+                B.conv_fused_raw(calls[i], dev)
             e1.record(stream)
             torch.cuda.synchronize(dev)
             ms = e0.elapsed_time(e1) / 3
@@ -143,6 +148,7 @@ def bench_fused_conv(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config5:resnet50_fused_conv", "batch": batch, "layers": len(geo), "image": 224,
+                   "y_dtype": args.y_dtype,
                    "macs_per_step": int(sum(macs)), "symbols": w.numel, "compressed_bytes": h.compressed_bytes(),
                    "bits_per_symbol": 8.0 * h.compressed_bytes() / w.numel, "chunks": int(len(h.chunks))},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -158,11 +164,11 @@ def bench_fused_conv(args):
         worst = 0.0
         for i in range(len(geo)):
             x, y, stride, pad = views(i)
-            B.conv_fused(d, i, first[i], rows[i], x, shapes[i], stride, pad, y=y)
+            B.conv_fused_raw(calls[i], dev)
             torch.cuda.synchronize(dev)
             cout, cin, kh, kw = shapes[i]
             where = np.stack([rng.integers(0, n, 24) for n in (batch, out_hw[i], out_hw[i], cout)], axis=1)
-            got = y[tuple(torch.from_numpy(where.T).to(dev))].cpu().numpy().astype(np.float64)
+            got = y[tuple(torch.from_numpy(where.T).to(dev))].float().cpu().numpy().astype(np.float64)
             size = geo[i][4]
             xh = values[:batch * size * size * cin].reshape(batch, size, size, cin)
             wts = CO.dequantized_weights(syms[i], L[i].zero_point, L[i].scale, (cout, kh, kw, cin))
@@ -198,6 +204,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=64, help="config 5 only: images per step")
     ap.add_argument("--per-layer", action="store_true", help="config 5 only: also time every layer on its own")
+    ap.add_argument("--y-dtype", default="bf16", choices=["bf16", "f32"], help="config 5 only: output element type")
     ap.add_argument("--blocks", type=int, default=32, help="config 4 only: number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",

@@ -239,8 +239,11 @@ typedef struct {
                                             holds rows_per_chunk * kh*kw*cin symbols              */
     uint32_t             batch, in_h, in_w, cin, cout, kh, kw, stride, pad;
     const uint16_t*      x;              /* [device] bf16 activations [batch][in_h][in_w][cin], 16-byte aligned */
-    float*               y;              /* [device] [batch][out_h][out_w][cout], out = (in + 2 pad - k) / stride + 1,
-                                            16-byte aligned; every element is written              */
+    void*                y;              /* [device] [batch][out_h][out_w][cout] elements of y_dtype,
+                                            out = (in + 2 pad - k) / stride + 1, 16-byte aligned; every
+                                            element is written                                     */
+    uint32_t             y_dtype;        /* ANSZP_OUT_F32, or ANSZP_OUT_BF16 (the fp32 result rounded
+                                            to nearest even)                                      */
     uint32_t*            status;         /* [device] 2 words, as for anszp_decode                 */
 } anszp_conv_args_t;
 

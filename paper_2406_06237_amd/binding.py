@@ -49,7 +49,7 @@ class ConvArgs(C.Structure):
                 ("rows_per_chunk", C.c_uint32), ("batch", C.c_uint32), ("in_h", C.c_uint32), ("in_w", C.c_uint32),
                 ("cin", C.c_uint32), ("cout", C.c_uint32), ("kh", C.c_uint32), ("kw", C.c_uint32),
                 ("stride", C.c_uint32), ("pad", C.c_uint32),
-                ("x", C.c_void_p), ("y", C.c_void_p), ("status", C.c_void_p)]
+                ("x", C.c_void_p), ("y", C.c_void_p), ("y_dtype", C.c_uint32), ("status", C.c_void_p)]
 
 
 class AnszpError(RuntimeError):
@@ -395,19 +395,19 @@ def pack_conv_layers(layer_symbols: Sequence[np.ndarray], shapes: Sequence[tuple
     return h, [int(f) for f in first], rows
 
 
-def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
-               pad: int, y=None):
-    """anszp_conv_fused on torch's current stream: x is a bf16 NHWC tensor, shape = (cout, cin, kh, kw);
-    returns y, fp32 NHWC."""
+def conv_args(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
+              pad: int, y) -> ConvArgs:
+    """The argument struct of anszp_conv_fused for one layer: x a bf16 NHWC tensor, y an fp32 or bf16 NHWC
+    tensor, shape = (cout, cin, kh, kw)."""
     torch = _torch()
     h = d.host
     cout, cin, kh, kw = shape
     B, H, W, cin_x = x.shape
+    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     if x.dtype != torch.bfloat16 or not x.is_contiguous() or cin_x != cin:
         raise ValueError("x must be a contiguous bf16 [batch][h][w][cin] tensor")
-    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
-    if y is None:
-        y = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=x.device)
+    if y.dtype not in (torch.float32, torch.bfloat16) or not y.is_contiguous() or tuple(y.shape) != (B, ho, wo, cout):
+        raise ValueError("y must be a contiguous fp32 or bf16 [batch][out_h][out_w][cout] tensor")
     a = ConvArgs()
     a.tables = d.tables.data_ptr(); a.n_tables = len(h.freqs); a.table_log = h.table_log
     a.n_streams = h.n_streams; a.layer_id = layer
@@ -418,6 +418,28 @@ def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk:
     a.rows_per_chunk = rows_per_chunk
     a.batch, a.in_h, a.in_w, a.cin, a.cout, a.kh, a.kw, a.stride, a.pad = B, H, W, cin, cout, kh, kw, stride, pad
     a.x = x.data_ptr(); a.y = y.data_ptr(); a.status = d.status.data_ptr()
-    with torch.cuda.device(x.device):
-        _check(lib().anszp_conv_fused(C.byref(a), _stream_ptr(torch, x.device)), "anszp_conv_fused")
+    a.y_dtype = OUT_F32 if y.dtype == torch.float32 else OUT_BF16
+    return a
+
+
+def conv_fused_raw(args: ConvArgs, device="cuda:0"):
+    """anszp_conv_fused on torch's current stream of `device`."""
+    torch = _torch()
+    with torch.cuda.device(device):
+        _check(lib().anszp_conv_fused(C.byref(args), _stream_ptr(torch, device)), "anszp_conv_fused")
+
+
+def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
+               pad: int, y=None, y_dtype: str = "f32"):
+    """anszp_conv_fused on torch's current stream: x is a bf16 NHWC tensor, shape = (cout, cin, kh, kw);
+    returns y, NHWC, fp32 or bf16 (y_dtype, or the dtype of the y passed in)."""
+    torch = _torch()
+    cout, cin, kh, kw = shape
+    B, H, W, _ = x.shape
+    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    if ho < 1 or wo < 1:
+        raise AnszpError(-2, "anszp_conv_fused")
+    if y is None:
+        y = torch.empty((B, ho, wo, cout), dtype=getattr(torch, _TORCH_OUT[y_dtype]), device=x.device)
+    conv_fused_raw(conv_args(d, layer, first_chunk, rows_per_chunk, x, shape, stride, pad, y), x.device)
     return y

@@ -47,12 +47,12 @@ struct ConvParams {
     const anszp_layer_t* layers;
     const float* scales;
     const uint16_t* x;
-    float* y;
+    void* y;
     uint32_t* status;
     uint64_t n_stream_hdr, payload_words, n_scales;
     uint32_t layer_id, table_log, n_streams, rows_per_chunk, chunks_per_panel;
     uint32_t in_h, in_w, cin, cout, kh, kw, stride, pad, out_h, out_w;
-    uint32_t K, row_stride, n_pixels, n_mtiles, blocks_per_split;   // n_mtiles: panels of 16 * MR rows
+    uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles, blocks_per_split;   // n_mtiles: panels of 16 * MR rows
 };
 
 __device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
@@ -227,9 +227,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 
         if constexpr (!GENERIC) {
-            // Steps of 32 k: kernel taps outermost, 32 input channels at a time inside a tap.  The
-            // activation vectors of a group of kGroup steps are requested while the MFMAs of the group
-            // before run, so a wavefront waits for memory once per group at most.
+            // Steps of 32 k: kernel taps outermost, 32 input channels at a time inside a tap.
             const uint32_t steps_per_tap = (p.cin + 31u) / 32u;
             const uint32_t n_steps = p.kh * p.kw * steps_per_tap;
             struct Cursor { uint32_t r, s, c0, a_off; };          // a_off: the step's first k (its panel column)
@@ -241,44 +239,52 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                     if (++c.s == p.kw) { c.s = 0; ++c.r; }
                 }
             };
-            auto load_step = [&](const Cursor& c, bool in_range, words4 (&b)[4]) {
-                const bool live = in_range && c.c0 + 8u * kg < p.cin;   // the last 32 k of a tap may be partly beyond it
+            // where each column's pixel under the load cursor's kernel tap lies (recomputed when the cursor
+            // enters a tap), so that a step costs one address addition per column
+            const uint16_t* tap_ptr[4];
+            bool tap_inside[4];
+            auto enter_tap = [&](const Cursor& c) {
 #pragma unroll
                 for (uint32_t q = 0; q < 4; ++q) {
                     const int32_t h = h0[q] + int32_t(c.r), w = w0[q] + int32_t(c.s);
-                    const bool inside = live && valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
-                    b[q] = words4{0u, 0u, 0u, 0u};
-                    if (inside)
-                        b[q] = *reinterpret_cast<const words4*>(
-                            p.x + uint64_t(img[q] + uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c.c0 + 8u * kg);
+                    tap_inside[q] = valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                    const uint32_t at = tap_inside[q] ? img[q] + uint32_t(h) * p.in_w + uint32_t(w) : 0u;
+                    tap_ptr[q] = p.x + uint64_t(at) * p.cin + 8u * kg;
                 }
             };
-            constexpr uint32_t kGroup = MR >= 4 ? 2 : 4;            // the accumulators need the registers
-            words4 cur[kGroup][4], nxt[kGroup][4];
+            auto load_step = [&](const Cursor& c, bool in_range, words4 (&b)[4]) {
+                if (c.c0 == 0) enter_tap(c);                            // wavefront-uniform
+                const bool live = in_range && c.c0 + 8u * kg < p.cin;   // the last 32 k of a tap may be partly beyond it
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    b[q] = words4{0u, 0u, 0u, 0u};
+                    if (live && tap_inside[q]) b[q] = *reinterpret_cast<const words4*>(tap_ptr[q] + c.c0);
+                }
+            };
+            // a ring of kDepth steps' activation vectors: a step's slot is refilled, for the step kDepth
+            // later, as soon as its MFMAs are issued
+            constexpr uint32_t kDepth = 8;
+            words4 ring[kDepth][4];
             Cursor ld{0u, 0u, 0u, 0u}, use{0u, 0u, 0u, 0u};
 #pragma unroll
-            for (uint32_t j = 0; j < kGroup; ++j) { load_step(ld, j < n_steps, cur[j]); advance(ld); }
-            for (uint32_t g = 0; g < n_steps; g += kGroup) {
+            for (uint32_t d = 0; d < kDepth; ++d) { load_step(ld, d < n_steps, ring[d]); advance(ld); }
+            for (uint32_t base = 0; base < n_steps; base += kDepth) {
 #pragma unroll
-                for (uint32_t j = 0; j < kGroup; ++j) { load_step(ld, g + kGroup + j < n_steps, nxt[j]); advance(ld); }
-#pragma unroll
-                for (uint32_t j = 0; j < kGroup; ++j) {
-                    if (g + j < n_steps) {
+                for (uint32_t d = 0; d < kDepth; ++d) {
+                    if (base + d < n_steps) {
 #pragma unroll
                         for (uint32_t m = 0; m < MR; ++m) {
                             const words2 aq = *reinterpret_cast<const words2*>(a_row + m * tile_stride + use.a_off + use.c0);
                             const bf16x8 a = weights_of(aq, zf);
 #pragma unroll
                             for (uint32_t q = 0; q < 4; ++q)
-                                acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, cur[j][q]), acc[m][q], 0, 0, 0);
+                                acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
                         }
                     }
                     advance(use);
+                    load_step(ld, base + d + kDepth < n_steps, ring[d]);
+                    advance(ld);
                 }
-#pragma unroll
-                for (uint32_t j = 0; j < kGroup; ++j)
-#pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q) cur[j][q] = nxt[j][q];
             }
         } else {
             for (uint32_t k0 = 0; k0 < Kp; k0 += 32u) {
@@ -329,7 +335,15 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             for (uint32_t q = 0; q < 4; ++q) {
                 if (valid[q]) {
                     const floatx4 out = {acc[m][q][0] * sc[0], acc[m][q][1] * sc[1], acc[m][q][2] * sc[2], acc[m][q][3] * sc[3]};
-                    *reinterpret_cast<floatx4*>(p.y + uint64_t(pix[q]) * p.cout + o) = out;
+                    const uint64_t at = uint64_t(pix[q]) * p.cout + o;
+                    if (p.y_bf16) {                                   // round to nearest even (v_cvt_pk_bf16_f32)
+                        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                        const bf16x4 r = {static_cast<__bf16>(out[0]), static_cast<__bf16>(out[1]),
+                                          static_cast<__bf16>(out[2]), static_cast<__bf16>(out[3])};
+                        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(p.y) + at) = r;
+                    } else {
+                        *reinterpret_cast<floatx4*>(static_cast<float*>(p.y) + at) = out;
+                    }
                 }
             }
         }
@@ -346,6 +360,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     if (a->payload_words && !a->payload) return ANSZP_E_NULL;
     if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 || a->n_streams > 64) return ANSZP_E_RANGE;
     if (a->layer_id >= a->n_tables) return ANSZP_E_RANGE;
+    if (a->y_dtype != ANSZP_OUT_F32 && a->y_dtype != ANSZP_OUT_BF16) return ANSZP_E_RANGE;
     if (!a->batch || !a->in_h || !a->in_w || !a->cin || !a->cout || !a->kh || !a->kw || !a->stride) return ANSZP_E_RANGE;
     if (a->in_h > 32768u || a->in_w > 32768u || a->cin > 65536u || a->kh > 64u || a->kw > 64u || a->pad > 64u) return ANSZP_E_RANGE;
     if (a->cout % kRows) return ANSZP_E_RANGE;
@@ -372,6 +387,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     ConvParams p{};
     p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
     p.layers = a->layers; p.scales = a->scales; p.x = a->x; p.y = a->y; p.status = a->status;
+    p.y_bf16 = a->y_dtype == ANSZP_OUT_BF16;
     p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words; p.n_scales = a->scales ? a->n_scales : 0;
     p.layer_id = a->layer_id; p.table_log = a->table_log; p.n_streams = a->n_streams;
     p.rows_per_chunk = R;
@@ -403,8 +419,15 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     void (*kernel)(ConvParams) = nullptr;
     if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4> : mr == 2 ? conv_fused_kernel<true, 2> : conv_fused_kernel<true, 1>;
     else kernel = mr == 4 ? conv_fused_kernel<false, 4> : mr == 2 ? conv_fused_kernel<false, 2> : conv_fused_kernel<false, 1>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            int(lds_bytes)) != hipSuccess) return ANSZP_E_HIP;
+    // the kernels may use all of the CU's LDS: said once per kernel and device
+    static bool lds_allowed[2][3][64] = {};
+    const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
+    if (device < 0 || device >= 64) return ANSZP_E_HIP;
+    if (!lds_allowed[generic][slot][device]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(kLdsLimit)) != hipSuccess) return ANSZP_E_HIP;
+        lds_allowed[generic][slot][device] = true;
+    }
     hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }

@@ -91,6 +91,27 @@ def test_scale_per_output_channel(orc):
     _check(*_case(orc, (32, 16, 3, 3), 2, 6, 6, 1, 1, per_channel=True))
 
 
+def test_bf16_output_is_the_fp32_output_rounded(orc):
+    shape, K = (32, 32, 3, 3), 288
+    rows = B.conv_rows_per_chunk(K)
+    lay = _layer(shape, 4, 0.7, 11)
+    w = W.Workload("conv_case", [lay], 12, 64, rows * K, "bf16")
+    d = B.to_device(host_from_oracle(oracle_encode(orc, w), w))
+    codes, values = W.bf16_activations(2 * 9 * 9 * 32, 12)
+    x = torch.from_numpy(codes.view(np.int16).reshape(2, 9, 9, 32)).to("cuda:0").view(torch.bfloat16)
+    y32 = B.conv_fused(d, 0, 0, rows, x, shape, 1, 1)
+    y16 = B.conv_fused(d, 0, 0, rows, x, shape, 1, 1, y_dtype="bf16")
+    assert d.read_status() == (0, 0)
+    assert y16.dtype == torch.bfloat16
+    assert torch.equal(y16, y32.to(torch.bfloat16))               # round to nearest even of the same fp32 sums
+    sym = lay.symbols().reshape(32, 3, 3, 32)
+    want = CO.conv2d_nhwc(values.astype(np.float64).reshape(2, 9, 9, 32),
+                          CO.dequantized_weights(sym, lay.zero_point, lay.scale, sym.shape), 1, 1)
+    got = y16.float().cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - want) - 2.0 ** -8 * np.abs(want)) <= 1e-6 * np.max(np.abs(want))
+    assert np.max(np.abs(got - want)) <= 1e-2 * np.max(np.abs(want))
+
+
 def test_many_pixels_several_splits(orc):
     # 2 * 40 * 40 = 3200 output pixels: 50 blocks of 64 spread over workgroups and wavefronts
     _check(*_case(orc, (64, 32, 3, 3), 2, 40, 40, 1, 1, seed=9))
