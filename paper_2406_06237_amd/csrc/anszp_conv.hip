@@ -98,14 +98,22 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
     const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
     const bool staged = word_limit <= kStageWords;
     if (staged) {
-        const bool aligned = (c.payload_offset & 3u) == 0;          // the packer's chunks start on 16 bytes
-        for (uint32_t i = 4u * lane; i < word_limit; i += 4u * kWave) {
-            if (aligned && i + 4u <= word_limit) {
-                *reinterpret_cast<words4*>(stage + i) = *reinterpret_cast<const words4*>(words + i);
-            } else {
-                for (uint32_t j = i; j < min(i + 4u, word_limit); ++j) stage[j] = words[j];
-            }
-        }
+        // all loads first (from clamped, always valid addresses; chunks start on 16 bytes), then the stores:
+        // a load and its store under one condition would be waited for one after the other
+        constexpr uint32_t kLoads = kStageWords / (4u * kWave);
+        static_assert(kLoads * 4u * kWave == kStageWords, "whole 16-byte loads per lane");
+        const uint32_t quads = word_limit >> 2;
+        const words4* qsrc = reinterpret_cast<const words4*>(quads ? words : p.payload);
+        const uint32_t q_last = quads ? quads - 1u : 0u;
+        words4 v[kLoads];
+#pragma unroll
+        for (uint32_t u = 0; u < kLoads; ++u) v[u] = p.payload_words >= 4u ? qsrc[min(lane + u * kWave, q_last)] : words4{0u, 0u, 0u, 0u};
+        const uint32_t tail_at = (quads << 2) + lane;
+        const uint32_t tail = (lane < 3u && tail_at < word_limit) ? words[tail_at] : 0u;
+#pragma unroll
+        for (uint32_t u = 0; u < kLoads; ++u)
+            if (lane + u * kWave < quads) *reinterpret_cast<words4*>(stage + 4u * (lane + u * kWave)) = v[u];
+        if (lane < 3u && tail_at < word_limit) stage[tail_at] = tail;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // LDS serves a wavefront's accesses in order
         __builtin_amdgcn_wave_barrier();
         words = stage;
@@ -177,13 +185,28 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
 
     // ---- phase 1: the layer's triples (Sec. II-A) into LDS, then this workgroup's 16 weight rows
     const uint32_t* src = p.tables + (uint64_t(p.layer_id) << (p.table_log + 2)) + 2u * L;
-    for (uint32_t i = tid; i < L; i += kThreads) table[i] = src[i];
+    // every global read that depends only on the kernel's arguments is issued before any is waited for:
+    // the table (two 16-byte rows per thread, clamped), the layer's quantizer, this wavefront's first chunk
+    const uint32_t t_rows = L >> 2;
+    const words4* tsrc = reinterpret_cast<const words4*>(src);
+    const uint32_t t_last = t_rows ? t_rows - 1u : 0u;
+    static_assert((1u << ANSZP_MAX_TABLE_LOG) / 4u <= 2u * kThreads, "two table rows per thread");
+    words4 tv0 = {0u, 0u, 0u, 0u}, tv1 = {0u, 0u, 0u, 0u};
+    if (t_rows) { tv0 = tsrc[min(tid, t_last)]; tv1 = tsrc[min(tid + kThreads, t_last)]; }     // uniform condition
+    const uint32_t small = (!t_rows && tid < L) ? src[tid] : 0u;                                // a 2-state table
     const anszp_layer_t lay = p.layers[p.layer_id];
+    const anszp_chunk_t first_chunk = p.chunks[uint64_t(mtile) * p.chunks_per_panel + min(wave, p.chunks_per_panel - 1u)];
+    if (t_rows) {
+        reinterpret_cast<words4*>(table)[min(tid, t_last)] = tv0;
+        reinterpret_cast<words4*>(table)[min(tid + kThreads, t_last)] = tv1;
+    } else if (tid < L) {
+        table[tid] = small;
+    }
     __syncthreads();
     uint32_t err = (lay.channel_len != 0 && lay.channel_len != p.K) ? ANSZP_ST_BAD_DESC : 0u;   // scales per output channel only
     for (uint32_t j = wave; j < p.chunks_per_panel; j += kWaves) {
-        const anszp_chunk_t c = p.chunks[uint64_t(mtile) * p.chunks_per_panel + j];
-        const bool ok = c.layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K &&
+        const anszp_chunk_t c = j == wave ? first_chunk : p.chunks[uint64_t(mtile) * p.chunks_per_panel + j];
+        const bool ok = c.layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K && (c.payload_offset & 3u) == 0 &&
                         c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
                         uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
         if (!ok) { err |= ANSZP_ST_BAD_DESC; continue; }
@@ -382,7 +405,8 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     uint32_t mr = 4;
     while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride > kLdsLimit)) mr >>= 1;
     const uint32_t n_mtiles = a->cout / (kRows * mr);
-    if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y)) & 15u) return ANSZP_E_RANGE;
+    if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y) | reinterpret_cast<uintptr_t>(a->payload) |
+         reinterpret_cast<uintptr_t>(a->tables)) & 15u) return ANSZP_E_RANGE;
 
     ConvParams p{};
     p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
