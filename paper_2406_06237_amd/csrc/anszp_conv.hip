@@ -82,8 +82,10 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
 // LDS panel: symbol i of the chunk belongs to panel row i / K, column i % K.  Returns error bits.
 // The chunk's words are first copied to `stage` (LDS, this wavefront's own) with 16-byte loads when they
 // fit, so that the decode loop waits for no global load; a larger chunk is read word by word in place.
+// P16: the panel holds bf16 values q - z (two bytes per weight) instead of the symbols q.
+template <bool P16>
 __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk_t& c, const uint32_t* table,
-                                          uint32_t* stage, uint8_t* rows, uint32_t lane) {
+                                          uint32_t* stage, uint8_t* rows, uint32_t lane, int32_t zero_point) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
@@ -141,7 +143,12 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
             buf >>= nb;
             have -= nb;
             X = ((e & 0xFFFFu) + bits) & (L - 1u);
-            rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
+            if constexpr (P16) {                     // an integer of at most 8 bits: the upper half of its binary32 form is exact
+                const float w = static_cast<float>(int32_t(e >> 24) - zero_point);
+                reinterpret_cast<uint16_t*>(rows)[row * p.row_stride + col] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
+            } else {
+                rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
+            }
             row += row_step;
             col += col_step;
             if (col >= p.K) { col -= p.K; ++row; }
@@ -171,13 +178,15 @@ __device__ __forceinline__ bf16x8 weights_of(words2 q, float z) {
 // input channels are a multiple of 8 and a lane's 8 consecutive k lie under one kernel tap.
 // MR: MFMA row tiles per workgroup.  Every wavefront multiplies all 16 * MR panel rows with its columns, so
 // an activation vector loaded once feeds MR MFMAs.
-template <bool GENERIC, uint32_t MR>
+// P16: the panel is kept as bf16 (short rows: K <= 576), so that the contraction reads its A operands as they are.
+template <bool GENERIC, uint32_t MR, bool P16>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint32_t* table = reinterpret_cast<uint32_t*>(lds);
     const uint32_t table_bytes = max(4u << p.table_log, 16u);      // what follows stays 16-byte aligned
     uint32_t* stage = reinterpret_cast<uint32_t*>(lds + table_bytes);
     uint8_t* panel = lds + table_bytes + kWaves * kStageWords * 4u;
+    constexpr uint32_t kElem = P16 ? 2u : 1u;                     // bytes per panel element
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t mtile = blockIdx.x % p.n_mtiles, split = blockIdx.x / p.n_mtiles;
@@ -210,16 +219,21 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                         c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
                         uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
         if (!ok) { err |= ANSZP_ST_BAD_DESC; continue; }
-        err |= decode_chunk_to_panel(p, c, table, stage + wave * kStageWords, panel + j * p.rows_per_chunk * p.row_stride, lane);
+        err |= decode_chunk_to_panel<P16>(p, c, table, stage + wave * kStageWords,
+                                          panel + j * p.rows_per_chunk * p.row_stride * kElem, lane, int32_t(lay.zero_point));
     }
     if (err && lane == 0) report(p.status, err);
     __syncthreads();
 
     // ---- phase 2: the panel times the activations
     const uint32_t col = lane & 15u, kg = lane >> 4;              // MFMA operand layout: row or column, group of 8 k
-    const uint8_t* a_row = panel + col * p.row_stride + 8u * kg;  // A: lane holds row lane % 16 of a row tile, k = 8 * (lane / 16) + 0..7
-    const uint32_t tile_stride = kRows * p.row_stride;
+    const uint8_t* a_row = panel + (col * p.row_stride + 8u * kg) * kElem;  // A: lane holds row lane % 16 of a row tile, k = 8 * (lane / 16) + 0..7
+    const uint32_t tile_stride = kRows * p.row_stride * kElem;
     const float zf = static_cast<float>(lay.zero_point);
+    auto a_operand = [&](const uint8_t* at) {                     // 8 consecutive k of this lane's row
+        if constexpr (P16) return *reinterpret_cast<const bf16x8*>(at);
+        else return weights_of(*reinterpret_cast<const words2*>(at), zf);
+    };
     const bool per_channel = lay.channel_len != 0;
     const uint32_t n_blocks = (p.n_pixels + kColsPerWave - 1u) / kColsPerWave;
     const uint32_t first_block = split * p.blocks_per_split;
@@ -297,8 +311,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                     if (base + d < n_steps) {
 #pragma unroll
                         for (uint32_t m = 0; m < MR; ++m) {
-                            const words2 aq = *reinterpret_cast<const words2*>(a_row + m * tile_stride + use.a_off + use.c0);
-                            const bf16x8 a = weights_of(aq, zf);
+                            const bf16x8 a = a_operand(a_row + m * tile_stride + (use.a_off + use.c0) * kElem);
 #pragma unroll
                             for (uint32_t q = 0; q < 4; ++q)
                                 acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
@@ -332,8 +345,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                                   uint32_t(bv[q][4]) | uint32_t(bv[q][5]) << 16, uint32_t(bv[q][6]) | uint32_t(bv[q][7]) << 16};
 #pragma unroll
                 for (uint32_t m = 0; m < MR; ++m) {
-                    const words2 aq = *reinterpret_cast<const words2*>(a_row + m * tile_stride + k0);
-                    const bf16x8 a = weights_of(aq, zf);
+                    const bf16x8 a = a_operand(a_row + m * tile_stride + k0 * kElem);
 #pragma unroll
                     for (uint32_t q = 0; q < 4; ++q)
                         acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[q]), acc[m][q], 0, 0, 0);
@@ -375,6 +387,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
 
 constexpr uint32_t kMaxK = 4608;           // reduction length whose 16-row panel (72 KiB) fits LDS beside the table
 constexpr uint32_t kLdsLimit = 160u * 1024u;
+constexpr uint32_t kMaxK16 = 576;          // up to here 64 rows fit as bf16 (73 KiB), and no conversion is left in the loop
 
 }  // namespace
 
@@ -402,8 +415,10 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     const uint32_t row_stride = ((uint32_t(K) + 31u) & ~31u) + kRowPad;
     const uint32_t table_bytes = (4u << a->table_log) < 16u ? 16u : (4u << a->table_log);
     const uint32_t fixed_bytes = table_bytes + kWaves * kStageWords * 4u + 64u;
+    const bool p16 = K <= kMaxK16;                              // short rows: the panel as bf16
+    const uint32_t elem = p16 ? 2u : 1u;
     uint32_t mr = 4;
-    while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride > kLdsLimit)) mr >>= 1;
+    while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride * elem > kLdsLimit)) mr >>= 1;
     const uint32_t n_mtiles = a->cout / (kRows * mr);
     if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y) | reinterpret_cast<uintptr_t>(a->payload) |
          reinterpret_cast<uintptr_t>(a->tables)) & 15u) return ANSZP_E_RANGE;
@@ -428,7 +443,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
     // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once
     // (one or two per CU, by LDS), each with at least one block of pixels per wavefront.
-    const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride;
+    const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride * elem;
     const uint32_t per_cu = 2u * lds_bytes <= kLdsLimit ? 2u : 1u;
     const uint32_t n_blocks = uint32_t((n_pixels + kColsPerWave - 1u) / kColsPerWave);
     uint32_t splits = (per_cu * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
@@ -441,16 +456,21 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     // (fixed_bytes counts 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row)
     const bool generic = (a->cin % 8u) != 0;
     void (*kernel)(ConvParams) = nullptr;
-    if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4> : mr == 2 ? conv_fused_kernel<true, 2> : conv_fused_kernel<true, 1>;
-    else kernel = mr == 4 ? conv_fused_kernel<false, 4> : mr == 2 ? conv_fused_kernel<false, 2> : conv_fused_kernel<false, 1>;
+    if (p16) {
+        if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4, true> : mr == 2 ? conv_fused_kernel<true, 2, true> : conv_fused_kernel<true, 1, true>;
+        else kernel = mr == 4 ? conv_fused_kernel<false, 4, true> : mr == 2 ? conv_fused_kernel<false, 2, true> : conv_fused_kernel<false, 1, true>;
+    } else {
+        if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4, false> : mr == 2 ? conv_fused_kernel<true, 2, false> : conv_fused_kernel<true, 1, false>;
+        else kernel = mr == 4 ? conv_fused_kernel<false, 4, false> : mr == 2 ? conv_fused_kernel<false, 2, false> : conv_fused_kernel<false, 1, false>;
+    }
     // the kernels may use all of the CU's LDS: said once per kernel and device
-    static bool lds_allowed[2][3][64] = {};
+    static bool lds_allowed[2][2][3][64] = {};
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
-    if (!lds_allowed[generic][slot][device]) {
+    if (!lds_allowed[p16][generic][slot][device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 int(kLdsLimit)) != hipSuccess) return ANSZP_E_HIP;
-        lds_allowed[generic][slot][device] = true;
+        lds_allowed[p16][generic][slot][device] = true;
     }
     hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
