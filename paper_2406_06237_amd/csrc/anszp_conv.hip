@@ -98,7 +98,7 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
 
     const uint32_t* words = p.payload + c.payload_offset;
     const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
-    const bool staged = word_limit <= kStageWords;
+    const bool staged = word_limit + 2u <= kStageWords;         // two zero words behind the chunk's own
     if (staged) {
         // all loads first (from clamped, always valid addresses; chunks start on 16 bytes), then the stores:
         // a load and its store under one condition would be waited for one after the other
@@ -116,18 +116,54 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
         for (uint32_t u = 0; u < kLoads; ++u)
             if (lane + u * kWave < quads) *reinterpret_cast<words4*>(stage + 4u * (lane + u * kWave)) = v[u];
         if (lane < 3u && tail_at < word_limit) stage[tail_at] = tail;
+        if (lane < 2u) stage[word_limit + lane] = 0u;                // what a stream reads beyond the chunk
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // LDS serves a wavefront's accesses in order
         __builtin_amdgcn_wave_barrier();
-        words = stage;
+    }
+    const uint32_t steps = (c.n_symbols + N - 1u) / N;
+    uint32_t row = lane / p.K, col = lane % p.K;      // of this lane's next symbol
+    const uint32_t row_step = N / p.K, col_step = N % p.K;
+    auto put = [&](uint32_t e) {                      // the entry's symbol into the panel, then on to the lane's next place
+        if constexpr (P16) {                          // an integer of at most 8 bits: the upper half of its binary32 form is exact
+            const float w = static_cast<float>(int32_t(e >> 24) - zero_point);
+            reinterpret_cast<uint16_t*>(rows)[row * p.row_stride + col] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
+        } else {
+            rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
+        }
+        row += row_step;
+        col += col_step;
+        if (col >= p.K) { col -= p.K; ++row; }
+    };
+    if (staged) {
+        // The chunk's words are in LDS: a lane keeps its bit position and reads the two words around it at every
+        // step, together with the table entry, so that a step is two LDS round trips' worth of latency and
+        // about two dozen instructions (the step's bits are stored most significant first: bit-reverse the
+        // window and take its top nb_bits).
+        uint32_t bit = first_word << 5;
+        for (uint32_t t = 0; t < steps; ++t) {
+            if (t < len) {
+                const uint32_t wi = min(bit >> 5, word_limit);
+                const uint32_t w0 = stage[wi], w1 = stage[wi + 1u];
+                const uint32_t e = table[X];
+                const uint32_t nb = min((e >> 16) & 0xFFu, 31u);
+                const uint32_t window = __builtin_amdgcn_alignbit(w1, w0, bit);
+                const uint32_t bits = (__brev(window) >> 1) >> (31u - nb);      // none: 0
+                X = ((e & 0xFFFFu) + bits) & (L - 1u);
+                bit += nb;
+                put(e);
+            }
+        }
+        if (lane < N) {
+            if (X != 0) err |= ANSZP_ST_BAD_STATE;
+            if (((bit - (first_word << 5)) + 31u) >> 5 != n_words) err |= ANSZP_ST_BAD_LENGTH;
+        }
+        return wave_or(err);
     }
     auto word_at = [&](uint32_t i) { return i < word_limit ? words[i] : 0u; };
     uint32_t next_word = first_word;
     uint64_t buf = 0;
     uint32_t have = 0;
     uint32_t ahead = word_at(first_word);             // the word after those in buf, requested one refill early
-    const uint32_t steps = (c.n_symbols + N - 1u) / N;
-    uint32_t row = lane / p.K, col = lane % p.K;      // of this lane's next symbol
-    const uint32_t row_step = N / p.K, col_step = N % p.K;
     for (uint32_t t = 0; t < steps; ++t) {
         if (t < len) {
             const uint32_t e = table[X];
@@ -143,15 +179,7 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk
             buf >>= nb;
             have -= nb;
             X = ((e & 0xFFFFu) + bits) & (L - 1u);
-            if constexpr (P16) {                     // an integer of at most 8 bits: the upper half of its binary32 form is exact
-                const float w = static_cast<float>(int32_t(e >> 24) - zero_point);
-                reinterpret_cast<uint16_t*>(rows)[row * p.row_stride + col] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
-            } else {
-                rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
-            }
-            row += row_step;
-            col += col_step;
-            if (col >= p.K) { col -= p.K; ++row; }
+            put(e);
         }
     }
     if (lane < N) {

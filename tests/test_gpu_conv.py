@@ -117,6 +117,28 @@ def test_many_pixels_several_splits(orc):
     _check(*_case(orc, (64, 32, 3, 3), 2, 40, 40, 1, 1, seed=9))
 
 
+def test_chunk_whose_words_exceed_the_staging_buffer(orc):
+    # a table that gives the layer's only symbol one state in 4096: every weight costs 12 bits, a chunk of one
+    # output channel (4608 weights) 1728 words, more than a wavefront stages on chip: decoded from global memory
+    shape, K = (16, 512, 3, 3), 4608
+    sym = np.ones(16 * K, dtype=np.uint8)
+    freqs = np.zeros(256, dtype=np.uint32)
+    freqs[0], freqs[1] = 4095, 1
+    c = orc.encode_layers([sym], 12, 64, K, freqs=[freqs])
+    assert int(c.chunk_payload_words.max()) > 1280
+    lay = W.Layer("rare", shape, 1, 0, 0.5, np.array([0.0, 1.0]), 0)
+    w = W.Workload("rare", [lay], 12, 64, K, "bf16")
+    d = B.to_device(host_from_oracle(c, w))
+    codes, values = W.bf16_activations(1 * 5 * 5 * 512, 21)
+    x = torch.from_numpy(codes.view(np.int16).reshape(1, 5, 5, 512)).to("cuda:0").view(torch.bfloat16)
+    y = B.conv_fused(d, 0, 0, 1, x, shape, 1, 1)
+    status = d.read_status()
+    x64 = values.astype(np.float64).reshape(1, 5, 5, 512)
+    wts = CO.dequantized_weights(sym, 0, 0.5, (16, 3, 3, 512))
+    _check(status, y.cpu().numpy().astype(np.float64), CO.conv2d_nhwc(x64, wts, 1, 1),
+           CO.conv2d_nhwc(np.abs(x64), np.abs(wts), 1, 1))
+
+
 def test_corrupt_stream_is_reported(orc):
     shape, K = (16, 32, 3, 3), 288
     rows = B.conv_rows_per_chunk(K)
