@@ -216,6 +216,12 @@ int anszp_dequant_zp(const uint8_t* symbols_dev, uint64_t n, const anszp_layer_t
                      const float* scales_dev, uint64_t n_scales, void* out_dev, int out_dtype,
                      void* hip_stream);
 
+/* activation layouts of anszp_conv_fused */
+#define ANSZP_ACT_NHWC        0     /* [batch][h][w][channels]                                    */
+#define ANSZP_ACT_C8          1     /* [batch][channels / 8][h][w][8]: blocks of 8 channels, so that
+                                       the 16 pixels a matrix instruction's operand rows come from
+                                       are 256 contiguous bytes; channels a multiple of 8          */
+
 /* Arguments of anszp_conv_fused (the struct itself is read on the host).  The container fields
  * mean what they mean in anszp_decode_args_t; `chunks` points at the FIRST chunk of the layer to
  * convolve with, `n_chunks` counts the chunks from there on. */
@@ -238,12 +244,15 @@ typedef struct {
     uint32_t             rows_per_chunk; /* output channels per chunk: 1, 2, 4, 8 or 16; every chunk
                                             holds rows_per_chunk * kh*kw*cin symbols              */
     uint32_t             batch, in_h, in_w, cin, cout, kh, kw, stride, pad;
-    const uint16_t*      x;              /* [device] bf16 activations [batch][in_h][in_w][cin], 16-byte aligned */
-    void*                y;              /* [device] [batch][out_h][out_w][cout] elements of y_dtype,
-                                            out = (in + 2 pad - k) / stride + 1, 16-byte aligned; every
-                                            element is written                                     */
+    const uint16_t*      x;              /* [device] bf16 activations in x_layout, batch * in_h * in_w * cin
+                                            elements (fewer than 2^32), 16-byte aligned            */
+    void*                y;              /* [device] batch * out_h * out_w * cout elements (fewer than 2^32)
+                                            of y_dtype in y_layout, out = (in + 2 pad - k) / stride + 1,
+                                            16-byte aligned; every element is written              */
     uint32_t             y_dtype;        /* ANSZP_OUT_F32, or ANSZP_OUT_BF16 (the fp32 result rounded
                                             to nearest even)                                      */
+    uint32_t             x_layout;       /* ANSZP_ACT_*; ANSZP_ACT_C8 needs cin to be a multiple of 8 */
+    uint32_t             y_layout;       /* ANSZP_ACT_*                                            */
     uint32_t*            status;         /* [device] 2 words, as for anszp_decode                 */
 } anszp_conv_args_t;
 

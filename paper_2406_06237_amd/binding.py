@@ -49,7 +49,8 @@ class ConvArgs(C.Structure):
                 ("rows_per_chunk", C.c_uint32), ("batch", C.c_uint32), ("in_h", C.c_uint32), ("in_w", C.c_uint32),
                 ("cin", C.c_uint32), ("cout", C.c_uint32), ("kh", C.c_uint32), ("kw", C.c_uint32),
                 ("stride", C.c_uint32), ("pad", C.c_uint32),
-                ("x", C.c_void_p), ("y", C.c_void_p), ("y_dtype", C.c_uint32), ("status", C.c_void_p)]
+                ("x", C.c_void_p), ("y", C.c_void_p), ("y_dtype", C.c_uint32), ("x_layout", C.c_uint32),
+                ("y_layout", C.c_uint32), ("status", C.c_void_p)]
 
 
 class AnszpError(RuntimeError):
@@ -395,19 +396,51 @@ def pack_conv_layers(layer_symbols: Sequence[np.ndarray], shapes: Sequence[tuple
     return h, [int(f) for f in first], rows
 
 
+ACT_NHWC, ACT_C8 = 0, 1
+ACT_CODES = {"nhwc": ACT_NHWC, "c8": ACT_C8}
+
+
+def to_c8(t):
+    """[batch][h][w][channels] -> [batch][channels / 8][h][w][8] (blocks of 8 channels), a copy."""
+    b, h, w, c = t.shape
+    return t.view(b, h, w, c // 8, 8).permute(0, 3, 1, 2, 4).contiguous()
+
+
+def from_c8(t):
+    """[batch][channels / 8][h][w][8] -> [batch][h][w][channels], a copy."""
+    b, cb, h, w, _ = t.shape
+    return t.permute(0, 2, 3, 1, 4).contiguous().view(b, h, w, cb * 8)
+
+
+def _act_dims(t, layout: str):
+    if layout == "c8":
+        b, cb, h, w, e = t.shape
+        if e != 8:
+            raise ValueError("a c8 tensor is [batch][channels / 8][h][w][8]")
+        return b, h, w, cb * 8
+    b, h, w, c = t.shape
+    return b, h, w, c
+
+
+def conv_out_shape(batch: int, out_h: int, out_w: int, cout: int, layout: str):
+    return (batch, cout // 8, out_h, out_w, 8) if layout == "c8" else (batch, out_h, out_w, cout)
+
+
 def conv_args(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
-              pad: int, y) -> ConvArgs:
-    """The argument struct of anszp_conv_fused for one layer: x a bf16 NHWC tensor, y an fp32 or bf16 NHWC
-    tensor, shape = (cout, cin, kh, kw)."""
+              pad: int, y, x_layout: str = "nhwc", y_layout: str = "nhwc") -> ConvArgs:
+    """The argument struct of anszp_conv_fused for one layer: x a bf16 tensor in x_layout, y an fp32 or bf16
+    tensor in y_layout ("nhwc": [batch][h][w][channels]; "c8": [batch][channels / 8][h][w][8]),
+    shape = (cout, cin, kh, kw)."""
     torch = _torch()
     h = d.host
     cout, cin, kh, kw = shape
-    B, H, W, cin_x = x.shape
+    B, H, W, cin_x = _act_dims(x, x_layout)
     ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     if x.dtype != torch.bfloat16 or not x.is_contiguous() or cin_x != cin:
-        raise ValueError("x must be a contiguous bf16 [batch][h][w][cin] tensor")
-    if y.dtype not in (torch.float32, torch.bfloat16) or not y.is_contiguous() or tuple(y.shape) != (B, ho, wo, cout):
-        raise ValueError("y must be a contiguous fp32 or bf16 [batch][out_h][out_w][cout] tensor")
+        raise ValueError("x must be a contiguous bf16 tensor with the layer's input channels")
+    if y.dtype not in (torch.float32, torch.bfloat16) or not y.is_contiguous() or \
+            tuple(y.shape) != conv_out_shape(B, ho, wo, cout, y_layout):
+        raise ValueError("y must be a contiguous fp32 or bf16 tensor of the output's shape in y_layout")
     a = ConvArgs()
     a.tables = d.tables.data_ptr(); a.n_tables = len(h.freqs); a.table_log = h.table_log
     a.n_streams = h.n_streams; a.layer_id = layer
@@ -419,6 +452,7 @@ def conv_args(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: 
     a.batch, a.in_h, a.in_w, a.cin, a.cout, a.kh, a.kw, a.stride, a.pad = B, H, W, cin, cout, kh, kw, stride, pad
     a.x = x.data_ptr(); a.y = y.data_ptr(); a.status = d.status.data_ptr()
     a.y_dtype = OUT_F32 if y.dtype == torch.float32 else OUT_BF16
+    a.x_layout = ACT_CODES[x_layout]; a.y_layout = ACT_CODES[y_layout]
     return a
 
 
@@ -430,16 +464,18 @@ def conv_fused_raw(args: ConvArgs, device="cuda:0"):
 
 
 def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk: int, x, shape: tuple, stride: int,
-               pad: int, y=None, y_dtype: str = "f32"):
-    """anszp_conv_fused on torch's current stream: x is a bf16 NHWC tensor, shape = (cout, cin, kh, kw);
-    returns y, NHWC, fp32 or bf16 (y_dtype, or the dtype of the y passed in)."""
+               pad: int, y=None, y_dtype: str = "f32", x_layout: str = "nhwc", y_layout: str = "nhwc"):
+    """anszp_conv_fused on torch's current stream: x is a bf16 tensor in x_layout, shape = (cout, cin, kh, kw);
+    returns y in y_layout, fp32 or bf16 (y_dtype, or the dtype of the y passed in)."""
     torch = _torch()
     cout, cin, kh, kw = shape
-    B, H, W, _ = x.shape
+    B, H, W, _ = _act_dims(x, x_layout)
     ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     if ho < 1 or wo < 1:
         raise AnszpError(-2, "anszp_conv_fused")
     if y is None:
-        y = torch.empty((B, ho, wo, cout), dtype=getattr(torch, _TORCH_OUT[y_dtype]), device=x.device)
-    conv_fused_raw(conv_args(d, layer, first_chunk, rows_per_chunk, x, shape, stride, pad, y), x.device)
+        if y_layout == "c8" and cout % 8:
+            raise AnszpError(-2, "anszp_conv_fused")
+        y = torch.empty(conv_out_shape(B, ho, wo, cout, y_layout), dtype=getattr(torch, _TORCH_OUT[y_dtype]), device=x.device)
+    conv_fused_raw(conv_args(d, layer, first_chunk, rows_per_chunk, x, shape, stride, pad, y, x_layout, y_layout), x.device)
     return y

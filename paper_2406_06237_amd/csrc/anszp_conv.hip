@@ -52,6 +52,11 @@ struct ConvParams {
     uint64_t n_stream_hdr, payload_words, n_scales;
     uint32_t layer_id, table_log, n_streams, rows_per_chunk, chunks_per_panel;
     uint32_t in_h, in_w, cin, cout, kh, kw, stride, pad, out_h, out_w;
+    // element strides that tell the two activation layouts apart (see anszp_conv_args_t):
+    //   x element (image b, pixel i, channel c) = b * in_h*in_w*cin + i * x_pixel + (c / 8) * x_block + c % 8
+    //   y element (image b, pixel i, channel o) = b * out_h*out_w*cout + i * y_pixel + (o / 8) * y_block + o % 8
+    // NHWC: pixel = channels, block = 8;  blocks of 8 channels: pixel = 8, block = 8 * pixels per image
+    uint32_t x_pixel, x_block, y_pixel, y_block;
     uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles, blocks_per_split;   // n_mtiles: panels of 16 * MR rows
 };
 
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         // B: lane holds column lane % 16 of each of the block's four column tiles
         uint32_t pix[4];
         int32_t h0[4], w0[4];
-        uint32_t img[4];
+        uint32_t img[4], out_at[4];                              // first element of the image in x; of the pixel in y
         bool valid[4];
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
@@ -283,7 +288,8 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             const uint32_t ho = t % p.out_h, b = t / p.out_h;
             h0[q] = int32_t(ho * p.stride) - int32_t(p.pad);
             w0[q] = int32_t(wo * p.stride) - int32_t(p.pad);
-            img[q] = b * p.in_h * p.in_w;
+            img[q] = b * p.in_h * p.in_w * p.cin;
+            out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
         }
         floatx4 acc[MR][4];
 #pragma unroll
@@ -313,8 +319,8 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 for (uint32_t q = 0; q < 4; ++q) {
                     const int32_t h = h0[q] + int32_t(c.r), w = w0[q] + int32_t(c.s);
                     tap_inside[q] = valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
-                    const uint32_t at = tap_inside[q] ? img[q] + uint32_t(h) * p.in_w + uint32_t(w) : 0u;
-                    tap_ptr[q] = p.x + uint64_t(at) * p.cin + 8u * kg;
+                    const uint32_t at = tap_inside[q] ? img[q] + (uint32_t(h) * p.in_w + uint32_t(w)) * p.x_pixel : 0u;
+                    tap_ptr[q] = p.x + at + kg * p.x_block;           // this lane's block of 8 channels of the step's first 32
                 }
             };
             auto load_step = [&](const Cursor& c, bool in_range, words4 (&b)[4]) {
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
 #pragma unroll
                 for (uint32_t q = 0; q < 4; ++q) {
                     b[q] = words4{0u, 0u, 0u, 0u};
-                    if (live && tap_inside[q]) b[q] = *reinterpret_cast<const words4*>(tap_ptr[q] + c.c0);
+                    if (live && tap_inside[q]) b[q] = *reinterpret_cast<const words4*>(tap_ptr[q] + (c.c0 >> 3) * p.x_block);
                 }
             };
             // a ring of kDepth steps' activation vectors: a step's slot is refilled, for the step kDepth
@@ -363,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                     for (uint32_t q = 0; q < 4; ++q) {
                         const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(s);
                         const bool inside = valid[q] && k < p.K && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
-                        bv[q][j] = inside ? p.x[uint64_t(img[q] + uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c] : uint16_t(0);
+                        bv[q][j] = inside ? p.x[img[q] + (uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c] : uint16_t(0);   // NHWC only
                     }
                 }
                 words4 b[4];
@@ -398,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             for (uint32_t q = 0; q < 4; ++q) {
                 if (valid[q]) {
                     const floatx4 out = {acc[m][q][0] * sc[0], acc[m][q][1] * sc[1], acc[m][q][2] * sc[2], acc[m][q][3] * sc[3]};
-                    const uint64_t at = uint64_t(pix[q]) * p.cout + o;
+                    const uint32_t at = out_at[q] + (o >> 3) * p.y_block + (o & 7u);
                     if (p.y_bf16) {                                   // round to nearest even (v_cvt_pk_bf16_f32)
                         typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
                         const bf16x4 r = {static_cast<__bf16>(out[0]), static_cast<__bf16>(out[1]),
@@ -437,6 +443,10 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     const uint32_t out_w = (a->in_w + 2u * a->pad - a->kw) / a->stride + 1u;
     const uint64_t n_pixels = uint64_t(a->batch) * out_h * out_w;
     if (n_pixels >= (1ull << 31) || uint64_t(a->batch) * a->in_h * a->in_w >= (1ull << 31)) return ANSZP_E_RANGE;
+    if (uint64_t(a->batch) * a->in_h * a->in_w * a->cin >= (1ull << 32) || n_pixels * a->cout >= (1ull << 32))
+        return ANSZP_E_RANGE;                                    // elements of x and y are addressed with 32 bits
+    if (a->x_layout > ANSZP_ACT_C8 || a->y_layout > ANSZP_ACT_C8) return ANSZP_E_RANGE;
+    if (a->x_layout == ANSZP_ACT_C8 && (a->cin % 8u) != 0) return ANSZP_E_RANGE;
     if (a->n_chunks < a->cout / R) return ANSZP_E_RANGE;
     // Row tiles per workgroup: as many of 4, 2, 1 as divide the output channels and leave the panel room in LDS
     // beside the table and the staging buffers (more rows per activation vector loaded).
@@ -460,6 +470,10 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     p.rows_per_chunk = R;
     p.in_h = a->in_h; p.in_w = a->in_w; p.cin = a->cin; p.cout = a->cout; p.kh = a->kh; p.kw = a->kw;
     p.stride = a->stride; p.pad = a->pad; p.out_h = out_h; p.out_w = out_w;
+    p.x_pixel = a->x_layout == ANSZP_ACT_C8 ? 8u : a->cin;
+    p.x_block = a->x_layout == ANSZP_ACT_C8 ? 8u * a->in_h * a->in_w : 8u;
+    p.y_pixel = a->y_layout == ANSZP_ACT_C8 ? 8u : a->cout;
+    p.y_block = a->y_layout == ANSZP_ACT_C8 ? 8u * out_h * out_w : 8u;
     p.K = uint32_t(K);
     p.row_stride = row_stride;
     p.chunks_per_panel = kRows * mr / R;

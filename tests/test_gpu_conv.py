@@ -24,7 +24,8 @@ def _layer(shape, bitwidth, p0, seed, scale=0.03125, channel_scales=None):
     return lay
 
 
-def _case(orc, shape, B_, H, Wd, stride, pad, bitwidth=4, p0=0.7, n_streams=64, table_log=12, seed=1, per_channel=False):
+def _case(orc, shape, B_, H, Wd, stride, pad, bitwidth=4, p0=0.7, n_streams=64, table_log=12, seed=1, per_channel=False,
+          x_layout="nhwc", y_layout="nhwc"):
     cout, cin, kh, kw = shape
     K = cin * kh * kw
     rows = B.conv_rows_per_chunk(K)
@@ -37,8 +38,12 @@ def _case(orc, shape, B_, H, Wd, stride, pad, bitwidth=4, p0=0.7, n_streams=64, 
     d = B.to_device(host_from_oracle(c, w))
     codes, values = W.bf16_activations(B_ * H * Wd * cin, seed + 100)
     x = torch.from_numpy(codes.view(np.int16).reshape(B_, H, Wd, cin)).to("cuda:0").view(torch.bfloat16)
-    y = B.conv_fused(d, 0, 0, rows, x, shape, stride, pad)
+    if x_layout == "c8":
+        x = B.to_c8(x)
+    y = B.conv_fused(d, 0, 0, rows, x, shape, stride, pad, x_layout=x_layout, y_layout=y_layout)
     status = d.read_status()
+    if y_layout == "c8":
+        y = B.from_c8(y)
     got = y.cpu().numpy().astype(np.float64)
 
     sym = lay.symbols().reshape(cout, kh, kw, cin)              # order [cout][kh][kw][cin]
@@ -112,6 +117,19 @@ def test_bf16_output_is_the_fp32_output_rounded(orc):
     assert np.max(np.abs(got - want)) <= 1e-2 * np.max(np.abs(want))
 
 
+@pytest.mark.parametrize("shape,B_,H,Wd,stride,pad", [
+    ((32, 64, 1, 1), 2, 9, 7, 1, 0), ((64, 32, 3, 3), 2, 10, 11, 1, 1), ((48, 64, 3, 3), 1, 13, 11, 2, 1),
+    ((32, 40, 3, 3), 1, 7, 7, 1, 1), ((16, 512, 3, 3), 1, 7, 7, 1, 1), ((64, 256, 3, 3), 2, 7, 7, 1, 1),
+])
+@pytest.mark.parametrize("x_layout,y_layout", [("c8", "c8"), ("nhwc", "c8"), ("c8", "nhwc")])
+def test_channel_blocked_layouts(orc, shape, B_, H, Wd, stride, pad, x_layout, y_layout):
+    _check(*_case(orc, shape, B_, H, Wd, stride, pad, x_layout=x_layout, y_layout=y_layout))
+
+
+def test_first_layer_reads_an_image_and_writes_channel_blocks(orc):
+    _check(*_case(orc, (64, 3, 7, 7), 2, 20, 20, 2, 3, y_layout="c8"))
+
+
 def test_many_pixels_several_splits(orc):
     # 2 * 40 * 40 = 3200 output pixels: 50 blocks of 64 spread over workgroups and wavefronts
     _check(*_case(orc, (64, 32, 3, 3), 2, 40, 40, 1, 1, seed=9))
@@ -165,6 +183,10 @@ def test_rejected_arguments(orc):
         B.conv_fused(d, 0, 0, 16, x, (24, 32, 1, 1), 1, 0)          # cout not a multiple of 16
     with pytest.raises(B.AnszpError):
         B.conv_fused(d, 0, 0, 3, x, (16, 32, 1, 1), 1, 0)           # rows per chunk must divide 16
+    a = B.conv_args(d, 0, 0, 16, x, (16, 32, 1, 1), 1, 0, torch.empty((1, 4, 4, 16), dtype=torch.float32, device="cuda:0"))
+    a.x_layout = 7
+    with pytest.raises(B.AnszpError):
+        B.conv_fused_raw(a)                                        # unknown layout
     with pytest.raises(B.AnszpError):
         B.conv_fused(d, 0, 0, 16, x, (16, 32, 5, 5), 1, 0)          # kernel larger than the padded image
     big = torch.zeros((1, 4, 4, 1024), dtype=torch.bfloat16, device="cuda:0")
