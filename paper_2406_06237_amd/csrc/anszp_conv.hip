@@ -8,15 +8,19 @@
 //   A[o, k] = q - z, the decoded symbol minus the layer's zero-point (Sec. II-B): an integer of at
 //   most 8 bits and therefore exact in bf16; the scale multiplies the fp32 sums at the end,
 //   B[k, n] = the bf16 activation under kernel tap (r, s) of output pixel n, zero outside the image.
-// Activations and outputs are NHWC, so the 8 consecutive k one lane feeds into an MFMA are 16
-// contiguous bytes of the activation tensor.
+// Activations and outputs are NHWC or in blocks of 8 channels ([batch][channels / 8][h][w][8]); in both
+// the 8 consecutive k one lane feeds into an MFMA are 16 contiguous bytes of the activation tensor.  In
+// the blocked layout the 16 lanes that hold the same 8 k of 16 neighbouring pixels read 256 contiguous
+// bytes, where NHWC makes them read 16 pieces a whole pixel apart.
 //
-// One workgroup owns 16 output channels (the M of v_mfma_f32_16x16x32_bf16) and a range of output
-// pixels.  Phase 1: its eight wavefronts decode the chunks that hold those 16 weight rows, one
-// symbol per look-up with one lane per stream (Sec. II-A, III-B), into a [16][K] byte panel in LDS.
-// Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column tiles): per 32 k it
-// reads 8 panel bytes per lane, converts them once, loads four 16-byte activation vectors and
-// issues four MFMAs.  fp32 accumulators, one 16-byte store per lane and column tile.
+// One workgroup owns a panel of 16 * MR output channels (MR = 4, 2 or 1 row tiles of
+// v_mfma_f32_16x16x32_bf16: as many as fit in LDS) and a range of output pixels.  Phase 1: its eight
+// wavefronts decode the chunks that hold those weight rows, one symbol per look-up with one lane per
+// stream (Sec. II-A, III-B), into a [16 * MR][K] panel in LDS: symbols as bytes, or, for short rows,
+// the bf16 values q - z.  Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column
+// tiles): per 32 k it reads the panel's 8 k per row tile (converting bytes once), loads four 16-byte
+// activation vectors and issues 4 * MR MFMAs.  fp32 accumulators; one store of four consecutive output
+// channels per lane, row tile and column tile.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
