@@ -487,10 +487,11 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     int device = 0, cus = 0;
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
-    // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once
-    // (one or two per CU, by LDS), each with at least one block of pixels per wavefront.
+    // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once,
+    // which is one per CU (eight wavefronts of more than 128 VGPRs fill a CU's four SIMDs whatever the LDS
+    // would allow), each with at least one block of pixels per wavefront.
     const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride * elem;
-    const uint32_t per_cu = 2u * lds_bytes <= kLdsLimit ? 2u : 1u;
+    const uint32_t per_cu = 1u;
     const uint32_t n_blocks = uint32_t((n_pixels + kColsPerWave - 1u) / kColsPerWave);
     uint32_t splits = (per_cu * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
     const uint32_t max_splits = (n_blocks + kWaves - 1u) / kWaves;
