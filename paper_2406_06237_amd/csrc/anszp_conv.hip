@@ -14,7 +14,7 @@
 // bytes, where NHWC makes them read 16 pieces a whole pixel apart.
 //
 // One workgroup owns a panel of 16 * MR output channels (MR = 4, 2 or 1 row tiles of
-// v_mfma_f32_16x16x32_bf16: as many as fit in LDS) and a range of output pixels.  Phase 1: its eight
+// v_mfma_f32_16x16x32_bf16: as many as fit in LDS) and a range of output pixels.  Phase 1: its twelve
 // wavefronts decode the chunks that hold those weight rows, one symbol per look-up with one lane per
 // stream (Sec. II-A, III-B), into a [16 * MR][K] panel in LDS: symbols as bytes, or, for short rows,
 // the bf16 values q - z.  Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column
@@ -30,7 +30,7 @@
 namespace {
 
 constexpr uint32_t kWave = 64;
-constexpr uint32_t kThreads = 512;
+constexpr uint32_t kThreads = 768;
 constexpr uint32_t kWaves = kThreads / kWave;
 constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
 constexpr uint32_t kColsPerWave = 64;       // output pixels a wavefront works on at a time: 4 MFMA column tiles
@@ -337,8 +337,10 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 }
             };
             // a ring of kDepth steps' activation vectors: a step's slot is refilled, for the step kDepth
-            // later, as soon as its MFMAs are issued
-            constexpr uint32_t kDepth = 8;
+            // later, as soon as its MFMAs are issued.  Two steps: a deeper ring buys nothing as long as the
+            // compiler waits for all outstanding loads before a step's MFMAs, and its registers are better
+            // spent on a third wavefront per SIMD.
+            constexpr uint32_t kDepth = 2;
             words4 ring[kDepth][4];
             Cursor ld{0u, 0u, 0u, 0u}, use{0u, 0u, 0u, 0u};
 #pragma unroll
@@ -488,7 +490,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
     // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once,
-    // which is one per CU (eight wavefronts of more than 128 VGPRs fill a CU's four SIMDs whatever the LDS
+    // which is one per CU (twelve wavefronts of more than 128 VGPRs fill a CU's four SIMDs whatever the LDS
     // would allow), each with at least one block of pixels per wavefront.
     const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride * elem;
     const uint32_t per_cu = 1u;
