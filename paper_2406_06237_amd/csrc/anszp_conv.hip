@@ -33,7 +33,6 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kThreads = 768;
 constexpr uint32_t kWaves = kThreads / kWave;
 constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
-constexpr uint32_t kColsPerWave = 64;       // output pixels a wavefront works on at a time: 4 MFMA column tiles
 constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
 constexpr uint32_t kStageWords = 1280;      // per wavefront: LDS room for one chunk's compressed words (a chunk of
                                             // 4608 8-bit symbols in 64 streams needs at most 1152 + 64)
@@ -61,7 +60,8 @@ struct ConvParams {
     //   y element (image b, pixel i, channel o) = b * out_h*out_w*cout + i * y_pixel + (o / 8) * y_block + o % 8
     // NHWC: pixel = channels, block = 8;  blocks of 8 channels: pixel = 8, block = 8 * pixels per image
     uint32_t x_pixel, x_block, y_pixel, y_block;
-    uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles, blocks_per_split;   // n_mtiles: panels of 16 * MR rows
+    uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles;   // n_mtiles: panels of 16 * MR rows
+    uint32_t pixels_per_split, block_pixels;              // multiples of 16: the pixels of a workgroup; of one block (<= 64)
 };
 
 __device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
@@ -211,12 +211,14 @@ __device__ __forceinline__ bf16x8 weights_of(words2 q, float z) {
     return __builtin_bit_cast(bf16x8, w);
 }
 
-// GENERIC: any number of input channels (every activation is addressed on its own); otherwise the
-// input channels are a multiple of 8 and a lane's 8 consecutive k lie under one kernel tap.
 // MR: MFMA row tiles per workgroup.  Every wavefront multiplies all 16 * MR panel rows with its columns, so
 // an activation vector loaded once feeds MR MFMAs.
 // P16: the panel is kept as bf16 (short rows: K <= 576), so that the contraction reads its A operands as they are.
-template <bool GENERIC, uint32_t MR, bool P16>
+// KIND: how the contraction addresses the activations.
+enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecutive k lie under one kernel tap
+       kPointwise = 1,   // as kTaps with a 1 x 1 kernel and no padding: one pixel per column, nothing outside the image
+       kGeneric = 2 };   // any number of input channels (NHWC): every activation is addressed on its own
+template <int KIND, uint32_t MR, bool P16>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint32_t* table = reinterpret_cast<uint32_t*>(lds);
@@ -272,12 +274,15 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         else return weights_of(*reinterpret_cast<const words2*>(at), zf);
     };
     const bool per_channel = lay.channel_len != 0;
-    const uint32_t n_blocks = (p.n_pixels + kColsPerWave - 1u) / kColsPerWave;
-    const uint32_t first_block = split * p.blocks_per_split;
-    const uint32_t end_block = min(first_block + p.blocks_per_split, n_blocks);
     const uint32_t Kp = (p.K + 31u) & ~31u;
+    // The workgroup's pixels are dealt out to its wavefronts in blocks of block_pixels, round robin, so that at
+    // any time the wavefronts work on neighbouring pixels (kernel taps of neighbours share input rows).  A block
+    // is 64 pixels unless the workgroup has fewer than 64 per wavefront: then it is narrower and the column
+    // tiles beyond it are switched off, rather than wavefronts left without work.
+    const uint32_t split_end = min((split + 1u) * p.pixels_per_split, p.n_pixels);
 
-    for (uint32_t blk = first_block + wave; blk < end_block; blk += kWaves) {
+    for (uint32_t pix0 = split * p.pixels_per_split + wave * p.block_pixels; pix0 < split_end; pix0 += kWaves * p.block_pixels) {
+        const uint32_t block_end = min(pix0 + p.block_pixels, split_end);
         // B: lane holds column lane % 16 of each of the block's four column tiles
         uint32_t pix[4];
         int32_t h0[4], w0[4];
@@ -285,8 +290,8 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         bool valid[4];
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
-            pix[q] = blk * kColsPerWave + q * 16u + col;
-            valid[q] = pix[q] < p.n_pixels;
+            pix[q] = pix0 + q * 16u + col;
+            valid[q] = pix[q] < block_end;
             const uint32_t n = valid[q] ? pix[q] : 0u;
             const uint32_t wo = n % p.out_w, t = n / p.out_w;
             const uint32_t ho = t % p.out_h, b = t / p.out_h;
@@ -301,7 +306,37 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        if constexpr (!GENERIC) {
+        if constexpr (KIND == kPointwise) {
+            // One pixel per column for the whole reduction: a step of 32 input channels is one address
+            // addition per column.  The next step's activation vectors are requested before this step's MFMAs.
+            const uint32_t n_steps = (p.cin + 31u) / 32u;
+            const uint16_t* px[4];
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q)
+                px[q] = p.x + (valid[q] ? img[q] + (uint32_t(h0[q]) * p.in_w + uint32_t(w0[q])) * p.x_pixel : 0u) + kg * p.x_block;
+            auto load_step = [&](uint32_t step, words4 (&b)[4]) {
+                const bool live = step < n_steps && step * 32u + 8u * kg < p.cin;   // the last step may be partly beyond the channels
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    b[q] = words4{0u, 0u, 0u, 0u};
+                    if (live && valid[q]) b[q] = *reinterpret_cast<const words4*>(px[q] + step * 4u * p.x_block);
+                }
+            };
+            words4 cur[4], nxt[4];
+            load_step(0u, cur);
+            for (uint32_t step = 0; step < n_steps; ++step) {
+                load_step(step + 1u, nxt);
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m) {
+                    const bf16x8 a = a_operand(a_row + m * tile_stride + step * 32u * kElem);
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q)
+                        acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, cur[q]), acc[m][q], 0, 0, 0);
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) cur[q] = nxt[q];
+            }
+        } else if constexpr (KIND == kTaps) {
             // Steps of 32 k: kernel taps outermost, 32 input channels at a time inside a tap.
             const uint32_t steps_per_tap = (p.cin + 31u) / 32u;
             const uint32_t n_steps = p.kh * p.kw * steps_per_tap;
@@ -491,35 +526,36 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return ANSZP_E_HIP;
     // Every workgroup decodes its panel once, so few, long-lived workgroups: as many as are resident at once,
     // which is one per CU (twelve wavefronts of more than 128 VGPRs fill a CU's four SIMDs whatever the LDS
-    // would allow), each with at least one block of pixels per wavefront.
+    // would allow).  A panel's pixels are dealt out in column tiles of 16, evenly over the workgroups that
+    // share the panel.
     const uint32_t lds_bytes = fixed_bytes + kRows * mr * row_stride * elem;
-    const uint32_t per_cu = 1u;
-    const uint32_t n_blocks = uint32_t((n_pixels + kColsPerWave - 1u) / kColsPerWave);
-    uint32_t splits = (per_cu * uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
-    const uint32_t max_splits = (n_blocks + kWaves - 1u) / kWaves;
-    if (splits > max_splits) splits = max_splits;
+    const uint32_t n_tiles = uint32_t((n_pixels + 15u) / 16u);
+    uint32_t splits = (uint32_t(cus > 0 ? cus : 256) + n_mtiles - 1u) / n_mtiles;
+    if (splits > n_tiles) splits = n_tiles;
     if (splits == 0) splits = 1;
-    p.blocks_per_split = (n_blocks + splits - 1u) / splits;
-    splits = (n_blocks + p.blocks_per_split - 1u) / p.blocks_per_split;
+    const uint32_t tiles_per_split = (n_tiles + splits - 1u) / splits;
+    splits = (n_tiles + tiles_per_split - 1u) / tiles_per_split;
+    p.pixels_per_split = 16u * tiles_per_split;
+    const uint32_t tiles_per_wave = (tiles_per_split + kWaves - 1u) / kWaves;
+    p.block_pixels = 16u * (tiles_per_wave < 4u ? tiles_per_wave : 4u);
 
     // (fixed_bytes counts 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row)
     const bool generic = (a->cin % 8u) != 0;
     void (*kernel)(ConvParams) = nullptr;
-    if (p16) {
-        if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4, true> : mr == 2 ? conv_fused_kernel<true, 2, true> : conv_fused_kernel<true, 1, true>;
-        else kernel = mr == 4 ? conv_fused_kernel<false, 4, true> : mr == 2 ? conv_fused_kernel<false, 2, true> : conv_fused_kernel<false, 1, true>;
-    } else {
-        if (generic) kernel = mr == 4 ? conv_fused_kernel<true, 4, false> : mr == 2 ? conv_fused_kernel<true, 2, false> : conv_fused_kernel<true, 1, false>;
-        else kernel = mr == 4 ? conv_fused_kernel<false, 4, false> : mr == 2 ? conv_fused_kernel<false, 2, false> : conv_fused_kernel<false, 1, false>;
-    }
+    const int kind = generic ? kGeneric : (a->kh == 1 && a->kw == 1 && a->pad == 0) ? kPointwise : kTaps;
+#define ANSZP_CONV_PICK(KIND)                                                                                          \
+    (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true> : mr == 2 ? conv_fused_kernel<KIND, 2, true> : conv_fused_kernel<KIND, 1, true>) \
+         : (mr == 4 ? conv_fused_kernel<KIND, 4, false> : mr == 2 ? conv_fused_kernel<KIND, 2, false> : conv_fused_kernel<KIND, 1, false>))
+    kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise) : ANSZP_CONV_PICK(kTaps);
+#undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device
-    static bool lds_allowed[2][2][3][64] = {};
+    static bool lds_allowed[2][3][3][64] = {};
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
-    if (!lds_allowed[p16][generic][slot][device]) {
+    if (!lds_allowed[p16][kind][slot][device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 int(kLdsLimit)) != hipSuccess) return ANSZP_E_HIP;
-        lds_allowed[p16][generic][slot][device] = true;
+        lds_allowed[p16][kind][slot][device] = true;
     }
     hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
