@@ -229,3 +229,31 @@ def test_stream_grouping_geometries():
     assert abs(streams["by channel"] / streams["benchmark"] - 1.0) < 0.06
     assert int(cs["by channel"].chunks["n_symbols"].max()) // 64 == 4608
     assert int(cs["benchmark"].chunks["n_symbols"].max()) // 64 == 1024
+
+
+def test_conv_packing_geometry():
+    """Host side of the fused decode + convolution path: chunks follow the rows of the GEMM panels."""
+    assert [B.conv_rows_per_chunk(k) for k in (64, 147, 256, 512, 576, 1024, 1152, 2048, 2304, 4608)] == \
+           [16, 16, 16, 8, 4, 4, 2, 2, 1, 1]
+    for k in (20, 64, 147, 576, 1152, 4608):
+        r = B.conv_rows_per_chunk(k)
+        assert 16 % r == 0 and (r == 1 or r * k <= 4096)
+    shapes = [(32, 16, 3, 3), (16, 64, 1, 1)]
+    rng = np.random.default_rng(3)
+    syms = [rng.integers(0, 4, size=int(np.prod(s))).astype(np.uint8) for s in shapes]
+    h, first, rows = B.pack_conv_layers(syms, shapes, 10, 64, [2, 2], [0.5, 0.25], [2, 2])
+    assert rows == [B.conv_rows_per_chunk(144), B.conv_rows_per_chunk(64)]
+    assert first == [0, 32 // rows[0]]
+    assert len(h.chunks) == 32 // rows[0] + 16 // rows[1]
+    assert list(h.chunks["n_symbols"][:first[1]]) == [rows[0] * 144] * first[1]
+    assert list(h.chunks["n_symbols"][first[1]:]) == [rows[1] * 64] * (16 // rows[1])
+    assert np.all(h.chunks["payload_offset"] % 4 == 0)
+    with pytest.raises(ValueError):
+        B.pack_conv_layers([syms[0][:-1]], [shapes[0]], 10, 64, [2], [0.5])
+    with pytest.raises(ValueError):
+        B.pack_conv_layers([np.zeros(24 * 16, np.uint8)], [(24, 16, 1, 1)], 10, 64, [0], [1.0])   # cout not a multiple of 16
+    geo = W.resnet50_conv_geometry()
+    assert len(geo) == 53 and geo[0][1:] == ((64, 3, 7, 7), 2, 3, 224)
+    assert all(co % 64 == 0 and ci * kh * kw <= 4608 for _, (co, ci, kh, kw), _, _, _ in geo)
+    macs = sum(co * ci * kh * kw * (((s + 2 * p - kh) // st + 1) ** 2) for _, (co, ci, kh, kw), st, p, s in geo)
+    assert macs == 4087136256                                  # multiply-adds per 224 x 224 image
