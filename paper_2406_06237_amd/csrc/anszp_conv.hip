@@ -257,7 +257,12 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         const bool ok = c.layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K && (c.payload_offset & 3u) == 0 &&
                         c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
                         uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
-        if (!ok) { err |= ANSZP_ST_BAD_DESC; continue; }
+        if (!ok) {                                               // rows of a rejected chunk: zeros (any bytes would do as symbols,
+            err |= ANSZP_ST_BAD_DESC;                            // but not as bf16 values)
+            uint32_t* rows32 = reinterpret_cast<uint32_t*>(panel + j * p.rows_per_chunk * p.row_stride * kElem);
+            for (uint32_t i = lane; i < p.rows_per_chunk * p.row_stride * kElem / 4u; i += kWave) rows32[i] = 0u;
+            continue;
+        }
         err |= decode_chunk_to_panel<P16>(p, c, table, stage + wave * kStageWords,
                                           panel + j * p.rows_per_chunk * p.row_stride * kElem, lane, int32_t(lay.zero_point));
     }

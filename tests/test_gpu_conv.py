@@ -174,6 +174,26 @@ def test_corrupt_stream_is_reported(orc):
     assert torch.isfinite(y).all()
 
 
+@pytest.mark.parametrize("shape", [(16, 32, 3, 3), (16, 256, 3, 3)])        # bf16 panel, byte panel
+@pytest.mark.parametrize("field,value", [("n_symbols", 17), ("layer_id", 1), ("payload_offset", 1 << 40),
+                                         ("payload_offset", 2), ("payload_words", 1 << 30), ("stream_offset", 0xFFFFFF00)])
+def test_chunk_descriptor_that_does_not_fit_is_skipped(orc, shape, field, value):
+    cout, cin, kh, kw = shape
+    K = cin * kh * kw
+    rows = B.conv_rows_per_chunk(K)
+    lay = _layer(shape, 4, 0.7, 31)
+    w = W.Workload("conv_case", [lay], 12, 64, rows * K, "bf16")
+    h = host_from_oracle(oracle_encode(orc, w), w)
+    h.chunks[field][len(h.chunks) - 1] = value
+    d = B.to_device(h)
+    codes, _ = W.bf16_activations(1 * 6 * 6 * cin, 32)
+    x = torch.from_numpy(codes.view(np.int16).reshape(1, 6, 6, cin)).to("cuda:0").view(torch.bfloat16)
+    y = B.conv_fused(d, 0, 0, rows, x, shape, 1, 1)
+    bits, count = d.read_status()
+    assert bits & B.ST_BAD_DESC and count >= 1
+    assert torch.isfinite(y).all()
+
+
 def test_rejected_arguments(orc):
     lay = _layer((16, 32, 1, 1), 4, 0.7, 5)
     w = W.Workload("conv_case", [lay], 12, 64, 16 * 32, "bf16")
