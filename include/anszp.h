@@ -71,7 +71,9 @@ extern "C" {
 #define ANSZP_ST_BAD_STATE    2u    /* a stream did not end in state 0                          */
 #define ANSZP_ST_BAD_LENGTH   4u    /* a stream read more or fewer words than its header says   */
 #define ANSZP_ST_INTERNAL     8u    /* a hand-over between wavefronts did not complete; chunk abandoned */
-#define ANSZP_ST_BAD_FREQ     16u   /* anszp_build_tables_device: a frequency row does not sum to 2^table_log */
+#define ANSZP_ST_BAD_FREQ     16u   /* anszp_build_tables_device, anszp_pack_layer_device: a frequency row does not sum to 2^table_log */
+#define ANSZP_ST_BAD_SYMBOL   32u   /* anszp_pack_layer_device: the data contain a symbol whose frequency is zero */
+#define ANSZP_ST_NO_SPACE     64u   /* anszp_pack_layer_device: payload buffer too small, or a stream longer than 65535 words */
 
 /* output element types */
 #define ANSZP_OUT_U8          0     /* decoded symbols, no dequantisation                       */
@@ -215,6 +217,25 @@ int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip
 int anszp_dequant_zp(const uint8_t* symbols_dev, uint64_t n, const anszp_layer_t* layer,
                      const float* scales_dev, uint64_t n_scales, void* out_dev, int out_dtype,
                      void* hip_stream);
+
+/* The packer on the GPU (Sec. II-A, the encoding direction: a stream's symbols are walked backwards,
+ * the state dropping low bits until the symbol's sub-range holds it): anszp_pack_layer for symbols and
+ * frequencies that live in device memory, writing the same descriptors, stream headers and payload
+ * words, word for word.  symbols_dev [device] n_symbols bytes; freqs_dev [device] 256 frequencies
+ * summing to 2^table_log; chunks_dev [device] ceil(n_symbols / chunk_size) descriptors, stream_hdr_dev
+ * [device] n_streams headers per chunk, payload_dev [device] payload_cap_words words where this layer's
+ * words begin (its chunks' payload_offset fields count from payload_word_offset, a multiple of 4);
+ * payload_words_used_dev [device] one 64-bit count; status_dev [device] 2 words as for anszp_decode.
+ * Asynchronous on hip_stream; three kernel launches, nothing allocated.  Errors: E_NULL, E_RANGE, E_HIP on
+ * the host; in status: ANSZP_ST_BAD_FREQ (nothing is written), ANSZP_ST_BAD_SYMBOL (the layer's output is
+ * unspecified), ANSZP_ST_NO_SPACE (chunks that do not fit are not written; *payload_words_used_dev still
+ * holds what the layer needs). */
+int anszp_pack_layer_device(const uint8_t* symbols_dev, uint64_t n_symbols, const uint32_t* freqs_dev,
+                            int table_log, int n_streams, uint32_t chunk_size, uint32_t layer_id,
+                            uint64_t out_offset, uint64_t payload_word_offset, uint32_t stream_offset,
+                            anszp_chunk_t* chunks_dev, uint32_t* stream_hdr_dev, uint32_t* payload_dev,
+                            uint64_t payload_cap_words, uint64_t* payload_words_used_dev,
+                            uint32_t* status_dev, void* hip_stream);
 
 /* activation layouts of anszp_conv_fused */
 #define ANSZP_ACT_NHWC        0     /* [batch][h][w][channels]                                    */

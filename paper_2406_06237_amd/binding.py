@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libanszp.so")
 
 OUT_U8, OUT_F32, OUT_BF16 = 0, 1, 2
 OUT_CODES = {"u8": OUT_U8, "f32": OUT_F32, "bf16": OUT_BF16}
-ST_BAD_DESC, ST_BAD_STATE, ST_BAD_LENGTH, ST_INTERNAL, ST_BAD_FREQ = 1, 2, 4, 8, 16
+ST_BAD_DESC, ST_BAD_STATE, ST_BAD_LENGTH, ST_INTERNAL, ST_BAD_FREQ, ST_BAD_SYMBOL, ST_NO_SPACE = 1, 2, 4, 8, 16, 32, 64
 MAX_TABLE_LOG, MAX_STREAMS, ALPHABET = 12, 64, 256
 
 CHUNK_DTYPE = np.dtype([("layer_id", "<u4"), ("n_symbols", "<u4"), ("out_offset", "<u8"),
@@ -62,7 +62,7 @@ class AnszpError(RuntimeError):
 _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
-           "anszp_dequant_zp", "anszp_conv_fused"]
+           "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device"]
 
 
 def lib():
@@ -93,6 +93,9 @@ def lib():
         L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
                                        C.c_void_p, C.c_int, C.c_void_p]
         L.anszp_conv_fused.argtypes = [C.POINTER(ConvArgs), C.c_void_p]
+        L.anszp_pack_layer_device.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int, C.c_int, C.c_uint32, C.c_uint32,
+                                              C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -479,3 +482,29 @@ def conv_fused(d: DeviceContainer, layer: int, first_chunk: int, rows_per_chunk:
         y = torch.empty(conv_out_shape(B, ho, wo, cout, y_layout), dtype=getattr(torch, _TORCH_OUT[y_dtype]), device=x.device)
     conv_fused_raw(conv_args(d, layer, first_chunk, rows_per_chunk, x, shape, stride, pad, y, x_layout, y_layout), x.device)
     return y
+
+
+# --------------------------------------------------------------------------- packing on the GPU
+def pack_layer_device(symbols_dev, freqs_dev, table_log: int, n_streams: int, chunk_size: int, layer_id: int = 0,
+                      out_offset: int = 0, payload_word_offset: int = 0, stream_offset: int = 0,
+                      payload_cap_words: Optional[int] = None):
+    """anszp_pack_layer_device on torch's current stream: symbols_dev a uint8 tensor, freqs_dev an int32 tensor of
+    256 frequencies, both on the GPU.  Returns (chunks, stream_hdr, payload, used, status) as device tensors
+    (chunks as raw bytes of anszp_chunk_t; used: one int64; status: two int32)."""
+    torch = _torch()
+    dev = symbols_dev.device
+    n = symbols_dev.numel()
+    nc = C.c_uint64(); bound = C.c_uint64()
+    _check(lib().anszp_pack_bound(n, table_log, n_streams, chunk_size, C.byref(nc), C.byref(bound)), "anszp_pack_bound")
+    cap = bound.value if payload_cap_words is None else payload_cap_words
+    chunks = torch.zeros(max(nc.value, 1) * CHUNK_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    hdr = torch.zeros(max(nc.value * n_streams, 4), dtype=torch.int32, device=dev)
+    payload = torch.full((max(cap, 4),), -1, dtype=torch.int32, device=dev)
+    used = torch.zeros(1, dtype=torch.int64, device=dev)
+    status = torch.zeros(2, dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib().anszp_pack_layer_device(symbols_dev.data_ptr(), n, freqs_dev.data_ptr(), table_log, n_streams, chunk_size,
+                                             layer_id, out_offset, payload_word_offset, stream_offset, chunks.data_ptr(),
+                                             hdr.data_ptr(), payload.data_ptr(), cap, used.data_ptr(), status.data_ptr(),
+                                             _stream_ptr(torch, dev)), "anszp_pack_layer_device")
+    return chunks, hdr, payload, used, status

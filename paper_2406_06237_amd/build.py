@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libanszp.so")
 SOURCES = [os.path.join(CSRC, "anszp_host.cpp"), os.path.join(CSRC, "anszp_device.hip"),
-           os.path.join(CSRC, "anszp_conv.hip")]
+           os.path.join(CSRC, "anszp_conv.hip"), os.path.join(CSRC, "anszp_encode.hip")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include")]
