@@ -122,27 +122,39 @@ def normalize_freqs(counts: np.ndarray, table_log: int) -> np.ndarray:
     return f
 
 
+TABLE_WORDS_PER_STATE = 8     # a table of L states occupies 8 L words (see anszp.h)
+
+
+def table_words(n_tables: int, table_log: int) -> int:
+    return (n_tables * TABLE_WORDS_PER_STATE) << table_log
+
+
 def build_tables_host(freqs: np.ndarray, table_log: int) -> np.ndarray:
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
-    size = len(freqs) << (max(0, min(table_log, 20)) + 2)
-    tables = np.zeros(size, dtype=np.uint32)
+    tables = np.zeros(table_words(len(freqs), max(0, min(table_log, 20))), dtype=np.uint32)
     _check(lib().anszp_build_tables_host(freqs.ctypes.data, len(freqs), table_log, tables.ctypes.data),
            "anszp_build_tables_host")
     return tables.reshape(len(freqs), -1)
 
 
 def split_table(tables: np.ndarray):
-    """Fields of a table (or stack of tables): the paper's triple per state and the look-ahead entries."""
+    """Fields of a table (or stack of tables): the byte table (tables of at most 256 states), the paper's
+    triple per state and the look-ahead entries."""
     t = np.asarray(tables, dtype=np.uint32)
-    L = t.shape[-1] // 4
-    la, lo = t[..., :2 * L], t[..., 2 * L:3 * L]
-    base = (la >> 18).astype(np.int32)
-    base = np.where(base >= 1 << 13, base - (1 << 14), base)
+    L = t.shape[-1] // TABLE_WORDS_PER_STATE
+    lo = t[..., 2 * L:3 * L]
+    la = t[..., 4 * L:8 * L]
+    first, second = la[..., 0::2], la[..., 1::2]
+    base8 = second.astype(np.int32)
     return {"newX": (lo & 0xFFFF).astype(np.uint16), "nb": ((lo >> 16) & 0xFF).astype(np.uint8),
             "sym": (lo >> 24).astype(np.uint8),
-            "la_bits": (31 - (la & 31)).astype(np.uint8), "la_pad": ((la >> 5) & 7).astype(np.uint8),
-            "la_sym": ((la >> 8) & 0xFF).astype(np.uint8), "la_count": (((la >> 16) & 3) + 1).astype(np.uint8),
-            "la_base": base, "tail": t[..., 3 * L:]}
+            "bytes": np.ascontiguousarray(t[..., :L]).view(np.uint8)[..., :3 * L],
+            "la_bits": ((first >> 16) & 15).astype(np.uint8), "la_shift": (first & 31).astype(np.uint8),
+            "la_pad": (((first >> 5) & 7) | (((first >> 11) & 31) << 3)).astype(np.uint8),
+            "la_sym": (first >> 24).astype(np.uint8), "la_count": (((first >> 20) & 7) + 1).astype(np.uint8),
+            "la_count_low": (((first >> 8) & 7) + 1).astype(np.uint8), "la_state0": ((first >> 23) & 1).astype(np.uint8),
+            "la_base": base8 // 8, "la_base_rem": base8 % 8,
+            "zero": np.concatenate([t[..., L:2 * L], t[..., 3 * L:4 * L]], axis=-1)}
 
 
 @dataclass
@@ -245,11 +257,11 @@ def _stream_ptr(torch, device):
 
 
 def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
-    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 4 * 2^table_log uint32)."""
+    """anszp_build_tables into a new device tensor (uint8 view of n_tables * 8 * 2^table_log uint32)."""
     torch = _torch()
     freqs = np.ascontiguousarray(freqs, dtype=np.uint32).reshape(-1, ALPHABET)
     with torch.cuda.device(device):
-        tables = torch.empty((len(freqs) << table_log) * 16, dtype=torch.uint8, device=device)
+        tables = torch.empty(table_words(len(freqs), table_log) * 4, dtype=torch.uint8, device=device)
         _check(lib().anszp_build_tables(freqs.ctypes.data, len(freqs), table_log, tables.data_ptr(),
                                         _stream_ptr(torch, device)), "anszp_build_tables")
     return tables
@@ -257,12 +269,12 @@ def build_tables(freqs: np.ndarray, table_log: int, device="cuda:0"):
 
 def build_tables_device(freqs_dev, table_log: int, status=None):
     """anszp_build_tables_device: freqs_dev is an int32/uint32-valued device tensor of n_tables x 256 entries;
-    returns the tables as a new device tensor (int32 view of n_tables * 4 * 2^table_log words)."""
+    returns the tables as a new device tensor (int32 view of n_tables * 8 * 2^table_log words)."""
     torch = _torch()
     device = freqs_dev.device
     n_tables = freqs_dev.numel() // ALPHABET
     with torch.cuda.device(device):
-        tables = torch.empty((n_tables << table_log) * 4, dtype=torch.int32, device=device)
+        tables = torch.empty(table_words(n_tables, table_log), dtype=torch.int32, device=device)
         _check(lib().anszp_build_tables_device(freqs_dev.data_ptr(), n_tables, table_log, tables.data_ptr(),
                                                status.data_ptr() if status is not None else None,
                                                _stream_ptr(torch, device)), "anszp_build_tables_device")

@@ -26,6 +26,7 @@
 #include <cstdint>
 
 #include "anszp.h"
+#include "anszp_layout.h"
 
 namespace {
 
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     const uint32_t L = 1u << p.table_log;
 
     // ---- phase 1: the layer's triples (Sec. II-A) into LDS, then this workgroup's 16 weight rows
-    const uint32_t* src = p.tables + (uint64_t(p.layer_id) << (p.table_log + 2)) + 2u * L;
+    const uint32_t* src = p.tables + p.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
     // every global read that depends only on the kernel's arguments is issued before any is waited for:
     // the table (two 16-byte rows per thread, clamped), the layer's quantizer, this wavefront's first chunk
     const uint32_t t_rows = L >> 2;

@@ -24,6 +24,7 @@
 // The look-ahead path needs the chunk's words to fit its LDS window and the chunk's first output
 // element to be 16-byte aligned; other chunks take the step-wise path inside the same launch.
 #include "anszp.h"
+#include "anszp_layout.h"
 
 #include <hip/hip_runtime.h>
 
@@ -34,21 +35,21 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 512;                    // 8 wavefronts stage, six of them stay for the decode
+constexpr int kBlock = 768;                    // twelve wavefronts stage, eight of them stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
-constexpr uint32_t kMaxMerged = 4u;             // symbols one look-ahead entry can stand for
-constexpr uint32_t kLogSlotBytes = 8u * kWave * 4u;
+constexpr uint32_t kLogSlotBytes = 9u * kWave * 2u + kWave * 4u;   // nine rows of 16 bits per lane, one of 32
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
-// LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states and leaves
-// room for two workgroups per CU; the small one (tables of up to 2^11 states, shorter windows) for three.
+// LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states (64 KiB of
+// look-ahead entries) and two chunks of a layer per workgroup, one workgroup per CU; the small one (tables
+// of up to 2^11 states, shorter windows) leaves room for two workgroups per CU.
 struct LargeLds {
-    static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 3584u, kRingElems = 16u * 1024u;
-    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 2u;
+    static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 4096u, kRingElems = 16u * 1024u;
+    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 1u;
 };
 struct SmallLds {
     static constexpr uint32_t kTableLog = 11u, kPayloadWords = 2048u, kRingElems = 8u * 1024u;
-    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 3u;
+    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 2u;
 };
 
 struct DecodeParams {
@@ -68,7 +69,24 @@ struct DecodeParams {
     uint32_t table_log;
     uint32_t n_streams;
     uint32_t n_cus;             // compute units of the device: workgroups n_cus apart tend to share one
+    uint32_t n_chunks;
 };
+
+// The chip hands consecutive workgroups to its eight dies (XCDs) in turn, and every die has an L2 of its
+// own.  Consecutive units of work (chunks, pairs of chunks) belong to one layer and read one table: with
+// workgroup b taking unit b, every die would fetch every large layer's table from memory (measured on
+// the ResNet-50-shaped set: 13.0 MB fetched per launch, 5.2 MB when a table is fetched by one or two dies).
+// So die x (workgroups b = x mod 8) takes groups of kDieGroup consecutive units, the groups dealt to the
+// dies in turn.  The launch is rounded up to whole rounds; workgroups that map beyond the last unit return.
+constexpr uint32_t kDies = 8u;
+constexpr uint32_t kDieGroup = 4u;
+__host__ __device__ __forceinline__ uint32_t mapped_workgroups(uint32_t n_units) {
+    return (n_units + kDies * kDieGroup - 1u) / (kDies * kDieGroup) * (kDies * kDieGroup);
+}
+__device__ __forceinline__ uint32_t unit_of_workgroup(uint32_t b) {
+    const uint32_t die = b % kDies, j = b / kDies;
+    return ((j / kDieGroup) * kDies + die) * kDieGroup + j % kDieGroup;
+}
 
 __device__ __forceinline__ uint32_t bf16_rne(float w) {
     uint32_t u = __float_as_uint(w);
@@ -210,7 +228,7 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
         return;
     }
-    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + (2u << p.table_log);   // the paper's triples
+    const uint32_t* src = p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log);   // the paper's triples
     for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = src[i];
     const anszp_layer_t lay = p.layers[c.layer_id];
     __syncthreads();
@@ -232,11 +250,11 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
     const uint32_t L = 1u << p.table_log;
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
     if (layer_a < p.n_tables) {
-        const uint32_t* src = p.tables + (uint64_t(layer_a) << (p.table_log + 2)) + 2u * L;    // the paper's triples
+        const uint32_t* src = p.tables + layer_a * table_stride_words(p.table_log) + table_triples_offset(p.table_log);    // the paper's triples
         for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[0][i] = src[i];
     }
     if (layer_b != layer_a && layer_b < p.n_tables) {
-        const uint32_t* src = p.tables + (uint64_t(layer_b) << (p.table_log + 2)) + 2u * L;
+        const uint32_t* src = p.tables + layer_b * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
         for (uint32_t i = tid; i < L; i += kSharedWaves * kWave) table[1][i] = src[i];
     }
     __syncthreads();
@@ -248,7 +266,7 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
     }
     const anszp_layer_t lay = p.layers[c.layer_id];
     const uint32_t* mine = c.layer_id == layer_a ? table[0] : c.layer_id == layer_b ? table[1]
-                           : p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L;
+                           : p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
     const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, mine, lane);
     if (err && lane == 0) report(p.status, err);
 }
@@ -359,8 +377,8 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     if (tid == 0) *gave_up = 0u;
 
     // the paper's triples of both tables, held in registers until the form of the entries is known
-    const uint32_t* src_a = p.tables + (uint64_t(have_a ? layer_a : 0u) << (p.table_log + 2)) + 2u * L;
-    const uint32_t* src_b = p.tables + (uint64_t(have_b ? layer_b : 0u) << (p.table_log + 2)) + 2u * L;
+    const uint32_t* src_a = p.tables + (have_a ? layer_a : 0u) * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
+    const uint32_t* src_b = p.tables + (have_b ? layer_b : 0u) * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
     constexpr uint32_t kNoTriple = 0x00010000u;           // reads one bit
     uint32_t ta0 = kNoTriple, ta1 = kNoTriple, ta2 = kNoTriple, ta3 = kNoTriple;
     uint32_t tb0 = kNoTriple, tb1 = kNoTriple, tb2 = kNoTriple, tb3 = kNoTriple;
@@ -549,7 +567,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     if (c.layer_id != layer_a && c.layer_id != layer_b) {
         // a third layer in one workgroup: the plain loop, table from global memory
         no_more_positions();
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + (uint64_t(c.layer_id) << (p.table_log + 2)) + 2u * L, lane);
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log), lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
@@ -856,521 +874,563 @@ struct Flusher {
     }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Which chunks a workgroup of the look-ahead kernel decodes.  Two consecutive chunks of one layer
+// (chunk numbers 2j and 2j+1) form a unit and share one workgroup and its LDS copy of the layer's
+// table; any other chunk is a unit of its own.  The host does not see the descriptors, so every
+// workgroup finds unit number `u` itself: thread t looks at chunks t, t + kBlock, ...; a 64-bit mask
+// per 64 chunks marks those that start a unit; the masks go through LDS and every wavefront picks
+// the u-th set bit.  Launches with more than kPairScanChunks chunks do not pair.
+constexpr uint32_t kPairScanRounds = 4u;
+struct Unit { uint32_t first, count; };          // count 0: no such unit
+
+template <uint32_t THREADS>
+__device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint64_t* masks /* LDS, kPairScanRounds * THREADS / 64 */) {
+    constexpr uint32_t kWaves = THREADS / kWave;
+    const uint32_t n = p.n_chunks;
+    if (n > kPairScanRounds * THREADS) return Unit{u, u < n ? 1u : 0u};
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = uniform(tid >> 6);
+    uint32_t mine[kPairScanRounds], before[kPairScanRounds];
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
+        const uint32_t i = k * THREADS + tid;
+        mine[k] = p.chunks[min(i, n - 1u)].layer_id;
+        before[k] = p.chunks[min(i ? i - 1u : 0u, n - 1u)].layer_id;
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
+        const uint32_t i = k * THREADS + tid;
+        const bool second = (i & 1u) && mine[k] == before[k];
+        const uint64_t starts = __ballot(i < n && !second);
+        if (lane == 0) masks[k * kWaves + wave] = starts;
+    }
+    __syncthreads();
+    // every wavefront on its own: lane m holds mask m
+    constexpr uint32_t kMasks = kPairScanRounds * kWaves;
+    static_assert(kMasks <= kWave, "one mask per lane");
+    const uint64_t m = lane < kMasks ? masks[lane] : 0ull;
+    uint32_t total;
+    const uint32_t ahead = wave_exclusive_sum(static_cast<uint32_t>(__popcll(m)), &total);
+    if (u >= total) return Unit{0u, 0u};
+    const uint64_t holds = __ballot(lane < kMasks && ahead <= u && u < ahead + static_cast<uint32_t>(__popcll(m)));
+    const uint32_t which = static_cast<uint32_t>(__ffsll(static_cast<unsigned long long>(holds))) - 1u;   // exactly one lane
+    const uint32_t lo = __shfl(static_cast<uint32_t>(m), which, kWave), hi = __shfl(static_cast<uint32_t>(m >> 32), which, kWave);
+    const uint32_t rank = u - __shfl(ahead, which, kWave);            // the rank-th set bit of that mask
+    const uint32_t below = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));   // set bits below this lane's
+    const uint64_t mask = (uint64_t(hi) << 32) | lo;
+    const uint64_t found = __ballot(((mask >> lane) & 1ull) && below == rank);
+    const uint32_t first = which * kWave + static_cast<uint32_t>(__ffsll(static_cast<unsigned long long>(found))) - 1u;
+    // the chunk after it belongs to the unit when it starts none
+    uint32_t count = 1u;
+    if (first + 1u < n) {
+        const uint32_t next = first + 1u;
+        const uint32_t nlo = __shfl(static_cast<uint32_t>(m), next / kWave, kWave), nhi = __shfl(static_cast<uint32_t>(m >> 32), next / kWave, kWave);
+        const uint64_t next_mask = (uint64_t(nhi) << 32) | nlo;
+        if (!((next_mask >> (next % kWave)) & 1ull)) count = 2u;
+    }
+    return Unit{uniform(first), uniform(count)};
+}
+
+// ---------------------------------------------------------------------------------------------
+// The look-ahead kernel.  One workgroup = one unit (one or two chunks of a layer), twelve wavefronts:
+// all stage, then eight keep a task each, four per chunk:
+//   decode   lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
+//            table) through the look-ahead entries, in blocks of 8 look-ups with no per-step checks,
+//            and logs 16 bits of every entry it passes;
+//   expand   turns logged entries into symbols in the chunk's LDS ring (an entry stands for c symbols:
+//            c-1 copies of the dominant symbol, which the ring holds as background, then its own),
+//            publishes how far every stream has got, and checks every stream's end: the entry that
+//            holds the stream's last symbol must end with it and arrive in state 0 (entries never pass
+//            through state 0), having read the stream's words and no more;
+//   store x2 move finished slabs of the ring to global memory, even and odd slabs, 16 bytes per lane.
+// A lane joins a block while its stream is unfinished and the ring has room for 8 entries of 8 symbols
+// (what the storing wavefronts have stored decides); a stream that ends inside a block goes on through
+// whatever follows it: the table keeps every index in range, the window of compressed words is
+// clamped to the chunk, and symbols beyond the chunk's last land in ring slots nobody reads again.
+// Hand-overs go through LDS words; LDS performs a wavefront's accesses in order, so a reader that
+// sees a count sees everything written before it.  Every wait is bounded.
 template <int OUT, bool PER_CHANNEL, class G>
 __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
-    constexpr uint32_t kTableBytes = 8u << G::kTableLog;           // two look-ahead entries of 4 bytes per state
-    constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each)
+    constexpr uint32_t kTableBytes = 16u << G::kTableLog;          // 2 L entries of 8 bytes
+    constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each), per chunk
     constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
-    constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks of look-ups in flight between two wavefronts
-    // One LDS block carved by hand.  The compressed words sit at offset 0 (their two-dword reads have no
-    // room for a large immediate offset); everything the hand-scheduled look-up addresses with an
-    // immediate offset lies below 64 KiB.
+    constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks in flight between decoding and expanding wavefront
+    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: words, hand-over words, block headers, positions, log
+    constexpr uint32_t kRingOff = kTableBytes;
+    constexpr uint32_t kLutOff = kRingOff + 2u * kRingElems;
+    constexpr uint32_t kPipeOff = kLutOff + 512u;
     constexpr uint32_t kWordsBytes = (kPayloadWords + 8u) * 4u;
-    constexpr uint32_t kCtlOff = kWordsBytes;                       // hand-over words, then block headers
+    constexpr uint32_t kCtlOff = kWordsBytes;                       // within a chunk's area
     constexpr uint32_t kHdrOff = kCtlOff + 64u;
-    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 16u;        // per lane: chunk index of the next symbol to expand
-    constexpr uint32_t kSimdOff = kProgOff + kWave * 4u;            // SIMD each of the first 8 wavefronts runs on
-    constexpr uint32_t kTableOff = kSimdOff + 32u;                  // 2L look-ahead entries, later the L triples
-    constexpr uint32_t kLutOff = kTableOff + kTableBytes;           // symbol -> bf16 weight
-    constexpr uint32_t kRingOff = kLutOff + 512u;
-    constexpr uint32_t kLogOff = kRingOff + kRingElems;             // logged entries: [slot][look-up][lane]
-    constexpr uint32_t kLdsBytes = kLogOff + kLogSlots * kLogSlotBytes;
-    static_assert(kTableOff % 16u == 0 && kRingOff % 16u == 0 && kCtlOff % 16u == 0 && kHdrOff % 16u == 0 &&
-                  kRingOff < 65536u && kLogSlotBytes == 16u << 7, "LDS layout");
+    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 8u;
+    constexpr uint32_t kLogOff = kProgOff + kWave * 4u;
+    constexpr uint32_t kPipeBytes = kLogOff + kLogSlots * kLogSlotBytes;
+    constexpr uint32_t kLdsBytes = kPipeOff + 2u * kPipeBytes;
+    static_assert(kTableBytes % kRingElems == 0u && (kRingElems & (kRingElems - 1u)) == 0u, "rings aligned to their size");
+    static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u && kHdrOff % 8u == 0u, "LDS layout");
+    static_assert(kRingElems >= 2u * 8u * kLookaheadMaxSymbols * kWave && kRingElems % kSlab == 0u, "a lane may run a block ahead of a full slab");
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
+    static_assert(kLdsBytes * 8u < (1u << 22), "bit positions count from the start of LDS");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
-    uint32_t* const lds_words = reinterpret_cast<uint32_t*>(lds);
-    uint32_t* const lds_table = reinterpret_cast<uint32_t*>(lds + kTableOff);
     uint16_t* const lds_lut = reinterpret_cast<uint16_t*>(lds + kLutOff);
-    uint8_t* const ring8 = lds + kRingOff;
-    // hand-over words: 0 blocks logged by the decoding wavefront | 1 blocks expanded | 2, 3 first element of
-    // the next slab each storing wavefront will take | 4 the block phase is over | 5 a wait gave up |
-    // 6, 7 a storing wavefront has stored all it can | 8, 9 lower, upper half of the triples are in LDS
-    lds_flag_t* const ctl = (lds_flag_t*)(lds + kCtlOff);
-    // (block headers at kHdrOff, written and read by the assembly below: lanes lo, lanes hi, look-ups, -)
-    enum { kLogged = 0, kExpanded = 1, kStored0 = 2, kStored1 = 3, kOver = 4, kGaveUp = 5, kStoreDone0 = 6, kStoreDone1 = 7,
-           kTriplesLo = 8, kTriplesHi = 9 };
+    // hand-over words of a chunk: 0 blocks logged | 1 blocks expanded | 2, 3 first element of the next slab
+    // each storing wavefront will take | 4 no more blocks will be logged | 5 a wait gave up
+    enum { kLogged = 0, kExpanded = 1, kStored0 = 2, kStored1 = 3, kOver = 4, kGaveUp = 5 };
     constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
-    constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 4u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
-    constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;
-    constexpr uint32_t kTripleLoads = (1u << ANSZP_MAX_TABLE_LOG) / 4u / kWave;                   // per lane of one wavefront
+    constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 2u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
+    constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;                  // per chunk
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1);
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wave = uniform(tid >> 6);
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
-    const anszp_chunk_t c = p.chunks[blockIdx.x];
-    if (!chunk_in_bounds(p, c)) {
-        if (tid == 0) report(p.status, ANSZP_ST_BAD_DESC);
-        return;
+
+    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), reinterpret_cast<uint64_t*>(lds + kPipeOff));
+    if (unit.count == 0u) return;
+    // descriptors (the second repeats the first when the unit is a single chunk)
+    const anszp_chunk_t c0 = p.chunks[unit.first], c1 = p.chunks[unit.first + unit.count - 1u];
+    const bool in0 = chunk_in_bounds(p, c0), in1 = unit.count == 2u && chunk_in_bounds(p, c1);
+    if (tid == 0) {
+        if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
+        if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
+        if (lds_address(lds) != 0u) report(p.status, ANSZP_ST_INTERNAL);       // the hand-written parts address LDS from 0
     }
-    // Issue every global read that depends only on the descriptor before waiting for any of them:
-    // stream headers, the look-ahead half of the layer's table, the chunk's compressed words (from
-    // clamped, always valid indices) and the layer's quantizer.
-    const uint32_t hdr = (wave < 8u && lane < N) ? p.stream_hdr[c.stream_offset + lane] : 0u;   // any of them may decode
-    const uint32_t* src = p.tables + (uint64_t(c.layer_id) << (p.table_log + 2));
-    const uint4* tsrc = reinterpret_cast<const uint4*>(src);                  // look-ahead entries, 4 per load
-    const uint4* wsrc = reinterpret_cast<const uint4*>(p.payload + c.payload_offset);
-    const uint32_t quads = min(c.payload_words, kPayloadWords) >> 2;
-    const bool wide = L >= 4;                                                 // a 2-state table has no 16-byte row of triples
-    // (named values rather than arrays: an array that lives across a barrier is kept in scratch
-    // memory by the compiler)
-    static_assert(kTableLoads <= 4u && kWordLoads <= 2u, "loads per thread are written out below (clamped when fewer)");
-    const uint32_t t_last = (L >> 1) - 1u;
-    const uint32_t w_last = quads ? quads - 1u : 0u;
-    const uint4* wsafe = quads ? wsrc : tsrc;
-    const uint4 tv0 = tsrc[min(tid, t_last)], tv1 = tsrc[min(tid + kBlock, t_last)];
-    const uint4 tv2 = tsrc[min(tid + 2u * kBlock, t_last)], tv3 = tsrc[min(tid + 3u * kBlock, t_last)];
-    const uint4 wv0 = wsafe[min(tid, w_last)], wv1 = wsafe[min(tid + kBlock, w_last)];
-    uint32_t tail = 0;
-    if (tid < 8 && (quads << 2) + tid < c.payload_words && c.payload_words <= kPayloadWords)
-        tail = p.payload[c.payload_offset + (quads << 2) + tid];
-    const uint32_t top = src[3u * L - 1u];               // state L-1 carries the dominant symbol if there is one
-    const anszp_layer_t lay = p.layers[c.layer_id];
-    // While those loads are in flight: which wavefront does what, and where each stream's words begin.
-    if (lane == 0 && wave < 8u)                          // HW_ID bits 4..5: the SIMD this wavefront runs on
-        reinterpret_cast<uint32_t*>(lds + kSimdOff)[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
+    if ((!in0 && !in1) || lds_address(lds) != 0u) return;
+    const uint32_t layer_id = in0 ? c0.layer_id : c1.layer_id;      // both alike when both are in bounds
+
+    // Issue every global read that depends only on the descriptors before waiting for any of them.
+    const uint32_t* src = p.tables + layer_id * table_stride_words(p.table_log);
+    const uint4* tsrc = reinterpret_cast<const uint4*>(src + table_lookahead_offset(p.table_log));   // 2 entries per load
+    const uint32_t t_last = L - 1u;
+    // (named values rather than arrays: an array that lives across a barrier is kept in scratch memory
+    // by the compiler; loads beyond the geometry's count repeat the last row and are dropped)
+    static_assert(kTableLoads <= 6u && kWordLoads <= 2u, "loads per thread are written out below");
+    const uint4 tv0 = tsrc[min(tid, t_last)], tv1 = tsrc[min(tid + kBlock, t_last)], tv2 = tsrc[min(tid + 2u * kBlock, t_last)];
+    uint4 tv3 = tv2, tv4 = tv2, tv5 = tv2;
+    if constexpr (kTableLoads > 3u) {
+        tv3 = tsrc[min(tid + 3u * kBlock, t_last)]; tv4 = tsrc[min(tid + 4u * kBlock, t_last)]; tv5 = tsrc[min(tid + 5u * kBlock, t_last)];
+    }
+    const uint32_t hdr0 = (in0 && lane < N) ? p.stream_hdr[c0.stream_offset + lane] : 0u;
+    const uint32_t hdr1 = (in1 && lane < N) ? p.stream_hdr[c1.stream_offset + lane] : 0u;
+    const uint32_t quads0 = in0 ? min(c0.payload_words, kPayloadWords) >> 2 : 0u;
+    const uint32_t quads1 = in1 ? min(c1.payload_words, kPayloadWords) >> 2 : 0u;
+    const uint4* wsrc0 = quads0 ? reinterpret_cast<const uint4*>(p.payload + c0.payload_offset) : tsrc;
+    const uint4* wsrc1 = quads1 ? reinterpret_cast<const uint4*>(p.payload + c1.payload_offset) : tsrc;
+    const uint32_t w_last0 = quads0 ? quads0 - 1u : 0u, w_last1 = quads1 ? quads1 - 1u : 0u;
+    const uint4 wv00 = wsrc0[min(tid, w_last0)], wv10 = wsrc1[min(tid, w_last1)];
+    uint4 wv01 = wv00, wv11 = wv10;
+    if constexpr (kWordLoads > 1u) { wv01 = wsrc0[min(tid + kBlock, w_last0)]; wv11 = wsrc1[min(tid + kBlock, w_last1)]; }
+    uint32_t tail0 = 0, tail1 = 0;                        // the words behind the last whole row of four
+    if (in0 && tid < 8 && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= kPayloadWords)
+        tail0 = p.payload[c0.payload_offset + (quads0 << 2) + tid];
+    if (in1 && tid < 8 && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
+        tail1 = p.payload[c1.payload_offset + (quads1 << 2) + tid];
+    const uint32_t top = src[table_triples_offset(p.table_log) + L - 1u];   // state L-1 carries the dominant symbol if there is one
+    const anszp_layer_t lay = p.layers[layer_id];
+    // While those loads are in flight: the SIMD every wavefront runs on (HW_ID bits 4..5).
+    uint32_t* const simd_of = reinterpret_cast<uint32_t*>(lds + kLutOff);      // (the symbol table is written after the barrier)
+    if (lane == 0) simd_of[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
     __syncthreads();
-    // Six wavefronts stay, each with one task; the others were staging helpers.  A lone wavefront's
-    // speed is set by how often its SIMD lets it issue, so the tasks are spread over the CU's four
-    // SIMDs, and two workgroups that share a CU (workgroups n_cus apart, as a rule) pick different
-    // SIMDs for their decoding wavefronts, which then have a SIMD each to themselves but for a
-    // sleeper:  SIMD 0/1 decode | 2/3 expand | 2 first storer | 3 second storer; the two placing
-    // wavefronts sleep until the end.
-    enum { kDecode = 0, kExpand = 1, kStore0 = 2, kStore1 = 3, kPlaceLo = 4, kPlaceHi = 5, kNoTask = 6 };
-    uint32_t task = kNoTask;
+    // Tasks.  A lone wavefront's speed is set by how often its SIMD lets it issue, so the two decoding
+    // wavefronts get a SIMD each that they share with nothing but wavefronts that leave after staging;
+    // expanding and storing wavefronts share the other two.  The second workgroup of a CU (small
+    // geometry) mirrors the choice.
+    enum { kDecode = 0, kExpand = 1, kStore0 = 2, kStore1 = 3, kNoTask = 4 };
+    uint32_t task = kNoTask, pipe = 0;
     {
-        const uint32_t turn = (blockIdx.x / max(p.n_cus, 1u)) % G::kWorkgroupsPerCu;
-        const uint32_t want[6] = {turn, turn < 2u ? 2u + turn : 3u, turn < 2u ? 2u : 0u, turn < 2u ? 3u : 1u,
-                                  turn < 2u ? 1u - turn : 3u, turn < 2u ? 3u - turn : 3u};
-        const uint32_t mine = reinterpret_cast<const uint32_t*>(lds + kSimdOff)[lane & 7u];   // one read, eight answers
-        uint32_t simd[8];
+        constexpr uint32_t kWaves = kBlock / kWave;
+        const uint32_t flip = G::kWorkgroupsPerCu > 1u ? ((blockIdx.x / max(p.n_cus, 1u)) & 1u) * 2u : 0u;
+        //                         decode 0, decode 1, expand 0, expand 1, store 0/0, store 1/0, store 0/1, store 1/1
+        const uint32_t want[8] = {0u ^ flip, 1u ^ flip, 2u ^ flip, 3u ^ flip, 2u ^ flip, 3u ^ flip, 3u ^ flip, 2u ^ flip};
+        const uint32_t role_task[8] = {kDecode, kDecode, kExpand, kExpand, kStore0, kStore1, kStore0, kStore1};
+        const uint32_t role_pipe[8] = {0u, 1u, 0u, 1u, 0u, 0u, 1u, 1u};
+        const uint32_t mine = simd_of[lane % kWaves];
+        uint32_t simd[kWaves];
 #pragma unroll
-        for (uint32_t w = 0; w < 8u; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
+        for (uint32_t w = 0; w < kWaves; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
         uint32_t taken = 0;
 #pragma unroll
-        for (uint32_t t = 0; t < 6u; ++t) {
-            uint32_t pick = 8u;
+        for (uint32_t r = 0; r < 8u; ++r) {
+            uint32_t pick = kWaves;
 #pragma unroll
-            for (uint32_t w = 0; w < 8u; ++w)
-                if (pick == 8u && !((taken >> w) & 1u) && simd[w] == want[t]) pick = w;
+            for (uint32_t w = 0; w < kWaves; ++w)
+                if (pick == kWaves && !((taken >> w) & 1u) && simd[w] == want[r]) pick = w;
 #pragma unroll
-            for (uint32_t w = 0; w < 8u; ++w)          // no wavefront on that SIMD: any free one
-                if (pick == 8u && !((taken >> w) & 1u)) pick = w;
+            for (uint32_t w = 0; w < kWaves; ++w)          // no wavefront on that SIMD: any free one
+                if (pick == kWaves && !((taken >> w) & 1u)) pick = w;
             taken |= 1u << pick;
-            if (pick == wave) task = t;
+            if (pick == wave) { task = role_task[r]; pipe = role_pipe[r]; }
         }
     }
-    const uint32_t n_words = hdr >> 16;
-    uint32_t total_words = 0, first_word = 0;
-    if (task == kDecode) first_word = wave_exclusive_sum(n_words, &total_words);
-    const uint64_t layer_elem0 = c.out_offset - lay.out_base;
-    const uint32_t n = c.n_symbols;
-    const bool merged_ok = wide && p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords &&
-                           ((c.out_offset * kElemBytes) & 15u) == 0 && n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
-                           (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
+    pipe = uniform(pipe);
+    task = uniform(task);
+    __syncthreads();                                      // simd_of is read; its place becomes the symbol table
 
-    if (!merged_ok) {                                     // whole workgroup agrees
-        for (uint32_t i = tid; i < L; i += kBlock) lds_table[i] = src[2u * L + i];
-        __syncthreads();
-        if (wave != 0) return;
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, lds_table, lane);
-        if (err && lane == 0) report(p.status, err);
-        return;
-    }
-
-    // ---- stage: look-ahead entries, compressed words, symbol -> code, ring background, hand-over words
+    // ---- stage: look-ahead entries, both chunks' compressed words, symbol -> bf16, ring background, hand-over words
     {
         // every thread stores what it loaded, to the clamped index it loaded from (threads past the
-        // end repeat the last row): stores under a per-thread condition would let the compiler move
-        // each load down to its store and wait for them one at a time
-        uint4* tdst = reinterpret_cast<uint4*>(lds_table);
+        // end repeat the last row)
+        uint4* tdst = reinterpret_cast<uint4*>(lds);
         tdst[min(tid, t_last)] = tv0;
         tdst[min(tid + kBlock, t_last)] = tv1;
         tdst[min(tid + 2u * kBlock, t_last)] = tv2;
-        tdst[min(tid + 3u * kBlock, t_last)] = tv3;
-        uint4* wdst = reinterpret_cast<uint4*>(quads ? lds : lds + kLogOff);     // no whole row of words: anywhere unused
-        wdst[min(tid, w_last)] = wv0;
-        wdst[min(tid + kBlock, w_last)] = wv1;
-        if (tid < 8) lds_words[(quads << 2) + tid] = tail;      // tail words, then zeros for clamped reads
+        if constexpr (kTableLoads > 3u) {
+            tdst[min(tid + 3u * kBlock, t_last)] = tv3;
+            tdst[min(tid + 4u * kBlock, t_last)] = tv4;
+            tdst[min(tid + 5u * kBlock, t_last)] = tv5;
+        }
+        uint4* wdst0 = reinterpret_cast<uint4*>(lds + kPipeOff);
+        uint4* wdst1 = reinterpret_cast<uint4*>(lds + kPipeOff + kPipeBytes);
+        if (quads0) { wdst0[min(tid, w_last0)] = wv00; if constexpr (kWordLoads > 1u) wdst0[min(tid + kBlock, w_last0)] = wv01; }
+        if (quads1) { wdst1[min(tid, w_last1)] = wv10; if constexpr (kWordLoads > 1u) wdst1[min(tid + kBlock, w_last1)] = wv11; }
+        if (tid < 8) {                                    // tail words, then zeros for clamped reads
+            reinterpret_cast<uint32_t*>(lds + kPipeOff)[(quads0 << 2) + tid] = tail0;
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + kPipeBytes)[(quads1 << 2) + tid] = tail1;
+        }
         if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
-        if (tid < 16 + kLogSlots * 4u) reinterpret_cast<uint32_t*>(lds + kCtlOff)[tid] = 0u;
-        if (tid == 0) reinterpret_cast<uint32_t*>(lds + kCtlOff)[kStored1] = kSlab;   // the second storer's first slab
-        if (tid < kWave) reinterpret_cast<uint32_t*>(lds + kProgOff)[tid] = (tid < N) ? tid : n;
+        if (tid < 2u * (16u + kLogSlots * 2u)) {          // hand-over words and block headers of both chunks
+            const uint32_t q = tid / (16u + kLogSlots * 2u), i = tid % (16u + kLogSlots * 2u);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = (i == kStored1) ? kSlab : 0u;
+        }
+        if (tid < 2u * kWave) {                           // where every stream is: its first element, or nothing to wait for
+            const uint32_t q = tid / kWave, l = tid % kWave;
+            const uint32_t n_q = q ? (in1 ? c1.n_symbols : 0u) : (in0 ? c0.n_symbols : 0u);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[l] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
+        }
     }
-    const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the ring's background: the dominant symbol
+    const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the rings' background: the dominant symbol
     {
-        uint4* rdst = reinterpret_cast<uint4*>(ring8);
+        uint4* rdst = reinterpret_cast<uint4*>(lds + kRingOff);
 #pragma unroll
-        for (uint32_t k = 0; k < (kRingElems / 16u + kBlock - 1u) / kBlock; ++k)
-            if (tid + k * kBlock < kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(bg4, bg4, bg4, bg4);
+        for (uint32_t k = 0; k < (2u * kRingElems / 16u + kBlock - 1u) / kBlock; ++k)
+            if (tid + k * kBlock < 2u * kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(bg4, bg4, bg4, bg4);
     }
     __syncthreads();
-    if (task == kNoTask) return;
+    if (task == kNoTask || (pipe == 1u && !in1) || (pipe == 0u && !in0)) return;
 
+    // ---- this wavefront's chunk
+    const anszp_chunk_t c = pipe ? c1 : c0;
+    const uint32_t hdr = pipe ? hdr1 : hdr0;
+    const uint32_t pipe_off = kPipeOff + pipe * kPipeBytes;          // the chunk's area: its compressed words come first
+    uint8_t* const ring8 = lds + kRingOff + pipe * kRingElems;
+    lds_flag_t* const ctl = (lds_flag_t*)(lds + pipe_off + kCtlOff);
+    const uint32_t n = c.n_symbols;
+    const uint64_t layer_elem0 = c.out_offset - lay.out_base;
+    const uint32_t n_words = hdr >> 16;
+    const uint32_t len = (lane < N && n > lane) ? (n - lane + N - 1u) / N : 0u;
+    const uint32_t lane_end = lane < N ? lane + len * N : n;         // first element of this lane at or beyond the chunk's end
+    const bool merged_ok = p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords &&
+                           ((c.out_offset * kElemBytes) & 15u) == 0 && n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
+                           (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
+    if (!merged_ok) {                                     // the plain loop of Sec. II-A, table read from global memory
+        if (task != kDecode) return;
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, src + table_triples_offset(p.table_log), lane);
+        if (err && lane == 0) report(p.status, err);
+        return;
+    }
     constexpr uint32_t kRingMask = kRingElems - 1u;
 
-    if (task == kPlaceLo || task == kPlaceHi) {
-        // ---- placing wavefronts: when the block phase is over the look-ahead entries are dead; put
-        // the triples (Sec. II-A), kept in registers until then, in their place for the last symbols
-        // of every stream.  Each of the two holds half of the rows (eight named values rather than
-        // an array: an array that lives across the wait is kept in scratch memory by the compiler).
-        const uint4* psrc = reinterpret_cast<const uint4*>(src + 2u * L);
-        const uint32_t rows = L >> 2;
-        const uint32_t first_row = lane + (task == kPlaceHi ? kTripleLoads / 2u : 0u) * kWave;
-#define ANSZP_8(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
-#define ANSZP_LOAD_ROW(k) const uint4 row##k = psrc[min(first_row + k * kWave, rows - 1u)];
-#define ANSZP_STORE_ROW(k) if (first_row + k * kWave < rows) dst[first_row + k * kWave] = row##k;
-        static_assert(kTripleLoads == 16u, "eight 16-byte rows per lane and wavefront");
-        ANSZP_8(ANSZP_LOAD_ROW)
-        for (uint32_t spins = 0; !uniform(ctl[kOver]); ++spins) {
-            if (uniform(ctl[kGaveUp]) || spins > kSpinLimit) return;
-            __builtin_amdgcn_s_sleep(4);
+    // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.  A lane
+    // takes elements 8*lane .. 8*lane+7 of each half of a slab, so that every store instruction writes
+    // one contiguous run; the slots go back to the background value.
+    auto store_slab = [&](uint32_t first_elem) {
+        uint8_t* q = ring8 + ((first_elem & kRingMask) + lane * 8u);         // the ring is a whole number of slabs
+        const uint2 lo = *reinterpret_cast<const uint2*>(q);
+        const uint2 hi = *reinterpret_cast<const uint2*>(q + kSlab / 2u);
+        *reinterpret_cast<uint2*>(q) = make_uint2(bg4, bg4);
+        *reinterpret_cast<uint2*>(q + kSlab / 2u) = make_uint2(bg4, bg4);
+        const uint32_t first = first_elem + lane * 8u;
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first, layer_elem0 + first, lo, lds_lut);
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u, hi, lds_lut);
+    };
+
+    if (task == kStore0 || task == kStore1) {
+        // ---- storing wavefronts: one takes the even slabs, the other the odd ones
+        const uint32_t which = task - kStore0;
+        uint32_t mine = which * kSlab, spins = 0;        // first element of the next slab this one takes
+        for (;;) {
+            uint32_t over_v, logged_v, expanded_v, next;
+            asm volatile(                                // the flag first, the positions last
+                "ds_read_b32 %[ov], %[ctla] offset:16\n"
+                "ds_read_b32 %[lg], %[ctla]\n"
+                "ds_read_b32 %[ex], %[ctla] offset:4\n"
+                "ds_read_b32 %[nx], %[pa]\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                : [ov] "=&v"(over_v), [lg] "=&v"(logged_v), [ex] "=&v"(expanded_v), [nx] "=&v"(next)
+                : [ctla] "v"(pipe_off + kCtlOff), [pa] "v"(pipe_off + kProgOff + lane * 4u)
+                : "memory");
+            // everything logged was expanded before the positions were read: no more will come
+            const bool last_pass = uniform(over_v) && uniform(logged_v) == uniform(expanded_v);
+            const uint32_t before = mine;
+            while (mine + kSlab <= n && __ballot(next < mine + kSlab) == 0) {
+                store_slab(mine);
+                mine += 2u * kSlab;
+            }
+            if (mine != before) {
+                asm volatile("ds_write_b32 %[wa], %[st]\n" :: [wa] "v"(pipe_off + kCtlOff + 4u * (kStored0 + which)), [st] "v"(mine) : "memory");
+                spins = 0;
+            }
+            if (last_pass) break;
+            if (mine == before) {
+                if (uniform(ctl[kGaveUp])) return;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                    return;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
         }
-        uint4* dst = reinterpret_cast<uint4*>(lds_table);
-        ANSZP_8(ANSZP_STORE_ROW)
-#undef ANSZP_STORE_ROW
-#undef ANSZP_LOAD_ROW
-#undef ANSZP_8
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        if (lane == 0) ctl[task == kPlaceHi ? kTriplesHi : kTriplesLo] = 1u;
+        // the elements behind the last whole slab, by the wavefront whose turn that slab would have been
+        const uint32_t rest = n / kSlab * kSlab;
+        if (((rest / kSlab) & 1u) == which)
+            for (uint32_t j = rest + lane; j < n; j += kWave)
+                Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & kRingMask], lds_lut);
         return;
     }
 
-    // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.  Up to
-    // four leave per call, their LDS reads issued together.  A lane takes elements 8*lane .. 8*lane+7
-    // of each half of a slab, so that every store instruction writes one contiguous run.
-    auto store_slabs = [&](uint32_t stored, auto count) {
-        constexpr uint32_t K = decltype(count)::value;
-        uint2 lo[K], hi[K];
-#pragma unroll
-        for (uint32_t k = 0; k < K; ++k) {              // the ring is a whole number of slabs: wrap per slab
-            const uint8_t* q = ring8 + (((stored + k * kSlab) & kRingMask) + lane * 8u);
-            lo[k] = *reinterpret_cast<const uint2*>(q);
-            hi[k] = *reinterpret_cast<const uint2*>(q + kSlab / 2u);
-        }
-#pragma unroll
-        for (uint32_t k = 0; k < K; ++k) {
-            uint8_t* q = ring8 + (((stored + k * kSlab) & kRingMask) + lane * 8u);
-            *reinterpret_cast<uint2*>(q) = make_uint2(bg4, bg4);
-            *reinterpret_cast<uint2*>(q + kSlab / 2u) = make_uint2(bg4, bg4);
-        }
-#pragma unroll
-        for (uint32_t k = 0; k < K; ++k) {
-            const uint32_t first = stored + k * kSlab + lane * 8u;
-            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first, layer_elem0 + first, lo[k], lds_lut);
-            Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u,
-                                              hi[k], lds_lut);
-        }
-    };
-    constexpr uint32_t kStoreBatch = PER_CHANNEL ? 1u : 2u;   // conversion needs the registers
-    auto store_ready = [&](uint32_t ne, uint32_t& stored) {
-        for (;;) {
-            uint32_t ready = 0;
-            while (ready < kStoreBatch && stored + (ready + 1u) * kSlab <= n &&
-                   __ballot(ne < stored + (ready + 1u) * kSlab) == 0)
-                ++ready;
-            if (ready == 0) return;
-            if constexpr (kStoreBatch == 2u) {
-                if (ready == 2u) store_slabs(stored, std::integral_constant<uint32_t, 2u>{});
-                else store_slabs(stored, std::integral_constant<uint32_t, 1u>{});
-            } else {
-                store_slabs(stored, std::integral_constant<uint32_t, 1u>{});
-            }
-            stored += ready * kSlab;
-            if (ready < kStoreBatch) return;
-        }
-    };
+    uint32_t total_words;
+    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    const uint32_t first_bit = (pipe_off + 4u * min(first_word, c.payload_words)) << 3;   // counted from the start of LDS
 
     if (task == kExpand) {
-        // ---- expanding wavefront: turn logged entries into symbols in the ring.  An entry stands for c symbols: c-1
-        // copies of the dominant symbol, which the ring already holds as background, then its own
-        // symbol.  Every pass reads the count of logged
-        // blocks and, in the same batch of LDS reads, the header and the entries of the block it
-        // waits for: if the count (read first) says the block is there, what was read after it is
-        // the block.
+        // ---- expanding wavefront.  Every pass reads the count of logged blocks and, in the same batch
+        // of LDS reads, the header and the entries of the block it waits for: if the count (read
+        // first) says the block is there, what was read after it is the block.
         __builtin_amdgcn_s_setprio(2);                   // ahead of the storing wavefronts it shares a SIMD with
-        uint32_t ne = (lane < N) ? lane : n;             // chunk index of this lane's next symbol
+        uint32_t ne = (lane < N && lane < n) ? lane : lane_end;   // chunk index of this lane's next symbol
+        uint32_t at_bit = first_bit;                     // where the stream stood when its last block began
+        uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+        bool ended = ne >= lane_end;                     // no symbols: the initial state must be the final one
+        if (lane < N && ended) {
+            if ((hdr & (L - 1u)) != 0u) err |= ANSZP_ST_BAD_STATE;
+            if (n_words != 0u) err |= ANSZP_ST_BAD_LENGTH;
+        }
         uint32_t expanded = 0, spins = 0;
         for (;;) {
             const uint32_t slot = expanded & (kLogSlots - 1u);
-            uint32_t logged_v, lookups_v, ent[8];
+            uint32_t logged_v, ent[9], bit_after;
             uint64_t lanes_v;
-            // one batch of LDS reads (no wait between them; LDS serves a wavefront's reads in order)
             asm volatile(
-                "ds_read_b32 %[lg], %[zero] offset:%[ctlw0]\n"
+                "ds_read_b32 %[lg], %[ctla]\n"
                 "ds_read_b64 %[lanes], %[hdra] offset:%[hdr]\n"
-                "ds_read_b32 %[lk], %[hdra] offset:%[hdr]+8\n"
-                "ds_read_b32 %[e0], %[loga]\n"
-                "ds_read_b32 %[e1], %[loga] offset:256\n"
-                "ds_read_b32 %[e2], %[loga] offset:512\n"
-                "ds_read_b32 %[e3], %[loga] offset:768\n"
-                "ds_read_b32 %[e4], %[loga] offset:1024\n"
-                "ds_read_b32 %[e5], %[loga] offset:1280\n"
-                "ds_read_b32 %[e6], %[loga] offset:1536\n"
-                "ds_read_b32 %[e7], %[loga] offset:1792\n"
+                "ds_read_u16 %[e0], %[loga]\n"
+                "ds_read_u16 %[e1], %[loga] offset:128\n"
+                "ds_read_u16 %[e2], %[loga] offset:256\n"
+                "ds_read_u16 %[e3], %[loga] offset:384\n"
+                "ds_read_u16 %[e4], %[loga] offset:512\n"
+                "ds_read_u16 %[e5], %[loga] offset:640\n"
+                "ds_read_u16 %[e6], %[loga] offset:768\n"
+                "ds_read_u16 %[e7], %[loga] offset:896\n"
+                "ds_read_u16 %[e8], %[loga] offset:1024\n"
+                "ds_read_b32 %[ba], %[bita] offset:1152\n"
                 "s_waitcnt lgkmcnt(0)\n"
-                : [lg] "=&v"(logged_v), [lanes] "=&v"(lanes_v), [lk] "=&v"(lookups_v),
-                  [e0] "=&v"(ent[0]), [e1] "=&v"(ent[1]), [e2] "=&v"(ent[2]), [e3] "=&v"(ent[3]),
-                  [e4] "=&v"(ent[4]), [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7])
-                : [zero] "v"(0u), [hdra] "v"(slot * 16u), [loga] "v"(kLogOff + slot * kLogSlotBytes + lane * 4u),
-                  [ctlw0] "n"(kCtlOff), [hdr] "n"(kHdrOff)
+                : [lg] "=&v"(logged_v), [lanes] "=&v"(lanes_v), [ba] "=&v"(bit_after),
+                  [e0] "=&v"(ent[0]), [e1] "=&v"(ent[1]), [e2] "=&v"(ent[2]), [e3] "=&v"(ent[3]), [e4] "=&v"(ent[4]),
+                  [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7]), [e8] "=&v"(ent[8])
+                : [ctla] "v"(pipe_off + kCtlOff), [hdra] "v"(pipe_off + slot * 8u),
+                  [loga] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 2u),
+                  [bita] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 4u), [hdr] "n"(kHdrOff)
                 : "memory");
             if (uniform(logged_v) == expanded) {         // nothing new
                 if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
                     if (uniform(ctl[kLogged]) == expanded) break;
                     continue;
                 }
-                if (uniform(ctl[kGaveUp])) break;
+                if (uniform(ctl[kGaveUp])) return;
                 if (++spins > kSpinLimit) {
                     if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
-                    break;
+                    return;
                 }
                 __builtin_amdgcn_s_sleep(1);
                 continue;
             }
             spins = 0;
-            const uint32_t lookups = uniform(lookups_v);
             if ((lanes_v >> lane) & 1u) {                // the same word in every lane: did this lane take part?
-                auto expand = [&](auto count) {
-                    constexpr uint32_t S = decltype(count)::value;
+                const uint32_t ne_before = ne;
 #pragma unroll
-                    for (uint32_t k = 0; k < S; ++k) {
-                        const uint32_t last = __umul24((ent[k] >> 16) & 3u, N) + ne;
-                        ring8[last & kRingMask] = static_cast<uint8_t>(ent[k] >> 8);
-                        ne = last + N;
+                for (uint32_t k = 0; k < 8u; ++k) {      // log entry: bits 0..3 T | 4..6 c-1 | 7 entry of state 0 | 8..15 symbol
+                    const uint32_t last = __umul24((ent[k] >> 4) & 7u, N) + ne;
+                    ring8[last & kRingMask] = static_cast<uint8_t>(ent[k] >> 8);
+                    ne = last + N;
+                }
+                if (!ended && ne >= lane_end) {          // the stream's last symbol lies in this block: find its entry
+                    ended = true;
+                    uint32_t pos = ne_before, bits = at_bit;
+                    bool found = false;
+#pragma unroll
+                    for (uint32_t k = 0; k < 8u; ++k) {
+                        const uint32_t after = pos + (((ent[k] >> 4) & 7u) + 1u) * N;
+                        bits += ent[k] & 15u;
+                        if (!found && after >= lane_end) {
+                            found = true;
+                            // it must end with the entry, in state 0, the stream's words read and no more
+                            if (after != lane_end || !((ent[k + 1u] >> 7) & 1u)) err |= ANSZP_ST_BAD_STATE;
+                            if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
+                        }
+                        pos = after;
                     }
-                };
-                if (lookups == 8u) expand(std::integral_constant<uint32_t, 8u>{});
-                else if (lookups == 4u) expand(std::integral_constant<uint32_t, 4u>{});
-                else expand(std::integral_constant<uint32_t, 2u>{});
+                }
+                at_bit = bit_after;
             }
             ++expanded;
-            // publish the lanes' positions, then the count, issued after the ring writes above (LDS keeps
-            // a wavefront's accesses in order, so nothing has to be waited for)
+            // publish the lanes' positions, then the count, issued after the ring writes above
             asm volatile("ds_write_b32 %[pa], %[ne]\n"
-                         "ds_write_b32 %[zero], %[ex] offset:%[ctlw1]\n"
-                         :: [pa] "v"(kProgOff + lane * 4u), [ne] "v"(ne), [zero] "v"(0u), [ex] "v"(expanded),
-                            [ctlw1] "n"(kCtlOff + 4u)
+                         "ds_write_b32 %[ctla], %[ex] offset:4\n"
+                         :: [pa] "v"(pipe_off + kProgOff + lane * 4u), [ne] "v"(ne), [ctla] "v"(pipe_off + kCtlOff), [ex] "v"(expanded)
                          : "memory");
         }
+        if (lane < N && !ended) err |= ANSZP_ST_INTERNAL;  // cannot happen: the decoding wavefront logs until every stream has ended
+        err = wave_or(err);
+        if (err && lane == 0) report(p.status, err);
         return;
     }
 
-    if (task == kStore0 || task == kStore1) {
-        // ---- storing wavefronts: move finished slabs of the ring to global memory; one takes the
-        // even slabs, the other the odd ones
-        const uint32_t which = task - kStore0;
-        uint32_t mine = which * kSlab, spins = 0;        // first element of the next slab this one takes
-        for (;;) {
-            uint32_t over_v, logged_v, expanded_v, next;
-            asm volatile(                                // the flag first, the positions last
-                "ds_read_b32 %[ov], %[zero] offset:%[ctlw4]\n"
-                "ds_read_b32 %[lg], %[zero] offset:%[ctlw0]\n"
-                "ds_read_b32 %[ex], %[zero] offset:%[ctlw1]\n"
-                "ds_read_b32 %[nx], %[pa]\n"
-                "s_waitcnt lgkmcnt(0)\n"
-                : [ov] "=&v"(over_v), [lg] "=&v"(logged_v), [ex] "=&v"(expanded_v), [nx] "=&v"(next)
-                : [zero] "v"(0u), [pa] "v"(kProgOff + lane * 4u), [ctlw0] "n"(kCtlOff), [ctlw1] "n"(kCtlOff + 4u),
-                  [ctlw4] "n"(kCtlOff + 16u)
-                : "memory");
-            // everything logged was expanded before the positions were read: no more will come
-            const bool last_pass = uniform(over_v) && uniform(logged_v) == uniform(expanded_v);
-            const uint32_t before = mine;
-            while (mine + kSlab <= n && __ballot(next < mine + kSlab) == 0) {
-                store_slabs(mine, std::integral_constant<uint32_t, 1u>{});
-                mine += 2u * kSlab;
-            }
-            if (mine != before) {
-                asm volatile("ds_write_b32 %[wa], %[st]\n"
-                             :: [wa] "v"(kCtlOff + 4u * (kStored0 + which)), [st] "v"(mine) : "memory");
-                spins = 0;
-            }
-            if (last_pass) {
-                if (lane == 0) ctl[kStoreDone0 + which] = 1u;
-                break;
-            }
-            if (mine == before) {
-                if (uniform(ctl[kGaveUp])) break;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
-        }
-        return;
-    }
-
-    // ---- decoding wavefront: per-lane stream state
+    // ---- decoding wavefront
     __builtin_amdgcn_s_setprio(3);
-    uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
-    const uint32_t last_word4 = c.payload_words << 2;    // byte offset of the zero words behind the payload
-
+    const uint32_t last_word = pipe_off + (c.payload_words << 2);        // address of the zero words behind the payload
+    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(lds + pipe_off);
     // Look-ahead entries are indexed by 2 * state + the next stream bit (peeked, not yet read).
-    uint32_t X4 = (2u * (hdr & (L - 1u)) + (lds_words[min(first_word, c.payload_words)] & 1u)) << 2;
-    uint32_t abit = first_word << 5;                     // bit position in the chunk's payload
-    uint32_t ne = (lane < N) ? lane : n;                 // chunk index of this lane's next symbol
-    if (ne >= n && (hdr & (L - 1u)) != 0) err |= ANSZP_ST_BAD_STATE;   // empty stream must carry state 0
-    uint32_t logged = 0;
+    const uint32_t index0 = 2u * (hdr & (L - 1u)) + (lds_words[min(first_word, c.payload_words)] & 1u);
+    uint2 e = reinterpret_cast<const uint2*>(lds)[index0];
+    uint32_t abit = first_bit;                           // bit position, counted from the start of LDS
+    uint32_t ne = (lane < N && lane < n) ? lane : lane_end;
+    uint32_t logged = 0, spins = 0;
     bool gave_up = false;
-
-    // Block phase: blocks of 8 look-ups with no per-step checks.  A lane joins a block only if even
-    // 8 full-length entries keep it inside its stream and inside the ring (whose room follows from
-    // what the storing wavefront has stored), so nothing can finish or overrun in the middle of a block.
-    // The block is hand-scheduled: a lone wavefront issues one instruction every 5-8 cycles, and
-    // what a look-up costs is the LDS round trip plus the instructions between its arrival and the
-    // next read.  This wavefront therefore only walks the automaton and logs the entries it passes;
-    // the expanding wavefront turns them into symbols.  At the start of a block every lane loads four payload
-    // words (128 bits, at least 97 of them ahead of its bit position: 8 look-ups use at most 8 * 12
-    // and peek one more) and shifts them down so that the stream continues at bit 0 of w0; r is w0
-    // bit-reversed, so the first bit read is on top.  Per look-up, for an entry e with T bits:
-    //   index' = base(e) + (r >> (31 - T));  e' = table[index']       Sec. II-A: newX' + bits, plus the peeked bit
-    //   log[k] = e;  w0..w3 >>= T (funnel shift);  r = bitrev(w0)
-    //   sum += e (low byte: 31 - T per look-up);  ne += (c(e) - 1) * N
-    // A block ends by publishing the lanes that took part and the new count of logged blocks,
-    // reloading every lane's four words and recomputing who may join the next block from the words
-    // the other wavefronts publish (read at the start of the block, so their latency is hidden).
-    // Blocks of 8 look-ups run first; when no lane can take one any more (streams within 32
-    // symbols of their end), blocks of 4 and then of 2 take over, and only the last few symbols
-    // of each stream go through the checked step below.
-    {
-        uint32_t e = lds_table[X4 >> 2];
-        const uint32_t lane_log = kLogOff + lane * 4u;
-// The window is shifted only as far up as a later look-up of the block can still read: a look-up
-// reads at most 12 bits and peeks one, so with j look-ups to follow only the first 12 j + 1 bits
-// matter: w0 is shifted by every look-up but the last, w1 while four or more follow, w2 while
-// seven follow, w3 never (what a stale register feeds into its neighbour lies beyond that reach).
+    // the first four hand-over words in one LDS read
+    auto hand_over_words = [&]() {
+        uint4 v;
+        asm volatile("ds_read_b128 %[v], %[ctla]\n s_waitcnt lgkmcnt(0)\n" : [v] "=v"(v) : [ctla] "v"(pipe_off + kCtlOff) : "memory");
+        return v;
+    };
+    // A block, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and what a
+    // look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
+    //   v = r >> (31 - T)            the next T+1 stream bits, r = the window's first word bit-reversed
+    //   address' = 8 v + 8 base      Sec. II-A: newX + bits, plus the peeked bit
+    //   e' = table[address'];  log[k] = e (its upper half);  w0..w3 >>= T (funnel shift);  r = bitrev(w0)
+    //   sum += e                     byte 0: 31 - T per look-up; bits 8..13: c - 1 per look-up
+    // At the start of a block every lane loads four words of its stream (128 bits, at least 97 of them
+    // ahead of its bit position: 8 look-ups use at most 8 * 12 and peek one more).  The window is shifted
+    // only as far up as a later look-up of the block can still read: with j look-ups to follow only the
+    // first 12 j + 1 bits matter, so w0 is shifted by every look-up but the last, w1 while four or more
+    // follow, w2 while seven follow, w3 never.  A block ends by logging what each lane's next look-up
+    // starts from and the lane's bit position, publishing the lanes that took part and the new count of
+    // blocks, reloading every lane's four words and recomputing who may join the next block from the
+    // words the other wavefronts publish (read at the start of the block, so their latency is hidden).
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
-#define ANSZP_LOOKUP(EA, EB, K, SHIFT, SUM)                                             \
+#define ANSZP_LOOKUP(ELO, EHI, FB, K, SHIFT, SUM)                                      \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
-        "v_lshrrev_b32 v36, " EA ", v33\n"                                             \
-        "v_bfe_i32 v37, " EA ", 18, 14\n"                                              \
-        "v_add_lshl_u32 v36, v36, v37, 2\n"                                            \
-        "ds_read_b32 " EB ", v36 offset:%[table]\n"                                    \
-        "ds_write_b32 v42, " EA " offset:" K "*256\n"                                  \
-        "v_not_b32 v35, " EA "\n"                                                      \
-        "v_bfe_u32 v39, " EA ", 16, 2\n"                                               \
+        "v_lshrrev_b32 v36, " ELO ", v33\n"                                            \
+        "v_lshl_add_u32 v36, v36, 3, " EHI "\n"                                        \
+        "ds_read_b64 " FB ", v36\n"                                                    \
+        "ds_write_b16_d16_hi v42, " ELO " offset:" K "*128\n"                          \
+        "v_not_b32 v35, " ELO "\n"                                                     \
         SHIFT                                                                          \
         "v_bfrev_b32 v33, v28\n"                                                       \
-        SUM                                                                            \
-        "v_mad_u32_u24 v34, v39, %[nstr], v34\n"
-// (the first look-up of a block starts the block's sum of 31 - T, the others add to it)
-#define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT, "v_mov_b32 v41, v24\n")
-#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", K, SHIFT, "v_add_u32 v41, v41, v24\n")
-#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v25", "v24", K, SHIFT, "v_add_u32 v41, v41, v25\n")
-// BODY = all look-ups of a block but the last, which is written out below: it skips the window
-// shift.  Blocks have an even number of look-ups, so the entry ends up in v24 again.
-#define ANSZP_RUN_BLOCKS(STEPS, BODY)                                                                                 \
-        while (!gave_up && n > (STEPS) * kMaxMerged * N) {                                                            \
-            const uint32_t reach = (STEPS) * kMaxMerged * N;                                                          \
-            const uint32_t near_end = n - reach;                                                                      \
-            if (__ballot(ne < near_end) == 0) break;                                                                  \
-            const uint4 seen = hand_over_words();                                                                     \
-            const uint32_t stored = min(uniform(seen.z), uniform(seen.w)), expanded = uniform(seen.y);               \
-            const uint32_t limit = min(near_end, stored + (kRingElems - reach));                                      \
-            if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) { /* ring or log full: wait */           \
-                if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;                                    \
-                __builtin_amdgcn_s_sleep(1);                                                                          \
-                continue;                                                                                             \
-            }                                                                                                         \
-            spins = 0;                                                                                                \
-            uint32_t logged_v = logged;                                                                               \
-            asm volatile(                                                                                             \
-                "v_mov_b32 v24, %[e]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v34, %[ne]\n v_mov_b32 v36, %[x4]\n"          \
-                "v_mov_b32 v43, 0\n v_mov_b32 v46, " #STEPS "\n v_mov_b32 v40, %[hdr0]\n"                            \
-                "v_readfirstlane_b32 s44, %[logged]\n"                                                                        \
-                "s_mov_b64 s[40:41], exec\n"                                                                          \
-                "v_cmp_gt_u32 vcc, %[lim], v34\n"                                                                     \
-                "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
-                "v_and_b32 v38, 0x1ffffffc, v38\n"                                                                    \
-                "v_min_u32 v38, %[lastw], v38\n"                                                                      \
-                "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
-                "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
-                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* -, blocks expanded, elements stored (two) */        \
-                "s_and_b64 exec, s[40:41], vcc\n"      /* lanes that can run a whole block (some can) */              \
-                "1:\n"                                                                                                \
-                "v_lshl_add_u32 v42, v40, 7, %[lanelog]\n" /* this lane's column in the block's log slot */           \
-                "s_waitcnt lgkmcnt(1)\n"              /* the window words; the hand-over words were asked for last */ \
-                "v_alignbit_b32 v28, v29, v28, v32\n"                                                                 \
-                "v_alignbit_b32 v29, v30, v29, v32\n"                                                                 \
-                "v_alignbit_b32 v30, v31, v30, v32\n"                                                                 \
-                "v_lshrrev_b32 v31, v32, v31\n"                                                                       \
-                "v_bfrev_b32 v33, v28\n"                                                                              \
-                BODY                                                                                                  \
-                "s_waitcnt lgkmcnt(1)\n"                                                                              \
-                "v_lshrrev_b32 v36, v25, v33\n"                                                                       \
-                "v_bfe_i32 v37, v25, 18, 14\n"                                                                        \
-                "v_add_lshl_u32 v36, v36, v37, 2\n"                                                                   \
-                "ds_read_b32 v24, v36 offset:%[table]\n"                                                              \
-                "ds_write_b32 v42, v25 offset:(" #STEPS "-1)*256\n"                                                   \
-                "v_bfe_u32 v39, v25, 16, 2\n"                                                                         \
-                "v_add_u32 v41, v41, v25\n"                                                                           \
-                "v_mad_u32_u24 v34, v39, %[nstr], v34\n"                                                               \
-                "v_and_b32 v41, 0xff, v41\n"                                                                          \
-                "v_add_u32 v34, %[snstr], v34\n"         /* one symbol per look-up on top of the runs */                \
-                "v_sub_u32 v41, 31*" #STEPS ", v41\n"                                                                 \
-                "v_mov_b32 v44, exec_lo\n"                                                                            \
-                "v_mov_b32 v45, exec_hi\n"                                                                            \
-                "v_add_u32 v32, v32, v41\n"            /* bit position after the block */                             \
-                "ds_write_b96 v40, v[44:46] offset:%[hdr]\n" /* header: lanes taking part, look-ups */              \
-                "s_add_u32 s44, s44, 1\n"                                                                             \
-                "v_mov_b32 v44, s44\n"                                                                                \
-                "v_readfirstlane_b32 s46, v49\n"       /* blocks expanded when the previous block ended */            \
-                "ds_write_b32 v43, v44 offset:%[ctlw0]\n" /* publish the block */                                     \
-                "s_mov_b64 exec, s[40:41]\n"           /* every lane reloads its words */                             \
-                "v_add_u32 v40, 16, v40\n"            /* offset of the next block's header */                        \
-                "v_and_b32 v40, %[hdrmask], v40\n"                                                                    \
-                "v_lshrrev_b32 v38, 3, v32\n"                                                                         \
-                "v_and_b32 v38, 0x1ffffffc, v38\n"                                                                    \
-                "v_min_u32 v38, %[lastw], v38\n"                                                                      \
-                "ds_read2_b32 v[28:29], v38 offset1:1\n"                                                              \
-                "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"                                                    \
-                "v_min_u32 v50, v50, v51\n"           /* elements stored when the previous block ended: every */     \
-                "v_add_u32 v50, %[room], v50\n"       /* slab below the next one of either storing wavefront */      \
-                "v_min_u32 v50, %[nearend], v50\n"                                                                    \
-                "v_cmp_gt_u32 vcc, v50, v34\n"        /* lanes that can run another block */                         \
-                "ds_read_b128 v[48:51], v43 offset:%[ctlw0]\n" /* the same words, for the end of the next block */    \
-                "s_sub_u32 s46, s44, s46\n"                                                                           \
-                "s_cmp_ge_u32 s46, %[slots]\n"         /* the next log slot may still be in use */                    \
-                "s_cbranch_scc1 2f\n"                                                                                 \
-                "s_and_b64 exec, s[40:41], vcc\n"                                                                     \
-                "s_cbranch_scc1 1b\n"                                                                                 \
-                "2:\n"                                                                                                \
-                "s_mov_b64 exec, s[40:41]\n"                                                                          \
-                "s_waitcnt lgkmcnt(0)\n"                                                                              \
-                "v_mov_b32 %[e], v24\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v34\n v_mov_b32 %[x4], v36\n"          \
-                "v_mov_b32 %[logged], s44\n"                                                                          \
-                : [e] "+v"(e), [ab] "+v"(abit), [ne] "+v"(ne), [x4] "+v"(X4), [logged] "+v"(logged_v)                 \
-                : [lim] "s"(uniform(limit)), [nearend] "s"(uniform(near_end)), [room] "s"(uniform(kRingElems - reach)),\
-                  [nstr] "s"(uniform(N)), [snstr] "s"(uniform((STEPS) * N)), [lastw] "s"(uniform(last_word4)),        \
-                  [lanelog] "v"(lane_log), [hdr0] "s"(uniform((logged & (kLogSlots - 1u)) << 4)),                     \
-                  [table] "n"(kTableOff), [hdr] "n"(kHdrOff), [ctlw0] "n"(kCtlOff),                                \
-                  [slots] "n"(kLogSlots), [hdrmask] "n"(kLogSlots * 16u - 1u)                                         \
-                : "memory", "vcc", "scc", "s40", "s41", "s44", "s46", "v24", "v25", "v28", "v29", "v30",\
-                  "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44",   \
-                  "v45", "v46", "v48", "v49", "v50", "v51");                                                   \
-            logged = uniform(logged_v);                                                                               \
+        SUM
+#define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_mov_b32 v37, v24\n")
+#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n")
+#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n")
+    static_assert(ANSZP_MAX_TABLE_LOG <= 12, "the reach of a look-up assumed by the window shifts");
+    static_assert(kLogSlotBytes == 1408u, "log slot: nine rows of 16 bits per lane, then a row of 32");
+    const uint32_t room = kRingElems - 8u * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 8 entries of 8 symbols
+    while (!gave_up) {
+        if (__ballot(ne < lane_end) == 0) break;          // every stream has ended
+        const uint4 seen = hand_over_words();
+        const uint32_t stored = min(uniform(seen.z), uniform(seen.w)), expanded = uniform(seen.y);
+        const uint32_t limit = min(lane_end, stored + room);
+        if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) {        // ring or log full: wait
+            if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;
+            __builtin_amdgcn_s_sleep(1);
+            continue;
         }
-        uint32_t spins = 0;
-        // the first four hand-over words in one LDS read
-        auto hand_over_words = [&]() {
-            uint4 v;
-            asm volatile("ds_read_b128 %[v], %[zero] offset:%[ctlw0]\n s_waitcnt lgkmcnt(0)\n"
-                         : [v] "=v"(v) : [zero] "v"(0u), [ctlw0] "n"(kCtlOff) : "memory");
-            return v;
-        };
-        static_assert(ANSZP_MAX_TABLE_LOG <= 12, "the reach of a look-up assumed by the window shifts");
-        ANSZP_RUN_BLOCKS(8, ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
-                            ANSZP_BA("3", ANSZP_SHIFT_W1) ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0)
-                            ANSZP_AB("6", ANSZP_SHIFT_W0))
-        ANSZP_RUN_BLOCKS(4, ANSZP_FIRST("0", ANSZP_SHIFT_W1) ANSZP_BA("1", ANSZP_SHIFT_W0) ANSZP_AB("2", ANSZP_SHIFT_W0))
-        ANSZP_RUN_BLOCKS(2, ANSZP_FIRST("0", ANSZP_SHIFT_W0))
-#undef ANSZP_RUN_BLOCKS
+        spins = 0;
+        uint32_t logged_v = logged;
+        asm volatile(
+            "v_mov_b32 v24, %[elo]\n v_mov_b32 v25, %[ehi]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v39, %[ne]\n"
+            "v_mov_b32 v43, %[ctla]\n"
+            "v_readfirstlane_b32 s44, %[logged]\n"
+            "s_mov_b64 s[40:41], exec\n"
+            "v_cmp_gt_u32 vcc, %[lim], v39\n"
+            "v_lshrrev_b32 v38, 3, v32\n"
+            "v_and_b32 v38, 0x1ffffffc, v38\n"
+            "v_min_u32 v38, %[lastw], v38\n"
+            "ds_read2_b32 v[28:29], v38 offset1:1\n"
+            "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
+            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, blocks expanded, elements stored (two) */
+            "s_and_b64 exec, s[40:41], vcc\n"          /* lanes that run this block (some do) */
+            "1:\n"
+            "s_and_b32 s45, s44, %[slotmask]\n"        /* the block's log slot */
+            "s_mul_i32 s46, s45, 1408\n"
+            "v_add_u32 v42, s46, %[lanelog]\n"         /* this lane's 16-bit column in the slot */
+            "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the row of bit positions */
+            "s_waitcnt lgkmcnt(1)\n"                   /* the window words; the hand-over words were asked for last */
+            "v_alignbit_b32 v28, v29, v28, v32\n"
+            "v_alignbit_b32 v29, v30, v29, v32\n"
+            "v_alignbit_b32 v30, v31, v30, v32\n"
+            "v_lshrrev_b32 v31, v32, v31\n"
+            "v_bfrev_b32 v33, v28\n"
+            ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
+            ANSZP_BA("3", ANSZP_SHIFT_W1) ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0)
+            ANSZP_AB("6", ANSZP_SHIFT_W0)
+            "s_waitcnt lgkmcnt(1)\n"                   /* the eighth look-up shifts no window */
+            "v_lshrrev_b32 v36, v26, v33\n"
+            "v_lshl_add_u32 v36, v36, 3, v27\n"
+            "ds_read_b64 v[24:25], v36\n"
+            "ds_write_b16_d16_hi v42, v26 offset:7*128\n"
+            "v_add_u32 v37, v37, v26\n"
+            "v_and_b32 v46, 0xff, v37\n"
+            "v_bfe_u32 v35, v37, 8, 6\n"
+            "v_sub_u32 v46, 31*8, v46\n"               /* stream bits the block consumed */
+            "v_add_u32 v35, 8, v35\n"                  /* symbols it stands for */
+            "v_add_u32 v32, v32, v46\n"
+            "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
+            "ds_write_b32 v47, v32 offset:1152\n"      /* bit position after the block */
+            "v_mov_b32 v44, exec_lo\n"
+            "v_mov_b32 v45, exec_hi\n"
+            "s_lshl_b32 s46, s45, 3\n"
+            "v_add_u32 v40, s46, v43\n"
+            "s_add_u32 s44, s44, 1\n"
+            "v_mov_b32 v46, s44\n"
+            "s_waitcnt lgkmcnt(2)\n"                   /* the entry the next look-up starts from */
+            "ds_write_b16_d16_hi v42, v24 offset:8*128\n"
+            "ds_write_b64 v40, v[44:45] offset:64\n"   /* header: lanes taking part */
+            "ds_write_b32 v43, v46\n"                  /* publish the block */
+            "v_readfirstlane_b32 s46, v49\n"           /* blocks expanded when the previous block ended */
+            "s_mov_b64 exec, s[40:41]\n"               /* every lane reloads its words */
+            "v_lshrrev_b32 v38, 3, v32\n"
+            "v_and_b32 v38, 0x1ffffffc, v38\n"
+            "v_min_u32 v38, %[lastw], v38\n"
+            "ds_read2_b32 v[28:29], v38 offset1:1\n"
+            "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
+            "v_min_u32 v50, v50, v51\n"                /* elements stored when the previous block ended: every */
+            "v_add_u32 v50, %[room], v50\n"            /* slab below the next one of either storing wavefront */
+            "v_min_u32 v50, %[lend], v50\n"
+            "v_cmp_gt_u32 vcc, v50, v39\n"             /* lanes that can run another block */
+            "ds_read_b128 v[48:51], v43\n"             /* the same words, for the end of the next block */
+            "s_sub_u32 s46, s44, s46\n"
+            "s_cmp_ge_u32 s46, %[slots]\n"             /* the next log slot may still be in use */
+            "s_cbranch_scc1 2f\n"
+            "s_and_b64 exec, s[40:41], vcc\n"
+            "s_cbranch_scc1 1b\n"
+            "2:\n"
+            "s_mov_b64 exec, s[40:41]\n"
+            "s_waitcnt lgkmcnt(0)\n"
+            "v_mov_b32 %[elo], v24\n v_mov_b32 %[ehi], v25\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v39\n"
+            "v_mov_b32 %[logged], s44\n"
+            : [elo] "+v"(e.x), [ehi] "+v"(e.y), [ab] "+v"(abit), [ne] "+v"(ne), [logged] "+v"(logged_v)
+            : [lim] "v"(limit), [lend] "v"(lane_end), [room] "s"(uniform(room)), [nstr] "s"(uniform(N)),
+              [lastw] "s"(uniform(last_word)), [ctla] "s"(uniform(pipe_off + kCtlOff)),
+              [lanelog] "v"(pipe_off + kLogOff + lane * 2u), [lanebit] "v"(pipe_off + kLogOff + lane * 4u),
+              [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u)
+            : "memory", "vcc", "scc", "s40", "s41", "s44", "s45", "s46", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31",
+              "v32", "v33", "v35", "v36", "v37", "v38", "v39", "v40", "v42", "v43", "v44", "v45", "v46", "v47",
+              "v48", "v49", "v50", "v51");
+        logged = uniform(logged_v);
+    }
 #undef ANSZP_FIRST
 #undef ANSZP_AB
 #undef ANSZP_BA
@@ -1378,71 +1438,22 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #undef ANSZP_SHIFT_W2
 #undef ANSZP_SHIFT_W1
 #undef ANSZP_SHIFT_W0
-        // the block phase is over: the look-ahead entries may be replaced, the expanding and storing
-        // wavefronts finish what is logged; then this wavefront owns the ring
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        if (lane == 0) ctl[kOver] = 1u;
-        for (spins = 0; !gave_up && (!uniform(ctl[kStoreDone0]) || !uniform(ctl[kStoreDone1]) || !uniform(ctl[kTriplesLo]) ||
-                                       !uniform(ctl[kTriplesHi])); ++spins) {
-            if (uniform(ctl[kGaveUp]) || spins > kSpinLimit) gave_up = true;
-            __builtin_amdgcn_s_sleep(1);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        if (gave_up) {
-            if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
-            return;
-        }
+    if (gave_up) {
+        if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+        return;
     }
-
-    // Careful phase (Sec. II-A, one step per symbol): every step checks the end of the stream and
-    // the room in the ring.
-    uint32_t X = X4 >> 3;                                // the peeked bit is dropped: it has not been read
-    uint32_t stored = min(uniform(ctl[kStored0]), uniform(ctl[kStored1]));
-    auto step = [&](uint32_t bound) {
-        if (ne < bound) {
-            // both reads are issued before either is waited for, and there is no branch on nb_bits
-            const uint32_t* q = reinterpret_cast<const uint32_t*>(lds + min((abit >> 3) & ~3u, last_word4));
-            const uint32_t q0 = q[0], q1 = q[1];
-            const uint32_t t = lds_table[X];
-            const uint32_t nb = min((t >> 16) & 0xFFu, 31u);
-            const uint32_t window = __builtin_amdgcn_alignbit(q1, q0, abit);
-            const uint32_t bits = (__brev(window) >> (31u - nb)) >> 1;       // first bit read is the top bit; none: 0
-            X = ((t & 0xFFFFu) + bits) & (L - 1u);
-            ring8[ne & kRingMask] = static_cast<uint8_t>(t >> 24);
-            abit += nb;
-            ne += N;
-            if (ne >= n && X != 0) err |= ANSZP_ST_BAD_STATE;     // stream finished: it must have arrived in state 0
-        }
-    };
-    for (;;) {
-        if (__ballot(ne < n) == 0) break;
-        const uint32_t bound = min(n, stored + kRingElems);
-        step(bound);
-        step(bound);
-        step(bound);
-        step(bound);
-        store_ready(ne, stored);
-    }
-    // every stream is finished: the rest of the ring is final
-    while (stored + kSlab <= n) { store_slabs(stored, std::integral_constant<uint32_t, 1u>{}); stored += kSlab; }
-    for (uint32_t j = stored + lane; j < n; j += kWave)
-        Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & kRingMask], lds_lut);
-
-    if (lane < N) {
-        const uint32_t bits_read = abit - (first_word << 5);
-        if (((bits_read + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
-    }
-    err = wave_or(err);
-    if (err && lane == 0) report(p.status, err);
+    // no more blocks: the expanding and storing wavefronts finish what is logged
+    if (lane == 0) ctl[kOver] = 1u;
 }
 
 template <int OUT, bool PER_CHANNEL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))   // 2 workgroups per CU; more buys nothing
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3)))   // one workgroup per CU
 void decode_merged(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, LargeLds>(p); }
 
 template <int OUT, bool PER_CHANNEL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 6)))   // 3 workgroups per CU
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 6)))   // two workgroups per CU
 void decode_merged_small(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, SmallLds>(p); }
+
 
 // ---------------------------------------------------------------------------------------------
 // Sec. II-B alone.
@@ -1469,7 +1480,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_tables_kernel(const uint3
     const uint32_t tid = threadIdx.x;
     const uint32_t L = 1u << table_log;
     const uint32_t* f = freqs + size_t(blockIdx.x) * ANSZP_ALPHABET;
-    uint32_t* out = tables + (size_t(blockIdx.x) << (table_log + 2));
+    uint32_t* out = tables + size_t(blockIdx.x) * table_stride_words(table_log);
     if (tid < ANSZP_ALPHABET) freq[tid] = f[tid];
     __syncthreads();
     if (tid == 0) {
@@ -1491,7 +1502,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_tables_kernel(const uint3
     }
     __syncthreads();
     if (total != L) {                                   // not a normalised row: an all-zero table and a status bit
-        for (uint32_t i = tid; i < 4u * L; i += kBuildThreads) out[i] = 0u;
+        for (uint32_t i = tid; i < 8u * L; i += kBuildThreads) out[i] = 0u;
         if (tid == 0 && status) report(status, ANSZP_ST_BAD_FREQ);
         return;
     }
@@ -1524,37 +1535,49 @@ __global__ __launch_bounds__(kBuildThreads) void build_tables_kernel(const uint3
         st_newX[rank] = static_cast<uint16_t>((v << shift) - L);
     }
     __syncthreads();
+    // every word the planes below do not fill is zero
+    for (uint32_t i = tid; i < 2u * L; i += kBuildThreads) { out[i] = 0u; if (i < L) out[3u * L + i] = 0u; }
+    __syncthreads();
     for (uint32_t X = tid; X < L; X += kBuildThreads) {
-        out[2u * L + X] = uint32_t(st_newX[X]) | (uint32_t(st_nb[X]) << 16) | (uint32_t(st_sym[X]) << 24);
-        out[3u * L + X] = 0u;
+        out[table_triples_offset(table_log) + X] = uint32_t(st_newX[X]) | (uint32_t(st_nb[X]) << 16) | (uint32_t(st_sym[X]) << 24);
+        if (L <= 256u) {                                // Sec. II-A: three bytes per state
+            uint8_t* bytes = reinterpret_cast<uint8_t*>(out + table_bytes_offset(table_log));
+            bytes[3u * X] = st_sym[X];
+            bytes[3u * X + 1u] = st_nb[X];
+            bytes[3u * X + 2u] = static_cast<uint8_t>(st_newX[X]);
+        }
     }
-    // look-ahead entries: up to kMaxMerged steps merged into one look-up, indexed by the state and the next bit
+    // look-ahead entries: up to kLookaheadMaxSymbols steps merged into one look-up, indexed by the state and
+    // the next bit; a run never passes through state 0 (a stream then always ends where an entry ends)
     const uint32_t dominant = dominant_sym;
+    uint32_t* ahead = out + table_lookahead_offset(table_log);
     for (uint32_t e = tid; e < 2u * L; e += kBuildThreads) {
         const uint32_t X = e >> 1, b = e & 1u;
         uint32_t Y = X, count = 0, bits = 0, last_sym = 0, saved_Y = 0, saved_count = 0;
-        bool took_b = false;
+        bool took_b = false, may_take_b = true;
         int32_t base = 0;
         for (;;) {
             const uint32_t n = st_nb[Y];
-            const bool room = count + 1u < kMaxMerged;                 // another symbol may follow this one
-            if (n == 0u && room) { ++count; Y = st_newX[Y]; continue; }
-            if (n == 1u && room && !took_b && uint32_t(st_sym[Y]) == dominant) {
+            const bool room = count + 1u < kLookaheadMaxSymbols;       // another symbol may follow this one
+            const bool is_dominant = uint32_t(st_sym[Y]) == dominant;
+            if (is_dominant && room && n == 0u && st_newX[Y] != 0u) { ++count; Y = st_newX[Y]; continue; }
+            if (is_dominant && room && n == 1u && !took_b && may_take_b && (uint32_t(st_newX[Y]) | b) != 0u) {
                 saved_Y = Y; saved_count = count;
                 took_b = true; ++count; Y = uint32_t(st_newX[Y]) | b;
                 continue;
             }
-            if (took_b && 1u + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {    // too many bits for one look-up: stop at the 1-bit step
-                Y = saved_Y; count = saved_count;
-                bits = 1u; base = int32_t(2u * st_newX[Y]); last_sym = st_sym[Y];
-                break;
+            if (took_b && 1u + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {    // too many bits for one look-up: the 1-bit step is the last
+                Y = saved_Y; count = saved_count; took_b = false; may_take_b = false;
+                continue;
             }
             bits = (took_b ? 1u : 0u) + n;
             base = int32_t(2u * st_newX[Y]) - (took_b ? int32_t(b << (n + 1u)) : 0);
             last_sym = st_sym[Y];
+            ++count;
             break;
         }
-        out[e] = (31u - bits) | (last_sym << 8) | (count << 16) | (uint32_t(base) << 18);
+        ahead[2u * e] = lookahead_first_word(bits, count, last_sym, X == 0u);
+        ahead[2u * e + 1u] = lookahead_second_word(base);
     }
 }
 
@@ -1598,10 +1621,13 @@ void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, b
         hipLaunchKernelGGL(decode_stepwise_shared<OUT>, dim3((n_chunks + kSharedWaves - 1) / kSharedWaves),
                            dim3(kSharedWaves * kWave), 0, s, p, n_chunks);
     else if (stepwise) hipLaunchKernelGGL(decode_stepwise<OUT>, dim3(n_chunks), dim3(kWave), 0, s, p);
-    else if (small && per_channel) hipLaunchKernelGGL((decode_merged_small<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
-    else if (small) hipLaunchKernelGGL((decode_merged_small<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
-    else if (per_channel) hipLaunchKernelGGL((decode_merged<OUT, true>), dim3(n_chunks), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL((decode_merged<OUT, false>), dim3(n_chunks), dim3(kBlock), 0, s, p);
+    else {
+        const dim3 grid(mapped_workgroups(n_chunks));
+        if (small && per_channel) hipLaunchKernelGGL((decode_merged_small<OUT, true>), grid, dim3(kBlock), 0, s, p);
+        else if (small) hipLaunchKernelGGL((decode_merged_small<OUT, false>), grid, dim3(kBlock), 0, s, p);
+        else if (per_channel) hipLaunchKernelGGL((decode_merged<OUT, true>), grid, dim3(kBlock), 0, s, p);
+        else hipLaunchKernelGGL((decode_merged<OUT, false>), grid, dim3(kBlock), 0, s, p);
+    }
 }
 
 int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
@@ -1622,6 +1648,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     p.n_scales = a->scales ? a->n_scales : 0; p.out_elems = a->out_elems;
     p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
     p.n_cus = device_cus();
+    p.n_chunks = static_cast<uint32_t>(a->n_chunks);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
     // chunks whose compressed words cannot fit the look-ahead kernel's LDS window would all take its
@@ -1651,7 +1678,7 @@ int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
     if (!freqs_host || !tables_dev) return ANSZP_E_NULL;
     if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_tables < 1) return ANSZP_E_RANGE;
     if (reinterpret_cast<uintptr_t>(tables_dev) & 15) return ANSZP_E_RANGE;
-    const size_t entries = size_t(n_tables) << (table_log + 2);
+    const size_t entries = size_t(n_tables) * table_stride_words(table_log);
     uint32_t* staging = nullptr;
     if (hipHostMalloc(reinterpret_cast<void**>(&staging), entries * sizeof(uint32_t), hipHostMallocDefault) != hipSuccess)
         return ANSZP_E_NOMEM;

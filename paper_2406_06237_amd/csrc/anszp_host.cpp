@@ -6,6 +6,7 @@
 // newX; rate depends on how symbols are spread over states), Sec. III-A (one table per
 // layer), Sec. III-B (parallel streams sharing one table).
 #include "anszp.h"
+#include "anszp_layout.h"
 
 #include <algorithm>
 #include <cstring>
@@ -14,8 +15,6 @@
 #include <vector>
 
 namespace {
-
-constexpr uint32_t kMaxMerged = 4;   // symbols one look-ahead entry may emit
 
 bool freqs_ok(const uint32_t* f, int table_log) {
     uint64_t total = 0;
@@ -77,15 +76,17 @@ void build_step_table(const uint32_t* f, int table_log, StepTable& t) {
     }
 }
 
-// One table = 4L words: [0, 2L) look-ahead entries indexed by 2X + b (b = the next stream bit,
-// peeked, not yet consumed), [2L, 3L) the paper's triple per state, [3L, 4L) zero.
+// One table (layout: anszp_layout.h): the byte table of Sec. II-A for L <= 256, the paper's triple
+// per state, and the look-ahead entries indexed by 2X + b (b = the next stream bit, peeked, not yet
+// consumed).
 //
-// A look-ahead entry is the same automaton with up to kMaxMerged steps merged into one look-up:
-// starting in state X with next bit b it emits c-1 copies of the dominant symbol (the symbol with
-// f > L/2: empty-label transitions, and at most one of its 1-bit transitions, which consumes b)
-// and then one more symbol, having consumed T <= 12 stream bits in all.  With v = the next T+1
-// stream bits read most significant first (so v ends in the new peeked bit), the next index is
-// base + v.
+// A look-ahead entry is the same automaton with up to kLookaheadMaxSymbols steps merged into one
+// look-up: starting in state X with next bit b it emits c-1 copies of the dominant symbol (the
+// symbol with f > L/2: empty-label transitions, and at most one of its 1-bit transitions, which
+// consumes b) and then one more symbol, having consumed T <= 12 stream bits in all.  With v = the
+// next T+1 stream bits read most significant first (so v ends in the new peeked bit), the next
+// index is base + v.  A run never passes through state 0: the step that arrives there is the
+// entry's last.  Every stream ends in state 0, so a stream always ends where an entry ends.
 void build_one_table(const uint32_t* f, int table_log, uint32_t* out) {
     const uint32_t L = 1u << table_log;
     StepTable t;
@@ -93,35 +94,50 @@ void build_one_table(const uint32_t* f, int table_log, uint32_t* out) {
     int dominant = -1;
     for (int s = 0; s < ANSZP_ALPHABET; ++s)
         if (f[s] > L / 2) dominant = s;
+    std::memset(out, 0, size_t(table_stride_words(table_log)) * sizeof(uint32_t));
+    uint32_t* triples = out + table_triples_offset(table_log);
+    uint32_t* ahead = out + table_lookahead_offset(table_log);
+    if (L <= 256) {                                       // Sec. II-A: three bytes per state
+        uint8_t* bytes = reinterpret_cast<uint8_t*>(out + table_bytes_offset(table_log));
+        for (uint32_t X = 0; X < L; ++X) {
+            bytes[3 * X] = t.sym[X];
+            bytes[3 * X + 1] = t.nb[X];
+            bytes[3 * X + 2] = static_cast<uint8_t>(t.newX[X]);
+        }
+    }
     for (uint32_t X = 0; X < L; ++X) {
-        out[2 * L + X] = uint32_t(t.newX[X]) | (uint32_t(t.nb[X]) << 16) | (uint32_t(t.sym[X]) << 24);
-        out[3 * L + X] = 0;
+        triples[X] = uint32_t(t.newX[X]) | (uint32_t(t.nb[X]) << 16) | (uint32_t(t.sym[X]) << 24);
         for (uint32_t b = 0; b < 2; ++b) {
             uint32_t Y = X, count = 0, bits = 0;
-            bool took_b = false;
+            bool took_b = false, may_take_b = true;
             uint32_t saved_Y = 0, saved_count = 0;
             int32_t base = 0;
             uint32_t last_sym = 0;
             for (;;) {
                 const uint32_t n = t.nb[Y];
-                const bool room = count + 1 < kMaxMerged;          // another symbol may follow this one
-                if (n == 0 && room) { ++count; Y = t.newX[Y]; continue; }
-                if (n == 1 && room && !took_b && int(t.sym[Y]) == dominant) {
+                const bool room = count + 1 < kLookaheadMaxSymbols;   // another symbol may follow this one
+                const bool is_dominant = int(t.sym[Y]) == dominant;
+                // a step of the dominant symbol whose bits are known (none, or the peeked one) joins the
+                // run unless it arrives in state 0
+                if (is_dominant && room && n == 0 && t.newX[Y] != 0) { ++count; Y = t.newX[Y]; continue; }
+                if (is_dominant && room && n == 1 && !took_b && may_take_b && (t.newX[Y] | b) != 0) {
                     saved_Y = Y; saved_count = count;
                     took_b = true; ++count; Y = t.newX[Y] | b;
                     continue;
                 }
-                if (took_b && 1 + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {   // too many bits for one look-up: stop at the 1-bit step
-                    Y = saved_Y; count = saved_count; took_b = false;
-                    bits = 1; base = int32_t(2 * t.newX[Y]); last_sym = t.sym[Y];
-                    break;
+                if (took_b && 1 + n > uint32_t(ANSZP_MAX_TABLE_LOG)) {   // too many bits for one look-up: the 1-bit step is the last
+                    Y = saved_Y; count = saved_count; took_b = false; may_take_b = false;
+                    continue;
                 }
+                // the entry's last symbol: its n bits are read into the next index
                 bits = (took_b ? 1 : 0) + n;
                 base = int32_t(2 * t.newX[Y]) - (took_b ? int32_t(b << (n + 1)) : 0);
                 last_sym = t.sym[Y];
+                ++count;
                 break;
             }
-            out[2 * X + b] = (31u - bits) | (last_sym << 8) | (count << 16) | (uint32_t(base) << 18);
+            ahead[2 * (2 * X + b)] = lookahead_first_word(bits, count, last_sym, X == 0);
+            ahead[2 * (2 * X + b) + 1] = lookahead_second_word(base);
         }
     }
 }
@@ -234,7 +250,7 @@ int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, 
         if (!freqs_ok(freqs + size_t(t) * ANSZP_ALPHABET, table_log)) return ANSZP_E_FREQ;
     try {
         for (int t = 0; t < n_tables; ++t)
-            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + (size_t(t) << (table_log + 2)));
+            build_one_table(freqs + size_t(t) * ANSZP_ALPHABET, table_log, tables + size_t(t) * table_stride_words(table_log));
     } catch (const std::bad_alloc&) {
         return ANSZP_E_NOMEM;
     }

@@ -71,11 +71,16 @@ def test_tables_equal_oracle_tables(orc, R):
         f = B.split_table(t)
         sym, nb, newX = orc.decode_table(row, R)
         assert np.array_equal(f["sym"], sym) and np.array_equal(f["nb"], nb) and np.array_equal(f["newX"], newX)
+        # the three-bytes-per-state table of Sec. II-A, for tables it can hold (at most 256 states)
+        if L <= 256:
+            assert np.array_equal(f["bytes"], orc.decode_table_bytes(row, R))
+        else:
+            assert not f["bytes"].any()
 
 
 def _lookahead_decode(t, words, x0, n, dominant):
-    """Decode n symbols with the look-ahead entries only (pure Python), returning symbols and bits consumed
-    at the last entry boundary not after the stream's end."""
+    """Decode n symbols with the look-ahead entries only (pure Python), returning symbols, symbols emitted,
+    bits consumed, the last index, and whether the last look-up started in an entry marked as state 0."""
     bits = int.from_bytes(np.asarray(words, dtype=np.uint32).tobytes(), "little")
 
     def peek(pos, k):                                   # next k stream bits, first bit on top
@@ -88,6 +93,7 @@ def _lookahead_decode(t, words, x0, n, dominant):
     idx = 2 * x0 + peek(0, 1)
     while len(out) < n:
         T, c = int(t["la_bits"][idx]), int(t["la_count"][idx])
+        assert int(t["la_state0"][idx]) == (1 if idx >> 1 == 0 else 0)
         out.extend([dominant] * (c - 1))
         out.append(int(t["la_sym"][idx]))
         idx = int(t["la_base"][idx]) + peek(pos, T + 1)
@@ -113,21 +119,23 @@ def test_lookahead_entries_decode_what_the_oracle_encodes(orc, R):
         sym = W.sample_symbols(pmf, n, int(rng.integers(1 << 30)))
         f = orc.normalize(np.bincount(sym, minlength=256), R)
         t = B.split_table(B.build_tables_host(f[None, :], R)[0])
-        assert np.all(t["la_pad"] == 0) and np.all(t["tail"] == 0)
-        assert int(t["la_bits"].max()) <= 12 and int(t["la_count"].max()) <= 4
+        assert np.all(t["la_pad"] == 0) and np.all(t["zero"] == 0) and np.all(t["la_base_rem"] == 0)
+        assert int(t["la_bits"].max()) <= 12 and int(t["la_count"].max()) <= 8
+        assert np.array_equal(t["la_shift"], 31 - t["la_bits"]) and np.array_equal(t["la_count_low"], t["la_count"])
         dominant = int(np.argmax(f)) if f.max() > L // 2 else 255
         for length in (n, 1, 2, 7, 100):
             words, x0 = orc.encode_stream(sym[:length], f, R)
             out, emitted, pos, idx = _lookahead_decode(t, words, x0, length, dominant)
             assert np.array_equal(out, sym[:length])
-            if emitted == length:                       # stream ended on an entry boundary
-                _, _, total = orc.decode_stream(words, x0, length, f, R)
-                assert pos == total and idx >> 1 == 0
+            # an entry never passes through state 0, so every stream ends where an entry ends
+            assert emitted == length
+            _, _, total = orc.decode_stream(words, x0, length, f, R)
+            assert pos == total and idx >> 1 == 0
         # entries with and without look-ahead agree when there is no dominant symbol
         if f.max() <= L // 2:
             assert np.all(t["la_count"] == 1)
-            la = B.build_tables_host(f[None, :], R)[0][:2 * L].reshape(L, 2)
-            assert np.array_equal(la[:, 0], la[:, 1])
+            la = B.build_tables_host(f[None, :], R)[0][4 * L:8 * L].reshape(L, 2, 2)
+            assert np.array_equal(la[1:, 0], la[1:, 1])
             assert np.array_equal(t["la_bits"].reshape(L, 2)[:, 0], t["nb"])
             assert np.array_equal(t["la_sym"].reshape(L, 2)[:, 0], t["sym"])
             assert np.array_equal(t["la_base"].reshape(L, 2)[:, 0], 2 * t["newX"].astype(np.int32))
@@ -174,7 +182,7 @@ def test_host_error_codes():
     lib = B.lib()
     f = np.zeros(256, dtype=np.uint32)
     f[0] = 255
-    t = np.zeros(4 * 256, dtype=np.uint32)
+    t = np.zeros(B.table_words(1, 8), dtype=np.uint32)
     assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == -3          # sum != 2^R
     f[0] = 256
     assert lib.anszp_build_tables_host(f.ctypes.data, 1, 8, t.ctypes.data) == 0
