@@ -149,10 +149,10 @@ def split_table(tables: np.ndarray):
     return {"newX": (lo & 0xFFFF).astype(np.uint16), "nb": ((lo >> 16) & 0xFF).astype(np.uint8),
             "sym": (lo >> 24).astype(np.uint8),
             "bytes": np.ascontiguousarray(t[..., :L]).view(np.uint8)[..., :3 * L],
-            "la_bits": ((first >> 16) & 15).astype(np.uint8), "la_shift": (first & 31).astype(np.uint8),
-            "la_pad": (((first >> 5) & 7) | (((first >> 11) & 31) << 3)).astype(np.uint8),
-            "la_sym": (first >> 24).astype(np.uint8), "la_count": (((first >> 20) & 7) + 1).astype(np.uint8),
-            "la_count_low": (((first >> 8) & 7) + 1).astype(np.uint8), "la_state0": ((first >> 23) & 1).astype(np.uint8),
+            "la_bits": ((first >> 24) & 15).astype(np.uint8), "la_shift": (first & 31).astype(np.uint8),
+            "la_pad": (((first >> 5) & 15) | (((first >> 12) & 15) << 4)).astype(np.uint8),
+            "la_sym": ((first >> 16) & 0xFF).astype(np.uint8), "la_count": (((first >> 28) & 7) + 1).astype(np.uint8),
+            "la_count_low": (((first >> 9) & 7) + 1).astype(np.uint8), "la_state0": (first >> 31).astype(np.uint8),
             "la_base": base8 // 8, "la_base_rem": base8 % 8,
             "zero": np.concatenate([t[..., L:2 * L], t[..., 3 * L:4 * L]], axis=-1)}
 

@@ -37,7 +37,8 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kBlock = 768;                    // twelve wavefronts stage, eight of them stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
-constexpr uint32_t kLogSlotBytes = 9u * kWave * 2u + kWave * 4u;   // nine rows of 16 bits per lane, one of 32
+constexpr uint32_t kBlockLookups = 16u;        // look-ups a lane makes per block of the look-ahead kernel
+constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + kWave * 4u;   // seventeen rows of 16 bits per lane, one of 32
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
 // LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states (64 KiB of
@@ -45,11 +46,11 @@ constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over betw
 // of up to 2^11 states, shorter windows) leaves room for two workgroups per CU.
 struct LargeLds {
     static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 4096u, kRingElems = 16u * 1024u;
-    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 1u;
+    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 1u;
 };
 struct SmallLds {
     static constexpr uint32_t kTableLog = 11u, kPayloadWords = 2048u, kRingElems = 8u * 1024u;
-    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 2u;
+    static constexpr uint32_t kLogSlots = 2u, kWorkgroupsPerCu = 2u;
 };
 
 struct DecodeParams {
@@ -890,17 +891,17 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
     const uint32_t n = p.n_chunks;
     if (n > kPairScanRounds * THREADS) return Unit{u, u < n ? 1u : 0u};
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = uniform(tid >> 6);
-    uint32_t mine[kPairScanRounds], before[kPairScanRounds];
+    // (chunk i - 1 of an odd i sits in the lane below: blocks of 64 chunks start at even numbers)
+    const uint32_t rounds = (n + THREADS - 1u) / THREADS;
+    uint32_t mine[kPairScanRounds];
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k)
+        mine[k] = k < rounds ? p.chunks[min(k * THREADS + tid, n - 1u)].layer_id : 0u;
 #pragma unroll
     for (uint32_t k = 0; k < kPairScanRounds; ++k) {
         const uint32_t i = k * THREADS + tid;
-        mine[k] = p.chunks[min(i, n - 1u)].layer_id;
-        before[k] = p.chunks[min(i ? i - 1u : 0u, n - 1u)].layer_id;
-    }
-#pragma unroll
-    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
-        const uint32_t i = k * THREADS + tid;
-        const bool second = (i & 1u) && mine[k] == before[k];
+        const uint32_t below = __shfl_up(mine[k], 1, kWave);          // by every lane: the even lanes are the sources
+        const bool second = (i & 1u) && mine[k] == below;
         const uint64_t starts = __ballot(i < n && !second);
         if (lane == 0) masks[k * kWaves + wave] = starts;
     }
@@ -935,7 +936,7 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
 // The look-ahead kernel.  One workgroup = one unit (one or two chunks of a layer), twelve wavefronts:
 // all stage, then eight keep a task each, four per chunk:
 //   decode   lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
-//            table) through the look-ahead entries, in blocks of 8 look-ups with no per-step checks,
+//            table) through the look-ahead entries, in blocks of 16 look-ups with no per-step checks,
 //            and logs 16 bits of every entry it passes;
 //   expand   turns logged entries into symbols in the chunk's LDS ring (an entry stands for c symbols:
 //            c-1 copies of the dominant symbol, which the ring holds as background, then its own),
@@ -943,7 +944,7 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
 //            holds the stream's last symbol must end with it and arrive in state 0 (entries never pass
 //            through state 0), having read the stream's words and no more;
 //   store x2 move finished slabs of the ring to global memory, even and odd slabs, 16 bytes per lane.
-// A lane joins a block while its stream is unfinished and the ring has room for 8 entries of 8 symbols
+// A lane joins a block while its stream is unfinished and the ring has room for 16 entries of 8 symbols
 // (what the storing wavefronts have stored decides); a stream that ends inside a block goes on through
 // whatever follows it: the table keeps every index in range, the window of compressed words is
 // clamped to the chunk, and symbols beyond the chunk's last land in ring slots nobody reads again.
@@ -955,20 +956,21 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each), per chunk
     constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
     constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks in flight between decoding and expanding wavefront
-    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: words, hand-over words, block headers, positions, log
+    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: words, hand-over words, positions, log
     constexpr uint32_t kRingOff = kTableBytes;
     constexpr uint32_t kLutOff = kRingOff + 2u * kRingElems;
-    constexpr uint32_t kPipeOff = kLutOff + 512u;
-    constexpr uint32_t kWordsBytes = (kPayloadWords + 8u) * 4u;
+    constexpr uint32_t kSimdOff = kLutOff + 512u;                  // SIMD of each wavefront
+    constexpr uint32_t kPipeOff = kSimdOff + 64u;
+    constexpr uint32_t kTailWords = 12u;                            // zero words behind a chunk's last: a window of seven words may start at the last
+    constexpr uint32_t kWordsBytes = (kPayloadWords + kTailWords) * 4u;
     constexpr uint32_t kCtlOff = kWordsBytes;                       // within a chunk's area
-    constexpr uint32_t kHdrOff = kCtlOff + 64u;
-    constexpr uint32_t kProgOff = kHdrOff + kLogSlots * 8u;
+    constexpr uint32_t kProgOff = kCtlOff + 64u;
     constexpr uint32_t kLogOff = kProgOff + kWave * 4u;
     constexpr uint32_t kPipeBytes = kLogOff + kLogSlots * kLogSlotBytes;
     constexpr uint32_t kLdsBytes = kPipeOff + 2u * kPipeBytes;
     static_assert(kTableBytes % kRingElems == 0u && (kRingElems & (kRingElems - 1u)) == 0u, "rings aligned to their size");
-    static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u && kHdrOff % 8u == 0u, "LDS layout");
-    static_assert(kRingElems >= 2u * 8u * kLookaheadMaxSymbols * kWave && kRingElems % kSlab == 0u, "a lane may run a block ahead of a full slab");
+    static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u, "LDS layout");
+    static_assert(kRingElems % kSlab == 0u, "whole slabs");
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
     static_assert(kLdsBytes * 8u < (1u << 22), "bit positions count from the start of LDS");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
@@ -1023,14 +1025,14 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     uint4 wv01 = wv00, wv11 = wv10;
     if constexpr (kWordLoads > 1u) { wv01 = wsrc0[min(tid + kBlock, w_last0)]; wv11 = wsrc1[min(tid + kBlock, w_last1)]; }
     uint32_t tail0 = 0, tail1 = 0;                        // the words behind the last whole row of four
-    if (in0 && tid < 8 && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= kPayloadWords)
+    if (in0 && tid < kTailWords && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= kPayloadWords)
         tail0 = p.payload[c0.payload_offset + (quads0 << 2) + tid];
-    if (in1 && tid < 8 && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
+    if (in1 && tid < kTailWords && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
         tail1 = p.payload[c1.payload_offset + (quads1 << 2) + tid];
     const uint32_t top = src[table_triples_offset(p.table_log) + L - 1u];   // state L-1 carries the dominant symbol if there is one
     const anszp_layer_t lay = p.layers[layer_id];
     // While those loads are in flight: the SIMD every wavefront runs on (HW_ID bits 4..5).
-    uint32_t* const simd_of = reinterpret_cast<uint32_t*>(lds + kLutOff);      // (the symbol table is written after the barrier)
+    uint32_t* const simd_of = reinterpret_cast<uint32_t*>(lds + kSimdOff);
     if (lane == 0) simd_of[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
     __syncthreads();
     // Tasks.  A lone wavefront's speed is set by how often its SIMD lets it issue, so the two decoding
@@ -1042,31 +1044,37 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     {
         constexpr uint32_t kWaves = kBlock / kWave;
         const uint32_t flip = G::kWorkgroupsPerCu > 1u ? ((blockIdx.x / max(p.n_cus, 1u)) & 1u) * 2u : 0u;
-        //                         decode 0, decode 1, expand 0, expand 1, store 0/0, store 1/0, store 0/1, store 1/1
-        const uint32_t want[8] = {0u ^ flip, 1u ^ flip, 2u ^ flip, 3u ^ flip, 2u ^ flip, 3u ^ flip, 3u ^ flip, 2u ^ flip};
-        const uint32_t role_task[8] = {kDecode, kDecode, kExpand, kExpand, kStore0, kStore1, kStore0, kStore1};
-        const uint32_t role_pipe[8] = {0u, 1u, 0u, 1u, 0u, 0u, 1u, 1u};
-        const uint32_t mine = simd_of[lane % kWaves];
-        uint32_t simd[kWaves];
-#pragma unroll
-        for (uint32_t w = 0; w < kWaves; ++w) simd[w] = __builtin_amdgcn_readlane(mine, w);
-        uint32_t taken = 0;
-#pragma unroll
-        for (uint32_t r = 0; r < 8u; ++r) {
-            uint32_t pick = kWaves;
-#pragma unroll
-            for (uint32_t w = 0; w < kWaves; ++w)
-                if (pick == kWaves && !((taken >> w) & 1u) && simd[w] == want[r]) pick = w;
-#pragma unroll
-            for (uint32_t w = 0; w < kWaves; ++w)          // no wavefront on that SIMD: any free one
-                if (pick == kWaves && !((taken >> w) & 1u)) pick = w;
-            taken |= 1u << pick;
-            if (pick == wave) { task = role_task[r]; pipe = role_pipe[r]; }
+        const uint32_t theirs = lane < kWaves ? simd_of[lane] : 4u;                  // lane w: the SIMD of wavefront w
+        const uint32_t my_simd = __builtin_amdgcn_readlane(theirs, wave);
+        const uint64_t same = __ballot(theirs == my_simd);
+        const uint32_t rank = static_cast<uint32_t>(__popcll(same & ((1ull << wave) - 1ull)));
+        const bool even = __popcll(__ballot(theirs == 0u)) == 3 && __popcll(__ballot(theirs == 1u)) == 3 &&
+                          __popcll(__ballot(theirs == 2u)) == 3 && __popcll(__ballot(theirs == 3u)) == 3;
+        // three wavefronts on every SIMD: SIMD 0, 1: the first decodes chunk 0, 1, the others leave;
+        // SIMD 2, 3: the first expands chunk 0, 1, the second stores for chunk 0, the third for chunk 1.
+        // Any other placement: tasks by wavefront number.
+        const uint32_t s2 = even ? my_simd ^ flip : (wave < 4u ? wave : (wave - 4u) & 1u);
+        const uint32_t r2 = even ? rank : (wave < 4u ? 0u : wave < 8u ? 1u + ((wave - 4u) >> 1) : 3u);
+#ifdef ANSZP_STORES_WITH_EXPAND
+        if (s2 < 2u) {
+            if (r2 == 0u) { task = kDecode; pipe = s2; }
+        } else if (r2 == 0u) {
+            task = kExpand; pipe = s2 - 2u;
+        } else if (r2 < 3u) {
+            task = kStore0 + ((r2 - 1u) ^ (s2 - 2u)); pipe = r2 - 1u;
         }
+#else
+        // SIMD 0, 1: decode chunk 0, 1, and one storing wavefront of either chunk; SIMD 2, 3: expand chunk 0, 1
+        if (s2 < 2u) {
+            if (r2 == 0u) { task = kDecode; pipe = s2; }
+            else if (r2 < 3u) { task = kStore0 + ((r2 - 1u) ^ s2); pipe = r2 - 1u; }
+        } else if (r2 == 0u) {
+            task = kExpand; pipe = s2 - 2u;
+        }
+#endif
     }
     pipe = uniform(pipe);
     task = uniform(task);
-    __syncthreads();                                      // simd_of is read; its place becomes the symbol table
 
     // ---- stage: look-ahead entries, both chunks' compressed words, symbol -> bf16, ring background, hand-over words
     {
@@ -1085,14 +1093,18 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         uint4* wdst1 = reinterpret_cast<uint4*>(lds + kPipeOff + kPipeBytes);
         if (quads0) { wdst0[min(tid, w_last0)] = wv00; if constexpr (kWordLoads > 1u) wdst0[min(tid + kBlock, w_last0)] = wv01; }
         if (quads1) { wdst1[min(tid, w_last1)] = wv10; if constexpr (kWordLoads > 1u) wdst1[min(tid + kBlock, w_last1)] = wv11; }
-        if (tid < 8) {                                    // tail words, then zeros for clamped reads
+        if (tid < kTailWords) {                           // tail words, then zeros for clamped reads
             reinterpret_cast<uint32_t*>(lds + kPipeOff)[(quads0 << 2) + tid] = tail0;
             reinterpret_cast<uint32_t*>(lds + kPipeOff + kPipeBytes)[(quads1 << 2) + tid] = tail1;
         }
         if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
-        if (tid < 2u * (16u + kLogSlots * 2u)) {          // hand-over words and block headers of both chunks
-            const uint32_t q = tid / (16u + kLogSlots * 2u), i = tid % (16u + kLogSlots * 2u);
+        if (tid < 2u * 16u) {                             // hand-over words of both chunks
+            const uint32_t q = tid / 16u, i = tid % 16u;
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = (i == kStored1) ? kSlab : 0u;
+        }
+        if (tid < 2u * kLogSlots * kWave) {               // the rows of bit positions: no lane has taken part in any block
+            const uint32_t q = tid / (kLogSlots * kWave), i = tid % (kLogSlots * kWave);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + kBlockLookups * 2u * kWave + 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
         }
         if (tid < 2u * kWave) {                           // where every stream is: its first element, or nothing to wait for
             const uint32_t q = tid / kWave, l = tid % kWave;
@@ -1208,13 +1220,13 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             if (n_words != 0u) err |= ANSZP_ST_BAD_LENGTH;
         }
         uint32_t expanded = 0, spins = 0;
+        constexpr uint32_t kBitRow = (kBlockLookups + 1u) * 2u * kWave;      // offset of the row of bit positions in a log slot
         for (;;) {
             const uint32_t slot = expanded & (kLogSlots - 1u);
-            uint32_t logged_v, ent[9], bit_after;
-            uint64_t lanes_v;
+            uint32_t logged_v, ent[kBlockLookups + 1u], bit_after;
+            // one batch of LDS reads, the count first (no wait between them; LDS serves a wavefront's reads in order)
             asm volatile(
                 "ds_read_b32 %[lg], %[ctla]\n"
-                "ds_read_b64 %[lanes], %[hdra] offset:%[hdr]\n"
                 "ds_read_u16 %[e0], %[loga]\n"
                 "ds_read_u16 %[e1], %[loga] offset:128\n"
                 "ds_read_u16 %[e2], %[loga] offset:256\n"
@@ -1224,14 +1236,23 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 "ds_read_u16 %[e6], %[loga] offset:768\n"
                 "ds_read_u16 %[e7], %[loga] offset:896\n"
                 "ds_read_u16 %[e8], %[loga] offset:1024\n"
-                "ds_read_b32 %[ba], %[bita] offset:1152\n"
+                "ds_read_u16 %[e9], %[loga] offset:1152\n"
+                "ds_read_u16 %[e10], %[loga] offset:1280\n"
+                "ds_read_u16 %[e11], %[loga] offset:1408\n"
+                "ds_read_u16 %[e12], %[loga] offset:1536\n"
+                "ds_read_u16 %[e13], %[loga] offset:1664\n"
+                "ds_read_u16 %[e14], %[loga] offset:1792\n"
+                "ds_read_u16 %[e15], %[loga] offset:1920\n"
+                "ds_read_u16 %[e16], %[loga] offset:2048\n"
+                "ds_read_b32 %[ba], %[bita] offset:%[bitrow]\n"
                 "s_waitcnt lgkmcnt(0)\n"
-                : [lg] "=&v"(logged_v), [lanes] "=&v"(lanes_v), [ba] "=&v"(bit_after),
+                : [lg] "=&v"(logged_v), [ba] "=&v"(bit_after),
                   [e0] "=&v"(ent[0]), [e1] "=&v"(ent[1]), [e2] "=&v"(ent[2]), [e3] "=&v"(ent[3]), [e4] "=&v"(ent[4]),
-                  [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7]), [e8] "=&v"(ent[8])
-                : [ctla] "v"(pipe_off + kCtlOff), [hdra] "v"(pipe_off + slot * 8u),
-                  [loga] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 2u),
-                  [bita] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 4u), [hdr] "n"(kHdrOff)
+                  [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7]), [e8] "=&v"(ent[8]), [e9] "=&v"(ent[9]),
+                  [e10] "=&v"(ent[10]), [e11] "=&v"(ent[11]), [e12] "=&v"(ent[12]), [e13] "=&v"(ent[13]), [e14] "=&v"(ent[14]),
+                  [e15] "=&v"(ent[15]), [e16] "=&v"(ent[16])
+                : [ctla] "v"(pipe_off + kCtlOff), [loga] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 2u),
+                  [bita] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 4u), [bitrow] "n"(kBitRow)
                 : "memory");
             if (uniform(logged_v) == expanded) {         // nothing new
                 if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
@@ -1247,32 +1268,35 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 continue;
             }
             spins = 0;
-            if ((lanes_v >> lane) & 1u) {                // the same word in every lane: did this lane take part?
+            // a lane that took part in this block tagged its bit position with the block's number
+            if (!ended && (bit_after >> 22) == (expanded & 0x3FFu)) {
                 const uint32_t ne_before = ne;
+                // log entries 0..15: bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0; 16: address of the next entry
 #pragma unroll
-                for (uint32_t k = 0; k < 8u; ++k) {      // log entry: bits 0..3 T | 4..6 c-1 | 7 entry of state 0 | 8..15 symbol
-                    const uint32_t last = __umul24((ent[k] >> 4) & 7u, N) + ne;
-                    ring8[last & kRingMask] = static_cast<uint8_t>(ent[k] >> 8);
+                for (uint32_t k = 0; k < kBlockLookups; ++k) {
+                    const uint32_t last = __umul24((ent[k] >> 12) & 7u, N) + ne;
+                    ring8[last & kRingMask] = static_cast<uint8_t>(ent[k]);
                     ne = last + N;
                 }
-                if (!ended && ne >= lane_end) {          // the stream's last symbol lies in this block: find its entry
+                if (ne >= lane_end) {                    // the stream's last symbol lies in this block: find its entry
                     ended = true;
                     uint32_t pos = ne_before, bits = at_bit;
                     bool found = false;
 #pragma unroll
-                    for (uint32_t k = 0; k < 8u; ++k) {
-                        const uint32_t after = pos + (((ent[k] >> 4) & 7u) + 1u) * N;
-                        bits += ent[k] & 15u;
+                    for (uint32_t k = 0; k < kBlockLookups; ++k) {
+                        const uint32_t after = pos + (((ent[k] >> 12) & 7u) + 1u) * N;
+                        bits += (ent[k] >> 8) & 15u;
                         if (!found && after >= lane_end) {
                             found = true;
                             // it must end with the entry, in state 0, the stream's words read and no more
-                            if (after != lane_end || !((ent[k + 1u] >> 7) & 1u)) err |= ANSZP_ST_BAD_STATE;
+                            const bool in_state_0 = k + 1u < kBlockLookups ? (ent[k + 1u] >> 15) != 0u : ent[kBlockLookups] < 16u;
+                            if (after != lane_end || !in_state_0) err |= ANSZP_ST_BAD_STATE;
                             if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
                         }
                         pos = after;
                     }
                 }
-                at_bit = bit_after;
+                at_bit = bit_after & 0x3FFFFFu;
             }
             ++expanded;
             // publish the lanes' positions, then the count, issued after the ring writes above
@@ -1304,39 +1328,48 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         asm volatile("ds_read_b128 %[v], %[ctla]\n s_waitcnt lgkmcnt(0)\n" : [v] "=v"(v) : [ctla] "v"(pipe_off + kCtlOff) : "memory");
         return v;
     };
-    // A block, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and what a
-    // look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
+    // A block of 16 look-ups, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and
+    // what a look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
     //   v = r >> (31 - T)            the next T+1 stream bits, r = the window's first word bit-reversed
     //   address' = 8 v + 8 base      Sec. II-A: newX + bits, plus the peeked bit
-    //   e' = table[address'];  log[k] = e (its upper half);  w0..w3 >>= T (funnel shift);  r = bitrev(w0)
-    //   sum += e                     byte 0: 31 - T per look-up; bits 8..13: c - 1 per look-up
-    // At the start of a block every lane loads four words of its stream (128 bits, at least 97 of them
-    // ahead of its bit position: 8 look-ups use at most 8 * 12 and peek one more).  The window is shifted
+    //   e' = table[address'];  log[k] = e (its upper half);  window >>= T (funnel shifts);  r = bitrev(w0)
+    //   sum += e                     bits 0..8: 31 - T per look-up; bits 9..15: c - 1 per look-up
+    // At the start of a block every lane loads seven words of its stream (224 bits, at least 193 of them
+    // ahead of its bit position: 16 look-ups use at most 16 * 12 and peek one more).  The window is shifted
     // only as far up as a later look-up of the block can still read: with j look-ups to follow only the
-    // first 12 j + 1 bits matter, so w0 is shifted by every look-up but the last, w1 while four or more
-    // follow, w2 while seven follow, w3 never.  A block ends by logging what each lane's next look-up
-    // starts from and the lane's bit position, publishing the lanes that took part and the new count of
-    // blocks, reloading every lane's four words and recomputing who may join the next block from the
-    // words the other wavefronts publish (read at the start of the block, so their latency is hidden).
+    // first 12 j + 1 bits matter, so register m is shifted while 12 j + 1 > 32 m (a register that is no
+    // longer shifted goes stale; what it feeds into its lower neighbour lies beyond that reach).  A block
+    // ends by logging where each lane's next look-up starts and the lane's bit position tagged with the
+    // block's number (a lane that sat the block out keeps an older tag), publishing the new count of
+    // blocks, reloading every lane's words and recomputing who may join the next block from the words
+    // the other wavefronts publish (read at the start of the block, so their latency is hidden).
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
+#define ANSZP_SHIFT_W3 ANSZP_SHIFT_W2 "v_alignbit_b32 v31, v32, v31, v35\n"
+#define ANSZP_SHIFT_W4 ANSZP_SHIFT_W3 "v_alignbit_b32 v32, v33, v32, v35\n"
+#define ANSZP_SHIFT_W5 ANSZP_SHIFT_W4 "v_alignbit_b32 v33, v34, v33, v35\n"
 #define ANSZP_LOOKUP(ELO, EHI, FB, K, SHIFT, SUM)                                      \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
-        "v_lshrrev_b32 v36, " ELO ", v33\n"                                            \
+        "v_lshrrev_b32 v36, " ELO ", v53\n"                                            \
         "v_lshl_add_u32 v36, v36, 3, " EHI "\n"                                        \
         "ds_read_b64 " FB ", v36\n"                                                    \
         "ds_write_b16_d16_hi v42, " ELO " offset:" K "*128\n"                          \
         "v_not_b32 v35, " ELO "\n"                                                     \
         SHIFT                                                                          \
-        "v_bfrev_b32 v33, v28\n"                                                       \
+        "v_bfrev_b32 v53, v28\n"                                                       \
         SUM
 #define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_mov_b32 v37, v24\n")
 #define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n")
 #define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n")
-    static_assert(ANSZP_MAX_TABLE_LOG <= 12, "the reach of a look-up assumed by the window shifts");
-    static_assert(kLogSlotBytes == 1408u, "log slot: nine rows of 16 bits per lane, then a row of 32");
-    const uint32_t room = kRingElems - 8u * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 8 entries of 8 symbols
+    static_assert(ANSZP_MAX_TABLE_LOG <= 12 && kBlockLookups == 16u, "the reach of a look-up assumed by the window shifts");
+    static_assert(kLogSlotBytes == 2432u, "log slot: seventeen rows of 16 bits per lane, then a row of 32");
+    const uint32_t reach = kBlockLookups * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 16 entries of 8 symbols
+    if (reach >= kRingElems) {                                            // (the host picks a geometry with room)
+        if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+        return;
+    }
+    const uint32_t room = kRingElems - reach;
     while (!gave_up) {
         if (__ballot(ne < lane_end) == 0) break;          // every stream has ended
         const uint4 seen = hand_over_words();
@@ -1350,62 +1383,68 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         spins = 0;
         uint32_t logged_v = logged;
         asm volatile(
-            "v_mov_b32 v24, %[elo]\n v_mov_b32 v25, %[ehi]\n v_mov_b32 v32, %[ab]\n v_mov_b32 v39, %[ne]\n"
+            "v_mov_b32 v24, %[elo]\n v_mov_b32 v25, %[ehi]\n v_mov_b32 v52, %[ab]\n v_mov_b32 v39, %[ne]\n"
             "v_mov_b32 v43, %[ctla]\n"
             "v_readfirstlane_b32 s44, %[logged]\n"
             "s_mov_b64 s[40:41], exec\n"
             "v_cmp_gt_u32 vcc, %[lim], v39\n"
-            "v_lshrrev_b32 v38, 3, v32\n"
+            "v_lshrrev_b32 v38, 3, v52\n"
             "v_and_b32 v38, 0x1ffffffc, v38\n"
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
+            "ds_read2_b32 v[32:33], v38 offset0:4 offset1:5\n"
+            "ds_read_b32 v34, v38 offset:24\n"
             "ds_read_b128 v[48:51], v43\n"             /* blocks logged, blocks expanded, elements stored (two) */
             "s_and_b64 exec, s[40:41], vcc\n"          /* lanes that run this block (some do) */
             "1:\n"
             "s_and_b32 s45, s44, %[slotmask]\n"        /* the block's log slot */
-            "s_mul_i32 s46, s45, 1408\n"
+            "s_mul_i32 s46, s45, 2432\n"
             "v_add_u32 v42, s46, %[lanelog]\n"         /* this lane's 16-bit column in the slot */
             "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the row of bit positions */
             "s_waitcnt lgkmcnt(1)\n"                   /* the window words; the hand-over words were asked for last */
-            "v_alignbit_b32 v28, v29, v28, v32\n"
-            "v_alignbit_b32 v29, v30, v29, v32\n"
-            "v_alignbit_b32 v30, v31, v30, v32\n"
-            "v_lshrrev_b32 v31, v32, v31\n"
-            "v_bfrev_b32 v33, v28\n"
-            ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1)
-            ANSZP_BA("3", ANSZP_SHIFT_W1) ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0)
-            ANSZP_AB("6", ANSZP_SHIFT_W0)
-            "s_waitcnt lgkmcnt(1)\n"                   /* the eighth look-up shifts no window */
-            "v_lshrrev_b32 v36, v26, v33\n"
+            "v_alignbit_b32 v28, v29, v28, v52\n"
+            "v_alignbit_b32 v29, v30, v29, v52\n"
+            "v_alignbit_b32 v30, v31, v30, v52\n"
+            "v_alignbit_b32 v31, v32, v31, v52\n"
+            "v_alignbit_b32 v32, v33, v32, v52\n"
+            "v_alignbit_b32 v33, v34, v33, v52\n"
+            "v_lshrrev_b32 v34, v52, v34\n"
+            "v_bfrev_b32 v53, v28\n"
+            ANSZP_FIRST("0", ANSZP_SHIFT_W5) ANSZP_BA("1", ANSZP_SHIFT_W5) ANSZP_AB("2", ANSZP_SHIFT_W4) ANSZP_BA("3", ANSZP_SHIFT_W4)
+            ANSZP_AB("4", ANSZP_SHIFT_W4) ANSZP_BA("5", ANSZP_SHIFT_W3) ANSZP_AB("6", ANSZP_SHIFT_W3) ANSZP_BA("7", ANSZP_SHIFT_W3)
+            ANSZP_AB("8", ANSZP_SHIFT_W2) ANSZP_BA("9", ANSZP_SHIFT_W2) ANSZP_AB("10", ANSZP_SHIFT_W1) ANSZP_BA("11", ANSZP_SHIFT_W1)
+            ANSZP_AB("12", ANSZP_SHIFT_W1) ANSZP_BA("13", ANSZP_SHIFT_W0) ANSZP_AB("14", ANSZP_SHIFT_W0)
+            "s_waitcnt lgkmcnt(1)\n"                   /* the sixteenth look-up shifts no window */
+            "v_lshrrev_b32 v36, v26, v53\n"
             "v_lshl_add_u32 v36, v36, 3, v27\n"
             "ds_read_b64 v[24:25], v36\n"
-            "ds_write_b16_d16_hi v42, v26 offset:7*128\n"
+            "ds_write_b16_d16_hi v42, v26 offset:15*128\n"
+            "ds_write_b16 v42, v36 offset:16*128\n"   /* where the next look-up starts: below 16 in state 0 */
             "v_add_u32 v37, v37, v26\n"
-            "v_and_b32 v46, 0xff, v37\n"
-            "v_bfe_u32 v35, v37, 8, 6\n"
-            "v_sub_u32 v46, 31*8, v46\n"               /* stream bits the block consumed */
-            "v_add_u32 v35, 8, v35\n"                  /* symbols it stands for */
-            "v_add_u32 v32, v32, v46\n"
-            "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
-            "ds_write_b32 v47, v32 offset:1152\n"      /* bit position after the block */
-            "v_mov_b32 v44, exec_lo\n"
-            "v_mov_b32 v45, exec_hi\n"
-            "s_lshl_b32 s46, s45, 3\n"
-            "v_add_u32 v40, s46, v43\n"
-            "s_add_u32 s44, s44, 1\n"
-            "v_mov_b32 v46, s44\n"
-            "s_waitcnt lgkmcnt(2)\n"                   /* the entry the next look-up starts from */
-            "ds_write_b16_d16_hi v42, v24 offset:8*128\n"
-            "ds_write_b64 v40, v[44:45] offset:64\n"   /* header: lanes taking part */
-            "ds_write_b32 v43, v46\n"                  /* publish the block */
-            "v_readfirstlane_b32 s46, v49\n"           /* blocks expanded when the previous block ended */
+            "v_and_b32 v46, 0x1ff, v37\n"
+            "v_sub_u32 v46, 31*16, v46\n"              /* stream bits the block consumed */
+            "v_add_u32 v52, v52, v46\n"
+            "v_lshl_or_b32 v46, s44, 22, v52\n"       /* bit position after the block, tagged with the block's number */
+            "ds_write_b32 v47, v46 offset:%[bitrow]\n"
+            "s_mov_b64 s[42:43], exec\n"
             "s_mov_b64 exec, s[40:41]\n"               /* every lane reloads its words */
-            "v_lshrrev_b32 v38, 3, v32\n"
+            "v_lshrrev_b32 v38, 3, v52\n"
             "v_and_b32 v38, 0x1ffffffc, v38\n"
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
+            "ds_read2_b32 v[32:33], v38 offset0:4 offset1:5\n"
+            "ds_read_b32 v34, v38 offset:24\n"
+            "s_mov_b64 exec, s[42:43]\n"               /* the block's lanes again */
+            "v_bfe_u32 v35, v37, 9, 7\n"
+            "v_add_u32 v35, 16, v35\n"                 /* symbols the block stands for */
+            "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
+            "s_add_u32 s44, s44, 1\n"
+            "v_mov_b32 v46, s44\n"
+            "ds_write_b32 v43, v46\n"                  /* publish the block */
+            "v_readfirstlane_b32 s46, v49\n"           /* blocks expanded when the previous block ended */
+            "s_mov_b64 exec, s[40:41]\n"
             "v_min_u32 v50, v50, v51\n"                /* elements stored when the previous block ended: every */
             "v_add_u32 v50, %[room], v50\n"            /* slab below the next one of either storing wavefront */
             "v_min_u32 v50, %[lend], v50\n"
@@ -1419,22 +1458,25 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "2:\n"
             "s_mov_b64 exec, s[40:41]\n"
             "s_waitcnt lgkmcnt(0)\n"
-            "v_mov_b32 %[elo], v24\n v_mov_b32 %[ehi], v25\n v_mov_b32 %[ab], v32\n v_mov_b32 %[ne], v39\n"
+            "v_mov_b32 %[elo], v24\n v_mov_b32 %[ehi], v25\n v_mov_b32 %[ab], v52\n v_mov_b32 %[ne], v39\n"
             "v_mov_b32 %[logged], s44\n"
             : [elo] "+v"(e.x), [ehi] "+v"(e.y), [ab] "+v"(abit), [ne] "+v"(ne), [logged] "+v"(logged_v)
             : [lim] "v"(limit), [lend] "v"(lane_end), [room] "s"(uniform(room)), [nstr] "s"(uniform(N)),
               [lastw] "s"(uniform(last_word)), [ctla] "s"(uniform(pipe_off + kCtlOff)),
               [lanelog] "v"(pipe_off + kLogOff + lane * 2u), [lanebit] "v"(pipe_off + kLogOff + lane * 4u),
-              [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u)
-            : "memory", "vcc", "scc", "s40", "s41", "s44", "s45", "s46", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31",
-              "v32", "v33", "v35", "v36", "v37", "v38", "v39", "v40", "v42", "v43", "v44", "v45", "v46", "v47",
-              "v48", "v49", "v50", "v51");
+              [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [bitrow] "n"((kBlockLookups + 1u) * 2u * kWave)
+            : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "v24", "v25", "v26", "v27", "v28", "v29", "v30",
+              "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v42", "v43", "v46", "v47",
+              "v48", "v49", "v50", "v51", "v52", "v53");
         logged = uniform(logged_v);
     }
 #undef ANSZP_FIRST
 #undef ANSZP_AB
 #undef ANSZP_BA
 #undef ANSZP_LOOKUP
+#undef ANSZP_SHIFT_W5
+#undef ANSZP_SHIFT_W4
+#undef ANSZP_SHIFT_W3
 #undef ANSZP_SHIFT_W2
 #undef ANSZP_SHIFT_W1
 #undef ANSZP_SHIFT_W0
@@ -1659,7 +1701,8 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     const bool shared = mode == 3;
     const bool streaming = mode == 4 || (mode == 0 && stepwise);
     // small tables and short chunks: the variant that fits three workgroups on a CU
-    const bool small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords;
+    const bool small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords &&
+                       kBlockLookups * kLookaheadMaxSymbols * a->n_streams < SmallLds::kRingElems;     // a block must fit its ring
     const bool per_channel = a->scales != nullptr && a->n_scales != 0;
     switch (a->out_dtype) {
         case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;

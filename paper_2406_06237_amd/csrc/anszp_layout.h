@@ -26,15 +26,16 @@ ANSZP_HD uint32_t table_bytes_offset(uint32_t) { return 0u; }
 ANSZP_HD uint32_t table_triples_offset(uint32_t table_log) { return 2u << table_log; }
 ANSZP_HD uint32_t table_lookahead_offset(uint32_t table_log) { return 4u << table_log; }
 
-// Look-ahead entry, first word (what the decoding wavefront accumulates and logs):
-//   bits 0..4   31 - T, T <= 12 the stream bits the entry consumes     bits 5..7   zero
-//   bits 8..10  c - 1, c <= 8 the symbols the entry stands for         bits 11..15 zero
-//   bits 16..19 T      bits 20..22 c - 1      bit 23  set for the entries of state 0
-//   bits 24..31 the entry's last symbol (the c - 1 before it are the dominant symbol)
+// Look-ahead entry, first word.  The lower half is what the decoding wavefront shifts by and adds up over a
+// block of 16 look-ups (no field's sum reaches the next field); the upper half is what it logs:
+//   bits 0..4   31 - T, T <= 12 the stream bits the entry consumes     bits 5..8   zero
+//   bits 9..11  c - 1, c <= 8 the symbols the entry stands for         bits 12..15 zero
+//   bits 16..23 the entry's last symbol (the c - 1 before it are the dominant symbol)
+//   bits 24..27 T      bits 28..30 c - 1      bit 31  set for the entries of state 0
 // second word: 8 * base as a signed number; the next entry is number base + v, v the next T + 1
 // stream bits read most significant first (the last of them is the new peeked bit).
 ANSZP_HD uint32_t lookahead_first_word(uint32_t T, uint32_t count, uint32_t symbol, bool state_zero) {
-    return (31u - T) | ((count - 1u) << 8) | (T << 16) | ((count - 1u) << 20) | (state_zero ? 1u << 23 : 0u) | (symbol << 24);
+    return (31u - T) | ((count - 1u) << 9) | (symbol << 16) | (T << 24) | ((count - 1u) << 28) | (state_zero ? 1u << 31 : 0u);
 }
 ANSZP_HD uint32_t lookahead_second_word(int32_t base) { return static_cast<uint32_t>(base * 8); }
 
