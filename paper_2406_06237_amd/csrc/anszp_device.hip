@@ -37,8 +37,8 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kBlock = 768;                    // twelve wavefronts stage, eight of them stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
-constexpr uint32_t kBlockLookups = 16u;        // look-ups a lane makes per block of the look-ahead kernel
-constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + kWave * 4u;   // seventeen rows of 16 bits per lane, one of 32
+constexpr uint32_t kBlockLookups = 8u;         // look-ups a lane makes per block of the look-ahead kernel
+constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + kWave * 4u;   // nine rows of 16 bits per lane, one of 32
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
 // LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states (64 KiB of
@@ -46,11 +46,11 @@ constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over betw
 // of up to 2^11 states, shorter windows) leaves room for two workgroups per CU.
 struct LargeLds {
     static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 4096u, kRingElems = 16u * 1024u;
-    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 1u;
+    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 1u;
 };
 struct SmallLds {
     static constexpr uint32_t kTableLog = 11u, kPayloadWords = 2048u, kRingElems = 8u * 1024u;
-    static constexpr uint32_t kLogSlots = 2u, kWorkgroupsPerCu = 2u;
+    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 2u;
 };
 
 struct DecodeParams {
@@ -876,43 +876,91 @@ struct Flusher {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Which chunks a workgroup of the look-ahead kernel decodes.  Two consecutive chunks of one layer
-// (chunk numbers 2j and 2j+1) form a unit and share one workgroup and its LDS copy of the layer's
-// table; any other chunk is a unit of its own.  The host does not see the descriptors, so every
-// workgroup finds unit number `u` itself: thread t looks at chunks t, t + kBlock, ...; a 64-bit mask
-// per 64 chunks marks those that start a unit; the masks go through LDS and every wavefront picks
-// the u-th set bit.  Launches with more than kPairScanChunks chunks do not pair.
+// Which chunks a workgroup of the look-ahead kernel decodes.  A workgroup that has a CU to itself decodes a
+// chunk fastest (its wavefronts get a SIMD each); two consecutive chunks of one layer (chunk numbers 2j and
+// 2j+1) can share a workgroup and its LDS copy of the layer's table, each a little slower.  A launch with
+// more chunks than the chip holds workgroups at once therefore pairs chunks, the most compressible first
+// (few stream words: short chains), and only as many as it takes: of the levels below (stream bits per
+// symbol under which a chunk may be paired) the lowest that leaves no more units than `capacity`.  The host
+// does not see the descriptors, so every workgroup finds unit number `u` itself: thread t looks at chunks
+// t, t + THREADS, ...; per level a 64-bit mask per 64 chunks marks those that start a unit; the masks go
+// through LDS and every wavefront counts the levels' units and picks the u-th set bit of the chosen level.
+// Launches with more than kPairScanRounds * THREADS chunks do not pair.
 constexpr uint32_t kPairScanRounds = 4u;
+constexpr uint32_t kPairLevels = 8u;
 struct Unit { uint32_t first, count; };          // count 0: no such unit
 
+// level from which a chunk may be paired, by its stream bits per symbol (level 0: nothing is paired; 7: everything)
+__device__ __forceinline__ uint32_t pair_level_of(uint32_t payload_words, uint32_t n_symbols) {
+    const float bits = 32.0f * static_cast<float>(payload_words), n = static_cast<float>(n_symbols);
+    uint32_t level = 7u;
+    if (bits < 1.2f * n) level = 6u;
+    if (bits < 1.0f * n) level = 5u;
+    if (bits < 0.8f * n) level = 4u;
+    if (bits < 0.7f * n) level = 3u;
+    if (bits < 0.6f * n) level = 2u;
+    if (bits < 0.5f * n) level = 1u;
+    return level;
+}
+
 template <uint32_t THREADS>
-__device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint64_t* masks /* LDS, kPairScanRounds * THREADS / 64 */) {
+__device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint32_t capacity,
+                                          uint64_t* masks /* LDS, kPairLevels * (kPairScanRounds * THREADS / 64 + 1) words of 8 bytes */) {
     constexpr uint32_t kWaves = THREADS / kWave;
-    const uint32_t n = p.n_chunks;
-    if (n > kPairScanRounds * THREADS) return Unit{u, u < n ? 1u : 0u};
-    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = uniform(tid >> 6);
-    // (chunk i - 1 of an odd i sits in the lane below: blocks of 64 chunks start at even numbers)
-    const uint32_t rounds = (n + THREADS - 1u) / THREADS;
-    uint32_t mine[kPairScanRounds];
-#pragma unroll
-    for (uint32_t k = 0; k < kPairScanRounds; ++k)
-        mine[k] = k < rounds ? p.chunks[min(k * THREADS + tid, n - 1u)].layer_id : 0u;
-#pragma unroll
-    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
-        const uint32_t i = k * THREADS + tid;
-        const uint32_t below = __shfl_up(mine[k], 1, kWave);          // by every lane: the even lanes are the sources
-        const bool second = (i & 1u) && mine[k] == below;
-        const uint64_t starts = __ballot(i < n && !second);
-        if (lane == 0) masks[k * kWaves + wave] = starts;
-    }
-    __syncthreads();
-    // every wavefront on its own: lane m holds mask m
     constexpr uint32_t kMasks = kPairScanRounds * kWaves;
     static_assert(kMasks <= kWave, "one mask per lane");
-    const uint64_t m = lane < kMasks ? masks[lane] : 0ull;
-    uint32_t total;
-    const uint32_t ahead = wave_exclusive_sum(static_cast<uint32_t>(__popcll(m)), &total);
+    const uint32_t n = p.n_chunks;
+    if (n > kPairScanRounds * THREADS || n <= capacity) return Unit{u, u < n ? 1u : 0u};
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = uniform(tid >> 6);
+    const uint32_t rounds = (n + THREADS - 1u) / THREADS;
+    uint32_t* const units = reinterpret_cast<uint32_t*>(masks + kPairLevels * kMasks);     // units per level
+    uint32_t layer[kPairScanRounds], words[kPairScanRounds], symbols[kPairScanRounds];
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
+        layer[k] = 0u; words[k] = 0u; symbols[k] = 1u;
+        if (k < rounds) {
+            const anszp_chunk_t& c = p.chunks[min(k * THREADS + tid, n - 1u)];
+            layer[k] = c.layer_id; words[k] = c.payload_words; symbols[k] = c.n_symbols;
+        }
+    }
+    if (tid < kPairLevels) units[tid] = 0u;              // (while the loads are in flight)
+    __syncthreads();
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
+        if (k >= rounds) break;
+        const uint32_t i = k * THREADS + tid;
+        const uint32_t level = pair_level_of(words[k], symbols[k]);
+        // (chunk i - 1 of an odd i sits in the lane below: blocks of 64 chunks start at even numbers; the
+        // shuffles are done by every lane, the even lanes are their sources)
+        const uint32_t layer_below = __shfl_up(layer[k], 1, kWave), level_below = __shfl_up(level, 1, kWave);
+        // from this level on, chunk i is the second of a pair
+        const uint32_t second_from = ((i & 1u) && layer[k] == layer_below) ? max(level, level_below) : kPairLevels;
+#pragma unroll
+        for (uint32_t j = 0; j < kPairLevels; ++j) {
+            const uint64_t starts = __ballot(i < n && !(j >= second_from));
+            if (lane == 0) {
+                masks[j * kMasks + k * kWaves + wave] = starts;
+                atomicAdd(&units[j], static_cast<uint32_t>(__popcll(starts)));
+            }
+        }
+    }
+    __syncthreads();
+    // the lowest level that leaves no more units than there is room for (the last pairs all it can)
+    uint32_t chosen = kPairLevels - 1u, total = 0;
+    {
+        const uint32_t mine = units[lane % kPairLevels];
+        bool picked = false;
+#pragma unroll
+        for (uint32_t j = 0; j < kPairLevels; ++j) {
+            const uint32_t count = __builtin_amdgcn_readlane(mine, j);
+            if (!picked && (count <= capacity || j == kPairLevels - 1u)) { picked = true; chosen = j; total = count; }
+        }
+    }
+    chosen = uniform(chosen);
     if (u >= total) return Unit{0u, 0u};
+    const uint64_t m = lane < rounds * kWaves ? masks[chosen * kMasks + lane] : 0ull;
+    uint32_t unused;
+    const uint32_t ahead = wave_exclusive_sum(static_cast<uint32_t>(__popcll(m)), &unused);
     const uint64_t holds = __ballot(lane < kMasks && ahead <= u && u < ahead + static_cast<uint32_t>(__popcll(m)));
     const uint32_t which = static_cast<uint32_t>(__ffsll(static_cast<unsigned long long>(holds))) - 1u;   // exactly one lane
     const uint32_t lo = __shfl(static_cast<uint32_t>(m), which, kWave), hi = __shfl(static_cast<uint32_t>(m >> 32), which, kWave);
@@ -936,7 +984,7 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
 // The look-ahead kernel.  One workgroup = one unit (one or two chunks of a layer), twelve wavefronts:
 // all stage, then eight keep a task each, four per chunk:
 //   decode   lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
-//            table) through the look-ahead entries, in blocks of 16 look-ups with no per-step checks,
+//            table) through the look-ahead entries, in blocks of 8 look-ups with no per-step checks,
 //            and logs 16 bits of every entry it passes;
 //   expand   turns logged entries into symbols in the chunk's LDS ring (an entry stands for c symbols:
 //            c-1 copies of the dominant symbol, which the ring holds as background, then its own),
@@ -944,7 +992,7 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
 //            holds the stream's last symbol must end with it and arrive in state 0 (entries never pass
 //            through state 0), having read the stream's words and no more;
 //   store x2 move finished slabs of the ring to global memory, even and odd slabs, 16 bytes per lane.
-// A lane joins a block while its stream is unfinished and the ring has room for 16 entries of 8 symbols
+// A lane joins a block while its stream is unfinished and the ring has room for 8 entries of 8 symbols
 // (what the storing wavefronts have stored decides); a stream that ends inside a block goes on through
 // whatever follows it: the table keeps every index in range, the window of compressed words is
 // clamped to the chunk, and symbols beyond the chunk's last land in ring slots nobody reads again.
@@ -961,7 +1009,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kLutOff = kRingOff + 2u * kRingElems;
     constexpr uint32_t kSimdOff = kLutOff + 512u;                  // SIMD of each wavefront
     constexpr uint32_t kPipeOff = kSimdOff + 64u;
-    constexpr uint32_t kTailWords = 12u;                            // zero words behind a chunk's last: a window of seven words may start at the last
+    constexpr uint32_t kTailWords = 8u;                             // zero words behind a chunk's last: a window of four words may start at the last
     constexpr uint32_t kWordsBytes = (kPayloadWords + kTailWords) * 4u;
     constexpr uint32_t kCtlOff = kWordsBytes;                       // within a chunk's area
     constexpr uint32_t kProgOff = kCtlOff + 64u;
@@ -989,7 +1037,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
 
-    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), reinterpret_cast<uint64_t*>(lds + kPipeOff));
+    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu,
+                                        reinterpret_cast<uint64_t*>(lds + kPipeOff));
     if (unit.count == 0u) return;
     // descriptors (the second repeats the first when the unit is a single chunk)
     const anszp_chunk_t c0 = p.chunks[unit.first], c1 = p.chunks[unit.first + unit.count - 1u];
@@ -1002,7 +1051,10 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     if ((!in0 && !in1) || lds_address(lds) != 0u) return;
     const uint32_t layer_id = in0 ? c0.layer_id : c1.layer_id;      // both alike when both are in bounds
 
-    // Issue every global read that depends only on the descriptors before waiting for any of them.
+    // Issue every global read that depends only on the descriptors before waiting for any of them (the
+    // stream headers first: they are used first).
+    const uint32_t hdr0 = (in0 && lane < N) ? p.stream_hdr[c0.stream_offset + lane] : 0u;
+    const uint32_t hdr1 = (in1 && lane < N) ? p.stream_hdr[c1.stream_offset + lane] : 0u;
     const uint32_t* src = p.tables + layer_id * table_stride_words(p.table_log);
     const uint4* tsrc = reinterpret_cast<const uint4*>(src + table_lookahead_offset(p.table_log));   // 2 entries per load
     const uint32_t t_last = L - 1u;
@@ -1014,8 +1066,6 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     if constexpr (kTableLoads > 3u) {
         tv3 = tsrc[min(tid + 3u * kBlock, t_last)]; tv4 = tsrc[min(tid + 4u * kBlock, t_last)]; tv5 = tsrc[min(tid + 5u * kBlock, t_last)];
     }
-    const uint32_t hdr0 = (in0 && lane < N) ? p.stream_hdr[c0.stream_offset + lane] : 0u;
-    const uint32_t hdr1 = (in1 && lane < N) ? p.stream_hdr[c1.stream_offset + lane] : 0u;
     const uint32_t quads0 = in0 ? min(c0.payload_words, kPayloadWords) >> 2 : 0u;
     const uint32_t quads1 = in1 ? min(c1.payload_words, kPayloadWords) >> 2 : 0u;
     const uint4* wsrc0 = quads0 ? reinterpret_cast<const uint4*>(p.payload + c0.payload_offset) : tsrc;
@@ -1031,7 +1081,10 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         tail1 = p.payload[c1.payload_offset + (quads1 << 2) + tid];
     const uint32_t top = src[table_triples_offset(p.table_log) + L - 1u];   // state L-1 carries the dominant symbol if there is one
     const anszp_layer_t lay = p.layers[layer_id];
-    // While those loads are in flight: the SIMD every wavefront runs on (HW_ID bits 4..5).
+    // While those loads are in flight: where every stream's words begin, and the SIMD every wavefront
+    // runs on (HW_ID bits 4..5).
+    uint32_t total_words0, total_words1;
+    const uint32_t first_word0 = wave_exclusive_sum(hdr0 >> 16, &total_words0), first_word1 = wave_exclusive_sum(hdr1 >> 16, &total_words1);
     uint32_t* const simd_of = reinterpret_cast<uint32_t*>(lds + kSimdOff);
     if (lane == 0) simd_of[wave] = (__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u;
     __syncthreads();
@@ -1055,23 +1108,16 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         // Any other placement: tasks by wavefront number.
         const uint32_t s2 = even ? my_simd ^ flip : (wave < 4u ? wave : (wave - 4u) & 1u);
         const uint32_t r2 = even ? rank : (wave < 4u ? 0u : wave < 8u ? 1u + ((wave - 4u) >> 1) : 3u);
-#ifdef ANSZP_STORES_WITH_EXPAND
-        if (s2 < 2u) {
-            if (r2 == 0u) { task = kDecode; pipe = s2; }
-        } else if (r2 == 0u) {
-            task = kExpand; pipe = s2 - 2u;
-        } else if (r2 < 3u) {
-            task = kStore0 + ((r2 - 1u) ^ (s2 - 2u)); pipe = r2 - 1u;
-        }
-#else
-        // SIMD 0, 1: decode chunk 0, 1, and one storing wavefront of either chunk; SIMD 2, 3: expand chunk 0, 1
-        if (s2 < 2u) {
+        if (unit.count == 1u) {
+            // one chunk: a SIMD per task (decode, expand, the two storing wavefronts)
+            if (r2 == 0u) task = s2;
+        } else if (s2 < 2u) {
+            // two chunks.  SIMD 0, 1: decode chunk 0, 1, and one storing wavefront of either chunk; SIMD 2, 3: expand chunk 0, 1
             if (r2 == 0u) { task = kDecode; pipe = s2; }
             else if (r2 < 3u) { task = kStore0 + ((r2 - 1u) ^ s2); pipe = r2 - 1u; }
         } else if (r2 == 0u) {
             task = kExpand; pipe = s2 - 2u;
         }
-#endif
     }
     pipe = uniform(pipe);
     task = uniform(task);
@@ -1102,9 +1148,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             const uint32_t q = tid / 16u, i = tid % 16u;
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = (i == kStored1) ? kSlab : 0u;
         }
-        if (tid < 2u * kLogSlots * kWave) {               // the rows of bit positions: no lane has taken part in any block
-            const uint32_t q = tid / (kLogSlots * kWave), i = tid % (kLogSlots * kWave);
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + kBlockLookups * 2u * kWave + 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
+        for (uint32_t t = tid; t < 2u * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
+            const uint32_t q = t / (kLogSlots * kWave), i = t % (kLogSlots * kWave);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + (kBlockLookups + 1u) * 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
         }
         if (tid < 2u * kWave) {                           // where every stream is: its first element, or nothing to wait for
             const uint32_t q = tid / kWave, l = tid % kWave;
@@ -1126,6 +1172,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const anszp_chunk_t c = pipe ? c1 : c0;
     const uint32_t hdr = pipe ? hdr1 : hdr0;
     const uint32_t pipe_off = kPipeOff + pipe * kPipeBytes;          // the chunk's area: its compressed words come first
+    // (a workgroup with a single chunk uses the space of both rings as one)
+    const uint32_t ring_elems = unit.count == 1u ? 2u * kRingElems : kRingElems;
+    const uint32_t ring_mask = ring_elems - 1u;
     uint8_t* const ring8 = lds + kRingOff + pipe * kRingElems;
     lds_flag_t* const ctl = (lds_flag_t*)(lds + pipe_off + kCtlOff);
     const uint32_t n = c.n_symbols;
@@ -1142,13 +1191,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         if (err && lane == 0) report(p.status, err);
         return;
     }
-    constexpr uint32_t kRingMask = kRingElems - 1u;
 
     // Slabs of the ring are final once every unfinished lane's next symbol lies beyond them.  A lane
     // takes elements 8*lane .. 8*lane+7 of each half of a slab, so that every store instruction writes
     // one contiguous run; the slots go back to the background value.
     auto store_slab = [&](uint32_t first_elem) {
-        uint8_t* q = ring8 + ((first_elem & kRingMask) + lane * 8u);         // the ring is a whole number of slabs
+        uint8_t* q = ring8 + ((first_elem & ring_mask) + lane * 8u);         // the ring is a whole number of slabs
         const uint2 lo = *reinterpret_cast<const uint2*>(q);
         const uint2 hi = *reinterpret_cast<const uint2*>(q + kSlab / 2u);
         *reinterpret_cast<uint2*>(q) = make_uint2(bg4, bg4);
@@ -1198,12 +1246,11 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         const uint32_t rest = n / kSlab * kSlab;
         if (((rest / kSlab) & 1u) == which)
             for (uint32_t j = rest + lane; j < n; j += kWave)
-                Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & kRingMask], lds_lut);
+                Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & ring_mask], lds_lut);
         return;
     }
 
-    uint32_t total_words;
-    const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
+    const uint32_t total_words = pipe ? total_words1 : total_words0, first_word = pipe ? first_word1 : first_word0;
     const uint32_t first_bit = (pipe_off + 4u * min(first_word, c.payload_words)) << 3;   // counted from the start of LDS
 
     if (task == kExpand) {
@@ -1221,61 +1268,18 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         }
         uint32_t expanded = 0, spins = 0;
         constexpr uint32_t kBitRow = (kBlockLookups + 1u) * 2u * kWave;      // offset of the row of bit positions in a log slot
-        for (;;) {
-            const uint32_t slot = expanded & (kLogSlots - 1u);
-            uint32_t logged_v, ent[kBlockLookups + 1u], bit_after;
-            // one batch of LDS reads, the count first (no wait between them; LDS serves a wavefront's reads in order)
-            asm volatile(
-                "ds_read_b32 %[lg], %[ctla]\n"
-                "ds_read_u16 %[e0], %[loga]\n"
-                "ds_read_u16 %[e1], %[loga] offset:128\n"
-                "ds_read_u16 %[e2], %[loga] offset:256\n"
-                "ds_read_u16 %[e3], %[loga] offset:384\n"
-                "ds_read_u16 %[e4], %[loga] offset:512\n"
-                "ds_read_u16 %[e5], %[loga] offset:640\n"
-                "ds_read_u16 %[e6], %[loga] offset:768\n"
-                "ds_read_u16 %[e7], %[loga] offset:896\n"
-                "ds_read_u16 %[e8], %[loga] offset:1024\n"
-                "ds_read_u16 %[e9], %[loga] offset:1152\n"
-                "ds_read_u16 %[e10], %[loga] offset:1280\n"
-                "ds_read_u16 %[e11], %[loga] offset:1408\n"
-                "ds_read_u16 %[e12], %[loga] offset:1536\n"
-                "ds_read_u16 %[e13], %[loga] offset:1664\n"
-                "ds_read_u16 %[e14], %[loga] offset:1792\n"
-                "ds_read_u16 %[e15], %[loga] offset:1920\n"
-                "ds_read_u16 %[e16], %[loga] offset:2048\n"
-                "ds_read_b32 %[ba], %[bita] offset:%[bitrow]\n"
-                "s_waitcnt lgkmcnt(0)\n"
-                : [lg] "=&v"(logged_v), [ba] "=&v"(bit_after),
-                  [e0] "=&v"(ent[0]), [e1] "=&v"(ent[1]), [e2] "=&v"(ent[2]), [e3] "=&v"(ent[3]), [e4] "=&v"(ent[4]),
-                  [e5] "=&v"(ent[5]), [e6] "=&v"(ent[6]), [e7] "=&v"(ent[7]), [e8] "=&v"(ent[8]), [e9] "=&v"(ent[9]),
-                  [e10] "=&v"(ent[10]), [e11] "=&v"(ent[11]), [e12] "=&v"(ent[12]), [e13] "=&v"(ent[13]), [e14] "=&v"(ent[14]),
-                  [e15] "=&v"(ent[15]), [e16] "=&v"(ent[16])
-                : [ctla] "v"(pipe_off + kCtlOff), [loga] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 2u),
-                  [bita] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 4u), [bitrow] "n"(kBitRow)
-                : "memory");
-            if (uniform(logged_v) == expanded) {         // nothing new
-                if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
-                    if (uniform(ctl[kLogged]) == expanded) break;
-                    continue;
-                }
-                if (uniform(ctl[kGaveUp])) return;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
-                    return;
-                }
-                __builtin_amdgcn_s_sleep(1);
-                continue;
-            }
-            spins = 0;
-            // a lane that took part in this block tagged its bit position with the block's number
-            if (!ended && (bit_after >> 22) == (expanded & 0x3FFu)) {
+        typedef __attribute__((address_space(3))) uint8_t lds_uint8_t;
+        const uint32_t ring_at = lds_address(ring8);     // a multiple of the ring's size: its bits and an element's index do not overlap
+        // One logged block: entries 0..7 (bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0), 8: address
+        // of the lane's next entry; the lane's bit position after the block, tagged with the block's number
+        // by the lanes that took part in it.
+        auto expand_block = [&](const uint32_t (&ent)[kBlockLookups + 1u], uint32_t bit_after, uint32_t block) {
+            if (!ended && (bit_after >> 22) == (block & 0x3FFu)) {
                 const uint32_t ne_before = ne;
-                // log entries 0..15: bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0; 16: address of the next entry
 #pragma unroll
                 for (uint32_t k = 0; k < kBlockLookups; ++k) {
                     const uint32_t last = __umul24((ent[k] >> 12) & 7u, N) + ne;
-                    ring8[last & kRingMask] = static_cast<uint8_t>(ent[k]);
+                    *reinterpret_cast<lds_uint8_t*>(static_cast<uintptr_t>((last & ring_mask) | ring_at)) = static_cast<uint8_t>(ent[k]);
                     ne = last + N;
                 }
                 if (ne >= lane_end) {                    // the stream's last symbol lies in this block: find its entry
@@ -1298,7 +1302,69 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                 }
                 at_bit = bit_after & 0x3FFFFFu;
             }
+        };
+        // Every pass reads the count of logged blocks and, in the same batch of LDS reads, the next two
+        // log slots: if the count (read first) says a block is there, what was read after it is the block.
+        // Two blocks per pass when the decoding wavefront is that far ahead: a pass costs about as much in
+        // waiting and bookkeeping as a block does in work.
+        static_assert(kLogSlots >= 2u, "two slots are read per pass");
+        for (;;) {
+            const uint32_t slot_a = expanded & (kLogSlots - 1u), slot_b = (expanded + 1u) & (kLogSlots - 1u);
+            uint32_t logged_v, ea[kBlockLookups + 1u], eb[kBlockLookups + 1u], bit_a, bit_b;
+            asm volatile(
+                "ds_read_b32 %[lg], %[ctla]\n"
+                "ds_read_u16 %[a0], %[loga]\n"
+                "ds_read_u16 %[a1], %[loga] offset:128\n"
+                "ds_read_u16 %[a2], %[loga] offset:256\n"
+                "ds_read_u16 %[a3], %[loga] offset:384\n"
+                "ds_read_u16 %[a4], %[loga] offset:512\n"
+                "ds_read_u16 %[a5], %[loga] offset:640\n"
+                "ds_read_u16 %[a6], %[loga] offset:768\n"
+                "ds_read_u16 %[a7], %[loga] offset:896\n"
+                "ds_read_u16 %[a8], %[loga] offset:1024\n"
+                "ds_read_b32 %[ba], %[bita] offset:%[bitrow]\n"
+                "ds_read_u16 %[b0], %[logb]\n"
+                "ds_read_u16 %[b1], %[logb] offset:128\n"
+                "ds_read_u16 %[b2], %[logb] offset:256\n"
+                "ds_read_u16 %[b3], %[logb] offset:384\n"
+                "ds_read_u16 %[b4], %[logb] offset:512\n"
+                "ds_read_u16 %[b5], %[logb] offset:640\n"
+                "ds_read_u16 %[b6], %[logb] offset:768\n"
+                "ds_read_u16 %[b7], %[logb] offset:896\n"
+                "ds_read_u16 %[b8], %[logb] offset:1024\n"
+                "ds_read_b32 %[bb], %[bitb] offset:%[bitrow]\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                : [lg] "=&v"(logged_v), [ba] "=&v"(bit_a), [bb] "=&v"(bit_b),
+                  [a0] "=&v"(ea[0]), [a1] "=&v"(ea[1]), [a2] "=&v"(ea[2]), [a3] "=&v"(ea[3]), [a4] "=&v"(ea[4]),
+                  [a5] "=&v"(ea[5]), [a6] "=&v"(ea[6]), [a7] "=&v"(ea[7]), [a8] "=&v"(ea[8]),
+                  [b0] "=&v"(eb[0]), [b1] "=&v"(eb[1]), [b2] "=&v"(eb[2]), [b3] "=&v"(eb[3]), [b4] "=&v"(eb[4]),
+                  [b5] "=&v"(eb[5]), [b6] "=&v"(eb[6]), [b7] "=&v"(eb[7]), [b8] "=&v"(eb[8])
+                : [ctla] "v"(pipe_off + kCtlOff),
+                  [loga] "v"(pipe_off + kLogOff + slot_a * kLogSlotBytes + lane * 2u), [bita] "v"(pipe_off + kLogOff + slot_a * kLogSlotBytes + lane * 4u),
+                  [logb] "v"(pipe_off + kLogOff + slot_b * kLogSlotBytes + lane * 2u), [bitb] "v"(pipe_off + kLogOff + slot_b * kLogSlotBytes + lane * 4u),
+                  [bitrow] "n"(kBitRow)
+                : "memory");
+            const uint32_t ahead = uniform(logged_v) - expanded;
+            if (ahead == 0u) {                           // nothing new
+                if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
+                    if (uniform(ctl[kLogged]) == expanded) break;
+                    continue;
+                }
+                if (uniform(ctl[kGaveUp])) return;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                    return;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                continue;
+            }
+            spins = 0;
+            expand_block(ea, bit_a, expanded);
             ++expanded;
+            if (ahead >= 2u) {
+                expand_block(eb, bit_b, expanded);
+                ++expanded;
+            }
             // publish the lanes' positions, then the count, issued after the ring writes above
             asm volatile("ds_write_b32 %[pa], %[ne]\n"
                          "ds_write_b32 %[ctla], %[ex] offset:4\n"
@@ -1328,14 +1394,14 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         asm volatile("ds_read_b128 %[v], %[ctla]\n s_waitcnt lgkmcnt(0)\n" : [v] "=v"(v) : [ctla] "v"(pipe_off + kCtlOff) : "memory");
         return v;
     };
-    // A block of 16 look-ups, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and
+    // A block of 8 look-ups, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and
     // what a look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
     //   v = r >> (31 - T)            the next T+1 stream bits, r = the window's first word bit-reversed
     //   address' = 8 v + 8 base      Sec. II-A: newX + bits, plus the peeked bit
     //   e' = table[address'];  log[k] = e (its upper half);  window >>= T (funnel shifts);  r = bitrev(w0)
-    //   sum += e                     bits 0..8: 31 - T per look-up; bits 9..15: c - 1 per look-up
-    // At the start of a block every lane loads seven words of its stream (224 bits, at least 193 of them
-    // ahead of its bit position: 16 look-ups use at most 16 * 12 and peek one more).  The window is shifted
+    //   sum += e                     bits 0..8: 31 - T per look-up; bits 9..15: c - 1 per look-up (sums of up to 16 fit)
+    // At the start of a block every lane loads four words of its stream (128 bits, at least 97 of them
+    // ahead of its bit position: 8 look-ups use at most 8 * 12 and peek one more).  The window is shifted
     // only as far up as a later look-up of the block can still read: with j look-ups to follow only the
     // first 12 j + 1 bits matter, so register m is shifted while 12 j + 1 > 32 m (a register that is no
     // longer shifted goes stale; what it feeds into its lower neighbour lies beyond that reach).  A block
@@ -1346,9 +1412,6 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
-#define ANSZP_SHIFT_W3 ANSZP_SHIFT_W2 "v_alignbit_b32 v31, v32, v31, v35\n"
-#define ANSZP_SHIFT_W4 ANSZP_SHIFT_W3 "v_alignbit_b32 v32, v33, v32, v35\n"
-#define ANSZP_SHIFT_W5 ANSZP_SHIFT_W4 "v_alignbit_b32 v33, v34, v33, v35\n"
 #define ANSZP_LOOKUP(ELO, EHI, FB, K, SHIFT, SUM)                                      \
         "s_waitcnt lgkmcnt(1)\n"                                                       \
         "v_lshrrev_b32 v36, " ELO ", v53\n"                                            \
@@ -1362,14 +1425,14 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_mov_b32 v37, v24\n")
 #define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n")
 #define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n")
-    static_assert(ANSZP_MAX_TABLE_LOG <= 12 && kBlockLookups == 16u, "the reach of a look-up assumed by the window shifts");
-    static_assert(kLogSlotBytes == 2432u, "log slot: seventeen rows of 16 bits per lane, then a row of 32");
-    const uint32_t reach = kBlockLookups * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 16 entries of 8 symbols
-    if (reach >= kRingElems) {                                            // (the host picks a geometry with room)
+    static_assert(ANSZP_MAX_TABLE_LOG <= 12 && kBlockLookups == 8u, "the reach of a look-up assumed by the window shifts");
+    static_assert(kLogSlotBytes == 1408u, "log slot: nine rows of 16 bits per lane, then a row of 32");
+    const uint32_t reach = kBlockLookups * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 8 entries of 8 symbols
+    if (reach >= ring_elems) {                                            // (the host picks a geometry with room)
         if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
         return;
     }
-    const uint32_t room = kRingElems - reach;
+    const uint32_t room = ring_elems - reach;
     while (!gave_up) {
         if (__ballot(ne < lane_end) == 0) break;          // every stream has ended
         const uint4 seen = hand_over_words();
@@ -1393,37 +1456,30 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "ds_read2_b32 v[32:33], v38 offset0:4 offset1:5\n"
-            "ds_read_b32 v34, v38 offset:24\n"
             "ds_read_b128 v[48:51], v43\n"             /* blocks logged, blocks expanded, elements stored (two) */
             "s_and_b64 exec, s[40:41], vcc\n"          /* lanes that run this block (some do) */
             "1:\n"
             "s_and_b32 s45, s44, %[slotmask]\n"        /* the block's log slot */
-            "s_mul_i32 s46, s45, 2432\n"
+            "s_mul_i32 s46, s45, 1408\n"
             "v_add_u32 v42, s46, %[lanelog]\n"         /* this lane's 16-bit column in the slot */
             "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the row of bit positions */
             "s_waitcnt lgkmcnt(1)\n"                   /* the window words; the hand-over words were asked for last */
             "v_alignbit_b32 v28, v29, v28, v52\n"
             "v_alignbit_b32 v29, v30, v29, v52\n"
             "v_alignbit_b32 v30, v31, v30, v52\n"
-            "v_alignbit_b32 v31, v32, v31, v52\n"
-            "v_alignbit_b32 v32, v33, v32, v52\n"
-            "v_alignbit_b32 v33, v34, v33, v52\n"
-            "v_lshrrev_b32 v34, v52, v34\n"
+            "v_lshrrev_b32 v31, v52, v31\n"
             "v_bfrev_b32 v53, v28\n"
-            ANSZP_FIRST("0", ANSZP_SHIFT_W5) ANSZP_BA("1", ANSZP_SHIFT_W5) ANSZP_AB("2", ANSZP_SHIFT_W4) ANSZP_BA("3", ANSZP_SHIFT_W4)
-            ANSZP_AB("4", ANSZP_SHIFT_W4) ANSZP_BA("5", ANSZP_SHIFT_W3) ANSZP_AB("6", ANSZP_SHIFT_W3) ANSZP_BA("7", ANSZP_SHIFT_W3)
-            ANSZP_AB("8", ANSZP_SHIFT_W2) ANSZP_BA("9", ANSZP_SHIFT_W2) ANSZP_AB("10", ANSZP_SHIFT_W1) ANSZP_BA("11", ANSZP_SHIFT_W1)
-            ANSZP_AB("12", ANSZP_SHIFT_W1) ANSZP_BA("13", ANSZP_SHIFT_W0) ANSZP_AB("14", ANSZP_SHIFT_W0)
-            "s_waitcnt lgkmcnt(1)\n"                   /* the sixteenth look-up shifts no window */
+            ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1) ANSZP_BA("3", ANSZP_SHIFT_W1)
+            ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0) ANSZP_AB("6", ANSZP_SHIFT_W0)
+            "s_waitcnt lgkmcnt(1)\n"                   /* the eighth look-up shifts no window */
             "v_lshrrev_b32 v36, v26, v53\n"
             "v_lshl_add_u32 v36, v36, 3, v27\n"
             "ds_read_b64 v[24:25], v36\n"
-            "ds_write_b16_d16_hi v42, v26 offset:15*128\n"
-            "ds_write_b16 v42, v36 offset:16*128\n"   /* where the next look-up starts: below 16 in state 0 */
+            "ds_write_b16_d16_hi v42, v26 offset:7*128\n"
+            "ds_write_b16 v42, v36 offset:8*128\n"   /* where the next look-up starts: below 16 in state 0 */
             "v_add_u32 v37, v37, v26\n"
             "v_and_b32 v46, 0x1ff, v37\n"
-            "v_sub_u32 v46, 31*16, v46\n"              /* stream bits the block consumed */
+            "v_sub_u32 v46, 31*8, v46\n"              /* stream bits the block consumed */
             "v_add_u32 v52, v52, v46\n"
             "v_lshl_or_b32 v46, s44, 22, v52\n"       /* bit position after the block, tagged with the block's number */
             "ds_write_b32 v47, v46 offset:%[bitrow]\n"
@@ -1434,11 +1490,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "ds_read2_b32 v[32:33], v38 offset0:4 offset1:5\n"
-            "ds_read_b32 v34, v38 offset:24\n"
             "s_mov_b64 exec, s[42:43]\n"               /* the block's lanes again */
             "v_bfe_u32 v35, v37, 9, 7\n"
-            "v_add_u32 v35, 16, v35\n"                 /* symbols the block stands for */
+            "v_add_u32 v35, 8, v35\n"                  /* symbols the block stands for */
             "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
             "s_add_u32 s44, s44, 1\n"
             "v_mov_b32 v46, s44\n"
@@ -1474,9 +1528,6 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #undef ANSZP_AB
 #undef ANSZP_BA
 #undef ANSZP_LOOKUP
-#undef ANSZP_SHIFT_W5
-#undef ANSZP_SHIFT_W4
-#undef ANSZP_SHIFT_W3
 #undef ANSZP_SHIFT_W2
 #undef ANSZP_SHIFT_W1
 #undef ANSZP_SHIFT_W0
