@@ -18,7 +18,11 @@
  * General conventions
  *   - Pointers marked [device] are device addresses of the current HIP device;
  *     pointers marked [host] are ordinary host addresses.  The caller owns every
- *     buffer.  The library keeps no global state and allocates no device memory.
+ *     buffer.  The library allocates no device memory and keeps nothing between calls but two
+ *     small per-device caches (the device's number of compute units, and which kernels have
+ *     been given leave to use the whole of a CU's on-chip memory); they are tables of atomics,
+ *     so calls from several host threads are safe.  anszp_build_tables allocates and frees
+ *     pinned host memory for its upload and waits for the copy.
  *   - `hip_stream` is a hipStream_t (NULL = default stream).  Device work is
  *     enqueued on it and the call returns without waiting, unless stated.
  *   - Return value: 0 on success, a negative ANSZP_E_* code when the host can
@@ -55,6 +59,7 @@ extern "C" {
 #define ANSZP_ALPHABET        256   /* symbols are bytes; frequency rows have 256 entries     */
 #define ANSZP_MAX_TABLE_LOG   12    /* tables have L = 2^table_log states, 1 <= table_log <= 12 */
 #define ANSZP_MAX_STREAMS     64    /* streams per chunk = lanes of one wavefront              */
+#define ANSZP_TABLE_WORDS_PER_STATE 8 /* a table of L states occupies 8 L 32-bit words           */
 
 /* error codes returned by the functions */
 #define ANSZP_OK              0
@@ -106,7 +111,7 @@ typedef struct {
 
 /* Arguments of anszp_decode (the struct itself is read on the host). */
 typedef struct {
-    const uint32_t*      tables;        /* [device] n_tables * 4 * 2^table_log words from anszp_build_tables, 16-byte aligned */
+    const uint32_t*      tables;        /* [device] n_tables * 8 * 2^table_log words from anszp_build_tables, 16-byte aligned */
     uint32_t             n_tables;
     uint32_t             table_log;     /* R, 1..12                                             */
     uint32_t             n_streams;     /* N, 1..64                                             */
@@ -140,19 +145,24 @@ const char* anszp_strerror(int code);
 int anszp_normalize_freqs(const uint64_t* counts, int table_log, uint32_t* freqs);
 
 /* [host only] Sec. II-A / III-A: build n_tables decode tables from normalised frequencies.
- * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * 4 * 2^table_log 32-bit words.
- * Table t occupies words [t*4L, (t+1)*4L), L = 2^table_log:
- *   word [2L + X]   the paper's triple for state X:
- *                   bits 0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol
- *   word [2X + b]   the same automaton with up to 4 steps merged and one bit of look-ahead: in state
- *                   X with next stream bit b (peeked, not consumed) the next c-1 symbols are the
- *                   dominant symbol (f > L/2: its zero-bit transitions and at most one of its 1-bit
- *                   transitions, which consumes b), then `symbol` is emitted; T stream bits are
- *                   consumed in all, and with v = the next T+1 stream bits, first bit on top, the
- *                   next index is base + v.
- *                   bits 0..4 31-T (T <= 12)   bits 5..7 zero   bits 8..15 symbol
- *                   bits 16..17 c-1            bits 18..31 base (two's complement)
- *   words [3L, 4L)  zero
+ * freqs: [host] n_tables rows of 256.  tables: [host] n_tables * ANSZP_TABLE_WORDS_PER_STATE * 2^table_log
+ * 32-bit words.  Table t occupies words [t*8L, (t+1)*8L), L = 2^table_log:
+ *   words [0, L)     tables of at most 256 states: the byte table of Sec. II-A, 3 L bytes, state X at
+ *                    bytes 3X (symbol), 3X+1 (nb_bits), 3X+2 (newX), the rest zero; larger tables: zero
+ *   word [2L + X]    the paper's triple for state X:
+ *                    bits 0..15 newX      bits 16..23 nb_bits   bits 24..31 symbol
+ *   words [4L + 2(2X + b)], [4L + 2(2X + b) + 1]
+ *                    the same automaton with up to 8 steps merged and one bit of look-ahead: in state
+ *                    X with next stream bit b (peeked, not consumed) the next c-1 symbols are the
+ *                    dominant symbol (f > L/2: its zero-bit transitions and at most one of its 1-bit
+ *                    transitions, which consumes b), then `symbol` is emitted; T stream bits are
+ *                    consumed in all, and with v = the next T+1 stream bits, first bit on top, the
+ *                    next entry is number base + v.  A run never passes through state 0 (the step that
+ *                    arrives there ends the entry), so a stream ends where an entry ends.
+ *                    first word:  bits 0..4 31-T (T <= 12)   bits 9..11 c-1   bits 16..23 symbol
+ *                                 bits 24..27 T   bits 28..30 c-1   bit 31 set for X = 0   other bits zero
+ *                    second word: 8 * base (two's complement)
+ *   words [L, 2L), [3L, 4L)  zero
  * Errors: E_NULL, E_RANGE, E_FREQ. */
 int anszp_build_tables_host(const uint32_t* freqs, int n_tables, int table_log, uint32_t* tables);
 
@@ -164,7 +174,7 @@ int anszp_build_tables(const uint32_t* freqs_host, int n_tables, int table_log,
 
 /* Sec. II-A / III-A on the device: the same tables, word for word, from normalised frequencies that
  * are already in device memory (one workgroup per table; nothing passes through the host).
- * freqs_dev: [device] n_tables rows of 256.  tables_dev: [device] n_tables * 4 * 2^table_log words,
+ * freqs_dev: [device] n_tables rows of 256.  tables_dev: [device] n_tables * 8 * 2^table_log words,
  * 16-byte aligned.  status_dev: [device] 2 words as in anszp_decode_args_t, or NULL: a row that
  * does not sum to 2^table_log leaves its table all zero and sets ANSZP_ST_BAD_FREQ (the host cannot
  * see the rows, so this is not a return code).  Asynchronous on hip_stream; both buffers stay owned
@@ -201,14 +211,17 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  *   1  step-wise kernel: one look-up per symbol, exactly the loop of Sec. II-A / III-B; also the
  *      path any chunk takes whose compressed words exceed the on-chip window or whose first
  *      output element is not 16-byte aligned
- *   2  look-ahead kernel: look-ups use the merged entries of the table (word [2X + b] above),
+ *   2  look-ahead kernel: look-ups use the look-ahead entries of the table (entry 2X + b above),
  *      compressed words and decoded symbols are staged in LDS, and the work of a chunk is split
  *      over several wavefronts of its workgroup
  *   3  step-wise kernel with sixteen chunks per workgroup sharing the tables in LDS
  *   4  streaming kernel: one look-up per symbol from compact entries in LDS, each stream's words
  *      fetched 64 bytes at a time through a ring in LDS by wavefronts that only load (what the
  *      automatic choice takes when the chunks are too large for the on-chip window)
- * Errors: as anszp_decode, E_RANGE for an unknown variant. */
+ *   5  byte-table kernel: the decoder as Sec. II-A sizes it, for tables of at most 256 states
+ *      (table_log <= 8): the 3 l-byte table (one byte each for symbol, nb_bits and newX; 192 bytes for
+ *      64 states) in LDS, three byte reads and a log2(l)-bit addition per symbol
+ * Errors: as anszp_decode, E_RANGE for an unknown variant or variant 5 with table_log > 8. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 
 /* Sec. II-B alone: out[i] = scale * (symbols[i] - zero_point) for i < n, the scale chosen as in

@@ -193,9 +193,11 @@ def encode_layer(symbols: np.ndarray, f: np.ndarray, R: int, N: int, chunk_size:
     return nsym, poff, pwords, hdr, payload[:used].copy()
 
 
-def encode_layers(layer_symbols: Sequence[np.ndarray], R: int, N: int, chunk_size: int,
+def encode_layers(layer_symbols: Sequence[np.ndarray], R: int, N: int, chunk_size,
                   freqs: Sequence[np.ndarray] | None = None) -> Container:
-    """Histogram + normalise each layer (unless freqs are given), encode, and concatenate."""
+    """Histogram + normalise each layer (unless freqs are given), encode, and concatenate.  chunk_size: one
+    number for all layers, or one per layer."""
+    sizes = [int(chunk_size)] * len(layer_symbols) if np.isscalar(chunk_size) else [int(v) for v in chunk_size]
     fr, c_layer, c_nsym, c_out, c_poff, c_pw, c_soff, hdrs, pays = [], [], [], [], [], [], [], [], []
     numel, out_base = [], []
     elem = 0
@@ -207,14 +209,14 @@ def encode_layers(layer_symbols: Sequence[np.ndarray], R: int, N: int, chunk_siz
             f = normalize(np.bincount(sym, minlength=256).astype(np.uint64), R)
         else:
             f = _f256(freqs[li])
-        nsym, poff, pw, hdr, pay = encode_layer(sym, f, R, N, chunk_size)
+        nsym, poff, pw, hdr, pay = encode_layer(sym, f, R, N, sizes[li])
         nc = len(nsym)
         fr.append(f)
         numel.append(len(sym))
         out_base.append(elem)
         c_layer.append(np.full(nc, li, dtype=np.uint32))
         c_nsym.append(nsym)
-        c_out.append(elem + np.arange(nc, dtype=np.uint64) * np.uint64(chunk_size))
+        c_out.append(elem + np.arange(nc, dtype=np.uint64) * np.uint64(sizes[li]))
         c_poff.append(poff + np.uint64(words))
         c_pw.append(pw)
         c_soff.append((streams + np.arange(nc, dtype=np.uint64) * N).astype(np.uint32))
@@ -224,7 +226,7 @@ def encode_layers(layer_symbols: Sequence[np.ndarray], R: int, N: int, chunk_siz
         words += len(pay)
         streams += nc * N
     cat = np.concatenate
-    return Container(R, N, chunk_size, np.stack(fr).astype(np.uint32),
+    return Container(R, N, max(sizes) if sizes else 0, np.stack(fr).astype(np.uint32),
                      np.array(numel, dtype=np.uint64), np.array(out_base, dtype=np.uint64),
                      cat(c_layer), cat(c_nsym), cat(c_out).astype(np.uint64), cat(c_poff).astype(np.uint64),
                      cat(c_pw), cat(c_soff), cat(hdrs), cat(pays) if words else np.zeros(0, np.uint32))

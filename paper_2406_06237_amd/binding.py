@@ -232,7 +232,8 @@ def pack_workload(w) -> HostContainer:
     L = w.layers
     return pack_layers(w.symbols(), w.table_log, w.n_streams, w.chunk_size,
                        [l.zero_point for l in L], [l.scale for l in L], [l.bitwidth for l in L],
-                       [l.channel_len for l in L], [l.channel_scales for l in L], w.out_dtype)
+                       [l.channel_len for l in L], [l.channel_scales for l in L], w.out_dtype,
+                       chunk_sizes=getattr(w, "chunk_sizes", None))
 
 
 # --------------------------------------------------------------------------- device entry points
@@ -331,7 +332,7 @@ def decode_args(d: DeviceContainer, out, out_dtype: Optional[str] = None) -> Dec
     return a
 
 
-VARIANT_AUTO, VARIANT_STEPWISE, VARIANT_MERGED, VARIANT_STEPWISE_SHARED, VARIANT_STREAMING = 0, 1, 2, 3, 4
+VARIANT_AUTO, VARIANT_STEPWISE, VARIANT_MERGED, VARIANT_STEPWISE_SHARED, VARIANT_STREAMING, VARIANT_BYTE_TABLE = 0, 1, 2, 3, 4, 5
 
 
 def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None):
@@ -343,6 +344,34 @@ def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None)
         else:
             _check(lib().anszp_decode_variant(C.byref(args), variant, _stream_ptr(torch, device)),
                    "anszp_decode_variant")
+
+
+LOOKAHEAD_WINDOW_WORDS = 4096      # stream words of one chunk the look-ahead kernel holds on chip
+
+
+def decode_by_chunk_size(d: DeviceContainer, out=None, out_dtype: Optional[str] = None):
+    """Decode a container whose chunks differ much in size (streams that follow the input channels: a chunk is a
+    group of 64 channels of its layer) with two calls of anszp_decode: one over the chunks whose stream words fit
+    the look-ahead kernel's on-chip window, one over the others with the streaming kernel
+    (a call decodes all its chunks with one kernel; the descriptors of a call may be any subset in any order).  Returns the output tensor."""
+    torch = _torch()
+    if out is None:
+        out = alloc_out(d, out_dtype)
+    words = d.host.chunks["payload_words"]
+    parts = [(np.nonzero(words <= LOOKAHEAD_WINDOW_WORDS)[0], VARIANT_MERGED),
+             (np.nonzero(words > LOOKAHEAD_WINDOW_WORDS)[0], VARIANT_STREAMING)]
+    keep = []
+    for idx, variant in parts:
+        if len(idx) == 0:
+            continue
+        sub = _dev(np.ascontiguousarray(d.host.chunks[idx]), d.device)
+        keep.append(sub)
+        a = decode_args(d, out, out_dtype)
+        a.chunks = sub.data_ptr()
+        a.n_chunks = len(idx)
+        decode_raw(a, d.device, variant)
+    torch.cuda.synchronize(d.device)                   # the descriptor copies live until both calls are done
+    return out
 
 
 def decode(d: DeviceContainer, out=None, out_dtype: Optional[str] = None, variant: Optional[int] = None):

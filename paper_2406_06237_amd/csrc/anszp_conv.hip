@@ -23,6 +23,8 @@
 // channels per lane, row tile and column tile.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include <cstdint>
 
 #include "anszp.h"
@@ -250,6 +252,16 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         reinterpret_cast<words4*>(table)[min(tid + kThreads, t_last)] = tv1;
     } else if (tid < L) {
         table[tid] = small;
+    }
+    if constexpr (P16) {
+        // A panel of bf16 values is read beyond what decoding writes: the columns from K to the row's end,
+        // and up to 64 bytes behind the last row (the last 32 k of a row tile or of a kernel tap).  Those
+        // products meet activations that are zero, but whatever an earlier kernel left in LDS may read as
+        // Inf or NaN, and 0 * Inf is NaN: the whole panel and the 64 bytes behind it start as zeros.
+        // (A panel of symbol bytes needs none of this: any byte is a finite weight.)
+        const uint32_t panel_words = (kRows * MR * p.row_stride * kElem + 64u) / 4u;
+        uint32_t* panel32 = reinterpret_cast<uint32_t*>(panel);
+        for (uint32_t i = tid; i < panel_words; i += kThreads) panel32[i] = 0u;
     }
     __syncthreads();
     uint32_t err = (lay.channel_len != 0 && lay.channel_len != p.K) ? ANSZP_ST_BAD_DESC : 0u;   // scales per output channel only
@@ -554,14 +566,15 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
          : (mr == 4 ? conv_fused_kernel<KIND, 4, false> : mr == 2 ? conv_fused_kernel<KIND, 2, false> : conv_fused_kernel<KIND, 1, false>))
     kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise) : ANSZP_CONV_PICK(kTaps);
 #undef ANSZP_CONV_PICK
-    // the kernels may use all of the CU's LDS: said once per kernel and device
-    static bool lds_allowed[2][3][3][64] = {};
+    // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
+    // concurrent callers at worst both say it)
+    static std::atomic<bool> lds_allowed[2][3][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
-    if (!lds_allowed[p16][kind][slot][device]) {
+    if (!lds_allowed[p16][kind][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 int(kLdsLimit)) != hipSuccess) return ANSZP_E_HIP;
-        lds_allowed[p16][kind][slot][device] = true;
+        lds_allowed[p16][kind][slot][device].store(true, std::memory_order_relaxed);
     }
     hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;

@@ -29,6 +29,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstddef>
 #include <type_traits>
 
@@ -147,8 +148,18 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
 __device__ __forceinline__ bool chunk_in_bounds(const DecodeParams& p, const anszp_chunk_t& c) {
     return c.layer_id < p.n_tables && c.n_symbols <= (1u << 31) &&
            c.out_offset <= p.out_elems && c.n_symbols <= p.out_elems - c.out_offset &&
+           (c.payload_offset & 3u) == 0u &&
            c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
            uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
+}
+
+// True when the layer's quantizer covers the chunk: a layer with a scale per output channel needs every
+// channel the chunk touches to have one in the caller's array, and the chunk to lie inside the layer.
+__device__ __forceinline__ bool scales_in_bounds(const DecodeParams& p, const anszp_layer_t& lay, const anszp_chunk_t& c) {
+    if (lay.channel_len == 0u || c.n_symbols == 0u) return true;
+    if (c.out_offset < lay.out_base) return false;
+    const uint64_t last_channel = (c.out_offset - lay.out_base + c.n_symbols - 1u) / lay.channel_len;
+    return lay.scales_offset <= p.n_scales && last_channel < p.n_scales - lay.scales_offset;
 }
 
 __device__ __forceinline__ float channel_scale(const DecodeParams& p, const anszp_layer_t& lay, uint64_t layer_elem) {
@@ -160,9 +171,23 @@ __device__ __forceinline__ float channel_scale(const DecodeParams& p, const ansz
 // One look-up per symbol (Sec. III-B: n look-ups and n small additions for a stream of n
 // weights).  Executed by one wavefront; `table` is 2^table_log dwords of LDS holding the
 // (newX, nb_bits, symbol) half of the entries.  Returns the chunk's error bits (wave-uniform).
-template <int OUT>
+// The triple of state X as one word (newX | nb_bits << 16 | symbol << 24) from a table of such words ...
+struct WordTable {
+    const uint32_t* words;
+    __device__ __forceinline__ uint32_t operator()(uint32_t X) const { return words[X]; }
+};
+// ... or from the table of Sec. II-A itself, three bytes per state (symbol, nb_bits, newX), which holds
+// tables of at most 256 states.
+struct ByteTable {
+    const uint8_t* bytes;
+    __device__ __forceinline__ uint32_t operator()(uint32_t X) const {
+        return uint32_t(bytes[3u * X + 2u]) | (uint32_t(bytes[3u * X + 1u]) << 16) | (uint32_t(bytes[3u * X]) << 24);
+    }
+};
+
+template <int OUT, class TABLE>
 __device__ uint32_t decode_chunk_stepwise(const DecodeParams& p, const anszp_chunk_t& c, const anszp_layer_t& lay,
-                                          const uint32_t* table, uint32_t lane) {
+                                          const TABLE table, uint32_t lane) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
     const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
@@ -190,7 +215,7 @@ __device__ uint32_t decode_chunk_stepwise(const DecodeParams& p, const anszp_chu
     if (per_channel) scale = channel < p.n_scales ? p.scales[channel] : 0.0f;
     for (uint32_t t = 0; t < steps; ++t) {
         if (t < len) {
-            const uint32_t e = table[X];
+            const uint32_t e = table(X);
             const uint32_t nb = (e >> 16) & 0xFFu;
             if (have < nb) {
                 buf |= uint64_t(ahead) << have;
@@ -233,7 +258,39 @@ __global__ __launch_bounds__(kWave) void decode_stepwise(DecodeParams p) {
     for (uint32_t i = lane; i < (1u << p.table_log); i += kWave) table[i] = src[i];
     const anszp_layer_t lay = p.layers[c.layer_id];
     __syncthreads();
-    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, table, lane);
+    if (!scales_in_bounds(p, lay, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, WordTable{table}, lane);
+    if (err && lane == 0) report(p.status, err);
+}
+
+// The decoder of Sec. II-A as the paper sizes it: the table is 3 l bytes (symbol, nb_bits, newX: one byte
+// each), 192 bytes for 64 states, read from LDS; a step is three byte reads, nb_bits bits from the stream and
+// an addition of log2(l) bits.  Four wavefronts per workgroup, a chunk and a copy of its layer's table each.
+constexpr int kByteWaves = 4;
+template <int OUT>
+__global__ __launch_bounds__(kByteWaves * kWave) void decode_byte_table(DecodeParams p) {
+    __shared__ uint32_t table[kByteWaves][3u * 256u / 4u];
+    const uint32_t lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t index = blockIdx.x * kByteWaves + wave;
+    if (index >= p.n_chunks) return;
+    const anszp_chunk_t c = p.chunks[index];
+    if (!chunk_in_bounds(p, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const anszp_layer_t lay = p.layers[c.layer_id];
+    if (!scales_in_bounds(p, lay, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
+    const uint32_t* src = p.tables + c.layer_id * table_stride_words(p.table_log) + table_bytes_offset(p.table_log);
+    for (uint32_t i = lane; i < (3u << p.table_log) / 4u + 1u && i < 3u * 256u / 4u; i += kWave) table[wave][i] = src[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the wavefront's own copy: LDS serves its accesses in order
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, ByteTable{reinterpret_cast<const uint8_t*>(table[wave])}, lane);
     if (err && lane == 0) report(p.status, err);
 }
 
@@ -266,9 +323,13 @@ __global__ __launch_bounds__(kSharedWaves * kWave) void decode_stepwise_shared(D
         return;
     }
     const anszp_layer_t lay = p.layers[c.layer_id];
+    if (!scales_in_bounds(p, lay, c)) {
+        if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
+        return;
+    }
     const uint32_t* mine = c.layer_id == layer_a ? table[0] : c.layer_id == layer_b ? table[1]
                            : p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
-    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, mine, lane);
+    const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, WordTable{mine}, lane);
     if (err && lane == 0) report(p.status, err);
 }
 
@@ -479,7 +540,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             alive[j] = false;
             if (d < count) {
                 const anszp_chunk_t cj = p.chunks[first + d];
-                if (chunk_in_bounds(p, cj)) {
+                if (chunk_in_bounds(p, cj) && scales_in_bounds(p, p.layers[cj.layer_id], cj)) {
                     uint32_t n_words, skew;
                     bool sums_up;
                     where[j] = locate(cj, n_words, skew, readable[j], sums_up);
@@ -549,7 +610,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     auto no_more_positions = [&]() { position[lane] = kStreamFinished; };
     if (wave >= count) { no_more_positions(); return; }
     const anszp_chunk_t c = p.chunks[first + wave];
-    if (!chunk_in_bounds(p, c)) {
+    if (!chunk_in_bounds(p, c) || !scales_in_bounds(p, p.layers[c.layer_id], c)) {
         if (lane == 0) report(p.status, ANSZP_ST_BAD_DESC);
         no_more_positions();
         return;
@@ -568,7 +629,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     if (c.layer_id != layer_a && c.layer_id != layer_b) {
         // a third layer in one workgroup: the plain loop, table from global memory
         no_more_positions();
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log), lane);
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, WordTable{p.tables + c.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log)}, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
@@ -1042,7 +1103,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     if (unit.count == 0u) return;
     // descriptors (the second repeats the first when the unit is a single chunk)
     const anszp_chunk_t c0 = p.chunks[unit.first], c1 = p.chunks[unit.first + unit.count - 1u];
-    const bool in0 = chunk_in_bounds(p, c0), in1 = unit.count == 2u && chunk_in_bounds(p, c1);
+    const bool in0 = chunk_in_bounds(p, c0) && scales_in_bounds(p, p.layers[c0.layer_id], c0);
+    const bool in1 = unit.count == 2u && chunk_in_bounds(p, c1) && scales_in_bounds(p, p.layers[c1.layer_id], c1);
     if (tid == 0) {
         if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
         if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
@@ -1187,7 +1249,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
     if (!merged_ok) {                                     // the plain loop of Sec. II-A, table read from global memory
         if (task != kDecode) return;
-        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, src + table_triples_offset(p.table_log), lane);
+        const uint32_t err = decode_chunk_stepwise<OUT>(p, c, lay, WordTable{src + table_triples_offset(p.table_log)}, lane);
         if (err && lane == 0) report(p.status, err);
         return;
     }
@@ -1549,13 +1611,12 @@ void decode_merged_small(DecodeParams p) { decode_lookahead<OUT, PER_CHANNEL, Sm
 
 
 // ---------------------------------------------------------------------------------------------
-// Sec. II-B alone.
-// ---------------------------------------------------------------------------------------------
-// Decode tables built on the device (Sec. II-A "initialization of the states", Sec. III-A one
-// table per layer): one workgroup per table, same words as anszp_build_tables_host.
+// Decode tables built on the device (Sec. II-A table, Sec. III-A one table per layer): one workgroup
+// per table, same words as anszp_build_tables_host.
 //
-// The host merges the per-symbol position sequences (occurrence i of a symbol of frequency f sits
-// at (2i+1)/(2f); ties go to the smaller symbol) with a heap.  Here every occurrence computes its
+// The host merges the per-symbol position sequences (this library's choice of spread, which Sec. II-A
+// leaves open: occurrence i of a symbol of frequency f sits at (2i+1)/(2f); ties go to the smaller
+// symbol) with a heap.  Here every occurrence computes its
 // own rank instead: the number of occurrences of every other symbol that come before it, in exact
 // integer arithmetic, is a quotient.  The rank is the state X; the occurrence index gives the
 // sub-state f + i, hence nb_bits and newX; the look-ahead entries then follow the step table in LDS.
@@ -1674,6 +1735,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_tables_kernel(const uint3
     }
 }
 
+// Sec. II-B alone.
 template <int OUT>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* sym, uint64_t n, anszp_layer_t lay,
                                                       const float* scales, uint64_t n_scales, void* out) {
@@ -1688,23 +1750,28 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* sym, uint64
     }
 }
 
-// Compute units of the current device (queried once per device).
+// Compute units of the current device (queried once per device; the cache is a table of atomics, so
+// concurrent callers at worst both query).
 uint32_t device_cus() {
-    static uint32_t cached[64] = {};
+    static std::atomic<uint32_t> cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256u;
-    if (!cached[dev]) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = static_cast<uint32_t>(n);
+    uint32_t n = cached[dev].load(std::memory_order_relaxed);
+    if (!n) {
+        int count = 0;
+        if (hipDeviceGetAttribute(&count, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || count <= 0) count = 256;
+        n = static_cast<uint32_t>(count);
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 template <int OUT>
 void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, bool stepwise, bool shared, bool streaming,
-                   bool small, hipStream_t s) {
-    if (stepwise && streaming) {
+                   bool small, bool byte_table, hipStream_t s) {
+    if (byte_table) {
+        hipLaunchKernelGGL(decode_byte_table<OUT>, dim3((n_chunks + kByteWaves - 1) / kByteWaves), dim3(kByteWaves * kWave), 0, s, p);
+    } else if (stepwise && streaming) {
         // chunks dealt evenly to as many workgroups as fill whole rounds of the device's CUs
         const uint32_t per_round = device_cus() * uint32_t(kStreamDecoders);
         const uint32_t rounds = (n_chunks + per_round - 1u) / per_round;
@@ -1732,7 +1799,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
         a->n_streams > ANSZP_MAX_STREAMS || a->out_dtype > ANSZP_OUT_BF16 || a->n_tables == 0 ||
         a->n_chunks >= (1ull << 31) || (reinterpret_cast<uintptr_t>(a->payload) & 15) ||
         (reinterpret_cast<uintptr_t>(a->tables) & 15) ||
-        (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 4)
+        (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 5 || (mode == 5 && a->table_log > 8))
         return ANSZP_E_RANGE;
     DecodeParams p;
     p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
@@ -1748,7 +1815,8 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     // fallback: they go to the streaming kernel, whatever their number (measured on 772 to 24,704
     // chunks of 82 KB of words: 5 to 7 times faster than one step-wise wavefront per chunk)
     const uint64_t mean_words = a->payload_words / a->n_chunks;
-    const bool stepwise = mode == 1 || mode >= 3 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    const bool stepwise = mode == 1 || mode == 3 || mode == 4 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    const bool byte_table = mode == 5;
     const bool shared = mode == 3;
     const bool streaming = mode == 4 || (mode == 0 && stepwise);
     // small tables and short chunks: the variant that fits three workgroups on a CU
@@ -1756,9 +1824,9 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
                        kBlockLookups * kLookaheadMaxSymbols * a->n_streams < SmallLds::kRingElems;     // a block must fit its ring
     const bool per_channel = a->scales != nullptr && a->n_scales != 0;
     switch (a->out_dtype) {
-        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
-        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
-        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, shared, streaming, small, s); break;
+        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
+        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
+        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
     }
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }

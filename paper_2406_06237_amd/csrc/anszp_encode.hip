@@ -12,7 +12,8 @@
 // over the chunks (payload offsets, total), the writing pass.  One lane per stream, one wavefront
 // per chunk at a time; every workgroup builds the encoding tables in LDS for itself from the
 // frequencies: the states of a symbol in increasing order are the ranks of its occurrences in the
-// merged position sequences of Sec. II-A, and a rank is a sum of integer quotients.
+// merged position sequences (the spread this library chose; Sec. II-A says only that the rate depends
+// on how the states are initialised), and a rank is a sum of integer quotients.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

@@ -22,8 +22,10 @@ bool freqs_ok(const uint32_t* f, int table_log) {
     return total == (1ull << table_log);
 }
 
-// Position of occurrence i of a symbol with frequency f is (2i+1)/(2f).  Ordered by that
-// fraction, ties by symbol.  Kept as numerator/denominator and compared by cross product.
+// The spread of symbols over states is this library's choice (Sec. II-A says that the rate depends on
+// how the states are initialised, not how to do it): occurrence i of a symbol with frequency f is given
+// the position (2i+1)/(2f); states follow that fraction, ties by symbol.  Kept as
+// numerator/denominator and compared by cross product.
 struct Slot {
     uint64_t num;   // 2i+1
     uint64_t den;   // f (the common factor 2 cancels)
@@ -37,7 +39,7 @@ struct SlotLater {
     }
 };
 
-// Sec. II-A "initialization of the states": merge the per-symbol position sequences.
+// The "initialization of the states" Sec. II-A leaves open: merge the per-symbol position sequences.
 void spread_states(const uint32_t* f, int table_log, std::vector<uint8_t>& state_sym) {
     const uint32_t L = 1u << table_log;
     state_sym.resize(L);

@@ -114,6 +114,72 @@ class Layer:
         return sample_symbols(self.pmf, self.numel, self.seed)
 
 
+CHANNEL_GROUP = 64        # input channels per group = streams per chunk when streams follow the input channels
+
+
+def to_channel_groups(tensor: np.ndarray) -> np.ndarray:
+    """A conv weight tensor [cout][cin][kh][kw] (cin a multiple of 64) in the order [cin / 64][cout][kh][kw][64]:
+    with 64 streams per chunk and chunks that start on multiples of 64, stream k of every chunk holds weights of
+    input channel 64 g + k only, and a wavefront-step still writes 64 consecutive elements."""
+    cout, cin, kh, kw = tensor.shape
+    assert cin % CHANNEL_GROUP == 0
+    t = tensor.reshape(cout, cin // CHANNEL_GROUP, CHANNEL_GROUP, kh, kw)
+    return np.ascontiguousarray(t.transpose(1, 0, 3, 4, 2)).reshape(-1)
+
+
+def from_channel_groups(flat: np.ndarray, shape) -> np.ndarray:
+    """Inverse of to_channel_groups."""
+    cout, cin, kh, kw = shape
+    t = np.asarray(flat).reshape(cin // CHANNEL_GROUP, cout, kh, kw, CHANNEL_GROUP)
+    return np.ascontiguousarray(t.transpose(1, 0, 4, 2, 3)).reshape(cout, cin, kh, kw)
+
+
+@dataclass
+class ChannelLayer(Layer):
+    """A conv layer whose weights follow their INPUT channel (Sec. III-B: the streams of a layer are its input
+    channels): channel c has its own P(zero-point), spread evenly over [p0_low, p0_high] in a seeded random
+    order, so streams differ in compressibility and the storage order matters.  symbols() returns the layer in
+    storage order [cin / 64][cout][kh][kw][64]; tensor() the same weights as [cout][cin][kh][kw]."""
+    p0_low: float = 0.6
+    p0_high: float = 0.95
+
+    def tensor(self) -> np.ndarray:
+        cout, cin, kh, kw = self.shape
+        alphabet = 1 << self.bitwidth
+        order = np.argsort(splitmix64(self.seed, cin))
+        p0 = self.p0_low + (self.p0_high - self.p0_low) * (order.astype(np.float64) + 0.5) / cin
+        t = np.empty((cout, cin, kh, kw), dtype=np.uint8)
+        for c in range(cin):
+            pmf = peaked_geometric_pmf(alphabet, self.zero_point, float(p0[c]))
+            t[:, c] = sample_symbols(pmf, cout * kh * kw, self.seed + 1 + c).reshape(cout, kh, kw)
+        return t
+
+    def symbols(self) -> np.ndarray:
+        return to_channel_groups(self.tensor())
+
+    @property
+    def group_symbols(self) -> int:
+        """Symbols of one group of 64 input channels: the chunk size that makes a stream a whole channel."""
+        cout, cin, kh, kw = self.shape
+        return cout * kh * kw * CHANNEL_GROUP
+
+
+def channel_grouped(shapes=((128, 128, 3, 3), (512, 64, 3, 3), (256, 256, 1, 1), (64, 64, 1, 1)), table_log: int = 12,
+                    seed: int = 77) -> "Workload":
+    """Conv layers coded with one stream per input channel.  The layer's pmf (mixture over its channels) is only
+    informational: tables come from the symbols' histogram.  chunk_sizes holds one chunk size per layer."""
+    layers = []
+    for i, shape in enumerate(shapes):
+        b = 3 + (i % 3) * 2
+        z = 1 << (b - 1)
+        layers.append(ChannelLayer(f"grouped{i}", tuple(shape), b, z, 0.01 * (i + 1), peaked_geometric_pmf(1 << b, z, 0.8),
+                                   BASE_SEED + 7000 * (i + 1) + seed))
+    w = Workload("channel_grouped", layers, table_log, CHANNEL_GROUP, 65536, "bf16",
+                 notes="streams follow the input channels; storage order [cin/64][cout][kh][kw][64]")
+    w.chunk_sizes = [l.group_symbols for l in layers]
+    return w
+
+
 @dataclass
 class Workload:
     name: str
@@ -123,6 +189,7 @@ class Workload:
     chunk_size: int
     out_dtype: str                            # "f32" | "bf16"
     notes: str = ""
+    chunk_sizes: Optional[List[int]] = None   # one chunk size per layer instead of chunk_size for all
     _cache: dict = field(default_factory=dict, repr=False)
 
     @property

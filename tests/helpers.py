@@ -28,7 +28,8 @@ def host_from_oracle(c, workload) -> B.HostContainer:
 
 
 def oracle_encode(orc, workload):
-    return orc.encode_layers(workload.symbols(), workload.table_log, workload.n_streams, workload.chunk_size)
+    sizes = getattr(workload, "chunk_sizes", None)
+    return orc.encode_layers(workload.symbols(), workload.table_log, workload.n_streams, sizes if sizes is not None else workload.chunk_size)
 
 
 def oracle_expected(orc, c, workload, out_dtype=None, n_threads=8):

@@ -213,3 +213,26 @@ def test_rejected_arguments(orc):
     with pytest.raises(B.AnszpError):
         B.conv_fused(d, 0, 0, 1, big, (16, 1024, 3, 3), 1, 1)       # K = 9216 > 4608
     assert d.read_status() == (0, 0)
+
+
+def test_bf16_panel_does_not_depend_on_stale_lds(orc):
+    """Short rows (K <= 576) keep the panel as bf16 values, and the contraction reads it beyond what decoding
+    writes (a row's columns from K to its end, the bytes behind the last row).  Those reads meet activations
+    that are zero; whatever an earlier kernel left there must not turn 0 * x into NaN.  A helper kernel first
+    fills every CU's LDS with +Inf (0x7F80) or NaN (0xFFFF) patterns."""
+    import ctypes as C
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gpu_helpers", "liblds_fill.so")
+    assert os.path.exists(path), "tests/gpu_helpers/liblds_fill.so is missing: run python -m paper_2406_06237_amd.build"
+    helper = C.CDLL(path)
+    helper.lds_fill.argtypes = [C.c_uint32, C.c_void_p, C.c_void_p]
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    for pattern in (0x7F807F80, 0xFFFFFFFF, 0x7F80FF80):
+        for shape, size, stride, pad in (((64, 3, 7, 7), 20, 2, 3), ((32, 40, 3, 3), 11, 1, 1), ((16, 8, 1, 1), 9, 1, 0)):
+            assert helper.lds_fill(pattern, sink.data_ptr(), None) == 0
+            torch.cuda.synchronize()
+            layout = "c8" if shape[1] % 8 == 0 else "nhwc"
+            status, got, want, mag = _case(orc, shape, 2, size, size, stride, pad, seed=pattern & 0xFFF, x_layout=layout)
+            assert np.isfinite(got).all(), f"pattern {pattern:#x}, shape {shape}: non-finite outputs"
+            _check(status, got, want, mag)
+    assert int(sink[0]) == 0

@@ -16,7 +16,10 @@ def _run(orc, w, out_dtype=None):
     c = oracle_encode(orc, w)
     _, expect = oracle_expected(orc, c, w, out_dtype)
     d = B.to_device(host_from_oracle(c, w))
-    for variant in (None, B.VARIANT_STEPWISE, B.VARIANT_MERGED, B.VARIANT_STEPWISE_SHARED, B.VARIANT_STREAMING):
+    variants = [None, B.VARIANT_STEPWISE, B.VARIANT_MERGED, B.VARIANT_STEPWISE_SHARED, B.VARIANT_STREAMING]
+    if w.table_log <= 8:
+        variants.append(B.VARIANT_BYTE_TABLE)       # the 3 l-byte table of Sec. II-A holds at most 256 states
+    for variant in variants:
         out = B.alloc_out(d, out_dtype)
         out.view(torch.uint8).fill_(0xA5)
         B.decode(d, out=out, out_dtype=out_dtype, variant=variant)
@@ -62,7 +65,25 @@ def test_per_channel_scales(orc):
     rng = np.random.default_rng(1)
     lay = W.Layer("odd", (37, 101), 4, 8, 0.0, W.laplace_pmf(16, 8, 1.0), 9, channel_len=101,
                   channel_scales=rng.uniform(0.005, 0.05, 37).astype(np.float32))
-    _run(orc, W.Workload("odd", [lay, lay], 10, 64, 1000, "bf16"))
+    w2 = W.Workload("odd", [lay, lay], 10, 64, 1000, "bf16")
+    _run(orc, w2)
+    # a layer with a scale per channel and no scales to read: every chunk is refused, nothing is written as zeros
+    d = B.to_device(host_from_oracle(oracle_encode(orc, w2), w2))
+    for variant in (None, B.VARIANT_STEPWISE, B.VARIANT_MERGED, B.VARIANT_STEPWISE_SHARED, B.VARIANT_STREAMING):
+        out = B.alloc_out(d)
+        out.view(torch.uint8).fill_(0xA5)
+        a = B.decode_args(d, out)
+        a.scales, a.n_scales = None, 0
+        B.decode_raw(a, d.device, variant)
+        st = d.read_status()
+        assert st[0] == B.ST_BAD_DESC and st[1] == len(d.host.chunks), f"variant {variant}: {st}"
+        assert bool((out.view(torch.uint8) == 0xA5).all()), f"variant {variant} wrote weights without scales"
+        d.status.zero_()
+    # too few scales for the last channels
+    a = B.decode_args(d, B.alloc_out(d))
+    a.n_scales = a.n_scales - 1
+    B.decode_raw(a, d.device)
+    assert d.read_status()[0] == B.ST_BAD_DESC
 
 
 def test_config2_resnet18(orc):
@@ -138,6 +159,41 @@ def test_streaming_workgroups_spanning_many_layers(orc):
         B.decode(d, out=out, variant=variant)
         assert d.read_status() == (0, 0), f"variant {variant}"
         assert np.array_equal(B.bits_of(out)[:w.numel], expect), f"variant {variant}"
+
+
+@pytest.mark.parametrize("R", [6, 7, 8])
+def test_byte_tables_on_the_device_equal_the_oracles(orc, R):
+    """Sec. II-A: the look-up table is 3 l bytes (symbol, nb_bits, newX, one byte each; 192 bytes for 64 states).
+    The bytes anszp_build_tables_device and anszp_build_tables leave in device memory equal the oracle's table
+    byte for byte at l = 64, 128, 256, and decoding through them (the byte-table kernel) gives the oracle's
+    weights on the odd-bin set."""
+    w = W.resnet50_odd_bins()
+    w.layers = w.layers[:12]
+    w.table_log = R
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    h = host_from_oracle(c, w)
+    d = B.to_device(h)
+    L = 1 << R
+    on_device = d.tables.cpu().numpy().view(np.uint32).reshape(len(w.layers), -1)
+    built = B.build_tables_device(torch.from_numpy(np.ascontiguousarray(h.freqs).astype(np.int32)).cuda(), R)
+    built = built.cpu().numpy().view(np.uint32).reshape(len(w.layers), -1)
+    for i in range(len(w.layers)):
+        want = orc.decode_table_bytes(h.freqs[i], R)
+        assert len(want) == 3 * L
+        assert np.array_equal(B.split_table(on_device[i])["bytes"], want)
+        assert np.array_equal(B.split_table(built[i])["bytes"], want)
+    out = B.alloc_out(d)
+    out.view(torch.uint8).fill_(0xA5)
+    B.decode(d, out=out, variant=B.VARIANT_BYTE_TABLE)
+    assert d.read_status() == (0, 0)
+    assert np.array_equal(B.bits_of(out)[:w.numel], expect)
+    # larger tables have no byte form: the variant is refused
+    w2 = W.tiny(n=1000, chunk_size=512, table_log=9)
+    d2 = B.to_device(host_from_oracle(oracle_encode(orc, w2), w2))
+    with pytest.raises(B.AnszpError) as e:
+        B.decode(d2, variant=B.VARIANT_BYTE_TABLE)
+    assert e.value.code == -2
 
 
 @pytest.mark.parametrize("R", [6, 8])
