@@ -346,7 +346,7 @@ def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None)
                    "anszp_decode_variant")
 
 
-LOOKAHEAD_WINDOW_WORDS = 4096      # stream words of one chunk the look-ahead kernel holds on chip
+LOOKAHEAD_WINDOW_WORDS = 11096     # stream words of one chunk the look-ahead kernel can hold on chip (a chunk that has a workgroup to itself)
 
 
 def decode_by_chunk_size(d: DeviceContainer, out=None, out_dtype: Optional[str] = None):

@@ -965,7 +965,7 @@ __device__ __forceinline__ uint32_t pair_level_of(uint32_t payload_words, uint32
 }
 
 template <uint32_t THREADS>
-__device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint32_t capacity,
+__device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint32_t capacity, uint32_t pair_words,
                                           uint64_t* masks /* LDS, kPairLevels * (kPairScanRounds * THREADS / 64 + 1) words of 8 bytes */) {
     constexpr uint32_t kWaves = THREADS / kWave;
     constexpr uint32_t kMasks = kPairScanRounds * kWaves;
@@ -990,7 +990,7 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
     for (uint32_t k = 0; k < kPairScanRounds; ++k) {
         if (k >= rounds) break;
         const uint32_t i = k * THREADS + tid;
-        const uint32_t level = pair_level_of(words[k], symbols[k]);
+        const uint32_t level = words[k] <= pair_words ? pair_level_of(words[k], symbols[k]) : kPairLevels;   // too long to share: never
         // (chunk i - 1 of an odd i sits in the lane below: blocks of 64 chunks start at even numbers; the
         // shuffles are done by every lane, the even lanes are their sources)
         const uint32_t layer_below = __shfl_up(layer[k], 1, kWave), level_below = __shfl_up(level, 1, kWave);
@@ -1065,20 +1065,22 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each), per chunk
     constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
     constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks in flight between decoding and expanding wavefront
-    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: words, hand-over words, positions, log
+    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: hand-over words, positions, log, compressed words
     constexpr uint32_t kRingOff = kTableBytes;
     constexpr uint32_t kLutOff = kRingOff + 2u * kRingElems;
     constexpr uint32_t kSimdOff = kLutOff + 512u;                  // SIMD of each wavefront
     constexpr uint32_t kPipeOff = kSimdOff + 64u;
     constexpr uint32_t kTailWords = 8u;                             // zero words behind a chunk's last: a window of four words may start at the last
     constexpr uint32_t kWordsBytes = (kPayloadWords + kTailWords) * 4u;
-    constexpr uint32_t kCtlOff = kWordsBytes;                       // within a chunk's area
+    constexpr uint32_t kCtlOff = 0u;                                // within a chunk's area
     constexpr uint32_t kProgOff = kCtlOff + 64u;
     constexpr uint32_t kLogOff = kProgOff + kWave * 4u;
-    constexpr uint32_t kPipeBytes = kLogOff + kLogSlots * kLogSlotBytes;
+    constexpr uint32_t kWordsOff = kLogOff + kLogSlots * kLogSlotBytes;   // the compressed words come last: a single chunk's
+    constexpr uint32_t kPipeBytes = kWordsOff + kWordsBytes;             // may run on through the second chunk's area
+    constexpr uint32_t kSoloWords = (kWordsBytes + kPipeBytes) / 4u - kTailWords;
     constexpr uint32_t kLdsBytes = kPipeOff + 2u * kPipeBytes;
     static_assert(kTableBytes % kRingElems == 0u && (kRingElems & (kRingElems - 1u)) == 0u, "rings aligned to their size");
-    static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u, "LDS layout");
+    static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u && kWordsOff % 16u == 0u, "LDS layout");
     static_assert(kRingElems % kSlab == 0u, "whole slabs");
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
     static_assert(kLdsBytes * 8u < (1u << 22), "bit positions count from the start of LDS");
@@ -1091,6 +1093,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
     constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 2u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
     constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;                  // per chunk
+    static_assert(kSoloWords <= 2u * kWordLoads * 4u * kBlock, "a single chunk's words are loaded by both chunks' loads");
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (kWave - 1);
@@ -1098,7 +1101,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
 
-    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu,
+    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, kPayloadWords,
                                         reinterpret_cast<uint64_t*>(lds + kPipeOff));
     if (unit.count == 0u) return;
     // descriptors (the second repeats the first when the unit is a single chunk)
@@ -1128,16 +1131,21 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     if constexpr (kTableLoads > 3u) {
         tv3 = tsrc[min(tid + 3u * kBlock, t_last)]; tv4 = tsrc[min(tid + 4u * kBlock, t_last)]; tv5 = tsrc[min(tid + 5u * kBlock, t_last)];
     }
-    const uint32_t quads0 = in0 ? min(c0.payload_words, kPayloadWords) >> 2 : 0u;
-    const uint32_t quads1 = in1 ? min(c1.payload_words, kPayloadWords) >> 2 : 0u;
+    // (a single chunk may be longer than a chunk's own window: its words then run on through the second chunk's
+    // area, and the second chunk's loads fetch them)
+    constexpr uint32_t kRowsPerChunk = kWordLoads * kBlock;       // 16-byte rows of words a chunk's loads cover
+    const bool single = unit.count == 1u;
+    const uint32_t window0 = single ? kSoloWords : kPayloadWords;
+    const uint32_t quads0 = in0 ? min(c0.payload_words, window0) >> 2 : 0u;
+    const uint32_t quads1 = in1 ? min(c1.payload_words, kPayloadWords) >> 2 : (single && quads0 > kRowsPerChunk ? quads0 - kRowsPerChunk : 0u);
     const uint4* wsrc0 = quads0 ? reinterpret_cast<const uint4*>(p.payload + c0.payload_offset) : tsrc;
-    const uint4* wsrc1 = quads1 ? reinterpret_cast<const uint4*>(p.payload + c1.payload_offset) : tsrc;
-    const uint32_t w_last0 = quads0 ? quads0 - 1u : 0u, w_last1 = quads1 ? quads1 - 1u : 0u;
+    const uint4* wsrc1 = !quads1 ? tsrc : single ? wsrc0 + kRowsPerChunk : reinterpret_cast<const uint4*>(p.payload + c1.payload_offset);
+    const uint32_t w_last0 = quads0 ? min(quads0, kRowsPerChunk) - 1u : 0u, w_last1 = quads1 ? quads1 - 1u : 0u;
     const uint4 wv00 = wsrc0[min(tid, w_last0)], wv10 = wsrc1[min(tid, w_last1)];
     uint4 wv01 = wv00, wv11 = wv10;
     if constexpr (kWordLoads > 1u) { wv01 = wsrc0[min(tid + kBlock, w_last0)]; wv11 = wsrc1[min(tid + kBlock, w_last1)]; }
     uint32_t tail0 = 0, tail1 = 0;                        // the words behind the last whole row of four
-    if (in0 && tid < kTailWords && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= kPayloadWords)
+    if (in0 && tid < kTailWords && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= window0)
         tail0 = p.payload[c0.payload_offset + (quads0 << 2) + tid];
     if (in1 && tid < kTailWords && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
         tail1 = p.payload[c1.payload_offset + (quads1 << 2) + tid];
@@ -1197,24 +1205,24 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             tdst[min(tid + 4u * kBlock, t_last)] = tv4;
             tdst[min(tid + 5u * kBlock, t_last)] = tv5;
         }
-        uint4* wdst0 = reinterpret_cast<uint4*>(lds + kPipeOff);
-        uint4* wdst1 = reinterpret_cast<uint4*>(lds + kPipeOff + kPipeBytes);
+        uint4* wdst0 = reinterpret_cast<uint4*>(lds + kPipeOff + kWordsOff);
+        uint4* wdst1 = single ? wdst0 + kRowsPerChunk : reinterpret_cast<uint4*>(lds + kPipeOff + kPipeBytes + kWordsOff);
         if (quads0) { wdst0[min(tid, w_last0)] = wv00; if constexpr (kWordLoads > 1u) wdst0[min(tid + kBlock, w_last0)] = wv01; }
         if (quads1) { wdst1[min(tid, w_last1)] = wv10; if constexpr (kWordLoads > 1u) wdst1[min(tid + kBlock, w_last1)] = wv11; }
         if (tid < kTailWords) {                           // tail words, then zeros for clamped reads
-            reinterpret_cast<uint32_t*>(lds + kPipeOff)[(quads0 << 2) + tid] = tail0;
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + kPipeBytes)[(quads1 << 2) + tid] = tail1;
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + kWordsOff)[(quads0 << 2) + tid] = tail0;
+            if (!single) reinterpret_cast<uint32_t*>(lds + kPipeOff + kPipeBytes + kWordsOff)[(quads1 << 2) + tid] = tail1;
         }
         if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
-        if (tid < 2u * 16u) {                             // hand-over words of both chunks
+        if (tid < (single ? 16u : 2u * 16u)) {            // hand-over words (of both chunks)
             const uint32_t q = tid / 16u, i = tid % 16u;
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = (i == kStored1) ? kSlab : 0u;
         }
-        for (uint32_t t = tid; t < 2u * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
+        for (uint32_t t = tid; t < (single ? 1u : 2u) * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
             const uint32_t q = t / (kLogSlots * kWave), i = t % (kLogSlots * kWave);
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + (kBlockLookups + 1u) * 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
         }
-        if (tid < 2u * kWave) {                           // where every stream is: its first element, or nothing to wait for
+        if (tid < (single ? 1u : 2u) * kWave) {           // where every stream is: its first element, or nothing to wait for
             const uint32_t q = tid / kWave, l = tid % kWave;
             const uint32_t n_q = q ? (in1 ? c1.n_symbols : 0u) : (in0 ? c0.n_symbols : 0u);
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[l] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
@@ -1233,7 +1241,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // ---- this wavefront's chunk
     const anszp_chunk_t c = pipe ? c1 : c0;
     const uint32_t hdr = pipe ? hdr1 : hdr0;
-    const uint32_t pipe_off = kPipeOff + pipe * kPipeBytes;          // the chunk's area: its compressed words come first
+    const uint32_t pipe_off = kPipeOff + pipe * kPipeBytes;          // the chunk's area
+    const uint32_t words_off = pipe_off + kWordsOff;                 // its compressed words
     // (a workgroup with a single chunk uses the space of both rings as one)
     const uint32_t ring_elems = unit.count == 1u ? 2u * kRingElems : kRingElems;
     const uint32_t ring_mask = ring_elems - 1u;
@@ -1244,7 +1253,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t n_words = hdr >> 16;
     const uint32_t len = (lane < N && n > lane) ? (n - lane + N - 1u) / N : 0u;
     const uint32_t lane_end = lane < N ? lane + len * N : n;         // first element of this lane at or beyond the chunk's end
-    const bool merged_ok = p.table_log <= G::kTableLog && c.payload_words <= kPayloadWords &&
+    const bool merged_ok = p.table_log <= G::kTableLog && c.payload_words <= (single ? kSoloWords : kPayloadWords) &&
                            ((c.out_offset * kElemBytes) & 15u) == 0 && n <= (1u << 24) && PER_CHANNEL == (lay.channel_len != 0) &&
                            (!PER_CHANNEL || layer_elem0 + n < (1ull << 32));
     if (!merged_ok) {                                     // the plain loop of Sec. II-A, table read from global memory
@@ -1313,7 +1322,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     }
 
     const uint32_t total_words = pipe ? total_words1 : total_words0, first_word = pipe ? first_word1 : first_word0;
-    const uint32_t first_bit = (pipe_off + 4u * min(first_word, c.payload_words)) << 3;   // counted from the start of LDS
+    const uint32_t first_bit = (words_off + 4u * min(first_word, c.payload_words)) << 3;   // counted from the start of LDS
 
     if (task == kExpand) {
         // ---- expanding wavefront.  Every pass reads the count of logged blocks and, in the same batch
@@ -1441,8 +1450,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 
     // ---- decoding wavefront
     __builtin_amdgcn_s_setprio(3);
-    const uint32_t last_word = pipe_off + (c.payload_words << 2);        // address of the zero words behind the payload
-    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(lds + pipe_off);
+    const uint32_t last_word = words_off + (c.payload_words << 2);       // address of the zero words behind the payload
+    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(lds + words_off);
     // Look-ahead entries are indexed by 2 * state + the next stream bit (peeked, not yet read).
     const uint32_t index0 = 2u * (hdr & (L - 1u)) + (lds_words[min(first_word, c.payload_words)] & 1u);
     uint2 e = reinterpret_cast<const uint2*>(lds)[index0];
