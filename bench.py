@@ -21,22 +21,150 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
 def load_traffic(name: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary
-    for this workload has been committed under profiles/."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE).  The counters cannot be
+    read from inside this run; the figure is the one in the summary committed under profiles/ for this
+    workload, and the second value returned says which file and which state of the kernel it belongs to."""
+    rel = os.path.join("profiles", f"hbm_traffic_{name}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
-    vals = {}
+        return None, None
+    vals, commit = {}, None
     for line in open(path):
-        if ":" in line and not line.startswith("#"):
+        if line.startswith("kernel_source_commit:"):
+            commit = line.split(":", 1)[1].strip()
+        elif ":" in line and not line.startswith("#"):
             k, v = line.split(":", 1)
             try:
                 vals[k.strip()] = float(v.split()[0])
             except (ValueError, IndexError):
                 pass
     if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
-        return vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]
-    return None
+        return (vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"],
+                f"{rel} (rocprofv3 --pmc, not measured in this run; kernel sources as of commit {commit})")
+    return None, None
+
+
+def lookups_per_stream(h):
+    """Table look-ups the look-ahead kernel makes for every stream of a container (Sec. II-A steps merged into
+    entries, see anszp.h): the automaton of the library's own tables walked on the host for all streams at
+    once.  A stream's look-ups are a dependent chain, one lane each, whatever the bandwidth."""
+    import numpy as np
+    from paper_2406_06237_amd import binding as B
+    t = B.split_table(B.build_tables_host(h.freqs, h.table_log))
+    E = 2 << h.table_log                                                  # entries per table
+    bits, count, base = (t[k].reshape(-1).astype(np.int64) for k in ("la_bits", "la_count", "la_base"))
+    N = h.n_streams
+    n_sym = (np.maximum(h.chunks["n_symbols"].astype(np.int64)[:, None] - np.arange(N)[None, :] + N - 1, 0) // N).reshape(-1)
+    hdr = h.stream_hdr.astype(np.int64)
+    words = (hdr >> 16).reshape(-1, N)
+    first = (h.chunks["payload_offset"].astype(np.int64)[:, None] + np.cumsum(words, axis=1) - words).reshape(-1)
+    table0 = np.repeat(h.chunks["layer_id"].astype(np.int64) * E, N)
+    payload = np.concatenate([h.payload, np.zeros(4, np.uint32)]).astype(np.uint64)
+    rev13 = np.array([int(f"{v:013b}"[::-1], 2) for v in range(1 << 13)], dtype=np.int64)
+
+    def peek(pos, k):                                                     # next k <= 13 stream bits, first bit on top
+        w = first + (pos >> 5)
+        two = payload[w] | (payload[w + 1] << np.uint64(32))
+        return rev13[((two >> (pos & 31).astype(np.uint64)) & np.uint64(0x1FFF)).astype(np.int64)] >> (13 - k)
+
+    pos = np.zeros(len(hdr), np.int64)
+    idx = 2 * (hdr & ((1 << h.table_log) - 1)) + peek(pos, np.ones(len(hdr), np.int64))
+    left, lookups = n_sym.copy(), np.zeros(len(hdr), np.int64)
+    while True:
+        live = left > 0
+        if not live.any():
+            break
+        e = table0 + np.where(live, idx, 0)
+        idx = np.where(live, base[e] + peek(pos, bits[e] + 1), idx)
+        pos = np.where(live, pos + bits[e], pos)
+        left = left - np.where(live, count[e], 0)
+        lookups += live
+    return lookups.reshape(-1, N)
+
+
+def time_launches(B, torch, args, dev, steps, warmup):
+    """Average duration of one anszp_decode launch, events on the launch stream."""
+    stream = torch.cuda.current_stream(dev)
+    for _ in range(warmup):
+        B.decode_raw(args, dev)
+    torch.cuda.synchronize(dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        B.decode_raw(args, dev)
+    e1.record(stream)
+    torch.cuda.synchronize(dev)
+    return e0.elapsed_time(e1) / steps
+
+
+def chain_bound(w, h, steps):
+    """The second bound beside the HBM roofline: look-ups of the slowest stream x the time of one look-up.
+    The time of a look-up is measured in this run as a slope: the slowest chunk's layer decoded alone, as one
+    chunk of full size and as one chunk of half size (one workgroup each, so launch and staging cancel)."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2406_06237_amd import binding as B
+    from paper_2406_06237_amd import workloads as W
+    per_stream = lookups_per_stream(h)
+    slowest = int(np.argmax(per_stream.max(axis=1)))
+    layer = w.layers[int(h.chunks["layer_id"][slowest])]
+    full = min(w.chunk_size, layer.numel)
+    points = []
+    for n in (full, full // 2):
+        one = W.Workload(f"{layer.name}[:{n}]", [dataclasses.replace(layer, shape=(n,))], w.table_log, w.n_streams,
+                         w.chunk_size, w.out_dtype)
+        hh = B.pack_workload(one)
+        d = B.to_device(hh, "cuda:0")
+        out = B.alloc_out(d)
+        ms = time_launches(B, torch, B.decode_args(d, out), "cuda:0", steps, 10)
+        assert d.read_status() == (0, 0)
+        points.append((int(lookups_per_stream(hh).max()), ms * 1e3))
+    (s1, t1), (s0, t0) = points
+    ns = 1e3 * (t1 - t0) / max(1, s1 - s0)
+    s = int(per_stream.max())
+    return {"us": s * ns * 1e-3, "lookups_slowest_stream": s, "ns_per_lookup": ns,
+            "symbols_slowest_stream": int(-(-int(h.chunks["n_symbols"][slowest]) // w.n_streams)),
+            "how": f"slope of two one-chunk launches of layer {layer.name}: {s1} look-ups in {t1:.2f} us, {s0} in {t0:.2f} us "
+                   "(events on the launch stream); launch, staging and the wait for the last stores are not in it"}
+
+
+def replicate(h, k):
+    """k copies of a container side by side (own tables, words, headers and outputs), for one launch."""
+    import dataclasses
+    import numpy as np
+    chunks, layers = [], []
+    for r in range(k):
+        c, l = h.chunks.copy(), h.layers.copy()
+        c["layer_id"] += r * len(h.layers)
+        c["out_offset"] += r * h.numel
+        c["payload_offset"] += r * len(h.payload)
+        c["stream_offset"] += r * len(h.stream_hdr)
+        l["out_base"] += r * h.numel
+        l["scales_offset"] += r * len(h.scales)
+        chunks.append(c)
+        layers.append(l)
+    assert len(h.payload) % 4 == 0
+    return dataclasses.replace(h, freqs=np.tile(h.freqs, (k, 1)), layers=np.concatenate(layers), chunks=np.concatenate(chunks),
+                               stream_hdr=np.tile(h.stream_hdr, k), payload=np.tile(h.payload, k), scales=np.tile(h.scales, k),
+                               numel=h.numel * k)
+
+
+def steady_state(w, h, k, steps, elem_bytes):
+    """k replicas of the set decoded by ONE launch: what the kernel sustains once the chip is full.  Never the
+    headline: the headline decodes the set once per launch."""
+    import torch
+    from paper_2406_06237_amd import binding as B
+    d = B.to_device(replicate(h, k), "cuda:0")
+    out = B.alloc_out(d)
+    ms = time_launches(B, torch, B.decode_args(d, out), "cuda:0", steps, 5)
+    assert d.read_status() == (0, 0)
+    same = bool(torch.equal(out[:h.numel].view(torch.int16), out[(k - 1) * h.numel:k * h.numel].view(torch.int16))) \
+        if w.out_dtype == "bf16" else None
+    nbytes = k * (h.compressed_bytes() + w.numel * elem_bytes)
+    return {"label": f"{k} replicas of the set in one launch (not the headline)", "replicas": k, "kernel_ms": ms,
+            "Gsymbols_per_s": k * w.numel / (ms * 1e-3) / 1e9, "GBps": nbytes / (ms * 1e-3) / 1e9,
+            "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "first_and_last_replica_equal": same}
 
 
 def cpu_baseline(workload, repeats: int = 3):
@@ -50,17 +178,25 @@ def cpu_baseline(workload, repeats: int = 3):
     env = os.environ.get("OMP_NUM_THREADS")
     if env and env.isdigit():
         cores = max(1, min(cores, int(env)))
-    best = float("inf")
-    for _ in range(repeats):
-        t0 = time.perf_counter()
-        sym, wts, rc = oracle.decode_dequant(c, [l.zero_point for l in L], [l.scale for l in L],
-                                             [l.channel_len for l in L], [l.channel_scales for l in L],
-                                             out_dtype=workload.out_dtype, n_threads=cores, tables=tables)
-        best = min(best, time.perf_counter() - t0)
-        assert rc == 0
+
+    def timed(n_threads):
+        best, wts = float("inf"), None
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            sym, wts, rc = oracle.decode_dequant(c, [l.zero_point for l in L], [l.scale for l in L],
+                                                 [l.channel_len for l in L], [l.channel_scales for l in L],
+                                                 out_dtype=workload.out_dtype, n_threads=n_threads, tables=tables)
+            best = min(best, time.perf_counter() - t0)
+            assert rc == 0
+        return best, wts
+
+    best, wts = timed(cores)
+    single, _ = timed(1)
     return {"value": workload.numel / best / 1e9, "unit": "Gsymbols/s", "cores": cores, "kind": "oracle",
             "sample": f"whole {workload.name} set ({workload.numel} symbols), decode+dequant, best of {repeats}, "
-                      f"{best * 1e3:.1f} ms"}, wts
+                      f"{best * 1e3:.1f} ms",
+            "single_thread": {"value": workload.numel / single / 1e9, "unit": "Gsymbols/s", "cores": 1,
+                              "sample": f"the same set on one thread, best of {repeats}, {single * 1e3:.1f} ms"}}, wts
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
@@ -218,6 +354,8 @@ def main():
                     help="config 5 only: activations and outputs in blocks of 8 channels, or NHWC")
     ap.add_argument("--blocks", type=int, default=32, help="config 4 only: number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="config 3 only: leave out the ResNet-18-shaped set")
+    ap.add_argument("--no-extras", action="store_true", help="leave out the chain bound and the steady-state launch")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run a plain device copy of this many MiB five times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -229,12 +367,25 @@ def main():
     if args.config == 5:
         return bench_fused_conv(args)
 
+    result = bench_decode(args, args.config, headline=True)
+    if args.config == 3 and not args.no_secondary:
+        # the ResNet-18-shaped set beside the headline, same measurement (bench.py --config 4 and --config 5 run
+        # the large stack and the fused convolution: minutes each, not part of the default run)
+        sec = bench_decode(args, 2, headline=False)
+        result["secondary"] = [{k: sec[k] for k in ("config", "value", "unit", "ms_per_step", "roofline", "chain_bound",
+                                                    "cpu_baseline", "matches_oracle") if k in sec}]
+    print(json.dumps(result))
+
+
+def bench_decode(args, config, headline):
+    """One decode configuration: K launches timed on the wall clock and with events, the roofline of the
+    launch, the chain bound, and the oracle on the host cores with a bit-for-bit comparison."""
     import numpy as np
     import torch
     from paper_2406_06237_amd import binding as B
     from paper_2406_06237_amd import workloads as W
 
-    w = {1: W.config1, 2: W.config2, 3: W.config3}.get(args.config, lambda: W.config4(args.blocks))()
+    w = {1: W.config1, 2: W.config2, 3: W.config3}.get(config, lambda: W.config4(args.blocks))()
     h = B.pack_workload(w)                      # library's own host packer
     dev = "cuda:0"
     d = B.to_device(h, dev)
@@ -258,7 +409,7 @@ def main():
         print(f"bench.py: device status {status}", file=sys.stderr)
         sys.exit(1)
     kernel_ms = ev0.elapsed_time(ev1) / args.steps
-    if args.calib_copy:
+    if headline and args.calib_copy:
         src = torch.full((args.calib_copy << 20,), 7, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(5):
@@ -269,6 +420,7 @@ def main():
     elem_bytes = {"u8": 1, "f32": 4, "bf16": 2}[w.out_dtype]
     algo_bytes = h.compressed_bytes() + w.numel * elem_bytes
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    traffic, traffic_source = load_traffic(f"config{config}")
     result = {
         "metric": "decoded Gsymbols/s (tANS decode + zero-point dequant, whole weight set per step)",
         "value": w.numel / (ms_per_step * 1e-3) / 1e9,
@@ -276,7 +428,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
-        "config": {"workload": f"config{args.config}:{w.name}", "symbols": w.numel, "layers": len(w.layers),
+        "config": {"workload": f"config{config}:{w.name}", "symbols": w.numel, "layers": len(w.layers),
                    "chunks": int(len(h.chunks)), "streams_per_chunk": w.n_streams, "chunk_size": w.chunk_size,
                    "table_log": w.table_log, "out_dtype": w.out_dtype,
                    "compressed_bytes": h.compressed_bytes(),
@@ -284,16 +436,21 @@ def main():
                    "source_entropy_bits": w.model_entropy_bits()},
         "effective_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": load_traffic(f"config{args.config}"),
-                     "kernel_ms": kernel_ms, "algorithmic_bytes": algo_bytes},
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel_ms": kernel_ms, "algorithmic_bytes": algo_bytes,
+                     "timer": "events on the launch stream around the K launches / K"},
     }
+    if config in (2, 3) and not args.no_extras:
+        result["chain_bound"] = chain_bound(w, h, max(20, args.steps // 4))
+        if headline:
+            result["steady_state"] = steady_state(w, h, 8, max(10, args.steps // 10), elem_bytes)
     if not args.no_cpu_baseline:
         base, wts = cpu_baseline(w)
         result["cpu_baseline"] = base
         got = B.bits_of(out)[:w.numel]
         want = wts.view(np.uint32) if w.out_dtype == "f32" else wts
         result["matches_oracle"] = bool(np.array_equal(got, want))
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":

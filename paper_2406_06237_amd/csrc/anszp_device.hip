@@ -39,7 +39,8 @@ constexpr int kWave = 64;
 constexpr int kBlock = 768;                    // twelve wavefronts stage, eight of them stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
 constexpr uint32_t kBlockLookups = 8u;         // look-ups a lane makes per block of the look-ahead kernel
-constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + kWave * 4u;   // nine rows of 16 bits per lane, one of 32
+constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + 2u * kWave * 4u;   // nine rows of 16 bits per lane, two of 32
+constexpr uint32_t kExpanders = 2u;            // expanding wavefronts per chunk: they take the logged blocks in turn
 constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over between wavefronts is declared stuck
 
 // LDS geometry of the look-ahead kernel.  The large one takes tables of up to 2^12 states (64 KiB of
@@ -964,24 +965,44 @@ __device__ __forceinline__ uint32_t pair_level_of(uint32_t payload_words, uint32
     return level;
 }
 
+// A chunk descriptor as two 16-byte words, and back (the scan below keeps the descriptors it has read, so that
+// the unit's own need not be fetched again once the unit is known).
+struct ChunkWords { uint4 a, b; };
+__device__ __forceinline__ anszp_chunk_t chunk_of(const ChunkWords& w) {
+    anszp_chunk_t c;
+    c.layer_id = uniform(w.a.x); c.n_symbols = uniform(w.a.y);
+    c.out_offset = uniform(w.a.z) | (uint64_t(uniform(w.a.w)) << 32);
+    c.payload_offset = uniform(w.b.x) | (uint64_t(uniform(w.b.y)) << 32);
+    c.payload_words = uniform(w.b.z); c.stream_offset = uniform(w.b.w);
+    return c;
+}
+static_assert(sizeof(anszp_chunk_t) == 32, "two 16-byte words");
+
 template <uint32_t THREADS>
 __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uint32_t capacity, uint32_t pair_words,
-                                          uint64_t* masks /* LDS, kPairLevels * (kPairScanRounds * THREADS / 64 + 1) words of 8 bytes */) {
+                                          uint64_t* masks /* LDS, kPairLevels * (kPairScanRounds * THREADS / 64 + 1) + 8 words of 8 bytes */,
+                                          anszp_chunk_t& c0, anszp_chunk_t& c1 /* the unit's chunks (the second repeats the first in a unit of one) */) {
     constexpr uint32_t kWaves = THREADS / kWave;
     constexpr uint32_t kMasks = kPairScanRounds * kWaves;
     static_assert(kMasks <= kWave, "one mask per lane");
     const uint32_t n = p.n_chunks;
-    if (n > kPairScanRounds * THREADS || n <= capacity) return Unit{u, u < n ? 1u : 0u};
+    if (n > kPairScanRounds * THREADS || n <= capacity) {
+        if (u < n) c0 = c1 = p.chunks[u];
+        return Unit{u, u < n ? 1u : 0u};
+    }
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = uniform(tid >> 6);
     const uint32_t rounds = (n + THREADS - 1u) / THREADS;
     uint32_t* const units = reinterpret_cast<uint32_t*>(masks + kPairLevels * kMasks);     // units per level
+    ChunkWords* const handed = reinterpret_cast<ChunkWords*>(masks + kPairLevels * kMasks + 4u);   // the unit's descriptors
+    ChunkWords seen[kPairScanRounds];
     uint32_t layer[kPairScanRounds], words[kPairScanRounds], symbols[kPairScanRounds];
 #pragma unroll
     for (uint32_t k = 0; k < kPairScanRounds; ++k) {
         layer[k] = 0u; words[k] = 0u; symbols[k] = 1u;
         if (k < rounds) {
-            const anszp_chunk_t& c = p.chunks[min(k * THREADS + tid, n - 1u)];
-            layer[k] = c.layer_id; words[k] = c.payload_words; symbols[k] = c.n_symbols;
+            const uint4* c = reinterpret_cast<const uint4*>(p.chunks + min(k * THREADS + tid, n - 1u));
+            seen[k].a = c[0]; seen[k].b = c[1];
+            layer[k] = seen[k].a.x; words[k] = seen[k].b.z; symbols[k] = seen[k].a.y;
         }
     }
     if (tid < kPairLevels) units[tid] = 0u;              // (while the loads are in flight)
@@ -1038,6 +1059,17 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
         const uint64_t next_mask = (uint64_t(nhi) << 32) | nlo;
         if (!((next_mask >> (next % kWave)) & 1ull)) count = 2u;
     }
+    // the threads that read the unit's descriptors hand them to everybody
+#pragma unroll
+    for (uint32_t k = 0; k < kPairScanRounds; ++k) {
+        if (k >= rounds) break;
+        const uint32_t i = k * THREADS + tid;
+        if (i == first) handed[0] = seen[k];
+        if (i == first + count - 1u) handed[1] = seen[k];
+    }
+    __syncthreads();
+    c0 = chunk_of(handed[0]);
+    c1 = chunk_of(handed[1]);
     return Unit{uniform(first), uniform(count)};
 }
 
@@ -1074,7 +1106,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kWordsBytes = (kPayloadWords + kTailWords) * 4u;
     constexpr uint32_t kCtlOff = 0u;                                // within a chunk's area
     constexpr uint32_t kProgOff = kCtlOff + 64u;
-    constexpr uint32_t kLogOff = kProgOff + kWave * 4u;
+    constexpr uint32_t kLogOff = kProgOff + kExpanders * kWave * 4u;      // (positions: a row per expanding wavefront)
     constexpr uint32_t kWordsOff = kLogOff + kLogSlots * kLogSlotBytes;   // the compressed words come last: a single chunk's
     constexpr uint32_t kPipeBytes = kWordsOff + kWordsBytes;             // may run on through the second chunk's area
     constexpr uint32_t kSoloWords = (kWordsBytes + kPipeBytes) / 4u - kTailWords;
@@ -1086,9 +1118,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     static_assert(kLdsBytes * 8u < (1u << 22), "bit positions count from the start of LDS");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     uint16_t* const lds_lut = reinterpret_cast<uint16_t*>(lds + kLutOff);
-    // hand-over words of a chunk: 0 blocks logged | 1 blocks expanded | 2, 3 first element of the next slab
-    // each storing wavefront will take | 4 no more blocks will be logged | 5 a wait gave up
-    enum { kLogged = 0, kExpanded = 1, kStored0 = 2, kStored1 = 3, kOver = 4, kGaveUp = 5 };
+    // hand-over words of a chunk: 0 blocks logged | 1, 2 the next block each expanding wavefront will take |
+    // 3 no more blocks will be logged | 4..7 first element of the next slab each storing wavefront will take
+    // (all ones where there is no such wavefront) | 8 a wait gave up
+    enum { kLogged = 0, kNext0 = 1, kOver = 3, kStored0 = 4, kGaveUp = 8 };
+    constexpr uint32_t kMaxStorers = 4u;
+    static_assert(kExpanders == 2u, "hand-over words 1 and 2");
     constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
     constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 2u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
@@ -1101,25 +1136,27 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
 
+    anszp_chunk_t c0, c1;        // descriptors (the second repeats the first when the unit is a single chunk)
     const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, kPayloadWords,
-                                        reinterpret_cast<uint64_t*>(lds + kPipeOff));
+                                        reinterpret_cast<uint64_t*>(lds + kPipeOff), c0, c1);
     if (unit.count == 0u) return;
-    // descriptors (the second repeats the first when the unit is a single chunk)
-    const anszp_chunk_t c0 = p.chunks[unit.first], c1 = p.chunks[unit.first + unit.count - 1u];
-    const bool in0 = chunk_in_bounds(p, c0) && scales_in_bounds(p, p.layers[c0.layer_id], c0);
-    const bool in1 = unit.count == 2u && chunk_in_bounds(p, c1) && scales_in_bounds(p, p.layers[c1.layer_id], c1);
-    if (tid == 0) {
-        if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
-        if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
-        if (lds_address(lds) != 0u) report(p.status, ANSZP_ST_INTERNAL);       // the hand-written parts address LDS from 0
+    // What the loads below touch depends on the chunk descriptors alone; whether the layer's scales cover the
+    // chunks is looked at once the layer's descriptor has arrived, with everything else already on its way.
+    const bool ok0 = chunk_in_bounds(p, c0), ok1 = unit.count == 2u && chunk_in_bounds(p, c1);
+    if ((!ok0 && !ok1) || lds_address(lds) != 0u) {
+        if (tid == 0) {
+            report(p.status, lds_address(lds) != 0u ? ANSZP_ST_INTERNAL : ANSZP_ST_BAD_DESC);   // the hand-written parts address LDS from 0
+            if (unit.count == 2u && lds_address(lds) == 0u) report(p.status, ANSZP_ST_BAD_DESC);
+        }
+        return;
     }
-    if ((!in0 && !in1) || lds_address(lds) != 0u) return;
-    const uint32_t layer_id = in0 ? c0.layer_id : c1.layer_id;      // both alike when both are in bounds
+    const uint32_t layer_id = ok0 ? c0.layer_id : c1.layer_id;      // both alike when both are in bounds
+    const anszp_layer_t lay = p.layers[layer_id];
 
     // Issue every global read that depends only on the descriptors before waiting for any of them (the
     // stream headers first: they are used first).
-    const uint32_t hdr0 = (in0 && lane < N) ? p.stream_hdr[c0.stream_offset + lane] : 0u;
-    const uint32_t hdr1 = (in1 && lane < N) ? p.stream_hdr[c1.stream_offset + lane] : 0u;
+    const uint32_t hdr0 = (ok0 && lane < N) ? p.stream_hdr[c0.stream_offset + lane] : 0u;
+    const uint32_t hdr1 = (ok1 && lane < N) ? p.stream_hdr[c1.stream_offset + lane] : 0u;
     const uint32_t* src = p.tables + layer_id * table_stride_words(p.table_log);
     const uint4* tsrc = reinterpret_cast<const uint4*>(src + table_lookahead_offset(p.table_log));   // 2 entries per load
     const uint32_t t_last = L - 1u;
@@ -1136,8 +1173,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRowsPerChunk = kWordLoads * kBlock;       // 16-byte rows of words a chunk's loads cover
     const bool single = unit.count == 1u;
     const uint32_t window0 = single ? kSoloWords : kPayloadWords;
-    const uint32_t quads0 = in0 ? min(c0.payload_words, window0) >> 2 : 0u;
-    const uint32_t quads1 = in1 ? min(c1.payload_words, kPayloadWords) >> 2 : (single && quads0 > kRowsPerChunk ? quads0 - kRowsPerChunk : 0u);
+    const uint32_t quads0 = ok0 ? min(c0.payload_words, window0) >> 2 : 0u;
+    const uint32_t quads1 = ok1 ? min(c1.payload_words, kPayloadWords) >> 2 : (single && quads0 > kRowsPerChunk ? quads0 - kRowsPerChunk : 0u);
     const uint4* wsrc0 = quads0 ? reinterpret_cast<const uint4*>(p.payload + c0.payload_offset) : tsrc;
     const uint4* wsrc1 = !quads1 ? tsrc : single ? wsrc0 + kRowsPerChunk : reinterpret_cast<const uint4*>(p.payload + c1.payload_offset);
     const uint32_t w_last0 = quads0 ? min(quads0, kRowsPerChunk) - 1u : 0u, w_last1 = quads1 ? quads1 - 1u : 0u;
@@ -1145,12 +1182,16 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     uint4 wv01 = wv00, wv11 = wv10;
     if constexpr (kWordLoads > 1u) { wv01 = wsrc0[min(tid + kBlock, w_last0)]; wv11 = wsrc1[min(tid + kBlock, w_last1)]; }
     uint32_t tail0 = 0, tail1 = 0;                        // the words behind the last whole row of four
-    if (in0 && tid < kTailWords && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= window0)
+    if (ok0 && tid < kTailWords && (quads0 << 2) + tid < c0.payload_words && c0.payload_words <= window0)
         tail0 = p.payload[c0.payload_offset + (quads0 << 2) + tid];
-    if (in1 && tid < kTailWords && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
+    if (ok1 && tid < kTailWords && (quads1 << 2) + tid < c1.payload_words && c1.payload_words <= kPayloadWords)
         tail1 = p.payload[c1.payload_offset + (quads1 << 2) + tid];
     const uint32_t top = src[table_triples_offset(p.table_log) + L - 1u];   // state L-1 carries the dominant symbol if there is one
-    const anszp_layer_t lay = p.layers[layer_id];
+    const bool in0 = ok0 && scales_in_bounds(p, lay, c0), in1 = ok1 && scales_in_bounds(p, lay, c1);
+    if (tid == 0) {
+        if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
+        if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
+    }
     // While those loads are in flight: where every stream's words begin, and the SIMD every wavefront
     // runs on (HW_ID bits 4..5).
     uint32_t total_words0, total_words1;
@@ -1162,8 +1203,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // wavefronts get a SIMD each that they share with nothing but wavefronts that leave after staging;
     // expanding and storing wavefronts share the other two.  The second workgroup of a CU (small
     // geometry) mirrors the choice.
-    enum { kDecode = 0, kExpand = 1, kStore0 = 2, kStore1 = 3, kNoTask = 4 };
-    uint32_t task = kNoTask, pipe = 0;
+    enum { kDecode = 0, kExpand = 1, kStore = 2, kNoTask = 3 };
+    uint32_t task = kNoTask, pipe = 0, sub = 0;          // sub: which of the chunk's expanding or storing wavefronts
+    const uint32_t storers = unit.count == 1u ? 4u : 3u; // storing wavefronts per chunk
     {
         constexpr uint32_t kWaves = kBlock / kWave;
         const uint32_t flip = G::kWorkgroupsPerCu > 1u ? ((blockIdx.x / max(p.n_cus, 1u)) & 1u) * 2u : 0u;
@@ -1173,24 +1215,33 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         const uint32_t rank = static_cast<uint32_t>(__popcll(same & ((1ull << wave) - 1ull)));
         const bool even = __popcll(__ballot(theirs == 0u)) == 3 && __popcll(__ballot(theirs == 1u)) == 3 &&
                           __popcll(__ballot(theirs == 2u)) == 3 && __popcll(__ballot(theirs == 3u)) == 3;
-        // three wavefronts on every SIMD: SIMD 0, 1: the first decodes chunk 0, 1, the others leave;
-        // SIMD 2, 3: the first expands chunk 0, 1, the second stores for chunk 0, the third for chunk 1.
-        // Any other placement: tasks by wavefront number.
-        const uint32_t s2 = even ? my_simd ^ flip : (wave < 4u ? wave : (wave - 4u) & 1u);
-        const uint32_t r2 = even ? rank : (wave < 4u ? 0u : wave < 8u ? 1u + ((wave - 4u) >> 1) : 3u);
+        // three wavefronts on every SIMD (s2: the SIMD, r2: which of its three); any other placement: as
+        // if wavefront w ran on SIMD w mod 4.
+        const uint32_t s2 = even ? my_simd ^ flip : (wave & 3u);
+        const uint32_t r2 = even ? rank : (wave >> 2);
         if (unit.count == 1u) {
-            // one chunk: a SIMD per task (decode, expand, the two storing wavefronts)
-            if (r2 == 0u) task = s2;
+            // one chunk: SIMD 0 decodes and does nothing else, SIMD 1 and 2 expand and store, SIMD 3 stores twice
+            if (r2 == 0u) {
+                if (s2 == 0u) task = kDecode;
+                else if (s2 < 3u) { task = kExpand; sub = s2 - 1u; }
+                else task = kStore;
+            } else if (r2 == 1u && s2 != 0u) {
+                task = kStore; sub = s2 == 3u ? 1u : s2 + 1u;
+            }
         } else if (s2 < 2u) {
-            // two chunks.  SIMD 0, 1: decode chunk 0, 1, and one storing wavefront of either chunk; SIMD 2, 3: expand chunk 0, 1
+            // two chunks.  SIMD 0, 1: decode chunk 0, 1, and one storing wavefront of either chunk;
+            // SIMD 2, 3: expand chunk 0, 1 (two wavefronts), and the chunk's third storing wavefront
             if (r2 == 0u) { task = kDecode; pipe = s2; }
-            else if (r2 < 3u) { task = kStore0 + ((r2 - 1u) ^ s2); pipe = r2 - 1u; }
-        } else if (r2 == 0u) {
-            task = kExpand; pipe = s2 - 2u;
+            else { task = kStore; sub = (r2 - 1u) ^ s2; pipe = r2 - 1u; }
+        } else if (r2 < kExpanders) {
+            task = kExpand; pipe = s2 - 2u; sub = r2;
+        } else {
+            task = kStore; pipe = s2 - 2u; sub = 2u;
         }
     }
     pipe = uniform(pipe);
     task = uniform(task);
+    sub = uniform(sub);
 
     // ---- stage: look-ahead entries, both chunks' compressed words, symbol -> bf16, ring background, hand-over words
     {
@@ -1216,16 +1267,19 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
         if (tid < (single ? 16u : 2u * 16u)) {            // hand-over words (of both chunks)
             const uint32_t q = tid / 16u, i = tid % 16u;
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = (i == kStored1) ? kSlab : 0u;
+            uint32_t v = 0u;
+            if (i >= kNext0 && i < kNext0 + kExpanders) v = i - kNext0;
+            if (i >= kStored0 && i < kStored0 + kMaxStorers) v = i - kStored0 < storers ? (i - kStored0) * kSlab : 0xFFFFFFFFu;
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = v;
         }
         for (uint32_t t = tid; t < (single ? 1u : 2u) * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
             const uint32_t q = t / (kLogSlots * kWave), i = t % (kLogSlots * kWave);
             reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + (kBlockLookups + 1u) * 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
         }
-        if (tid < (single ? 1u : 2u) * kWave) {           // where every stream is: its first element, or nothing to wait for
-            const uint32_t q = tid / kWave, l = tid % kWave;
+        if (tid < (single ? 1u : 2u) * kExpanders * kWave) {   // where every stream is: its first element, or nothing to wait for
+            const uint32_t q = tid / (kExpanders * kWave), l = tid % kWave;
             const uint32_t n_q = q ? (in1 ? c1.n_symbols : 0u) : (in0 ? c0.n_symbols : 0u);
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[l] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[tid % (kExpanders * kWave)] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
         }
     }
     const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the rings' background: the dominant symbol
@@ -1277,30 +1331,37 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u, hi, lds_lut);
     };
 
-    if (task == kStore0 || task == kStore1) {
-        // ---- storing wavefronts: one takes the even slabs, the other the odd ones
-        const uint32_t which = task - kStore0;
-        uint32_t mine = which * kSlab, spins = 0;        // first element of the next slab this one takes
+    if (task == kStore) {
+        // ---- storing wavefronts: wavefront `sub` takes every `storers`-th slab
+        uint32_t mine = sub * kSlab, spins = 0;          // first element of the next slab this one takes
         for (;;) {
-            uint32_t over_v, logged_v, expanded_v, next;
+            uint32_t over_v, next_a, next_b;
+            uint2 logged_next;                            // blocks logged, the first expanding wavefront's next block
+            uint32_t next_1;
             asm volatile(                                // the flag first, the positions last
-                "ds_read_b32 %[ov], %[ctla] offset:16\n"
-                "ds_read_b32 %[lg], %[ctla]\n"
-                "ds_read_b32 %[ex], %[ctla] offset:4\n"
-                "ds_read_b32 %[nx], %[pa]\n"
+                "ds_read_b32 %[ov], %[ctla] offset:12\n"
+                "ds_read2_b32 %[ln], %[ctla] offset1:1\n"
+                "ds_read_b32 %[n1], %[ctla] offset:8\n"
+                "ds_read_b32 %[na], %[pa]\n"
+                "ds_read_b32 %[nb], %[pa] offset:256\n"
                 "s_waitcnt lgkmcnt(0)\n"
-                : [ov] "=&v"(over_v), [lg] "=&v"(logged_v), [ex] "=&v"(expanded_v), [nx] "=&v"(next)
+                : [ov] "=&v"(over_v), [ln] "=&v"(logged_next), [n1] "=&v"(next_1), [na] "=&v"(next_a), [nb] "=&v"(next_b)
                 : [ctla] "v"(pipe_off + kCtlOff), [pa] "v"(pipe_off + kProgOff + lane * 4u)
                 : "memory");
-            // everything logged was expanded before the positions were read: no more will come
-            const bool last_pass = uniform(over_v) && uniform(logged_v) == uniform(expanded_v);
+            static_assert(kExpanders == 2u && kWave * 4u == 256u, "two rows of positions, 256 bytes apart");
+            // A block is expanded once the wavefront whose turn it was has moved past it: every block below both
+            // wavefronts' next one is, and a lane's position after the last of those is the smaller of the two
+            // rows (positions only grow).  Once no more blocks will be logged and all have been expanded, every
+            // stream is complete (the row of the wavefront that did not expand the last block stays behind).
+            const bool last_pass = uniform(over_v) && uniform(logged_next.x) <= min(uniform(logged_next.y), uniform(next_1));
+            const uint32_t next = last_pass ? 0xFFFFFFFFu : min(next_a, next_b);
             const uint32_t before = mine;
             while (mine + kSlab <= n && __ballot(next < mine + kSlab) == 0) {
                 store_slab(mine);
-                mine += 2u * kSlab;
+                mine += storers * kSlab;
             }
             if (mine != before) {
-                asm volatile("ds_write_b32 %[wa], %[st]\n" :: [wa] "v"(pipe_off + kCtlOff + 4u * (kStored0 + which)), [st] "v"(mine) : "memory");
+                asm volatile("ds_write_b32 %[wa], %[st]\n" :: [wa] "v"(pipe_off + kCtlOff + 4u * (kStored0 + sub)), [st] "v"(mine) : "memory");
                 spins = 0;
             }
             if (last_pass) break;
@@ -1315,7 +1376,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         }
         // the elements behind the last whole slab, by the wavefront whose turn that slab would have been
         const uint32_t rest = n / kSlab * kSlab;
-        if (((rest / kSlab) & 1u) == which)
+        if ((rest / kSlab) % storers == sub)
             for (uint32_t j = rest + lane; j < n; j += kWave)
                 Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & ring_mask], lds_lut);
         return;
@@ -1325,28 +1386,65 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t first_bit = (words_off + 4u * min(first_word, c.payload_words)) << 3;   // counted from the start of LDS
 
     if (task == kExpand) {
-        // ---- expanding wavefront.  Every pass reads the count of logged blocks and, in the same batch
-        // of LDS reads, the header and the entries of the block it waits for: if the count (read
-        // first) says the block is there, what was read after it is the block.
-        __builtin_amdgcn_s_setprio(2);                   // ahead of the storing wavefronts it shares a SIMD with
-        uint32_t ne = (lane < N && lane < n) ? lane : lane_end;   // chunk index of this lane's next symbol
-        uint32_t at_bit = first_bit;                     // where the stream stood when its last block began
-        uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
-        bool ended = ne >= lane_end;                     // no symbols: the initial state must be the final one
-        if (lane < N && ended) {
+        // ---- expanding wavefronts.  The two of a chunk take the logged blocks in turn (this one: sub, sub + 2,
+        // ...); a block's log slot holds all a block needs: the position of every lane when the block began, the
+        // entries, where the lane's next look-up starts, and the lane's bit position after the block, tagged with
+        // the block's number by the lanes that took part.  Every pass reads the count of logged blocks and, in
+        // the same batch of LDS reads, the slot: if the count (read first) says the block is there, what was
+        // read after it is the block.
+        __builtin_amdgcn_s_setprio(2);                   // ahead of the storing wavefronts
+        uint32_t err = (sub == 0u && total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
+        if (sub == 0u && lane < N && !(lane < n)) {      // no symbols: the initial state must be the final one
             if ((hdr & (L - 1u)) != 0u) err |= ANSZP_ST_BAD_STATE;
             if (n_words != 0u) err |= ANSZP_ST_BAD_LENGTH;
         }
-        uint32_t expanded = 0, spins = 0;
+        uint32_t block = sub, spins = 0;
+        uint32_t ne = (lane < N && lane < n) ? lane : 0xFFFFFFF0u;          // as staged: after the last block (none yet)
         constexpr uint32_t kBitRow = (kBlockLookups + 1u) * 2u * kWave;      // offset of the row of bit positions in a log slot
+        constexpr uint32_t kPosRow = kBitRow + 4u * kWave;                   // and of the row of positions
         typedef __attribute__((address_space(3))) uint8_t lds_uint8_t;
         const uint32_t ring_at = lds_address(ring8);     // a multiple of the ring's size: its bits and an element's index do not overlap
-        // One logged block: entries 0..7 (bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0), 8: address
-        // of the lane's next entry; the lane's bit position after the block, tagged with the block's number
-        // by the lanes that took part in it.
-        auto expand_block = [&](const uint32_t (&ent)[kBlockLookups + 1u], uint32_t bit_after, uint32_t block) {
-            if (!ended && (bit_after >> 22) == (block & 0x3FFu)) {
-                const uint32_t ne_before = ne;
+        for (;;) {
+            const uint32_t slot = block & (kLogSlots - 1u);
+            uint32_t logged_v, ent[kBlockLookups + 1u], bit_after, ne_before;
+            asm volatile(
+                "ds_read_b32 %[lg], %[ctla]\n"
+                "ds_read_u16 %[a0], %[loga]\n"
+                "ds_read_u16 %[a1], %[loga] offset:128\n"
+                "ds_read_u16 %[a2], %[loga] offset:256\n"
+                "ds_read_u16 %[a3], %[loga] offset:384\n"
+                "ds_read_u16 %[a4], %[loga] offset:512\n"
+                "ds_read_u16 %[a5], %[loga] offset:640\n"
+                "ds_read_u16 %[a6], %[loga] offset:768\n"
+                "ds_read_u16 %[a7], %[loga] offset:896\n"
+                "ds_read_u16 %[a8], %[loga] offset:1024\n"
+                "ds_read_b32 %[ba], %[bita] offset:%[bitrow]\n"
+                "ds_read_b32 %[nb], %[bita] offset:%[posrow]\n"
+                "s_waitcnt lgkmcnt(0)\n"
+                : [lg] "=&v"(logged_v), [ba] "=&v"(bit_after), [nb] "=&v"(ne_before),
+                  [a0] "=&v"(ent[0]), [a1] "=&v"(ent[1]), [a2] "=&v"(ent[2]), [a3] "=&v"(ent[3]), [a4] "=&v"(ent[4]),
+                  [a5] "=&v"(ent[5]), [a6] "=&v"(ent[6]), [a7] "=&v"(ent[7]), [a8] "=&v"(ent[8])
+                : [ctla] "v"(pipe_off + kCtlOff),
+                  [loga] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 2u), [bita] "v"(pipe_off + kLogOff + slot * kLogSlotBytes + lane * 4u),
+                  [bitrow] "n"(kBitRow), [posrow] "n"(kPosRow)
+                : "memory");
+            if (uniform(logged_v) <= block) {            // not logged yet
+                if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
+                    if (uniform(ctl[kLogged]) <= block) break;
+                    continue;
+                }
+                if (uniform(ctl[kGaveUp])) return;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
+                    return;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                continue;
+            }
+            spins = 0;
+            ne = ne_before;                              // (every lane's, whether it took part or not)
+            if ((bit_after >> 22) == (block & 0x3FFu) && ne_before < lane_end) {    // (a lane that never took part keeps the tag it was staged with)
+                // entries 0..7: bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0; 8: address of the lane's next entry
 #pragma unroll
                 for (uint32_t k = 0; k < kBlockLookups; ++k) {
                     const uint32_t last = __umul24((ent[k] >> 12) & 7u, N) + ne;
@@ -1354,8 +1452,10 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                     ne = last + N;
                 }
                 if (ne >= lane_end) {                    // the stream's last symbol lies in this block: find its entry
-                    ended = true;
-                    uint32_t pos = ne_before, bits = at_bit;
+                    uint32_t consumed = 0;
+#pragma unroll
+                    for (uint32_t k = 0; k < kBlockLookups; ++k) consumed += (ent[k] >> 8) & 15u;
+                    uint32_t pos = ne_before, bits = (bit_after & 0x3FFFFFu) - consumed;     // where the stream stood when the block began
                     bool found = false;
 #pragma unroll
                     for (uint32_t k = 0; k < kBlockLookups; ++k) {
@@ -1371,78 +1471,17 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                         pos = after;
                     }
                 }
-                at_bit = bit_after & 0x3FFFFFu;
             }
-        };
-        // Every pass reads the count of logged blocks and, in the same batch of LDS reads, the next two
-        // log slots: if the count (read first) says a block is there, what was read after it is the block.
-        // Two blocks per pass when the decoding wavefront is that far ahead: a pass costs about as much in
-        // waiting and bookkeeping as a block does in work.
-        static_assert(kLogSlots >= 2u, "two slots are read per pass");
-        for (;;) {
-            const uint32_t slot_a = expanded & (kLogSlots - 1u), slot_b = (expanded + 1u) & (kLogSlots - 1u);
-            uint32_t logged_v, ea[kBlockLookups + 1u], eb[kBlockLookups + 1u], bit_a, bit_b;
-            asm volatile(
-                "ds_read_b32 %[lg], %[ctla]\n"
-                "ds_read_u16 %[a0], %[loga]\n"
-                "ds_read_u16 %[a1], %[loga] offset:128\n"
-                "ds_read_u16 %[a2], %[loga] offset:256\n"
-                "ds_read_u16 %[a3], %[loga] offset:384\n"
-                "ds_read_u16 %[a4], %[loga] offset:512\n"
-                "ds_read_u16 %[a5], %[loga] offset:640\n"
-                "ds_read_u16 %[a6], %[loga] offset:768\n"
-                "ds_read_u16 %[a7], %[loga] offset:896\n"
-                "ds_read_u16 %[a8], %[loga] offset:1024\n"
-                "ds_read_b32 %[ba], %[bita] offset:%[bitrow]\n"
-                "ds_read_u16 %[b0], %[logb]\n"
-                "ds_read_u16 %[b1], %[logb] offset:128\n"
-                "ds_read_u16 %[b2], %[logb] offset:256\n"
-                "ds_read_u16 %[b3], %[logb] offset:384\n"
-                "ds_read_u16 %[b4], %[logb] offset:512\n"
-                "ds_read_u16 %[b5], %[logb] offset:640\n"
-                "ds_read_u16 %[b6], %[logb] offset:768\n"
-                "ds_read_u16 %[b7], %[logb] offset:896\n"
-                "ds_read_u16 %[b8], %[logb] offset:1024\n"
-                "ds_read_b32 %[bb], %[bitb] offset:%[bitrow]\n"
-                "s_waitcnt lgkmcnt(0)\n"
-                : [lg] "=&v"(logged_v), [ba] "=&v"(bit_a), [bb] "=&v"(bit_b),
-                  [a0] "=&v"(ea[0]), [a1] "=&v"(ea[1]), [a2] "=&v"(ea[2]), [a3] "=&v"(ea[3]), [a4] "=&v"(ea[4]),
-                  [a5] "=&v"(ea[5]), [a6] "=&v"(ea[6]), [a7] "=&v"(ea[7]), [a8] "=&v"(ea[8]),
-                  [b0] "=&v"(eb[0]), [b1] "=&v"(eb[1]), [b2] "=&v"(eb[2]), [b3] "=&v"(eb[3]), [b4] "=&v"(eb[4]),
-                  [b5] "=&v"(eb[5]), [b6] "=&v"(eb[6]), [b7] "=&v"(eb[7]), [b8] "=&v"(eb[8])
-                : [ctla] "v"(pipe_off + kCtlOff),
-                  [loga] "v"(pipe_off + kLogOff + slot_a * kLogSlotBytes + lane * 2u), [bita] "v"(pipe_off + kLogOff + slot_a * kLogSlotBytes + lane * 4u),
-                  [logb] "v"(pipe_off + kLogOff + slot_b * kLogSlotBytes + lane * 2u), [bitb] "v"(pipe_off + kLogOff + slot_b * kLogSlotBytes + lane * 4u),
-                  [bitrow] "n"(kBitRow)
-                : "memory");
-            const uint32_t ahead = uniform(logged_v) - expanded;
-            if (ahead == 0u) {                           // nothing new
-                if (uniform(ctl[kOver])) {               // the count may have moved before the flag was set
-                    if (uniform(ctl[kLogged]) == expanded) break;
-                    continue;
-                }
-                if (uniform(ctl[kGaveUp])) return;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
-                    return;
-                }
-                __builtin_amdgcn_s_sleep(1);
-                continue;
-            }
-            spins = 0;
-            expand_block(ea, bit_a, expanded);
-            ++expanded;
-            if (ahead >= 2u) {
-                expand_block(eb, bit_b, expanded);
-                ++expanded;
-            }
-            // publish the lanes' positions, then the count, issued after the ring writes above
+            block += kExpanders;
+            // publish the lanes' positions, then the next block, issued after the ring writes above
             asm volatile("ds_write_b32 %[pa], %[ne]\n"
-                         "ds_write_b32 %[ctla], %[ex] offset:4\n"
-                         :: [pa] "v"(pipe_off + kProgOff + lane * 4u), [ne] "v"(ne), [ctla] "v"(pipe_off + kCtlOff), [ex] "v"(expanded)
+                         "ds_write_b32 %[nxa], %[nx]\n"
+                         :: [pa] "v"(pipe_off + kProgOff + sub * (kWave * 4u) + lane * 4u), [ne] "v"(ne),
+                            [nxa] "v"(pipe_off + kCtlOff + 4u * (kNext0 + sub)), [nx] "v"(block)
                          : "memory");
         }
-        if (lane < N && !ended) err |= ANSZP_ST_INTERNAL;  // cannot happen: the decoding wavefront logs until every stream has ended
+        // the wavefront that expanded the last block knows where every stream stands: at its end
+        if (block >= kExpanders && uniform(ctl[kLogged]) == block - kExpanders + 1u && lane < N && ne < lane_end) err |= ANSZP_ST_INTERNAL;
         err = wave_or(err);
         if (err && lane == 0) report(p.status, err);
         return;
@@ -1459,12 +1498,14 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     uint32_t ne = (lane < N && lane < n) ? lane : lane_end;
     uint32_t logged = 0, spins = 0;
     bool gave_up = false;
-    // the first four hand-over words in one LDS read
-    auto hand_over_words = [&]() {
+    // the first eight hand-over words in two LDS reads
+    auto hand_over_words = [&](uint4& stored) {
         uint4 v;
-        asm volatile("ds_read_b128 %[v], %[ctla]\n s_waitcnt lgkmcnt(0)\n" : [v] "=v"(v) : [ctla] "v"(pipe_off + kCtlOff) : "memory");
+        asm volatile("ds_read_b128 %[v], %[ctla]\n ds_read_b128 %[w], %[ctla] offset:16\n s_waitcnt lgkmcnt(0)\n"
+                     : [v] "=&v"(v), [w] "=&v"(stored) : [ctla] "v"(pipe_off + kCtlOff) : "memory");
         return v;
     };
+    static_assert(kLogged == 0 && kNext0 == 1 && kExpanders == 2u && kStored0 == 4 && kMaxStorers == 4u, "the hand-over words as the decoding wavefront reads them");
     // A block of 8 look-ups, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and
     // what a look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
     //   v = r >> (31 - T)            the next T+1 stream bits, r = the window's first word bit-reversed
@@ -1497,7 +1538,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n")
 #define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n")
     static_assert(ANSZP_MAX_TABLE_LOG <= 12 && kBlockLookups == 8u, "the reach of a look-up assumed by the window shifts");
-    static_assert(kLogSlotBytes == 1408u, "log slot: nine rows of 16 bits per lane, then a row of 32");
+    static_assert(kLogSlotBytes == 1664u, "log slot: nine rows of 16 bits per lane, then two rows of 32");
     const uint32_t reach = kBlockLookups * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 8 entries of 8 symbols
     if (reach >= ring_elems) {                                            // (the host picks a geometry with room)
         if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
@@ -1506,8 +1547,10 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t room = ring_elems - reach;
     while (!gave_up) {
         if (__ballot(ne < lane_end) == 0) break;          // every stream has ended
-        const uint4 seen = hand_over_words();
-        const uint32_t stored = min(uniform(seen.z), uniform(seen.w)), expanded = uniform(seen.y);
+        uint4 slabs;
+        const uint4 seen = hand_over_words(slabs);
+        const uint32_t stored = min(min(uniform(slabs.x), uniform(slabs.y)), min(uniform(slabs.z), uniform(slabs.w)));
+        const uint32_t expanded = min(uniform(seen.y), uniform(seen.z));      // every block below this one has been expanded
         const uint32_t limit = min(lane_end, stored + room);
         if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) {        // ring or log full: wait
             if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;
@@ -1527,14 +1570,17 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, blocks expanded, elements stored (two) */
-            "s_and_b64 exec, s[40:41], vcc\n"          /* lanes that run this block (some do) */
+            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, the expanding wavefronts' next blocks */
+            "ds_read_b128 v[54:57], v43 offset:16\n"   /* elements stored (by up to four wavefronts) */
+            "s_and_b64 s[42:43], s[40:41], vcc\n"      /* lanes that run this block (some do) */
             "1:\n"
             "s_and_b32 s45, s44, %[slotmask]\n"        /* the block's log slot */
-            "s_mul_i32 s46, s45, 1408\n"
+            "s_mul_i32 s46, s45, 1664\n"
             "v_add_u32 v42, s46, %[lanelog]\n"         /* this lane's 16-bit column in the slot */
-            "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the row of bit positions */
-            "s_waitcnt lgkmcnt(1)\n"                   /* the window words; the hand-over words were asked for last */
+            "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the rows of bit positions and positions */
+            "ds_write_b32 v47, v39 offset:%[posrow]\n" /* where every lane stands as the block begins */
+            "s_mov_b64 exec, s[42:43]\n"
+            "s_waitcnt lgkmcnt(3)\n"                   /* the window words; the hand-over words were asked for after them */
             "v_alignbit_b32 v28, v29, v28, v52\n"
             "v_alignbit_b32 v29, v30, v29, v52\n"
             "v_alignbit_b32 v30, v31, v30, v52\n"
@@ -1554,7 +1600,6 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "v_add_u32 v52, v52, v46\n"
             "v_lshl_or_b32 v46, s44, 22, v52\n"       /* bit position after the block, tagged with the block's number */
             "ds_write_b32 v47, v46 offset:%[bitrow]\n"
-            "s_mov_b64 s[42:43], exec\n"
             "s_mov_b64 exec, s[40:41]\n"               /* every lane reloads its words */
             "v_lshrrev_b32 v38, 3, v52\n"
             "v_and_b32 v38, 0x1ffffffc, v38\n"
@@ -1568,17 +1613,20 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "s_add_u32 s44, s44, 1\n"
             "v_mov_b32 v46, s44\n"
             "ds_write_b32 v43, v46\n"                  /* publish the block */
-            "v_readfirstlane_b32 s46, v49\n"           /* blocks expanded when the previous block ended */
+            "v_min_u32 v49, v49, v50\n"                /* blocks expanded when the previous block ended: every one */
+            "v_readfirstlane_b32 s46, v49\n"           /* below the next of either expanding wavefront */
             "s_mov_b64 exec, s[40:41]\n"
-            "v_min_u32 v50, v50, v51\n"                /* elements stored when the previous block ended: every */
-            "v_add_u32 v50, %[room], v50\n"            /* slab below the next one of either storing wavefront */
+            "v_min3_u32 v50, v54, v55, v56\n"          /* elements stored when the previous block ended: every */
+            "v_min_u32 v50, v50, v57\n"                /* slab below the next one of any storing wavefront */
+            "v_add_u32 v50, %[room], v50\n"
             "v_min_u32 v50, %[lend], v50\n"
             "v_cmp_gt_u32 vcc, v50, v39\n"             /* lanes that can run another block */
             "ds_read_b128 v[48:51], v43\n"             /* the same words, for the end of the next block */
+            "ds_read_b128 v[54:57], v43 offset:16\n"
             "s_sub_u32 s46, s44, s46\n"
             "s_cmp_ge_u32 s46, %[slots]\n"             /* the next log slot may still be in use */
             "s_cbranch_scc1 2f\n"
-            "s_and_b64 exec, s[40:41], vcc\n"
+            "s_and_b64 s[42:43], s[40:41], vcc\n"
             "s_cbranch_scc1 1b\n"
             "2:\n"
             "s_mov_b64 exec, s[40:41]\n"
@@ -1589,10 +1637,11 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             : [lim] "v"(limit), [lend] "v"(lane_end), [room] "s"(uniform(room)), [nstr] "s"(uniform(N)),
               [lastw] "s"(uniform(last_word)), [ctla] "s"(uniform(pipe_off + kCtlOff)),
               [lanelog] "v"(pipe_off + kLogOff + lane * 2u), [lanebit] "v"(pipe_off + kLogOff + lane * 4u),
-              [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [bitrow] "n"((kBlockLookups + 1u) * 2u * kWave)
+              [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [bitrow] "n"((kBlockLookups + 1u) * 2u * kWave),
+              [posrow] "n"((kBlockLookups + 1u) * 2u * kWave + 4u * kWave)
             : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "v24", "v25", "v26", "v27", "v28", "v29", "v30",
               "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v42", "v43", "v46", "v47",
-              "v48", "v49", "v50", "v51", "v52", "v53");
+              "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57");
         logged = uniform(logged_v);
     }
 #undef ANSZP_FIRST
