@@ -224,6 +224,29 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  * Errors: as anszp_decode, E_RANGE for an unknown variant or variant 5 with table_log > 8. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 
+/* Sec. III-A: the weights of a network are decoded again at every inference, from arrays that do not
+ * change.  What every launch of anszp_decode first works out on the device (which chunks of a layer
+ * share a workgroup and its on-chip copy of the layer's table, in which order the chip's dies take
+ * them) can therefore be prepared once: anszp_plan_decode writes it to plan_dev, anszp_decode_planned
+ * decodes with it and gives the same output and status words as anszp_decode.
+ *   anszp_plan_bytes    bytes of device memory a plan for n_chunks chunks takes (128 per workgroup of
+ *                       the launch); 0 for n_chunks >= 2^31.
+ *   anszp_plan_decode   args as for anszp_decode (every array already in place; out and status are not
+ *                       touched); plan_dev [device, caller's, 16-byte aligned] at least
+ *                       anszp_plan_bytes(args->n_chunks) bytes, written on hip_stream.  A launch that
+ *                       the automatic choice does not give to the look-ahead kernel needs no plan:
+ *                       nothing is written then, and anszp_decode_planned does not read plan_dev.
+ *   anszp_decode_planned  the plan must have been written for these very arrays (same pointers'
+ *                       contents, same scalar arguments) on this device.  A plan that was made for
+ *                       another number of chunks or another kernel is refused on the device
+ *                       (ANSZP_ST_BAD_DESC, nothing decoded); one whose descriptors no longer match the
+ *                       arrays decodes what it describes, checked against the caller's buffers like any
+ *                       descriptor: never out of bounds.
+ * Errors: as anszp_decode; E_NULL for a missing plan, E_RANGE for one that is too small or misaligned. */
+uint64_t anszp_plan_bytes(uint64_t n_chunks);
+int anszp_plan_decode(const anszp_decode_args_t* args, void* plan_dev, uint64_t plan_bytes, void* hip_stream);
+int anszp_decode_planned(const anszp_decode_args_t* args, const void* plan_dev, uint64_t plan_bytes, void* hip_stream);
+
 /* Sec. II-B alone: out[i] = scale * (symbols[i] - zero_point) for i < n, the scale chosen as in
  * anszp_layer_t with the layer starting at element 0.  symbols_dev, scales_dev, out_dev: [device];
  * layer: [host].  out_dtype is ANSZP_OUT_F32 or ANSZP_OUT_BF16.  Errors: E_NULL, E_RANGE. */

@@ -62,7 +62,8 @@ class AnszpError(RuntimeError):
 _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
-           "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device"]
+           "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device",
+           "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned"]
 
 
 def lib():
@@ -90,6 +91,10 @@ def lib():
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         L.anszp_decode.argtypes = [C.POINTER(DecodeArgs), C.c_void_p]
         L.anszp_decode_variant.argtypes = [C.POINTER(DecodeArgs), C.c_int, C.c_void_p]
+        L.anszp_plan_bytes.restype = C.c_uint64
+        L.anszp_plan_bytes.argtypes = [C.c_uint64]
+        L.anszp_plan_decode.argtypes = [C.POINTER(DecodeArgs), C.c_void_p, C.c_uint64, C.c_void_p]
+        L.anszp_decode_planned.argtypes = [C.POINTER(DecodeArgs), C.c_void_p, C.c_uint64, C.c_void_p]
         L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
                                        C.c_void_p, C.c_int, C.c_void_p]
         L.anszp_conv_fused.argtypes = [C.POINTER(ConvArgs), C.c_void_p]
@@ -344,6 +349,26 @@ def decode_raw(args: DecodeArgs, device="cuda:0", variant: Optional[int] = None)
         else:
             _check(lib().anszp_decode_variant(C.byref(args), variant, _stream_ptr(torch, device)),
                    "anszp_decode_variant")
+
+
+def plan_bytes(n_chunks: int) -> int:
+    return int(lib().anszp_plan_bytes(n_chunks))
+
+
+def plan_decode(args: DecodeArgs, device="cuda:0"):
+    """anszp_plan_decode into a new device buffer (returned as a torch uint8 tensor)."""
+    torch = _torch()
+    plan = torch.empty(max(16, plan_bytes(args.n_chunks)), dtype=torch.uint8, device=device)
+    with torch.cuda.device(device):
+        _check(lib().anszp_plan_decode(C.byref(args), plan.data_ptr(), plan.numel(), _stream_ptr(torch, device)), "anszp_plan_decode")
+    return plan
+
+
+def decode_planned_raw(args: DecodeArgs, plan, device="cuda:0"):
+    """anszp_decode_planned on torch's current stream of `device`."""
+    torch = _torch()
+    with torch.cuda.device(device):
+        _check(lib().anszp_decode_planned(C.byref(args), plan.data_ptr(), plan.numel(), _stream_ptr(torch, device)), "anszp_decode_planned")
 
 
 LOOKAHEAD_WINDOW_WORDS = 11096     # stream words of one chunk the look-ahead kernel can hold on chip (a chunk that has a workgroup to itself)

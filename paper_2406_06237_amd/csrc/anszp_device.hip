@@ -48,11 +48,11 @@ constexpr uint32_t kSpinLimit = 1u << 22;       // polls before a hand-over betw
 // of up to 2^11 states, shorter windows) leaves room for two workgroups per CU.
 struct LargeLds {
     static constexpr uint32_t kTableLog = ANSZP_MAX_TABLE_LOG, kPayloadWords = 4096u, kRingElems = 16u * 1024u;
-    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 1u;
+    static constexpr uint32_t kLogSlots = 8u, kWorkgroupsPerCu = 1u, kTag = 1u;
 };
 struct SmallLds {
     static constexpr uint32_t kTableLog = 11u, kPayloadWords = 2048u, kRingElems = 8u * 1024u;
-    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 2u;
+    static constexpr uint32_t kLogSlots = 4u, kWorkgroupsPerCu = 2u, kTag = 2u;
 };
 
 struct DecodeParams {
@@ -73,6 +73,7 @@ struct DecodeParams {
     uint32_t n_streams;
     uint32_t n_cus;             // compute units of the device: workgroups n_cus apart tend to share one
     uint32_t n_chunks;
+    const uint32_t* plan;       // work assignment prepared by plan_units for these very arrays, or null
 };
 
 // The chip hands consecutive workgroups to its eight dies (XCDs) in turn, and every die has an L2 of its
@@ -1074,6 +1075,37 @@ __device__ __forceinline__ Unit find_unit(const DecodeParams& p, uint32_t u, uin
 }
 
 // ---------------------------------------------------------------------------------------------
+// A prepared work assignment (anszp_plan_decode): what workgroup b of the look-ahead kernel would find out for
+// itself at the start of every launch (its unit, the unit's chunk descriptors, their layer), written down once
+// for arrays that stay as they are from launch to launch, one record of 128 bytes per workgroup.  The
+// kernel checks a record's descriptors against the caller's buffers like any other, so a plan that no longer
+// fits its arrays cannot make it read or write out of bounds.
+struct PlanRecord {
+    uint32_t tag, n_chunks, first, count;        // tag: kPlanTag + the geometry's tag
+    anszp_chunk_t c0, c1;
+    anszp_layer_t lay;                           // of the unit's chunks (zero when neither is in bounds)
+    uint32_t unused[4];
+};
+static_assert(sizeof(PlanRecord) == 128, "one record per workgroup, 128 bytes");
+constexpr uint32_t kPlanTag = 0x414E5300u;
+
+template <class G>
+__global__ __launch_bounds__(kBlock) void plan_units(DecodeParams p, PlanRecord* plan) {
+    __shared__ uint64_t masks[kPairLevels * (kPairScanRounds * kBlock / kWave) + 16u];
+    anszp_chunk_t c0, c1;
+    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, G::kPayloadWords, masks, c0, c1);
+    if (threadIdx.x != 0) return;
+    PlanRecord r = {};
+    r.tag = kPlanTag + G::kTag; r.n_chunks = p.n_chunks; r.first = unit.first; r.count = unit.count;
+    if (unit.count != 0u) {
+        r.c0 = c0; r.c1 = c1;
+        const bool ok0 = chunk_in_bounds(p, c0), ok1 = unit.count == 2u && chunk_in_bounds(p, c1);
+        if (ok0 || ok1) r.lay = p.layers[ok0 ? c0.layer_id : c1.layer_id];
+    }
+    plan[blockIdx.x] = r;
+}
+
+// ---------------------------------------------------------------------------------------------
 // The look-ahead kernel.  One workgroup = one unit (one or two chunks of a layer), twelve wavefronts:
 // all stage, then eight keep a task each, four per chunk:
 //   decode   lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
@@ -1137,8 +1169,21 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t L = 1u << p.table_log;
 
     anszp_chunk_t c0, c1;        // descriptors (the second repeats the first when the unit is a single chunk)
-    const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, kPayloadWords,
-                                        reinterpret_cast<uint64_t*>(lds + kPipeOff), c0, c1);
+    anszp_layer_t planned_lay;
+    Unit unit;
+    if (p.plan) {
+        // the unit as prepared: one record, read through the scalar cache
+        const PlanRecord& r = reinterpret_cast<const PlanRecord*>(p.plan)[blockIdx.x];
+        if (r.tag != kPlanTag + G::kTag || r.n_chunks != p.n_chunks || r.count > 2u) {       // not a plan for this launch
+            if (tid == 0) report(p.status, ANSZP_ST_BAD_DESC);
+            return;
+        }
+        unit = Unit{r.first, r.count};
+        c0 = r.c0; c1 = r.c1; planned_lay = r.lay;
+    } else {
+        unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, kPayloadWords,
+                                 reinterpret_cast<uint64_t*>(lds + kPipeOff), c0, c1);
+    }
     if (unit.count == 0u) return;
     // What the loads below touch depends on the chunk descriptors alone; whether the layer's scales cover the
     // chunks is looked at once the layer's descriptor has arrived, with everything else already on its way.
@@ -1151,7 +1196,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         return;
     }
     const uint32_t layer_id = ok0 ? c0.layer_id : c1.layer_id;      // both alike when both are in bounds
-    const anszp_layer_t lay = p.layers[layer_id];
+    const anszp_layer_t lay = p.plan ? planned_lay : p.layers[layer_id];
 
     // Issue every global read that depends only on the descriptors before waiting for any of them (the
     // stream headers first: they are used first).
@@ -1848,9 +1893,48 @@ void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, b
     }
 }
 
-int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
+// What a launch would be: checks of the arguments, the kernel's parameters, which kernel.
+struct LaunchChoice { bool stepwise, byte_table, shared, streaming, small, per_channel; };
+
+int choose_launch(const anszp_decode_args_t* a, int mode, DecodeParams& p, LaunchChoice& k);
+
+// plan: null, or device memory written by plan_units for these arrays (used by the look-ahead kernel only);
+// plan_only: write the plan instead of decoding
+int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream, uint32_t* plan = nullptr, uint64_t plan_bytes = 0,
+                bool plan_only = false) {
     if (!a) return ANSZP_E_NULL;
     if (a->n_chunks == 0) return ANSZP_OK;
+    DecodeParams p;
+    LaunchChoice k;
+    const int rc = choose_launch(a, mode, p, k);
+    if (rc != ANSZP_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
+    const bool lookahead = !k.stepwise && !k.byte_table;
+    if (plan || plan_only) {
+        if (!plan) return ANSZP_E_NULL;
+        if ((reinterpret_cast<uintptr_t>(plan) & 15) || plan_bytes < uint64_t(mapped_workgroups(nc)) * sizeof(PlanRecord)) return ANSZP_E_RANGE;
+    }
+    if (plan_only) {
+        // (a launch that does not go to the look-ahead kernel needs no plan: the memory stays as it is, and
+        // anszp_decode_planned does not read it)
+        if (lookahead) {
+            const dim3 grid(mapped_workgroups(nc));
+            if (k.small) hipLaunchKernelGGL(plan_units<SmallLds>, grid, dim3(kBlock), 0, s, p, reinterpret_cast<PlanRecord*>(plan));
+            else hipLaunchKernelGGL(plan_units<LargeLds>, grid, dim3(kBlock), 0, s, p, reinterpret_cast<PlanRecord*>(plan));
+        }
+        return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+    }
+    p.plan = lookahead ? plan : nullptr;
+    switch (a->out_dtype) {
+        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, k.per_channel, k.stepwise, k.shared, k.streaming, k.small, k.byte_table, s); break;
+        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, k.per_channel, k.stepwise, k.shared, k.streaming, k.small, k.byte_table, s); break;
+        default: launch_decode<ANSZP_OUT_BF16>(p, nc, k.per_channel, k.stepwise, k.shared, k.streaming, k.small, k.byte_table, s); break;
+    }
+    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+}
+
+int choose_launch(const anszp_decode_args_t* a, int mode, DecodeParams& p, LaunchChoice& k) {
     if (!a->tables || !a->chunks || !a->stream_hdr || !a->layers || !a->out || !a->status) return ANSZP_E_NULL;
     if (!a->payload && a->payload_words) return ANSZP_E_NULL;
     if (a->table_log < 1 || a->table_log > ANSZP_MAX_TABLE_LOG || a->n_streams < 1 ||
@@ -1859,7 +1943,6 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
         (reinterpret_cast<uintptr_t>(a->tables) & 15) ||
         (reinterpret_cast<uintptr_t>(a->out) & 15) || mode < 0 || mode > 5 || (mode == 5 && a->table_log > 8))
         return ANSZP_E_RANGE;
-    DecodeParams p;
     p.tables = a->tables; p.chunks = a->chunks; p.stream_hdr = a->stream_hdr; p.payload = a->payload;
     p.layers = a->layers; p.scales = a->scales; p.out = a->out; p.status = a->status;
     p.n_stream_hdr = a->n_stream_hdr; p.payload_words = a->payload_words;
@@ -1867,26 +1950,20 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream) {
     p.n_tables = a->n_tables; p.table_log = a->table_log; p.n_streams = a->n_streams;
     p.n_cus = device_cus();
     p.n_chunks = static_cast<uint32_t>(a->n_chunks);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const uint32_t nc = static_cast<uint32_t>(a->n_chunks);
+    p.plan = nullptr;
     // chunks whose compressed words cannot fit the look-ahead kernel's LDS window would all take its
     // fallback: they go to the streaming kernel, whatever their number (measured on 772 to 24,704
     // chunks of 82 KB of words: 5 to 7 times faster than one step-wise wavefront per chunk)
     const uint64_t mean_words = a->payload_words / a->n_chunks;
-    const bool stepwise = mode == 1 || mode == 3 || mode == 4 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
-    const bool byte_table = mode == 5;
-    const bool shared = mode == 3;
-    const bool streaming = mode == 4 || (mode == 0 && stepwise);
-    // small tables and short chunks: the variant that fits three workgroups on a CU
-    const bool small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords &&
-                       kBlockLookups * kLookaheadMaxSymbols * a->n_streams < SmallLds::kRingElems;     // a block must fit its ring
-    const bool per_channel = a->scales != nullptr && a->n_scales != 0;
-    switch (a->out_dtype) {
-        case ANSZP_OUT_U8: launch_decode<ANSZP_OUT_U8>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
-        case ANSZP_OUT_F32: launch_decode<ANSZP_OUT_F32>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
-        default: launch_decode<ANSZP_OUT_BF16>(p, nc, per_channel, stepwise, shared, streaming, small, byte_table, s); break;
-    }
-    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+    k.stepwise = mode == 1 || mode == 3 || mode == 4 || (mode == 0 && mean_words > LargeLds::kPayloadWords);
+    k.byte_table = mode == 5;
+    k.shared = mode == 3;
+    k.streaming = mode == 4 || (mode == 0 && k.stepwise);
+    // small tables and short chunks: the variant that fits two workgroups on a CU
+    k.small = a->table_log <= SmallLds::kTableLog && 2u * mean_words <= SmallLds::kPayloadWords &&
+              kBlockLookups * kLookaheadMaxSymbols * a->n_streams < SmallLds::kRingElems;     // a block must fit its ring
+    k.per_channel = a->scales != nullptr && a->n_scales != 0;
+    return ANSZP_OK;
 }
 
 }  // namespace
@@ -1924,6 +2001,20 @@ int anszp_build_tables_device(const uint32_t* freqs_dev, int n_tables, int table
 }
 
 int anszp_decode(const anszp_decode_args_t* args, void* hip_stream) { return decode_impl(args, 0, hip_stream); }
+
+uint64_t anszp_plan_bytes(uint64_t n_chunks) {
+    if (n_chunks >= (1ull << 31)) return 0;
+    return uint64_t(mapped_workgroups(static_cast<uint32_t>(n_chunks))) * sizeof(PlanRecord);
+}
+
+int anszp_plan_decode(const anszp_decode_args_t* args, void* plan_dev, uint64_t plan_bytes, void* hip_stream) {
+    return decode_impl(args, 0, hip_stream, static_cast<uint32_t*>(plan_dev), plan_bytes, true);
+}
+
+int anszp_decode_planned(const anszp_decode_args_t* args, const void* plan_dev, uint64_t plan_bytes, void* hip_stream) {
+    if (!plan_dev) return ANSZP_E_NULL;
+    return decode_impl(args, 0, hip_stream, static_cast<uint32_t*>(const_cast<void*>(plan_dev)), plan_bytes, false);
+}
 
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream) {
     return decode_impl(args, variant, hip_stream);
