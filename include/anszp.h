@@ -247,6 +247,17 @@ uint64_t anszp_plan_bytes(uint64_t n_chunks);
 int anszp_plan_decode(const anszp_decode_args_t* args, void* plan_dev, uint64_t plan_bytes, void* hip_stream);
 int anszp_decode_planned(const anszp_decode_args_t* args, const void* plan_dev, uint64_t plan_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under stream capture, serving loops, harnesses
+ * that forbid it): anszp_decode_planned with the plan kept in device memory of the library's own, a
+ * fixed array of 512 KiB per device that holds a plan for at most 4096 chunks and stays until the
+ * process ends.  Calls no allocating routine.  replan != 0: the plan is written first (as by
+ * anszp_plan_decode) and the decode follows on the same stream; replan == 0: the array must still hold
+ * the plan an earlier call on this device wrote for these arrays.  Every call on a device shares that
+ * device's array: calls that overlap on one device (other streams, other host threads) race unless all
+ * of them pass replan == 0 for the same arrays.
+ * Errors: as anszp_decode; E_RANGE for more than 4096 chunks; E_HIP if the array's address cannot be found. */
+int anszp_decode_static_plan(const anszp_decode_args_t* args, int replan, void* hip_stream);
+
 /* Sec. II-B alone: out[i] = scale * (symbols[i] - zero_point) for i < n, the scale chosen as in
  * anszp_layer_t with the layer starting at element 0.  symbols_dev, scales_dev, out_dev: [device];
  * layer: [host].  out_dtype is ANSZP_OUT_F32 or ANSZP_OUT_BF16.  Errors: E_NULL, E_RANGE. */

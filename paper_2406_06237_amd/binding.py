@@ -63,7 +63,7 @@ _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
            "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device",
-           "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned"]
+           "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned", "anszp_decode_static_plan"]
 
 
 def lib():
@@ -95,6 +95,7 @@ def lib():
         L.anszp_plan_bytes.argtypes = [C.c_uint64]
         L.anszp_plan_decode.argtypes = [C.POINTER(DecodeArgs), C.c_void_p, C.c_uint64, C.c_void_p]
         L.anszp_decode_planned.argtypes = [C.POINTER(DecodeArgs), C.c_void_p, C.c_uint64, C.c_void_p]
+        L.anszp_decode_static_plan.argtypes = [C.POINTER(DecodeArgs), C.c_int, C.c_void_p]
         L.anszp_dequant_zp.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint64,
                                        C.c_void_p, C.c_int, C.c_void_p]
         L.anszp_conv_fused.argtypes = [C.POINTER(ConvArgs), C.c_void_p]
@@ -369,6 +370,13 @@ def decode_planned_raw(args: DecodeArgs, plan, device="cuda:0"):
     torch = _torch()
     with torch.cuda.device(device):
         _check(lib().anszp_decode_planned(C.byref(args), plan.data_ptr(), plan.numel(), _stream_ptr(torch, device)), "anszp_decode_planned")
+
+
+def decode_static_plan_raw(args: DecodeArgs, replan: bool, device="cuda:0"):
+    """anszp_decode_static_plan on torch's current stream of `device`."""
+    torch = _torch()
+    with torch.cuda.device(device):
+        _check(lib().anszp_decode_static_plan(C.byref(args), 1 if replan else 0, _stream_ptr(torch, device)), "anszp_decode_static_plan")
 
 
 LOOKAHEAD_WINDOW_WORDS = 11096     # stream words of one chunk the look-ahead kernel can hold on chip (a chunk that has a workgroup to itself)

@@ -1966,6 +1966,24 @@ int choose_launch(const anszp_decode_args_t* a, int mode, DecodeParams& p, Launc
     return ANSZP_OK;
 }
 
+// The plan that anszp_decode_static_plan keeps: device memory of the library's own, one array per device.
+constexpr uint32_t kStaticPlanChunks = 4096u;
+static __device__ __align__(256) unsigned char scratch[size_t(kStaticPlanChunks) * sizeof(PlanRecord)];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_of_device[kMaxDevices];
+
+// The address of this device's copy of `scratch` (looked up once per device).
+void* device_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        scratch_of_device[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -2014,6 +2032,18 @@ int anszp_plan_decode(const anszp_decode_args_t* args, void* plan_dev, uint64_t 
 int anszp_decode_planned(const anszp_decode_args_t* args, const void* plan_dev, uint64_t plan_bytes, void* hip_stream) {
     if (!plan_dev) return ANSZP_E_NULL;
     return decode_impl(args, 0, hip_stream, static_cast<uint32_t*>(const_cast<void*>(plan_dev)), plan_bytes, false);
+}
+
+int anszp_decode_static_plan(const anszp_decode_args_t* args, int replan, void* hip_stream) {
+    if (!args) return ANSZP_E_NULL;
+    if (args->n_chunks > kStaticPlanChunks) return ANSZP_E_RANGE;
+    uint32_t* plan = static_cast<uint32_t*>(device_scratch());
+    if (!plan) return ANSZP_E_HIP;
+    if (replan) {
+        const int rc = decode_impl(args, 0, hip_stream, plan, sizeof(scratch), true);
+        if (rc != ANSZP_OK) return rc;
+    }
+    return decode_impl(args, 0, hip_stream, plan, sizeof(scratch), false);
 }
 
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream) {
