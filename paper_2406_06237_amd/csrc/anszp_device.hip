@@ -114,16 +114,19 @@ __device__ __forceinline__ void report(uint32_t* status, uint32_t bits) {
     atomicAdd(&status[1], 1u);
 }
 
-// Exclusive prefix sum over the 64 lanes of a wavefront; *total receives the sum.
+// Exclusive prefix sum over the 64 lanes of a wavefront; *total receives the sum.  Data-parallel-primitive
+// moves: within rows of 16 lanes by 1, 2, 4 and 8 (lanes without a source add zero), then lane 15 of rows 0
+// and 2 to the rows after them, then lane 31 to the upper half.
 __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* total) {
-    uint32_t inc = v;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t up = __shfl_up(inc, d, kWave);
-        if (static_cast<int>(threadIdx.x & (kWave - 1)) >= d) inc += up;
-    }
-    *total = __shfl(inc, kWave - 1, kWave);
-    return inc - v;
+    int x = static_cast<int>(v);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);      // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);      // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);      // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);      // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);     // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);     // row_bcast:31 into rows 2 and 3
+    *total = static_cast<uint32_t>(__builtin_amdgcn_readlane(x, kWave - 1));
+    return static_cast<uint32_t>(x) - v;
 }
 
 // A word in LDS that another wavefront of the workgroup writes or reads: every access is performed,
@@ -1488,7 +1491,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             }
             spins = 0;
             ne = ne_before;                              // (every lane's, whether it took part or not)
-            if ((bit_after >> 22) == (block & 0x3FFu) && ne_before < lane_end) {    // (a lane that never took part keeps the tag it was staged with)
+            const bool took_part = (bit_after >> 22) == (block & 0x3FFu) && ne_before < lane_end;   // (a lane that never took part keeps the tag it was staged with)
+            if (took_part) {
                 // entries 0..7: bits 0..7 symbol | 8..11 T | 12..14 c-1 | 15 entry of state 0; 8: address of the lane's next entry
 #pragma unroll
                 for (uint32_t k = 0; k < kBlockLookups; ++k) {
@@ -1496,34 +1500,35 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                     *reinterpret_cast<lds_uint8_t*>(static_cast<uintptr_t>((last & ring_mask) | ring_at)) = static_cast<uint8_t>(ent[k]);
                     ne = last + N;
                 }
-                if (ne >= lane_end) {                    // the stream's last symbol lies in this block: find its entry
-                    uint32_t consumed = 0;
-#pragma unroll
-                    for (uint32_t k = 0; k < kBlockLookups; ++k) consumed += (ent[k] >> 8) & 15u;
-                    uint32_t pos = ne_before, bits = (bit_after & 0x3FFFFFu) - consumed;     // where the stream stood when the block began
-                    bool found = false;
-#pragma unroll
-                    for (uint32_t k = 0; k < kBlockLookups; ++k) {
-                        const uint32_t after = pos + (((ent[k] >> 12) & 7u) + 1u) * N;
-                        bits += (ent[k] >> 8) & 15u;
-                        if (!found && after >= lane_end) {
-                            found = true;
-                            // it must end with the entry, in state 0, the stream's words read and no more
-                            const bool in_state_0 = k + 1u < kBlockLookups ? (ent[k + 1u] >> 15) != 0u : ent[kBlockLookups] < 16u;
-                            if (after != lane_end || !in_state_0) err |= ANSZP_ST_BAD_STATE;
-                            if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
-                        }
-                        pos = after;
-                    }
-                }
             }
             block += kExpanders;
-            // publish the lanes' positions, then the next block, issued after the ring writes above
+            // publish the lanes' positions, then the next block, issued after the ring writes above (the slot may
+            // be logged over from here on: what follows works on the registers)
             asm volatile("ds_write_b32 %[pa], %[ne]\n"
                          "ds_write_b32 %[nxa], %[nx]\n"
                          :: [pa] "v"(pipe_off + kProgOff + sub * (kWave * 4u) + lane * 4u), [ne] "v"(ne),
                             [nxa] "v"(pipe_off + kCtlOff + 4u * (kNext0 + sub)), [nx] "v"(block)
                          : "memory");
+            if (took_part && ne >= lane_end) {           // the stream's last symbol lies in this block: find its entry
+                uint32_t consumed = 0;
+#pragma unroll
+                for (uint32_t k = 0; k < kBlockLookups; ++k) consumed += (ent[k] >> 8) & 15u;
+                uint32_t pos = ne_before, bits = (bit_after & 0x3FFFFFu) - consumed;     // where the stream stood when the block began
+                bool found = false;
+#pragma unroll
+                for (uint32_t k = 0; k < kBlockLookups; ++k) {
+                    const uint32_t after = pos + (((ent[k] >> 12) & 7u) + 1u) * N;
+                    bits += (ent[k] >> 8) & 15u;
+                    if (!found && after >= lane_end) {
+                        found = true;
+                        // it must end with the entry, in state 0, the stream's words read and no more
+                        const bool in_state_0 = k + 1u < kBlockLookups ? (ent[k + 1u] >> 15) != 0u : ent[kBlockLookups] < 16u;
+                        if (after != lane_end || !in_state_0) err |= ANSZP_ST_BAD_STATE;
+                        if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
+                    }
+                    pos = after;
+                }
+            }
         }
         // the wavefront that expanded the last block knows where every stream stands: at its end
         if (block >= kExpanders && uniform(ctl[kLogged]) == block - kExpanders + 1u && lane < N && ne < lane_end) err |= ANSZP_ST_INTERNAL;
