@@ -894,10 +894,27 @@ struct Flusher {
 #pragma unroll
             for (int i = 0; i < 4; ++i) { sym[i] = (s.x >> (8 * i)) & 0xFFu; sym[4 + i] = (s.y >> (8 * i)) & 0xFFu; }
             if constexpr (kFolded) {
-                uint32_t w[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) w[i] = lut[sym[i]];
-                __builtin_nontemporal_store(words4{w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)},
+                // The table of weights sits at LDS address 0 (the look-ahead kernel checks that): twice a symbol
+                // is its entry's address, one instruction per symbol (an add that selects the byte in both operands).
+                uint32_t a0, a1, a2, a3, a4, a5, a6, a7, w0, w1, w2, w3, w4, w5, w6, w7;
+                asm volatile(
+                    "v_add_u32_sdwa %[a0], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:BYTE_0\n"
+                    "v_add_u32_sdwa %[a1], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:BYTE_1\n"
+                    "v_add_u32_sdwa %[a2], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:BYTE_2\n"
+                    "v_add_u32_sdwa %[a3], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:BYTE_3\n"
+                    "v_add_u32_sdwa %[a4], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:BYTE_0\n"
+                    "v_add_u32_sdwa %[a5], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:BYTE_1\n"
+                    "v_add_u32_sdwa %[a6], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:BYTE_2\n"
+                    "v_add_u32_sdwa %[a7], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:BYTE_3\n"
+                    "ds_read_u16 %[w0], %[a0]\n ds_read_u16 %[w1], %[a1]\n ds_read_u16 %[w2], %[a2]\n ds_read_u16 %[w3], %[a3]\n"
+                    "ds_read_u16 %[w4], %[a4]\n ds_read_u16 %[w5], %[a5]\n ds_read_u16 %[w6], %[a6]\n ds_read_u16 %[w7], %[a7]\n"
+                    "s_waitcnt lgkmcnt(0)\n"
+                    : [a0] "=&v"(a0), [a1] "=&v"(a1), [a2] "=&v"(a2), [a3] "=&v"(a3), [a4] "=&v"(a4), [a5] "=&v"(a5), [a6] "=&v"(a6), [a7] "=&v"(a7),
+                      [w0] "=&v"(w0), [w1] "=&v"(w1), [w2] "=&v"(w2), [w3] "=&v"(w3), [w4] "=&v"(w4), [w5] "=&v"(w5), [w6] "=&v"(w6), [w7] "=&v"(w7)
+                    : [x] "v"(s.x), [y] "v"(s.y)
+                    : "memory");
+                (void)lut;
+                __builtin_nontemporal_store(words4{w0 | (w1 << 16), w2 | (w3 << 16), w4 | (w5 << 16), w6 | (w7 << 16)},
                                             reinterpret_cast<words4*>(static_cast<uint16_t*>(p.out) + g));
             } else {
                 float v[8];
@@ -1087,7 +1104,8 @@ struct PlanRecord {
     uint32_t tag, n_chunks, first, count;        // tag: kPlanTag + the geometry's tag
     anszp_chunk_t c0, c1;
     anszp_layer_t lay;                           // of the unit's chunks (zero when neither is in bounds)
-    uint32_t unused[4];
+    uint32_t dominant;                           // symbol of the layer's last state: the dominant symbol if there is one
+    uint32_t unused[3];
 };
 static_assert(sizeof(PlanRecord) == 128, "one record per workgroup, 128 bytes");
 constexpr uint32_t kPlanTag = 0x414E5300u;
@@ -1103,7 +1121,11 @@ __global__ __launch_bounds__(kBlock) void plan_units(DecodeParams p, PlanRecord*
     if (unit.count != 0u) {
         r.c0 = c0; r.c1 = c1;
         const bool ok0 = chunk_in_bounds(p, c0), ok1 = unit.count == 2u && chunk_in_bounds(p, c1);
-        if (ok0 || ok1) r.lay = p.layers[ok0 ? c0.layer_id : c1.layer_id];
+        if (ok0 || ok1) {
+            const uint32_t layer_id = ok0 ? c0.layer_id : c1.layer_id;
+            r.lay = p.layers[layer_id];
+            r.dominant = p.tables[size_t(layer_id) * table_stride_words(p.table_log) + table_triples_offset(p.table_log) + (1u << p.table_log) - 1u] >> 24;
+        }
     }
     plan[blockIdx.x] = r;
 }
@@ -1132,10 +1154,11 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each), per chunk
     constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
     constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks in flight between decoding and expanding wavefront
-    // LDS: table | ring 0 | ring 1 | symbol -> bf16 | per chunk: hand-over words, positions, log, compressed words
-    constexpr uint32_t kRingOff = kTableBytes;
-    constexpr uint32_t kLutOff = kRingOff + 2u * kRingElems;
-    constexpr uint32_t kSimdOff = kLutOff + 512u;                  // SIMD of each wavefront
+    // LDS: symbol -> bf16 (at address 0: twice a symbol is its entry's address) | table | SIMD of each wavefront |
+    // per chunk: hand-over words, positions, log, compressed words | ring 0 | ring 1 (aligned to the size of both)
+    constexpr uint32_t kLutOff = 0u;
+    constexpr uint32_t kTableOff = kLutOff + 512u;
+    constexpr uint32_t kSimdOff = kTableOff + kTableBytes;
     constexpr uint32_t kPipeOff = kSimdOff + 64u;
     constexpr uint32_t kTailWords = 8u;                             // zero words behind a chunk's last: a window of four words may start at the last
     constexpr uint32_t kWordsBytes = (kPayloadWords + kTailWords) * 4u;
@@ -1145,8 +1168,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kWordsOff = kLogOff + kLogSlots * kLogSlotBytes;   // the compressed words come last: a single chunk's
     constexpr uint32_t kPipeBytes = kWordsOff + kWordsBytes;             // may run on through the second chunk's area
     constexpr uint32_t kSoloWords = (kWordsBytes + kPipeBytes) / 4u - kTailWords;
-    constexpr uint32_t kLdsBytes = kPipeOff + 2u * kPipeBytes;
-    static_assert(kTableBytes % kRingElems == 0u && (kRingElems & (kRingElems - 1u)) == 0u, "rings aligned to their size");
+    constexpr uint32_t kRingOff = (kPipeOff + 2u * kPipeBytes + 2u * kRingElems - 1u) / (2u * kRingElems) * (2u * kRingElems);
+    constexpr uint32_t kLdsBytes = kRingOff + 2u * kRingElems;
+    static_assert((kRingElems & (kRingElems - 1u)) == 0u && kTableOff == 512u, "rings aligned to their size; the table where the hand-written look-ups expect it");
     static_assert(kPipeOff % 16u == 0u && kPipeBytes % 16u == 0u && kCtlOff % 16u == 0u && kWordsOff % 16u == 0u, "LDS layout");
     static_assert(kRingElems % kSlab == 0u, "whole slabs");
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
@@ -1173,6 +1197,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 
     anszp_chunk_t c0, c1;        // descriptors (the second repeats the first when the unit is a single chunk)
     anszp_layer_t planned_lay;
+    uint32_t planned_dominant = 0;
     Unit unit;
     if (p.plan) {
         // the unit as prepared: one record, read through the scalar cache
@@ -1182,7 +1207,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             return;
         }
         unit = Unit{r.first, r.count};
-        c0 = r.c0; c1 = r.c1; planned_lay = r.lay;
+        c0 = r.c0; c1 = r.c1; planned_lay = r.lay; planned_dominant = r.dominant;
     } else {
         unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, kPayloadWords,
                                  reinterpret_cast<uint64_t*>(lds + kPipeOff), c0, c1);
@@ -1240,6 +1265,36 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
         if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
     }
+    // What staging writes without having loaded anything: symbol -> bf16, hand-over words, the log slots' rows of
+    // bit positions, the positions, the rings' background.  With a prepared plan this is done while the loads
+    // are in flight (the plan names the dominant symbol); without one the LDS it touches is still in use by
+    // the search for the unit, and the dominant symbol is on its way with the table.
+    const uint32_t storers = single ? 4u : 3u;           // storing wavefronts per chunk
+    auto init_pipes = [&](uint32_t dominant) {
+        if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
+        if (tid < (single ? 16u : 2u * 16u)) {            // hand-over words (of both chunks)
+            const uint32_t q = tid / 16u, i = tid % 16u;
+            uint32_t v = 0u;
+            if (i >= kNext0 && i < kNext0 + kExpanders) v = i - kNext0;
+            if (i >= kStored0 && i < kStored0 + kMaxStorers) v = i - kStored0 < storers ? (i - kStored0) * kSlab : 0xFFFFFFFFu;
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = v;
+        }
+        for (uint32_t t = tid; t < (single ? 1u : 2u) * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
+            const uint32_t q = t / (kLogSlots * kWave), i = t % (kLogSlots * kWave);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + (kBlockLookups + 1u) * 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
+        }
+        if (tid < (single ? 1u : 2u) * kExpanders * kWave) {   // where every stream is: its first element, or nothing to wait for
+            const uint32_t q = tid / (kExpanders * kWave), l = tid % kWave;
+            const uint32_t n_q = q ? (in1 ? c1.n_symbols : 0u) : (in0 ? c0.n_symbols : 0u);
+            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[tid % (kExpanders * kWave)] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
+        }
+        const uint32_t fill = dominant * 0x01010101u;
+        uint4* rdst = reinterpret_cast<uint4*>(lds + kRingOff);
+#pragma unroll
+        for (uint32_t k = 0; k < (2u * kRingElems / 16u + kBlock - 1u) / kBlock; ++k)
+            if (tid + k * kBlock < 2u * kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(fill, fill, fill, fill);
+    };
+    if (p.plan) init_pipes(planned_dominant);
     // While those loads are in flight: where every stream's words begin, and the SIMD every wavefront
     // runs on (HW_ID bits 4..5).
     uint32_t total_words0, total_words1;
@@ -1253,7 +1308,6 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // geometry) mirrors the choice.
     enum { kDecode = 0, kExpand = 1, kStore = 2, kNoTask = 3 };
     uint32_t task = kNoTask, pipe = 0, sub = 0;          // sub: which of the chunk's expanding or storing wavefronts
-    const uint32_t storers = unit.count == 1u ? 4u : 3u; // storing wavefronts per chunk
     {
         constexpr uint32_t kWaves = kBlock / kWave;
         const uint32_t flip = G::kWorkgroupsPerCu > 1u ? ((blockIdx.x / max(p.n_cus, 1u)) & 1u) * 2u : 0u;
@@ -1295,7 +1349,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     {
         // every thread stores what it loaded, to the clamped index it loaded from (threads past the
         // end repeat the last row)
-        uint4* tdst = reinterpret_cast<uint4*>(lds);
+        uint4* tdst = reinterpret_cast<uint4*>(lds + kTableOff);
         tdst[min(tid, t_last)] = tv0;
         tdst[min(tid + kBlock, t_last)] = tv1;
         tdst[min(tid + 2u * kBlock, t_last)] = tv2;
@@ -1312,31 +1366,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             reinterpret_cast<uint32_t*>(lds + kPipeOff + kWordsOff)[(quads0 << 2) + tid] = tail0;
             if (!single) reinterpret_cast<uint32_t*>(lds + kPipeOff + kPipeBytes + kWordsOff)[(quads1 << 2) + tid] = tail1;
         }
-        if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
-        if (tid < (single ? 16u : 2u * 16u)) {            // hand-over words (of both chunks)
-            const uint32_t q = tid / 16u, i = tid % 16u;
-            uint32_t v = 0u;
-            if (i >= kNext0 && i < kNext0 + kExpanders) v = i - kNext0;
-            if (i >= kStored0 && i < kStored0 + kMaxStorers) v = i - kStored0 < storers ? (i - kStored0) * kSlab : 0xFFFFFFFFu;
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kCtlOff)[i] = v;
-        }
-        for (uint32_t t = tid; t < (single ? 1u : 2u) * kLogSlots * kWave; t += kBlock) {   // the rows of bit positions: no lane has taken part in any block
-            const uint32_t q = t / (kLogSlots * kWave), i = t % (kLogSlots * kWave);
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kLogOff + (i / kWave) * kLogSlotBytes + (kBlockLookups + 1u) * 2u * kWave)[i % kWave] = 0xFFFFFFFFu;
-        }
-        if (tid < (single ? 1u : 2u) * kExpanders * kWave) {   // where every stream is: its first element, or nothing to wait for
-            const uint32_t q = tid / (kExpanders * kWave), l = tid % kWave;
-            const uint32_t n_q = q ? (in1 ? c1.n_symbols : 0u) : (in0 ? c0.n_symbols : 0u);
-            reinterpret_cast<uint32_t*>(lds + kPipeOff + q * kPipeBytes + kProgOff)[tid % (kExpanders * kWave)] = (l < N && l < n_q) ? l : 0xFFFFFFF0u;
-        }
     }
-    const uint32_t bg4 = (top >> 24) * 0x01010101u;      // the rings' background: the dominant symbol
-    {
-        uint4* rdst = reinterpret_cast<uint4*>(lds + kRingOff);
-#pragma unroll
-        for (uint32_t k = 0; k < (2u * kRingElems / 16u + kBlock - 1u) / kBlock; ++k)
-            if (tid + k * kBlock < 2u * kRingElems / 16u) rdst[tid + k * kBlock] = make_uint4(bg4, bg4, bg4, bg4);
-    }
+    if (!p.plan) init_pipes(top >> 24);
+    const uint32_t bg4 = (p.plan ? planned_dominant : top >> 24) * 0x01010101u;      // the rings' background: the dominant symbol
     __syncthreads();
     if (task == kNoTask || (pipe == 1u && !in1) || (pipe == 0u && !in0)) return;
 
@@ -1543,7 +1575,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(lds + words_off);
     // Look-ahead entries are indexed by 2 * state + the next stream bit (peeked, not yet read).
     const uint32_t index0 = 2u * (hdr & (L - 1u)) + (lds_words[min(first_word, c.payload_words)] & 1u);
-    uint2 e = reinterpret_cast<const uint2*>(lds)[index0];
+    uint2 e = reinterpret_cast<const uint2*>(lds + kTableOff)[index0];
     uint32_t abit = first_bit;                           // bit position, counted from the start of LDS
     uint32_t ne = (lane < N && lane < n) ? lane : lane_end;
     uint32_t logged = 0, spins = 0;
@@ -1578,7 +1610,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         "s_waitcnt lgkmcnt(1)\n"                                                       \
         "v_lshrrev_b32 v36, " ELO ", v53\n"                                            \
         "v_lshl_add_u32 v36, v36, 3, " EHI "\n"                                        \
-        "ds_read_b64 " FB ", v36\n"                                                    \
+        "ds_read_b64 " FB ", v36 offset:512\n"                                         \
         "ds_write_b16_d16_hi v42, " ELO " offset:" K "*128\n"                          \
         "v_not_b32 v35, " ELO "\n"                                                     \
         SHIFT                                                                          \
@@ -1641,7 +1673,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "s_waitcnt lgkmcnt(1)\n"                   /* the eighth look-up shifts no window */
             "v_lshrrev_b32 v36, v26, v53\n"
             "v_lshl_add_u32 v36, v36, 3, v27\n"
-            "ds_read_b64 v[24:25], v36\n"
+            "ds_read_b64 v[24:25], v36 offset:512\n"
             "ds_write_b16_d16_hi v42, v26 offset:7*128\n"
             "ds_write_b16 v42, v36 offset:8*128\n"   /* where the next look-up starts: below 16 in state 0 */
             "v_add_u32 v37, v37, v26\n"
