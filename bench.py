@@ -117,7 +117,7 @@ def chain_bound(w, h, steps):
         hh = B.pack_workload(one)
         d = B.to_device(hh, "cuda:0")
         out = B.alloc_out(d)
-        ms = time_launches(B, torch, B.decode_args(d, out), "cuda:0", steps, 10)
+        ms = time_launches(B, torch, B.decode_args(d, out), "cuda:0", steps, 10)      # (n_chunks == 1: nothing to plan)
         assert d.read_status() == (0, 0)
         points.append((int(lookups_per_stream(hh).max()), ms * 1e3))
     (s1, t1), (s0, t0) = points
@@ -157,7 +157,19 @@ def steady_state(w, h, k, steps, elem_bytes):
     from paper_2406_06237_amd import binding as B
     d = B.to_device(replicate(h, k), "cuda:0")
     out = B.alloc_out(d)
-    ms = time_launches(B, torch, B.decode_args(d, out), "cuda:0", steps, 5)
+    a = B.decode_args(d, out)
+    plan = B.plan_decode(a, "cuda:0")
+    stream = torch.cuda.current_stream("cuda:0")
+    for _ in range(5):
+        B.decode_planned_raw(a, plan, "cuda:0")
+    torch.cuda.synchronize("cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        B.decode_planned_raw(a, plan, "cuda:0")
+    e1.record(stream)
+    torch.cuda.synchronize("cuda:0")
+    ms = e0.elapsed_time(e1) / steps
     assert d.read_status() == (0, 0)
     same = bool(torch.equal(out[:h.numel].view(torch.int16), out[(k - 1) * h.numel:k * h.numel].view(torch.int16))) \
         if w.out_dtype == "bf16" else None
@@ -355,6 +367,7 @@ def main():
     ap.add_argument("--blocks", type=int, default=32, help="config 4 only: number of blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true", help="config 3 only: leave out the ResNet-18-shaped set")
+    ap.add_argument("--no-plan", action="store_true", help="time anszp_decode instead of anszp_decode_planned")
     ap.add_argument("--no-extras", action="store_true", help="leave out the chain bound and the steady-state launch")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run a plain device copy of this many MiB five times (reference for HBM byte counters)")
@@ -372,7 +385,7 @@ def main():
         # the ResNet-18-shaped set beside the headline, same measurement (bench.py --config 4 and --config 5 run
         # the large stack and the fused convolution: minutes each, not part of the default run)
         sec = bench_decode(args, 2, headline=False)
-        result["secondary"] = [{k: sec[k] for k in ("config", "value", "unit", "ms_per_step", "roofline", "chain_bound",
+        result["secondary"] = [{k: sec[k] for k in ("config", "value", "unit", "ms_per_step", "roofline", "without_plan", "chain_bound",
                                                     "cpu_baseline", "matches_oracle") if k in sec}]
     print(json.dumps(result))
 
@@ -392,15 +405,25 @@ def bench_decode(args, config, headline):
     out = B.alloc_out(d)
     a = B.decode_args(d, out)
     stream = torch.cuda.current_stream(dev)
+    # The work assignment of the launch is prepared once, like the tables (the arrays of a network do not change
+    # between inferences): anszp_plan_decode before the timed region, anszp_decode_planned inside it.  The launch
+    # without a plan (anszp_decode) is timed beside it.
+    plan = None if args.no_plan else B.plan_decode(a, dev)
+
+    def step():
+        if plan is None:
+            B.decode_raw(a, dev)
+        else:
+            B.decode_planned_raw(a, plan, dev)
 
     for _ in range(args.warmup):
-        B.decode_raw(a, dev)
+        step()
     torch.cuda.synchronize(dev)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(args.steps):
-        B.decode_raw(a, dev)
+        step()
     ev1.record(stream)
     torch.cuda.synchronize(dev)
     wall = time.perf_counter() - t0
@@ -431,6 +454,7 @@ def bench_decode(args, config, headline):
         "config": {"workload": f"config{config}:{w.name}", "symbols": w.numel, "layers": len(w.layers),
                    "chunks": int(len(h.chunks)), "streams_per_chunk": w.n_streams, "chunk_size": w.chunk_size,
                    "table_log": w.table_log, "out_dtype": w.out_dtype,
+                   "entry_point": "anszp_decode" if plan is None else "anszp_decode_planned (plan written once by anszp_plan_decode, before the timed region)",
                    "compressed_bytes": h.compressed_bytes(),
                    "bits_per_symbol": 8.0 * h.compressed_bytes() / w.numel,
                    "source_entropy_bits": w.model_entropy_bits()},
@@ -440,6 +464,9 @@ def bench_decode(args, config, headline):
                      "kernel_ms": kernel_ms, "algorithmic_bytes": algo_bytes,
                      "timer": "events on the launch stream around the K launches / K"},
     }
+    if plan is not None and not args.no_extras:
+        result["without_plan"] = {"entry_point": "anszp_decode", "kernel_ms": time_launches(B, torch, a, dev, args.steps, args.warmup)}
+        result["without_plan"]["hbm_frac"] = algo_bytes / (result["without_plan"]["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS
     if config in (2, 3) and not args.no_extras:
         result["chain_bound"] = chain_bound(w, h, max(20, args.steps // 4))
         if headline:
