@@ -281,7 +281,7 @@ def decode_dequant(container: Container, zero_points, scales, channel_len=None, 
     rc = lib().orc_decode_dequant(
         C.c_uint64(c.n_chunks), _p(c.chunk_layer, C.c_uint32), _p(c.chunk_nsym, C.c_uint32),
         _p(c.chunk_out_off, C.c_uint64), _p(c.chunk_payload_off, C.c_uint64), _p(c.chunk_stream_off, C.c_uint32),
-        _p(c.stream_hdr, C.c_uint32), _p(payload, C.c_uint32), C.c_int(c.R), C.c_uint32(c.N),
+        _p(c.stream_hdr, C.c_uint32), _p(payload, C.c_uint32), C.c_uint64(len(c.payload)), C.c_int(c.R), C.c_uint32(c.N),
         _p(tsym, C.c_uint8), _p(tnb, C.c_uint8), _p(tnx, C.c_uint16),
         _p(z, C.c_uint32), _p(sc, C.c_float), _p(cl, C.c_uint32), _p(soff, C.c_uint64),
         _p(c.layer_out_base, C.c_uint64), _p(all_scales, C.c_float),

@@ -373,7 +373,7 @@ int orc_decode_chunks(uint64_t c_begin, uint64_t c_end,
                       const uint32_t *chunk_layer, const uint32_t *chunk_nsym,
                       const uint64_t *chunk_out_off, const uint64_t *chunk_payload_off,
                       const uint32_t *chunk_stream_off,
-                      const uint32_t *stream_hdr, const uint32_t *payload,
+                      const uint32_t *stream_hdr, const uint32_t *payload, uint64_t payload_words,
                       int R, uint32_t N,
                       const uint8_t *tsym, const uint8_t *tnb, const uint16_t *tnewX,
                       uint8_t *out_sym)
@@ -388,7 +388,11 @@ int orc_decode_chunks(uint64_t c_begin, uint64_t c_end,
             uint32_t hdr = stream_hdr[chunk_stream_off[c] + k];
             uint64_t nw = hdr >> 16;
             uint64_t count = cn > k ? (cn - k + N - 1) / N : 0;
-            int rc = orc_decode_stream(payload + woff, nw, (uint16_t)(hdr & 0xFFFFu), count, R,
+            int rc;
+            if (woff > payload_words || nw > payload_words - woff)
+                rc = ORC_E_CORRUPT;        /* a header that points outside the payload: the stream is not read */
+            else
+                rc = orc_decode_stream(payload + woff, nw, (uint16_t)(hdr & 0xFFFFu), count, R,
                                        tsym + lay * L, tnb + lay * L, tnewX + lay * L,
                                        out_sym, chunk_out_off[c] + k, N, NULL);
             if (rc && !first_err) first_err = rc;
@@ -452,6 +456,7 @@ typedef struct {
     const uint32_t *chunk_layer, *chunk_nsym;
     const uint64_t *chunk_out_off, *chunk_payload_off;
     const uint32_t *chunk_stream_off, *stream_hdr, *payload;
+    uint64_t payload_words;
     int R; uint32_t N;
     const uint8_t *tsym, *tnb; const uint16_t *tnewX;
     const uint32_t *lay_z; const float *lay_scale; const uint32_t *lay_channel_len;
@@ -464,7 +469,7 @@ static void *job_run(void *p)
 {
     job_t *j = (job_t *)p;
     j->rc = orc_decode_chunks(j->c_begin, j->c_end, j->chunk_layer, j->chunk_nsym, j->chunk_out_off,
-                              j->chunk_payload_off, j->chunk_stream_off, j->stream_hdr, j->payload,
+                              j->chunk_payload_off, j->chunk_stream_off, j->stream_hdr, j->payload, j->payload_words,
                               j->R, j->N, j->tsym, j->tnb, j->tnewX, j->out_sym);
     for (uint64_t c = j->c_begin; c < j->c_end; c++) {
         uint32_t lay = j->chunk_layer[c];
@@ -483,7 +488,7 @@ int orc_decode_dequant(uint64_t n_chunks,
                        const uint32_t *chunk_layer, const uint32_t *chunk_nsym,
                        const uint64_t *chunk_out_off, const uint64_t *chunk_payload_off,
                        const uint32_t *chunk_stream_off,
-                       const uint32_t *stream_hdr, const uint32_t *payload,
+                       const uint32_t *stream_hdr, const uint32_t *payload, uint64_t payload_words,
                        int R, uint32_t N,
                        const uint8_t *tsym, const uint8_t *tnb, const uint16_t *tnewX,
                        const uint32_t *lay_z, const float *lay_scale, const uint32_t *lay_channel_len,
@@ -501,7 +506,7 @@ int orc_decode_dequant(uint64_t n_chunks,
         j->c_end = n_chunks * (uint64_t)(t + 1) / (uint64_t)n_threads;
         j->chunk_layer = chunk_layer; j->chunk_nsym = chunk_nsym; j->chunk_out_off = chunk_out_off;
         j->chunk_payload_off = chunk_payload_off; j->chunk_stream_off = chunk_stream_off;
-        j->stream_hdr = stream_hdr; j->payload = payload; j->R = R; j->N = N;
+        j->stream_hdr = stream_hdr; j->payload = payload; j->payload_words = payload_words; j->R = R; j->N = N;
         j->tsym = tsym; j->tnb = tnb; j->tnewX = tnewX;
         j->lay_z = lay_z; j->lay_scale = lay_scale; j->lay_channel_len = lay_channel_len;
         j->lay_scales_off = lay_scales_off; j->lay_out_base = lay_out_base; j->scales = scales;
