@@ -284,6 +284,29 @@ int anszp_pack_layer_device(const uint8_t* symbols_dev, uint64_t n_symbols, cons
                             uint64_t payload_cap_words, uint64_t* payload_words_used_dev,
                             uint32_t* status_dev, void* hip_stream);
 
+/* The same for a whole set of layers in three launches (one workgroup per chunk, so every chunk of every layer is
+ * encoded at once).  symbols_dev [device]: the layers' symbols, layer after layer; jobs_dev [device] n_layers
+ * entries in layer order; freqs_dev [device] n_layers rows of 256 frequencies summing to 2^table_log each;
+ * n_chunks: the sum over the layers of ceil(n_symbols / chunk_size) (anszp_pack_bound gives each term).
+ * Layer l becomes layer_id l; its chunks follow those of layer l-1 in chunks_dev and stream_hdr_dev
+ * (stream_offset = chunk index * n_streams), its elements start at out_offset = first_symbol, the payload
+ * starts at word 0 of payload_dev.  Writes what one anszp_pack_layer call per layer would write (and what the
+ * oracle's encoder writes), word for word.  Status bits as anszp_pack_layer_device, and ANSZP_ST_BAD_DESC
+ * when the jobs do not account for n_chunks chunks (those chunks get empty descriptors).
+ * Errors: E_NULL, E_RANGE (table_log, n_streams, n_chunks >= 2^31 or n_chunks * n_streams >= 2^32), E_HIP. */
+typedef struct {
+    uint64_t first_symbol;    /* index of the layer's first symbol in symbols_dev = out_offset of its first chunk */
+    uint64_t n_symbols;
+    uint32_t chunk_size;      /* >= 1 */
+    uint32_t first_chunk;     /* number of chunks of all layers before this one */
+    uint32_t reserved[2];     /* 0 */
+} anszp_pack_job_t;
+int anszp_pack_layers_device(const uint8_t* symbols_dev, const anszp_pack_job_t* jobs_dev, uint32_t n_layers,
+                             uint64_t n_chunks, const uint32_t* freqs_dev, int table_log, int n_streams,
+                             anszp_chunk_t* chunks_dev, uint32_t* stream_hdr_dev, uint32_t* payload_dev,
+                             uint64_t payload_cap_words, uint64_t* payload_words_used_dev,
+                             uint32_t* status_dev, void* hip_stream);
+
 /* activation layouts of anszp_conv_fused */
 #define ANSZP_ACT_NHWC        0     /* [batch][h][w][channels]                                    */
 #define ANSZP_ACT_C8          1     /* [batch][channels / 8][h][w][8]: blocks of 8 channels, so that

@@ -26,7 +26,9 @@ CHUNK_DTYPE = np.dtype([("layer_id", "<u4"), ("n_symbols", "<u4"), ("out_offset"
                         ("payload_offset", "<u8"), ("payload_words", "<u4"), ("stream_offset", "<u4")])
 LAYER_DTYPE = np.dtype([("scale", "<f4"), ("zero_point", "<u4"), ("bitwidth", "<u4"), ("channel_len", "<u4"),
                         ("scales_offset", "<u8"), ("out_base", "<u8")])
-assert CHUNK_DTYPE.itemsize == 32 and LAYER_DTYPE.itemsize == 32
+JOB_DTYPE = np.dtype([("first_symbol", "<u8"), ("n_symbols", "<u8"), ("chunk_size", "<u4"), ("first_chunk", "<u4"),
+                      ("reserved", "<u4", (2,))])
+assert CHUNK_DTYPE.itemsize == 32 and LAYER_DTYPE.itemsize == 32 and JOB_DTYPE.itemsize == 32
 
 
 class DecodeArgs(C.Structure):
@@ -63,7 +65,8 @@ _lib = None
 EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_build_tables_host",
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
            "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device",
-           "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned", "anszp_decode_static_plan"]
+           "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned", "anszp_decode_static_plan",
+           "anszp_pack_layers_device"]
 
 
 def lib():
@@ -102,6 +105,8 @@ def lib():
         L.anszp_pack_layer_device.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int, C.c_int, C.c_uint32, C.c_uint32,
                                               C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.anszp_pack_layers_device.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -581,4 +586,49 @@ def pack_layer_device(symbols_dev, freqs_dev, table_log: int, n_streams: int, ch
                                              layer_id, out_offset, payload_word_offset, stream_offset, chunks.data_ptr(),
                                              hdr.data_ptr(), payload.data_ptr(), cap, used.data_ptr(), status.data_ptr(),
                                              _stream_ptr(torch, dev)), "anszp_pack_layer_device")
+    return chunks, hdr, payload, used, status
+
+
+def pack_jobs(layer_sizes: Sequence[int], chunk_sizes: Sequence[int]) -> np.ndarray:
+    """The anszp_pack_job_t array of a set of layers stored one after the other."""
+    jobs = np.zeros(len(layer_sizes), dtype=JOB_DTYPE)
+    first = chunk = 0
+    for i, (n, cs) in enumerate(zip(layer_sizes, chunk_sizes)):
+        jobs[i] = (first, n, cs, chunk, (0, 0))
+        first += n
+        chunk += (n + cs - 1) // cs
+    return jobs
+
+
+def pack_layers_device(symbols_dev, layer_sizes: Sequence[int], freqs_dev, table_log: int, n_streams: int, chunk_size,
+                       payload_cap_words: Optional[int] = None, out=None):
+    """anszp_pack_layers_device on torch's current stream: symbols_dev a uint8 tensor holding the layers one after the
+    other, freqs_dev an int32 tensor [n_layers, 256], both on the GPU; chunk_size: one for all layers or one per layer.
+    Returns (chunks, stream_hdr, payload, used, status) as device tensors (out: the same five, to be reused)."""
+    torch = _torch()
+    dev = symbols_dev.device
+    sizes = [int(n) for n in layer_sizes]
+    css = [int(chunk_size)] * len(sizes) if np.isscalar(chunk_size) else [int(c) for c in chunk_size]
+    jobs = pack_jobs(sizes, css)
+    n_chunks = int(sum((n + c - 1) // c for n, c in zip(sizes, css)))
+    bound = 0
+    for n, c in zip(sizes, css):
+        nc, b = C.c_uint64(), C.c_uint64()
+        _check(lib().anszp_pack_bound(n, table_log, n_streams, c, C.byref(nc), C.byref(b)), "anszp_pack_bound")
+        bound += b.value
+    cap = bound if payload_cap_words is None else payload_cap_words
+    jobs_dev = torch.from_numpy(jobs.view(np.uint8).copy()).to(dev)
+    if out is None:
+        chunks = torch.zeros(max(n_chunks, 1) * CHUNK_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        hdr = torch.zeros(max(n_chunks * n_streams, 4), dtype=torch.int32, device=dev)
+        payload = torch.full((max(cap, 4),), -1, dtype=torch.int32, device=dev)
+        used = torch.zeros(1, dtype=torch.int64, device=dev)
+        status = torch.zeros(2, dtype=torch.int32, device=dev)
+    else:
+        chunks, hdr, payload, used, status = out
+    with torch.cuda.device(dev):
+        _check(lib().anszp_pack_layers_device(symbols_dev.data_ptr(), jobs_dev.data_ptr(), len(sizes), n_chunks, freqs_dev.data_ptr(),
+                                              table_log, n_streams, chunks.data_ptr(), hdr.data_ptr(), payload.data_ptr(), cap,
+                                              used.data_ptr(), status.data_ptr(), _stream_ptr(torch, dev)), "anszp_pack_layers_device")
+        torch.cuda.current_stream(dev).synchronize()      # (jobs_dev must outlive the launches)
     return chunks, hdr, payload, used, status

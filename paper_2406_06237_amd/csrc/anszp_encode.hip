@@ -245,7 +245,133 @@ __global__ __launch_bounds__(kThreads) void encode_write(EncParams p) {
     }
 }
 
+// ---- a whole set of layers in three launches.  One workgroup per chunk: all of it builds the chunk's layer's
+// tables, its first wavefront walks the chunk's streams.
+struct BatchParams {
+    EncParams p;                       // what all layers share (symbols: the set's first symbol; freqs: the first row)
+    const anszp_pack_job_t* jobs;
+    uint32_t n_layers;
+};
+
+// The layer of chunk c (jobs are in chunk order: the last one whose first_chunk is not beyond c), as EncParams
+// of that layer alone; local: the chunk's number within its layer.  False when c belongs to no layer.
+__device__ bool layer_of_chunk(const BatchParams& b, uint64_t c, EncParams& q, uint64_t& local) {
+    uint32_t lo = 0, hi = b.n_layers;
+    if (hi == 0 || b.jobs[0].first_chunk > c) return false;
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (b.jobs[mid].first_chunk <= c) lo = mid; else hi = mid;
+    }
+    const anszp_pack_job_t j = b.jobs[lo];
+    local = c - j.first_chunk;
+    if (j.chunk_size == 0 || local >= (j.n_symbols + j.chunk_size - 1) / j.chunk_size) return false;
+    q = b.p;
+    q.symbols = b.p.symbols + j.first_symbol;
+    q.freqs = b.p.freqs + size_t(lo) * ANSZP_ALPHABET;
+    q.n_symbols = j.n_symbols;
+    q.chunk_size = j.chunk_size;
+    q.layer_id = lo;
+    q.out_offset = j.first_symbol;
+    return true;
+}
+
+__global__ __launch_bounds__(kThreads) void encode_sizes_batch(BatchParams b) {
+    __shared__ EncTables t;
+    const uint64_t c = blockIdx.x;
+    EncParams q;
+    uint64_t local;
+    const bool mine = layer_of_chunk(b, c, q, local);           // (alike for every thread)
+    if (!mine) {
+        if (threadIdx.x == 0) {
+            report(b.p.status, ANSZP_ST_BAD_DESC);               // the jobs do not cover the chunks the caller counted
+            anszp_chunk_t d = {};
+            b.p.chunks[c] = d;
+        }
+        if (threadIdx.x < b.p.n_streams) b.p.stream_hdr[c * b.p.n_streams + threadIdx.x] = 0u;
+        return;
+    }
+    const bool tables_ok = build_tables(q.freqs, q.table_log, t);
+    const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (wave != 0) return;
+    const uint32_t N = q.n_streams, L = 1u << q.table_log;
+    const uint64_t begin = local * q.chunk_size;
+    const uint64_t rest = q.n_symbols - begin;
+    const uint32_t cn = rest < q.chunk_size ? static_cast<uint32_t>(rest) : q.chunk_size;
+    uint32_t x = L, nw = 0;
+    bool bad = false, too_long = false;
+    if (tables_ok) {
+        const uint32_t bits = walk_stream<false>(q, t, begin, cn, lane, nullptr, 0u, 0u, x, bad);
+        nw = (bits + 31u) >> 5;
+        too_long = nw > 0xFFFFu;
+    } else if (lane == 0 && local == 0) {
+        report(q.status, ANSZP_ST_BAD_FREQ);
+    }
+    if (lane < N) q.stream_hdr[c * N + lane] = (x - L) | (min(nw, 0xFFFFu) << 16);
+    const uint32_t chunk_words = wave_sum(lane < N ? min(nw, 0xFFFFu) : 0u);
+    if (__ballot(bad) && lane == 0) report(q.status, ANSZP_ST_BAD_SYMBOL);
+    if (__ballot(too_long) && lane == 0) report(q.status, ANSZP_ST_NO_SPACE);
+    if (lane == 0) {
+        anszp_chunk_t d;
+        d.layer_id = q.layer_id;
+        d.n_symbols = tables_ok ? cn : 0u;
+        d.out_offset = q.out_offset + begin;
+        d.payload_offset = 0;                                   // by the scan
+        d.payload_words = chunk_words;
+        d.stream_offset = static_cast<uint32_t>(c) * N;
+        q.chunks[c] = d;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void encode_write_batch(BatchParams b) {
+    __shared__ EncTables t;
+    const uint64_t c = blockIdx.x;
+    EncParams q;
+    uint64_t local;
+    if (!layer_of_chunk(b, c, q, local)) return;                 // reported by the first pass
+    if (!build_tables(q.freqs, q.table_log, t)) return;
+    const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (wave != 0) return;
+    const uint32_t N = q.n_streams, L = 1u << q.table_log;
+    const anszp_chunk_t d = q.chunks[c];
+    const uint64_t at = d.payload_offset;
+    const uint64_t padded = (uint64_t(d.payload_words) + 3ull) & ~3ull;
+    if (at > q.payload_cap_words || padded > q.payload_cap_words - at) return;     // no room: reported by the scan
+    const uint64_t begin = local * q.chunk_size;
+    const uint32_t nw = lane < N ? q.stream_hdr[c * N + lane] >> 16 : 0u;
+    uint32_t* words = q.payload + at + wave_exclusive_sum(nw, lane);
+    uint32_t x = L;
+    bool bad = false;
+    const uint32_t bits = walk_stream<false>(q, t, begin, d.n_symbols, lane, nullptr, 0u, 0u, x, bad);
+    if (((bits + 31u) >> 5) == nw)                               // (a stream too long for its header is not written)
+        walk_stream<true>(q, t, begin, d.n_symbols, lane, words, nw, bits, x, bad);
+    if (lane < padded - d.payload_words) q.payload[at + d.payload_words + lane] = 0u;   // up to three pad words
+}
+
 }  // namespace
+
+extern "C" int anszp_pack_layers_device(const uint8_t* symbols_dev, const anszp_pack_job_t* jobs_dev, uint32_t n_layers,
+                                        uint64_t n_chunks, const uint32_t* freqs_dev, int table_log, int n_streams,
+                                        anszp_chunk_t* chunks_dev, uint32_t* stream_hdr_dev, uint32_t* payload_dev,
+                                        uint64_t payload_cap_words, uint64_t* payload_words_used_dev,
+                                        uint32_t* status_dev, void* stream) {
+    if (!payload_words_used_dev || !status_dev) return ANSZP_E_NULL;
+    if (n_chunks && (!symbols_dev || !jobs_dev || !freqs_dev || !chunks_dev || !stream_hdr_dev)) return ANSZP_E_NULL;
+    if (!payload_dev && payload_cap_words) return ANSZP_E_NULL;
+    if (table_log < 1 || table_log > ANSZP_MAX_TABLE_LOG || n_streams < 1 || n_streams > ANSZP_MAX_STREAMS ||
+        n_chunks >= (1ull << 31) || uint64_t(n_chunks) * uint64_t(n_streams) >= (1ull << 32) || (n_chunks && n_layers == 0))
+        return ANSZP_E_RANGE;
+    BatchParams b{};
+    b.p.symbols = symbols_dev; b.p.freqs = freqs_dev; b.p.chunks = chunks_dev; b.p.stream_hdr = stream_hdr_dev;
+    b.p.payload = payload_dev; b.p.used = reinterpret_cast<unsigned long long*>(payload_words_used_dev); b.p.status = status_dev;
+    b.p.n_chunks = n_chunks; b.p.payload_word_offset = 0; b.p.payload_cap_words = payload_cap_words;
+    b.p.table_log = uint32_t(table_log); b.p.n_streams = uint32_t(n_streams);
+    b.jobs = jobs_dev; b.n_layers = n_layers;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_chunks) hipLaunchKernelGGL(encode_sizes_batch, dim3(uint32_t(n_chunks)), dim3(kThreads), 0, s, b);
+    hipLaunchKernelGGL(encode_scan, dim3(1), dim3(kThreads), 0, s, b.p);
+    if (n_chunks) hipLaunchKernelGGL(encode_write_batch, dim3(uint32_t(n_chunks)), dim3(kThreads), 0, s, b);
+    return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
+}
 
 extern "C" int anszp_pack_layer_device(const uint8_t* symbols_dev, uint64_t n_symbols, const uint32_t* freqs_dev,
                                        int table_log, int n_streams, uint32_t chunk_size, uint32_t layer_id,

@@ -97,3 +97,75 @@ def test_errors_are_reported(orc):
     c = orc.encode_layers([sym], 10, 8, 64)
     chunks, hdr, payload, used, status = _pack(sym, c.freqs[0], 10, 8, 64, payload_cap_words=8)
     assert status[0] & B.ST_NO_SPACE and used == len(c.payload) and np.all(payload[8:] == 0xFFFFFFFF)
+
+
+# ---- a whole set in three launches (anszp_pack_layers_device)
+def _pack_set(w, orc_container):
+    syms = w.symbols()
+    s = torch.from_numpy(np.concatenate(syms)).to("cuda:0")
+    f = torch.from_numpy(np.ascontiguousarray(orc_container.freqs, dtype=np.uint32).view(np.int32)).to("cuda:0")
+    sizes = getattr(w, "chunk_sizes", None) or w.chunk_size
+    chunks, hdr, payload, used, status = B.pack_layers_device(s, [len(x) for x in syms], f, w.table_log, w.n_streams, sizes)
+    torch.cuda.synchronize()
+    st = status.cpu().numpy().view(np.uint32)
+    return (chunks.cpu().numpy().view(B.CHUNK_DTYPE), hdr.cpu().numpy().view(np.uint32), payload.cpu().numpy().view(np.uint32),
+            int(used.item()), (int(st[0]), int(st[1])))
+
+
+@pytest.mark.parametrize("name", ["config2", "config3", "channel_grouped", "odd_bins", "mixed"])
+def test_whole_sets_in_one_call_equal_the_oracles_container(orc, name):
+    if name == "mixed":                                            # layers of 1 to 70,001 symbols, 48 streams
+        layers = [W.tiny(seed=s, n=n, bitwidth=b, n_streams=48, chunk_size=3000, table_log=10, p0=0.7).layers[0]
+                  for s, (n, b) in enumerate([(1, 2), (70001, 4), (2999, 1), (3000, 8), (3001, 3), (47, 5)])]
+        w = W.Workload("mixed", layers, 10, 48, 3000, "bf16")
+    else:
+        w = {"config2": W.config2, "config3": W.config3, "channel_grouped": W.channel_grouped, "odd_bins": W.resnet50_odd_bins}[name]()
+    from helpers import oracle_encode
+    c = oracle_encode(orc, w)
+    chunks, hdr, payload, used, status = _pack_set(w, c)
+    assert status == (0, 0)
+    assert used == len(c.payload)
+    nc, N = c.n_chunks, w.n_streams
+    for field, want in (("layer_id", c.chunk_layer), ("n_symbols", c.chunk_nsym), ("out_offset", c.chunk_out_off),
+                        ("payload_offset", c.chunk_payload_off), ("payload_words", c.chunk_payload_words),
+                        ("stream_offset", c.chunk_stream_off)):
+        assert np.array_equal(chunks[field][:nc], want), field
+    assert np.array_equal(hdr[:nc * N], c.stream_hdr)
+    assert np.array_equal(payload[:used], c.payload)
+    assert np.all(payload[used:] == 0xFFFFFFFF)
+
+
+def test_whole_set_error_bits_and_rate(orc):
+    w = W.config3()
+    syms = w.symbols()
+    from helpers import oracle_encode
+    c = oracle_encode(orc, w)
+    s = torch.from_numpy(np.concatenate(syms)).to("cuda:0")
+    f = torch.from_numpy(np.ascontiguousarray(c.freqs, dtype=np.uint32).view(np.int32)).to("cuda:0")
+    sizes = [len(x) for x in syms]
+    out = B.pack_layers_device(s, sizes, f, w.table_log, w.n_streams, w.chunk_size)
+    # the rate of the whole set, outputs reused (printed with -s; the host packer does 0.3 Gsymbols/s on one thread)
+    import time
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        B.pack_layers_device(s, sizes, f, w.table_log, w.n_streams, w.chunk_size, out=out)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / 5
+    print(f"anszp_pack_layers_device: {w.numel} symbols in {dt * 1e3:.2f} ms = {w.numel / dt / 1e9:.2f} Gsymbols/s")
+    assert np.array_equal(out[2].cpu().numpy().view(np.uint32)[:len(c.payload)], c.payload)
+    assert w.numel / dt / 1e9 > 3.0                                  # ten host threads' worth
+    # a frequency row that does not sum to L, a symbol without a frequency, a payload buffer that is too small
+    bad = f.clone()
+    bad[3, 0] += 1
+    st = B.pack_layers_device(s, sizes, bad, w.table_log, w.n_streams, w.chunk_size)[4].cpu().numpy().view(np.uint32)
+    assert st[0] & B.ST_BAD_FREQ
+    s2 = s.clone()
+    unused = int(np.nonzero(c.freqs[0] == 0)[0][0])
+    s2[5] = unused
+    st = B.pack_layers_device(s2, sizes, f, w.table_log, w.n_streams, w.chunk_size)[4].cpu().numpy().view(np.uint32)
+    assert st[0] & B.ST_BAD_SYMBOL
+    small = B.pack_layers_device(s, sizes, f, w.table_log, w.n_streams, w.chunk_size, payload_cap_words=len(c.payload) // 2)
+    st = small[4].cpu().numpy().view(np.uint32)
+    assert st[0] & B.ST_NO_SPACE and int(small[3].item()) == len(c.payload)
+    assert np.all(small[2].cpu().numpy().view(np.uint32)[len(c.payload) // 2:] == 0xFFFFFFFF)
