@@ -394,6 +394,14 @@ __device__ __forceinline__ float scaled_high_half(uint32_t entry, float scale) {
     asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(w) : "v"(entry & 0xFFF80000u), "v"(scale), "v"(-0.0f));
     return w;
 }
+// The same for an entry whose bits 5..18 are already clear (only the high half is read).
+__device__ __forceinline__ float scaled_clean_high_half(uint32_t cleared, float scale) {
+    float w;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(w) : "v"(cleared), "v"(scale), "v"(-0.0f));
+    return w;
+}
+typedef float floats2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16s2 __attribute__((ext_vector_type(2)));
 
 // Byte offset, from the first of the workgroup's entries, of the entry of state newX + bits (Sec.
 // II-A), newX taken from `entry`.  Written out so that the field extraction runs beside the
@@ -686,7 +694,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         constexpr int K = static_cast<int>(decltype(count_tag)::value);
         static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of K steps");
         w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
-        uint32_t sum = 0;                                 // 32 - nb_bits over the K steps
+        uint32_t sum = 0;                                 // 32 - nb_bits over the K steps, in its low bits
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const uint32_t e = entry_at(X);
@@ -695,10 +703,14 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             if (k <= K - 2) w0 = __builtin_amdgcn_alignbit(w0, w1, e);
             if (k <= K - 4) w1 = __builtin_amdgcn_alignbit(w1, w2, e);
             if (k <= K - 7) w2 = __builtin_amdgcn_alignbit(w2, 0u, e);
-            sum += e & 31u;
-            emit(k, e);
+            // one mask serves both uses of the entry that remain: with the index of the next entry cleared, the
+            // upper half is the centred symbol as fp16 and the lower bits add up to the bits not read (8 * 31
+            // fits below the cleared field, whatever the upper halves add up to)
+            const uint32_t cleared = e & 0xFFF8001Fu;
+            sum += cleared;
+            emit(k, cleared, k == K - 1);
         }
-        abit += 32u * K - sum;
+        abit += 32u * K - (sum & 0x7FFFFu);
     };
     // a lane asks for sixteen more words when the ring has room for them (they replace words it has passed)
     auto wants_words = [&]() { return fetched - (abit >> 5) <= kStreamRingWords - kStreamFetchWords; };
@@ -747,11 +759,24 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             bool stuck = false;
             // (stores marked non-temporal: the weights are not read again here, and the lines of stream words,
             // which are fetched in two halves some microseconds apart, should outlive them in the L2)
-            auto emit = [&](int k, uint32_t e) {
+            float held = 0.0f;                                             // the weight of an even step, until its odd neighbour's is there
+            auto emit = [&](int k, uint32_t e, bool last) {
                 char* const q = chunk_out + at + static_cast<uint32_t>(k) * (kWave * kElemBytes);
                 if constexpr (OUT == ANSZP_OUT_U8) __builtin_nontemporal_store(static_cast<uint8_t>(e >> 19), reinterpret_cast<uint8_t*>(q));
-                else if constexpr (OUT == ANSZP_OUT_F32) __builtin_nontemporal_store(scaled_high_half(e, scale), reinterpret_cast<float*>(q));
-                else __builtin_nontemporal_store(static_cast<__bf16>(scaled_high_half(e, scale)), reinterpret_cast<__bf16*>(q));
+                else if constexpr (OUT == ANSZP_OUT_F32) __builtin_nontemporal_store(scaled_clean_high_half(e, scale), reinterpret_cast<float*>(q));
+                else {
+                    // bf16: two steps' weights are rounded by one instruction and stored from the two halves of its result
+                    const float w = scaled_clean_high_half(e, scale);
+                    if ((k & 1) == 0 && !last) {
+                        held = w;
+                    } else if (k & 1) {
+                        const bf16s2 both = __builtin_convertvector(floats2{held, w}, bf16s2);
+                        __builtin_nontemporal_store(both.x, reinterpret_cast<__bf16*>(q - kWave * kElemBytes));
+                        __builtin_nontemporal_store(both.y, reinterpret_cast<__bf16*>(q));
+                    } else {
+                        __builtin_nontemporal_store(static_cast<__bf16>(w), reinterpret_cast<__bf16*>(q));
+                    }
+                }
             };
             // K steps from the ring as the loading wavefront fills it: the window's four words must be there
             auto block_fed = [&](auto count_tag) {
@@ -814,7 +839,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             uint32_t in_channel = per_channel ? static_cast<uint32_t>(elem0 % lay.channel_len) : 0;
             float scale = per_channel ? scale_of(channel) : lay.scale;
             uint64_t out_at = c.out_offset + lane;
-            auto emit_one = [&](int, uint32_t e) {
+            auto emit_one = [&](int, uint32_t e, bool) {
                 if constexpr (OUT == ANSZP_OUT_U8) static_cast<uint8_t*>(p.out)[out_at] = static_cast<uint8_t>(e >> 19);
                 else if constexpr (OUT == ANSZP_OUT_F32) static_cast<float*>(p.out)[out_at] = scaled_high_half(e, scale);
                 else static_cast<__bf16*>(p.out)[out_at] = static_cast<__bf16>(scaled_high_half(e, scale));
@@ -847,7 +872,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                     w2 = __builtin_amdgcn_alignbit(w3, w2, nb);
                     w3 >>= (nb & 31u);
                     sum += e & 31u;
-                    emit_one(k, e);
+                    emit_one(k, e, k == K - 1);
                 }
                 abit += 31u * K - sum;
                 if (fetching) {
