@@ -1626,7 +1626,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // longer shifted goes stale; what it feeds into its lower neighbour lies beyond that reach).  A block
     // ends by logging where each lane's next look-up starts and the lane's bit position tagged with the
     // block's number (a lane that sat the block out keeps an older tag), publishing the new count of
-    // blocks, reloading every lane's words and recomputing who may join the next block from the words
+    // blocks, reloading the words of the lanes that took part and recomputing who may join the next block from the words
     // the other wavefronts publish (read at the start of the block, so their latency is hidden).
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
@@ -1707,13 +1707,11 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "v_add_u32 v52, v52, v46\n"
             "v_lshl_or_b32 v46, s44, 22, v52\n"       /* bit position after the block, tagged with the block's number */
             "ds_write_b32 v47, v46 offset:%[bitrow]\n"
-            "s_mov_b64 exec, s[40:41]\n"               /* every lane reloads its words */
-            "v_lshrrev_b32 v38, 3, v52\n"
-            "v_and_b32 v38, 0x1ffffffc, v38\n"
+            "v_lshrrev_b32 v38, 3, v52\n"              /* the block's lanes reload their words (a lane that sat the */
+            "v_and_b32 v38, 0x1ffffffc, v38\n"         /* block out has not moved: its words are still in place)    */
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "s_mov_b64 exec, s[42:43]\n"               /* the block's lanes again */
             "v_bfe_u32 v35, v37, 9, 7\n"
             "v_add_u32 v35, 8, v35\n"                  /* symbols the block stands for */
             "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
