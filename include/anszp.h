@@ -224,6 +224,13 @@ int anszp_decode(const anszp_decode_args_t* args, void* hip_stream);
  * Errors: as anszp_decode, E_RANGE for an unknown variant or variant 5 with table_log > 8. */
 int anszp_decode_variant(const anszp_decode_args_t* args, int variant, void* hip_stream);
 
+/* For tests of the library's failure handling only.  Every wait of one wavefront for another inside the decode
+ * kernels is bounded by a number of polls, after which the chunk is abandoned with ANSZP_ST_INTERNAL and its
+ * workgroup drains.  polls >= 1: later launches give up after polls - 1 polls (1: at the first wait that is not
+ * satisfied at once, which every launch of the look-ahead and streaming kernels has); 0: back to the default
+ * (2^22).  Process-wide, not synchronised with launches in flight. */
+void anszp_test_set_spin_limit(uint32_t polls);
+
 /* Sec. III-A: the weights of a network are decoded again at every inference, from arrays that do not
  * change.  What every launch of anszp_decode first works out on the device (which chunks of a layer
  * share a workgroup and its on-chip copy of the layer's table, in which order the chip's dies take

@@ -66,7 +66,7 @@ EXPORTS = ["anszp_version", "anszp_strerror", "anszp_normalize_freqs", "anszp_bu
            "anszp_build_tables", "anszp_build_tables_device", "anszp_pack_bound", "anszp_pack_layer", "anszp_decode", "anszp_decode_variant",
            "anszp_dequant_zp", "anszp_conv_fused", "anszp_pack_layer_device",
            "anszp_plan_bytes", "anszp_plan_decode", "anszp_decode_planned", "anszp_decode_static_plan",
-           "anszp_pack_layers_device"]
+           "anszp_pack_layers_device", "anszp_test_set_spin_limit"]
 
 
 def lib():
@@ -107,6 +107,8 @@ def lib():
                                               C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.anszp_pack_layers_device.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_int, C.c_int,
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.anszp_test_set_spin_limit.argtypes = [C.c_uint32]
+        L.anszp_test_set_spin_limit.restype = None
         _lib = L
     return _lib
 

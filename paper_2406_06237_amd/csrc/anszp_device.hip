@@ -74,6 +74,7 @@ struct DecodeParams {
     uint32_t n_cus;             // compute units of the device: workgroups n_cus apart tend to share one
     uint32_t n_chunks;
     const uint32_t* plan;       // work assignment prepared by plan_units for these very arrays, or null
+    uint32_t spin_limit;        // polls before a hand-over between wavefronts is declared stuck (kSpinLimit unless a test says otherwise)
 };
 
 // The chip hands consecutive workgroups to its eight dies (XCDs) in turn, and every die has an L2 of its
@@ -608,7 +609,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
             if (!any_alive) break;
             if (moved) { idle = 0; continue; }
             if (uniform(*gave_up)) break;
-            if (++idle > kSpinLimit) {
+            if (++idle > p.spin_limit) {
                 if (lane == 0) { *gave_up = 1u; report(p.status, ANSZP_ST_INTERNAL); }
                 break;
             }
@@ -786,7 +787,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                     asm volatile("" ::: "memory");
                     window(w0, w1, w2, w3);
                     if (__ballot(have - (abit >> 5) < 4u) == 0ull) break;
-                    if (uniform(*gave_up) || ++spins > kSpinLimit) { stuck = true; return; }
+                    if (uniform(*gave_up) || ++spins > p.spin_limit) { stuck = true; return; }
                     __builtin_amdgcn_s_sleep(1);
                 }
                 steps_fast(count_tag, w0, w1, w2, emit);
@@ -1472,7 +1473,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             if (last_pass) break;
             if (mine == before) {
                 if (uniform(ctl[kGaveUp])) return;
-                if (++spins > kSpinLimit) {
+                if (++spins > p.spin_limit) {
                     if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
                     return;
                 }
@@ -1539,7 +1540,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                     continue;
                 }
                 if (uniform(ctl[kGaveUp])) return;
-                if (++spins > kSpinLimit) {
+                if (++spins > p.spin_limit) {
                     if (lane == 0) { ctl[kGaveUp] = 1u; report(p.status, ANSZP_ST_INTERNAL); }
                     return;
                 }
@@ -1660,7 +1661,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         const uint32_t expanded = min(uniform(seen.y), uniform(seen.z));      // every block below this one has been expanded
         const uint32_t limit = min(lane_end, stored + room);
         if (__ballot(ne < limit) == 0 || logged - expanded >= kLogSlots) {        // ring or log full: wait
-            if (uniform(ctl[kGaveUp]) || ++spins > kSpinLimit) gave_up = true;
+            if (uniform(ctl[kGaveUp]) || ++spins > p.spin_limit) gave_up = true;
             __builtin_amdgcn_s_sleep(1);
             continue;
         }
@@ -1953,6 +1954,10 @@ void launch_decode(const DecodeParams& p, uint32_t n_chunks, bool per_channel, b
     }
 }
 
+// The bound of every wait between wavefronts, in polls.  Tests lower it (anszp_test_set_spin_limit) to see that a
+// hand-over that does not complete ends in ANSZP_ST_INTERNAL and a drained launch, not in a hang.
+std::atomic<uint32_t> spin_limit_for_tests{kSpinLimit};
+
 // What a launch would be: checks of the arguments, the kernel's parameters, which kernel.
 struct LaunchChoice { bool stepwise, byte_table, shared, streaming, small, per_channel; };
 
@@ -2011,6 +2016,7 @@ int choose_launch(const anszp_decode_args_t* a, int mode, DecodeParams& p, Launc
     p.n_cus = device_cus();
     p.n_chunks = static_cast<uint32_t>(a->n_chunks);
     p.plan = nullptr;
+    p.spin_limit = spin_limit_for_tests.load(std::memory_order_relaxed);
     // chunks whose compressed words cannot fit the look-ahead kernel's LDS window would all take its
     // fallback: they go to the streaming kernel, whatever their number (measured on 772 to 24,704
     // chunks of 82 KB of words: 5 to 7 times faster than one step-wise wavefront per chunk)
@@ -2079,6 +2085,8 @@ int anszp_build_tables_device(const uint32_t* freqs_dev, int n_tables, int table
 }
 
 int anszp_decode(const anszp_decode_args_t* args, void* hip_stream) { return decode_impl(args, 0, hip_stream); }
+
+void anszp_test_set_spin_limit(uint32_t polls) { spin_limit_for_tests.store(polls ? polls - 1u : kSpinLimit, std::memory_order_relaxed); }
 
 uint64_t anszp_plan_bytes(uint64_t n_chunks) {
     if (n_chunks >= (1ull << 31)) return 0;
