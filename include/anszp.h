@@ -236,8 +236,9 @@ void anszp_test_set_spin_limit(uint32_t polls);
  * share a workgroup and its on-chip copy of the layer's table, in which order the chip's dies take
  * them) can therefore be prepared once: anszp_plan_decode writes it to plan_dev, anszp_decode_planned
  * decodes with it and gives the same output and status words as anszp_decode.
- *   anszp_plan_bytes    bytes of device memory a plan for n_chunks chunks takes (128 per workgroup of
- *                       the launch); 0 for n_chunks >= 2^31.
+ *   anszp_plan_bytes    bytes of device memory a plan for n_chunks chunks takes (a record of 128 bytes per
+ *                       workgroup of the launch, and as much again to sort them in: the workgroups take the
+ *                       units with the longest chains first); 0 for n_chunks >= 2^31.
  *   anszp_plan_decode   args as for anszp_decode (every array already in place; out and status are not
  *                       touched); plan_dev [device, caller's, 16-byte aligned] at least
  *                       anszp_plan_bytes(args->n_chunks) bytes, written on hip_stream.  A launch that
@@ -256,7 +257,7 @@ int anszp_decode_planned(const anszp_decode_args_t* args, const void* plan_dev, 
 
 /* For callers that cannot allocate device memory (code under stream capture, serving loops, harnesses
  * that forbid it): anszp_decode_planned with the plan kept in device memory of the library's own, a
- * fixed array of 512 KiB per device that holds a plan for at most 4096 chunks and stays until the
+ * fixed array of 1 MiB per device that holds a plan for at most 4096 chunks and stays until the
  * process ends.  Calls no allocating routine.  replan != 0: the plan is written first (as by
  * anszp_plan_decode) and the decode follows on the same stream; replan == 0: the array must still hold
  * the plan an earlier call on this device wrote for these arrays.  Every call on a device shares that

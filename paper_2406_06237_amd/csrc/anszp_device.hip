@@ -92,6 +92,11 @@ __device__ __forceinline__ uint32_t unit_of_workgroup(uint32_t b) {
     const uint32_t die = b % kDies, j = b / kDies;
     return ((j / kDieGroup) * kDies + die) * kDieGroup + j % kDieGroup;
 }
+// The workgroup that takes unit u (the inverse of unit_of_workgroup).
+__device__ __forceinline__ uint32_t workgroup_of_unit(uint32_t u) {
+    const uint32_t g = u % kDieGroup, t = u / kDieGroup, die = t % kDies, q = t / kDies;
+    return (q * kDieGroup + g) * kDies + die;
+}
 
 __device__ __forceinline__ uint32_t bf16_rne(float w) {
     uint32_t u = __float_as_uint(w);
@@ -1153,7 +1158,40 @@ __global__ __launch_bounds__(kBlock) void plan_units(DecodeParams p, PlanRecord*
             r.dominant = p.tables[size_t(layer_id) * table_stride_words(p.table_log) + table_triples_offset(p.table_log) + (1u << p.table_log) - 1u] >> 24;
         }
     }
-    plan[blockIdx.x] = r;
+    plan[gridDim.x + blockIdx.x] = r;              // (the second half of the plan's memory: plan_order puts the records in place)
+}
+
+// The records in the order the workgroups should take them: the chip starts workgroups in the order of their
+// numbers, over about a microsecond, and the launch ends with its slowest unit, so the units with the longest
+// chains (most stream words per chunk; two chunks in one workgroup run slower than one) go first.  Sorted units
+// keep the mapping to the dies: units of one layer are alike and stay neighbours.  One workgroup; launches of
+// more than kPlanOrderMax workgroups keep the order of the descriptors.
+constexpr uint32_t kPlanOrderMax = 8192u;
+__global__ __launch_bounds__(1024) void plan_order(PlanRecord* plan, uint32_t n) {
+    __shared__ uint32_t cost[kPlanOrderMax];
+    const PlanRecord* raw = plan + n;
+    const uint32_t tid = threadIdx.x;
+    if (n > kPlanOrderMax) {
+        for (uint32_t i = tid; i < n; i += 1024u) plan[i] = raw[i];
+        return;
+    }
+    for (uint32_t i = tid; i < n; i += 1024u) {
+        const PlanRecord& r = raw[i];
+        uint32_t c = 0;
+        if (r.count == 1u) c = 4u * min(r.c0.payload_words, 0x0FFFFFFFu);
+        else if (r.count == 2u) c = 5u * min(max(r.c0.payload_words, r.c1.payload_words), 0x0FFFFFFFu);
+        cost[i] = c;
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < n; i += 1024u) {
+        const uint32_t mine = cost[i], unit = unit_of_workgroup(i);
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < n; ++j) {
+            const uint32_t theirs = cost[j];
+            rank += (theirs > mine || (theirs == mine && unit_of_workgroup(j) < unit)) ? 1u : 0u;
+        }
+        plan[workgroup_of_unit(rank)] = raw[i];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1978,7 +2016,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream, uint32
     const bool lookahead = !k.stepwise && !k.byte_table;
     if (plan || plan_only) {
         if (!plan) return ANSZP_E_NULL;
-        if ((reinterpret_cast<uintptr_t>(plan) & 15) || plan_bytes < uint64_t(mapped_workgroups(nc)) * sizeof(PlanRecord)) return ANSZP_E_RANGE;
+        if ((reinterpret_cast<uintptr_t>(plan) & 15) || plan_bytes < 2u * uint64_t(mapped_workgroups(nc)) * sizeof(PlanRecord)) return ANSZP_E_RANGE;
     }
     if (plan_only) {
         // (a launch that does not go to the look-ahead kernel needs no plan: the memory stays as it is, and
@@ -1987,6 +2025,7 @@ int decode_impl(const anszp_decode_args_t* a, int mode, void* hip_stream, uint32
             const dim3 grid(mapped_workgroups(nc));
             if (k.small) hipLaunchKernelGGL(plan_units<SmallLds>, grid, dim3(kBlock), 0, s, p, reinterpret_cast<PlanRecord*>(plan));
             else hipLaunchKernelGGL(plan_units<LargeLds>, grid, dim3(kBlock), 0, s, p, reinterpret_cast<PlanRecord*>(plan));
+            hipLaunchKernelGGL(plan_order, dim3(1), dim3(1024), 0, s, reinterpret_cast<PlanRecord*>(plan), grid.x);
         }
         return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
     }
@@ -2034,7 +2073,7 @@ int choose_launch(const anszp_decode_args_t* a, int mode, DecodeParams& p, Launc
 
 // The plan that anszp_decode_static_plan keeps: device memory of the library's own, one array per device.
 constexpr uint32_t kStaticPlanChunks = 4096u;
-static __device__ __align__(256) unsigned char scratch[size_t(kStaticPlanChunks) * sizeof(PlanRecord)];
+static __device__ __align__(256) unsigned char scratch[2u * size_t(kStaticPlanChunks) * sizeof(PlanRecord)];
 constexpr int kMaxDevices = 64;
 std::atomic<void*> scratch_of_device[kMaxDevices];
 
@@ -2090,7 +2129,7 @@ void anszp_test_set_spin_limit(uint32_t polls) { spin_limit_for_tests.store(poll
 
 uint64_t anszp_plan_bytes(uint64_t n_chunks) {
     if (n_chunks >= (1ull << 31)) return 0;
-    return uint64_t(mapped_workgroups(static_cast<uint32_t>(n_chunks))) * sizeof(PlanRecord);
+    return 2u * uint64_t(mapped_workgroups(static_cast<uint32_t>(n_chunks))) * sizeof(PlanRecord);
 }
 
 int anszp_plan_decode(const anszp_decode_args_t* args, void* plan_dev, uint64_t plan_bytes, void* hip_stream) {
