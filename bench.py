@@ -464,7 +464,7 @@ def bench_decode(args, config, headline):
                      "kernel_ms": kernel_ms, "algorithmic_bytes": algo_bytes,
                      "timer": "events on the launch stream around the K launches / K"},
     }
-    if plan is not None and not args.no_extras:
+    if plan is not None and not args.no_extras and config != 4:
         result["without_plan"] = {"entry_point": "anszp_decode", "kernel_ms": time_launches(B, torch, a, dev, args.steps, args.warmup)}
         result["without_plan"]["hbm_frac"] = algo_bytes / (result["without_plan"]["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS
     if config in (2, 3) and not args.no_extras:
