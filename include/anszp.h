@@ -18,10 +18,11 @@
  * General conventions
  *   - Pointers marked [device] are device addresses of the current HIP device;
  *     pointers marked [host] are ordinary host addresses.  The caller owns every
- *     buffer.  The library allocates no device memory and keeps nothing between calls but two
- *     small per-device caches (the device's number of compute units, and which kernels have
- *     been given leave to use the whole of a CU's on-chip memory); they are tables of atomics,
- *     so calls from several host threads are safe.  anszp_build_tables allocates and frees
+ *     buffer.  The library allocates no device memory and keeps nothing between calls but
+ *     three small per-device caches (the device's number of compute units, which kernels have
+ *     been given leave to use the whole of a CU's on-chip memory, and the address of the
+ *     fixed plan area that anszp_decode_static_plan uses); they are tables of atomics, so
+ *     calls from several host threads are safe.  anszp_build_tables allocates and frees
  *     pinned host memory for its upload and waits for the copy.
  *   - `hip_stream` is a hipStream_t (NULL = default stream).  Device work is
  *     enqueued on it and the call returns without waiting, unless stated.

@@ -18,9 +18,12 @@
 //                          transitions of the dominant symbol, at most one of its 1-bit transitions
 //                          and the step that ends them are ONE look-up, indexed by the state and the
 //                          next stream bit).  The chunk's compressed words are staged in LDS.  One
-//                          wavefront only walks the automaton and logs the entries it passes; a
-//                          second turns logged entries into symbols in an LDS ring; two more convert
-//                          finished slabs of the ring and store them, 16 bytes per lane.
+//                          wavefront only walks the automaton and logs the entries it passes, eight
+//                          per lane and block; two more take the logged blocks in turn and expand
+//                          them into symbols in an LDS ring; three or four convert finished slabs
+//                          of the ring and store them, 16 bytes per lane.  A workgroup serves one
+//                          chunk or two chunks of one layer; which, and in what order the
+//                          workgroups take them, is found per launch or read from a prepared plan.
 // The look-ahead path needs the chunk's words to fit its LDS window and the chunk's first output
 // element to be 16-byte aligned; other chunks take the step-wise path inside the same launch.
 #include "anszp.h"
@@ -36,7 +39,7 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 768;                    // twelve wavefronts stage, eight of them stay for the decode
+constexpr int kBlock = 768;                    // twelve wavefronts stage; up to seven per chunk stay for the decode
 constexpr uint32_t kSlab = 1024u;              // elements that leave the ring together (two runs of 8 per lane)
 constexpr uint32_t kBlockLookups = 8u;         // look-ups a lane makes per block of the look-ahead kernel
 constexpr uint32_t kLogSlotBytes = (kBlockLookups + 1u) * kWave * 2u + 2u * kWave * 4u;   // nine rows of 16 bits per lane, two of 32
@@ -430,7 +433,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     // one object, the tables first: their entries are then within reach of an LDS instruction's offset field
     struct Lds {
         uint32_t table[2][kStates];
-        uint32_t rings[kStreamDecoders][kStreamRingWords][kWave];        // word s of lane l at [wave][s mod 32][l]
+        uint32_t rings[kStreamDecoders][kStreamRingWords + 1u][kWave];   // word s of lane l at [wave][s mod 32][l]; row 32 repeats row 0
         uint32_t position[kStreamDecoders][kWave];                       // word each stream's window starts at, or not started / finished
         uint32_t filled[kStreamDecoders][kWave];                         // words of each stream that are in its ring or before it
         uint32_t gave_up;
@@ -450,10 +453,6 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     const uint32_t layer_a = p.chunks[first].layer_id, layer_b = p.chunks[last].layer_id;
     const bool have_a = layer_a < p.n_tables, have_b = layer_b != layer_a && layer_b < p.n_tables;
     lds_flag_t* const gave_up = (lds_flag_t*)&lds.gave_up;
-    if (lds_address(&lds) % (kStreamRingWords * kWave * 4u) != 0u) {      // the ring addressing below relies on it
-        if (tid == 0) report(p.status, ANSZP_ST_INTERNAL);
-        return;
-    }
     if (tid < uint32_t(kStreamDecoders) * kWave) ((lds_flag_t*)&lds.position[0][0])[tid] = kStreamNotStarted;
     if (tid == 0) *gave_up = 0u;
 
@@ -541,6 +540,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         ring[s0 + 4][lane] = f.b.x; ring[s0 + 5][lane] = f.b.y; ring[s0 + 6][lane] = f.b.z; ring[s0 + 7][lane] = f.b.w;
         ring[s0 + 8][lane] = f.c.x; ring[s0 + 9][lane] = f.c.y; ring[s0 + 10][lane] = f.c.z; ring[s0 + 11][lane] = f.c.w;
         ring[s0 + 12][lane] = f.d.x; ring[s0 + 13][lane] = f.d.y; ring[s0 + 14][lane] = f.d.z; ring[s0 + 15][lane] = f.d.w;
+        if (s0 == 0u) ring[kStreamRingWords][lane] = f.a.x;              // so that a pair of neighbouring words never wraps
     };
 
     if (wave >= uint32_t(kStreamDecoders)) {
@@ -674,36 +674,39 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
     uint32_t fetched = kStreamRingWords;                  // words of the stream that are in the ring or before it (when this wavefront fetches itself)
 
     uint32_t abit = 32u * skew;                           // bit position, counted from the first word fetched
-    // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0
-    // (a ring is as large as it is aligned, so the slot of a word is a bit field of its address: two
-    // instructions per address instead of four)
-    constexpr uint32_t kRingBytes = kStreamRingWords * kWave * 4u;
-    static_assert((kRingBytes & (kRingBytes - 1u)) == 0u && offsetof(Lds, rings) % kRingBytes == 0u, "rings aligned to their size");
-    // (that the object itself starts on such a boundary is checked when the workgroup starts)
+    // the stream's next bits from the ring, bit `abit` of the stream in bit 0 of w0: four words, read as
+    // two pairs of neighbouring rows (one instruction each: the rows are 64 words apart)
     const uint32_t my_words = lds_address(&ring[0][lane]);               // word 0 of this lane
-    auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
-        constexpr uint32_t kSlotField = (kStreamRingWords - 1u) * kWave * 4u;          // 0x1F00
-        const uint32_t at = abit << 3;                                     // (abit >> 5) words * 256 bytes per slot, low bits dropped by the mask
-        auto word = [&](uint32_t i) {
-            return *reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(((at + i * kWave * 4u) & kSlotField) | my_words));
-        };
-        w0 = word(0); w1 = word(1); w2 = word(2); w3 = word(3);
+    auto pair_addresses = [&](uint32_t& a01, uint32_t& a23) {
+        a01 = my_words + (((abit >> 5) & (kStreamRingWords - 1u)) << 8);
+        a23 = my_words + ((((abit + 64u) >> 5) & (kStreamRingWords - 1u)) << 8);
+    };
+    auto shift_window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
         w0 = __builtin_amdgcn_alignbit(w1, w0, abit);
         w1 = __builtin_amdgcn_alignbit(w2, w1, abit);
         w2 = __builtin_amdgcn_alignbit(w3, w2, abit);
         w3 >>= (abit & 31u);
     };
+    auto window = [&](uint32_t& w0, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
+        uint32_t a01, a23;
+        pair_addresses(a01, a23);
+        const lds_uint32_t* const p01 = reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(a01));
+        const lds_uint32_t* const p23 = reinterpret_cast<const lds_uint32_t*>(static_cast<uintptr_t>(a23));
+        w0 = p01[0]; w1 = p01[kWave]; w2 = p23[0]; w3 = p23[kWave];
+        shift_window(w0, w1, w2, w3);
+    };
     // K steps of the fast form from the window w0..w2 (bit `abit` of the stream in bit 0 of w0).
     // A step may read table_log <= 12 bits, so of the 96 bits only those a later step of the K can
     // still reach are kept in place.
-    auto steps_fast = [&](auto count_tag, uint32_t w0, uint32_t w1, uint32_t w2, auto&& emit) {
+    // (`first` gives the entry of the current state: a caller may have asked for it with the window)
+    auto steps_fast = [&](auto count_tag, uint32_t w0, uint32_t w1, uint32_t w2, auto&& emit, auto&& first) {
         constexpr int K = static_cast<int>(decltype(count_tag)::value);
         static_assert(K * ANSZP_MAX_TABLE_LOG <= 96, "the window of K steps");
         w0 = __brev(w0); w1 = __brev(w1); w2 = __brev(w2);
         uint32_t sum = 0;                                 // 32 - nb_bits over the K steps, in its low bits
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const uint32_t e = entry_at(X);
+            const uint32_t e = k == 0 ? first() : entry_at(X);
             const uint32_t bits = w0 >> (e & 31u);                         // first bit read is the top bit
             X = next_entry_offset(e, bits);
             if (k <= K - 2) w0 = __builtin_amdgcn_alignbit(w0, w1, e);
@@ -729,7 +732,7 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
         if (fetching) fetch(mine, readable, fetched, f);
         uint32_t w0, w1, w2, w3;
         window(w0, w1, w2, w3);
-        steps_fast(count_tag, w0, w1, w2, emit);
+        steps_fast(count_tag, w0, w1, w2, emit, [&]() { return entry_at(X); });
         if (fetching) {
             land(ring, fetched, f);
             fetched += kStreamFetchWords;
@@ -785,17 +788,30 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
                 }
             };
             // K steps from the ring as the loading wavefront fills it: the window's four words must be there
+            const uint32_t filled_at = lds_address(&lds.filled[wave][lane]);
             auto block_fed = [&](auto count_tag) {
-                uint32_t w0, w1, w2, w3;
+                uint32_t w0, w1, w2, w3, e0;
                 for (uint32_t spins = 0;;) {
-                    const uint32_t have = filled[lane];                    // read before the words themselves
-                    asm volatile("" ::: "memory");
-                    window(w0, w1, w2, w3);
+                    // how far the ring is filled, read before the words themselves, and the entry of the current
+                    // state: all in flight together (left to the compiler, each waits for the one before)
+                    uint32_t a01, a23, have;
+                    words2 w01, w23;
+                    pair_addresses(a01, a23);
+                    asm volatile("ds_read_b32 %[have], %[at]\n\t"
+                                 "ds_read2st64_b32 %[w01], %[a01] offset1:1\n\t"
+                                 "ds_read2st64_b32 %[w23], %[a23] offset1:1\n\t"
+                                 "ds_read_b32 %[e0], %[x]\n\t"
+                                 "s_waitcnt lgkmcnt(0)"
+                                 : [have] "=&v"(have), [w01] "=&v"(w01), [w23] "=&v"(w23), [e0] "=&v"(e0)
+                                 : [at] "v"(filled_at), [a01] "v"(a01), [a23] "v"(a23), [x] "v"(entries + X)
+                                 : "memory");
+                    w0 = w01.x; w1 = w01.y; w2 = w23.x; w3 = w23.y;
+                    shift_window(w0, w1, w2, w3);
                     if (__ballot(have - (abit >> 5) < 4u) == 0ull) break;
                     if (uniform(*gave_up) || ++spins > p.spin_limit) { stuck = true; return; }
                     __builtin_amdgcn_s_sleep(1);
                 }
-                steps_fast(count_tag, w0, w1, w2, emit);
+                steps_fast(count_tag, w0, w1, w2, emit, [&]() { return e0; });
                 position[lane] = abit >> 5;
             };
             // Wavefronts go to the four SIMDs round robin, and a SIMD serves the oldest of its wavefronts
@@ -1670,8 +1686,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
-#define ANSZP_LOOKUP(ELO, EHI, FB, K, SHIFT, SUM)                                      \
-        "s_waitcnt lgkmcnt(1)\n"                                                       \
+#define ANSZP_LOOKUP(WAIT, ELO, EHI, FB, K, SHIFT, SUM, BESIDE)                         \
+        "s_waitcnt lgkmcnt(" WAIT ")\n"                                                \
         "v_lshrrev_b32 v36, " ELO ", v53\n"                                            \
         "v_lshl_add_u32 v36, v36, 3, " EHI "\n"                                        \
         "ds_read_b64 " FB ", v36 offset:512\n"                                         \
@@ -1679,10 +1695,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         "v_not_b32 v35, " ELO "\n"                                                     \
         SHIFT                                                                          \
         "v_bfrev_b32 v53, v28\n"                                                       \
-        SUM
-#define ANSZP_FIRST(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_mov_b32 v37, v24\n")
-#define ANSZP_AB(K, SHIFT) ANSZP_LOOKUP("v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n")
-#define ANSZP_BA(K, SHIFT) ANSZP_LOOKUP("v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n")
+        SUM BESIDE
+#define ANSZP_AB(WAIT, K, SHIFT, BESIDE) ANSZP_LOOKUP(WAIT, "v24", "v25", "v[26:27]", K, SHIFT, "v_add_u32 v37, v37, v24\n", BESIDE)
+#define ANSZP_BA(WAIT, K, SHIFT, BESIDE) ANSZP_LOOKUP(WAIT, "v26", "v27", "v[24:25]", K, SHIFT, "v_add_u32 v37, v37, v26\n", BESIDE)
     static_assert(ANSZP_MAX_TABLE_LOG <= 12 && kBlockLookups == 8u, "the reach of a look-up assumed by the window shifts");
     static_assert(kLogSlotBytes == 1664u, "log slot: nine rows of 16 bits per lane, then two rows of 32");
     const uint32_t reach = kBlockLookups * kLookaheadMaxSymbols * N;      // a block advances a lane by at most 8 entries of 8 symbols
@@ -1705,90 +1720,120 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         }
         spins = 0;
         uint32_t logged_v = logged;
+        // What the wavefront issues between the last look-up of a block and the first of the next one is what a
+        // block costs beyond its eight LDS round trips (there it is bound by what it issues, beside a look-up by
+        // the round trip), so only what needs the last entry stands there: the new bit position and the reload
+        // of the window, the count of symbols, who may run the next block.  The rest is issued beside the
+        // look-ups: the other wavefronts' hand-over words are read beside the first and reduced to scalars beside
+        // the third to sixth, the next block's number and log slot beside the fourth and fifth, the sums over the
+        // first seven entries beside the seventh; a block is published beside the first look-up of the next one.
         asm volatile(
             "v_mov_b32 v24, %[elo]\n v_mov_b32 v25, %[ehi]\n v_mov_b32 v52, %[ab]\n v_mov_b32 v39, %[ne]\n"
             "v_mov_b32 v43, %[ctla]\n"
             "v_readfirstlane_b32 s44, %[logged]\n"
             "s_mov_b64 s[40:41], exec\n"
+            "s_lshl_b32 s49, %[nstr], 3\n"
             "v_cmp_gt_u32 vcc, %[lim], v39\n"
             "v_lshrrev_b32 v38, 3, v52\n"
             "v_and_b32 v38, 0x1ffffffc, v38\n"
             "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, the expanding wavefronts' next blocks */
-            "ds_read_b128 v[54:57], v43 offset:16\n"   /* elements stored (by up to four wavefronts) */
             "s_and_b64 s[42:43], s[40:41], vcc\n"      /* lanes that run this block (some do) */
-            "1:\n"
             "s_and_b32 s45, s44, %[slotmask]\n"        /* the block's log slot */
             "s_mul_i32 s46, s45, 1664\n"
             "v_add_u32 v42, s46, %[lanelog]\n"         /* this lane's 16-bit column in the slot */
             "v_add_u32 v47, s46, %[lanebit]\n"         /* and its word in the rows of bit positions and positions */
             "ds_write_b32 v47, v39 offset:%[posrow]\n" /* where every lane stands as the block begins */
             "s_mov_b64 exec, s[42:43]\n"
-            "s_waitcnt lgkmcnt(3)\n"                   /* the window words; the hand-over words were asked for after them */
+            "s_waitcnt lgkmcnt(1)\n"
+            "s_branch 3f\n"
+            "1:\n"
+            "ds_write_b32 v47, v39 offset:%[posrow]\n"
+            "s_mov_b64 exec, s[42:43]\n"
+            "s_waitcnt lgkmcnt(2)\n"                   /* the window words (and the entry the block starts from) */
+            "3:\n"
             "v_alignbit_b32 v28, v29, v28, v52\n"
-            "v_alignbit_b32 v29, v30, v29, v52\n"
+            "v_bfrev_b32 v53, v28\n"
+            "v_lshrrev_b32 v36, v24, v53\n"            /* first look-up */
+            "v_lshl_add_u32 v36, v36, 3, v25\n"
+            "ds_read_b64 v[26:27], v36 offset:512\n"
+            "ds_write_b16_d16_hi v42, v24 offset:0\n"
+            "v_mov_b32 v41, s44\n"
+            "ds_write_b32 v43, v41\n"                  /* publish the block before this one */
+            "v_alignbit_b32 v29, v30, v29, v52\n"      /* the rest of the window into place */
             "v_alignbit_b32 v30, v31, v30, v52\n"
             "v_lshrrev_b32 v31, v52, v31\n"
+            "v_not_b32 v35, v24\n"
+            ANSZP_SHIFT_W2
             "v_bfrev_b32 v53, v28\n"
-            ANSZP_FIRST("0", ANSZP_SHIFT_W2) ANSZP_BA("1", ANSZP_SHIFT_W2) ANSZP_AB("2", ANSZP_SHIFT_W1) ANSZP_BA("3", ANSZP_SHIFT_W1)
-            ANSZP_AB("4", ANSZP_SHIFT_W1) ANSZP_BA("5", ANSZP_SHIFT_W0) ANSZP_AB("6", ANSZP_SHIFT_W0)
+            "v_mov_b32 v37, v24\n"
+            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, the expanding wavefronts' next blocks */
+            "ds_read_b128 v[54:57], v43 offset:16\n"   /* elements stored (by up to four wavefronts) */
+            "v_add_u32 v34, 31*8, v52\n"               /* the bit position if the block read no bits */
+            ANSZP_BA("4", "1", ANSZP_SHIFT_W2,
+                     "v_add_u32 v40, s49, v39\n")      /* the position if every look-up stood for one symbol */
+            ANSZP_AB("1", "2", ANSZP_SHIFT_W1,
+                     "v_min_u32 v49, v49, v50\n"       /* blocks expanded: every one below the next of either expanding wavefront */
+                     "v_readfirstlane_b32 s47, v49\n")
+            ANSZP_BA("1", "3", ANSZP_SHIFT_W1,
+                     "v_min3_u32 v50, v54, v55, v56\n" /* elements stored: every slab below the next one of any storing wavefront */
+                     "v_min_u32 v50, v50, v57\n"
+                     "s_lshl_b32 s51, s44, 22\n"       /* this block's number, as the bit positions are tagged with it */
+                     "s_add_u32 s44, s44, 1\n")        /* from here on: the next block */
+            ANSZP_AB("1", "4", ANSZP_SHIFT_W1,
+                     "v_readfirstlane_b32 s48, v50\n"
+                     "s_add_u32 s48, s48, %[room]\n"   /* lanes below this position fit the ring, */
+                     "s_min_u32 s48, s48, %[nsym]\n"   /* and have not ended (a lane's end is its first position at or beyond the chunk's) */
+                     "s_and_b32 s45, s44, %[slotmask]\n"
+                     "s_mul_i32 s46, s45, 1664\n")     /* the next block's log slot */
+            ANSZP_BA("1", "5", ANSZP_SHIFT_W0,
+                     "s_sub_u32 s45, s44, s47\n"
+                     "s_cmp_lt_u32 s45, %[slots]\n"    /* unless the next log slot may still be in use, */
+                     "s_cselect_b64 s[52:53], s[40:41], 0\n")   /* every lane may go on that fits the ring */
+            ANSZP_AB("1", "6", ANSZP_SHIFT_W0,
+                     "v_and_b32 v46, 0x1ff, v37\n"
+                     "v_sub_u32 v33, v34, v46\n"       /* minus the stream bits seven look-ups consumed */
+                     "v_bfe_u32 v46, v37, 9, 7\n"
+                     "v_mad_u32_u24 v40, v46, %[nstr], v40\n")   /* plus the symbols seven entries stand for beyond one each */
             "s_waitcnt lgkmcnt(1)\n"                   /* the eighth look-up shifts no window */
             "v_lshrrev_b32 v36, v26, v53\n"
-            "v_lshl_add_u32 v36, v36, 3, v27\n"
-            "ds_read_b64 v[24:25], v36 offset:512\n"
+            "v_lshl_add_u32 v45, v36, 3, v27\n"
+            "ds_read_b64 v[24:25], v45 offset:512\n"
             "ds_write_b16_d16_hi v42, v26 offset:7*128\n"
-            "ds_write_b16 v42, v36 offset:8*128\n"   /* where the next look-up starts: below 16 in state 0 */
-            "v_add_u32 v37, v37, v26\n"
-            "v_and_b32 v46, 0x1ff, v37\n"
-            "v_sub_u32 v46, 31*8, v46\n"              /* stream bits the block consumed */
-            "v_add_u32 v52, v52, v46\n"
-            "v_lshl_or_b32 v46, s44, 22, v52\n"       /* bit position after the block, tagged with the block's number */
-            "ds_write_b32 v47, v46 offset:%[bitrow]\n"
+            "ds_write_b16 v42, v45 offset:8*128\n"   /* where the next look-up starts: below 16 in state 0 */
+            "v_sub_u32_sdwa v52, v33, v26 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0\n"   /* and the eighth: the new bit position */
             "v_lshrrev_b32 v38, 3, v52\n"              /* the block's lanes reload their words (a lane that sat the */
             "v_and_b32 v38, 0x1ffffffc, v38\n"         /* block out has not moved: its words are still in place)    */
-            "v_min_u32 v38, %[lastw], v38\n"
             "ds_read2_b32 v[28:29], v38 offset1:1\n"
             "ds_read2_b32 v[30:31], v38 offset0:2 offset1:3\n"
-            "v_bfe_u32 v35, v37, 9, 7\n"
-            "v_add_u32 v35, 8, v35\n"                  /* symbols the block stands for */
-            "v_mad_u32_u24 v39, v35, %[nstr], v39\n"
-            "s_add_u32 s44, s44, 1\n"
-            "v_mov_b32 v46, s44\n"
-            "ds_write_b32 v43, v46\n"                  /* publish the block */
-            "v_min_u32 v49, v49, v50\n"                /* blocks expanded when the previous block ended: every one */
-            "v_readfirstlane_b32 s46, v49\n"           /* below the next of either expanding wavefront */
+            "v_bfe_u32 v46, v26, 9, 3\n"
+            "v_mad_u32_u24 v39, v46, %[nstr], v40\n"   /* the new position */
+            "v_or_b32 v46, s51, v52\n"                 /* bit position after the block, tagged with the block's number */
+            "ds_write_b32 v47, v46 offset:%[bitrow]\n"
             "s_mov_b64 exec, s[40:41]\n"
-            "v_min3_u32 v50, v54, v55, v56\n"          /* elements stored when the previous block ended: every */
-            "v_min_u32 v50, v50, v57\n"                /* slab below the next one of any storing wavefront */
-            "v_add_u32 v50, %[room], v50\n"
-            "v_min_u32 v50, %[lend], v50\n"
-            "v_cmp_gt_u32 vcc, v50, v39\n"             /* lanes that can run another block */
-            "ds_read_b128 v[48:51], v43\n"             /* the same words, for the end of the next block */
-            "ds_read_b128 v[54:57], v43 offset:16\n"
-            "s_sub_u32 s46, s44, s46\n"
-            "s_cmp_ge_u32 s46, %[slots]\n"             /* the next log slot may still be in use */
-            "s_cbranch_scc1 2f\n"
-            "s_and_b64 s[42:43], s[40:41], vcc\n"
+            "v_cmp_gt_u32 vcc, s48, v39\n"             /* lanes that can run another block */
+            "v_add_u32 v42, s46, %[lanelog]\n"
+            "v_add_u32 v47, s46, %[lanebit]\n"
+            "s_and_b64 s[42:43], s[52:53], vcc\n"
             "s_cbranch_scc1 1b\n"
-            "2:\n"
-            "s_mov_b64 exec, s[40:41]\n"
+            "v_mov_b32 v41, s44\n"
+            "ds_write_b32 v43, v41\n"                  /* publish the last block */
             "s_waitcnt lgkmcnt(0)\n"
             "v_mov_b32 %[elo], v24\n v_mov_b32 %[ehi], v25\n v_mov_b32 %[ab], v52\n v_mov_b32 %[ne], v39\n"
             "v_mov_b32 %[logged], s44\n"
             : [elo] "+v"(e.x), [ehi] "+v"(e.y), [ab] "+v"(abit), [ne] "+v"(ne), [logged] "+v"(logged_v)
-            : [lim] "v"(limit), [lend] "v"(lane_end), [room] "s"(uniform(room)), [nstr] "s"(uniform(N)),
+            : [lim] "v"(limit), [room] "s"(uniform(room)), [nstr] "s"(uniform(N)), [nsym] "s"(uniform(n)),
               [lastw] "s"(uniform(last_word)), [ctla] "s"(uniform(pipe_off + kCtlOff)),
               [lanelog] "v"(pipe_off + kLogOff + lane * 2u), [lanebit] "v"(pipe_off + kLogOff + lane * 4u),
               [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [bitrow] "n"((kBlockLookups + 1u) * 2u * kWave),
               [posrow] "n"((kBlockLookups + 1u) * 2u * kWave + 4u * kWave)
-            : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "v24", "v25", "v26", "v27", "v28", "v29", "v30",
-              "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v42", "v43", "v46", "v47",
+            : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s51", "s52", "s53",
+              "v24", "v25", "v26", "v27", "v28", "v29", "v30",
+              "v31", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v45", "v46", "v47",
               "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57");
         logged = uniform(logged_v);
     }
-#undef ANSZP_FIRST
 #undef ANSZP_AB
 #undef ANSZP_BA
 #undef ANSZP_LOOKUP
