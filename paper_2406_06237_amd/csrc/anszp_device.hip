@@ -941,27 +941,18 @@ struct Flusher {
 #pragma unroll
             for (int i = 0; i < 4; ++i) { sym[i] = (s.x >> (8 * i)) & 0xFFu; sym[4 + i] = (s.y >> (8 * i)) & 0xFFu; }
             if constexpr (kFolded) {
-                // The table of weights sits at LDS address 0 (the look-ahead kernel checks that): twice a symbol
-                // is its entry's address, one instruction per symbol (an add that selects the byte in both operands).
-                uint32_t a0, a1, a2, a3, a4, a5, a6, a7, w0, w1, w2, w3, w4, w5, w6, w7;
-                asm volatile(
-                    "v_add_u32_sdwa %[a0], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:BYTE_0\n"
-                    "v_add_u32_sdwa %[a1], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:BYTE_1\n"
-                    "v_add_u32_sdwa %[a2], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:BYTE_2\n"
-                    "v_add_u32_sdwa %[a3], %[x], %[x] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:BYTE_3\n"
-                    "v_add_u32_sdwa %[a4], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:BYTE_0\n"
-                    "v_add_u32_sdwa %[a5], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:BYTE_1\n"
-                    "v_add_u32_sdwa %[a6], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:BYTE_2\n"
-                    "v_add_u32_sdwa %[a7], %[y], %[y] dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:BYTE_3\n"
-                    "ds_read_u16 %[w0], %[a0]\n ds_read_u16 %[w1], %[a1]\n ds_read_u16 %[w2], %[a2]\n ds_read_u16 %[w3], %[a3]\n"
-                    "ds_read_u16 %[w4], %[a4]\n ds_read_u16 %[w5], %[a5]\n ds_read_u16 %[w6], %[a6]\n ds_read_u16 %[w7], %[a7]\n"
-                    "s_waitcnt lgkmcnt(0)\n"
-                    : [a0] "=&v"(a0), [a1] "=&v"(a1), [a2] "=&v"(a2), [a3] "=&v"(a3), [a4] "=&v"(a4), [a5] "=&v"(a5), [a6] "=&v"(a6), [a7] "=&v"(a7),
-                      [w0] "=&v"(w0), [w1] "=&v"(w1), [w2] "=&v"(w2), [w3] "=&v"(w3), [w4] "=&v"(w4), [w5] "=&v"(w5), [w6] "=&v"(w6), [w7] "=&v"(w7)
-                    : [x] "v"(s.x), [y] "v"(s.y)
-                    : "memory");
-                (void)lut;
-                __builtin_nontemporal_store(words4{w0 | (w1 << 16), w2 | (w3 << 16), w4 | (w5 << 16), w6 | (w7 << 16)},
+                // Per-layer scale, bf16 out: float(q) - float(z) is exact, the product is rounded once, and two
+                // weights are rounded to bf16 by one instruction.  (A table of the 256 weights in LDS costs a
+                // look-up per symbol instead; the storing wavefronts then wait for LDS, which the decoding and
+                // expanding wavefronts keep busy.)
+                const float zf = static_cast<float>(lay.zero_point), sc = lay.scale;
+                auto weights = [&](uint32_t word, int i) {
+                    const float a = sc * (static_cast<float>((word >> (16 * i)) & 0xFFu) - zf);
+                    const float b = sc * (static_cast<float>((word >> (16 * i + 8)) & 0xFFu) - zf);
+                    return __builtin_bit_cast(uint32_t, __builtin_convertvector(floats2{a, b}, bf16s2));
+                };
+                (void)lut; (void)sym;
+                __builtin_nontemporal_store(words4{weights(s.x, 0), weights(s.x, 1), weights(s.y, 0), weights(s.y, 1)},
                                             reinterpret_cast<words4*>(static_cast<uint16_t*>(p.out) + g));
             } else {
                 float v[8];
@@ -1560,6 +1551,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         }
         uint32_t block = sub, spins = 0;
         uint32_t ne = (lane < N && lane < n) ? lane : 0xFFFFFFF0u;          // as staged: after the last block (none yet)
+        // the block a lane's stream ends in (of this wavefront's blocks), kept for the checks behind the loop
+        uint32_t end_ent[kBlockLookups + 1u] = {}, end_bit_after = 0, end_ne_before = 0;
+        bool ended_here = false;
         constexpr uint32_t kBitRow = (kBlockLookups + 1u) * 2u * kWave;      // offset of the row of bit positions in a log slot
         constexpr uint32_t kPosRow = kBitRow + 4u * kWave;                   // and of the row of positions
         typedef __attribute__((address_space(3))) uint8_t lds_uint8_t;
@@ -1621,25 +1615,34 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
                          :: [pa] "v"(pipe_off + kProgOff + sub * (kWave * 4u) + lane * 4u), [ne] "v"(ne),
                             [nxa] "v"(pipe_off + kCtlOff + 4u * (kNext0 + sub)), [nx] "v"(block)
                          : "memory");
-            if (took_part && ne >= lane_end) {           // the stream's last symbol lies in this block: find its entry
-                uint32_t consumed = 0;
+            if (took_part && ne >= lane_end) {           // the stream's last symbol lies in this block: looked at behind the loop
 #pragma unroll
-                for (uint32_t k = 0; k < kBlockLookups; ++k) consumed += (ent[k] >> 8) & 15u;
-                uint32_t pos = ne_before, bits = (bit_after & 0x3FFFFFu) - consumed;     // where the stream stood when the block began
-                bool found = false;
+                for (uint32_t k = 0; k <= kBlockLookups; ++k) end_ent[k] = ent[k];
+                end_bit_after = bit_after;
+                end_ne_before = ne_before;
+                ended_here = true;
+            }
+        }
+        // Streams that ended in one of this wavefront's blocks (once each, so this waits until no block is held up
+        // by it): find the entry the last symbol lies in.
+        if (ended_here) {
+            uint32_t consumed = 0;
 #pragma unroll
-                for (uint32_t k = 0; k < kBlockLookups; ++k) {
-                    const uint32_t after = pos + (((ent[k] >> 12) & 7u) + 1u) * N;
-                    bits += (ent[k] >> 8) & 15u;
-                    if (!found && after >= lane_end) {
-                        found = true;
-                        // it must end with the entry, in state 0, the stream's words read and no more
-                        const bool in_state_0 = k + 1u < kBlockLookups ? (ent[k + 1u] >> 15) != 0u : ent[kBlockLookups] < 16u;
-                        if (after != lane_end || !in_state_0) err |= ANSZP_ST_BAD_STATE;
-                        if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
-                    }
-                    pos = after;
+            for (uint32_t k = 0; k < kBlockLookups; ++k) consumed += (end_ent[k] >> 8) & 15u;
+            uint32_t pos = end_ne_before, bits = (end_bit_after & 0x3FFFFFu) - consumed;     // where the stream stood when the block began
+            bool found = false;
+#pragma unroll
+            for (uint32_t k = 0; k < kBlockLookups; ++k) {
+                const uint32_t after = pos + (((end_ent[k] >> 12) & 7u) + 1u) * N;
+                bits += (end_ent[k] >> 8) & 15u;
+                if (!found && after >= lane_end) {
+                    found = true;
+                    // it must end with the entry, in state 0, the stream's words read and no more
+                    const bool in_state_0 = k + 1u < kBlockLookups ? (end_ent[k + 1u] >> 15) != 0u : end_ent[kBlockLookups] < 16u;
+                    if (after != lane_end || !in_state_0) err |= ANSZP_ST_BAD_STATE;
+                    if (((bits - first_bit + 31u) >> 5) != n_words) err |= ANSZP_ST_BAD_LENGTH;
                 }
+                pos = after;
             }
         }
         // the wavefront that expanded the last block knows where every stream stands: at its end
