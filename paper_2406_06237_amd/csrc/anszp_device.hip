@@ -1727,8 +1727,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         // block costs beyond its eight LDS round trips (there it is bound by what it issues, beside a look-up by
         // the round trip), so only what needs the last entry stands there: the new bit position and the reload
         // of the window, the count of symbols, who may run the next block.  The rest is issued beside the
-        // look-ups: the other wavefronts' hand-over words are read beside the first and reduced to scalars beside
-        // the third to sixth, the next block's number and log slot beside the fourth and fifth, the sums over the
+        // look-ups: the other wavefronts' hand-over words are read beside the fourth (late, so that they are fresh) and reduced
+        // to scalars beside the sixth and seventh, the next block's number and log slot beside the second and third, the sums over the
         // first seven entries beside the seventh; a block is published beside the first look-up of the next one.
         asm volatile(
             "v_mov_b32 v24, %[elo]\n v_mov_b32 v25, %[ehi]\n v_mov_b32 v52, %[ab]\n v_mov_b32 v39, %[ne]\n"
@@ -1771,30 +1771,31 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             ANSZP_SHIFT_W2
             "v_bfrev_b32 v53, v28\n"
             "v_mov_b32 v37, v24\n"
-            "ds_read_b128 v[48:51], v43\n"             /* blocks logged, the expanding wavefronts' next blocks */
-            "ds_read_b128 v[54:57], v43 offset:16\n"   /* elements stored (by up to four wavefronts) */
             "v_add_u32 v34, 31*8, v52\n"               /* the bit position if the block read no bits */
-            ANSZP_BA("4", "1", ANSZP_SHIFT_W2,
-                     "v_add_u32 v40, s49, v39\n")      /* the position if every look-up stood for one symbol */
-            ANSZP_AB("1", "2", ANSZP_SHIFT_W1,
-                     "v_min_u32 v49, v49, v50\n"       /* blocks expanded: every one below the next of either expanding wavefront */
-                     "v_readfirstlane_b32 s47, v49\n")
-            ANSZP_BA("1", "3", ANSZP_SHIFT_W1,
-                     "v_min3_u32 v50, v54, v55, v56\n" /* elements stored: every slab below the next one of any storing wavefront */
-                     "v_min_u32 v50, v50, v57\n"
+            ANSZP_BA("2", "1", ANSZP_SHIFT_W2,
+                     "v_add_u32 v40, s49, v39\n"       /* the position if every look-up stood for one symbol */
                      "s_lshl_b32 s51, s44, 22\n"       /* this block's number, as the bit positions are tagged with it */
                      "s_add_u32 s44, s44, 1\n")        /* from here on: the next block */
-            ANSZP_AB("1", "4", ANSZP_SHIFT_W1,
-                     "v_readfirstlane_b32 s48, v50\n"
-                     "s_add_u32 s48, s48, %[room]\n"   /* lanes below this position fit the ring, */
-                     "s_min_u32 s48, s48, %[nsym]\n"   /* and have not ended (a lane's end is its first position at or beyond the chunk's) */
+            ANSZP_AB("1", "2", ANSZP_SHIFT_W1,
                      "s_and_b32 s45, s44, %[slotmask]\n"
                      "s_mul_i32 s46, s45, 1664\n")     /* the next block's log slot */
+            ANSZP_BA("1", "3", ANSZP_SHIFT_W1,         /* (not earlier: what they say decides who runs the next block) */
+                     "ds_read_b128 v[48:51], v43\n"    /* blocks logged, the expanding wavefronts' next blocks */
+                     "ds_read_b128 v[54:57], v43 offset:16\n")   /* elements stored (by up to four wavefronts) */
+            ANSZP_AB("3", "4", ANSZP_SHIFT_W1, "")
             ANSZP_BA("1", "5", ANSZP_SHIFT_W0,
+                     "v_min_u32 v49, v49, v50\n"       /* blocks expanded: every one below the next of either expanding wavefront */
+                     "v_min3_u32 v50, v54, v55, v56\n" /* elements stored: every slab below the next one of any storing wavefront */
+                     "v_readfirstlane_b32 s47, v49\n"  /* (a lane read must not directly follow the instruction that writes its register) */
+                     "v_min_u32 v50, v50, v57\n"
+                     "s_nop 0\n"
+                     "v_readfirstlane_b32 s48, v50\n"
+                     "s_add_u32 s48, s48, %[room]\n"   /* lanes below this position fit the ring, */
+                     "s_min_u32 s48, s48, %[nsym]\n")  /* and have not ended (a lane's end is its first position at or beyond the chunk's) */
+            ANSZP_AB("1", "6", ANSZP_SHIFT_W0,
                      "s_sub_u32 s45, s44, s47\n"
                      "s_cmp_lt_u32 s45, %[slots]\n"    /* unless the next log slot may still be in use, */
-                     "s_cselect_b64 s[52:53], s[40:41], 0\n")   /* every lane may go on that fits the ring */
-            ANSZP_AB("1", "6", ANSZP_SHIFT_W0,
+                     "s_cselect_b64 s[52:53], s[40:41], 0\n"   /* every lane may go on that fits the ring */
                      "v_and_b32 v46, 0x1ff, v37\n"
                      "v_sub_u32 v33, v34, v46\n"       /* minus the stream bits seven look-ups consumed */
                      "v_bfe_u32 v46, v37, 9, 7\n"
@@ -1821,7 +1822,33 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
             "s_and_b64 s[42:43], s[52:53], vcc\n"
             "s_cbranch_scc1 1b\n"
             "v_mov_b32 v41, s44\n"
-            "ds_write_b32 v43, v41\n"                  /* publish the last block */
+            "ds_write_b32 v43, v41\n"                  /* nobody can: publish the last block */
+            "v_cmp_gt_u32 vcc, %[nsym], v39\n"
+            "s_cbranch_vccz 2f\n"                      /* every stream has ended */
+            "s_mov_b32 s54, 24\n"                      /* some wait for the storing or expanding wavefronts: a few looks from here, */
+            "4:\n"                                     /* with fresh hand-over words (leaving and coming back costs a block's time) */
+            "ds_read_b128 v[48:51], v43\n"
+            "ds_read_b128 v[54:57], v43 offset:16\n"
+            "s_waitcnt lgkmcnt(0)\n"
+            "v_min_u32 v49, v49, v50\n"
+            "v_min3_u32 v50, v54, v55, v56\n"
+            "v_readfirstlane_b32 s47, v49\n"
+            "v_min_u32 v50, v50, v57\n"
+            "s_nop 0\n"
+            "v_readfirstlane_b32 s48, v50\n"
+            "s_add_u32 s48, s48, %[room]\n"
+            "s_min_u32 s48, s48, %[nsym]\n"
+            "s_sub_u32 s45, s44, s47\n"
+            "s_cmp_lt_u32 s45, %[slots]\n"
+            "s_cselect_b64 s[52:53], s[40:41], 0\n"
+            "v_cmp_gt_u32 vcc, s48, v39\n"
+            "s_and_b64 s[42:43], s[52:53], vcc\n"
+            "s_cbranch_scc1 1b\n"
+            "s_sleep 1\n"
+            "s_sub_u32 s54, s54, 1\n"
+            "s_cmp_lg_u32 s54, 0\n"
+            "s_cbranch_scc1 4b\n"
+            "2:\n"
             "s_waitcnt lgkmcnt(0)\n"
             "v_mov_b32 %[elo], v24\n v_mov_b32 %[ehi], v25\n v_mov_b32 %[ab], v52\n v_mov_b32 %[ne], v39\n"
             "v_mov_b32 %[logged], s44\n"
@@ -1831,7 +1858,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
               [lanelog] "v"(pipe_off + kLogOff + lane * 2u), [lanebit] "v"(pipe_off + kLogOff + lane * 4u),
               [slots] "n"(kLogSlots), [slotmask] "n"(kLogSlots - 1u), [bitrow] "n"((kBlockLookups + 1u) * 2u * kWave),
               [posrow] "n"((kBlockLookups + 1u) * 2u * kWave + 4u * kWave)
-            : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s51", "s52", "s53",
+            : "memory", "vcc", "scc", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s51", "s52", "s53", "s54",
               "v24", "v25", "v26", "v27", "v28", "v29", "v30",
               "v31", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v45", "v46", "v47",
               "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57");
