@@ -922,9 +922,8 @@ __global__ __launch_bounds__(kStreamWaves * kWave) void decode_streaming(DecodeP
 }
 
 // ---------------------------------------------------------------------------------------------
-// Look-ahead path: conversion of decoded symbols on their way from the LDS ring to global memory.
-// `lut` maps a symbol to its bf16 weight when dequantisation is per layer and the output bf16
-// (Sec. II-B computed once per symbol value instead of once per weight).
+// Look-ahead path: conversion of decoded symbols on their way from the LDS ring to global memory
+// (Sec. II-B: w = scale * (q - z)).
 template <int OUT, bool PER_CHANNEL>
 struct Flusher {
     static constexpr bool kFolded = (OUT == ANSZP_OUT_BF16 && !PER_CHANNEL);
@@ -933,7 +932,7 @@ struct Flusher {
     // on the ResNet-50-shaped set: 30.4 -> 28.0 us per launch, with the same bytes fetched from
     // memory: the gain is in the L2's handling of the stores).
     static __device__ __forceinline__ void store8(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
-                                                  uint64_t layer_elem, uint2 s, const uint16_t* lut) {
+                                                  uint64_t layer_elem, uint2 s) {
         if constexpr (OUT == ANSZP_OUT_U8) {
             __builtin_nontemporal_store(words2{s.x, s.y}, reinterpret_cast<words2*>(static_cast<uint8_t*>(p.out) + g));
         } else {
@@ -942,8 +941,8 @@ struct Flusher {
             for (int i = 0; i < 4; ++i) { sym[i] = (s.x >> (8 * i)) & 0xFFu; sym[4 + i] = (s.y >> (8 * i)) & 0xFFu; }
             if constexpr (kFolded) {
                 // Per-layer scale, bf16 out: float(q) - float(z) is exact, the product is rounded once, and two
-                // weights are rounded to bf16 by one instruction.  (A table of the 256 weights in LDS costs a
-                // look-up per symbol instead; the storing wavefronts then wait for LDS, which the decoding and
+                // weights are rounded to bf16 by one instruction.  (A table of the 256 weights in LDS, one look-up
+                // per symbol, was slower: the storing wavefronts then wait for LDS, which the decoding and
                 // expanding wavefronts keep busy.)
                 const float zf = static_cast<float>(lay.zero_point), sc = lay.scale;
                 auto weights = [&](uint32_t word, int i) {
@@ -951,7 +950,7 @@ struct Flusher {
                     const float b = sc * (static_cast<float>((word >> (16 * i + 8)) & 0xFFu) - zf);
                     return __builtin_bit_cast(uint32_t, __builtin_convertvector(floats2{a, b}, bf16s2));
                 };
-                (void)lut; (void)sym;
+                (void)sym;
                 __builtin_nontemporal_store(words4{weights(s.x, 0), weights(s.x, 1), weights(s.y, 0), weights(s.y, 1)},
                                             reinterpret_cast<words4*>(static_cast<uint16_t*>(p.out) + g));
             } else {
@@ -986,13 +985,9 @@ struct Flusher {
     }
     // One element (tail of a chunk).
     static __device__ __forceinline__ void store1(const DecodeParams& p, const anszp_layer_t& lay, uint64_t g,
-                                                  uint64_t layer_elem, uint32_t sym, const uint16_t* lut) {
-        if constexpr (kFolded) {
-            static_cast<uint16_t*>(p.out)[g] = lut[sym];
-        } else {
-            const float sc = PER_CHANNEL ? channel_scale(p, lay, layer_elem) : lay.scale;
-            store_weight<OUT>(p.out, g, sym, lay.zero_point, sc);
-        }
+                                                  uint64_t layer_elem, uint32_t sym) {
+        const float sc = PER_CHANNEL ? channel_scale(p, lay, layer_elem) : lay.scale;
+        store_weight<OUT>(p.out, g, sym, lay.zero_point, sc);
     }
 };
 
@@ -1225,10 +1220,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     constexpr uint32_t kRingElems = G::kRingElems;                 // LDS ring of decoded symbols (one byte each), per chunk
     constexpr uint32_t kPayloadWords = G::kPayloadWords;           // LDS window for one chunk's compressed words
     constexpr uint32_t kLogSlots = G::kLogSlots;                   // blocks in flight between decoding and expanding wavefront
-    // LDS: symbol -> bf16 (at address 0: twice a symbol is its entry's address) | table | SIMD of each wavefront |
+    // LDS: 512 bytes not in use | table (where the hand-written look-ups expect it) | SIMD of each wavefront |
     // per chunk: hand-over words, positions, log, compressed words | ring 0 | ring 1 (aligned to the size of both)
-    constexpr uint32_t kLutOff = 0u;
-    constexpr uint32_t kTableOff = kLutOff + 512u;
+    constexpr uint32_t kTableOff = 512u;
     constexpr uint32_t kSimdOff = kTableOff + kTableBytes;
     constexpr uint32_t kPipeOff = kSimdOff + 64u;
     constexpr uint32_t kTailWords = 8u;                             // zero words behind a chunk's last: a window of four words may start at the last
@@ -1247,14 +1241,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     static_assert(G::kWorkgroupsPerCu * kLdsBytes <= 160u * 1024u, "workgroups per CU");
     static_assert(kLdsBytes * 8u < (1u << 22), "bit positions count from the start of LDS");
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
-    uint16_t* const lds_lut = reinterpret_cast<uint16_t*>(lds + kLutOff);
     // hand-over words of a chunk: 0 blocks logged | 1, 2 the next block each expanding wavefront will take |
     // 3 no more blocks will be logged | 4..7 first element of the next slab each storing wavefront will take
     // (all ones where there is no such wavefront) | 8 a wait gave up
     enum { kLogged = 0, kNext0 = 1, kOver = 3, kStored0 = 4, kGaveUp = 8 };
     constexpr uint32_t kMaxStorers = 4u;
     static_assert(kExpanders == 2u, "hand-over words 1 and 2");
-    constexpr bool kFolded = Flusher<OUT, PER_CHANNEL>::kFolded;
     constexpr uint32_t kElemBytes = OUT == ANSZP_OUT_U8 ? 1u : (OUT == ANSZP_OUT_F32 ? 4u : 2u);
     constexpr uint32_t kTableLoads = ((2u << G::kTableLog) / 2u + kBlock - 1u) / kBlock;          // 16-byte loads per thread
     constexpr uint32_t kWordLoads = (kPayloadWords / 4u + kBlock - 1u) / kBlock;                  // per chunk
@@ -1336,13 +1328,12 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         if (!in0) report(p.status, ANSZP_ST_BAD_DESC);
         if (unit.count == 2u && !in1) report(p.status, ANSZP_ST_BAD_DESC);
     }
-    // What staging writes without having loaded anything: symbol -> bf16, hand-over words, the log slots' rows of
+    // What staging writes without having loaded anything: hand-over words, the log slots' rows of
     // bit positions, the positions, the rings' background.  With a prepared plan this is done while the loads
     // are in flight (the plan names the dominant symbol); without one the LDS it touches is still in use by
     // the search for the unit, and the dominant symbol is on its way with the table.
     const uint32_t storers = single ? 4u : 3u;           // storing wavefronts per chunk
     auto init_pipes = [&](uint32_t dominant) {
-        if (kFolded && tid < 256) lds_lut[tid] = static_cast<uint16_t>(bf16_rne(dequant(tid, lay.zero_point, lay.scale)));
         if (tid < (single ? 16u : 2u * 16u)) {            // hand-over words (of both chunks)
             const uint32_t q = tid / 16u, i = tid % 16u;
             uint32_t v = 0u;
@@ -1416,7 +1407,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     task = uniform(task);
     sub = uniform(sub);
 
-    // ---- stage: look-ahead entries, both chunks' compressed words, symbol -> bf16, ring background, hand-over words
+    // ---- stage: look-ahead entries, both chunks' compressed words, ring background, hand-over words
     {
         // every thread stores what it loaded, to the clamped index it loaded from (threads past the
         // end repeat the last row)
@@ -1478,8 +1469,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         *reinterpret_cast<uint2*>(q) = make_uint2(bg4, bg4);
         *reinterpret_cast<uint2*>(q + kSlab / 2u) = make_uint2(bg4, bg4);
         const uint32_t first = first_elem + lane * 8u;
-        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first, layer_elem0 + first, lo, lds_lut);
-        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u, hi, lds_lut);
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first, layer_elem0 + first, lo);
+        Flusher<OUT, PER_CHANNEL>::store8(p, lay, c.out_offset + first + kSlab / 2u, layer_elem0 + first + kSlab / 2u, hi);
     };
 
     if (task == kStore) {
@@ -1529,7 +1520,7 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         const uint32_t rest = n / kSlab * kSlab;
         if ((rest / kSlab) % storers == sub)
             for (uint32_t j = rest + lane; j < n; j += kWave)
-                Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & ring_mask], lds_lut);
+                Flusher<OUT, PER_CHANNEL>::store1(p, lay, c.out_offset + j, layer_elem0 + j, ring8[j & ring_mask]);
         return;
     }
 
@@ -1671,8 +1662,9 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
         return v;
     };
     static_assert(kLogged == 0 && kNext0 == 1 && kExpanders == 2u && kStored0 == 4 && kMaxStorers == 4u, "the hand-over words as the decoding wavefront reads them");
-    // A block of 8 look-ups, hand-scheduled: a lone wavefront issues one instruction every 6-8 cycles, and
-    // what a look-up costs is the LDS round trip plus the instructions between its arrival and the next read:
+    // A block of 8 look-ups, hand-scheduled.  A look-up costs the LDS round trip plus the two instructions
+    // between an entry's arrival and the next read; what else is issued while the wavefront waits for an
+    // entry is free (up to a dozen instructions or so):
     //   v = r >> (31 - T)            the next T+1 stream bits, r = the window's first word bit-reversed
     //   address' = 8 v + 8 base      Sec. II-A: newX + bits, plus the peeked bit
     //   e' = table[address'];  log[k] = e (its upper half);  window >>= T (funnel shifts);  r = bitrev(w0)
@@ -1683,9 +1675,8 @@ __device__ __forceinline__ void decode_lookahead(const DecodeParams& p) {
     // first 12 j + 1 bits matter, so register m is shifted while 12 j + 1 > 32 m (a register that is no
     // longer shifted goes stale; what it feeds into its lower neighbour lies beyond that reach).  A block
     // ends by logging where each lane's next look-up starts and the lane's bit position tagged with the
-    // block's number (a lane that sat the block out keeps an older tag), publishing the new count of
-    // blocks, reloading the words of the lanes that took part and recomputing who may join the next block from the words
-    // the other wavefronts publish (read at the start of the block, so their latency is hidden).
+    // block's number (a lane that sat the block out keeps an older tag), reloading the words of the lanes
+    // that took part and deciding who may run the next block from the words the other wavefronts publish.
 #define ANSZP_SHIFT_W0 "v_alignbit_b32 v28, v29, v28, v35\n"
 #define ANSZP_SHIFT_W1 ANSZP_SHIFT_W0 "v_alignbit_b32 v29, v30, v29, v35\n"
 #define ANSZP_SHIFT_W2 ANSZP_SHIFT_W1 "v_alignbit_b32 v30, v31, v30, v35\n"
