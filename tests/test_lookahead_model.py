@@ -10,6 +10,9 @@ tables and containers under a random scheduler.  The kernel's invariants are ass
   * a log slot is written only after both expanding wavefronts have moved past the block that used it before;
   * the positions the storing wavefronts see (the smaller of the two rows) never run ahead of what is expanded;
   * every wait ends: some wavefront can always make progress until the chunk is complete.
+
+The decoding wavefront publishes a block late (beside the first look-up of the next block, or when it starts to
+wait, or when it is done): the other wavefronts see the count of blocks as published, not as logged.
 """
 import random
 
@@ -71,8 +74,9 @@ class Chunk:
         self.pos = list(self.first_bit)
         self.ne = [k if k < self.n else self.lane_end[k] for k in range(N)]
         self.idx = [2 * int(hdr[k] & (L2 // 2 - 1)) + self.peek(self.pos[k], 1) for k in range(N)]
-        self.logged, self.over = 0, False
+        self.logged, self.published, self.over = 0, 0, False
         self.seen_stored, self.seen_next = 0, 0            # hand-over words as read when the previous block began
+                                                           # (the kernel reads them later in that block: newer values are only larger)
         self.log = [None] * slots
         self.bit_row = [[0xFFFFFFFF] * N for _ in range(slots)]
         # expanding wavefronts
@@ -99,6 +103,8 @@ class Chunk:
         if self.over:
             return False
         N = self.N
+        newly_published = self.published != self.logged
+        self.published = self.logged                        # the block before: published whatever this pass does next
         if not any(self.ne[k] < self.lane_end[k] for k in range(N)):
             self.over = True
             return True
@@ -108,7 +114,7 @@ class Chunk:
         if not any(joins) or self.logged - self.seen_next >= self.slots:
             progress = (self.seen_stored, self.seen_next) != (stored_now, next_now)
             self.seen_stored, self.seen_next = stored_now, next_now
-            return progress
+            return progress or newly_published
         # the slot is free: both expanding wavefronts are past the block that used it
         assert self.logged - min(self.next) < self.slots
         slot = self.logged % self.slots
@@ -142,7 +148,7 @@ class Chunk:
         if self.done_x[e]:
             return False
         b = self.next[e]
-        if self.logged <= b:
+        if self.published <= b:
             if self.over:
                 self.done_x[e] = True
                 return True
@@ -186,7 +192,7 @@ class Chunk:
     def store(self, s):
         if self.done_s[s]:
             return False
-        last_pass = self.over and self.logged <= min(self.next)
+        last_pass = self.over and self.published <= min(self.next)
         nxt = [0xFFFFFFFF] * self.N if last_pass else [min(a, b) for a, b in zip(self.prog[0], self.prog[1])]
         # the smaller of the two rows never runs ahead of what both wavefronts have expanded
         moved = False
