@@ -1198,20 +1198,21 @@ __global__ __launch_bounds__(1024) void plan_order(PlanRecord* plan, uint32_t n)
 
 // ---------------------------------------------------------------------------------------------
 // The look-ahead kernel.  One workgroup = one unit (one or two chunks of a layer), twelve wavefronts:
-// all stage, then eight keep a task each, four per chunk:
-//   decode   lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
-//            table) through the look-ahead entries, in blocks of 8 look-ups with no per-step checks,
-//            and logs 16 bits of every entry it passes;
-//   expand   turns logged entries into symbols in the chunk's LDS ring (an entry stands for c symbols:
-//            c-1 copies of the dominant symbol, which the ring holds as background, then its own),
-//            publishes how far every stream has got, and checks every stream's end: the entry that
-//            holds the stream's last symbol must end with it and arrive in state 0 (entries never pass
-//            through state 0), having read the stream's words and no more;
-//   store x2 move finished slabs of the ring to global memory, even and odd slabs, 16 bytes per lane.
+// all stage, then up to seven per chunk keep a task:
+//   decode    (one) lane k walks the automaton of stream k (Sec. III-B: a vector of states sharing one
+//             table) through the look-ahead entries, in blocks of 8 look-ups with no per-step checks,
+//             and logs 16 bits of every entry it passes and where every lane stands when a block begins;
+//   expand    (two, taking the logged blocks in turn) turn logged entries into symbols in the chunk's LDS
+//             ring (an entry stands for c symbols: c-1 copies of the dominant symbol, which the ring holds
+//             as background, then its own), publish how far every stream has got, and check every stream's
+//             end: the entry that holds the stream's last symbol must end with it and arrive in state 0
+//             (entries never pass through state 0), having read the stream's words and no more;
+//   store     (four for a single chunk, three per chunk of a pair) move finished slabs of the ring to
+//             global memory, every fourth or third slab each, 16 bytes per lane and store.
 // A lane joins a block while its stream is unfinished and the ring has room for 8 entries of 8 symbols
 // (what the storing wavefronts have stored decides); a stream that ends inside a block goes on through
-// whatever follows it: the table keeps every index in range, the window of compressed words is
-// clamped to the chunk, and symbols beyond the chunk's last land in ring slots nobody reads again.
+// whatever follows it: the table keeps every index in range, what it reads behind the chunk's words
+// stays inside LDS, and symbols beyond the chunk's last land in ring slots nobody reads again.
 // Hand-overs go through LDS words; LDS performs a wavefront's accesses in order, so a reader that
 // sees a count sees everything written before it.  Every wait is bounded.
 template <int OUT, bool PER_CHANNEL, class G>
