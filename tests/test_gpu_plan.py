@@ -115,3 +115,28 @@ def test_launches_that_need_no_plan(orc):
     assert d.read_status() == (0, 0)
     assert np.array_equal(B.bits_of(out)[:w.numel], expect)
     assert bool((plan == 0x5A).all())
+
+
+@pytest.mark.parametrize("name", ["config2", "config3"])
+def test_many_launches_all_give_the_oracle_s_bits(orc, name):
+    """The hand-overs between a chunk's wavefronts depend on timing; 300 launches in a row (planned and not, back
+    to back, so that launches overlap each other's tails) must each leave exactly the oracle's bits and clean
+    status words."""
+    w = _workloads()[name]
+    c = oracle_encode(orc, w)
+    _, expect = oracle_expected(orc, c, w)
+    d = B.to_device(host_from_oracle(c, w))
+    out = B.alloc_out(d)
+    args = B.decode_args(d, out)
+    plan = B.plan_decode(args)
+    B.decode_planned_raw(args, plan)
+    assert np.array_equal(B.bits_of(out)[:w.numel], expect)
+    want = out.view(torch.int16).clone()
+    for i in range(300):
+        out.view(torch.uint8).fill_(0x5A)
+        if i % 3 == 2:
+            B.decode_raw(args)
+        else:
+            B.decode_planned_raw(args, plan)
+        assert bool(torch.equal(out.view(torch.int16), want)), f"launch {i} differs"
+    assert d.read_status() == (0, 0)
