@@ -1138,7 +1138,8 @@ struct PlanRecord {
     anszp_chunk_t c0, c1;
     anszp_layer_t lay;                           // of the unit's chunks (zero when neither is in bounds)
     uint32_t dominant;                           // symbol of the layer's last state: the dominant symbol if there is one
-    uint32_t unused[3];
+    uint32_t chain;                              // look-ups expected of a stream of the unit's longer chunk, times the streams (0: not known)
+    uint32_t unused[2];
 };
 static_assert(sizeof(PlanRecord) == 128, "one record per workgroup, 128 bytes");
 constexpr uint32_t kPlanTag = 0x414E5300u;
@@ -1148,16 +1149,35 @@ __global__ __launch_bounds__(kBlock) void plan_units(DecodeParams p, PlanRecord*
     __shared__ uint64_t masks[kPairLevels * (kPairScanRounds * kBlock / kWave) + 16u];
     anszp_chunk_t c0, c1;
     const Unit unit = find_unit<kBlock>(p, unit_of_workgroup(blockIdx.x), max(p.n_cus, 1u) * G::kWorkgroupsPerCu, G::kPayloadWords, masks, c0, c1);
+    const bool ok0 = unit.count != 0u && chunk_in_bounds(p, c0), ok1 = unit.count == 2u && chunk_in_bounds(p, c1);
+    const uint32_t layer_id = ok0 ? c0.layer_id : c1.layer_id;
+    const uint32_t* const triples = p.tables + size_t(ok0 || ok1 ? layer_id : 0u) * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
+    const uint32_t L = 1u << p.table_log;
+    // How long a stream's chain of look-ups will be: an entry of the look-ahead table ends with a symbol that is not
+    // the dominant one (or with a dominant one that had to read bits), so of n symbols about n * (1 - P(dominant))
+    // cost a look-up each.  P(dominant) is the share of the table's states that carry the dominant symbol (Sec. II-A:
+    // a symbol's states are its normalised frequency).  The stream words a chunk has say less: a layer of few
+    // quantisation levels has short codes and as many look-ups.
+    __shared__ uint32_t others;
+    if (threadIdx.x == 0) others = 0u;
+    __syncthreads();
+    if (ok0 || ok1) {
+        const uint32_t dominant = triples[L - 1u] >> 24;
+        uint32_t mine = 0;
+        for (uint32_t i = threadIdx.x; i < L; i += kBlock) mine += (triples[i] >> 24) != dominant ? 1u : 0u;
+        if (mine) atomicAdd(&others, mine);
+    }
+    __syncthreads();
     if (threadIdx.x != 0) return;
     PlanRecord r = {};
     r.tag = kPlanTag + G::kTag; r.n_chunks = p.n_chunks; r.first = unit.first; r.count = unit.count;
     if (unit.count != 0u) {
         r.c0 = c0; r.c1 = c1;
-        const bool ok0 = chunk_in_bounds(p, c0), ok1 = unit.count == 2u && chunk_in_bounds(p, c1);
         if (ok0 || ok1) {
-            const uint32_t layer_id = ok0 ? c0.layer_id : c1.layer_id;
             r.lay = p.layers[layer_id];
-            r.dominant = p.tables[size_t(layer_id) * table_stride_words(p.table_log) + table_triples_offset(p.table_log) + (1u << p.table_log) - 1u] >> 24;
+            r.dominant = triples[L - 1u] >> 24;
+            const uint32_t longer = max(ok0 ? c0.n_symbols : 0u, ok1 ? c1.n_symbols : 0u);
+            r.chain = static_cast<uint32_t>(min((uint64_t(longer) * others) >> p.table_log, uint64_t(0x0FFFFFFFu)));
         }
     }
     plan[gridDim.x + blockIdx.x] = r;              // (the second half of the plan's memory: plan_order puts the records in place)
@@ -1165,7 +1185,7 @@ __global__ __launch_bounds__(kBlock) void plan_units(DecodeParams p, PlanRecord*
 
 // The records in the order the workgroups should take them: the chip starts workgroups in the order of their
 // numbers, over about a microsecond, and the launch ends with its slowest unit, so the units with the longest
-// chains (most stream words per chunk; two chunks in one workgroup run slower than one) go first.  Sorted units
+// chains (as plan_units expects them; two chunks in one workgroup run slower than one) go first.  Sorted units
 // keep the mapping to the dies: units of one layer are alike and stay neighbours.  One workgroup; launches of
 // more than kPlanOrderMax workgroups keep the order of the descriptors.
 constexpr uint32_t kPlanOrderMax = 8192u;
@@ -1180,8 +1200,8 @@ __global__ __launch_bounds__(1024) void plan_order(PlanRecord* plan, uint32_t n)
     for (uint32_t i = tid; i < n; i += 1024u) {
         const PlanRecord& r = raw[i];
         uint32_t c = 0;
-        if (r.count == 1u) c = 4u * min(r.c0.payload_words, 0x0FFFFFFFu);
-        else if (r.count == 2u) c = 5u * min(max(r.c0.payload_words, r.c1.payload_words), 0x0FFFFFFFu);
+        if (r.count == 1u) c = 4u * r.chain;
+        else if (r.count == 2u) c = 5u * r.chain;
         cost[i] = c;
     }
     __syncthreads();
