@@ -37,8 +37,9 @@ constexpr uint32_t kThreads = 768;
 constexpr uint32_t kWaves = kThreads / kWave;
 constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
 constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
-constexpr uint32_t kStageWords = 1280;      // per wavefront: LDS room for one chunk's compressed words (a chunk of
-                                            // 4608 8-bit symbols in 64 streams needs at most 1152 + 64)
+constexpr uint32_t kStageWords = 384;       // per wavefront: LDS room for one chunk's compressed words (2.6 bit per
+                                            // weight at 4608 symbols; a larger chunk is read from global memory)
+constexpr uint32_t kMaxMine = (4u * kRows + kWaves - 1u) / kWaves;   // chunks of a panel one wavefront may have to decode
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float floatx4;
@@ -64,6 +65,7 @@ struct ConvParams {
     // NHWC: pixel = channels, block = 8;  blocks of 8 channels: pixel = 8, block = 8 * pixels per image
     uint32_t x_pixel, x_block, y_pixel, y_block;
     uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles;   // n_mtiles: panels of 16 * MR rows
+    uint32_t k_magic;                                     // floor(2^32 / K) + 1: i / K = mulhi(i, k_magic) for i * K < 2^32
     uint32_t pixels_per_split, block_pixels;              // multiples of 16: the pixels of a workgroup; of one block (<= 64)
 };
 
@@ -90,114 +92,96 @@ __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* tot
     return s - v;
 }
 
-// One chunk, one look-up per symbol (Sec. II-A; Sec. III-B: one lane per stream), symbols into the
-// LDS panel: symbol i of the chunk belongs to panel row i / K, column i % K.  Returns error bits.
-// The chunk's words are first copied to `stage` (LDS, this wavefront's own) with 16-byte loads when they
-// fit, so that the decode loop waits for no global load; a larger chunk is read word by word in place.
-// P16: the panel holds bf16 values q - z (two bytes per weight) instead of the symbols q.
+// What a wavefront fetches of a chunk before it decodes it: the stream headers (lane k: stream k), the chunk's
+// words as two 16-byte pieces per lane (kStageWords words in all) and the up to three words behind the last
+// whole piece.
+struct ChunkData {
+    uint32_t hdr;
+    words4 q0, q1;
+    uint32_t tail;
+};
+
+// A chunk's descriptor as the wavefront uses it (uniform values), checked against the layer and the buffers.
+struct ChunkDesc {
+    uint32_t n_symbols, payload_words, stream_offset;
+    uint64_t payload_offset;
+    bool ok, staged;             // staged: the chunk's words (and two zero words behind them) fit the wavefront's LDS room
+};
+
+// One chunk into the LDS panel: symbol i of the chunk belongs to panel row i / K, column i % K.  One lane per
+// stream (Sec. III-B) walks the automaton of Sec. II-A through the table's look-ahead entries (anszp_layout.h):
+// one look-up stands for up to eight symbols, all but the last the layer's dominant symbol, which the panel
+// already holds everywhere (the caller fills it), so a look-up writes one panel element.  The entry of index
+// 2X + b and the two stream words around the lane's bit position are read together; with T the bits the entry
+// consumes, the next index is base + (the next T + 1 stream bits, first bit most significant) and the bit
+// position moves on by T.  Returns error bits.
+// The chunk's words were fetched into `d` (16-byte loads issued long before) and go to `stage` (LDS, this
+// wavefront's own) when they fit, so that the loop waits for no global load; a larger chunk is read word by word
+// in place.  P16: the panel holds bf16 values q - z (two bytes per weight) instead of the symbols q.
 template <bool P16>
-__device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const anszp_chunk_t& c, const uint32_t* table,
-                                          uint32_t* stage, uint8_t* rows, uint32_t lane, int32_t zero_point) {
+__device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& c, const ChunkData& d, const uint8_t* ahead,
+                                          uint32_t ahead_mask, uint32_t* stage, uint8_t* rows, uint32_t lane, int32_t zero_point) {
     const uint32_t N = p.n_streams;
     const uint32_t L = 1u << p.table_log;
-    const uint32_t hdr = lane < N ? p.stream_hdr[c.stream_offset + lane] : 0u;
-    uint32_t X = hdr & (L - 1u);
-    const uint32_t n_words = hdr >> 16;
+    const uint32_t X0 = d.hdr & (L - 1u);
+    const uint32_t n_words = d.hdr >> 16;
     uint32_t total_words;
     const uint32_t first_word = wave_exclusive_sum(n_words, &total_words);
-    const uint32_t len = (lane < N && c.n_symbols > lane) ? (c.n_symbols - lane + N - 1u) / N : 0u;
     uint32_t err = (total_words != c.payload_words) ? ANSZP_ST_BAD_DESC : 0u;
 
     const uint32_t* words = p.payload + c.payload_offset;
     const uint32_t word_limit = c.payload_words;      // reads beyond the chunk see zeros
-    const bool staged = word_limit + 2u <= kStageWords;         // two zero words behind the chunk's own
-    if (staged) {
-        // all loads first (from clamped, always valid addresses; chunks start on 16 bytes), then the stores:
-        // a load and its store under one condition would be waited for one after the other
-        constexpr uint32_t kLoads = kStageWords / (4u * kWave);
-        static_assert(kLoads * 4u * kWave == kStageWords, "whole 16-byte loads per lane");
+    if (c.staged) {
         const uint32_t quads = word_limit >> 2;
-        const words4* qsrc = reinterpret_cast<const words4*>(quads ? words : p.payload);
-        const uint32_t q_last = quads ? quads - 1u : 0u;
-        words4 v[kLoads];
-#pragma unroll
-        for (uint32_t u = 0; u < kLoads; ++u) v[u] = p.payload_words >= 4u ? qsrc[min(lane + u * kWave, q_last)] : words4{0u, 0u, 0u, 0u};
+        if (lane < quads) *reinterpret_cast<words4*>(stage + 4u * lane) = d.q0;
+        if (lane + kWave < quads) *reinterpret_cast<words4*>(stage + 4u * (lane + kWave)) = d.q1;
         const uint32_t tail_at = (quads << 2) + lane;
-        const uint32_t tail = (lane < 3u && tail_at < word_limit) ? words[tail_at] : 0u;
-#pragma unroll
-        for (uint32_t u = 0; u < kLoads; ++u)
-            if (lane + u * kWave < quads) *reinterpret_cast<words4*>(stage + 4u * (lane + u * kWave)) = v[u];
-        if (lane < 3u && tail_at < word_limit) stage[tail_at] = tail;
+        if (lane < 3u && tail_at < word_limit) stage[tail_at] = d.tail;
         if (lane < 2u) stage[word_limit + lane] = 0u;                // what a stream reads beyond the chunk
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");       // LDS serves a wavefront's accesses in order
         __builtin_amdgcn_wave_barrier();
     }
-    const uint32_t steps = (c.n_symbols + N - 1u) / N;
-    uint32_t row = lane / p.K, col = lane % p.K;      // of this lane's next symbol
-    const uint32_t row_step = N / p.K, col_step = N % p.K;
-    auto put = [&](uint32_t e) {                      // the entry's symbol into the panel, then on to the lane's next place
-        if constexpr (P16) {                          // an integer of at most 8 bits: the upper half of its binary32 form is exact
-            const float w = static_cast<float>(int32_t(e >> 24) - zero_point);
-            reinterpret_cast<uint16_t*>(rows)[row * p.row_stride + col] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
-        } else {
-            rows[row * p.row_stride + col] = static_cast<uint8_t>(e >> 24);
-        }
-        row += row_step;
-        col += col_step;
-        if (col >= p.K) { col -= p.K; ++row; }
-    };
-    if (staged) {
-        // The chunk's words are in LDS: a lane keeps its bit position and reads the two words around it at every
-        // step, together with the table entry, so that a step is two LDS round trips' worth of latency and
-        // about two dozen instructions (the step's bits are stored most significant first: bit-reverse the
-        // window and take its top nb_bits).
-        uint32_t bit = first_word << 5;
-        for (uint32_t t = 0; t < steps; ++t) {
-            if (t < len) {
+    const uint32_t n = lane < N ? c.n_symbols : 0u;   // a lane without a stream never runs
+    const uint32_t first_bit = first_word << 5;
+    uint32_t bit = first_bit;
+    uint32_t elem = lane;                             // the chunk element of the lane's next symbol
+    auto walk = [&](auto word_at) {
+        uint32_t at = ((2u * X0 + (word_at(min(first_word, word_limit)) & 1u)) * 8u) & ahead_mask;   // entry 2 X0 + first stream bit
+        while (__ballot(elem < n) != 0) {
+            if (elem < n) {
                 const uint32_t wi = min(bit >> 5, word_limit);
-                const uint32_t w0 = stage[wi], w1 = stage[wi + 1u];
-                const uint32_t e = table[X];
-                const uint32_t nb = min((e >> 16) & 0xFFu, 31u);
+                const uint32_t w0 = word_at(wi), w1 = word_at(wi + 1u);
+                const words2 e = *reinterpret_cast<const words2*>(ahead + at);
                 const uint32_t window = __builtin_amdgcn_alignbit(w1, w0, bit);
-                const uint32_t bits = (__brev(window) >> 1) >> (31u - nb);      // none: 0
-                X = ((e & 0xFFFFu) + bits) & (L - 1u);
-                bit += nb;
-                put(e);
+                const uint32_t v = __brev(window) >> (e.x & 31u);           // the next T + 1 stream bits
+                at = (e.y + 8u * v) & ahead_mask;
+                bit += (e.x >> 24) & 15u;
+                elem += ((e.x >> 28) & 7u) * N;                             // past the entry's dominant symbols
+                if (elem < c.n_symbols) {
+                    const uint32_t row = p.K > 1u ? __umulhi(elem, p.k_magic) : elem;
+                    const uint32_t where = elem + row * (p.row_stride - p.K);
+                    const uint32_t sym = (e.x >> 16) & 0xFFu;
+                    if constexpr (P16) {              // an integer of at most 8 bits: the upper half of its binary32 form is exact
+                        const float w = static_cast<float>(int32_t(sym) - zero_point);
+                        reinterpret_cast<uint16_t*>(rows)[where] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
+                    } else {
+                        rows[where] = static_cast<uint8_t>(sym);
+                    }
+                }
+                elem += N;
             }
         }
+        // a stream ends where an entry ends, in state 0 (the index of the next entry is 2 X + peeked bit),
+        // having read exactly its words
         if (lane < N) {
-            if (X != 0) err |= ANSZP_ST_BAD_STATE;
-            if (((bit - (first_word << 5)) + 31u) >> 5 != n_words) err |= ANSZP_ST_BAD_LENGTH;
+            const uint32_t len = c.n_symbols > lane ? (c.n_symbols - lane + N - 1u) / N : 0u;
+            if (elem != lane + len * N) err |= ANSZP_ST_BAD_LENGTH;
+            if ((at >> 4) != 0u) err |= ANSZP_ST_BAD_STATE;
+            if (((bit - first_bit) + 31u) >> 5 != n_words) err |= ANSZP_ST_BAD_LENGTH;
         }
-        return wave_or(err);
-    }
-    auto word_at = [&](uint32_t i) { return i < word_limit ? words[i] : 0u; };
-    uint32_t next_word = first_word;
-    uint64_t buf = 0;
-    uint32_t have = 0;
-    uint32_t ahead = word_at(first_word);             // the word after those in buf, requested one refill early
-    for (uint32_t t = 0; t < steps; ++t) {
-        if (t < len) {
-            const uint32_t e = table[X];
-            const uint32_t nb = (e >> 16) & 0xFFu;
-            if (have < nb) {
-                buf |= uint64_t(ahead) << have;
-                have += 32;
-                ++next_word;
-                ahead = word_at(next_word);
-            }
-            const uint32_t low = static_cast<uint32_t>(buf) & ((1u << nb) - 1u);
-            const uint32_t bits = nb ? __brev(low) >> (32u - nb) : 0u;      // first bit read is the top bit
-            buf >>= nb;
-            have -= nb;
-            X = ((e & 0xFFFFu) + bits) & (L - 1u);
-            put(e);
-        }
-    }
-    if (lane < N) {
-        if (X != 0) err |= ANSZP_ST_BAD_STATE;
-        if (next_word - first_word != n_words) err |= ANSZP_ST_BAD_LENGTH;
-    }
+    };
+    if (c.staged) walk([&](uint32_t i) { return stage[i]; });
+    else walk([&](uint32_t i) { return i < word_limit ? words[i] : 0u; });
     return wave_or(err);
 }
 
@@ -214,73 +198,252 @@ __device__ __forceinline__ bf16x8 weights_of(words2 q, float z) {
     return __builtin_bit_cast(bf16x8, w);
 }
 
+// The accumulators of one block of up to 64 pixels times the scale(s), to y.  D operand layout: lane holds
+// column lane % 16, rows 4 * (lane / 16) + 0..3 of each row tile: four consecutive output channels.
+template <uint32_t MR>
+__device__ __forceinline__ void store_tiles(const ConvParams& p, const anszp_layer_t& lay, uint32_t mtile, uint32_t kg,
+                                            const floatx4 (&acc)[MR][4], const bool (&valid)[4], const uint32_t (&out_at)[4]) {
+    const bool per_channel = lay.channel_len != 0;
+#pragma unroll
+    for (uint32_t m = 0; m < MR; ++m) {
+        const uint32_t o = (mtile * MR + m) * kRows + 4u * kg;
+        float sc[4];
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) {
+            sc[i] = lay.scale;
+            if (per_channel) {
+                const uint64_t ch = lay.scales_offset + o + i;
+                sc[i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (valid[q]) {
+                const floatx4 out = {acc[m][q][0] * sc[0], acc[m][q][1] * sc[1], acc[m][q][2] * sc[2], acc[m][q][3] * sc[3]};
+                const uint32_t at = out_at[q] + (o >> 3) * p.y_block + (o & 7u);
+                if (p.y_bf16) {                                   // round to nearest even (v_cvt_pk_bf16_f32)
+                    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                    const bf16x4 r = {static_cast<__bf16>(out[0]), static_cast<__bf16>(out[1]),
+                                      static_cast<__bf16>(out[2]), static_cast<__bf16>(out[3])};
+                    *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(p.y) + at) = r;
+                } else {
+                    *reinterpret_cast<floatx4*>(static_cast<float*>(p.y) + at) = out;
+                }
+            }
+        }
+    }
+}
+
 // MR: MFMA row tiles per workgroup.  Every wavefront multiplies all 16 * MR panel rows with its columns, so
 // an activation vector loaded once feeds MR MFMAs.
 // P16: the panel is kept as bf16 (short rows: K <= 576), so that the contraction reads its A operands as they are.
 // KIND: how the contraction addresses the activations.
 enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecutive k lie under one kernel tap
        kPointwise = 1,   // as kTaps with a 1 x 1 kernel and no padding: one pixel per column, nothing outside the image
-       kGeneric = 2 };   // any number of input channels (NHWC): every activation is addressed on its own
-template <int KIND, uint32_t MR, bool P16>
+       kGeneric = 2,     // any number of input channels (NHWC): every activation is addressed on its own
+       kPointwiseRing = 3 };   // as kPointwise with input channels a multiple of 32 * D: D steps' activations in flight
+// D (kPointwiseRing only): steps of 32 input channels whose activation loads are in flight at any time.
+template <int KIND, uint32_t MR, bool P16, uint32_t D>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    uint32_t* table = reinterpret_cast<uint32_t*>(lds);
-    const uint32_t table_bytes = max(4u << p.table_log, 16u);      // what follows stays 16-byte aligned
-    uint32_t* stage = reinterpret_cast<uint32_t*>(lds + table_bytes);
-    uint8_t* panel = lds + table_bytes + kWaves * kStageWords * 4u;
+    const uint32_t L = 1u << p.table_log;
+    const uint32_t ahead_bytes = 16u * L;                         // 2 L look-ahead entries of two words
+    uint8_t* ahead = lds;
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds + ahead_bytes);
+    uint8_t* panel = lds + ahead_bytes + kWaves * kStageWords * 4u;
     constexpr uint32_t kElem = P16 ? 2u : 1u;                     // bytes per panel element
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t mtile = blockIdx.x % p.n_mtiles, split = blockIdx.x / p.n_mtiles;
-    const uint32_t L = 1u << p.table_log;
+    // The chip hands consecutive workgroups to its eight dies in turn and every die has its own L2: workgroup
+    // blockIdx.x is the (blockIdx.x / 8)-th of die blockIdx.x % 8.  Numbering the workgroups die after die, the
+    // panels of one range of pixels follow each other on one die, whose L2 then fetches those activations once
+    // for all of them.  (Any one-to-one numbering is correct; this one is for the cache.)
+    constexpr uint32_t kDies = 8;
+    const uint32_t per_die = gridDim.x / kDies, extra = gridDim.x % kDies, die = blockIdx.x % kDies;
+    const uint32_t unit = die * per_die + min(die, extra) + blockIdx.x / kDies;
+    const uint32_t mtile = unit % p.n_mtiles, split = unit / p.n_mtiles;
 
-    // ---- phase 1: the layer's triples (Sec. II-A) into LDS, then this workgroup's 16 weight rows
-    const uint32_t* src = p.tables + p.layer_id * table_stride_words(p.table_log) + table_triples_offset(p.table_log);
-    // every global read that depends only on the kernel's arguments is issued before any is waited for:
-    // the table (two 16-byte rows per thread, clamped), the layer's quantizer, this wavefront's first chunk
-    const uint32_t t_rows = L >> 2;
-    const words4* tsrc = reinterpret_cast<const words4*>(src);
-    const uint32_t t_last = t_rows ? t_rows - 1u : 0u;
-    static_assert((1u << ANSZP_MAX_TABLE_LOG) / 4u <= 2u * kThreads, "two table rows per thread");
-    words4 tv0 = {0u, 0u, 0u, 0u}, tv1 = {0u, 0u, 0u, 0u};
-    if (t_rows) { tv0 = tsrc[min(tid, t_last)]; tv1 = tsrc[min(tid + kThreads, t_last)]; }     // uniform condition
-    const uint32_t small = (!t_rows && tid < L) ? src[tid] : 0u;                                // a 2-state table
+    // ---- phase 1: the layer's look-ahead entries into LDS, then this workgroup's 16 * MR weight rows.
+    // Every global read that depends only on the kernel's arguments is issued before any is waited for: the
+    // descriptors of this wavefront's chunks (lane i: its i-th chunk, panel chunk wave + i * kWaves), the layer's
+    // quantizer, the triple of the last state (it carries the layer's dominant symbol if there is one), the
+    // table (one 16-byte row per state: the entries for both values of the peeked bit; up to six rows per thread).
+    const uint32_t cpp = p.chunks_per_panel;
+    const anszp_chunk_t* panel_chunks = p.chunks + uint64_t(mtile) * cpp;
+    const anszp_chunk_t held = panel_chunks[min(wave + min(lane, kMaxMine - 1u) * kWaves, cpp - 1u)];
+    const uint32_t* table_src = p.tables + p.layer_id * table_stride_words(p.table_log);
     const anszp_layer_t lay = p.layers[p.layer_id];
-    const anszp_chunk_t first_chunk = p.chunks[uint64_t(mtile) * p.chunks_per_panel + min(wave, p.chunks_per_panel - 1u)];
-    if (t_rows) {
-        reinterpret_cast<words4*>(table)[min(tid, t_last)] = tv0;
-        reinterpret_cast<words4*>(table)[min(tid + kThreads, t_last)] = tv1;
-    } else if (tid < L) {
-        table[tid] = small;
+    const uint32_t top = table_src[table_triples_offset(p.table_log) + L - 1u];
+    constexpr uint32_t kTableLoads = ((1u << ANSZP_MAX_TABLE_LOG) + kThreads - 1u) / kThreads;
+    const words4* tsrc = reinterpret_cast<const words4*>(table_src + table_lookahead_offset(p.table_log));
+    words4 tv[kTableLoads];
+#pragma unroll
+    for (uint32_t u = 0; u < kTableLoads; ++u) tv[u] = tsrc[min(tid + u * kThreads, L - 1u)];
+
+    auto desc_of = [&](uint32_t i) {                              // this wavefront's i-th chunk (i uniform)
+        ChunkDesc c;
+        const uint32_t layer_id = __builtin_amdgcn_readlane(held.layer_id, i);
+        c.n_symbols = __builtin_amdgcn_readlane(held.n_symbols, i);
+        c.payload_words = __builtin_amdgcn_readlane(held.payload_words, i);
+        c.stream_offset = __builtin_amdgcn_readlane(held.stream_offset, i);
+        c.payload_offset = uint64_t(uint32_t(__builtin_amdgcn_readlane(uint32_t(held.payload_offset), i))) |
+                           uint64_t(uint32_t(__builtin_amdgcn_readlane(uint32_t(held.payload_offset >> 32), i))) << 32;
+        c.ok = layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K && (c.payload_offset & 3u) == 0 &&
+               c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
+               uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
+        c.staged = c.payload_words + 2u <= kStageWords;           // two zero words behind the chunk's own
+        return c;
+    };
+    auto fetch = [&](const ChunkDesc& c, ChunkData& d) {          // from clamped, always valid addresses
+        d.hdr = 0u;
+        d.q0 = d.q1 = words4{0u, 0u, 0u, 0u};
+        d.tail = 0u;
+        if (!c.ok) return;                                        // uniform
+        if (lane < p.n_streams) d.hdr = p.stream_hdr[c.stream_offset + lane];
+        const uint32_t quads = c.payload_words >> 2;
+        if (c.staged && c.payload_words) {
+            const uint32_t* words = p.payload + c.payload_offset;
+            if (quads) {
+                d.q0 = reinterpret_cast<const words4*>(words)[min(lane, quads - 1u)];
+                d.q1 = reinterpret_cast<const words4*>(words)[min(lane + kWave, quads - 1u)];
+            }
+            const uint32_t tail_at = (quads << 2) + lane;
+            if (lane < 3u && tail_at < c.payload_words) d.tail = words[tail_at];
+        }
+    };
+    const uint32_t n_mine = wave < cpp ? (cpp - wave + kWaves - 1u) / kWaves : 0u;
+    ChunkDesc cur{};
+    ChunkData cur_data{};
+    if (n_mine) {
+        cur = desc_of(0u);
+        fetch(cur, cur_data);
     }
-    if constexpr (P16) {
-        // A panel of bf16 values is read beyond what decoding writes: the columns from K to the row's end,
-        // and up to 64 bytes behind the last row (the last 32 k of a row tile or of a kernel tap).  Those
-        // products meet activations that are zero, but whatever an earlier kernel left in LDS may read as
-        // Inf or NaN, and 0 * Inf is NaN: the whole panel and the 64 bytes behind it start as zeros.
-        // (A panel of symbol bytes needs none of this: any byte is a finite weight.)
-        const uint32_t panel_words = (kRows * MR * p.row_stride * kElem + 64u) / 4u;
-        uint32_t* panel32 = reinterpret_cast<uint32_t*>(panel);
-        for (uint32_t i = tid; i < panel_words; i += kThreads) panel32[i] = 0u;
+#pragma unroll
+    for (uint32_t u = 0; u < kTableLoads; ++u)
+        if (tid + u * kThreads < L) reinterpret_cast<words4*>(ahead)[tid + u * kThreads] = tv[u];
+    {
+        // The panel starts as the layer's dominant symbol everywhere (decoding writes only the other symbols);
+        // also the columns from K to a row's end and the 64 bytes behind the last row, which the contraction
+        // reads (the last 32 k of a row tile or of a kernel tap) against activations that are zero: as bf16
+        // values they must be finite, whatever an earlier kernel left in LDS.
+        const uint32_t dominant = top >> 24;
+        uint32_t fill = dominant * 0x01010101u;
+        if constexpr (P16) {
+            const uint32_t h = __float_as_uint(static_cast<float>(int32_t(dominant) - int32_t(lay.zero_point))) >> 16;
+            fill = h | h << 16;
+        }
+        const uint32_t panel_quads = (kRows * MR * p.row_stride * kElem + 64u) / 16u;
+        for (uint32_t i = tid; i < panel_quads; i += kThreads) reinterpret_cast<words4*>(panel)[i] = words4{fill, fill, fill, fill};
     }
     __syncthreads();
     uint32_t err = (lay.channel_len != 0 && lay.channel_len != p.K) ? ANSZP_ST_BAD_DESC : 0u;   // scales per output channel only
-    for (uint32_t j = wave; j < p.chunks_per_panel; j += kWaves) {
-        const anszp_chunk_t c = j == wave ? first_chunk : p.chunks[uint64_t(mtile) * p.chunks_per_panel + j];
-        const bool ok = c.layer_id == p.layer_id && c.n_symbols == p.rows_per_chunk * p.K && (c.payload_offset & 3u) == 0 &&
-                        c.payload_offset <= p.payload_words && c.payload_words <= p.payload_words - c.payload_offset &&
-                        uint64_t(c.stream_offset) + p.n_streams <= p.n_stream_hdr;
-        if (!ok) {                                               // rows of a rejected chunk: zeros (any bytes would do as symbols,
-            err |= ANSZP_ST_BAD_DESC;                            // but not as bf16 values)
-            uint32_t* rows32 = reinterpret_cast<uint32_t*>(panel + j * p.rows_per_chunk * p.row_stride * kElem);
-            for (uint32_t i = lane; i < p.rows_per_chunk * p.row_stride * kElem / 4u; i += kWave) rows32[i] = 0u;
-            continue;
+    for (uint32_t i = 0; i < n_mine; ++i) {
+        // the next chunk's words are asked for before this one is decoded
+        ChunkDesc nxt{};
+        ChunkData nxt_data{};
+        if (i + 1u < n_mine) {
+            nxt = desc_of(i + 1u);
+            fetch(nxt, nxt_data);
         }
-        err |= decode_chunk_to_panel<P16>(p, c, table, stage + wave * kStageWords,
-                                          panel + j * p.rows_per_chunk * p.row_stride * kElem, lane, int32_t(lay.zero_point));
+        const uint32_t j = wave + i * kWaves;
+        if (!cur.ok) err |= ANSZP_ST_BAD_DESC;                    // its rows stay the dominant symbol
+        else err |= decode_chunk_to_panel<P16>(p, cur, cur_data, ahead, ahead_bytes - 8u, stage + wave * kStageWords,
+                                               panel + j * p.rows_per_chunk * p.row_stride * kElem, lane, int32_t(lay.zero_point));
+        cur = nxt;
+        cur_data = nxt_data;
     }
     if (err && lane == 0) report(p.status, err);
     __syncthreads();
+
+    if constexpr (KIND == kPointwiseRing) {
+        // ---- phase 2 for 1 x 1 kernels without padding whose input channels are a multiple of 32 * D.
+        // A panel of symbol bytes is first widened in place to bf16 values q - z (the table and the staging room
+        // are free now and the widened panel starts at the beginning of LDS): every thread takes its 16-byte
+        // pieces into registers, all wait, then every piece is written back as 32 bytes.
+        const uint8_t* a_base = panel;
+        if constexpr (!P16) {
+            constexpr uint32_t kPieces = 6;
+            const uint32_t n_pieces = (kRows * MR * p.row_stride + 64u) / 16u;     // the host made sure: <= kPieces * kThreads
+            const float zf = static_cast<float>(lay.zero_point);
+            words4 held_q[kPieces];
+#pragma unroll
+            for (uint32_t u = 0; u < kPieces; ++u)
+                held_q[u] = reinterpret_cast<const words4*>(panel)[min(tid + u * kThreads, n_pieces - 1u)];
+            __syncthreads();
+#pragma unroll
+            for (uint32_t u = 0; u < kPieces; ++u) {
+                const uint32_t i = tid + u * kThreads;
+                if (i < n_pieces) {
+                    bf16x8* dst = reinterpret_cast<bf16x8*>(lds + 32u * i);
+                    dst[0] = weights_of(words2{held_q[u].x, held_q[u].y}, zf);
+                    dst[1] = weights_of(words2{held_q[u].z, held_q[u].w}, zf);
+                }
+            }
+            __syncthreads();
+            a_base = lds;
+        }
+        const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
+        const uint8_t* a_row = a_base + (col * p.row_stride + 8u * kg) * 2u;
+        const uint32_t tile_stride = kRows * p.row_stride * 2u;
+        const uint32_t n_steps = p.cin / 32u;                     // a multiple of D
+        const uint32_t step_elems = 4u * p.x_block;               // from one step's activation vector to the next's
+        const uint32_t split_begin = split * p.pixels_per_split;
+        const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
+        for (uint32_t pix0 = split_begin + wave * p.block_pixels; pix0 < split_end; pix0 += kWaves * p.block_pixels) {
+            const uint32_t block_end = min(pix0 + p.block_pixels, split_end);
+            // B: lane holds column lane % 16 of each of the block's four column tiles; a column beyond the block
+            // reads the block's first pixel (every load is unconditional) and is not stored
+            bool valid[4];
+            uint32_t out_at[4];
+            const uint16_t* px[4];
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t pix = pix0 + q * 16u + col;
+                valid[q] = pix < block_end;
+                const uint32_t n = valid[q] ? pix : pix0;
+                const uint32_t wo = n % p.out_w, t = n / p.out_w;
+                const uint32_t ho = t % p.out_h, b = t / p.out_h;
+                px[q] = p.x + (b * p.in_h * p.in_w * p.cin + (ho * p.stride * p.in_w + wo * p.stride) * p.x_pixel + kg * p.x_block);
+                out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
+            }
+            floatx4 acc[MR][4];
+#pragma unroll
+            for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            // a ring of D steps' activation vectors: a step's slot is refilled, for the step D later, as soon as
+            // its MFMAs are issued; nothing in the loop is conditional, so the loads are waited for by count
+            words4 ring[D][4];
+#pragma unroll
+            for (uint32_t d = 0; d < D; ++d)
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) ring[d][q] = *reinterpret_cast<const words4*>(px[q] + d * step_elems);
+            __builtin_amdgcn_sched_barrier(0);
+            auto multiply = [&](uint32_t step, uint32_t d) {
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + step * 64u);
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q)
+                        acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
+                }
+            };
+            uint32_t base = 0;
+            for (; base + D < n_steps; base += D) {               // every group of D steps but the last
+#pragma unroll
+                for (uint32_t d = 0; d < D; ++d) {
+                    multiply(base + d, d);
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) ring[d][q] = *reinterpret_cast<const words4*>(px[q] + (base + d + D) * step_elems);
+                    __builtin_amdgcn_sched_barrier(0);            // the loads stay here: moved down to their use, they would be waited for at once
+                }
+            }
+#pragma unroll
+            for (uint32_t d = 0; d < D; ++d) multiply(base + d, d);
+            store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+        }
+        return;
+    }
 
     // ---- phase 2: the panel times the activations
     const uint32_t col = lane & 15u, kg = lane >> 4;              // MFMA operand layout: row or column, group of 8 k
@@ -291,7 +454,6 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         if constexpr (P16) return *reinterpret_cast<const bf16x8*>(at);
         else return weights_of(*reinterpret_cast<const words2*>(at), zf);
     };
-    const bool per_channel = lay.channel_len != 0;
     const uint32_t Kp = (p.K + 31u) & ~31u;
     // The workgroup's pixels are dealt out to its wavefronts in blocks of block_pixels, round robin, so that at
     // any time the wavefronts work on neighbouring pixels (kernel taps of neighbours share input rows).  A block
@@ -446,35 +608,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             }
         }
 
-        // D: lane holds column lane % 16, rows 4 * (lane / 16) + 0..3 of each row tile: four consecutive output channels
-#pragma unroll
-        for (uint32_t m = 0; m < MR; ++m) {
-            const uint32_t o = (mtile * MR + m) * kRows + 4u * kg;
-            float sc[4];
-#pragma unroll
-            for (uint32_t i = 0; i < 4; ++i) {
-                sc[i] = lay.scale;
-                if (per_channel) {
-                    const uint64_t ch = lay.scales_offset + o + i;
-                    sc[i] = ch < p.n_scales ? p.scales[ch] : 0.0f;
-                }
-            }
-#pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
-                if (valid[q]) {
-                    const floatx4 out = {acc[m][q][0] * sc[0], acc[m][q][1] * sc[1], acc[m][q][2] * sc[2], acc[m][q][3] * sc[3]};
-                    const uint32_t at = out_at[q] + (o >> 3) * p.y_block + (o & 7u);
-                    if (p.y_bf16) {                                   // round to nearest even (v_cvt_pk_bf16_f32)
-                        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-                        const bf16x4 r = {static_cast<__bf16>(out[0]), static_cast<__bf16>(out[1]),
-                                          static_cast<__bf16>(out[2]), static_cast<__bf16>(out[3])};
-                        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(p.y) + at) = r;
-                    } else {
-                        *reinterpret_cast<floatx4*>(static_cast<float*>(p.y) + at) = out;
-                    }
-                }
-            }
-        }
+        store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
     }
 }
 
@@ -510,7 +644,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     // Row tiles per workgroup: as many of 4, 2, 1 as divide the output channels and leave the panel room in LDS
     // beside the table and the staging buffers (more rows per activation vector loaded).
     const uint32_t row_stride = ((uint32_t(K) + 31u) & ~31u) + kRowPad;
-    const uint32_t table_bytes = (4u << a->table_log) < 16u ? 16u : (4u << a->table_log);
+    const uint32_t table_bytes = 16u << a->table_log;             // the look-ahead entries
     const uint32_t fixed_bytes = table_bytes + kWaves * kStageWords * 4u + 64u;
     const bool p16 = K <= kMaxK16;                              // short rows: the panel as bf16
     const uint32_t elem = p16 ? 2u : 1u;
@@ -534,6 +668,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     p.y_pixel = a->y_layout == ANSZP_ACT_C8 ? 8u : a->cout;
     p.y_block = a->y_layout == ANSZP_ACT_C8 ? 8u * out_h * out_w : 8u;
     p.K = uint32_t(K);
+    p.k_magic = uint32_t((uint64_t(1) << 32) / K) + 1u;           // unused for K = 1
     p.row_stride = row_stride;
     p.chunks_per_panel = kRows * mr / R;
     p.n_pixels = uint32_t(n_pixels);
@@ -559,23 +694,36 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
 
     // (fixed_bytes counts 64 bytes beyond the panel: the last 32 k of a kernel tap may reach past the end of the last row)
     const bool generic = (a->cin % 8u) != 0;
+    const bool pointwise = !generic && a->kh == 1 && a->kw == 1 && a->pad == 0;
+    const uint32_t panel_bytes = kRows * mr * row_stride * elem;
+    uint32_t lds_total = lds_bytes;
+    // 1 x 1 kernels whose input channels are a multiple of 64: the contraction with several steps' loads in flight;
+    // a panel of bytes is widened to bf16 in place first, which needs twice its room from the start of LDS
+    bool ring = pointwise && (a->cin % 64u) == 0;
+    if (ring && !p16) {
+        ring = panel_bytes + 64u <= 6u * kThreads * 16u && 2u * (panel_bytes + 64u) <= kLdsLimit;
+        if (ring && lds_total < 2u * (panel_bytes + 64u)) lds_total = 2u * (panel_bytes + 64u);
+    }
+    const uint32_t depth = ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
+    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : kTaps;
     void (*kernel)(ConvParams) = nullptr;
-    const int kind = generic ? kGeneric : (a->kh == 1 && a->kw == 1 && a->pad == 0) ? kPointwise : kTaps;
-#define ANSZP_CONV_PICK(KIND)                                                                                          \
-    (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true> : mr == 2 ? conv_fused_kernel<KIND, 2, true> : conv_fused_kernel<KIND, 1, true>) \
-         : (mr == 4 ? conv_fused_kernel<KIND, 4, false> : mr == 2 ? conv_fused_kernel<KIND, 2, false> : conv_fused_kernel<KIND, 1, false>))
-    kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise) : ANSZP_CONV_PICK(kTaps);
+#define ANSZP_CONV_PICK(KIND, D)                                                                                       \
+    (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true, D> : mr == 2 ? conv_fused_kernel<KIND, 2, true, D> : conv_fused_kernel<KIND, 1, true, D>) \
+         : (mr == 4 ? conv_fused_kernel<KIND, 4, false, D> : mr == 2 ? conv_fused_kernel<KIND, 2, false, D> : conv_fused_kernel<KIND, 1, false, D>))
+    kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric, 0) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise, 0)
+           : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
 #undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
     // concurrent callers at worst both say it)
-    static std::atomic<bool> lds_allowed[2][3][3][64];
+    static std::atomic<bool> lds_allowed[2][5][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
+    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 4u : uint32_t(kind);
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
-    if (!lds_allowed[p16][kind][slot][device].load(std::memory_order_relaxed)) {
+    if (!lds_allowed[p16][kernel_no][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 int(kLdsLimit)) != hipSuccess) return ANSZP_E_HIP;
-        lds_allowed[p16][kind][slot][device].store(true, std::memory_order_relaxed);
+        lds_allowed[p16][kernel_no][slot][device].store(true, std::memory_order_relaxed);
     }
-    hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
+    hipLaunchKernelGGL(kernel, dim3(n_mtiles * splits), dim3(kThreads), lds_total, static_cast<hipStream_t>(stream), p);
     return hipGetLastError() == hipSuccess ? ANSZP_OK : ANSZP_E_HIP;
 }
