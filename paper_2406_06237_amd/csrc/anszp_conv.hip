@@ -23,7 +23,9 @@
 // channels per lane, row tile and column tile.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 #include <cstdint>
 
@@ -39,6 +41,8 @@ constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
 constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
 constexpr uint32_t kStageWords = 384;       // per wavefront: LDS room for one chunk's compressed words (2.6 bit per
                                             // weight at 4608 symbols; a larger chunk is read from global memory)
+constexpr uint32_t kPatchTaps = 9;          // kTapsPatch: a 3 x 3 kernel
+constexpr uint32_t kPatchPieces = 4;        // kTapsPatch: 16-byte pieces of a patch per thread
 constexpr uint32_t kMaxMine = (4u * kRows + kWaves - 1u) / kWaves;   // chunks of a panel one wavefront may have to decode
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -66,6 +70,9 @@ struct ConvParams {
     uint32_t x_pixel, x_block, y_pixel, y_block;
     uint32_t y_bf16, K, row_stride, n_pixels, n_mtiles;   // n_mtiles: panels of 16 * MR rows
     uint32_t k_magic;                                     // floor(2^32 / K) + 1: i / K = mulhi(i, k_magic) for i * K < 2^32
+    uint32_t panel_off;                                   // first byte of the panel in LDS (behind the table and the staging room)
+    uint32_t wave_pixels, patch_off, patch_plane;         // kTapsPatch: pixels per wavefront and round (16..64); first byte of the
+                                                          // patch; bytes of one of its four planes
     uint32_t pixels_per_split, block_pixels;              // multiples of 16: the pixels of a workgroup; of one block (<= 64)
 };
 
@@ -241,7 +248,9 @@ __device__ __forceinline__ void store_tiles(const ConvParams& p, const anszp_lay
 enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecutive k lie under one kernel tap
        kPointwise = 1,   // as kTaps with a 1 x 1 kernel and no padding: one pixel per column, nothing outside the image
        kGeneric = 2,     // any number of input channels (NHWC): every activation is addressed on its own
-       kPointwiseRing = 3 };   // as kPointwise with input channels a multiple of 32 * D: D steps' activations in flight
+       kPointwiseRing = 3,     // as kPointwise with input channels a multiple of 32 * D: D steps' activations in flight
+       kTapsPatch = 4 };       // as kTaps with input channels a multiple of 32: the activations under all kernel taps of a
+                               // round of pixels are staged in LDS once per 32 input channels
 // D (kPointwiseRing only): steps of 32 input channels whose activation loads are in flight at any time.
 template <int KIND, uint32_t MR, bool P16, uint32_t D>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
@@ -250,7 +259,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     const uint32_t ahead_bytes = 16u * L;                         // 2 L look-ahead entries of two words
     uint8_t* ahead = lds;
     uint32_t* stage = reinterpret_cast<uint32_t*>(lds + ahead_bytes);
-    uint8_t* panel = lds + ahead_bytes + kWaves * kStageWords * 4u;
+    uint8_t* panel = lds + p.panel_off;
     constexpr uint32_t kElem = P16 ? 2u : 1u;                     // bytes per panel element
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -440,6 +449,144 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             }
 #pragma unroll
             for (uint32_t d = 0; d < D; ++d) multiply(base + d, d);
+            store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+        }
+        return;
+    }
+
+    if constexpr (KIND == kTapsPatch) {
+        // ---- phase 2 for kernels of several taps whose input channels are a multiple of 32.
+        // The workgroup's pixels are taken in rounds of kWaves * wave_pixels; for a round and 32 input channels
+        // the activations under every kernel tap of every pixel of the round (the "patch": the rows of the
+        // zero-padded input images from the first pixel's first tap to the last pixel's last, each row with its
+        // padding columns) are copied to LDS once, zeros included, and every tap's B operands are read from
+        // there: a lane's address is its pixel's place in the patch plus an offset that only depends on the tap,
+        // and nothing in the loop tests for the image's border.  The patch is four planes, one per block of 8 of
+        // the 32 channels; patch element (row pr, column pc) is the 16 bytes number
+        // (pr * stride + pc % stride) * Wh + pc / stride of each plane, Wh = ceil(padded width / stride): the 16
+        // lanes that read the same 8 channels of a column tile's 16 pixels read 256 consecutive bytes for every
+        // tap and stride (no two of them the same LDS bank).
+        // A panel of symbol bytes is widened, 32 input channels of every tap at a time, into a slab of bf16
+        // values beside the patch.  The next 32 channels' activations are on their way (in registers) while
+        // the current ones are multiplied.
+        const uint32_t S = p.stride, Hp = p.in_h + 2u * p.pad, Wp = p.in_w + 2u * p.pad, Wh = (Wp + S - 1u) / S;
+        constexpr uint32_t taps = kPatchTaps;                     // 3 x 3 kernels only (the host sees to it)
+        constexpr uint32_t slab_row = taps * 64u + 16u;           // bytes; rows start four banks apart
+        uint8_t* slab = lds;
+        uint8_t* patch = lds + p.patch_off;
+        const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
+        uint32_t tap_off[taps];                                   // from a pixel's place in the patch to what lies under a tap
+#pragma unroll
+        for (uint32_t tap = 0; tap < taps; ++tap) {
+            const uint32_t r = tap / 3u, sx = tap % 3u;
+            tap_off[tap] = ((r * S + sx % S) * Wh + sx / S) * 16u;
+        }
+        // A: lane holds row lane % 16 of a row tile, k = 8 * (lane / 16) + 0..7 of a step
+        const uint8_t* a_lane = P16 ? panel + (col * p.row_stride + 8u * kg) * 2u : slab + col * slab_row + kg * 16u;
+        const float zf = static_cast<float>(lay.zero_point);
+        const uint32_t split_begin = split * p.pixels_per_split;
+        const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
+        constexpr uint32_t kPieces = kPatchPieces;                // 16-byte pieces of a patch one thread may have to copy
+        for (uint32_t round0 = split_begin; round0 < split_end; round0 += kWaves * p.wave_pixels) {
+            const uint32_t round_end = min(round0 + kWaves * p.wave_pixels, split_end);
+            // the patch's rows: flat index b * Hp + padded row
+            const uint32_t first_row = round0 / p.out_w, last_row = (round_end - 1u) / p.out_w;   // flat output rows b * out_h + ho
+            const uint32_t pr0 = (first_row / p.out_h) * Hp + (first_row % p.out_h) * S;
+            const uint32_t pr_last = (last_row / p.out_h) * Hp + (last_row % p.out_h) * S + p.kh - 1u;
+            const uint32_t n_pieces = (pr_last - pr0 + 1u) * 4u * Wp;
+            if (n_pieces > kPieces * kThreads) {                  // the host sized the rounds so that this cannot happen
+                if (tid == 0) report(p.status, ANSZP_ST_INTERNAL);
+                return;                                           // uniform
+            }
+            uint32_t src[kPieces], dst[kPieces];                  // element of x (none: zeros), byte of the patch (none: no piece)
+#pragma unroll
+            for (uint32_t u = 0; u < kPieces; ++u) {
+                const uint32_t i = tid + u * kThreads;            // piece (row, block of 8 channels, column), column fastest
+                src[u] = dst[u] = 0xFFFFFFFFu;
+                if (i < n_pieces) {
+                    const uint32_t pc = i % Wp, t = i / Wp;
+                    const uint32_t j = t & 3u, prl = t >> 2;
+                    const uint32_t pra = pr0 + prl;
+                    const uint32_t b = pra / Hp, h = pra % Hp - p.pad, w = pc - p.pad;   // unsigned: outside the image wraps around
+                    if (h < p.in_h && w < p.in_w) src[u] = b * p.in_h * p.in_w * p.cin + (h * p.in_w + w) * p.x_pixel + j * p.x_block;
+                    dst[u] = ((prl * S + pc % S) * Wh + pc / S) * 16u + j * p.patch_plane;
+                }
+            }
+            // this wavefront's pixels: up to four column tiles; a column beyond them stands on the round's first pixel
+            const uint32_t mine_begin = round0 + wave * p.wave_pixels;
+            const uint32_t mine_end = min(mine_begin + p.wave_pixels, round_end);
+            const uint32_t qt = mine_begin < mine_end ? (mine_end - mine_begin + 15u) / 16u : 0u;   // uniform
+            bool valid[4];
+            uint32_t out_at[4], at_patch[4];
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t pix = mine_begin + q * 16u + col;
+                valid[q] = pix < mine_end;
+                const uint32_t n = valid[q] ? pix : round0;
+                const uint32_t wo = n % p.out_w, t = n / p.out_w;
+                const uint32_t ho = t % p.out_h, b = t / p.out_h;
+                at_patch[q] = (((b * Hp + ho * S - pr0) * S) * Wh + wo) * 16u + kg * p.patch_plane;
+                out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
+            }
+            floatx4 acc[MR][4];
+#pragma unroll
+            for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+            words4 held_x[kPieces];
+            auto fetch_x = [&](uint32_t c0) {                     // the pieces of input channels c0 .. c0 + 31
+#pragma unroll
+                for (uint32_t u = 0; u < kPieces; ++u) {
+                    held_x[u] = words4{0u, 0u, 0u, 0u};
+                    if (src[u] != 0xFFFFFFFFu) held_x[u] = *reinterpret_cast<const words4*>(p.x + src[u] + (c0 >> 3) * p.x_block);
+                }
+            };
+            fetch_x(0u);
+            for (uint32_t c0 = 0; c0 < p.cin; c0 += 32u) {
+                __syncthreads();                                  // the previous step's patch and slab have been read
+#pragma unroll
+                for (uint32_t u = 0; u < kPieces; ++u)
+                    if (dst[u] != 0xFFFFFFFFu) *reinterpret_cast<words4*>(patch + dst[u]) = held_x[u];
+                if constexpr (!P16) {
+                    // slab[row][tap][32] = bf16(panel[row][tap * cin + c0 + 0..31] - z), 16 symbols per piece
+                    const uint32_t n_quads = kRows * MR * taps * 2u;
+                    for (uint32_t i = tid; i < n_quads; i += kThreads) {
+                        const uint32_t half = i & 1u, t = i >> 1;
+                        const uint32_t tap = t % taps, row = t / taps;
+                        const uint8_t* from = panel + row * p.row_stride + tap * p.cin + c0 + half * 16u;
+                        bf16x8* to = reinterpret_cast<bf16x8*>(slab + row * slab_row + tap * 64u + half * 32u);
+                        to[0] = weights_of(*reinterpret_cast<const words2*>(from), zf);
+                        to[1] = weights_of(*reinterpret_cast<const words2*>(from + 8), zf);
+                    }
+                }
+                if (c0 + 32u < p.cin) fetch_x(c0 + 32u);
+                __syncthreads();
+                // the nine taps, unrolled, with as many column tiles as this wavefront has (uniform)
+                auto multiply = [&](auto tiles) {
+                    constexpr uint32_t QT = decltype(tiles)::value;
+#pragma unroll
+                    for (uint32_t tap = 0; tap < kPatchTaps; ++tap) {
+                        bf16x8 a[MR];
+#pragma unroll
+                        for (uint32_t m = 0; m < MR; ++m) {
+                            if constexpr (P16) a[m] = *reinterpret_cast<const bf16x8*>(a_lane + (m * kRows * p.row_stride + tap * p.cin + c0) * 2u);
+                            else a[m] = *reinterpret_cast<const bf16x8*>(a_lane + m * kRows * slab_row + tap * 64u);
+                        }
+#pragma unroll
+                        for (uint32_t q = 0; q < QT; ++q) {
+                            const bf16x8 b = *reinterpret_cast<const bf16x8*>(patch + at_patch[q] + tap_off[tap]);
+#pragma unroll
+                            for (uint32_t m = 0; m < MR; ++m)
+                                acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b, acc[m][q], 0, 0, 0);
+                        }
+                    }
+                };
+                if (qt == 4u) multiply(std::integral_constant<uint32_t, 4>{});
+                else if (qt == 3u) multiply(std::integral_constant<uint32_t, 3>{});
+                else if (qt == 2u) multiply(std::integral_constant<uint32_t, 2>{});
+                else if (qt == 1u) multiply(std::integral_constant<uint32_t, 1>{});
+            }
             store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
         }
         return;
@@ -648,7 +795,10 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     const uint32_t fixed_bytes = table_bytes + kWaves * kStageWords * 4u + 64u;
     const bool p16 = K <= kMaxK16;                              // short rows: the panel as bf16
     const uint32_t elem = p16 ? 2u : 1u;
-    uint32_t mr = 4;
+    // (a 3 x 3 kernel of stride 1 whose activations go through LDS holds at most two row tiles: its accumulators
+    // and the operands in flight of four would not fit the registers of three wavefronts per SIMD)
+    const bool patch_wanted = (a->cin % 32u) == 0 && a->cin >= 128u && a->kh == 3 && a->kw == 3 && a->stride == 1;
+    uint32_t mr = patch_wanted ? 2 : 4;
     while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride * elem > kLdsLimit)) mr >>= 1;
     const uint32_t n_mtiles = a->cout / (kRows * mr);
     if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y) | reinterpret_cast<uintptr_t>(a->payload) |
@@ -705,19 +855,52 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
         if (ring && lds_total < 2u * (panel_bytes + 64u)) lds_total = 2u * (panel_bytes + 64u);
     }
     const uint32_t depth = ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
-    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : kTaps;
+    // Kernels of several taps (or with padding) whose input channels are a multiple of 32: the patch in LDS.  The
+    // pixels a wavefront takes per round are the most (of 64, 48, 32, 16, and no more than the workgroup's share
+    // asks for) whose largest possible patch fits: in pieces per thread, and, with the slab of widened weights,
+    // in the LDS below the panel.
+    p.panel_off = table_bytes + kWaves * kStageWords * 4u;
+    bool patch = patch_wanted;
+    if (patch) {
+        const uint32_t S = a->stride, Hp = a->in_h + 2u * a->pad, Wp = a->in_w + 2u * a->pad, Wh = (Wp + S - 1u) / S;
+        const uint32_t taps = a->kh * a->kw;
+        const uint32_t slab_bytes = p16 ? 0u : ((kRows * mr * (taps * 64u + 16u) + 63u) & ~63u);
+        const int64_t gap = int64_t(Hp) - int64_t(out_h) * S;     // patch rows between the last output row of an image and the next image's first
+        uint32_t wave_pixels = p.block_pixels;
+        patch = false;
+        for (; wave_pixels >= 16u; wave_pixels -= 16u) {
+            const uint64_t round = std::min<uint64_t>(uint64_t(kWaves) * wave_pixels, p.pixels_per_split);
+            const uint64_t rows_out = (round + out_w - 2u) / out_w + 1u;                   // output rows a round can touch
+            const uint64_t crossings = std::min<uint64_t>(a->batch - 1u, (rows_out + out_h - 2u) / out_h);
+            const uint64_t rows = (rows_out - 1u) * S + a->kh + crossings * uint64_t(gap > 0 ? gap : 0);
+            const uint64_t patch_bytes = rows * S * Wh * 64u;
+            const uint64_t below = std::max<uint64_t>(p.panel_off, slab_bytes + patch_bytes);
+            if (rows * 4u * Wp <= kPatchPieces * kThreads && below + panel_bytes + 64u <= kLdsLimit) {
+                patch = true;
+                p.wave_pixels = wave_pixels;
+                p.patch_off = slab_bytes;
+                p.patch_plane = uint32_t(rows * S * Wh * 16u);
+                p.panel_off = uint32_t((below + 15u) & ~uint64_t(15));
+                lds_total = p.panel_off + panel_bytes + 64u;
+                break;
+            }
+        }
+        if (!patch) p.panel_off = table_bytes + kWaves * kStageWords * 4u;
+    }
+    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : kTaps;
     void (*kernel)(ConvParams) = nullptr;
 #define ANSZP_CONV_PICK(KIND, D)                                                                                       \
     (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true, D> : mr == 2 ? conv_fused_kernel<KIND, 2, true, D> : conv_fused_kernel<KIND, 1, true, D>) \
          : (mr == 4 ? conv_fused_kernel<KIND, 4, false, D> : mr == 2 ? conv_fused_kernel<KIND, 2, false, D> : conv_fused_kernel<KIND, 1, false, D>))
     kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric, 0) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise, 0)
-           : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
+           : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : kind == kTapsPatch ? ANSZP_CONV_PICK(kTapsPatch, 0)
+           : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
 #undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
     // concurrent callers at worst both say it)
-    static std::atomic<bool> lds_allowed[2][5][3][64];
+    static std::atomic<bool> lds_allowed[2][6][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
-    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 4u : uint32_t(kind);
+    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 5u : uint32_t(kind);
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
     if (!lds_allowed[p16][kernel_no][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
