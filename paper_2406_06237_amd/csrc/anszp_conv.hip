@@ -518,8 +518,10 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             const uint32_t qt = mine_begin < mine_end ? (mine_end - mine_begin + 15u) / 16u : 0u;   // uniform
             bool valid[4];
             uint32_t out_at[4], at_patch[4];
+            valid[3] = false;                                     // at most three column tiles (48 pixels) per wavefront and round
+            out_at[3] = at_patch[3] = 0u;
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
+            for (uint32_t q = 0; q < 3; ++q) {
                 const uint32_t pix = mine_begin + q * 16u + col;
                 valid[q] = pix < mine_end;
                 const uint32_t n = valid[q] ? pix : round0;
@@ -582,8 +584,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                         }
                     }
                 };
-                if (qt == 4u) multiply(std::integral_constant<uint32_t, 4>{});
-                else if (qt == 3u) multiply(std::integral_constant<uint32_t, 3>{});
+                if (qt == 3u) multiply(std::integral_constant<uint32_t, 3>{});
                 else if (qt == 2u) multiply(std::integral_constant<uint32_t, 2>{});
                 else if (qt == 1u) multiply(std::integral_constant<uint32_t, 1>{});
             }
@@ -866,7 +867,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
         const uint32_t taps = a->kh * a->kw;
         const uint32_t slab_bytes = p16 ? 0u : ((kRows * mr * (taps * 64u + 16u) + 63u) & ~63u);
         const int64_t gap = int64_t(Hp) - int64_t(out_h) * S;     // patch rows between the last output row of an image and the next image's first
-        uint32_t wave_pixels = p.block_pixels;
+        uint32_t wave_pixels = std::min(p.block_pixels, 48u);
         patch = false;
         for (; wave_pixels >= 16u; wave_pixels -= 16u) {
             const uint64_t round = std::min<uint64_t>(uint64_t(kWaves) * wave_pixels, p.pixels_per_split);
