@@ -87,16 +87,19 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
     return v;
 }
 
-// Exclusive prefix sum over the wavefront, and the total.
+// Exclusive prefix sum over the 64 lanes of a wavefront; *total receives the sum.  Data-parallel-primitive
+// moves: within rows of 16 lanes by 1, 2, 4 and 8 (lanes without a source add zero), then lane 15 of rows 0
+// and 2 to the rows after them, then lane 31 to the upper half.
 __device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t v, uint32_t* total) {
-    uint32_t s = v;
-#pragma unroll
-    for (int d = 1; d < int(kWave); d <<= 1) {
-        const uint32_t t = __shfl_up(s, d, kWave);
-        if ((threadIdx.x & (kWave - 1)) >= uint32_t(d)) s += t;
-    }
-    *total = __shfl(s, kWave - 1, kWave);
-    return s - v;
+    int x = static_cast<int>(v);
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);      // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);      // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);      // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);      // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);     // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);     // row_bcast:31 into rows 2 and 3
+    *total = static_cast<uint32_t>(__builtin_amdgcn_readlane(x, kWave - 1));
+    return static_cast<uint32_t>(x) - v;
 }
 
 // What a wavefront fetches of a chunk before it decodes it: the stream headers (lane k: stream k), the chunk's
@@ -121,7 +124,7 @@ struct ChunkDesc {
 // already holds everywhere (the caller fills it), so a look-up writes one panel element.  The entry of index
 // 2X + b and the two stream words around the lane's bit position are read together; with T the bits the entry
 // consumes, the next index is base + (the next T + 1 stream bits, first bit most significant) and the bit
-// position moves on by T.  Returns error bits.
+// position moves on by T.  Returns the lane's error bits.
 // The chunk's words were fetched into `d` (16-byte loads issued long before) and go to `stage` (LDS, this
 // wavefront's own) when they fit, so that the loop waits for no global load; a larger chunk is read word by word
 // in place.  P16: the panel holds bf16 values q - z (two bytes per weight) instead of the symbols q.
@@ -189,7 +192,7 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& 
     };
     if (c.staged) walk([&](uint32_t i) { return stage[i]; });
     else walk([&](uint32_t i) { return i < word_limit ? words[i] : 0u; });
-    return wave_or(err);
+    return err;                                       // this lane's
 }
 
 // Eight symbols -> eight bf16 values q - z.  |q - z| <= 255 has at most 8 significant bits, so the
@@ -361,6 +364,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         cur = nxt;
         cur_data = nxt_data;
     }
+    err = wave_or(err);
     if (err && lane == 0) report(p.status, err);
     __syncthreads();
 

@@ -159,7 +159,7 @@ def test_chunk_whose_words_exceed_the_staging_buffer(orc):
 
 def test_corrupt_stream_is_reported(orc):
     shape, K = (16, 32, 3, 3), 288
-    rows = B.conv_rows_per_chunk(K)
+    rows = 8                                    # 36 symbols per stream: the flipped bits are bits a stream reads, not its padding
     lay = _layer(shape, 4, 0.7, 3)
     w = W.Workload("conv_case", [lay], 12, 64, rows * K, "bf16")
     c = oracle_encode(orc, w)
