@@ -155,31 +155,40 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& 
     const uint32_t first_bit = first_word << 5;
     uint32_t bit = first_bit;
     uint32_t elem = lane;                             // the chunk element of the lane's next symbol
-    auto walk = [&](auto word_at) {
+    // A chunk of one panel row needs no division to find a symbol's row.  An entry that would carry a stream
+    // past its end (corrupt data only: a valid stream ends where an entry ends) writes the chunk's last element.
+    const uint32_t last_elem = c.n_symbols - 1u;
+    constexpr uint32_t kElem = P16 ? 2u : 1u;
+    const uint32_t row_gap_bytes = (p.row_stride - p.K) * kElem;
+    auto walk = [&](auto word_at, auto one_row) {
         uint32_t at = ((2u * X0 + (word_at(min(first_word, word_limit)) & 1u)) * 8u) & ahead_mask;   // entry 2 X0 + first stream bit
-        while (__ballot(elem < n) != 0) {
-            if (elem < n) {
-                const uint32_t wi = min(bit >> 5, word_limit);
-                const uint32_t w0 = word_at(wi), w1 = word_at(wi + 1u);
-                const words2 e = *reinterpret_cast<const words2*>(ahead + at);
-                const uint32_t window = __builtin_amdgcn_alignbit(w1, w0, bit);
-                const uint32_t v = __brev(window) >> (e.x & 31u);           // the next T + 1 stream bits
-                at = (e.y + 8u * v) & ahead_mask;
-                bit += (e.x >> 24) & 15u;
-                elem += ((e.x >> 28) & 7u) * N;                             // past the entry's dominant symbols
-                if (elem < c.n_symbols) {
-                    const uint32_t row = p.K > 1u ? __umulhi(elem, p.k_magic) : elem;
-                    const uint32_t where = elem + row * (p.row_stride - p.K);
+        bool active = elem < n;
+        if (__ballot(active) != 0) {
+            do {
+                if (active) {
+                    const uint32_t wi = min(bit >> 5, word_limit);
+                    const uint32_t w0 = word_at(wi), w1 = word_at(wi + 1u);
+                    const words2 e = *reinterpret_cast<const words2*>(ahead + at);
+                    const uint32_t window = __builtin_amdgcn_alignbit(w1, w0, bit);
+                    const uint32_t v = __brev(window) >> (e.x & 31u);       // the next T + 1 stream bits
+                    at = (e.y + 8u * v) & ahead_mask;
+                    bit += (e.x >> 24) & 15u;
+                    elem += ((e.x >> 28) & 7u) * N;                         // past the entry's dominant symbols
+                    const uint32_t el = min(elem, last_elem);
+                    uint32_t where = el * kElem;                            // byte of the panel rows
+                    if constexpr (!decltype(one_row)::value)
+                        where = __umul24(p.K > 1u ? __umulhi(el, p.k_magic) : el, row_gap_bytes) + where;   // both factors below 2^24
                     const uint32_t sym = (e.x >> 16) & 0xFFu;
                     if constexpr (P16) {              // an integer of at most 8 bits: the upper half of its binary32 form is exact
                         const float w = static_cast<float>(int32_t(sym) - zero_point);
-                        reinterpret_cast<uint16_t*>(rows)[where] = static_cast<uint16_t>(__float_as_uint(w) >> 16);
+                        *reinterpret_cast<uint16_t*>(rows + where) = static_cast<uint16_t>(__float_as_uint(w) >> 16);
                     } else {
                         rows[where] = static_cast<uint8_t>(sym);
                     }
+                    elem += N;
+                    active = elem < n;
                 }
-                elem += N;
-            }
+            } while (__ballot(active) != 0);
         }
         // a stream ends where an entry ends, in state 0 (the index of the next entry is 2 X + peeked bit),
         // having read exactly its words
@@ -190,8 +199,12 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& 
             if (((bit - first_bit) + 31u) >> 5 != n_words) err |= ANSZP_ST_BAD_LENGTH;
         }
     };
-    if (c.staged) walk([&](uint32_t i) { return stage[i]; });
-    else walk([&](uint32_t i) { return i < word_limit ? words[i] : 0u; });
+    if (c.staged) {
+        if (p.rows_per_chunk == 1u) walk([&](uint32_t i) { return stage[i]; }, std::true_type{});
+        else walk([&](uint32_t i) { return stage[i]; }, std::false_type{});
+    } else {
+        walk([&](uint32_t i) { return i < word_limit ? words[i] : 0u; }, std::false_type{});
+    }
     return err;                                       // this lane's
 }
 
