@@ -380,6 +380,19 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
     err = wave_or(err);
     if (err && lane == 0) report(p.status, err);
     __syncthreads();
+    // kGeneric: what every k of the reduction means, worked out once (the table and the staging room are free now):
+    // two words per k, the offset of its activation from the one under the first tap's first channel, and its
+    // kernel row | kernel column << 8 (a column no image has for the k beyond K)
+    [[maybe_unused]] uint32_t* k_table = reinterpret_cast<uint32_t*>(lds);
+    if constexpr (KIND == kGeneric) {
+        for (uint32_t k = tid; k < ((p.K + 31u) & ~31u); k += kThreads) {
+            const uint32_t tap = k / p.cin, c = k % p.cin;
+            const uint32_t r = tap / p.kw, sx = tap % p.kw;
+            k_table[2u * k] = (r * p.in_w + sx) * p.cin + c;
+            k_table[2u * k + 1u] = k < p.K ? (r | sx << 8) : 0xFFFFFF00u;
+        }
+        __syncthreads();
+    }
 
     if constexpr (KIND == kPointwiseRing) {
         // ---- phase 2 for 1 x 1 kernels without padding whose input channels are a multiple of 32 * D.
@@ -743,19 +756,29 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 }
             }
         } else {
+            // where each column's pixel lies under the first kernel tap (possibly outside the image: only used
+            // together with a tap that is inside)
+            uint32_t corner[4];
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) corner[q] = img[q] + uint32_t((h0[q] * int32_t(p.in_w) + w0[q]) * int32_t(p.cin));
             for (uint32_t k0 = 0; k0 < Kp; k0 += 32u) {
                 const uint32_t kbase = k0 + 8u * kg;
                 uint16_t bv[4][8];
+                words2 kt[8];                                     // this lane's 8 k of the step: offset, kernel row and column
+#pragma unroll
+                for (uint32_t j = 0; j < 8; j += 2) {
+                    const words4 two = *reinterpret_cast<const words4*>(k_table + 2u * (kbase + j));
+                    kt[j] = words2{two.x, two.y};
+                    kt[j + 1] = words2{two.z, two.w};
+                }
 #pragma unroll
                 for (uint32_t j = 0; j < 8; ++j) {
-                    const uint32_t k = kbase + j;
-                    const uint32_t tap = k / p.cin, c = k % p.cin;
-                    const uint32_t r = tap / p.kw, s = tap % p.kw;
+                    const uint32_t r = kt[j].y & 0xFFu, s = kt[j].y >> 8;          // s = 0xFFFFFF beyond K: outside every image
 #pragma unroll
                     for (uint32_t q = 0; q < 4; ++q) {
                         const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(s);
-                        const bool inside = valid[q] && k < p.K && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
-                        bv[q][j] = inside ? p.x[img[q] + (uint32_t(h) * p.in_w + uint32_t(w)) * p.cin + c] : uint16_t(0);   // NHWC only
+                        const bool inside = valid[q] && uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                        bv[q][j] = inside ? p.x[corner[q] + kt[j].x] : uint16_t(0);   // NHWC only
                     }
                 }
                 words4 b[4];
@@ -904,6 +927,14 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
             }
         }
         if (!patch) p.panel_off = table_bytes + kWaves * kStageWords * 4u;
+    }
+    if (generic) {                                                // room for the table of the k below the panel
+        const uint32_t k_table_bytes = ((uint32_t(K) + 31u) & ~31u) * 8u;
+        if (p.panel_off < k_table_bytes) {
+            p.panel_off = k_table_bytes;
+            lds_total = p.panel_off + panel_bytes + 64u;
+            if (lds_total > kLdsLimit) return ANSZP_E_RANGE;
+        }
     }
     const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : kTaps;
     void (*kernel)(ConvParams) = nullptr;
