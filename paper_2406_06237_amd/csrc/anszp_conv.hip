@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
+#include <utility>
 
 #include <cstdint>
 
@@ -257,6 +258,27 @@ __device__ __forceinline__ void store_tiles(const ConvParams& p, const anszp_lay
     }
 }
 
+// kPointwiseRing: the loads of one ring slot (QT activation vectors) issued by hand, and the wait for them.  When a
+// slot is used, LATER loads have been asked for after its own, so the wait is for all but LATER loads; it names the
+// slot's registers as its results, so that nothing which uses them can be moved ahead of it.  (The compiler, left
+// to count loads that cross the loop's back edge, waits for every load at the head of the loop.)
+template <uint32_t QT>
+__device__ __forceinline__ void ring_request(words4 (&slot)[QT], const uint16_t* const (&px)[QT], uint32_t element_offset) {
+#pragma unroll
+    for (uint32_t q = 0; q < QT; ++q) {
+        const uint16_t* from = px[q] + element_offset;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(slot[q]) : "v"(from) : "memory");
+    }
+}
+template <uint32_t QT, uint32_t LATER>
+__device__ __forceinline__ void ring_arrived(words4 (&slot)[QT]) {
+    static_assert(QT >= 1 && QT <= 4 && LATER < 64, "one to four vectors per slot; the counter has six bits");
+    if constexpr (QT == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(slot[0]) : "n"(LATER) : "memory");
+    if constexpr (QT == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(slot[0]), "+v"(slot[1]) : "n"(LATER) : "memory");
+    if constexpr (QT == 3) asm volatile("s_waitcnt vmcnt(%3)" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]) : "n"(LATER) : "memory");
+    if constexpr (QT == 4) asm volatile("s_waitcnt vmcnt(%4)" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]) : "n"(LATER) : "memory");
+}
+
 // MR: MFMA row tiles per workgroup.  Every wavefront multiplies all 16 * MR panel rows with its columns, so
 // an activation vector loaded once feeds MR MFMAs.
 // P16: the panel is kept as bf16 (short rows: K <= 576), so that the contraction reads its A operands as they are.
@@ -428,15 +450,21 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         const uint32_t step_elems = 4u * p.x_block;               // from one step's activation vector to the next's
         const uint32_t split_begin = split * p.pixels_per_split;
         const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
-        for (uint32_t pix0 = split_begin + wave * p.block_pixels; pix0 < split_end; pix0 += kWaves * p.block_pixels) {
-            const uint32_t block_end = min(pix0 + p.block_pixels, split_end);
-            // B: lane holds column lane % 16 of each of the block's four column tiles; a column beyond the block
+        // The workgroup's column tiles of 16 pixels are dealt out in rounds of at most 4 * kWaves, and a round's tiles
+        // evenly over the wavefronts: every wavefront has one to four neighbouring tiles (as many loads in flight
+        // on as many SIMDs as possible: the loop is bound by the activations' way from the L2).
+        const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
+        const uint32_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
+        const uint32_t round_tiles = (tiles + n_rounds - 1u) / n_rounds;
+        auto block = [&](uint32_t pix0, uint32_t block_end, auto tiles_here) {
+            constexpr uint32_t QT = decltype(tiles_here)::value;
+            // B: lane holds column lane % 16 of each of the block's QT column tiles; a column beyond the block
             // reads the block's first pixel (every load is unconditional) and is not stored
-            bool valid[4];
-            uint32_t out_at[4];
-            const uint16_t* px[4];
+            bool valid[4] = {false, false, false, false};
+            uint32_t out_at[4] = {0u, 0u, 0u, 0u};
+            const uint16_t* px[QT];
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
+            for (uint32_t q = 0; q < QT; ++q) {
                 const uint32_t pix = pix0 + q * 16u + col;
                 valid[q] = pix < block_end;
                 const uint32_t n = valid[q] ? pix : pix0;
@@ -450,36 +478,61 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             for (uint32_t m = 0; m < MR; ++m)
 #pragma unroll
                 for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-            // a ring of D steps' activation vectors: a step's slot is refilled, for the step D later, as soon as
-            // its MFMAs are issued; nothing in the loop is conditional, so the loads are waited for by count
-            words4 ring[D][4];
-#pragma unroll
-            for (uint32_t d = 0; d < D; ++d)
-#pragma unroll
-                for (uint32_t q = 0; q < 4; ++q) ring[d][q] = *reinterpret_cast<const words4*>(px[q] + d * step_elems);
-            __builtin_amdgcn_sched_barrier(0);
+            // A ring of D steps' activation vectors: a step's slot is refilled, for the step D later, as soon as its
+            // MFMAs are issued (ring_request / ring_arrived: by hand).
+            words4 ring[D][QT];
             auto multiply = [&](uint32_t step, uint32_t d) {
 #pragma unroll
                 for (uint32_t m = 0; m < MR; ++m) {
                     const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + step * 64u);
 #pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q)
+                    for (uint32_t q = 0; q < QT; ++q)
                         acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
                 }
             };
+#pragma unroll
+            for (uint32_t d = 0; d < D; ++d) ring_request<QT>(ring[d], px, d * step_elems);
             uint32_t base = 0;
             for (; base + D < n_steps; base += D) {               // every group of D steps but the last
 #pragma unroll
                 for (uint32_t d = 0; d < D; ++d) {
+                    ring_arrived<QT, (D - 1u) * QT>(ring[d]);
                     multiply(base + d, d);
-#pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q) ring[d][q] = *reinterpret_cast<const words4*>(px[q] + (base + d + D) * step_elems);
-                    __builtin_amdgcn_sched_barrier(0);            // the loads stay here: moved down to their use, they would be waited for at once
+                    ring_request<QT>(ring[d], px, (base + d + D) * step_elems);
                 }
             }
-#pragma unroll
-            for (uint32_t d = 0; d < D; ++d) multiply(base + d, d);
+            // the last group: nothing is asked for any more, so fewer loads follow a slot's own
+            static_assert(D == 2 || D == 4, "written out for two and four slots");
+            if constexpr (D == 2) {
+                ring_arrived<QT, QT>(ring[0]);
+                multiply(base, 0u);
+                ring_arrived<QT, 0u>(ring[1]);
+                multiply(base + 1u, 1u);
+            } else {
+                ring_arrived<QT, 3u * QT>(ring[0]);
+                multiply(base, 0u);
+                ring_arrived<QT, 2u * QT>(ring[1]);
+                multiply(base + 1u, 1u);
+                ring_arrived<QT, QT>(ring[2]);
+                multiply(base + 2u, 2u);
+                ring_arrived<QT, 0u>(ring[3]);
+                multiply(base + 3u, 3u);
+            }
             store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+        };
+        for (uint32_t round = 0; round < n_rounds; ++round) {
+            const uint32_t t0 = round * round_tiles;
+            if (t0 >= tiles) break;
+            const uint32_t tn = min(round_tiles, tiles - t0);
+            const uint32_t w_begin = t0 + tn * wave / kWaves, w_end = t0 + tn * (wave + 1u) / kWaves;   // this wavefront's tiles
+            const uint32_t pix0 = split_begin + 16u * w_begin, block_end = min(split_begin + 16u * w_end, split_end);
+            switch (w_end - w_begin) {                            // uniform
+                case 1: block(pix0, block_end, std::integral_constant<uint32_t, 1>{}); break;
+                case 2: block(pix0, block_end, std::integral_constant<uint32_t, 2>{}); break;
+                case 3: block(pix0, block_end, std::integral_constant<uint32_t, 3>{}); break;
+                case 4: block(pix0, block_end, std::integral_constant<uint32_t, 4>{}); break;
+                default: break;
+            }
         }
         return;
     }
