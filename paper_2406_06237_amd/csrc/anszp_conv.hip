@@ -258,7 +258,10 @@ __device__ __forceinline__ void store_tiles(const ConvParams& p, const anszp_lay
     }
 }
 
-// kPointwiseRing: the loads of one ring slot (QT activation vectors) issued by hand, and the wait for them.  When a
+// What a kernel tap outside the image reads (kTapsRing: every load is unconditional).
+__device__ __attribute__((aligned(64))) const uint32_t zero_page[16] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+
+// kPointwiseRing, kTapsRing: the loads of one ring slot (QT activation vectors) issued by hand, and the wait for them.  When a
 // slot is used, LATER loads have been asked for after its own, so the wait is for all but LATER loads; it names the
 // slot's registers as its results, so that nothing which uses them can be moved ahead of it.  (The compiler, left
 // to count loads that cross the loop's back edge, waits for every load at the head of the loop.)
@@ -287,8 +290,9 @@ enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecuti
        kPointwise = 1,   // as kTaps with a 1 x 1 kernel and no padding: one pixel per column, nothing outside the image
        kGeneric = 2,     // any number of input channels (NHWC): every activation is addressed on its own
        kPointwiseRing = 3,     // as kPointwise with input channels a multiple of 32 * D: D steps' activations in flight
-       kTapsPatch = 4 };       // as kTaps with input channels a multiple of 32: the activations under all kernel taps of a
+       kTapsPatch = 4,         // as kTaps with input channels a multiple of 32: the activations under all kernel taps of a
                                // round of pixels are staged in LDS once per 32 input channels
+       kTapsRing = 5 };        // as kTaps with input channels a multiple of 32 * D: D steps' activations in flight
 // D (kPointwiseRing only): steps of 32 input channels whose activation loads are in flight at any time.
 template <int KIND, uint32_t MR, bool P16, uint32_t D>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
@@ -517,6 +521,135 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 multiply(base + 2u, 2u);
                 ring_arrived<QT, 0u>(ring[3]);
                 multiply(base + 3u, 3u);
+            }
+            store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+        };
+        for (uint32_t round = 0; round < n_rounds; ++round) {
+            const uint32_t t0 = round * round_tiles;
+            if (t0 >= tiles) break;
+            const uint32_t tn = min(round_tiles, tiles - t0);
+            const uint32_t w_begin = t0 + tn * wave / kWaves, w_end = t0 + tn * (wave + 1u) / kWaves;   // this wavefront's tiles
+            const uint32_t pix0 = split_begin + 16u * w_begin, block_end = min(split_begin + 16u * w_end, split_end);
+            switch (w_end - w_begin) {                            // uniform
+                case 1: block(pix0, block_end, std::integral_constant<uint32_t, 1>{}); break;
+                case 2: block(pix0, block_end, std::integral_constant<uint32_t, 2>{}); break;
+                case 3: block(pix0, block_end, std::integral_constant<uint32_t, 3>{}); break;
+                case 4: block(pix0, block_end, std::integral_constant<uint32_t, 4>{}); break;
+                default: break;
+            }
+        }
+        return;
+    }
+
+    if constexpr (KIND == kTapsRing) {
+        // ---- phase 2 for kernels of several taps whose input channels are a multiple of 32 * D: steps of 32 k, kernel
+        // taps outermost, in groups of D steps that never straddle a tap; tiles dealt out and loads issued as for
+        // kPointwiseRing.  A column whose pixel lies outside the image under a tap reads zero_page for that tap (with a
+        // step stride of zero), so every load is unconditional.
+        const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
+        const uint8_t* a_row = panel + (col * p.row_stride + 8u * kg) * kElem;
+        const uint32_t tile_stride = kRows * p.row_stride * kElem;
+        const float zf = static_cast<float>(lay.zero_point);
+        const uint32_t groups_per_tap = p.cin / (32u * D);
+        const uint32_t n_groups = p.kh * p.kw * groups_per_tap;
+        const uint32_t split_begin = split * p.pixels_per_split;
+        const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
+        const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
+        const uint32_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
+        const uint32_t round_tiles = (tiles + n_rounds - 1u) / n_rounds;
+        const uint16_t* zeros = reinterpret_cast<const uint16_t*>(zero_page);
+        auto block = [&](uint32_t pix0, uint32_t block_end, auto tiles_here) {
+            constexpr uint32_t QT = decltype(tiles_here)::value;
+            bool valid[4] = {false, false, false, false};
+            uint32_t out_at[4] = {0u, 0u, 0u, 0u};
+            int32_t h0[QT], w0[QT];
+            uint32_t img[QT];
+#pragma unroll
+            for (uint32_t q = 0; q < QT; ++q) {
+                const uint32_t pix = pix0 + q * 16u + col;
+                valid[q] = pix < block_end;
+                const uint32_t n = valid[q] ? pix : pix0;         // a column beyond the block stands on its first pixel
+                const uint32_t wo = n % p.out_w, t = n / p.out_w;
+                const uint32_t ho = t % p.out_h, b = t / p.out_h;
+                h0[q] = int32_t(ho * p.stride) - int32_t(p.pad);
+                w0[q] = int32_t(wo * p.stride) - int32_t(p.pad);
+                img[q] = b * p.in_h * p.in_w * p.cin;
+                out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
+            }
+            floatx4 acc[MR][4];
+#pragma unroll
+            for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            // where the requests of the group being asked for read: the tap's pixel of every column, and how far it
+            // is from one step's vector to the next's (nothing, on the zero page)
+            const uint16_t* tap_ptr[QT];
+            uint32_t tap_step[QT];
+            auto enter_tap = [&](uint32_t tap) {
+                const uint32_t r = tap / p.kw, sx = tap % p.kw;
+#pragma unroll
+                for (uint32_t q = 0; q < QT; ++q) {
+                    const int32_t h = h0[q] + int32_t(r), w = w0[q] + int32_t(sx);
+                    const bool inside = uint32_t(h) < p.in_h && uint32_t(w) < p.in_w;
+                    tap_ptr[q] = inside ? p.x + (img[q] + (uint32_t(h) * p.in_w + uint32_t(w)) * p.x_pixel + kg * p.x_block) : zeros;
+                    tap_step[q] = inside ? 4u * p.x_block : 0u;
+                }
+            };
+            words4 ring[D][QT];
+            auto request = [&](uint32_t d, uint32_t step_in_tap) {
+                const uint16_t* from[QT];
+#pragma unroll
+                for (uint32_t q = 0; q < QT; ++q) from[q] = tap_ptr[q] + __umul24(step_in_tap, tap_step[q]);
+                ring_request<QT>(ring[d], from, 0u);
+            };
+            auto multiply = [&](uint32_t k_first, uint32_t d) {   // k_first: the step's first k (its panel column)
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m) {
+                    bf16x8 a;
+                    if constexpr (P16) a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + k_first * 2u);
+                    else a = weights_of(*reinterpret_cast<const words2*>(a_row + m * tile_stride + k_first), zf);
+#pragma unroll
+                    for (uint32_t q = 0; q < QT; ++q)
+                        acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
+                }
+            };
+            enter_tap(0u);
+#pragma unroll
+            for (uint32_t d = 0; d < D; ++d) request(d, d);
+            uint32_t tap = 0, group_in_tap = 0;                   // of the group being multiplied
+            for (uint32_t g = 0; g + 1u < n_groups; ++g) {        // every group but the last
+                uint32_t next_tap = tap, next_in_tap = group_in_tap + 1u;
+                if (next_in_tap == groups_per_tap) {              // uniform
+                    next_in_tap = 0;
+                    ++next_tap;
+                    enter_tap(next_tap);
+                }
+                const uint32_t k_group = tap * p.cin + group_in_tap * (32u * D);
+#pragma unroll
+                for (uint32_t d = 0; d < D; ++d) {
+                    ring_arrived<QT, (D - 1u) * QT>(ring[d]);
+                    multiply(k_group + 32u * d, d);
+                    request(d, next_in_tap * D + d);
+                }
+                tap = next_tap;
+                group_in_tap = next_in_tap;
+            }
+            const uint32_t k_group = tap * p.cin + group_in_tap * (32u * D);
+            static_assert(D == 2 || D == 4, "written out for two and four slots");
+            if constexpr (D == 2) {
+                ring_arrived<QT, QT>(ring[0]);
+                multiply(k_group, 0u);
+                ring_arrived<QT, 0u>(ring[1]);
+                multiply(k_group + 32u, 1u);
+            } else {
+                ring_arrived<QT, 3u * QT>(ring[0]);
+                multiply(k_group, 0u);
+                ring_arrived<QT, 2u * QT>(ring[1]);
+                multiply(k_group + 32u, 1u);
+                ring_arrived<QT, QT>(ring[2]);
+                multiply(k_group + 64u, 2u);
+                ring_arrived<QT, 0u>(ring[3]);
+                multiply(k_group + 96u, 3u);
             }
             store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
         };
@@ -989,20 +1122,25 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
             if (lds_total > kLdsLimit) return ANSZP_E_RANGE;
         }
     }
-    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : kTaps;
+    // other kernels of several taps: the ring of loads, if the channels allow whole groups of steps per tap and a
+    // step's stride fits a 24-bit multiplication
+    const bool taps_ring = !generic && !pointwise && !patch && (a->cin % 64u) == 0 && 4ull * p.x_block < (1u << 24);
+    const uint32_t taps_depth = taps_ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
+    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : taps_ring ? kTapsRing : kTaps;
     void (*kernel)(ConvParams) = nullptr;
 #define ANSZP_CONV_PICK(KIND, D)                                                                                       \
     (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true, D> : mr == 2 ? conv_fused_kernel<KIND, 2, true, D> : conv_fused_kernel<KIND, 1, true, D>) \
          : (mr == 4 ? conv_fused_kernel<KIND, 4, false, D> : mr == 2 ? conv_fused_kernel<KIND, 2, false, D> : conv_fused_kernel<KIND, 1, false, D>))
     kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric, 0) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise, 0)
            : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : kind == kTapsPatch ? ANSZP_CONV_PICK(kTapsPatch, 0)
+           : kind == kTapsRing ? (taps_depth == 4 ? ANSZP_CONV_PICK(kTapsRing, 4) : ANSZP_CONV_PICK(kTapsRing, 2))
            : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
 #undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
     // concurrent callers at worst both say it)
-    static std::atomic<bool> lds_allowed[2][6][3][64];
+    static std::atomic<bool> lds_allowed[2][8][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
-    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 5u : uint32_t(kind);
+    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 6u : kind == kTapsRing && taps_depth == 4 ? 7u : uint32_t(kind);
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
     if (!lds_allowed[p16][kernel_no][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
