@@ -86,6 +86,22 @@ def test_convolution_shapes(orc, shape, B_, H, Wd, stride, pad):
     _check(*_case(orc, shape, B_, H, Wd, stride, pad))
 
 
+@pytest.mark.parametrize("shape,B_,H,Wd,stride,pad,layout", [
+    ((64, 256, 1, 1), 2, 14, 14, 1, 0, "c8"),     # pointwise, four steps' loads in flight, bf16 panel of four row tiles
+    ((32, 1024, 1, 1), 1, 7, 7, 1, 0, "c8"),      # pointwise, byte panel widened to bf16 in place
+    ((64, 128, 1, 1), 2, 9, 9, 2, 0, "c8"),       # strided pointwise through the ring of loads
+    ((64, 64, 1, 1), 1, 30, 30, 1, 0, "nhwc"),    # 900 pixels, 57 column tiles: two rounds of tiles, two steps in flight
+    ((32, 128, 3, 3), 3, 9, 9, 2, 1, "c8"),       # several taps through the ring: stride 2, taps outside the image
+    ((64, 64, 3, 3), 2, 12, 12, 1, 1, "c8"),      # several taps through the ring: one group of two steps per tap
+    ((32, 128, 3, 3), 5, 7, 7, 1, 1, "c8"),       # patch in LDS: a round of pixels spans five images
+    ((16, 512, 3, 3), 9, 7, 7, 1, 1, "c8"),       # patch in LDS, K = 4608, sixteen steps, 441 pixels
+    ((64, 128, 3, 3), 2, 30, 30, 1, 1, "nhwc"),   # patch in LDS: 1800 pixels, several workgroups and rounds, rows of 30
+    ((32, 256, 3, 3), 1, 17, 5, 1, 1, "c8"),      # patch in LDS: narrow images, rows shorter than a column tile
+])
+def test_shapes_of_the_pipelined_contractions(orc, shape, B_, H, Wd, stride, pad, layout):
+    _check(*_case(orc, shape, B_, H, Wd, stride, pad, seed=shape[1] + H, x_layout=layout, y_layout=layout))
+
+
 @pytest.mark.parametrize("bitwidth,p0,n_streams,table_log", [(1, 0.9, 64, 12), (8, 0.75, 64, 12), (3, 0.3, 32, 10), (5, 0.8, 7, 9)])
 def test_alphabets_streams_and_table_sizes(orc, bitwidth, p0, n_streams, table_log):
     _check(*_case(orc, (32, 32, 3, 3), 2, 8, 8, 1, 1, bitwidth=bitwidth, p0=p0, n_streams=n_streams,
