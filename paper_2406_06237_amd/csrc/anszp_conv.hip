@@ -15,12 +15,15 @@
 //
 // One workgroup owns a panel of 16 * MR output channels (MR = 4, 2 or 1 row tiles of
 // v_mfma_f32_16x16x32_bf16: as many as fit in LDS) and a range of output pixels.  Phase 1: its twelve
-// wavefronts decode the chunks that hold those weight rows, one symbol per look-up with one lane per
-// stream (Sec. II-A, III-B), into a [16 * MR][K] panel in LDS: symbols as bytes, or, for short rows,
-// the bf16 values q - z.  Phase 2: every wavefront walks blocks of 64 output pixels (four MFMA column
-// tiles): per 32 k it reads the panel's 8 k per row tile (converting bytes once), loads four 16-byte
-// activation vectors and issues 4 * MR MFMAs.  fp32 accumulators; one store of four consecutive output
-// channels per lane, row tile and column tile.
+// wavefronts decode the chunks that hold those weight rows, one lane per stream (Sec. II-A, III-B),
+// through the table's look-ahead entries (one look-up per run of up to eight symbols) into a
+// [16 * MR][K] panel in LDS: symbols as bytes, or, for short rows, the bf16 values q - z.  Phase 2, by
+// kind of layer (see the enumeration in front of the kernel): 1 x 1 kernels read their activation
+// vectors from global memory through a ring of hand-issued loads; 3 x 3 kernels of stride 1 stage the
+// activations under all nine taps of a round of pixels in LDS once per 32 input channels; other
+// kernels of several taps use the ring, or, with channel counts that are no multiple of 64, loops the
+// compiler schedules.  fp32 accumulators; one store of four consecutive output channels per lane, row
+// tile and column tile.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
