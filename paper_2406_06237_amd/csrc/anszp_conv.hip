@@ -77,6 +77,7 @@ struct ConvParams {
     uint32_t panel_off;                                   // first byte of the panel in LDS (behind the table and the staging room)
     uint32_t wave_pixels, patch_off, patch_plane;         // kTapsPatch: pixels per wavefront and round (16..64); first byte of the
                                                           // patch; bytes of one of its four planes
+    uint32_t row_pitch;                                   // kGenericPatch: bytes from one staged image row to the next
     uint32_t pixels_per_split, block_pixels;              // multiples of 16: the pixels of a workgroup; of one block (<= 64)
 };
 
@@ -295,7 +296,9 @@ enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecuti
        kPointwiseRing = 3,     // as kPointwise with input channels a multiple of 32 * D: D steps' activations in flight
        kTapsPatch = 4,         // as kTaps with input channels a multiple of 32: the activations under all kernel taps of a
                                // round of pixels are staged in LDS once per 32 input channels
-       kTapsRing = 5 };        // as kTaps with input channels a multiple of 32 * D: D steps' activations in flight
+       kTapsRing = 5,          // as kTaps with input channels a multiple of 32 * D: D steps' activations in flight
+       kGenericPatch = 6 };    // as kGeneric when whole image rows are multiples of 16 bytes: the image rows under a round
+                               // of pixels are staged in LDS, zero padding included, and gathered from there
 // D (kPointwiseRing only): steps of 32 input channels whose activation loads are in flight at any time.
 template <int KIND, uint32_t MR, bool P16, uint32_t D>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         // on as many SIMDs as possible: the loop is bound by the activations' way from the L2).
         const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
         const uint32_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
-        const uint32_t round_tiles = (tiles + n_rounds - 1u) / n_rounds;
+        const uint32_t round_tiles = n_rounds ? (tiles + n_rounds - 1u) / n_rounds : 0u;
         auto block = [&](uint32_t pix0, uint32_t block_end, auto tiles_here) {
             constexpr uint32_t QT = decltype(tiles_here)::value;
             // B: lane holds column lane % 16 of each of the block's QT column tiles; a column beyond the block
@@ -544,6 +547,136 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         return;
     }
 
+    if constexpr (KIND == kGenericPatch) {
+        // ---- phase 2 for any number of input channels (NHWC) when an image row is a multiple of 16 bytes: the
+        // workgroup's column tiles are taken in rounds (dealt out as for kPointwiseRing); the image rows under a
+        // round's pixels go to LDS as they are, 16 bytes at a time, each behind 32 bytes whose upper part is the
+        // left zero padding, followed by the right one; rows above and below an image are zeros.  A lane then
+        // gathers its 8 k per column from LDS: the pixel's place plus an offset per k that is worked out once (a
+        // table in LDS in front of the rows).  Nothing tests for the image's border.
+        const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
+        const uint8_t* a_row = panel + (col * p.row_stride + 8u * kg) * kElem;
+        const uint32_t tile_stride = kRows * p.row_stride * kElem;
+        const float zf = static_cast<float>(lay.zero_point);
+        const uint32_t S = p.stride, Hp = p.in_h + 2u * p.pad;
+        const uint32_t Kp = (p.K + 31u) & ~31u;
+        const uint32_t row_bytes = p.in_w * p.cin * 2u, pieces_per_row = row_bytes / 16u;
+        const uint32_t edge_pieces = 2u + (p.row_pitch - 32u - row_bytes) / 16u;   // the 16-byte pieces of a row that hold no image
+        uint32_t* k_offset = reinterpret_cast<uint32_t*>(lds);    // [Kp]: bytes from a pixel's first tap, first channel, to k's activation
+        uint8_t* rows_at = lds + p.patch_off;
+        for (uint32_t k = tid; k < Kp; k += kThreads) {
+            const uint32_t tap = k / p.cin, c = k % p.cin;
+            const uint32_t r = tap / p.kw, sx = tap % p.kw;
+            k_offset[k] = k < p.K ? r * p.row_pitch + (sx * p.cin + c) * 2u : 0u;
+        }
+        const uint32_t split_begin = split * p.pixels_per_split;
+        const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
+        const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
+        const uint32_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
+        const uint32_t round_tiles = n_rounds ? (tiles + n_rounds - 1u) / n_rounds : 0u;
+        constexpr uint32_t kPieces = kPatchPieces;
+        for (uint32_t round = 0; round < n_rounds; ++round) {
+            const uint32_t t0 = round * round_tiles;
+            if (t0 >= tiles) break;
+            const uint32_t tn = min(round_tiles, tiles - t0);
+            const uint32_t round0 = split_begin + 16u * t0, round_end = min(round0 + 16u * tn, split_end);
+            // the staged rows: flat index b * Hp + padded row, from the first pixel's first tap to the last pixel's last
+            const uint32_t first_row = round0 / p.out_w, last_row = (round_end - 1u) / p.out_w;   // flat output rows b * out_h + ho
+            const uint32_t pr0 = (first_row / p.out_h) * Hp + (first_row % p.out_h) * S;
+            const uint32_t pr_last = (last_row / p.out_h) * Hp + (last_row % p.out_h) * S + p.kh - 1u;
+            const uint32_t n_rows = pr_last - pr0 + 1u;
+            const uint32_t n_pieces = n_rows * pieces_per_row;
+            if (n_pieces > kPieces * kThreads) {                  // the host sized the rounds so that this cannot happen
+                if (tid == 0) report(p.status, ANSZP_ST_INTERNAL);
+                return;                                           // uniform
+            }
+            __syncthreads();                                      // the previous round's rows have been read (and k_offset written)
+            words4 held_x[kPieces];
+            uint32_t dst[kPieces];
+#pragma unroll
+            for (uint32_t u = 0; u < kPieces; ++u) {
+                const uint32_t i = tid + u * kThreads;
+                held_x[u] = words4{0u, 0u, 0u, 0u};
+                dst[u] = 0xFFFFFFFFu;
+                if (i < n_pieces) {
+                    const uint32_t piece = i % pieces_per_row, row = i / pieces_per_row;
+                    const uint32_t pra = pr0 + row;
+                    const uint32_t b = pra / Hp, h = pra % Hp - p.pad;                      // unsigned: above the image wraps around
+                    dst[u] = row * p.row_pitch + 32u + piece * 16u;
+                    if (h < p.in_h) held_x[u] = reinterpret_cast<const words4*>(p.x + (b * p.in_h + h) * p.in_w * p.cin)[piece];
+                }
+            }
+            for (uint32_t i = tid; i < n_rows * edge_pieces; i += kThreads) {
+                const uint32_t e = i % edge_pieces, row = i / edge_pieces;
+                const uint32_t at = row * p.row_pitch + (e < 2u ? e * 16u : 32u + row_bytes + (e - 2u) * 16u);
+                *reinterpret_cast<words4*>(rows_at + at) = words4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < kPieces; ++u)
+                if (dst[u] != 0xFFFFFFFFu) *reinterpret_cast<words4*>(rows_at + dst[u]) = held_x[u];
+            __syncthreads();
+
+            const uint32_t w_begin = t0 + tn * wave / kWaves, w_end = t0 + tn * (wave + 1u) / kWaves;   // this wavefront's tiles
+            const uint32_t pix0 = split_begin + 16u * w_begin, block_end = min(split_begin + 16u * w_end, split_end);
+            auto block = [&](auto tiles_here) {
+                constexpr uint32_t QT = decltype(tiles_here)::value;
+                bool valid[4] = {false, false, false, false};
+                uint32_t out_at[4] = {0u, 0u, 0u, 0u};
+                uint32_t at_rows[QT];                             // byte of the pixel's first tap, first channel (may lie in the left padding)
+#pragma unroll
+                for (uint32_t q = 0; q < QT; ++q) {
+                    const uint32_t pix = pix0 + q * 16u + col;
+                    valid[q] = pix < block_end;
+                    const uint32_t n = valid[q] ? pix : pix0;     // a column beyond the block stands on its first pixel
+                    const uint32_t wo = n % p.out_w, t = n / p.out_w;
+                    const uint32_t ho = t % p.out_h, b = t / p.out_h;
+                    at_rows[q] = (b * Hp + ho * S - pr0) * p.row_pitch + 32u + (wo * S * p.cin) * 2u - p.pad * p.cin * 2u;
+                    out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
+                }
+                floatx4 acc[MR][4];
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+                    for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                for (uint32_t k0 = 0; k0 < Kp; k0 += 32u) {
+                    const uint32_t kbase = k0 + 8u * kg;
+                    const words4 off_lo = *reinterpret_cast<const words4*>(k_offset + kbase);
+                    const words4 off_hi = *reinterpret_cast<const words4*>(k_offset + kbase + 4u);
+                    const uint32_t off[8] = {off_lo.x, off_lo.y, off_lo.z, off_lo.w, off_hi.x, off_hi.y, off_hi.z, off_hi.w};
+                    words4 b[QT];
+#pragma unroll
+                    for (uint32_t q = 0; q < QT; ++q) {
+                        uint32_t v[8];
+#pragma unroll
+                        for (uint32_t j = 0; j < 8; ++j) {
+                            v[j] = *reinterpret_cast<const uint16_t*>(rows_at + at_rows[q] + off[j]);
+                            if (kbase + j >= p.K) v[j] = 0u;      // beyond the reduction (the last step only)
+                        }
+                        b[q] = words4{v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16};
+                    }
+#pragma unroll
+                    for (uint32_t m = 0; m < MR; ++m) {
+                        bf16x8 a;
+                        if constexpr (P16) a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + k0 * 2u);
+                        else a = weights_of(*reinterpret_cast<const words2*>(a_row + m * tile_stride + k0), zf);
+#pragma unroll
+                        for (uint32_t q = 0; q < QT; ++q)
+                            acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[q]), acc[m][q], 0, 0, 0);
+                    }
+                }
+                store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+            };
+            switch (w_end - w_begin) {                            // uniform
+                case 1: block(std::integral_constant<uint32_t, 1>{}); break;
+                case 2: block(std::integral_constant<uint32_t, 2>{}); break;
+                case 3: block(std::integral_constant<uint32_t, 3>{}); break;
+                case 4: block(std::integral_constant<uint32_t, 4>{}); break;
+                default: break;
+            }
+        }
+        return;
+    }
+
     if constexpr (KIND == kTapsRing) {
         // ---- phase 2 for kernels of several taps whose input channels are a multiple of 32 * D: steps of 32 k, kernel
         // taps outermost, in groups of D steps that never straddle a tap; tiles dealt out and loads issued as for
@@ -559,7 +692,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
         const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
         const uint32_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
-        const uint32_t round_tiles = (tiles + n_rounds - 1u) / n_rounds;
+        const uint32_t round_tiles = n_rounds ? (tiles + n_rounds - 1u) / n_rounds : 0u;
         const uint16_t* zeros = reinterpret_cast<const uint16_t*>(zero_page);
         auto block = [&](uint32_t pix0, uint32_t block_end, auto tiles_here) {
             constexpr uint32_t QT = decltype(tiles_here)::value;
@@ -1117,33 +1250,61 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
         }
         if (!patch) p.panel_off = table_bytes + kWaves * kStageWords * 4u;
     }
-    if (generic) {                                                // room for the table of the k below the panel
-        const uint32_t k_table_bytes = ((uint32_t(K) + 31u) & ~31u) * 8u;
-        if (p.panel_off < k_table_bytes) {
-            p.panel_off = k_table_bytes;
-            lds_total = p.panel_off + panel_bytes + 64u;
-            if (lds_total > kLdsLimit) return ANSZP_E_RANGE;
+    bool generic_patch = false;
+    if (generic) {
+        // image rows that are multiples of 16 bytes (NHWC): the rows under a round of pixels staged in LDS, if the most
+        // rows a round can need fit below the panel (after the table of k offsets) and in pieces per thread
+        const uint32_t Kp = (uint32_t(K) + 31u) & ~31u;
+        const uint64_t row_bytes = uint64_t(a->in_w) * a->cin * 2u;
+        const uint64_t row_pitch = (32u + row_bytes + uint64_t(a->pad) * a->cin * 2u + 15u) & ~uint64_t(15);
+        if (a->x_layout == ANSZP_ACT_NHWC && row_bytes % 16u == 0 && uint64_t(a->pad) * a->cin * 2u <= 32u && row_pitch < (1u << 20)) {
+            const uint32_t S = a->stride, Hp = a->in_h + 2u * a->pad;
+            const int64_t gap = int64_t(Hp) - int64_t(out_h) * S;
+            const uint64_t tiles = (p.pixels_per_split + 15u) / 16u;
+            const uint64_t n_rounds = (tiles + 4u * kWaves - 1u) / (4u * kWaves);
+            const uint64_t round = ((tiles + n_rounds - 1u) / n_rounds) * 16u;
+            const uint64_t rows_out = (round + out_w - 2u) / out_w + 1u;
+            const uint64_t crossings = std::min<uint64_t>(a->batch - 1u, (rows_out + out_h - 2u) / out_h);
+            const uint64_t rows = (rows_out - 1u) * S + a->kh + crossings * uint64_t(gap > 0 ? gap : 0);
+            const uint64_t k_table_bytes = (uint64_t(Kp) * 4u + 63u) & ~uint64_t(63);
+            const uint64_t below = std::max<uint64_t>(p.panel_off, k_table_bytes + rows * row_pitch);
+            if (rows * (row_bytes / 16u) <= kPatchPieces * kThreads && below + panel_bytes + 64u <= kLdsLimit) {
+                generic_patch = true;
+                p.row_pitch = uint32_t(row_pitch);
+                p.patch_off = uint32_t(k_table_bytes);
+                p.panel_off = uint32_t((below + 15u) & ~uint64_t(15));
+                lds_total = p.panel_off + panel_bytes + 64u;
+            }
+        }
+        if (!generic_patch) {                                     // room for the table of the k below the panel
+            const uint32_t k_table_bytes = Kp * 8u;
+            if (p.panel_off < k_table_bytes) {
+                p.panel_off = k_table_bytes;
+                lds_total = p.panel_off + panel_bytes + 64u;
+                if (lds_total > kLdsLimit) return ANSZP_E_RANGE;
+            }
         }
     }
     // other kernels of several taps: the ring of loads, if the channels allow whole groups of steps per tap and a
     // step's stride fits a 24-bit multiplication
     const bool taps_ring = !generic && !pointwise && !patch && (a->cin % 64u) == 0 && 4ull * p.x_block < (1u << 24);
     const uint32_t taps_depth = taps_ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
-    const int kind = generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : taps_ring ? kTapsRing : kTaps;
+    const int kind = generic_patch ? kGenericPatch : generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : taps_ring ? kTapsRing : kTaps;
     void (*kernel)(ConvParams) = nullptr;
 #define ANSZP_CONV_PICK(KIND, D)                                                                                       \
     (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true, D> : mr == 2 ? conv_fused_kernel<KIND, 2, true, D> : conv_fused_kernel<KIND, 1, true, D>) \
          : (mr == 4 ? conv_fused_kernel<KIND, 4, false, D> : mr == 2 ? conv_fused_kernel<KIND, 2, false, D> : conv_fused_kernel<KIND, 1, false, D>))
     kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric, 0) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise, 0)
            : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : kind == kTapsPatch ? ANSZP_CONV_PICK(kTapsPatch, 0)
+           : kind == kGenericPatch ? ANSZP_CONV_PICK(kGenericPatch, 0)
            : kind == kTapsRing ? (taps_depth == 4 ? ANSZP_CONV_PICK(kTapsRing, 4) : ANSZP_CONV_PICK(kTapsRing, 2))
            : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
 #undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
     // concurrent callers at worst both say it)
-    static std::atomic<bool> lds_allowed[2][8][3][64];
+    static std::atomic<bool> lds_allowed[2][9][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
-    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 6u : kind == kTapsRing && taps_depth == 4 ? 7u : uint32_t(kind);
+    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 7u : kind == kTapsRing && taps_depth == 4 ? 8u : uint32_t(kind);
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
     if (!lds_allowed[p16][kernel_no][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,

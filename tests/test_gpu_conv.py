@@ -97,6 +97,10 @@ def test_convolution_shapes(orc, shape, B_, H, Wd, stride, pad):
     ((16, 512, 3, 3), 9, 7, 7, 1, 1, "c8"),       # patch in LDS, K = 4608, sixteen steps, 441 pixels
     ((64, 128, 3, 3), 2, 30, 30, 1, 1, "nhwc"),   # patch in LDS: 1800 pixels, several workgroups and rounds, rows of 30
     ((32, 256, 3, 3), 1, 17, 5, 1, 1, "c8"),      # patch in LDS: narrow images, rows shorter than a column tile
+    ((64, 3, 7, 7), 2, 24, 24, 2, 3, "nhwc"),     # 3 channels, image rows of 144 bytes staged in LDS with their padding
+    ((32, 3, 3, 3), 3, 16, 16, 1, 1, "nhwc"),     # the same over three images, stride 1
+    ((16, 5, 2, 2), 1, 9, 8, 1, 0, "nhwc"),       # 5 channels, no padding, a 2 x 2 kernel
+    ((16, 12, 5, 5), 2, 40, 40, 3, 2, "nhwc"),    # 12 channels, stride 3, 392 pixels: K = 300 spans ten steps
 ])
 def test_shapes_of_the_pipelined_contractions(orc, shape, B_, H, Wd, stride, pad, layout):
     _check(*_case(orc, shape, B_, H, Wd, stride, pad, seed=shape[1] + H, x_layout=layout, y_layout=layout))
