@@ -375,10 +375,8 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         cur = desc_of(0u);
         fetch(cur, cur_data);
     }
-#pragma unroll
-    for (uint32_t u = 0; u < kTableLoads; ++u)
-        if (tid + u * kThreads < L) reinterpret_cast<words4*>(ahead)[tid + u * kThreads] = tv[u];
     {
+        // (done while the table is still on its way: only the quantizer and the last state's triple are needed)
         // The panel starts as the layer's dominant symbol everywhere (decoding writes only the other symbols);
         // also the columns from K to a row's end and the 64 bytes behind the last row, which the contraction
         // reads (the last 32 k of a row tile or of a kernel tap) against activations that are zero: as bf16
@@ -392,6 +390,9 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         const uint32_t panel_quads = (kRows * MR * p.row_stride * kElem + 64u) / 16u;
         for (uint32_t i = tid; i < panel_quads; i += kThreads) reinterpret_cast<words4*>(panel)[i] = words4{fill, fill, fill, fill};
     }
+#pragma unroll
+    for (uint32_t u = 0; u < kTableLoads; ++u)
+        if (tid + u * kThreads < L) reinterpret_cast<words4*>(ahead)[tid + u * kThreads] = tv[u];
     __syncthreads();
     uint32_t err = (lay.channel_len != 0 && lay.channel_len != p.K) ? ANSZP_ST_BAD_DESC : 0u;   // scales per output channel only
     for (uint32_t i = 0; i < n_mine; ++i) {
