@@ -106,6 +106,29 @@ def test_shapes_of_the_pipelined_contractions(orc, shape, B_, H, Wd, stride, pad
     _check(*_case(orc, shape, B_, H, Wd, stride, pad, seed=shape[1] + H, x_layout=layout, y_layout=layout))
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        k = int(rng.choice([1, 3]))
+        cin = int(rng.choice([8, 32, 64, 96, 128, 160, 192, 256, 320]))
+        cout = int(rng.choice([16, 32, 48, 64, 128]))
+        stride = int(rng.choice([1, 2]))
+        pad = 0 if k == 1 else int(rng.choice([0, 1]))
+        h, w = int(rng.integers(k + 2, 19)), int(rng.integers(k + 2, 19))
+        batch = int(rng.integers(1, 5))
+        layout = str(rng.choice(["c8", "nhwc"]))
+        cases.append(((cout, cin, k, k), batch, h, w, stride, pad, layout, int(rng.integers(1, 9)), float(rng.choice([0.5, 0.8, 0.93])), 1000 + i))
+    return cases
+
+
+@pytest.mark.parametrize("shape,B_,H,Wd,stride,pad,layout,bitwidth,p0,seed", _random_cases(36, 20240611))
+def test_seeded_random_shapes(orc, shape, B_, H, Wd, stride, pad, layout, bitwidth, p0, seed):
+    """Channel counts, kernel sizes, strides, image sizes, batches, layouts and alphabets drawn from a seeded generator:
+    every way the kernel has of addressing the activations, with ragged pixel counts."""
+    _check(*_case(orc, shape, B_, H, Wd, stride, pad, bitwidth=bitwidth, p0=p0, seed=seed, x_layout=layout, y_layout=layout))
+
+
 @pytest.mark.parametrize("bitwidth,p0,n_streams,table_log", [(1, 0.9, 64, 12), (8, 0.75, 64, 12), (3, 0.3, 32, 10), (5, 0.8, 7, 9)])
 def test_alphabets_streams_and_table_sizes(orc, bitwidth, p0, n_streams, table_log):
     _check(*_case(orc, (32, 32, 3, 3), 2, 8, 8, 1, 1, bitwidth=bitwidth, p0=p0, n_streams=n_streams,
