@@ -279,3 +279,53 @@ def test_bf16_panel_does_not_depend_on_stale_lds(orc):
             assert np.isfinite(got).all(), f"pattern {pattern:#x}, shape {shape}: non-finite outputs"
             _check(status, got, want, mag)
     assert int(sink[0]) == 0
+
+
+def test_launches_replayed_from_a_captured_graph(orc):
+    """Callers may capture the launches of several layers into a graph (after one eager call per kernel, which sets
+    the kernel's LDS limit): every replay, with eager work and synchronisations between, must leave what the eager
+    launches left."""
+    cases = [((64, 128, 1, 1), 1, 0), ((32, 128, 3, 3), 1, 1), ((32, 64, 3, 3), 2, 1)]
+    calls, outs, keep = [], [], []
+    for i, (shape, stride, pad) in enumerate(cases):
+        cout, cin, kh, kw = shape
+        K = cin * kh * kw
+        rows = B.conv_rows_per_chunk(K)
+        lay = _layer(shape, 4, 0.8, 50 + i)
+        w = W.Workload("conv_case", [lay], 12, 64, rows * K, "bf16")
+        d = B.to_device(host_from_oracle(oracle_encode(orc, w), w))
+        codes, _ = W.bf16_activations(2 * 10 * 10 * cin, 60 + i)
+        x = B.to_c8(torch.from_numpy(codes.view(np.int16).reshape(2, 10, 10, cin)).to("cuda:0").view(torch.bfloat16))
+        ho = (10 + 2 * pad - kh) // stride + 1
+        y = torch.empty(B.conv_out_shape(2, ho, ho, cout, "c8"), dtype=torch.bfloat16, device="cuda:0")
+        calls.append((d, B.conv_args(d, 0, 0, rows, x, shape, stride, pad, y, "c8", "c8")))
+        outs.append(y)
+        keep.append(x)                                        # the arguments hold addresses, not tensors
+
+    def step():
+        for _, a in calls:
+            B.conv_fused_raw(a)
+
+    step()
+    torch.cuda.synchronize()
+    want = [y.clone() for y in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(4):
+        for y in outs:
+            y.view(torch.int16).fill_(0x7FC0)                 # NaN patterns: a replay must overwrite every element
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, ref in zip(outs, want):
+            assert torch.equal(y.view(torch.int16), ref.view(torch.int16))
+        step()                                                # eager work between the replays
+        torch.cuda.synchronize()
+    for d, _ in calls:
+        assert d.read_status() == (0, 0)
