@@ -45,6 +45,7 @@ constexpr uint32_t kRows = 16;              // output channels per MFMA row tile
 constexpr uint32_t kRowPad = 8;             // bytes between panel rows: rows start two LDS banks apart
 constexpr uint32_t kStageWords = 384;       // per wavefront: LDS room for one chunk's compressed words (2.6 bit per
                                             // weight at 4608 symbols; a larger chunk is read from global memory)
+constexpr uint32_t kWidenPieces = 7;        // 16-byte pieces of a byte panel one thread widens to bf16
 constexpr uint32_t kPatchTaps = 9;          // kTapsPatch: a 3 x 3 kernel
 constexpr uint32_t kPatchPieces = 4;        // kTapsPatch: 16-byte pieces of a patch per thread
 constexpr uint32_t kMaxMine = (4u * kRows + kWaves - 1u) / kWaves;   // chunks of a panel one wavefront may have to decode
@@ -427,23 +428,23 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         __syncthreads();
     }
 
-    if constexpr (KIND == kPointwiseRing) {
-        // ---- phase 2 for 1 x 1 kernels without padding whose input channels are a multiple of 32 * D.
-        // A panel of symbol bytes is first widened in place to bf16 values q - z (the table and the staging room
-        // are free now and the widened panel starts at the beginning of LDS): every thread takes its 16-byte
-        // pieces into registers, all wait, then every piece is written back as 32 bytes.
-        const uint8_t* a_base = panel;
-        if constexpr (!P16) {
-            constexpr uint32_t kPieces = 6;
-            const uint32_t n_pieces = (kRows * MR * p.row_stride + 64u) / 16u;     // the host made sure: <= kPieces * kThreads
+    // kPointwiseRing, kTapsRing (which need no other LDS in phase 2): a panel of symbol bytes is first widened in
+    // place to bf16 values q - z (the table and the staging room are free now and the widened panel starts at the
+    // beginning of LDS): every thread takes its 16-byte pieces into registers, all wait, then every piece is
+    // written back as 32 bytes.  Returns where the bf16 panel starts.
+    [[maybe_unused]] auto widened_panel = [&]() -> const uint8_t* {
+        if constexpr (P16) {
+            return panel;
+        } else {
+            const uint32_t n_pieces = (kRows * MR * p.row_stride + 64u) / 16u;     // the host made sure: <= kWidenPieces * kThreads
             const float zf = static_cast<float>(lay.zero_point);
-            words4 held_q[kPieces];
+            words4 held_q[kWidenPieces];
 #pragma unroll
-            for (uint32_t u = 0; u < kPieces; ++u)
+            for (uint32_t u = 0; u < kWidenPieces; ++u)
                 held_q[u] = reinterpret_cast<const words4*>(panel)[min(tid + u * kThreads, n_pieces - 1u)];
             __syncthreads();
 #pragma unroll
-            for (uint32_t u = 0; u < kPieces; ++u) {
+            for (uint32_t u = 0; u < kWidenPieces; ++u) {
                 const uint32_t i = tid + u * kThreads;
                 if (i < n_pieces) {
                     bf16x8* dst = reinterpret_cast<bf16x8*>(lds + 32u * i);
@@ -452,8 +453,12 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 }
             }
             __syncthreads();
-            a_base = lds;
+            return lds;
         }
+    };
+    if constexpr (KIND == kPointwiseRing) {
+        // ---- phase 2 for 1 x 1 kernels without padding whose input channels are a multiple of 32 * D.
+        const uint8_t* a_base = widened_panel();
         const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
         const uint8_t* a_row = a_base + (col * p.row_stride + 8u * kg) * 2u;
         const uint32_t tile_stride = kRows * p.row_stride * 2u;
@@ -684,9 +689,8 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
         // kPointwiseRing.  A column whose pixel lies outside the image under a tap reads zero_page for that tap (with a
         // step stride of zero), so every load is unconditional.
         const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
-        const uint8_t* a_row = panel + (col * p.row_stride + 8u * kg) * kElem;
-        const uint32_t tile_stride = kRows * p.row_stride * kElem;
-        const float zf = static_cast<float>(lay.zero_point);
+        const uint8_t* a_row = widened_panel() + (col * p.row_stride + 8u * kg) * 2u;   // (the host keeps this kind for panels that can be widened)
+        const uint32_t tile_stride = kRows * p.row_stride * 2u;
         const uint32_t groups_per_tap = p.cin / (32u * D);
         const uint32_t n_groups = p.kh * p.kw * groups_per_tap;
         const uint32_t split_begin = split * p.pixels_per_split;
@@ -742,9 +746,7 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
             auto multiply = [&](uint32_t k_first, uint32_t d) {   // k_first: the step's first k (its panel column)
 #pragma unroll
                 for (uint32_t m = 0; m < MR; ++m) {
-                    bf16x8 a;
-                    if constexpr (P16) a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + k_first * 2u);
-                    else a = weights_of(*reinterpret_cast<const words2*>(a_row + m * tile_stride + k_first), zf);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + k_first * 2u);
 #pragma unroll
                     for (uint32_t q = 0; q < QT; ++q)
                         acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, ring[d][q]), acc[m][q], 0, 0, 0);
@@ -1215,7 +1217,7 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     // a panel of bytes is widened to bf16 in place first, which needs twice its room from the start of LDS
     bool ring = pointwise && (a->cin % 64u) == 0;
     if (ring && !p16) {
-        ring = panel_bytes + 64u <= 6u * kThreads * 16u && 2u * (panel_bytes + 64u) <= kLdsLimit;
+        ring = panel_bytes + 64u <= kWidenPieces * kThreads * 16u && 2u * (panel_bytes + 64u) <= kLdsLimit;
         if (ring && lds_total < 2u * (panel_bytes + 64u)) lds_total = 2u * (panel_bytes + 64u);
     }
     const uint32_t depth = ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
@@ -1288,7 +1290,9 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     }
     // other kernels of several taps: the ring of loads, if the channels allow whole groups of steps per tap and a
     // step's stride fits a 24-bit multiplication
-    const bool taps_ring = !generic && !pointwise && !patch && (a->cin % 64u) == 0 && 4ull * p.x_block < (1u << 24);
+    const bool taps_ring = !generic && !pointwise && !patch && (a->cin % 64u) == 0 && 4ull * p.x_block < (1u << 24) &&
+                           (p16 || (panel_bytes + 64u <= kWidenPieces * kThreads * 16u && 2u * (panel_bytes + 64u) <= kLdsLimit));
+    if (taps_ring && !p16 && lds_total < 2u * (panel_bytes + 64u)) lds_total = 2u * (panel_bytes + 64u);
     const uint32_t taps_depth = taps_ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
     const int kind = generic_patch ? kGenericPatch : generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : taps_ring ? kTapsRing : kTaps;
     void (*kernel)(ConvParams) = nullptr;
