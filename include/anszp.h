@@ -366,7 +366,11 @@ typedef struct {
  * hip_stream; the buffers stay the caller's.  Errors: E_NULL, E_RANGE (a limit above, misaligned
  * x or y, too few chunks), E_HIP; a chunk whose descriptor does not fit the layer, a stream that
  * ends in the wrong state or length: ANSZP_ST_* bits in status, as for anszp_decode (the outputs
- * of the affected output channels are then unspecified but finite sums of finite values). */
+ * of the affected output channels are then unspecified but finite sums of finite values).
+ * The kernel reads the look-ahead entries of the layer's table (anszp_build_tables*).  The first
+ * call of each of its kernels on a device gives that kernel leave to use all of a CU's on-chip
+ * memory (a function attribute) and must not be part of a stream capture; later calls may be
+ * captured into a graph and replayed. */
 int anszp_conv_fused(const anszp_conv_args_t* args, void* hip_stream);
 
 #ifdef __cplusplus
