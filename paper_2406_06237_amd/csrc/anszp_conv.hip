@@ -298,8 +298,10 @@ enum { kTaps = 0,        // input channels a multiple of 8: a lane's 8 consecuti
        kTapsPatch = 4,         // as kTaps with input channels a multiple of 32: the activations under all kernel taps of a
                                // round of pixels are staged in LDS once per 32 input channels
        kTapsRing = 5,          // as kTaps with input channels a multiple of 32 * D: D steps' activations in flight
-       kGenericPatch = 6 };    // as kGeneric when whole image rows are multiples of 16 bytes: the image rows under a round
+       kGenericPatch = 6,      // as kGeneric when whole image rows are multiples of 16 bytes: the image rows under a round
                                // of pixels are staged in LDS, zero padding included, and gathered from there
+       kTapsRows = 7 };        // as kTapsRing for kernels three taps wide: the three taps of a kernel row and 32 channels
+                               // are loaded together, so that the L1 serves what they share
 // D (kPointwiseRing only): steps of 32 input channels whose activation loads are in flight at any time.
 template <int KIND, uint32_t MR, bool P16, uint32_t D>
 __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
@@ -677,6 +679,136 @@ __global__ __launch_bounds__(kThreads) void conv_fused_kernel(ConvParams p) {
                 case 2: block(std::integral_constant<uint32_t, 2>{}); break;
                 case 3: block(std::integral_constant<uint32_t, 3>{}); break;
                 case 4: block(std::integral_constant<uint32_t, 4>{}); break;
+                default: break;
+            }
+        }
+        return;
+    }
+
+    if constexpr (KIND == kTapsRows) {
+        // ---- phase 2 for kernels three taps wide whose input channels are a multiple of 64 (and that stage no patch).
+        // A step is a kernel row, 32 input channels and the row's three taps; two steps' activation vectors are in
+        // flight (hand-issued loads as for kPointwiseRing, each tap of a step waited for on its own).  Kernel rows
+        // outermost, channels next, the three taps innermost: the taps of a row read the same pixels shifted by one
+        // (stride 1) or alternate halves of the same lines (stride 2), and asked for together they cost the L1 one
+        // fetch of a line instead of up to three.  A column whose pixel lies outside the image under a tap reads
+        // zero_page with a step stride of zero.
+        const uint32_t col = lane & 15u, kg = lane >> 4;          // MFMA operand layout: row or column, group of 8 k
+        const uint8_t* a_row = widened_panel() + (col * p.row_stride + 8u * kg) * 2u;
+        const uint32_t tile_stride = kRows * p.row_stride * 2u;
+        const uint32_t steps_per_row = p.cin / 32u;               // even
+        const uint32_t n_steps = p.kh * steps_per_row;
+        const uint32_t split_begin = split * p.pixels_per_split;
+        const uint32_t split_end = min(split_begin + p.pixels_per_split, p.n_pixels);
+        const uint32_t tiles = (split_end - split_begin + 15u) / 16u;
+        constexpr uint32_t kTilesMost = MR == 4 ? 2u : 3u;        // column tiles per wavefront and round: what the registers hold
+        const uint32_t n_rounds = (tiles + kTilesMost * kWaves - 1u) / (kTilesMost * kWaves);
+        const uint32_t round_tiles = n_rounds ? (tiles + n_rounds - 1u) / n_rounds : 0u;
+        const uint16_t* zeros = reinterpret_cast<const uint16_t*>(zero_page);
+        auto block = [&](uint32_t pix0, uint32_t block_end, auto tiles_here) {
+            constexpr uint32_t QT = decltype(tiles_here)::value;
+            bool valid[4] = {false, false, false, false};
+            uint32_t out_at[4] = {0u, 0u, 0u, 0u};
+            int32_t h0[QT], w0[QT];
+            uint32_t img[QT];
+#pragma unroll
+            for (uint32_t q = 0; q < QT; ++q) {
+                const uint32_t pix = pix0 + q * 16u + col;
+                valid[q] = pix < block_end;
+                const uint32_t n = valid[q] ? pix : pix0;         // a column beyond the block stands on its first pixel
+                const uint32_t wo = n % p.out_w, t = n / p.out_w;
+                const uint32_t ho = t % p.out_h, b = t / p.out_h;
+                h0[q] = int32_t(ho * p.stride) - int32_t(p.pad);
+                w0[q] = int32_t(wo * p.stride) - int32_t(p.pad);
+                img[q] = b * p.in_h * p.in_w * p.cin;
+                out_at[q] = b * p.out_h * p.out_w * p.cout + (ho * p.out_w + wo) * p.y_pixel;
+            }
+            floatx4 acc[MR][4];
+#pragma unroll
+            for (uint32_t m = 0; m < MR; ++m)
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) acc[m][q] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            // where the requests of the kernel row being asked for read, per tap and column
+            const uint16_t* tap_ptr[3][QT];
+            uint32_t tap_step[3][QT];
+            auto enter_row = [&](uint32_t r) {
+#pragma unroll
+                for (uint32_t q = 0; q < QT; ++q) {
+                    const int32_t h = h0[q] + int32_t(r);
+                    const bool row_inside = uint32_t(h) < p.in_h;
+#pragma unroll
+                    for (uint32_t sx = 0; sx < 3; ++sx) {
+                        const int32_t w = w0[q] + int32_t(sx);
+                        const bool inside = row_inside && uint32_t(w) < p.in_w;
+                        tap_ptr[sx][q] = inside ? p.x + (img[q] + (uint32_t(h) * p.in_w + uint32_t(w)) * p.x_pixel + kg * p.x_block) : zeros;
+                        tap_step[sx][q] = inside ? 4u * p.x_block : 0u;
+                    }
+                }
+            };
+            words4 ring[2][3][QT];
+            auto request = [&](uint32_t slot, uint32_t step_in_row) {
+#pragma unroll
+                for (uint32_t sx = 0; sx < 3; ++sx) {
+                    const uint16_t* from[QT];
+#pragma unroll
+                    for (uint32_t q = 0; q < QT; ++q) from[q] = tap_ptr[sx][q] + __umul24(step_in_row, tap_step[sx][q]);
+                    ring_request<QT>(ring[slot][sx], from, 0u);
+                }
+            };
+            auto multiply = [&](uint32_t k_first, const words4 (&b)[QT]) {   // k_first: the step's first k under this tap (its panel column)
+#pragma unroll
+                for (uint32_t m = 0; m < MR; ++m) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + m * tile_stride + k_first * 2u);
+#pragma unroll
+                    for (uint32_t q = 0; q < QT; ++q)
+                        acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[q]), acc[m][q], 0, 0, 0);
+                }
+            };
+            // the cursor of the requests runs two steps ahead of the cursor of the multiplications
+            uint32_t req_row = 0, req_step = 0;
+            auto request_next = [&](uint32_t slot) {
+                request(slot, req_step);
+                if (++req_step == steps_per_row) {                // uniform
+                    req_step = 0;
+                    ++req_row;
+                    if (req_row < p.kh) enter_row(req_row);
+                }
+            };
+            enter_row(0u);
+            request_next(0u);
+            request_next(1u);
+            uint32_t row = 0, step = 0;                           // of the step being multiplied
+            auto use = [&](uint32_t slot, auto other_slot_pending) {
+                constexpr uint32_t kOther = decltype(other_slot_pending)::value ? 3u * QT : 0u;   // loads asked for after this slot's
+                const uint32_t k_row = row * 3u * p.cin + step * 32u;
+                ring_arrived<QT, 2u * QT + kOther>(ring[slot][0]);
+                multiply(k_row, ring[slot][0]);
+                ring_arrived<QT, QT + kOther>(ring[slot][1]);
+                multiply(k_row + p.cin, ring[slot][1]);
+                ring_arrived<QT, kOther>(ring[slot][2]);
+                multiply(k_row + 2u * p.cin, ring[slot][2]);
+                if (++step == steps_per_row) { step = 0; ++row; }
+            };
+            for (uint32_t t = 0; t + 2u < n_steps; t += 2u) {     // every pair of steps but the last
+                use(0u, std::true_type{});
+                request_next(0u);
+                use(1u, std::true_type{});
+                request_next(1u);
+            }
+            use(0u, std::true_type{});
+            use(1u, std::false_type{});
+            store_tiles<MR>(p, lay, mtile, kg, acc, valid, out_at);
+        };
+        for (uint32_t round = 0; round < n_rounds; ++round) {
+            const uint32_t t0 = round * round_tiles;
+            if (t0 >= tiles) break;
+            const uint32_t tn = min(round_tiles, tiles - t0);
+            const uint32_t w_begin = t0 + tn * wave / kWaves, w_end = t0 + tn * (wave + 1u) / kWaves;   // this wavefront's tiles
+            const uint32_t pix0 = split_begin + 16u * w_begin, block_end = min(split_begin + 16u * w_end, split_end);
+            switch (w_end - w_begin) {                            // uniform
+                case 1: block(pix0, block_end, std::integral_constant<uint32_t, 1>{}); break;
+                case 2: block(pix0, block_end, std::integral_constant<uint32_t, 2>{}); break;
+                case 3: if constexpr (kTilesMost >= 3) block(pix0, block_end, std::integral_constant<uint32_t, 3>{}); break;
                 default: break;
             }
         }
@@ -1294,22 +1426,24 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
                            (p16 || (panel_bytes + 64u <= kWidenPieces * kThreads * 16u && 2u * (panel_bytes + 64u) <= kLdsLimit));
     if (taps_ring && !p16 && lds_total < 2u * (panel_bytes + 64u)) lds_total = 2u * (panel_bytes + 64u);
     const uint32_t taps_depth = taps_ring ? ((a->cin % 128u) == 0 ? 4u : 2u) : 0u;
-    const int kind = generic_patch ? kGenericPatch : generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch : taps_ring ? kTapsRing : kTaps;
+    const bool taps_rows = taps_ring && a->kw == 3;
+    const int kind = generic_patch ? kGenericPatch : generic ? kGeneric : ring ? kPointwiseRing : pointwise ? kPointwise : patch ? kTapsPatch
+                   : taps_rows ? kTapsRows : taps_ring ? kTapsRing : kTaps;
     void (*kernel)(ConvParams) = nullptr;
 #define ANSZP_CONV_PICK(KIND, D)                                                                                       \
     (p16 ? (mr == 4 ? conv_fused_kernel<KIND, 4, true, D> : mr == 2 ? conv_fused_kernel<KIND, 2, true, D> : conv_fused_kernel<KIND, 1, true, D>) \
          : (mr == 4 ? conv_fused_kernel<KIND, 4, false, D> : mr == 2 ? conv_fused_kernel<KIND, 2, false, D> : conv_fused_kernel<KIND, 1, false, D>))
     kernel = kind == kGeneric ? ANSZP_CONV_PICK(kGeneric, 0) : kind == kPointwise ? ANSZP_CONV_PICK(kPointwise, 0)
            : kind == kTaps ? ANSZP_CONV_PICK(kTaps, 0) : kind == kTapsPatch ? ANSZP_CONV_PICK(kTapsPatch, 0)
-           : kind == kGenericPatch ? ANSZP_CONV_PICK(kGenericPatch, 0)
+           : kind == kGenericPatch ? ANSZP_CONV_PICK(kGenericPatch, 0) : kind == kTapsRows ? ANSZP_CONV_PICK(kTapsRows, 0)
            : kind == kTapsRing ? (taps_depth == 4 ? ANSZP_CONV_PICK(kTapsRing, 4) : ANSZP_CONV_PICK(kTapsRing, 2))
            : depth == 4 ? ANSZP_CONV_PICK(kPointwiseRing, 4) : ANSZP_CONV_PICK(kPointwiseRing, 2);
 #undef ANSZP_CONV_PICK
     // the kernels may use all of the CU's LDS: said once per kernel and device (a table of atomics:
     // concurrent callers at worst both say it)
-    static std::atomic<bool> lds_allowed[2][9][3][64];
+    static std::atomic<bool> lds_allowed[2][10][3][64];
     const uint32_t slot = mr == 4 ? 2u : mr == 2 ? 1u : 0u;
-    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 7u : kind == kTapsRing && taps_depth == 4 ? 8u : uint32_t(kind);
+    const uint32_t kernel_no = kind == kPointwiseRing && depth == 4 ? 8u : kind == kTapsRing && taps_depth == 4 ? 9u : uint32_t(kind);
     if (device < 0 || device >= 64) return ANSZP_E_HIP;
     if (!lds_allowed[p16][kernel_no][slot][device].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
