@@ -1293,11 +1293,12 @@ extern "C" int anszp_conv_fused(const anszp_conv_args_t* a, void* stream) {
     const uint32_t fixed_bytes = table_bytes + kWaves * kStageWords * 4u + 64u;
     const bool p16 = K <= kMaxK16;                              // short rows: the panel as bf16
     const uint32_t elem = p16 ? 2u : 1u;
-    // (a 3 x 3 kernel of stride 1 whose activations go through LDS holds at most two row tiles: its accumulators
-    // and the operands in flight of four would not fit the registers of three wavefronts per SIMD)
-    const bool patch_wanted = (a->cin % 32u) == 0 && a->cin >= 128u && a->kh == 3 && a->kw == 3 && a->stride == 1;
-    uint32_t mr = patch_wanted ? 2 : 4;
+    uint32_t mr = 4;
     while (mr > 1 && ((a->cout % (kRows * mr)) != 0 || fixed_bytes + kRows * mr * row_stride * elem > kLdsLimit)) mr >>= 1;
+    // A 3 x 3 kernel of stride 1 stages its activations in LDS where at most two row tiles fit anyway (K > 1152): with
+    // four, the loads of a kernel row's three taps issued together do as well through the L1 (measured), and the
+    // accumulators and operands in flight of four row tiles would not fit the patch kernel's registers.
+    const bool patch_wanted = (a->cin % 32u) == 0 && a->cin >= 128u && a->kh == 3 && a->kw == 3 && a->stride == 1 && mr <= 2;
     const uint32_t n_mtiles = a->cout / (kRows * mr);
     if ((reinterpret_cast<uintptr_t>(a->x) | reinterpret_cast<uintptr_t>(a->y) | reinterpret_cast<uintptr_t>(a->payload) |
          reinterpret_cast<uintptr_t>(a->tables)) & 15u) return ANSZP_E_RANGE;
