@@ -179,7 +179,7 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& 
                     const uint32_t v = __brev(window) >> (e.x & 31u);       // the next T + 1 stream bits
                     at = (e.y + 8u * v) & ahead_mask;
                     bit += (e.x >> 24) & 15u;
-                    elem += ((e.x >> 28) & 7u) * N;                         // past the entry's dominant symbols
+                    elem = __umul24((e.x >> 28) & 7u, N) + elem;            // past the entry's dominant symbols
                     const uint32_t el = min(elem, last_elem);
                     uint32_t where = el * kElem;                            // byte of the panel rows
                     if constexpr (!decltype(one_row)::value)
@@ -199,8 +199,9 @@ __device__ uint32_t decode_chunk_to_panel(const ConvParams& p, const ChunkDesc& 
         // a stream ends where an entry ends, in state 0 (the index of the next entry is 2 X + peeked bit),
         // having read exactly its words
         if (lane < N) {
-            const uint32_t len = c.n_symbols > lane ? (c.n_symbols - lane + N - 1u) / N : 0u;
-            if (elem != lane + len * N) err |= ANSZP_ST_BAD_LENGTH;
+            // the lane's elements are lane, lane + N, ...: it has produced exactly its symbols if it stands on the
+            // first of them that is no element of the chunk
+            if (elem - c.n_symbols >= N) err |= ANSZP_ST_BAD_LENGTH;
             if ((at >> 4) != 0u) err |= ANSZP_ST_BAD_STATE;
             if (((bit - first_bit) + 31u) >> 5 != n_words) err |= ANSZP_ST_BAD_LENGTH;
         }
