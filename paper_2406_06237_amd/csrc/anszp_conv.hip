@@ -19,11 +19,12 @@
 // through the table's look-ahead entries (one look-up per run of up to eight symbols) into a
 // [16 * MR][K] panel in LDS: symbols as bytes, or, for short rows, the bf16 values q - z.  Phase 2, by
 // kind of layer (see the enumeration in front of the kernel): 1 x 1 kernels read their activation
-// vectors from global memory through a ring of hand-issued loads; 3 x 3 kernels of stride 1 stage the
-// activations under all nine taps of a round of pixels in LDS once per 32 input channels; other
-// kernels of several taps use the ring, or, with channel counts that are no multiple of 64, loops the
-// compiler schedules.  fp32 accumulators; one store of four consecutive output channels per lane, row
-// tile and column tile.
+// vectors from global memory through a ring of hand-issued loads; kernels three taps wide load the
+// three taps of a kernel row and 32 channels together, so that the L1 serves what they share; 3 x 3
+// kernels of stride 1 with long rows (K > 1152) stage the activations under all nine taps of a round
+// of pixels in LDS once per 32 input channels; layers like the first one (3 channels) stage whole
+// image rows in LDS and gather from there; other shapes use loops the compiler schedules.  fp32
+// accumulators; one store of four consecutive output channels per lane, row tile and column tile.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

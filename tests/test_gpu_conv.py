@@ -101,6 +101,10 @@ def test_convolution_shapes(orc, shape, B_, H, Wd, stride, pad):
     ((32, 3, 3, 3), 3, 16, 16, 1, 1, "nhwc"),     # the same over three images, stride 1
     ((16, 5, 2, 2), 1, 9, 8, 1, 0, "nhwc"),       # 5 channels, no padding, a 2 x 2 kernel
     ((16, 12, 5, 5), 2, 40, 40, 3, 2, "nhwc"),    # 12 channels, stride 3, 392 pixels: K = 300 spans ten steps
+    ((32, 64, 1, 3), 2, 8, 9, 1, 1, "c8"),        # a kernel of one row of three taps (a kernel row's taps loaded together)
+    ((16, 128, 5, 3), 1, 9, 9, 2, 1, "c8"),       # five kernel rows of three taps, stride 2
+    ((16, 64, 3, 5), 1, 9, 9, 1, 2, "c8"),        # five taps wide: the ring with the taps outermost
+    ((128, 64, 3, 3), 1, 40, 40, 1, 1, "c8"),     # four row tiles, 1600 pixels: two column tiles per wavefront, several rounds
 ])
 def test_shapes_of_the_pipelined_contractions(orc, shape, B_, H, Wd, stride, pad, layout):
     _check(*_case(orc, shape, B_, H, Wd, stride, pad, seed=shape[1] + H, x_layout=layout, y_layout=layout))
