@@ -217,7 +217,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 def bench_fused_conv(args):
     """Config 5: every conv layer of the ResNet-50-shaped set, weights decoded inside the convolution kernel
     (anszp_conv_fused), batch 64 at 224 x 224 geometry, synthetic N(0,1) bf16 activations.  One step = the 53
-    launches, one per layer.  Prints one JSON line: TFLOP/s against the dense bf16 MFMA peak."""
+    launches, one per layer.  Returns the result (TFLOP/s against the dense bf16 MFMA peak): `--config 5` prints it as
+    the JSON line, the default run carries it as a secondary result beside the headline."""
     import numpy as np
     import torch
     from paper_2406_06237_amd import binding as B
@@ -350,7 +351,7 @@ def bench_fused_conv(args):
         result["cpu_baseline"] = {"value": 2.0 * macs[i] / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
                                   "sample": f"layer3.1.conv2 ({cout}x{cin}x{kh}x{kw}, {size}x{size}, batch {batch}): oracle "
                                             f"decode + fp64 convolution, {dt:.2f} s"}
-    print(json.dumps(result))
+    return result
 
 
 def main():
@@ -378,15 +379,20 @@ def main():
         sys.exit(2)
 
     if args.config == 5:
-        return bench_fused_conv(args)
+        print(json.dumps(bench_fused_conv(args)))
+        return
 
     result = bench_decode(args, args.config, headline=True)
     if args.config == 3 and not args.no_secondary:
-        # the ResNet-18-shaped set beside the headline, same measurement (bench.py --config 4 and --config 5 run
-        # the large stack and the fused convolution: minutes each, not part of the default run)
+        # the ResNet-18-shaped set beside the headline, same measurement (bench.py --config 4 runs the large
+        # stack: minutes, not part of the default run)
         sec = bench_decode(args, 2, headline=False)
         result["secondary"] = [{k: sec[k] for k in ("config", "value", "unit", "ms_per_step", "roofline", "without_plan", "chain_bound",
                                                     "cpu_baseline", "matches_oracle") if k in sec}]
+        # the fused decode + convolution over the same weight set (config 5), one step = its 53 launches
+        conv = bench_fused_conv(args)
+        result["secondary"].append({k: conv[k] for k in ("metric", "config", "value", "unit", "steps", "ms_per_step", "roofline",
+                                                         "max_relative_error_sampled", "matches_oracle", "cpu_baseline") if k in conv})
     print(json.dumps(result))
 
 
